@@ -1,0 +1,258 @@
+"""Plain fp64 reference of one transformer layer's forward and backward pass.
+
+TEST INFRASTRUCTURE ONLY -- never imported by the product path.
+
+Strand Interleaving does not change what is computed (paper Sec. 6.1, "Metrics":
+training semantics are unmodified; Sec. 4.2: the two strands have no data
+dependence), so what a strand must produce is the plain definition of a pre-norm
+transformer layer (the operators of Table 2: GEMM, FlashAttention, LayerNorm,
+fused bias-dropout-add with p=0, and the collectives, which on one GPU become
+fixed-order sums with frozen peer partials) and its exact chain-rule backward.
+Every function below writes that definition out with numpy in float64.  numpy's
+matmul is the only library primitive used as a step; there is no tiling, fusion or
+reordering.
+
+Conventions (readings of points the paper leaves open; listed in the design notes):
+  * weights are stored [in, out]; y = x @ W
+  * qkv columns are [q heads | k heads | v heads], head-major, head_dim minor
+  * gate/up columns are [gate F | up F]
+  * RoPE pairs element i with i + d/2 ("rotate-half"), theta_i = base**(-2i/d),
+    position restarts at 0 for every sequence
+  * attention is causal; q head h reads kv head h // (nq // nkv)
+  * a stand-in "collective" = partial 0 (this shard's GEMM output) + frozen peer
+    partials, summed in index order
+"""
+from dataclasses import dataclass
+import numpy as np
+
+
+@dataclass
+class LayerCfg:
+    batch: int
+    seq: int
+    H: int
+    nq: int
+    nkv: int
+    d: int
+    F: int
+    eps: float = 1e-5
+    rope_base: float = 10000.0
+
+    @property
+    def T(self):
+        return self.batch * self.seq
+
+    @property
+    def n_qkv(self):
+        return (self.nq + 2 * self.nkv) * self.d
+
+
+# --------------------------------------------------------------------------- norms
+def rmsnorm_fwd(x, gamma, eps):
+    """h = gamma * x * rstd, rstd = (mean_j x_j^2 + eps)^(-1/2)  (LayerNorm base of Table 2,
+    RMS form used by the Llama models of Sec. 6.1)."""
+    rstd = 1.0 / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + eps)
+    return gamma * x * rstd, rstd
+
+
+def rmsnorm_bwd(dy, x, gamma, rstd):
+    """Closed-form backward of rmsnorm_fwd: with xh = x*rstd, gh = gamma*dy,
+    dx = rstd * (gh - xh * mean_j(gh*xh)); dgamma = sum_t dy*xh."""
+    xh = x * rstd
+    gh = gamma * dy
+    dx = rstd * (gh - xh * np.mean(gh * xh, axis=-1, keepdims=True))
+    dgamma = np.sum(dy * xh, axis=0)
+    return dx, dgamma
+
+
+def layernorm_fwd(x, gamma, beta, eps):
+    """h = gamma * (x - mu) * rstd + beta with biased variance (LayerNorm of Table 2)."""
+    mu = np.mean(x, axis=-1, keepdims=True)
+    xc = x - mu
+    rstd = 1.0 / np.sqrt(np.mean(xc * xc, axis=-1, keepdims=True) + eps)
+    return gamma * xc * rstd + beta, mu, rstd
+
+
+def layernorm_bwd(dy, x, gamma, mu, rstd):
+    """dx = rstd * (gh - mean(gh) - xh*mean(gh*xh)); dgamma = sum dy*xh; dbeta = sum dy."""
+    xh = (x - mu) * rstd
+    gh = gamma * dy
+    dx = rstd * (gh - np.mean(gh, axis=-1, keepdims=True)
+                 - xh * np.mean(gh * xh, axis=-1, keepdims=True))
+    return dx, np.sum(dy * xh, axis=0), np.sum(dy, axis=0)
+
+
+# --------------------------------------------------------------------------- RoPE
+def rope(t, seq, base, inverse=False):
+    """Rotate head vectors t[T, nh, d] (T = batch*seq, sequence-major) by position*theta.
+
+    Pair (i, i+d/2) at position p turns by angle p*base**(-2i/d); inverse=True turns by the
+    negative angle, which is the backward of the forward rotation (a rotation's transpose).
+    """
+    T, nh, d = t.shape
+    half = d // 2
+    pos = (np.arange(T) % seq).astype(np.float64)
+    theta = base ** (-2.0 * np.arange(half, dtype=np.float64) / d)
+    ang = pos[:, None] * theta[None, :]
+    c = np.cos(ang)[:, None, :]
+    s = np.sin(ang)[:, None, :]
+    if inverse:
+        s = -s
+    a = t[..., :half]
+    b = t[..., half:]
+    return np.concatenate([a * c - b * s, a * s + b * c], axis=-1)
+
+
+# --------------------------------------------------------------------------- attention
+def attention_fwd(q, k, v, batch, seq):
+    """Causal softmax attention with grouped KV heads (FlashAttention base of Table 2 computes
+    exactly this).  q[T,nq,d], k,v[T,nkv,d] -> o[T,nq,d], lse[nq,T] (natural-log sum-exp of the
+    scaled, masked scores)."""
+    T, nq, d = q.shape
+    nkv = k.shape[1]
+    g = nq // nkv
+    scale = 1.0 / np.sqrt(d)
+    o = np.zeros_like(q)
+    lse = np.zeros((nq, T))
+    future = np.triu(np.ones((seq, seq), dtype=bool), 1)
+    for b in range(batch):
+        sl = slice(b * seq, (b + 1) * seq)
+        for h in range(nq):
+            S = (q[sl, h, :] @ k[sl, h // g, :].T) * scale
+            S[future] = -np.inf
+            m = np.max(S, axis=1, keepdims=True)
+            E = np.exp(S - m)
+            Z = np.sum(E, axis=1, keepdims=True)
+            o[sl, h, :] = (E / Z) @ v[sl, h // g, :]
+            lse[h, sl] = (m + np.log(Z))[:, 0]
+    return o, lse
+
+
+def attention_bwd(do, q, k, v, batch, seq):
+    """Chain rule of attention_fwd.  P is recomputed; dV = P^T dO, dP = dO V^T,
+    dS = P * (dP - rowsum(dP*P)), dQ = dS K * scale, dK = dS^T Q * scale; dK,dV of a kv head
+    sum over the q heads that read it."""
+    T, nq, d = q.shape
+    nkv = k.shape[1]
+    g = nq // nkv
+    scale = 1.0 / np.sqrt(d)
+    dq = np.zeros_like(q)
+    dk = np.zeros_like(k)
+    dv = np.zeros_like(v)
+    future = np.triu(np.ones((seq, seq), dtype=bool), 1)
+    for b in range(batch):
+        sl = slice(b * seq, (b + 1) * seq)
+        for h in range(nq):
+            hk = h // g
+            S = (q[sl, h, :] @ k[sl, hk, :].T) * scale
+            S[future] = -np.inf
+            E = np.exp(S - np.max(S, axis=1, keepdims=True))
+            P = E / np.sum(E, axis=1, keepdims=True)
+            dO = do[sl, h, :]
+            dv[sl, hk, :] += P.T @ dO
+            dP = dO @ v[sl, hk, :].T
+            dS = P * (dP - np.sum(dP * P, axis=1, keepdims=True))
+            dq[sl, h, :] = (dS @ k[sl, hk, :]) * scale
+            dk[sl, hk, :] += (dS.T @ q[sl, h, :]) * scale
+    return dq, dk, dv
+
+
+# --------------------------------------------------------------------------- activations
+def sigmoid(x):
+    return 1.0 / (1.0 + np.exp(-x))
+
+
+def swiglu_fwd(g, u):
+    """a = silu(g) * u, silu(g) = g * sigmoid(g)."""
+    return g * sigmoid(g) * u
+
+
+def swiglu_bwd(da, g, u):
+    """dg = da*u*sig*(1 + g*(1-sig)), du = da*g*sig."""
+    s = sigmoid(g)
+    return da * u * s * (1.0 + g * (1.0 - s)), da * g * s
+
+
+_K0 = np.sqrt(2.0 / np.pi)
+_K1 = 0.044715
+
+
+def gelu_fwd(x):
+    """tanh-form GeLU: 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3)))."""
+    return 0.5 * x * (1.0 + np.tanh(_K0 * (x + _K1 * x ** 3)))
+
+
+def gelu_bwd(dy, x):
+    t = np.tanh(_K0 * (x + _K1 * x ** 3))
+    return dy * (0.5 * (1.0 + t) + 0.5 * x * (1.0 - t * t) * _K0 * (1.0 + 3.0 * _K1 * x * x))
+
+
+# --------------------------------------------------------------------------- stand-in
+def standin_sum(own, peers):
+    """One-GPU stand-in of a tensor-parallel all-reduce (Sec. 2.1, "Collective Communication"):
+    own partial plus the frozen peer partials, added in index order."""
+    acc = np.array(own, dtype=np.float64, copy=True)
+    if peers is not None:
+        for r in range(len(peers)):
+            acc += peers[r].astype(np.float64)
+    return acc
+
+
+# --------------------------------------------------------------------------- Llama-style layer
+def llama_fwd(cfg, W, x, peers=None):
+    """Forward of one pre-norm Llama-style layer shard.  Returns (out, saved dict).
+
+    W: g1[H], Wqkv[H,n_qkv], Wo[nq*d,H], g2[H], Wgu[H,2F], Wd[F,H].
+    peers: optional dict 'ar1','ar2' -> [R-1,T,H] frozen partials of the two forward collectives.
+    """
+    peers = peers or {}
+    T, nq, nkv, d, F = cfg.T, cfg.nq, cfg.nkv, cfg.d, cfg.F
+    h1, r1 = rmsnorm_fwd(x, W["g1"], cfg.eps)
+    qkv = h1 @ W["Wqkv"]
+    q = qkv[:, : nq * d].reshape(T, nq, d)
+    k = qkv[:, nq * d: (nq + nkv) * d].reshape(T, nkv, d)
+    v = qkv[:, (nq + nkv) * d:].reshape(T, nkv, d)
+    q = rope(q, cfg.seq, cfg.rope_base)
+    k = rope(k, cfg.seq, cfg.rope_base)
+    o, lse = attention_fwd(q, k, v, cfg.batch, cfg.seq)
+    o2 = o.reshape(T, nq * d)
+    y = standin_sum(o2 @ W["Wo"], peers.get("ar1"))
+    x2 = x + y
+    h2, r2 = rmsnorm_fwd(x2, W["g2"], cfg.eps)
+    gu = h2 @ W["Wgu"]
+    g, u = gu[:, :F], gu[:, F:]
+    a = swiglu_fwd(g, u)
+    z = standin_sum(a @ W["Wd"], peers.get("ar2"))
+    out = x2 + z
+    saved = dict(x=x, r1=r1, h1=h1, q=q, k=k, v=v, o=o2, lse=lse, x2=x2, r2=r2, h2=h2, g=g, u=u, a=a)
+    return out, saved
+
+
+def llama_bwd(cfg, W, saved, dout, peers=None):
+    """Backward of llama_fwd.  Returns (dx, grads) where grads holds dWqkv, dWo, dWgu, dWd, dg1, dg2
+    (the increments that are added to the shared gradient buffers).
+    peers: optional 'ar3','ar4' -> frozen partials of the two backward collectives."""
+    peers = peers or {}
+    T, nq, nkv, d, F = cfg.T, cfg.nq, cfg.nkv, cfg.d, cfg.F
+    s = saved
+    da = dout @ W["Wd"].T
+    dWd = s["a"].T @ dout
+    dg, du = swiglu_bwd(da, s["g"], s["u"])
+    dgu = np.concatenate([dg, du], axis=1)
+    dWgu = s["h2"].T @ dgu
+    dh2 = standin_sum(dgu @ W["Wgu"].T, peers.get("ar3"))
+    dx2n, dg2 = rmsnorm_bwd(dh2, s["x2"], W["g2"], s["r2"])
+    dx2 = dout + dx2n
+    do = dx2 @ W["Wo"].T
+    dWo = s["o"].T @ dx2
+    dq, dk, dv = attention_bwd(do.reshape(T, nq, d), s["q"], s["k"], s["v"], cfg.batch, cfg.seq)
+    dq = rope(dq, cfg.seq, cfg.rope_base, inverse=True)
+    dk = rope(dk, cfg.seq, cfg.rope_base, inverse=True)
+    dqkv = np.concatenate([dq.reshape(T, -1), dk.reshape(T, -1), dv.reshape(T, -1)], axis=1)
+    dWqkv = s["h1"].T @ dqkv
+    dh1 = standin_sum(dqkv @ W["Wqkv"].T, peers.get("ar4"))
+    dxn, dg1 = rmsnorm_bwd(dh1, s["x"], W["g1"], s["r1"])
+    dx = dx2 + dxn
+    grads = dict(dWqkv=dWqkv, dWo=dWo, dWgu=dWgu, dWd=dWd, dg1=dg1, dg2=dg2)
+    inter = dict(da=da, dgu=dgu, dh2=dh2, dx2=dx2, do=do, dqkv=dqkv, dh1=dh1)
+    return dx, grads, inter
