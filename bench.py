@@ -1,0 +1,162 @@
+#!/usr/bin/env python3
+"""Benchmark of one Strand-Interleaving layer step (alpha forward || beta backward) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2_llama8b_tp8]
+
+A step = one dh_si_step over one micro-batch per strand with all inputs resident in HBM.  Prints one
+JSON line: model TFLOP/s of the step (2MNK per GEMM, causal attention at half dense, backward =
+2x forward), SI speedup over sequential alpha-then-beta through the same executor, the fraction of
+collective stand-in time hidden, the roofline of the dominant kernel and the CPU oracle baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def time_steps(fn, steps, warmup, torch):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def cpu_baseline(cfg, flops):
+    """Times the fp64 oracle (as it stands) on one strand's full forward+backward at the same shapes."""
+    import numpy as np
+    from oracle import layer_ref as R
+    from paper_2411_15871_amd import inputs as gen
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count()
+    T, H = cfg["batch"] * cfg["seq"], cfg["hidden"]
+    n_qkv = (cfg["nq"] + 2 * cfg["nkv"]) * cfg["d"]
+    ocfg = R.LayerCfg(batch=cfg["batch"], seq=cfg["seq"], H=H, nq=cfg["nq"], nkv=cfg["nkv"], d=cfg["d"], F=cfg["ffn"])
+    W = {k: v.astype(np.float64) for k, v in gen.llama_weights(H, n_qkv, cfg["nq"] * cfg["d"], cfg["ffn"], cfg["bf16"]).items()}
+    x = gen.strand_input(0, T, H, cfg["bf16"]).astype(np.float64)
+    dout = gen.strand_upstream_grad(0, T, H, cfg["bf16"]).astype(np.float64)
+    t0 = time.perf_counter()
+    _, saved = R.llama_fwd(ocfg, W, x)
+    R.llama_bwd(ocfg, W, saved, dout)
+    dt = time.perf_counter() - t0
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "sample": "one full layer forward+backward of one strand at the benchmark shapes (no peer partials), %.1f s" % dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c2_llama8b_tp8")
+    ap.add_argument("--comm-blocks", type=int, default=0, help="thread blocks per collective stand-in (0 = cover payload)")
+    ap.add_argument("--profile-reps", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the SI step is a per-GPU schedule); use --gpus 1")
+
+    import torch
+    from paper_2411_15871_amd import dhelix as dh
+    from paper_2411_15871_amd import harness as H
+
+    cfg = dict(H.CONFIGS[args.workload])
+    cfg["comm_blocks"] = args.comm_blocks
+    flops = H.model_flops(cfg)
+    run = H.LayerRun(cfg)
+    alpha, beta = run.strand(0), run.strand(1)
+    run.fwd(beta)   # beta's forward produced its saved activations earlier (untimed)
+    run.fwd(alpha)
+    run.bwd(beta)
+    torch.cuda.synchronize()
+    sa, sb, sc = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+
+    # offline part of the method: pairwise profiling and plan search (Sec. 3.2, 4.2)
+    t0 = time.perf_counter()
+    table = dh.dh_profile_pairs(run.layer, alpha.fwd_args, beta.bwd_args, run.ws, run.ws_bytes, sa, sb, sc, args.profile_reps)
+    t_prof = time.perf_counter() - t0
+    gf, gb = dh.dh_layer_op_graph(run.layer, 0), dh.dh_layer_op_graph(run.layer, 1)
+    t0 = time.perf_counter()
+    plan, predicted = dh.dh_plan_search(gf, gb, table, 5e-6, 256)
+    t_search = time.perf_counter() - t0
+    fo, bo, pairs = dh.plan_to_py(plan)
+    t_f = [table.t_fwd[i] for i in range(gf.n_ops)]
+    t_b = [table.t_bwd[j] for j in range(gb.n_ops)]
+    log("profile %.2fs, search %.2fs, predicted makespan %.1f us, sum solo %.1f us" % (t_prof, t_search, predicted * 1e6, (sum(t_f) + sum(t_b)) * 1e6))
+    log("fwd solo us:", {dh.FWD_OPS[i]: round(t_f[i] * 1e6, 1) for i in range(gf.n_ops)})
+    log("bwd solo us:", {dh.BWD_OPS[j]: round(t_b[j] * 1e6, 1) for j in range(gb.n_ops)})
+    log("plan:", [([dh.FWD_OPS[o] for o in fo[a:b]], [dh.BWD_OPS[o] for o in bo[c:d]]) for a, b, c, d in pairs])
+
+    nf, nb = gf.n_ops, gb.n_ops
+    seq_plan = dh.dh_plan_sequential(run.layer)
+    free_plan = dh.make_plan(list(range(nf)), list(range(nb)), [(0, nf, 0, nb)])
+    t_seq = time_steps(lambda: run.si_step(alpha, beta, seq_plan, sa, sb, sc), args.steps, args.warmup, torch)
+    t_free = time_steps(lambda: run.si_step(alpha, beta, free_plan, sa, sb, sc), args.steps, args.warmup, torch)
+    t_si = time_steps(lambda: run.si_step(alpha, beta, plan, sa, sb, sc), args.steps, args.warmup, torch)
+    t_comm = sum(t_f[i] for i in range(nf) if gf.is_comm[i]) + sum(t_b[j] for j in range(nb) if gb.is_comm[j])
+    log("T_seq %.1f us, T_free-running %.1f us, T_SI(plan) %.1f us, stand-ins solo %.1f us" % (t_seq * 1e6, t_free * 1e6, t_si * 1e6, t_comm * 1e6))
+
+    # roofline of the dominant kernel: the gate/up projection GEMM (largest share of the FLOPs), timed
+    # alone with events on the stream it is launched on
+    T, Hd, F = run.T, cfg["hidden"], cfg["ffn"]
+    a_mat = torch.empty(T, Hd, dtype=torch.bfloat16, device="cuda").normal_()
+    b_mat = torch.empty(Hd, 2 * F, dtype=torch.bfloat16, device="cuda").normal_(0, 0.02)
+    c_mat = torch.empty(T, 2 * F, dtype=torch.bfloat16, device="cuda")
+    wsb = dh.dh_gemm_workspace_bytes(dh.DH_BF16, 0, 0, T, 2 * F, Hd)
+    gws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    reps = 50
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(5):
+        dh.dh_gemm(dh.DH_BF16, 0, 0, T, 2 * F, Hd, a_mat, b_mat, c_mat, False, gws, wsb, sa)
+    e0.record(sa)
+    for _ in range(reps):
+        dh.dh_gemm(dh.DH_BF16, 0, 0, T, 2 * F, Hd, a_mat, b_mat, c_mat, False, gws, wsb, sa)
+    e1.record(sa)
+    torch.cuda.synchronize()
+    gemm_s = e0.elapsed_time(e1) * 1e-3 / reps
+    gemm_tflops = 2.0 * T * 2 * F * Hd / gemm_s / 1e12
+    log("dominant GEMM [%d x %d x %d]: %.1f us, %.1f TFLOP/s" % (T, 2 * F, Hd, gemm_s * 1e6, gemm_tflops))
+
+    value = flops / t_si / 1e12
+    out = {
+        "metric": "SI layer fwd+bwd TFLOP/s per MI355X (% bf16 peak); speedup vs sequential",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": t_si * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg["bf16"] else "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "tokens_per_strand": run.T, "comm_blocks": args.comm_blocks,
+                   "plan_pairs": len(pairs)},
+        "pct_bf16_peak": 100.0 * value / BF16_MFMA_PEAK_TFLOPS,
+        "tokens_per_s": run.T / t_si,
+        "speedup_vs_sequential": t_seq / t_si,
+        "ms_sequential": t_seq * 1e3, "ms_free_running": t_free * 1e3,
+        "comm_hidden_frac": (t_seq - t_si) / t_comm if t_comm > 0 else None,
+        "roofline": {"bound": "mfma", "achieved": gemm_tflops, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": gemm_tflops / BF16_MFMA_PEAK_TFLOPS, "traffic": None,
+                     "kernel": "gemm_bf16_kernel (gate/up projection %dx%dx%d)" % (T, 2 * F, Hd)},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, flops)
+    run.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,305 @@
+/*
+ * libdhelix -- one GPU's share of a Strand-Interleaving (SI) layer step on MI355X (gfx950).
+ *
+ * Strand Interleaving (paper Sec. 3.3, 4.2) co-executes the forward pass of micro-batch strand
+ * alpha with the backward pass of strand beta on one GPU.  Both strands use one copy of the
+ * weights and one weight-gradient buffer (Sec. 3.3, "share model states"), and the operators of
+ * the two strands are paired by a plan found offline from pairwise overlap profiling (Sec. 3.2,
+ * Eq. 1) with a dynamic program (Sec. 4.2, Eq. 2).
+ *
+ * General rules of this interface
+ *   - plain C ABI; every call returns a dh_status (0 = ok, negative = error) unless stated;
+ *     dh_last_error() gives a thread-local message for the last failing call.
+ *   - pointers documented "device" are raw HIP device pointers owned by the caller; the library
+ *     never allocates or frees device memory (Sec. 5: all allocation stays with one owner).
+ *     Handles (dh_layer, dh_plan) are host objects owned by the caller and freed by *_destroy.
+ *   - streams are hipStream_t passed as void*; NULL = the null stream.  Compute calls only enqueue
+ *     work and return; dh_profile_pairs and dh_plan_search run to completion on the host.
+ *   - matrices are row-major; weights are stored [in, out]; activations are [tokens, features]
+ *     with tokens = batch*seq laid out sequence after sequence.
+ *   - dtype DH_F32: every buffer float32.  DH_BF16: activations/weights bf16, statistics
+ *     (rstd, lse), weight gradients and norm-gain gradients float32, fp32 accumulation.
+ *   - feature dimensions (hidden, head_dim, ffn) must be multiples of 8; head_dim must be 64 or
+ *     128 for DH_BF16; the token count is arbitrary.  Violations return DH_ERR_SHAPE.
+ */
+#ifndef DHELIX_H
+#define DHELIX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  DH_OK = 0,
+  DH_ERR_INVALID_ARG = -1,
+  DH_ERR_SHAPE = -2,
+  DH_ERR_WORKSPACE_TOO_SMALL = -3,
+  DH_ERR_PLAN_INVALID = -4,
+  DH_ERR_HIP = -5,
+  DH_ERR_UNSUPPORTED = -6
+} dh_status;
+
+typedef enum { DH_F32 = 0, DH_BF16 = 1 } dh_dtype;
+typedef enum { DH_ARCH_LLAMA = 0 } dh_arch;
+
+/* Message of the last error raised on this thread ("" if none).  Host memory owned by the library. */
+const char* dh_last_error(void);
+
+/* ------------------------------------------------------------------------------------------
+ * Layer description: one tensor-parallel shard of a pre-norm Llama-style layer (the dense models
+ * of Sec. 6.1, Table 3): RMSNorm, QKV GEMM, RoPE, causal grouped-query attention, output GEMM,
+ * collective, residual, RMSNorm, gate/up GEMM, SwiGLU, down GEMM, collective, residual.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+  int arch;        /* dh_arch */
+  int dtype;       /* dh_dtype */
+  int batch;       /* sequences per micro-batch */
+  int seq;         /* tokens per sequence; tokens T = batch*seq */
+  int hidden;      /* H */
+  int n_q_heads;   /* local query heads */
+  int n_kv_heads;  /* local key/value heads; must divide n_q_heads */
+  int head_dim;    /* d */
+  int ffn;         /* local SwiGLU width F */
+  float eps;       /* RMSNorm epsilon */
+  float rope_base; /* RoPE base; pair (i, i+d/2) turns by position * base^(-2i/d) */
+  int n_ranks;     /* R: partials summed by each collective stand-in (1 = no peers) */
+  int comm_blocks; /* thread blocks a collective stand-in may use (its "channel" count); 0 = enough
+                      to cover the payload */
+} dh_layer_config;
+
+/* Device pointers to the shard's weights (read only).  g1,g2: [H]; Wqkv: [H,(nq+2nkv)d] with columns
+ * [q heads | k heads | v heads]; Wo: [nq*d,H]; Wgu: [H,2F] with columns [gate | up]; Wd: [F,H]. */
+typedef struct {
+  const void *g1, *Wqkv, *Wo, *g2, *Wgu, *Wd;
+} dh_weights;
+
+/* Device pointers to the float32 gradient buffers, same shapes as the weights.  The backward pass
+ * ADDS into them; one set is shared by both strands (Sec. 3.3). */
+typedef struct {
+  float *dg1, *dWqkv, *dWo, *dg2, *dWgu, *dWd;
+} dh_wgrads;
+
+typedef struct dh_layer dh_layer;
+
+/* Creates the host-side layer object (shapes, launch configuration, events).  Host only. */
+int dh_layer_create(const dh_layer_config* cfg, dh_layer** out);
+void dh_layer_destroy(dh_layer* layer);
+int dh_layer_bind_weights(dh_layer* layer, const dh_weights* w);
+int dh_layer_bind_wgrads(dh_layer* layer, const dh_wgrads* g);
+
+/* Bytes of one strand's saved-activation slot (written by forward, read by backward): rstd1, h1,
+ * rotated qkv, o, lse, x2, rstd2, h2, gate/up, a. */
+size_t dh_layer_saved_bytes(const dh_layer* layer);
+
+typedef enum { DH_WS_FWD = 0, DH_WS_BWD = 1, DH_WS_SI = 2 } dh_ws_kind;
+/* Bytes of transient workspace for a forward pass, a backward pass, or one SI step (a forward and a
+ * backward region side by side, so the two strands never share a transient buffer). */
+size_t dh_layer_workspace_bytes(const dh_layer* layer, int kind);
+
+/* One strand's forward call.  x: device [T,H] input, must stay valid and unchanged until that
+ * strand's backward has run.  out: device [T,H].  saved: device slot of dh_layer_saved_bytes.
+ * peers_ar1/peers_ar2: device [R-1,T,H] frozen partials of the two forward collectives (the other
+ * ranks' contributions; ignored when n_ranks == 1). */
+typedef struct {
+  const void* x;
+  void* out;
+  void* saved;
+  const void* peers_ar1;
+  const void* peers_ar2;
+} dh_fwd_args;
+
+/* One strand's backward call.  dout: device [T,H] upstream gradient; dx: device [T,H] result;
+ * x/saved: what the strand's forward call read/wrote; peers_ar3/peers_ar4: frozen partials of the
+ * two backward collectives. */
+typedef struct {
+  const void* dout;
+  void* dx;
+  const void* x;
+  const void* saved;
+  const void* peers_ar3;
+  const void* peers_ar4;
+} dh_bwd_args;
+
+/* Forward / backward of one strand, operators in their default order, all on `stream`
+ * (single-strand execution, the baseline of Sec. 6.1).  ws: device workspace of at least
+ * dh_layer_workspace_bytes(layer, DH_WS_FWD / DH_WS_BWD), ws_bytes its size. */
+int dh_layer_fwd(dh_layer* layer, const dh_fwd_args* a, void* ws, size_t ws_bytes, void* stream);
+int dh_layer_bwd(dh_layer* layer, const dh_bwd_args* b, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Operator graphs (Sec. 4.2, "Operator Sequencing and Partitioning").  Node ids are the operator
+ * ids below; an edge (src,dst) means src must run before dst within the strand.
+ * ------------------------------------------------------------------------------------------ */
+typedef enum {
+  DH_F_NORM1 = 0, DH_F_QKV, DH_F_ROPE, DH_F_ATTN, DH_F_PROJ, DH_F_AR1, DH_F_NORM2, DH_F_FC1,
+  DH_F_ACT, DH_F_FC2, DH_F_AR2, DH_F_BDA2, DH_F_NOPS
+} dh_fwd_op;
+typedef enum {
+  DH_B_FC2_DGRAD = 0, DH_B_FC2_WGRAD, DH_B_ACT, DH_B_FC1_DGRAD, DH_B_FC1_WGRAD, DH_B_AR3,
+  DH_B_NORM2, DH_B_PROJ_DGRAD, DH_B_PROJ_WGRAD, DH_B_ATTN, DH_B_ROPE, DH_B_QKV_DGRAD,
+  DH_B_QKV_WGRAD, DH_B_AR4, DH_B_NORM1, DH_B_NOPS
+} dh_bwd_op;
+
+#define DH_MAX_OPS 32
+#define DH_MAX_DEPS 96
+typedef struct {
+  int n_ops;
+  int is_comm[DH_MAX_OPS];   /* 1 = collective stand-in (issued on the communication stream) */
+  int n_deps;
+  int dep_src[DH_MAX_DEPS];
+  int dep_dst[DH_MAX_DEPS];
+} dh_op_graph;
+
+/* Fills the forward (direction 0) or backward (direction 1) operator graph of the layer. */
+int dh_layer_op_graph(const dh_layer* layer, int direction, dh_op_graph* out);
+/* Static name of an operator ("F_QKV", "B_ATTN", ...), NULL if out of range. */
+const char* dh_op_name(int direction, int op);
+
+/* ------------------------------------------------------------------------------------------
+ * Overlap table (Sec. 3.2): solo time of every operator and, for every (forward, backward)
+ * operator pair started together, the progress rate of each while both are active
+ * (1 = undisturbed).  From these, P(i,j) of Eq. 2 and OEF of Eq. 1 follow.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+  int n_fwd, n_bwd;
+  double t_fwd[DH_MAX_OPS];                 /* seconds */
+  double t_bwd[DH_MAX_OPS];
+  double rate_fwd[DH_MAX_OPS][DH_MAX_OPS];  /* [fwd op][bwd op] */
+  double rate_bwd[DH_MAX_OPS][DH_MAX_OPS];
+  double p_pair[DH_MAX_OPS][DH_MAX_OPS];    /* P_ij of one instance of each, seconds, from the measured rates */
+  double oef[DH_MAX_OPS][DH_MAX_OPS];       /* Eq. 1 */
+} dh_overlap_table;
+
+/* Eq. 1: (t_i + t_j - p_ij) / min(t_i, t_j).  Host only; returns the value. */
+double dh_oef(double t_i, double t_j, double p_ij);
+
+/* Co-run time of a forward segment with a backward segment under the two-queue fluid model
+ * (each strand runs its operators in order; a pair of active operators progresses at the table's
+ * rates; a lone operator at rate 1).  seg_f/seg_b: host arrays of operator ids.  Host only;
+ * returns seconds, or a negative dh_status cast to double on bad arguments. */
+double dh_segment_cost(const dh_overlap_table* t, const int* seg_f, int n_f, const int* seg_b, int n_b);
+
+/* Measures the table on the current device: every operator alone and every forward/backward pair
+ * co-started on two streams (collective stand-ins on comm_stream).  The strands' buffers must
+ * already hold a completed forward (alpha, beta) and backward (beta) so every operator has valid
+ * inputs; gradient buffers are added to.  Blocks until done.  reps: timed repetitions (>=1). */
+int dh_profile_pairs(dh_layer* layer, const dh_fwd_args* alpha, const dh_bwd_args* beta, void* ws,
+                     size_t ws_bytes, void* stream_alpha, void* stream_beta, void* comm_stream,
+                     int reps, dh_overlap_table* out);
+
+/* ------------------------------------------------------------------------------------------
+ * Plans (Sec. 4.2).  A plan = one operator sequence per strand plus segment pairs: pair k
+ * co-runs forward operators fwd_order[f_begin:f_end] with backward operators
+ * bwd_order[b_begin:b_end]; a cross-strand barrier follows every pair.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct { int f_begin, f_end, b_begin, b_end; } dh_seg_pair;
+typedef struct {
+  int n_fwd, n_bwd, n_pairs;
+  int fwd_order[DH_MAX_OPS];
+  int bwd_order[DH_MAX_OPS];
+  dh_seg_pair pairs[2 * DH_MAX_OPS];
+} dh_plan;
+
+/* Eq. 2 for given segments: p_f[i] = P(i, none), p_b[j] = P(none, j), p_fb[i*n_b + j] = P(i,j).
+ * Writes T_opt(n_f, n_b) to *t_opt; if steps != NULL writes up to n_f+n_b chosen steps as
+ * (i or -1, j or -1) pairs and their count to *n_steps.  Host only. */
+int dh_pair_dp(const double* p_f, int n_f, const double* p_b, int n_b, const double* p_fb,
+               double* t_opt, int* steps, int* n_steps);
+
+/* Plan search: enumerates topological orders of both graphs (at most max_orders per graph, 0 =
+ * library default), and for each pair of orders places barriers optimally by Eq. 2 applied over
+ * operator prefixes with dh_segment_cost (+ barrier_cost seconds per pair) as P.  Writes the best
+ * plan and its predicted makespan.  Host only. */
+int dh_plan_search(const dh_op_graph* fwd, const dh_op_graph* bwd, const dh_overlap_table* table,
+                   double barrier_cost, int max_orders, dh_plan* out, double* makespan);
+
+/* Checks that a plan's orders are permutations respecting the graphs and that its pairs tile both
+ * sequences.  Returns DH_OK or DH_ERR_PLAN_INVALID. */
+int dh_plan_validate(const dh_op_graph* fwd, const dh_op_graph* bwd, const dh_plan* plan);
+
+/* The degenerate plan "all forward, then all backward" in default order (sequential baseline). */
+int dh_plan_sequential(const dh_layer* layer, dh_plan* out);
+
+/* One SI step (Sec. 3.3, 5): forward of strand alpha and backward of strand beta, operators issued
+ * per plan on stream_alpha / stream_beta, collective stand-ins on stream_comm (NULL = issue them on
+ * the strand's own stream), barriers between segment pairs by events (no host synchronisation).
+ * On return all work is enqueued; all three streams are joined back into stream_alpha.
+ * ws: at least dh_layer_workspace_bytes(layer, DH_WS_SI). */
+int dh_si_step(dh_layer* layer, const dh_fwd_args* alpha, const dh_bwd_args* beta,
+               const dh_plan* plan, void* ws, size_t ws_bytes, void* stream_alpha,
+               void* stream_beta, void* stream_comm);
+
+/* ------------------------------------------------------------------------------------------
+ * Collective stand-in (Sec. 2.1, "Collective Communication"): a memory-bound local kernel with
+ * the payload of the collective it replaces.  DH_COMM_ALLREDUCE: out[i] = sum_r parts[r][i],
+ * added in index order in fp32.  parts: host array of n_ranks device pointers, each `elems`
+ * elements of `dtype`; out: device, elems elements.  n_blocks: 256-thread blocks the kernel may use
+ * (the analogue of a collective library's channel/thread limit, Sec. 5); 0 = enough to cover the
+ * payload (at most 2048).  Enqueued on `stream`.
+ * ------------------------------------------------------------------------------------------ */
+typedef enum { DH_COMM_ALLREDUCE = 0 } dh_comm_kind;
+int dh_comm_standin(int kind, int n_ranks, const void* const* parts, void* out, size_t elems,
+                    int dtype, int n_blocks, void* stream);
+
+/* Creates a stream whose kernels may only use n_cus compute units (spread over the chip), the
+ * analogue of limiting a collective's thread/channel count (Sec. 5).  Default priority. */
+int dh_stream_create_masked(int n_cus, void** stream);
+int dh_stream_destroy(void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Single operators, exposed for unit parity tests and micro-benchmarks.
+ * ------------------------------------------------------------------------------------------ */
+/* All take device pointers, enqueue on `stream` and return a dh_status.  dtype is the storage type of
+ * the activations (dh_dtype); rstd, lse, delta, dgamma are always float32. */
+
+/* C[M,N] (+)= opA(A) * opB(B) (GEMM operator base, Table 2).  trans_a = 0: A is [M,K]; 1: A is [K,M].
+ * trans_b = 0: B is [K,N]; 1: B is [N,K].  dtype = type of A and B; out_f32_accumulate = 0: C has
+ * dtype and is overwritten, 1: C is float32 and is added to (weight gradients).  DH_BF16 needs N and
+ * every contiguous operand dimension to be a multiple of 8 and does not build trans_a with trans_b.
+ * ws: device workspace for split-K partials of dh_gemm_workspace_bytes (fewer bytes, or NULL with
+ * ws_bytes 0, reduce or disable split-K; results then differ in rounding only). */
+int dh_gemm(int dtype, int trans_a, int trans_b, int M, int N, int K, const void* A, const void* B,
+            void* C, int out_f32_accumulate, void* ws, size_t ws_bytes, void* stream);
+size_t dh_gemm_workspace_bytes(int dtype, int trans_a, int trans_b, int M, int N, int K);
+
+/* RMSNorm forward (LayerNorm operator base, Table 2, RMS form).  If residual != NULL the fused
+ * bias-dropout-add residual is applied first: x_out = x + residual (stored), and the norm reads
+ * x_out.  h[T,H] = gamma * x * rstd, rstd[T] = (mean x^2 + eps)^(-1/2). */
+int dh_rmsnorm_fwd(int dtype, int T, int H, const void* x, const void* residual, const void* gamma,
+                   float eps, void* x_out, void* h, float* rstd, void* stream);
+/* RMSNorm backward: dx = rstd*(gamma*dy - xh*mean(gamma*dy*xh)) (+ dres if not NULL), xh = x*rstd;
+ * dgamma[H] += sum_t dy*xh (fixed summation order).  ws: dh_rmsnorm_bwd_ws_bytes(T,H) bytes. */
+int dh_rmsnorm_bwd(int dtype, int T, int H, const void* dy, const void* x, const void* gamma,
+                   const float* rstd, const void* dres, void* dx, float* dgamma, void* ws,
+                   size_t ws_bytes, void* stream);
+size_t dh_rmsnorm_bwd_ws_bytes(int T, int H);
+
+/* Rotary embedding in place on n_heads heads stored side by side at the start of each row of
+ * row_stride elements: pair (i, i+d/2) of a token at position p (= row % seq) turns by
+ * p * base^(-2i/d); inverse != 0 turns back (the backward of the rotation). */
+int dh_rope(int dtype, int T, int seq, int n_heads, int head_dim, int row_stride, float base,
+            int inverse, void* t, void* stream);
+
+/* SwiGLU: gu[T,2F] = [gate | up]; a[T,F] = gate*sigmoid(gate)*up; backward writes dgu[T,2F]. */
+int dh_swiglu_fwd(int dtype, int T, int F, const void* gu, void* a, void* stream);
+int dh_swiglu_bwd(int dtype, int T, int F, const void* gu, const void* da, void* dgu, void* stream);
+
+/* out[i] = a[i] + b[i], n elements (n multiple of 8): the residual of the bias-dropout-add operator. */
+int dh_add(int dtype, size_t n, const void* a, const void* b, void* out, void* stream);
+
+/* Causal grouped-query attention (FlashAttention operator base, Table 2).  qkv[T,(nq+2nkv)d] =
+ * [q heads | k heads | v heads] (already rotated); o[T,nq*d]; lse[nq,T] natural-log sum-exp of the
+ * scaled masked scores; attention is per sequence (T = batch*seq).  Backward writes dqkv (same
+ * layout as qkv; dk,dv summed over the query heads of each group) and uses delta[nq,T] as scratch. */
+int dh_attn_fwd(int dtype, int batch, int seq, int nq, int nkv, int d, const void* qkv, void* o,
+                float* lse, void* stream);
+int dh_attn_bwd(int dtype, int batch, int seq, int nq, int nkv, int d, const void* qkv, const void* o,
+                const void* dout, const float* lse, void* dqkv, float* delta, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

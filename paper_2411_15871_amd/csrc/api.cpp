@@ -1,0 +1,64 @@
+// Error reporting and the generic single-operator entry points of libdhelix.
+#include <cstdarg>
+#include <cstdio>
+#include "common.h"
+
+static thread_local char g_err[512] = "";
+
+int dh_set_error(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+extern "C" const char* dh_last_error(void) { return g_err; }
+
+extern "C" int dh_gemm(int dtype, int trans_a, int trans_b, int M, int N, int K, const void* A, const void* B, void* C,
+                       int out_f32_accumulate, void* ws, size_t ws_bytes, void* stream) {
+  if (M < 0 || N < 0 || K < 0) DH_FAIL(DH_ERR_SHAPE, "gemm: negative dimension");
+  if (M > 0 && N > 0 && (!C || (K > 0 && (!A || !B)))) DH_FAIL(DH_ERR_INVALID_ARG, "gemm: null pointer");
+  if (dtype == DH_F32)
+    return dh_launch_gemm_f32(trans_a != 0, trans_b != 0, M, N, K, (const float*)A, (const float*)B, (float*)C,
+                              out_f32_accumulate != 0, (hipStream_t)stream);
+  if (dtype == DH_BF16)
+    return dh_launch_gemm_bf16(trans_a != 0, trans_b != 0, M, N, K, (const bf16_t*)A, (const bf16_t*)B, C,
+                               out_f32_accumulate != 0, ws, ws_bytes, (hipStream_t)stream);
+  DH_FAIL(DH_ERR_INVALID_ARG, "gemm: unknown dtype %d", dtype);
+}
+
+extern "C" size_t dh_gemm_workspace_bytes(int dtype, int trans_a, int trans_b, int M, int N, int K) {
+  if (dtype != DH_BF16 || M <= 0 || N <= 0 || K <= 0) return 0;
+  return dh_gemm_bf16_ws_bytes(trans_a != 0, trans_b != 0, M, N, K);
+}
+
+static int check_attn(const char* who, int batch, int seq, int nq, int nkv, int d) {
+  if (batch < 0 || seq < 0 || nq <= 0 || nkv <= 0 || nq % nkv || d <= 0 || d % 8)
+    DH_FAIL(DH_ERR_SHAPE, "%s: batch=%d seq=%d nq=%d nkv=%d d=%d", who, batch, seq, nq, nkv, d);
+  return DH_OK;
+}
+
+extern "C" int dh_attn_fwd(int dtype, int batch, int seq, int nq, int nkv, int d, const void* qkv, void* o, float* lse,
+                           void* stream) {
+  int rc = check_attn("attn_fwd", batch, seq, nq, nkv, d);
+  if (rc) return rc;
+  if (batch * seq > 0 && (!qkv || !o || !lse)) DH_FAIL(DH_ERR_INVALID_ARG, "attn_fwd: null pointer");
+  if (dtype == DH_F32) return dh_launch_attn_fwd_f32(batch, seq, nq, nkv, d, (const float*)qkv, (float*)o, lse, (hipStream_t)stream);
+  if (dtype == DH_BF16) return dh_launch_attn_fwd_bf16(batch, seq, nq, nkv, d, (const bf16_t*)qkv, (bf16_t*)o, lse, (hipStream_t)stream);
+  DH_FAIL(DH_ERR_INVALID_ARG, "attn_fwd: unknown dtype %d", dtype);
+}
+
+extern "C" int dh_attn_bwd(int dtype, int batch, int seq, int nq, int nkv, int d, const void* qkv, const void* o,
+                           const void* dout, const float* lse, void* dqkv, float* delta, void* stream) {
+  int rc = check_attn("attn_bwd", batch, seq, nq, nkv, d);
+  if (rc) return rc;
+  if (batch * seq > 0 && (!qkv || !o || !dout || !lse || !dqkv || !delta)) DH_FAIL(DH_ERR_INVALID_ARG, "attn_bwd: null pointer");
+  if (dtype == DH_F32)
+    return dh_launch_attn_bwd_f32(batch, seq, nq, nkv, d, (const float*)qkv, (const float*)o, (const float*)dout, lse,
+                                  (float*)dqkv, delta, (hipStream_t)stream);
+  if (dtype == DH_BF16)
+    return dh_launch_attn_bwd_bf16(batch, seq, nq, nkv, d, (const bf16_t*)qkv, (const bf16_t*)o, (const bf16_t*)dout, lse,
+                                   (bf16_t*)dqkv, delta, (hipStream_t)stream);
+  DH_FAIL(DH_ERR_INVALID_ARG, "attn_bwd: unknown dtype %d", dtype);
+}

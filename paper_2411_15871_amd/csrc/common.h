@@ -1,0 +1,106 @@
+// Shared declarations of libdhelix's HIP sources (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/dhelix.h"
+
+typedef __bf16 bf16_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+// ---- error plumbing (host) -------------------------------------------------------------------
+int dh_set_error(int code, const char* fmt, ...);
+#define DH_FAIL(code, ...) return dh_set_error(code, __VA_ARGS__)
+#define DH_HIP(expr)                                                                     \
+  do {                                                                                   \
+    hipError_t _e = (expr);                                                              \
+    if (_e != hipSuccess)                                                                \
+      return dh_set_error(DH_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(_e));    \
+  } while (0)
+#define DH_LAUNCH_CHECK()                                                                \
+  do {                                                                                   \
+    hipError_t _e = hipGetLastError();                                                   \
+    if (_e != hipSuccess)                                                                \
+      return dh_set_error(DH_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(_e));\
+  } while (0)
+
+static inline size_t dh_elem_size(int dtype) { return dtype == DH_BF16 ? 2 : 4; }
+static inline size_t dh_align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- device helpers ----------------------------------------------------------------------------
+// bf16 <-> fp32.  Conversion to bf16 rounds to nearest even.
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16_t v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }
+
+// 8-element vector of the storage type, loaded/stored with the widest access.
+template <typename T> struct Vec8;
+template <> struct Vec8<float> {
+  float v[8];
+  __device__ __forceinline__ void load(const float* p) {
+    const float4* q = reinterpret_cast<const float4*>(p);
+    float4 a = q[0], b = q[1];
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+  __device__ __forceinline__ void store(float* p) const {
+    float4* q = reinterpret_cast<float4*>(p);
+    q[0] = make_float4(v[0], v[1], v[2], v[3]);
+    q[1] = make_float4(v[4], v[5], v[6], v[7]);
+  }
+};
+template <> struct Vec8<bf16_t> {
+  float v[8];
+  __device__ __forceinline__ void load(const bf16_t* p) {
+    bf16x8 t = *reinterpret_cast<const bf16x8*>(p);
+#pragma unroll
+    for (int i = 0; i < 8; i++) v[i] = (float)t[i];
+  }
+  __device__ __forceinline__ void store(bf16_t* p) const {
+    bf16x8 t;
+#pragma unroll
+    for (int i = 0; i < 8; i++) t[i] = (bf16_t)v[i];
+    *reinterpret_cast<bf16x8*>(p) = t;
+  }
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+// Sum over a 256-thread block; every thread gets the result.  red: 8 floats of LDS.
+__device__ __forceinline__ float block256_sum(float v, float* red) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+
+// ---- internal launchers (host, defined in the .hip files) ------------------------------------
+// All return a dh_status and only enqueue work on `stream`.
+int dh_launch_gemm_f32(bool ta, bool tb, int M, int N, int K, const float* A, const float* B, float* C,
+                       bool accumulate, hipStream_t stream);
+int dh_launch_gemm_bf16(bool ta, bool tb, int M, int N, int K, const bf16_t* A, const bf16_t* B, void* C,
+                        bool out_f32_accumulate, void* ws, size_t ws_bytes, hipStream_t stream);
+size_t dh_gemm_bf16_ws_bytes(bool ta, bool tb, int M, int N, int K);
+int dh_launch_attn_fwd_f32(int batch, int seq, int nq, int nkv, int d, const float* qkv, float* o, float* lse,
+                           hipStream_t stream);
+int dh_launch_attn_bwd_f32(int batch, int seq, int nq, int nkv, int d, const float* qkv, const float* o,
+                           const float* dout, const float* lse, float* dqkv, float* delta, hipStream_t stream);
+int dh_launch_attn_fwd_bf16(int batch, int seq, int nq, int nkv, int d, const bf16_t* qkv, bf16_t* o, float* lse,
+                            hipStream_t stream);
+int dh_launch_attn_bwd_bf16(int batch, int seq, int nq, int nkv, int d, const bf16_t* qkv, const bf16_t* o,
+                            const bf16_t* dout, const float* lse, bf16_t* dqkv, float* delta, hipStream_t stream);

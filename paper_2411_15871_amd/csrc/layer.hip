@@ -1,0 +1,523 @@
+// The layer object, its operator table, single-strand forward/backward, the Strand-Interleaving
+// executor (paper Sec. 3.3 and 5) and the pairwise overlap profiler (Sec. 3.2).
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <vector>
+#include "common.h"
+
+extern "C" size_t dh_rmsnorm_bwd_ws_bytes(int T, int H);
+extern "C" int dh_add(int dtype, size_t n, const void* a, const void* b, void* out, void* stream);
+extern "C" int dh_plan_validate(const dh_op_graph* fwd, const dh_op_graph* bwd, const dh_plan* plan);
+
+#define DH_EVENT_POOL 256
+
+struct dh_layer {
+  dh_layer_config c;
+  int T, n_qkv, n_o;
+  size_t es;  // bytes per activation element
+  dh_weights w;
+  dh_wgrads g;
+  bool have_w, have_g;
+  // saved-slot offsets (bytes)
+  size_t s_rstd1, s_h1, s_qkv, s_o, s_lse, s_x2, s_rstd2, s_h2, s_gu, s_a, saved_bytes;
+  // forward workspace offsets
+  size_t f_part, f_red, f_gemm, f_gemm_bytes, fwd_bytes;
+  // backward workspace offsets
+  size_t b_da, b_dgu, b_part, b_red, b_dx2, b_do, b_dqkv, b_delta, b_norm, b_norm_bytes, b_gemm, b_gemm_bytes, bwd_bytes;
+  hipEvent_t ev[DH_EVENT_POOL];  // created on the first SI step (needs a device)
+  bool have_events;
+  int ev_next;
+  dh_op_graph gf, gb;
+};
+
+static const char* kFwdNames[DH_F_NOPS] = {"F_NORM1", "F_QKV", "F_ROPE", "F_ATTN", "F_PROJ", "F_AR1",
+                                           "F_NORM2", "F_FC1", "F_ACT", "F_FC2", "F_AR2", "F_BDA2"};
+static const char* kBwdNames[DH_B_NOPS] = {"B_FC2_DGRAD", "B_FC2_WGRAD", "B_ACT", "B_FC1_DGRAD", "B_FC1_WGRAD",
+                                           "B_AR3", "B_NORM2", "B_PROJ_DGRAD", "B_PROJ_WGRAD", "B_ATTN",
+                                           "B_ROPE", "B_QKV_DGRAD", "B_QKV_WGRAD", "B_AR4", "B_NORM1"};
+
+extern "C" const char* dh_op_name(int direction, int op) {
+  if (direction == 0) return op >= 0 && op < DH_F_NOPS ? kFwdNames[op] : nullptr;
+  if (direction == 1) return op >= 0 && op < DH_B_NOPS ? kBwdNames[op] : nullptr;
+  return nullptr;
+}
+
+static void add_dep(dh_op_graph& g, int s, int d) {
+  g.dep_src[g.n_deps] = s;
+  g.dep_dst[g.n_deps] = d;
+  g.n_deps++;
+}
+
+// Forward: a chain.  Backward: the data-gradient chain plus four weight-gradient GEMMs, each
+// depending only on the operator that produces its dY (Sec. 4.2: wgrad may move in the sequence).
+static void build_graphs(dh_layer* L) {
+  dh_op_graph& f = L->gf;
+  memset(&f, 0, sizeof(f));
+  f.n_ops = DH_F_NOPS;
+  for (int i = 0; i + 1 < DH_F_NOPS; i++) add_dep(f, i, i + 1);
+  f.is_comm[DH_F_AR1] = f.is_comm[DH_F_AR2] = 1;
+  dh_op_graph& b = L->gb;
+  memset(&b, 0, sizeof(b));
+  b.n_ops = DH_B_NOPS;
+  const int chain[] = {DH_B_FC2_DGRAD, DH_B_ACT, DH_B_FC1_DGRAD, DH_B_AR3, DH_B_NORM2, DH_B_PROJ_DGRAD,
+                       DH_B_ATTN, DH_B_ROPE, DH_B_QKV_DGRAD, DH_B_AR4, DH_B_NORM1};
+  for (size_t i = 0; i + 1 < sizeof(chain) / sizeof(int); i++) add_dep(b, chain[i], chain[i + 1]);
+  add_dep(b, DH_B_ACT, DH_B_FC1_WGRAD);     // needs dgu
+  add_dep(b, DH_B_NORM2, DH_B_PROJ_WGRAD);  // needs dx2
+  add_dep(b, DH_B_ROPE, DH_B_QKV_WGRAD);    // needs dqkv
+  // FC2_WGRAD needs only the upstream gradient and the saved activation: no predecessor.
+  b.is_comm[DH_B_AR3] = b.is_comm[DH_B_AR4] = 1;
+}
+
+extern "C" int dh_layer_op_graph(const dh_layer* layer, int direction, dh_op_graph* out) {
+  if (!layer || !out || (direction != 0 && direction != 1)) DH_FAIL(DH_ERR_INVALID_ARG, "layer_op_graph: bad arguments");
+  *out = direction == 0 ? layer->gf : layer->gb;
+  return DH_OK;
+}
+
+static size_t take(size_t& cur, size_t bytes) {
+  size_t o = cur;
+  cur += dh_align_up(bytes, 256);
+  return o;
+}
+
+extern "C" int dh_layer_create(const dh_layer_config* cfg, dh_layer** out) {
+  if (!cfg || !out) DH_FAIL(DH_ERR_INVALID_ARG, "layer_create: null pointer");
+  const dh_layer_config& c = *cfg;
+  if (c.arch != DH_ARCH_LLAMA) DH_FAIL(DH_ERR_UNSUPPORTED, "layer_create: arch %d not supported", c.arch);
+  if (c.dtype != DH_F32 && c.dtype != DH_BF16) DH_FAIL(DH_ERR_INVALID_ARG, "layer_create: dtype %d", c.dtype);
+  if (c.batch < 0 || c.seq < 0 || c.hidden <= 0 || c.n_q_heads <= 0 || c.n_kv_heads <= 0 || c.head_dim <= 0 || c.ffn <= 0)
+    DH_FAIL(DH_ERR_SHAPE, "layer_create: non-positive dimension");
+  if (c.n_q_heads % c.n_kv_heads) DH_FAIL(DH_ERR_SHAPE, "layer_create: n_kv_heads %d must divide n_q_heads %d", c.n_kv_heads, c.n_q_heads);
+  if (c.hidden % 8 || c.ffn % 8 || c.head_dim % 16) DH_FAIL(DH_ERR_SHAPE, "layer_create: hidden/ffn must be multiples of 8 and head_dim of 16");
+  if (c.hidden > 16384) DH_FAIL(DH_ERR_SHAPE, "layer_create: hidden %d above 16384", c.hidden);
+  if (c.dtype == DH_BF16 && c.head_dim != 64 && c.head_dim != 128) DH_FAIL(DH_ERR_SHAPE, "layer_create: bf16 needs head_dim 64 or 128");
+  if (c.dtype == DH_F32 && c.head_dim > 256) DH_FAIL(DH_ERR_SHAPE, "layer_create: fp32 needs head_dim <= 256");
+  if (c.n_ranks < 1 || c.n_ranks > 16) DH_FAIL(DH_ERR_INVALID_ARG, "layer_create: n_ranks %d outside 1..16", c.n_ranks);
+  if (c.comm_blocks < 0 || c.comm_blocks > 65536) DH_FAIL(DH_ERR_INVALID_ARG, "layer_create: comm_blocks %d outside 0..65536", c.comm_blocks);
+  if ((long long)c.batch * c.seq > (1 << 24)) DH_FAIL(DH_ERR_SHAPE, "layer_create: too many tokens");
+  dh_layer* L = new dh_layer();
+  L->c = c;
+  L->T = c.batch * c.seq;
+  L->n_qkv = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+  L->n_o = c.n_q_heads * c.head_dim;
+  L->es = dh_elem_size(c.dtype);
+  L->have_w = L->have_g = false;
+  const size_t T = L->T, H = c.hidden, F = c.ffn, es = L->es;
+  size_t cur = 0;
+  L->s_rstd1 = take(cur, T * 4);
+  L->s_h1 = take(cur, T * H * es);
+  L->s_qkv = take(cur, T * L->n_qkv * es);
+  L->s_o = take(cur, T * L->n_o * es);
+  L->s_lse = take(cur, (size_t)c.n_q_heads * T * 4);
+  L->s_x2 = take(cur, T * H * es);
+  L->s_rstd2 = take(cur, T * 4);
+  L->s_h2 = take(cur, T * H * es);
+  L->s_gu = take(cur, T * 2 * F * es);
+  L->s_a = take(cur, T * F * es);
+  L->saved_bytes = cur;
+  const bool bf = c.dtype == DH_BF16;
+  auto gw = [&](bool ta, bool tb, int M, int N, int K) { return bf ? dh_gemm_bf16_ws_bytes(ta, tb, M, N, K) : (size_t)0; };
+  cur = 0;
+  L->f_part = take(cur, T * H * es);
+  L->f_red = take(cur, T * H * es);
+  L->f_gemm_bytes = std::max(std::max(gw(0, 0, T, L->n_qkv, H), gw(0, 0, T, H, L->n_o)), std::max(gw(0, 0, T, 2 * F, H), gw(0, 0, T, H, F)));
+  L->f_gemm = take(cur, L->f_gemm_bytes);
+  L->fwd_bytes = cur;
+  cur = 0;
+  L->b_da = take(cur, T * F * es);
+  L->b_dgu = take(cur, T * 2 * F * es);
+  L->b_part = take(cur, T * H * es);
+  L->b_red = take(cur, T * H * es);
+  L->b_dx2 = take(cur, T * H * es);
+  L->b_do = take(cur, T * L->n_o * es);
+  L->b_dqkv = take(cur, T * L->n_qkv * es);
+  L->b_delta = take(cur, (size_t)c.n_q_heads * T * 4);
+  L->b_norm_bytes = dh_rmsnorm_bwd_ws_bytes(L->T, c.hidden);
+  L->b_norm = take(cur, L->b_norm_bytes);
+  size_t gb = 0;
+  gb = std::max(gb, gw(0, 1, T, F, H));           // da = dout * Wd^T
+  gb = std::max(gb, gw(1, 0, F, H, T));           // dWd
+  gb = std::max(gb, gw(0, 1, T, H, 2 * F));       // dh2 = dgu * Wgu^T
+  gb = std::max(gb, gw(1, 0, H, 2 * F, T));       // dWgu
+  gb = std::max(gb, gw(0, 1, T, L->n_o, H));      // do = dx2 * Wo^T
+  gb = std::max(gb, gw(1, 0, L->n_o, H, T));      // dWo
+  gb = std::max(gb, gw(0, 1, T, H, L->n_qkv));    // dh1 = dqkv * Wqkv^T
+  gb = std::max(gb, gw(1, 0, H, L->n_qkv, T));    // dWqkv
+  L->b_gemm_bytes = gb;
+  L->b_gemm = take(cur, gb);
+  L->bwd_bytes = cur;
+  build_graphs(L);
+  for (int i = 0; i < DH_EVENT_POOL; i++) L->ev[i] = nullptr;
+  L->have_events = false;
+  L->ev_next = 0;
+  *out = L;
+  return DH_OK;
+}
+
+extern "C" void dh_layer_destroy(dh_layer* L) {
+  if (!L) return;
+  for (int i = 0; i < DH_EVENT_POOL; i++)
+    if (L->ev[i]) (void)hipEventDestroy(L->ev[i]);
+  delete L;
+}
+
+extern "C" int dh_layer_bind_weights(dh_layer* L, const dh_weights* w) {
+  if (!L || !w) DH_FAIL(DH_ERR_INVALID_ARG, "bind_weights: null pointer");
+  if (!w->g1 || !w->Wqkv || !w->Wo || !w->g2 || !w->Wgu || !w->Wd) DH_FAIL(DH_ERR_INVALID_ARG, "bind_weights: a weight pointer is null");
+  L->w = *w;
+  L->have_w = true;
+  return DH_OK;
+}
+
+extern "C" int dh_layer_bind_wgrads(dh_layer* L, const dh_wgrads* g) {
+  if (!L || !g) DH_FAIL(DH_ERR_INVALID_ARG, "bind_wgrads: null pointer");
+  if (!g->dg1 || !g->dWqkv || !g->dWo || !g->dg2 || !g->dWgu || !g->dWd) DH_FAIL(DH_ERR_INVALID_ARG, "bind_wgrads: a gradient pointer is null");
+  L->g = *g;
+  L->have_g = true;
+  return DH_OK;
+}
+
+extern "C" size_t dh_layer_saved_bytes(const dh_layer* L) { return L ? L->saved_bytes : 0; }
+
+extern "C" size_t dh_layer_workspace_bytes(const dh_layer* L, int kind) {
+  if (!L) return 0;
+  if (kind == DH_WS_FWD) return L->fwd_bytes;
+  if (kind == DH_WS_BWD) return L->bwd_bytes;
+  if (kind == DH_WS_SI) return L->fwd_bytes + L->bwd_bytes;
+  return 0;
+}
+
+// ------------------------------------------------------------------------------------ operators
+static int gemm(const dh_layer* L, bool ta, bool tb, int M, int N, int K, const void* A, const void* B, void* C, bool acc,
+                void* ws, size_t ws_bytes, hipStream_t s) {
+  if (L->c.dtype == DH_BF16)
+    return dh_launch_gemm_bf16(ta, tb, M, N, K, (const bf16_t*)A, (const bf16_t*)B, C, acc, ws, ws_bytes, s);
+  return dh_launch_gemm_f32(ta, tb, M, N, K, (const float*)A, (const float*)B, (float*)C, acc, s);
+}
+
+static int allreduce(const dh_layer* L, const void* own, const void* peers, void* out, hipStream_t s) {
+  const void* parts[16];
+  const size_t n = (size_t)L->T * L->c.hidden;
+  parts[0] = own;
+  for (int r = 1; r < L->c.n_ranks; r++) parts[r] = (const char*)peers + (size_t)(r - 1) * n * L->es;
+  return dh_comm_standin(DH_COMM_ALLREDUCE, L->c.n_ranks, parts, out, n, L->c.dtype, L->c.comm_blocks, (void*)s);
+}
+
+static int run_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hipStream_t s) {
+  const dh_layer_config& c = L->c;
+  const int T = L->T, H = c.hidden, F = c.ffn, dt = c.dtype;
+  char* sv = (char*)a.saved;
+  void* gws = ws + L->f_gemm;
+  switch (op) {
+    case DH_F_NORM1:
+      return dh_rmsnorm_fwd(dt, T, H, a.x, nullptr, L->w.g1, c.eps, nullptr, sv + L->s_h1, (float*)(sv + L->s_rstd1), s);
+    case DH_F_QKV:
+      return gemm(L, false, false, T, L->n_qkv, H, sv + L->s_h1, L->w.Wqkv, sv + L->s_qkv, false, gws, L->f_gemm_bytes, s);
+    case DH_F_ROPE:
+      return dh_rope(dt, T, c.seq, c.n_q_heads + c.n_kv_heads, c.head_dim, L->n_qkv, c.rope_base, 0, sv + L->s_qkv, s);
+    case DH_F_ATTN:
+      return dh_attn_fwd(dt, c.batch, c.seq, c.n_q_heads, c.n_kv_heads, c.head_dim, sv + L->s_qkv, sv + L->s_o,
+                         (float*)(sv + L->s_lse), s);
+    case DH_F_PROJ:
+      return gemm(L, false, false, T, H, L->n_o, sv + L->s_o, L->w.Wo, ws + L->f_part, false, gws, L->f_gemm_bytes, s);
+    case DH_F_AR1:
+      return allreduce(L, ws + L->f_part, a.peers_ar1, ws + L->f_red, s);
+    case DH_F_NORM2:  // x2 = x + y (residual of the bias-dropout-add operator), h2 = norm(x2)
+      return dh_rmsnorm_fwd(dt, T, H, a.x, ws + L->f_red, L->w.g2, c.eps, sv + L->s_x2, sv + L->s_h2, (float*)(sv + L->s_rstd2), s);
+    case DH_F_FC1:
+      return gemm(L, false, false, T, 2 * F, H, sv + L->s_h2, L->w.Wgu, sv + L->s_gu, false, gws, L->f_gemm_bytes, s);
+    case DH_F_ACT:
+      return dh_swiglu_fwd(dt, T, F, sv + L->s_gu, sv + L->s_a, s);
+    case DH_F_FC2:
+      return gemm(L, false, false, T, H, F, sv + L->s_a, L->w.Wd, ws + L->f_part, false, gws, L->f_gemm_bytes, s);
+    case DH_F_AR2:
+      return allreduce(L, ws + L->f_part, a.peers_ar2, ws + L->f_red, s);
+    case DH_F_BDA2:
+      return dh_add(dt, (size_t)T * H, sv + L->s_x2, ws + L->f_red, a.out, s);
+  }
+  DH_FAIL(DH_ERR_INVALID_ARG, "unknown forward operator %d", op);
+}
+
+static int run_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipStream_t s) {
+  const dh_layer_config& c = L->c;
+  const int T = L->T, H = c.hidden, F = c.ffn, dt = c.dtype;
+  const char* sv = (const char*)b.saved;
+  void* gws = ws + L->b_gemm;
+  const size_t gwb = L->b_gemm_bytes;
+  switch (op) {
+    case DH_B_FC2_DGRAD:
+      return gemm(L, false, true, T, F, H, b.dout, L->w.Wd, ws + L->b_da, false, gws, gwb, s);
+    case DH_B_FC2_WGRAD:
+      return gemm(L, true, false, F, H, T, sv + L->s_a, b.dout, L->g.dWd, true, gws, gwb, s);
+    case DH_B_ACT:
+      return dh_swiglu_bwd(dt, T, F, sv + L->s_gu, ws + L->b_da, ws + L->b_dgu, s);
+    case DH_B_FC1_DGRAD:
+      return gemm(L, false, true, T, H, 2 * F, ws + L->b_dgu, L->w.Wgu, ws + L->b_part, false, gws, gwb, s);
+    case DH_B_FC1_WGRAD:
+      return gemm(L, true, false, H, 2 * F, T, sv + L->s_h2, ws + L->b_dgu, L->g.dWgu, true, gws, gwb, s);
+    case DH_B_AR3:
+      return allreduce(L, ws + L->b_part, b.peers_ar3, ws + L->b_red, s);
+    case DH_B_NORM2:  // dx2 = dout + norm2_bwd(dh2)
+      return dh_rmsnorm_bwd(dt, T, H, ws + L->b_red, sv + L->s_x2, L->w.g2, (const float*)(sv + L->s_rstd2), b.dout,
+                            ws + L->b_dx2, L->g.dg2, ws + L->b_norm, L->b_norm_bytes, s);
+    case DH_B_PROJ_DGRAD:
+      return gemm(L, false, true, T, L->n_o, H, ws + L->b_dx2, L->w.Wo, ws + L->b_do, false, gws, gwb, s);
+    case DH_B_PROJ_WGRAD:
+      return gemm(L, true, false, L->n_o, H, T, sv + L->s_o, ws + L->b_dx2, L->g.dWo, true, gws, gwb, s);
+    case DH_B_ATTN:
+      return dh_attn_bwd(dt, c.batch, c.seq, c.n_q_heads, c.n_kv_heads, c.head_dim, sv + L->s_qkv, sv + L->s_o, ws + L->b_do,
+                         (const float*)(sv + L->s_lse), ws + L->b_dqkv, (float*)(ws + L->b_delta), s);
+    case DH_B_ROPE:
+      return dh_rope(dt, T, c.seq, c.n_q_heads + c.n_kv_heads, c.head_dim, L->n_qkv, c.rope_base, 1, ws + L->b_dqkv, s);
+    case DH_B_QKV_DGRAD:
+      return gemm(L, false, true, T, H, L->n_qkv, ws + L->b_dqkv, L->w.Wqkv, ws + L->b_part, false, gws, gwb, s);
+    case DH_B_QKV_WGRAD:
+      return gemm(L, true, false, H, L->n_qkv, T, sv + L->s_h1, ws + L->b_dqkv, L->g.dWqkv, true, gws, gwb, s);
+    case DH_B_AR4:
+      return allreduce(L, ws + L->b_part, b.peers_ar4, ws + L->b_red, s);
+    case DH_B_NORM1:  // dx = dx2 + norm1_bwd(dh1)
+      return dh_rmsnorm_bwd(dt, T, H, ws + L->b_red, b.x, L->w.g1, (const float*)(sv + L->s_rstd1), ws + L->b_dx2, b.dx,
+                            L->g.dg1, ws + L->b_norm, L->b_norm_bytes, s);
+  }
+  DH_FAIL(DH_ERR_INVALID_ARG, "unknown backward operator %d", op);
+}
+
+static int check_fwd_args(const dh_layer* L, const dh_fwd_args* a) {
+  if (!L || !a) DH_FAIL(DH_ERR_INVALID_ARG, "forward: null pointer");
+  if (!L->have_w) DH_FAIL(DH_ERR_INVALID_ARG, "forward: weights not bound");
+  if (L->T > 0 && (!a->x || !a->out || !a->saved)) DH_FAIL(DH_ERR_INVALID_ARG, "forward: x/out/saved is null");
+  if (L->T > 0 && L->c.n_ranks > 1 && (!a->peers_ar1 || !a->peers_ar2)) DH_FAIL(DH_ERR_INVALID_ARG, "forward: peer partials are null but n_ranks > 1");
+  return DH_OK;
+}
+static int check_bwd_args(const dh_layer* L, const dh_bwd_args* b) {
+  if (!L || !b) DH_FAIL(DH_ERR_INVALID_ARG, "backward: null pointer");
+  if (!L->have_w || !L->have_g) DH_FAIL(DH_ERR_INVALID_ARG, "backward: weights or gradient buffers not bound");
+  if (L->T > 0 && (!b->dout || !b->dx || !b->x || !b->saved)) DH_FAIL(DH_ERR_INVALID_ARG, "backward: dout/dx/x/saved is null");
+  if (L->T > 0 && L->c.n_ranks > 1 && (!b->peers_ar3 || !b->peers_ar4)) DH_FAIL(DH_ERR_INVALID_ARG, "backward: peer partials are null but n_ranks > 1");
+  return DH_OK;
+}
+static int check_ws(const dh_layer* L, int kind, const void* ws, size_t ws_bytes) {
+  size_t need = dh_layer_workspace_bytes(L, kind);
+  if (need > 0 && (!ws || ws_bytes < need)) DH_FAIL(DH_ERR_WORKSPACE_TOO_SMALL, "workspace %zu bytes, need %zu", ws_bytes, need);
+  if (((uintptr_t)ws & 255) != 0) DH_FAIL(DH_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+  return DH_OK;
+}
+
+extern "C" int dh_layer_fwd(dh_layer* L, const dh_fwd_args* a, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_fwd_args(L, a);
+  if (rc) return rc;
+  if ((rc = check_ws(L, DH_WS_FWD, ws, ws_bytes))) return rc;
+  if (L->T == 0) return DH_OK;
+  for (int op = 0; op < DH_F_NOPS; op++)
+    if ((rc = run_fwd_op(L, op, *a, (char*)ws, (hipStream_t)stream))) return rc;
+  return DH_OK;
+}
+
+extern "C" int dh_layer_bwd(dh_layer* L, const dh_bwd_args* b, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_bwd_args(L, b);
+  if (rc) return rc;
+  if ((rc = check_ws(L, DH_WS_BWD, ws, ws_bytes))) return rc;
+  if (L->T == 0) return DH_OK;
+  for (int op = 0; op < DH_B_NOPS; op++)
+    if ((rc = run_bwd_op(L, op, *b, (char*)ws, (hipStream_t)stream))) return rc;
+  return DH_OK;
+}
+
+extern "C" int dh_plan_sequential(const dh_layer* L, dh_plan* out) {
+  if (!L || !out) DH_FAIL(DH_ERR_INVALID_ARG, "plan_sequential: null pointer");
+  memset(out, 0, sizeof(*out));
+  out->n_fwd = DH_F_NOPS;
+  out->n_bwd = DH_B_NOPS;
+  for (int i = 0; i < DH_F_NOPS; i++) out->fwd_order[i] = i;
+  for (int j = 0; j < DH_B_NOPS; j++) out->bwd_order[j] = j;
+  out->n_pairs = 2;
+  out->pairs[0] = {0, DH_F_NOPS, 0, 0};
+  out->pairs[1] = {DH_F_NOPS, DH_F_NOPS, 0, DH_B_NOPS};
+  return DH_OK;
+}
+
+// ------------------------------------------------------------------------------------ SI executor
+static int ensure_events(dh_layer* L) {
+  if (L->have_events) return DH_OK;
+  for (int i = 0; i < DH_EVENT_POOL; i++)
+    if (!L->ev[i]) DH_HIP(hipEventCreateWithFlags(&L->ev[i], hipEventDisableTiming));
+  L->have_events = true;
+  return DH_OK;
+}
+
+static hipEvent_t next_event(dh_layer* L) {
+  hipEvent_t e = L->ev[L->ev_next];
+  L->ev_next = (L->ev_next + 1) % DH_EVENT_POOL;
+  return e;
+}
+
+// Runs `launch` on the communication stream between the work already queued on `strand` and the
+// work queued on it afterwards.
+template <typename Fn>
+static int on_comm_stream(dh_layer* L, hipStream_t strand, hipStream_t comm, Fn launch) {
+  if (comm == nullptr || comm == strand) return launch(strand);
+  hipEvent_t before = next_event(L), after = next_event(L);
+  DH_HIP(hipEventRecord(before, strand));
+  DH_HIP(hipStreamWaitEvent(comm, before, 0));
+  int rc = launch(comm);
+  if (rc) return rc;
+  DH_HIP(hipEventRecord(after, comm));
+  DH_HIP(hipStreamWaitEvent(strand, after, 0));
+  return DH_OK;
+}
+
+extern "C" int dh_si_step(dh_layer* L, const dh_fwd_args* alpha, const dh_bwd_args* beta, const dh_plan* plan, void* ws,
+                          size_t ws_bytes, void* stream_alpha, void* stream_beta, void* stream_comm) {
+  int rc = check_fwd_args(L, alpha);
+  if (rc) return rc;
+  if ((rc = check_bwd_args(L, beta))) return rc;
+  if (!plan) DH_FAIL(DH_ERR_INVALID_ARG, "si_step: plan is null");
+  if ((rc = dh_plan_validate(&L->gf, &L->gb, plan))) return rc;
+  if ((rc = check_ws(L, DH_WS_SI, ws, ws_bytes))) return rc;
+  if (L->T == 0) return DH_OK;
+  if ((rc = ensure_events(L))) return rc;
+  hipStream_t sa = (hipStream_t)stream_alpha, sb = (hipStream_t)stream_beta, sc = (hipStream_t)stream_comm;
+  char* ws_f = (char*)ws;
+  char* ws_b = (char*)ws + L->fwd_bytes;
+  const bool two = sb != sa;
+  if (two) {  // beta starts after whatever alpha's stream already holds
+    hipEvent_t e = next_event(L);
+    DH_HIP(hipEventRecord(e, sa));
+    DH_HIP(hipStreamWaitEvent(sb, e, 0));
+  }
+  for (int k = 0; k < plan->n_pairs; k++) {
+    const dh_seg_pair& p = plan->pairs[k];
+    int fi = p.f_begin, bj = p.b_begin;
+    // alternate the two strands' launches so both streams receive work early
+    while (fi < p.f_end || bj < p.b_end) {
+      if (fi < p.f_end) {
+        const int op = plan->fwd_order[fi++];
+        if (L->gf.is_comm[op]) rc = on_comm_stream(L, sa, sc, [&](hipStream_t s) { return run_fwd_op(L, op, *alpha, ws_f, s); });
+        else rc = run_fwd_op(L, op, *alpha, ws_f, sa);
+        if (rc) return rc;
+      }
+      if (bj < p.b_end) {
+        const int op = plan->bwd_order[bj++];
+        if (L->gb.is_comm[op]) rc = on_comm_stream(L, sb, sc, [&](hipStream_t s) { return run_bwd_op(L, op, *beta, ws_b, s); });
+        else rc = run_bwd_op(L, op, *beta, ws_b, sb);
+        if (rc) return rc;
+      }
+    }
+    if (two) {  // cross-strand barrier on the device
+      hipEvent_t ea = next_event(L), eb = next_event(L);
+      DH_HIP(hipEventRecord(ea, sa));
+      DH_HIP(hipEventRecord(eb, sb));
+      DH_HIP(hipStreamWaitEvent(sa, eb, 0));
+      DH_HIP(hipStreamWaitEvent(sb, ea, 0));
+    }
+  }
+  return DH_OK;
+}
+
+// ------------------------------------------------------------------------------------ profiler
+struct TimedOp {
+  int dir, op;
+};
+
+static int launch_op(dh_layer* L, const TimedOp& o, const dh_fwd_args& a, const dh_bwd_args& b, char* ws_f, char* ws_b,
+                     hipStream_t s) {
+  return o.dir == 0 ? run_fwd_op(L, o.op, a, ws_f, s) : run_bwd_op(L, o.op, b, ws_b, s);
+}
+
+extern "C" int dh_profile_pairs(dh_layer* L, const dh_fwd_args* alpha, const dh_bwd_args* beta, void* ws, size_t ws_bytes,
+                                void* stream_alpha, void* stream_beta, void* comm_stream, int reps, dh_overlap_table* out) {
+  int rc = check_fwd_args(L, alpha);
+  if (rc) return rc;
+  if ((rc = check_bwd_args(L, beta))) return rc;
+  if (!out || reps < 1) DH_FAIL(DH_ERR_INVALID_ARG, "profile_pairs: bad arguments");
+  if ((rc = check_ws(L, DH_WS_SI, ws, ws_bytes))) return rc;
+  if (stream_alpha == stream_beta) DH_FAIL(DH_ERR_INVALID_ARG, "profile_pairs: needs two distinct strand streams");
+  hipStream_t sa = (hipStream_t)stream_alpha, sb = (hipStream_t)stream_beta, sc = (hipStream_t)comm_stream;
+  char* ws_f = (char*)ws;
+  char* ws_b = (char*)ws + L->fwd_bytes;
+  memset(out, 0, sizeof(*out));
+  out->n_fwd = DH_F_NOPS;
+  out->n_bwd = DH_B_NOPS;
+  if (L->T == 0) return DH_OK;
+  hipEvent_t e0, e1, e2, e3, gate;
+  DH_HIP(hipEventCreate(&e0));
+  DH_HIP(hipEventCreate(&e1));
+  DH_HIP(hipEventCreate(&e2));
+  DH_HIP(hipEventCreate(&e3));
+  DH_HIP(hipEventCreateWithFlags(&gate, hipEventDisableTiming));
+  auto stream_of = [&](int dir, int op) {
+    bool comm = dir == 0 ? L->gf.is_comm[op] : L->gb.is_comm[op];
+    if (comm && sc) return sc;
+    return dir == 0 ? sa : sb;
+  };
+  auto cleanup = [&]() {
+    (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); (void)hipEventDestroy(e2); (void)hipEventDestroy(e3);
+    (void)hipEventDestroy(gate);
+  };
+  // solo times
+  for (int dir = 0; dir < 2; dir++) {
+    const int n = dir == 0 ? DH_F_NOPS : DH_B_NOPS;
+    for (int op = 0; op < n; op++) {
+      hipStream_t s = stream_of(dir, op);
+      TimedOp t{dir, op};
+      if ((rc = launch_op(L, t, *alpha, *beta, ws_f, ws_b, s))) { cleanup(); return rc; }  // warm-up
+      (void)hipEventRecord(e0, s);
+      for (int r = 0; r < reps; r++)
+        if ((rc = launch_op(L, t, *alpha, *beta, ws_f, ws_b, s))) { cleanup(); return rc; }
+      (void)hipEventRecord(e1, s);
+      hipError_t he = hipEventSynchronize(e1);
+      if (he != hipSuccess) { cleanup(); return dh_set_error(DH_ERR_HIP, "profile: %s", hipGetErrorString(he)); }
+      float ms = 0.f;
+      (void)hipEventElapsedTime(&ms, e0, e1);
+      (dir == 0 ? out->t_fwd : out->t_bwd)[op] = (double)ms * 1e-3 / reps;
+    }
+  }
+  // pairs: both operators repeated so that the two streams stay busy for about the same window
+  for (int i = 0; i < DH_F_NOPS; i++)
+    for (int j = 0; j < DH_B_NOPS; j++) {
+      const double ta = out->t_fwd[i], tb = out->t_bwd[j];
+      const double window = std::max(ta, tb) * reps;
+      const int ra = std::max(1, (int)std::lround(window / ta)), rb = std::max(1, (int)std::lround(window / tb));
+      hipStream_t s1 = stream_of(0, i), s2 = stream_of(1, j);
+      TimedOp A{0, i}, B{1, j};
+      double end_a, end_b;
+      if (s1 == s2) {  // both on the one communication stream: they serialise
+        end_a = ta * ra;
+        end_b = ta * ra + tb * rb;
+      } else {
+        (void)hipEventRecord(gate, s1);
+        (void)hipStreamWaitEvent(s2, gate, 0);
+        (void)hipEventRecord(e0, s1);
+        for (int r = 0; r < std::max(ra, rb); r++) {
+          if (r < ra && (rc = launch_op(L, A, *alpha, *beta, ws_f, ws_b, s1))) { cleanup(); return rc; }
+          if (r < rb && (rc = launch_op(L, B, *alpha, *beta, ws_f, ws_b, s2))) { cleanup(); return rc; }
+        }
+        (void)hipEventRecord(e1, s1);
+        (void)hipEventRecord(e3, s2);
+        hipError_t he = hipEventSynchronize(e1);
+        if (he == hipSuccess) he = hipEventSynchronize(e3);
+        if (he != hipSuccess) { cleanup(); return dh_set_error(DH_ERR_HIP, "profile: %s", hipGetErrorString(he)); }
+        float ma = 0.f, mb = 0.f;
+        (void)hipEventElapsedTime(&ma, e0, e1);
+        (void)hipEventElapsedTime(&mb, e0, e3);
+        end_a = (double)ma * 1e-3;
+        end_b = (double)mb * 1e-3;
+      }
+      // invert the fluid model on the aggregated operators (ra*ta, rb*tb)
+      const double wa = ta * ra, wb = tb * rb, t1 = std::min(end_a, end_b);
+      double qa, qb;
+      if (end_a <= end_b) { qa = wa / t1; qb = (wb - (end_b - t1)) / t1; }
+      else { qa = (wa - (end_a - t1)) / t1; qb = wb / t1; }
+      qa = std::min(1.0, std::max(0.02, qa));
+      qb = std::min(1.0, std::max(0.02, qb));
+      out->rate_fwd[i][j] = qa;
+      out->rate_bwd[i][j] = qb;
+      const int sf[1] = {i}, sbk[1] = {j};
+      out->p_pair[i][j] = dh_segment_cost(out, sf, 1, sbk, 1);
+      out->oef[i][j] = dh_oef(ta, tb, out->p_pair[i][j]);
+    }
+  cleanup();
+  return DH_OK;
+}

@@ -1,0 +1,364 @@
+"""ctypes binding of libdhelix (include/dhelix.h): argument marshalling only.
+
+Every function has the name of the C entry point it calls.  Tensors are passed as torch tensors
+(their data_ptr is handed over) or raw integers; streams as torch.cuda.Stream, raw hipStream_t
+integers or None.  Importing this module fails loudly if the library has not been built: there is
+no fallback path.
+"""
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libdhelix.so")
+if not os.path.exists(_LIB_PATH):
+    raise ImportError("libdhelix.so is not built: run `python -m paper_2411_15871_amd.build` (needs hipcc)")
+lib = C.CDLL(_LIB_PATH)
+
+DH_OK, DH_ERR_INVALID_ARG, DH_ERR_SHAPE, DH_ERR_WORKSPACE_TOO_SMALL = 0, -1, -2, -3
+DH_ERR_PLAN_INVALID, DH_ERR_HIP, DH_ERR_UNSUPPORTED = -4, -5, -6
+DH_F32, DH_BF16 = 0, 1
+DH_ARCH_LLAMA = 0
+DH_WS_FWD, DH_WS_BWD, DH_WS_SI = 0, 1, 2
+DH_COMM_ALLREDUCE = 0
+DH_MAX_OPS, DH_MAX_DEPS = 32, 96
+FWD_OPS = ["F_NORM1", "F_QKV", "F_ROPE", "F_ATTN", "F_PROJ", "F_AR1", "F_NORM2", "F_FC1", "F_ACT", "F_FC2", "F_AR2",
+           "F_BDA2"]
+BWD_OPS = ["B_FC2_DGRAD", "B_FC2_WGRAD", "B_ACT", "B_FC1_DGRAD", "B_FC1_WGRAD", "B_AR3", "B_NORM2", "B_PROJ_DGRAD",
+           "B_PROJ_WGRAD", "B_ATTN", "B_ROPE", "B_QKV_DGRAD", "B_QKV_WGRAD", "B_AR4", "B_NORM1"]
+
+
+class DhelixError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("libdhelix error %d: %s" % (code, msg))
+        self.code = code
+
+
+class dh_layer_config(C.Structure):
+    _fields_ = [("arch", C.c_int), ("dtype", C.c_int), ("batch", C.c_int), ("seq", C.c_int), ("hidden", C.c_int),
+                ("n_q_heads", C.c_int), ("n_kv_heads", C.c_int), ("head_dim", C.c_int), ("ffn", C.c_int),
+                ("eps", C.c_float), ("rope_base", C.c_float), ("n_ranks", C.c_int), ("comm_blocks", C.c_int)]
+
+
+class dh_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("g1", "Wqkv", "Wo", "g2", "Wgu", "Wd")]
+
+
+class dh_wgrads(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("dg1", "dWqkv", "dWo", "dg2", "dWgu", "dWd")]
+
+
+class dh_fwd_args(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("x", "out", "saved", "peers_ar1", "peers_ar2")]
+
+
+class dh_bwd_args(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("dout", "dx", "x", "saved", "peers_ar3", "peers_ar4")]
+
+
+class dh_op_graph(C.Structure):
+    _fields_ = [("n_ops", C.c_int), ("is_comm", C.c_int * DH_MAX_OPS), ("n_deps", C.c_int),
+                ("dep_src", C.c_int * DH_MAX_DEPS), ("dep_dst", C.c_int * DH_MAX_DEPS)]
+
+
+class dh_overlap_table(C.Structure):
+    _fields_ = [("n_fwd", C.c_int), ("n_bwd", C.c_int), ("t_fwd", C.c_double * DH_MAX_OPS),
+                ("t_bwd", C.c_double * DH_MAX_OPS), ("rate_fwd", (C.c_double * DH_MAX_OPS) * DH_MAX_OPS),
+                ("rate_bwd", (C.c_double * DH_MAX_OPS) * DH_MAX_OPS), ("p_pair", (C.c_double * DH_MAX_OPS) * DH_MAX_OPS),
+                ("oef", (C.c_double * DH_MAX_OPS) * DH_MAX_OPS)]
+
+
+class dh_seg_pair(C.Structure):
+    _fields_ = [("f_begin", C.c_int), ("f_end", C.c_int), ("b_begin", C.c_int), ("b_end", C.c_int)]
+
+
+class dh_plan(C.Structure):
+    _fields_ = [("n_fwd", C.c_int), ("n_bwd", C.c_int), ("n_pairs", C.c_int), ("fwd_order", C.c_int * DH_MAX_OPS),
+                ("bwd_order", C.c_int * DH_MAX_OPS), ("pairs", dh_seg_pair * (2 * DH_MAX_OPS))]
+
+
+# Every symbol include/dhelix.h declares, with its C signature.
+_P, _I, _Z, _D, _F = C.c_void_p, C.c_int, C.c_size_t, C.c_double, C.c_float
+SIGNATURES = {
+    "dh_last_error": (C.c_char_p, []),
+    "dh_layer_create": (_I, [C.POINTER(dh_layer_config), C.POINTER(_P)]),
+    "dh_layer_destroy": (None, [_P]),
+    "dh_layer_bind_weights": (_I, [_P, C.POINTER(dh_weights)]),
+    "dh_layer_bind_wgrads": (_I, [_P, C.POINTER(dh_wgrads)]),
+    "dh_layer_saved_bytes": (_Z, [_P]),
+    "dh_layer_workspace_bytes": (_Z, [_P, _I]),
+    "dh_layer_fwd": (_I, [_P, C.POINTER(dh_fwd_args), _P, _Z, _P]),
+    "dh_layer_bwd": (_I, [_P, C.POINTER(dh_bwd_args), _P, _Z, _P]),
+    "dh_layer_op_graph": (_I, [_P, _I, C.POINTER(dh_op_graph)]),
+    "dh_op_name": (C.c_char_p, [_I, _I]),
+    "dh_oef": (_D, [_D, _D, _D]),
+    "dh_segment_cost": (_D, [C.POINTER(dh_overlap_table), C.POINTER(_I), _I, C.POINTER(_I), _I]),
+    "dh_profile_pairs": (_I, [_P, C.POINTER(dh_fwd_args), C.POINTER(dh_bwd_args), _P, _Z, _P, _P, _P, _I,
+                              C.POINTER(dh_overlap_table)]),
+    "dh_pair_dp": (_I, [C.POINTER(_D), _I, C.POINTER(_D), _I, C.POINTER(_D), C.POINTER(_D), C.POINTER(_I), C.POINTER(_I)]),
+    "dh_plan_search": (_I, [C.POINTER(dh_op_graph), C.POINTER(dh_op_graph), C.POINTER(dh_overlap_table), _D, _I,
+                            C.POINTER(dh_plan), C.POINTER(_D)]),
+    "dh_plan_validate": (_I, [C.POINTER(dh_op_graph), C.POINTER(dh_op_graph), C.POINTER(dh_plan)]),
+    "dh_plan_sequential": (_I, [_P, C.POINTER(dh_plan)]),
+    "dh_si_step": (_I, [_P, C.POINTER(dh_fwd_args), C.POINTER(dh_bwd_args), C.POINTER(dh_plan), _P, _Z, _P, _P, _P]),
+    "dh_comm_standin": (_I, [_I, _I, C.POINTER(_P), _P, _Z, _I, _I, _P]),
+    "dh_stream_create_masked": (_I, [_I, C.POINTER(_P)]),
+    "dh_stream_destroy": (_I, [_P]),
+    "dh_gemm": (_I, [_I, _I, _I, _I, _I, _I, _P, _P, _P, _I, _P, _Z, _P]),
+    "dh_gemm_workspace_bytes": (_Z, [_I, _I, _I, _I, _I, _I]),
+    "dh_rmsnorm_fwd": (_I, [_I, _I, _I, _P, _P, _P, _F, _P, _P, _P, _P]),
+    "dh_rmsnorm_bwd": (_I, [_I, _I, _I, _P, _P, _P, _P, _P, _P, _P, _P, _Z, _P]),
+    "dh_rmsnorm_bwd_ws_bytes": (_Z, [_I, _I]),
+    "dh_rope": (_I, [_I, _I, _I, _I, _I, _I, _F, _I, _P, _P]),
+    "dh_swiglu_fwd": (_I, [_I, _I, _I, _P, _P, _P]),
+    "dh_swiglu_bwd": (_I, [_I, _I, _I, _P, _P, _P, _P]),
+    "dh_add": (_I, [_I, _Z, _P, _P, _P, _P]),
+    "dh_attn_fwd": (_I, [_I, _I, _I, _I, _I, _I, _P, _P, _P, _P]),
+    "dh_attn_bwd": (_I, [_I, _I, _I, _I, _I, _I, _P, _P, _P, _P, _P, _P, _P]),
+}
+for _name, (_res, _args) in SIGNATURES.items():
+    _fn = getattr(lib, _name)
+    _fn.restype = _res
+    _fn.argtypes = _args
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(s):
+    if s is None:
+        return None
+    if isinstance(s, int):
+        return s
+    return s.cuda_stream
+
+
+def _check(rc):
+    if rc != DH_OK:
+        raise DhelixError(rc, lib.dh_last_error().decode())
+
+
+def dh_last_error():
+    return lib.dh_last_error().decode()
+
+
+def dh_layer_create(**cfg):
+    c = dh_layer_config(**cfg)
+    h = _P()
+    _check(lib.dh_layer_create(C.byref(c), C.byref(h)))
+    return h
+
+
+def dh_layer_destroy(layer):
+    lib.dh_layer_destroy(layer)
+
+
+def dh_layer_bind_weights(layer, **w):
+    s = dh_weights(**{k: _ptr(v) for k, v in w.items()})
+    _check(lib.dh_layer_bind_weights(layer, C.byref(s)))
+
+
+def dh_layer_bind_wgrads(layer, **g):
+    s = dh_wgrads(**{k: _ptr(v) for k, v in g.items()})
+    _check(lib.dh_layer_bind_wgrads(layer, C.byref(s)))
+
+
+def dh_layer_saved_bytes(layer):
+    return lib.dh_layer_saved_bytes(layer)
+
+
+def dh_layer_workspace_bytes(layer, kind):
+    return lib.dh_layer_workspace_bytes(layer, kind)
+
+
+def fwd_args(x, out, saved, peers_ar1=None, peers_ar2=None):
+    return dh_fwd_args(_ptr(x), _ptr(out), _ptr(saved), _ptr(peers_ar1), _ptr(peers_ar2))
+
+
+def bwd_args(dout, dx, x, saved, peers_ar3=None, peers_ar4=None):
+    return dh_bwd_args(_ptr(dout), _ptr(dx), _ptr(x), _ptr(saved), _ptr(peers_ar3), _ptr(peers_ar4))
+
+
+def dh_layer_fwd(layer, args, ws, ws_bytes, stream=None):
+    _check(lib.dh_layer_fwd(layer, C.byref(args), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def dh_layer_bwd(layer, args, ws, ws_bytes, stream=None):
+    _check(lib.dh_layer_bwd(layer, C.byref(args), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def dh_layer_op_graph(layer, direction):
+    g = dh_op_graph()
+    _check(lib.dh_layer_op_graph(layer, direction, C.byref(g)))
+    return g
+
+
+def dh_op_name(direction, op):
+    r = lib.dh_op_name(direction, op)
+    return r.decode() if r else None
+
+
+def dh_oef(t_i, t_j, p_ij):
+    return lib.dh_oef(t_i, t_j, p_ij)
+
+
+def make_table(t_fwd, t_bwd, rate_fwd, rate_bwd):
+    t = dh_overlap_table()
+    t.n_fwd, t.n_bwd = len(t_fwd), len(t_bwd)
+    for i, v in enumerate(t_fwd):
+        t.t_fwd[i] = v
+    for j, v in enumerate(t_bwd):
+        t.t_bwd[j] = v
+    for i in range(len(t_fwd)):
+        for j in range(len(t_bwd)):
+            t.rate_fwd[i][j] = rate_fwd[i][j]
+            t.rate_bwd[i][j] = rate_bwd[i][j]
+    return t
+
+
+def make_graph(n_ops, deps, comm=()):
+    g = dh_op_graph()
+    g.n_ops = n_ops
+    g.n_deps = len(deps)
+    for e, (s, d) in enumerate(deps):
+        g.dep_src[e], g.dep_dst[e] = s, d
+    for c in comm:
+        g.is_comm[c] = 1
+    return g
+
+
+def make_plan(fwd_order, bwd_order, pairs):
+    p = dh_plan()
+    p.n_fwd, p.n_bwd, p.n_pairs = len(fwd_order), len(bwd_order), len(pairs)
+    for i, v in enumerate(fwd_order):
+        p.fwd_order[i] = v
+    for j, v in enumerate(bwd_order):
+        p.bwd_order[j] = v
+    for k, (a, b, c, d) in enumerate(pairs):
+        p.pairs[k] = dh_seg_pair(a, b, c, d)
+    return p
+
+
+def plan_to_py(p):
+    return (list(p.fwd_order[: p.n_fwd]), list(p.bwd_order[: p.n_bwd]),
+            [(q.f_begin, q.f_end, q.b_begin, q.b_end) for q in p.pairs[: p.n_pairs]])
+
+
+def dh_segment_cost(table, seg_f, seg_b):
+    a = (C.c_int * max(1, len(seg_f)))(*seg_f)
+    b = (C.c_int * max(1, len(seg_b)))(*seg_b)
+    r = lib.dh_segment_cost(C.byref(table), a, len(seg_f), b, len(seg_b))
+    if r < 0:
+        raise DhelixError(int(r), dh_last_error())
+    return r
+
+
+def dh_pair_dp(p_f, p_b, p_fb):
+    nf, nb = len(p_f), len(p_b)
+    a = (C.c_double * max(1, nf))(*p_f)
+    b = (C.c_double * max(1, nb))(*p_b)
+    flat = [p_fb[i][j] for i in range(nf) for j in range(nb)]
+    c = (C.c_double * max(1, nf * nb))(*flat)
+    t = C.c_double()
+    steps = (C.c_int * (2 * (nf + nb) + 2))()
+    n = C.c_int()
+    _check(lib.dh_pair_dp(a, nf, b, nb, c, C.byref(t), steps, C.byref(n)))
+    return t.value, [(steps[2 * k] if steps[2 * k] >= 0 else None, steps[2 * k + 1] if steps[2 * k + 1] >= 0 else None)
+                     for k in range(n.value)]
+
+
+def dh_plan_search(fwd_graph, bwd_graph, table, barrier_cost=0.0, max_orders=0):
+    p = dh_plan()
+    m = C.c_double()
+    _check(lib.dh_plan_search(C.byref(fwd_graph), C.byref(bwd_graph), C.byref(table), barrier_cost, max_orders,
+                              C.byref(p), C.byref(m)))
+    return p, m.value
+
+
+def dh_plan_validate(fwd_graph, bwd_graph, plan):
+    _check(lib.dh_plan_validate(C.byref(fwd_graph), C.byref(bwd_graph), C.byref(plan)))
+
+
+def dh_plan_sequential(layer):
+    p = dh_plan()
+    _check(lib.dh_plan_sequential(layer, C.byref(p)))
+    return p
+
+
+def dh_profile_pairs(layer, alpha, beta, ws, ws_bytes, stream_alpha, stream_beta, comm_stream, reps=5):
+    t = dh_overlap_table()
+    _check(lib.dh_profile_pairs(layer, C.byref(alpha), C.byref(beta), _ptr(ws), ws_bytes, _stream(stream_alpha),
+                                _stream(stream_beta), _stream(comm_stream), reps, C.byref(t)))
+    return t
+
+
+def dh_si_step(layer, alpha, beta, plan, ws, ws_bytes, stream_alpha, stream_beta, stream_comm=None):
+    _check(lib.dh_si_step(layer, C.byref(alpha), C.byref(beta), C.byref(plan), _ptr(ws), ws_bytes,
+                          _stream(stream_alpha), _stream(stream_beta), _stream(stream_comm)))
+
+
+def dh_comm_standin(kind, parts, out, elems, dtype, n_blocks=0, stream=None):
+    arr = (_P * len(parts))(*[_ptr(p) for p in parts])
+    _check(lib.dh_comm_standin(kind, len(parts), arr, _ptr(out), elems, dtype, n_blocks, _stream(stream)))
+
+
+def dh_stream_create_masked(n_cus):
+    s = _P()
+    _check(lib.dh_stream_create_masked(n_cus, C.byref(s)))
+    return s.value
+
+
+def dh_stream_destroy(stream):
+    _check(lib.dh_stream_destroy(stream))
+
+
+def dh_gemm(dtype, trans_a, trans_b, M, N, K, A, B, Cout, out_f32_accumulate=False, ws=None, ws_bytes=0, stream=None):
+    _check(lib.dh_gemm(dtype, int(trans_a), int(trans_b), M, N, K, _ptr(A), _ptr(B), _ptr(Cout), int(out_f32_accumulate),
+                       _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def dh_gemm_workspace_bytes(dtype, trans_a, trans_b, M, N, K):
+    return lib.dh_gemm_workspace_bytes(dtype, int(trans_a), int(trans_b), M, N, K)
+
+
+def dh_rmsnorm_fwd(dtype, T, H, x, residual, gamma, eps, x_out, h, rstd, stream=None):
+    _check(lib.dh_rmsnorm_fwd(dtype, T, H, _ptr(x), _ptr(residual), _ptr(gamma), eps, _ptr(x_out), _ptr(h), _ptr(rstd),
+                              _stream(stream)))
+
+
+def dh_rmsnorm_bwd_ws_bytes(T, H):
+    return lib.dh_rmsnorm_bwd_ws_bytes(T, H)
+
+
+def dh_rmsnorm_bwd(dtype, T, H, dy, x, gamma, rstd, dres, dx, dgamma, ws, ws_bytes, stream=None):
+    _check(lib.dh_rmsnorm_bwd(dtype, T, H, _ptr(dy), _ptr(x), _ptr(gamma), _ptr(rstd), _ptr(dres), _ptr(dx),
+                              _ptr(dgamma), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def dh_rope(dtype, T, seq, n_heads, head_dim, row_stride, base, inverse, t, stream=None):
+    _check(lib.dh_rope(dtype, T, seq, n_heads, head_dim, row_stride, base, int(inverse), _ptr(t), _stream(stream)))
+
+
+def dh_swiglu_fwd(dtype, T, F, gu, a, stream=None):
+    _check(lib.dh_swiglu_fwd(dtype, T, F, _ptr(gu), _ptr(a), _stream(stream)))
+
+
+def dh_swiglu_bwd(dtype, T, F, gu, da, dgu, stream=None):
+    _check(lib.dh_swiglu_bwd(dtype, T, F, _ptr(gu), _ptr(da), _ptr(dgu), _stream(stream)))
+
+
+def dh_add(dtype, n, a, b, out, stream=None):
+    _check(lib.dh_add(dtype, n, _ptr(a), _ptr(b), _ptr(out), _stream(stream)))
+
+
+def dh_attn_fwd(dtype, batch, seq, nq, nkv, d, qkv, o, lse, stream=None):
+    _check(lib.dh_attn_fwd(dtype, batch, seq, nq, nkv, d, _ptr(qkv), _ptr(o), _ptr(lse), _stream(stream)))
+
+
+def dh_attn_bwd(dtype, batch, seq, nq, nkv, d, qkv, o, dout, lse, dqkv, delta, stream=None):
+    _check(lib.dh_attn_bwd(dtype, batch, seq, nq, nkv, d, _ptr(qkv), _ptr(o), _ptr(dout), _ptr(lse), _ptr(dqkv),
+                           _ptr(delta), _stream(stream)))

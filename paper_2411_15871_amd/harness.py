@@ -1,0 +1,108 @@
+"""Device-memory plumbing around libdhelix for tests, the smoke check and the benchmark.
+
+PyTorch is used for allocation, host<->device copies and streams only; every step of the layer
+runs in the library's HIP kernels through the ctypes binding.
+"""
+import numpy as np
+import torch
+
+from . import dhelix as dh
+from . import inputs as gen
+
+CONFIGS = {
+    # name: batch, seq, hidden, nq, nkv, d, ffn, n_ranks, bf16
+    "c1_tiny_fp32": dict(batch=1, seq=128, hidden=256, nq=4, nkv=4, d=64, ffn=688, n_ranks=2, bf16=False),
+    "c2_llama8b_tp8": dict(batch=1, seq=4096, hidden=4096, nq=4, nkv=1, d=128, ffn=1792, n_ranks=8, bf16=True),
+    "c4_llama70b_tp8": dict(batch=1, seq=8192, hidden=8192, nq=8, nkv=1, d=128, ffn=3584, n_ranks=8, bf16=True),
+}
+
+
+def model_flops(cfg):
+    """Model FLOPs of one forward+backward of the layer shard: 2*M*N*K per GEMM, causal attention at
+    half of the dense 4*s^2*d per head, backward = 2 x forward (no recompute credit)."""
+    T, H, nq, nkv, d, F = cfg["batch"] * cfg["seq"], cfg["hidden"], cfg["nq"], cfg["nkv"], cfg["d"], cfg["ffn"]
+    gemm = 2.0 * T * H * ((nq + 2 * nkv) * d + nq * d + 2 * F + F)
+    attn = 0.5 * 4.0 * cfg["batch"] * cfg["seq"] ** 2 * d * nq
+    return 3.0 * (gemm + attn)
+
+
+def to_dev(a, bf16):
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    return t.to(torch.bfloat16) if bf16 else t
+
+
+def to_np(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+class Strand:
+    """One micro-batch strand's buffers: input, output, saved-activation slot, frozen peer partials."""
+
+    def __init__(self, run, seed):
+        c = run.cfg
+        T, H, bf = run.T, c["hidden"], c["bf16"]
+        self.x_np = gen.strand_input(seed, T, H, bf)
+        self.dout_np = gen.strand_upstream_grad(seed, T, H, bf)
+        n_peers = c["n_ranks"] - 1
+        self.peers_np = {k: gen.peer_partials(base + 10 * i + 1000 * seed, n_peers, T, H, bf)
+                         for i, (k, base) in enumerate([("ar1", gen.SEED_PEER_FWD), ("ar2", gen.SEED_PEER_FWD),
+                                                        ("ar3", gen.SEED_PEER_BWD), ("ar4", gen.SEED_PEER_BWD)])}
+        self.x = to_dev(self.x_np, bf)
+        self.dout = to_dev(self.dout_np, bf)
+        self.peers = {k: to_dev(v, bf) for k, v in self.peers_np.items()}
+        self.out = torch.empty_like(self.x)
+        self.dx = torch.empty_like(self.x)
+        self.saved = torch.empty(dh.dh_layer_saved_bytes(run.layer), dtype=torch.uint8, device="cuda")
+        self.fwd_args = dh.fwd_args(self.x, self.out, self.saved, self.peers["ar1"] if n_peers else None,
+                                    self.peers["ar2"] if n_peers else None)
+        self.bwd_args = dh.bwd_args(self.dout, self.dx, self.x, self.saved, self.peers["ar3"] if n_peers else None,
+                                    self.peers["ar4"] if n_peers else None)
+
+
+class LayerRun:
+    def __init__(self, cfg):
+        self.cfg = dict(cfg)
+        c = self.cfg
+        c.setdefault("eps", 1e-5)
+        c.setdefault("rope_base", 10000.0)
+        self.T = c["batch"] * c["seq"]
+        bf = c["bf16"]
+        self.layer = dh.dh_layer_create(arch=dh.DH_ARCH_LLAMA, dtype=dh.DH_BF16 if bf else dh.DH_F32, batch=c["batch"],
+                                        seq=c["seq"], hidden=c["hidden"], n_q_heads=c["nq"], n_kv_heads=c["nkv"],
+                                        head_dim=c["d"], ffn=c["ffn"], eps=c["eps"], rope_base=c["rope_base"],
+                                        n_ranks=c["n_ranks"], comm_blocks=c.get("comm_blocks", 0))
+        n_qkv = (c["nq"] + 2 * c["nkv"]) * c["d"]
+        self.w_np = gen.llama_weights(c["hidden"], n_qkv, c["nq"] * c["d"], c["ffn"], bf)
+        self.w = {k: to_dev(v, bf) for k, v in self.w_np.items()}
+        self.g = {"d" + k: torch.zeros(v.shape, dtype=torch.float32, device="cuda") for k, v in self.w_np.items()}
+        dh.dh_layer_bind_weights(self.layer, **self.w)
+        dh.dh_layer_bind_wgrads(self.layer, **self.g)
+        self.ws_bytes = dh.dh_layer_workspace_bytes(self.layer, dh.DH_WS_SI)
+        self.ws = torch.empty(max(self.ws_bytes, 256), dtype=torch.uint8, device="cuda")
+        self.fwd_ws_bytes = dh.dh_layer_workspace_bytes(self.layer, dh.DH_WS_FWD)
+
+    def close(self):
+        if self.layer is not None:
+            dh.dh_layer_destroy(self.layer)
+            self.layer = None
+
+    def zero_grads(self):
+        for t in self.g.values():
+            t.zero_()
+
+    def grads_np(self):
+        return {k: to_np(v) for k, v in self.g.items()}
+
+    def strand(self, seed):
+        return Strand(self, seed)
+
+    def fwd(self, s, stream=None):
+        dh.dh_layer_fwd(self.layer, s.fwd_args, self.ws, self.ws_bytes, stream)
+
+    def bwd(self, s, stream=None):
+        # the backward region of the SI workspace, so forward and backward never share transients
+        dh.dh_layer_bwd(self.layer, s.bwd_args, self.ws.data_ptr() + self.fwd_ws_bytes,
+                        self.ws_bytes - self.fwd_ws_bytes, stream)
+
+    def si_step(self, alpha, beta, plan, s_alpha, s_beta, s_comm=None):
+        dh.dh_si_step(self.layer, alpha.fwd_args, beta.bwd_args, plan, self.ws, self.ws_bytes, s_alpha, s_beta, s_comm)
