@@ -293,11 +293,15 @@ int dh_add(int dtype, size_t n, const void* a, const void* b, void* out, void* s
 /* Causal grouped-query attention (FlashAttention operator base, Table 2).  qkv[T,(nq+2nkv)d] =
  * [q heads | k heads | v heads] (already rotated); o[T,nq*d]; lse[nq,T] natural-log sum-exp of the
  * scaled masked scores; attention is per sequence (T = batch*seq).  Backward writes dqkv (same
- * layout as qkv; dk,dv summed over the query heads of each group) and uses delta[nq,T] as scratch. */
+ * layout as qkv; dk,dv summed over the query heads of each group in head order) and uses
+ * delta[nq,T] and ws (dh_attn_bwd_workspace_bytes; per-head float32 dk,dv partials when nq > nkv)
+ * as scratch. */
 int dh_attn_fwd(int dtype, int batch, int seq, int nq, int nkv, int d, const void* qkv, void* o,
                 float* lse, void* stream);
 int dh_attn_bwd(int dtype, int batch, int seq, int nq, int nkv, int d, const void* qkv, const void* o,
-                const void* dout, const float* lse, void* dqkv, float* delta, void* stream);
+                const void* dout, const float* lse, void* dqkv, float* delta, void* ws, size_t ws_bytes,
+                void* stream);
+size_t dh_attn_bwd_workspace_bytes(int dtype, int batch, int seq, int nq, int nkv, int d);
 
 #ifdef __cplusplus
 }

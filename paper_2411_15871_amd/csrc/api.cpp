@@ -49,8 +49,14 @@ extern "C" int dh_attn_fwd(int dtype, int batch, int seq, int nq, int nkv, int d
   DH_FAIL(DH_ERR_INVALID_ARG, "attn_fwd: unknown dtype %d", dtype);
 }
 
+extern "C" size_t dh_attn_bwd_workspace_bytes(int dtype, int batch, int seq, int nq, int nkv, int d) {
+  if (dtype != DH_BF16 || batch <= 0 || seq <= 0 || nq <= 0 || nkv <= 0 || d <= 0) return 0;
+  return dh_attn_bwd_bf16_ws_bytes(batch, seq, nq, nkv, d);
+}
+
 extern "C" int dh_attn_bwd(int dtype, int batch, int seq, int nq, int nkv, int d, const void* qkv, const void* o,
-                           const void* dout, const float* lse, void* dqkv, float* delta, void* stream) {
+                           const void* dout, const float* lse, void* dqkv, float* delta, void* ws, size_t ws_bytes,
+                           void* stream) {
   int rc = check_attn("attn_bwd", batch, seq, nq, nkv, d);
   if (rc) return rc;
   if (batch * seq > 0 && (!qkv || !o || !dout || !lse || !dqkv || !delta)) DH_FAIL(DH_ERR_INVALID_ARG, "attn_bwd: null pointer");
@@ -59,6 +65,6 @@ extern "C" int dh_attn_bwd(int dtype, int batch, int seq, int nq, int nkv, int d
                                   (float*)dqkv, delta, (hipStream_t)stream);
   if (dtype == DH_BF16)
     return dh_launch_attn_bwd_bf16(batch, seq, nq, nkv, d, (const bf16_t*)qkv, (const bf16_t*)o, (const bf16_t*)dout, lse,
-                                   (bf16_t*)dqkv, delta, (hipStream_t)stream);
+                                   (bf16_t*)dqkv, delta, ws, ws_bytes, (hipStream_t)stream);
   DH_FAIL(DH_ERR_INVALID_ARG, "attn_bwd: unknown dtype %d", dtype);
 }

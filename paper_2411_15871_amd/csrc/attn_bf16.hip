@@ -20,11 +20,19 @@
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 
+// A 64-token tile is stored [token][D] without padding; the 16-byte chunk c of row r sits at chunk
+// position c ^ swz(r).  With 256-byte rows (D = 128) this makes both access patterns conflict-free:
+// the 16-byte reads of 16 consecutive rows at one chunk index (swz is a bijection on r%16) and the
+// transposing reads of 4 consecutive rows x 64 bytes (r%4 lands in the upper two chunk bits).
 template <int D>
 struct ATile {
-  static constexpr int LD = D + 8;          // padded row, elements
+  static constexpr int LD = D;
   static constexpr int ELEMS = AB_KT * LD;  // one 64-token tile
   static constexpr int CHUNKS = AB_KT * D / 8 / AB_THREADS;
+  static constexpr int CPR = D / 8;         // chunks per row
+  __device__ static __forceinline__ int swz(int r) { return (((r & 3) << 2) | ((r >> 2) & 3)) & (CPR - 1); }
+  // element offset of (row r, column c) for c a multiple of 4 (stays inside one chunk)
+  __device__ static __forceinline__ int off(int r, int c) { return r * LD + ((((c >> 3) ^ swz(r)) << 3) | (c & 7)); }
 };
 
 // fetch a [64 tokens][D] tile (row stride ld elements) into registers; rows >= limit read as zero.
@@ -45,19 +53,19 @@ __device__ __forceinline__ void astash(const bf16x8 (&reg)[ATile<D>::CHUNKS], bf
 #pragma unroll
   for (int i = 0; i < ATile<D>::CHUNKS; i++) {
     int id = threadIdx.x + i * AB_THREADS;
-    *reinterpret_cast<bf16x8*>(lds + (id / (D / 8)) * ATile<D>::LD + (id % (D / 8)) * 8) = reg[i];
+    *reinterpret_cast<bf16x8*>(lds + ATile<D>::off(id / (D / 8), (id % (D / 8)) * 8)) = reg[i];
   }
 }
 // A/B fragment whose 8 k-values are contiguous in the tile row: row `r`, columns c0..c0+7.
 template <int D>
 __device__ __forceinline__ bf16x8 frag_direct(const bf16_t* tile, int r, int c0) {
-  return *reinterpret_cast<const bf16x8*>(tile + r * ATile<D>::LD + c0);
+  return *reinterpret_cast<const bf16x8*>(tile + ATile<D>::off(r, c0));
 }
 // Fragment whose k runs down the tile's rows: column c16+s (s = lane%16), rows ka..ka+3 and kb..kb+3.
 template <int D>
 __device__ __forceinline__ bf16x8 frag_tr(const bf16_t* tile, int ka, int kb, int c16, int s) {
-  const bf16_t* p0 = tile + (ka + (s >> 2)) * ATile<D>::LD + c16 + ((s & 3) << 2);
-  const bf16_t* p1 = tile + (kb + (s >> 2)) * ATile<D>::LD + c16 + ((s & 3) << 2);
+  const bf16_t* p0 = tile + ATile<D>::off(ka + (s >> 2), c16 + ((s & 3) << 2));
+  const bf16_t* p1 = tile + ATile<D>::off(kb + (s >> 2), c16 + ((s & 3) << 2));
   s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(__attribute__((address_space(3))) void*)p0);
   s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(__attribute__((address_space(3))) void*)p1);
   return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7));
@@ -75,7 +83,7 @@ __device__ __forceinline__ bf16x8 pack_rows(const f32x16& t, int c) {
 // ================================================================================ forward
 // grid (ceil(seq/128), nq, batch); wave w owns query rows i0 + 32w .. +31.
 template <int D>
-__global__ __launch_bounds__(AB_THREADS) void attn_fwd_bf16_kernel(int seq, int nq, int nkv, const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(int seq, int nq, int nkv, const bf16_t* __restrict__ qkv,
                                                                    bf16_t* __restrict__ o, float* __restrict__ lse, int T,
                                                                    float scale_log2) {
   using TL = ATile<D>;
@@ -291,23 +299,25 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(int seq, i
 }
 
 // ================================================================================ backward: dK, dV
-// grid (ceil(seq/128), nkv, batch); wave w owns keys j0 + 32w .. +31 and keeps their K, V fragments
-// and the dK^T, dV^T accumulators in registers while 64-query tiles of Q and dO stream through LDS
-// for every query head of the group.
+// grid (ceil(seq/128), nq, batch): one block per (key block, query head); wave w owns keys
+// j0 + 32w .. +31 and keeps their K, V fragments and the dK^T, dV^T accumulators in registers while
+// 64-query tiles of that head's Q and dO stream through LDS.  With grouped heads (nq > nkv) the
+// block writes float32 partials part[query head][token][dK | dV] and attn_bwd_group_reduce_kernel
+// adds the group's heads in index order; with nq == nkv it writes dK, dV directly.
 template <int D>
 __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, int nq, int nkv, const bf16_t* __restrict__ qkv,
                                                                        const bf16_t* __restrict__ dout,
                                                                        const float* __restrict__ lse,
                                                                        const float* __restrict__ delta,
-                                                                       bf16_t* __restrict__ dqkv, int T, float scale,
-                                                                       float scale_log2) {
+                                                                       bf16_t* __restrict__ dqkv, float* __restrict__ part,
+                                                                       int T, float scale, float scale_log2) {
   using TL = ATile<D>;
   __shared__ __attribute__((aligned(16))) bf16_t Qs[TL::ELEMS];
   __shared__ __attribute__((aligned(16))) bf16_t Os[TL::ELEMS];
   __shared__ float lse_s[AB_KT], del_s[AB_KT];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int l32 = lane & 31, kg = lane >> 5, s16 = lane & 15, h16 = (lane >> 4) & 1;
-  const int hk = blockIdx.y, b = blockIdx.z, grp = nq / nkv;
+  const int hq = blockIdx.y, b = blockIdx.z, grp = nq / nkv, hk = hq / grp;
   const int ld = (nq + 2 * nkv) * D;
   const int j0 = blockIdx.x * 128, jw = j0 + wave * 32, jk = jw + l32;  // key positions within the sequence
   const size_t tok0 = (size_t)b * seq;
@@ -326,12 +336,11 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, 
     for (int r = 0; r < 16; r++) { dkt[dt][r] = 0.f; dvt[dt][r] = 0.f; }
 
   const int qstart = j0 / AB_KT * AB_KT;
-  const int ntile = (seq - qstart + AB_KT - 1) / AB_KT;  // query tiles per head
-  const int total = grp * ntile;
+  const int total = (seq - qstart + AB_KT - 1) / AB_KT;  // query tiles
   bf16x8 rq[TL::CHUNKS], ro[TL::CHUNKS];
   float rl = 0.f, rd = 0.f;
   auto fetch = [&](int it) {
-    int hq = hk * grp + it / ntile, qb = qstart + (it % ntile) * AB_KT;
+    int qb = qstart + it * AB_KT;
     afetch<D>(rq, qkv + tok0 * ld + (size_t)hq * D, ld, qb, seq);
     afetch<D>(ro, dout + tok0 * (size_t)nq * D + (size_t)hq * D, nq * D, qb, seq);
     if (threadIdx.x < AB_KT) {
@@ -348,7 +357,7 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, 
   if (total > 0) { fetch(0); stash(); }
   __syncthreads();
   for (int it = 0; it < total; it++) {
-    const int qb = qstart + (it % ntile) * AB_KT;
+    const int qb = qstart + it * AB_KT;
     const bool more = it + 1 < total;
     if (more) fetch(it + 1);
     if (qb + AB_KT - 1 >= jw) {  // some query of the tile sees some key of this wave
@@ -391,7 +400,19 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, 
     if (more) stash();
     __syncthreads();
   }
-  if (jk < seq) {
+  if (jk < seq && part != nullptr) {
+    float* prow = part + ((size_t)hq * T + tok0 + jk) * (2 * D);  // hq = hk*grp + head-in-group
+#pragma unroll
+    for (int dt = 0; dt < D / 32; dt++)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; q4++) {
+        f32x4 a, c;
+#pragma unroll
+        for (int i = 0; i < 4; i++) { a[i] = dkt[dt][4 * q4 + i] * scale; c[i] = dvt[dt][4 * q4 + i]; }
+        *reinterpret_cast<f32x4*>(prow + dt * 32 + 8 * q4 + 4 * kg) = a;
+        *reinterpret_cast<f32x4*>(prow + D + dt * 32 + 8 * q4 + 4 * kg) = c;
+      }
+  } else if (jk < seq) {
     bf16_t* krow = dqkv + (tok0 + jk) * ld + (size_t)(nq + hk) * D;
     bf16_t* vrow = dqkv + (tok0 + jk) * ld + (size_t)(nq + nkv + hk) * D;
 #pragma unroll
@@ -410,6 +431,25 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, 
   }
 }
 
+// dk,dv[token][kv head] = sum over the group's query heads (ascending) of the float32 partials
+// part[query head][token][dK | dV].
+template <int D>
+__global__ void attn_bwd_group_reduce_kernel(const float* __restrict__ part, bf16_t* __restrict__ dqkv, int T, int nq,
+                                             int nkv) {
+  const int grp = nq / nkv, ld = (nq + 2 * nkv) * D;
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // over T * nkv * (2D/4)
+  const int per_tok = 2 * D / 4;
+  if (idx >= (size_t)T * nkv * per_tok) return;
+  int c4 = (int)(idx % per_tok) * 4;
+  int hk = (int)((idx / per_tok) % nkv);
+  size_t tok = idx / ((size_t)per_tok * nkv);
+  f32x4 s = {0.f, 0.f, 0.f, 0.f};
+  for (int g = 0; g < grp; g++) s += *reinterpret_cast<const f32x4*>(part + (((size_t)hk * grp + g) * T + tok) * (2 * D) + c4);
+  bf16x4 o = {(bf16_t)s[0], (bf16_t)s[1], (bf16_t)s[2], (bf16_t)s[3]};
+  bf16_t* dst = dqkv + tok * ld + (c4 < D ? (size_t)(nq + hk) * D + c4 : (size_t)(nq + nkv + hk) * D + (c4 - D));
+  *reinterpret_cast<bf16x4*>(dst) = o;
+}
+
 // ------------------------------------------------------------------------------------ host side
 int dh_launch_attn_delta_bf16(int T, int nq, int d, const bf16_t* o, const bf16_t* dout, float* delta, hipStream_t stream);
 
@@ -425,23 +465,34 @@ int dh_launch_attn_fwd_bf16(int batch, int seq, int nq, int nkv, int d, const bf
   return DH_OK;
 }
 
+size_t dh_attn_bwd_bf16_ws_bytes(int batch, int seq, int nq, int nkv, int d) {
+  return nq > nkv ? (size_t)nq * batch * seq * 2 * d * sizeof(float) : 0;
+}
+
 int dh_launch_attn_bwd_bf16(int batch, int seq, int nq, int nkv, int d, const bf16_t* qkv, const bf16_t* o,
-                            const bf16_t* dout, const float* lse, bf16_t* dqkv, float* delta, hipStream_t stream) {
+                            const bf16_t* dout, const float* lse, bf16_t* dqkv, float* delta, void* ws, size_t ws_bytes,
+                            hipStream_t stream) {
   if (d != 64 && d != 128) DH_FAIL(DH_ERR_SHAPE, "attention (bf16): head_dim %d must be 64 or 128", d);
   int T = batch * seq;
   if (T == 0) return DH_OK;
+  size_t need = dh_attn_bwd_bf16_ws_bytes(batch, seq, nq, nkv, d);
+  if (need > 0 && (!ws || ws_bytes < need)) DH_FAIL(DH_ERR_WORKSPACE_TOO_SMALL, "attn_bwd: workspace %zu < %zu bytes", ws_bytes, need);
+  float* part = need > 0 ? (float*)ws : nullptr;
   int rc = dh_launch_attn_delta_bf16(T, nq, d, o, dout, delta, stream);
   if (rc != DH_OK) return rc;
   float sc = (float)(1.0 / sqrt((double)d)), sl2 = (float)(1.4426950408889634 / sqrt((double)d));
-  dim3 gq((seq + 127) / 128, nq, batch), gk((seq + 127) / 128, nkv, batch);
+  dim3 gq((seq + 127) / 128, nq, batch), gk((seq + 127) / 128, nq, batch);
+  const unsigned nred = (unsigned)(((size_t)T * nkv * (2 * d / 4) + 255) / 256);
   if (d == 128) {
     attn_bwd_dq_bf16_kernel<128><<<gq, AB_THREADS, 0, stream>>>(seq, nq, nkv, qkv, dout, lse, delta, dqkv, T, sc, sl2);
     DH_LAUNCH_CHECK();
-    attn_bwd_dkv_bf16_kernel<128><<<gk, AB_THREADS, 0, stream>>>(seq, nq, nkv, qkv, dout, lse, delta, dqkv, T, sc, sl2);
+    attn_bwd_dkv_bf16_kernel<128><<<gk, AB_THREADS, 0, stream>>>(seq, nq, nkv, qkv, dout, lse, delta, dqkv, part, T, sc, sl2);
+    if (part) { DH_LAUNCH_CHECK(); attn_bwd_group_reduce_kernel<128><<<nred, 256, 0, stream>>>(part, dqkv, T, nq, nkv); }
   } else {
     attn_bwd_dq_bf16_kernel<64><<<gq, AB_THREADS, 0, stream>>>(seq, nq, nkv, qkv, dout, lse, delta, dqkv, T, sc, sl2);
     DH_LAUNCH_CHECK();
-    attn_bwd_dkv_bf16_kernel<64><<<gk, AB_THREADS, 0, stream>>>(seq, nq, nkv, qkv, dout, lse, delta, dqkv, T, sc, sl2);
+    attn_bwd_dkv_bf16_kernel<64><<<gk, AB_THREADS, 0, stream>>>(seq, nq, nkv, qkv, dout, lse, delta, dqkv, part, T, sc, sl2);
+    if (part) { DH_LAUNCH_CHECK(); attn_bwd_group_reduce_kernel<64><<<nred, 256, 0, stream>>>(part, dqkv, T, nq, nkv); }
   }
   DH_LAUNCH_CHECK();
   return DH_OK;

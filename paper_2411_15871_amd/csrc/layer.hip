@@ -24,7 +24,7 @@ struct dh_layer {
   // forward workspace offsets
   size_t f_part, f_red, f_gemm, f_gemm_bytes, fwd_bytes;
   // backward workspace offsets
-  size_t b_da, b_dgu, b_part, b_red, b_dx2, b_do, b_dqkv, b_delta, b_norm, b_norm_bytes, b_gemm, b_gemm_bytes, bwd_bytes;
+  size_t b_da, b_dgu, b_part, b_red, b_dx2, b_do, b_dqkv, b_delta, b_attn, b_attn_bytes, b_norm, b_norm_bytes, b_gemm, b_gemm_bytes, bwd_bytes;
   hipEvent_t ev[DH_EVENT_POOL];  // created on the first SI step (needs a device)
   bool have_events;
   int ev_next;
@@ -134,6 +134,8 @@ extern "C" int dh_layer_create(const dh_layer_config* cfg, dh_layer** out) {
   L->b_do = take(cur, T * L->n_o * es);
   L->b_dqkv = take(cur, T * L->n_qkv * es);
   L->b_delta = take(cur, (size_t)c.n_q_heads * T * 4);
+  L->b_attn_bytes = bf ? dh_attn_bwd_bf16_ws_bytes(c.batch, c.seq, c.n_q_heads, c.n_kv_heads, c.head_dim) : 0;
+  L->b_attn = take(cur, L->b_attn_bytes);
   L->b_norm_bytes = dh_rmsnorm_bwd_ws_bytes(L->T, c.hidden);
   L->b_norm = take(cur, L->b_norm_bytes);
   size_t gb = 0;
@@ -268,7 +270,8 @@ static int run_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipSt
       return gemm(L, true, false, L->n_o, H, T, sv + L->s_o, ws + L->b_dx2, L->g.dWo, true, gws, gwb, s);
     case DH_B_ATTN:
       return dh_attn_bwd(dt, c.batch, c.seq, c.n_q_heads, c.n_kv_heads, c.head_dim, sv + L->s_qkv, sv + L->s_o, ws + L->b_do,
-                         (const float*)(sv + L->s_lse), ws + L->b_dqkv, (float*)(ws + L->b_delta), s);
+                         (const float*)(sv + L->s_lse), ws + L->b_dqkv, (float*)(ws + L->b_delta), ws + L->b_attn,
+                         L->b_attn_bytes, s);
     case DH_B_ROPE:
       return dh_rope(dt, T, c.seq, c.n_q_heads + c.n_kv_heads, c.head_dim, L->n_qkv, c.rope_base, 1, ws + L->b_dqkv, s);
     case DH_B_QKV_DGRAD:

@@ -53,10 +53,12 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_fwd_kernel(const T* __res
 
 // ------------------------------------------------------------------------------------ RMSNorm bwd
 // Block b handles rows [b*RPB, (b+1)*RPB).  dx = rstd*(gh - xh*mean(gh*xh)) (+ dres), gh = gamma*dy,
-// xh = x*rstd.  The gain gradient sum_t dy*xh is accumulated per thread over the block's rows and
-// written as one partial row per block; a second kernel adds the partials in block order so the
-// result does not depend on scheduling.
+// xh = x*rstd.  The next row is already in flight while the current one is reduced.  The gain
+// gradient sum_t dy*xh is accumulated per thread over the block's rows and written as one partial
+// row per block; two small kernels then add the partial rows in a fixed order (first groups of
+// COLSUM_GROUP consecutive rows, then the groups), so the result does not depend on scheduling.
 #define NORM_BWD_RPB 8
+#define COLSUM_GROUP 32
 template <typename T, int NCH>
 __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                                                                   const T* __restrict__ gamma,
@@ -73,18 +75,33 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_bwd_kernel(const T* __res
 #pragma unroll
     for (int i = 0; i < 8; i++) dg[c][i] = 0.f;
   }
-  for (int rr = 0; rr < NORM_BWD_RPB; rr++) {
-    size_t row = (size_t)blockIdx.x * NORM_BWD_RPB + rr;
-    if (row >= (size_t)rows) break;  // uniform across the block
-    float r = rstd[row];
-    Vec8<T> gh[NCH], xh[NCH];
+  const size_t row0 = (size_t)blockIdx.x * NORM_BWD_RPB;
+  const int nrows = min(NORM_BWD_RPB, rows - (int)row0);
+  Vec8<T> ndy[NCH], nx[NCH], nres[NCH];
+  auto fetch = [&](size_t row) {
+#pragma unroll
+    for (int c = 0; c < NCH; c++) {
+      int col = (threadIdx.x + ROW_THREADS * c) * 8;
+      if (col < H) {
+        ndy[c].load(dy + row * H + col);
+        nx[c].load(x + row * H + col);
+        if (dres != nullptr) nres[c].load(dres + row * H + col);
+      }
+    }
+  };
+  fetch(row0);
+  for (int rr = 0; rr < nrows; rr++) {
+    const size_t row = row0 + rr;
+    const float r = rstd[row];
+    Vec8<T> gh[NCH], xh[NCH], rs[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; c++) { gh[c] = ndy[c]; xh[c] = nx[c]; rs[c] = nres[c]; }
+    if (rr + 1 < nrows) fetch(row + 1);
     float dot = 0.f;
 #pragma unroll
     for (int c = 0; c < NCH; c++) {
       int col = (threadIdx.x + ROW_THREADS * c) * 8;
       if (col < H) {
-        gh[c].load(dy + row * H + col);
-        xh[c].load(x + row * H + col);
 #pragma unroll
         for (int i = 0; i < 8; i++) {
           xh[c].v[i] *= r;
@@ -103,10 +120,8 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_bwd_kernel(const T* __res
 #pragma unroll
         for (int i = 0; i < 8; i++) o.v[i] = r * (gh[c].v[i] - xh[c].v[i] * dot);
         if (dres != nullptr) {
-          Vec8<T> d;
-          d.load(dres + row * H + col);
 #pragma unroll
-          for (int i = 0; i < 8; i++) o.v[i] += d.v[i];
+          for (int i = 0; i < 8; i++) o.v[i] += rs[c].v[i];
         }
         o.store(dx + row * H + col);
       }
@@ -123,7 +138,21 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_bwd_kernel(const T* __res
   }
 }
 
-// dgamma[col] += sum_b partial[b][col], b ascending.
+// out[grp][col] = sum of partial rows grp*COLSUM_GROUP .. +COLSUM_GROUP-1 (ascending), one thread per column.
+__global__ void colsum_group_kernel(const float* __restrict__ partial, float* __restrict__ out, int nrows, int H) {
+  int col = blockIdx.x * blockDim.x + threadIdx.x;
+  if (col >= H) return;
+  int r0 = blockIdx.y * COLSUM_GROUP, r1 = min(nrows, r0 + COLSUM_GROUP);
+  float v[COLSUM_GROUP];
+#pragma unroll
+  for (int i = 0; i < COLSUM_GROUP; i++) v[i] = r0 + i < r1 ? partial[(size_t)(r0 + i) * H + col] : 0.f;
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < COLSUM_GROUP; i++) s += v[i];
+  out[(size_t)blockIdx.y * H + col] = s;
+}
+
+// dst[col] += sum_b partial[b][col], b ascending.
 __global__ void colsum_accumulate_kernel(const float* __restrict__ partial, float* __restrict__ dst, int nblk, int H) {
   int col = blockIdx.x * blockDim.x + threadIdx.x;
   if (col >= H) return;
@@ -268,13 +297,19 @@ static int rmsnorm_bwd_t(int rows, int H, const void* dy, const void* x, const v
   }
 #undef GO
   DH_LAUNCH_CHECK();
-  colsum_accumulate_kernel<<<(H + 255) / 256, 256, 0, s>>>(partial, dgamma, nblk, H);
+  const int ngrp = (nblk + COLSUM_GROUP - 1) / COLSUM_GROUP;
+  float* grouped = partial + (size_t)nblk * H;
+  colsum_group_kernel<<<dim3((H + 255) / 256, ngrp), 256, 0, s>>>(partial, grouped, nblk, H);
+  DH_LAUNCH_CHECK();
+  colsum_accumulate_kernel<<<(H + 255) / 256, 256, 0, s>>>(grouped, dgamma, ngrp, H);
   DH_LAUNCH_CHECK();
   return DH_OK;
 }
 
 extern "C" size_t dh_rmsnorm_bwd_ws_bytes(int T, int H) {
-  return (size_t)((T + NORM_BWD_RPB - 1) / NORM_BWD_RPB) * H * sizeof(float);
+  size_t nblk = (size_t)(T + NORM_BWD_RPB - 1) / NORM_BWD_RPB;
+  size_t ngrp = (nblk + COLSUM_GROUP - 1) / COLSUM_GROUP;
+  return (nblk + ngrp) * H * sizeof(float);
 }
 
 extern "C" int dh_rmsnorm_bwd(int dtype, int T, int H, const void* dy, const void* x, const void* gamma,

@@ -8,6 +8,8 @@ no fallback path.
 import ctypes as C
 import os
 
+import torch  # noqa: F401  -- first, so that libdhelix binds to the HIP runtime PyTorch has already loaded
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libdhelix.so")
 if not os.path.exists(_LIB_PATH):
@@ -113,7 +115,8 @@ SIGNATURES = {
     "dh_swiglu_bwd": (_I, [_I, _I, _I, _P, _P, _P, _P]),
     "dh_add": (_I, [_I, _Z, _P, _P, _P, _P]),
     "dh_attn_fwd": (_I, [_I, _I, _I, _I, _I, _I, _P, _P, _P, _P]),
-    "dh_attn_bwd": (_I, [_I, _I, _I, _I, _I, _I, _P, _P, _P, _P, _P, _P, _P]),
+    "dh_attn_bwd": (_I, [_I, _I, _I, _I, _I, _I, _P, _P, _P, _P, _P, _P, _P, _Z, _P]),
+    "dh_attn_bwd_workspace_bytes": (_Z, [_I, _I, _I, _I, _I, _I]),
 }
 for _name, (_res, _args) in SIGNATURES.items():
     _fn = getattr(lib, _name)
@@ -359,6 +362,10 @@ def dh_attn_fwd(dtype, batch, seq, nq, nkv, d, qkv, o, lse, stream=None):
     _check(lib.dh_attn_fwd(dtype, batch, seq, nq, nkv, d, _ptr(qkv), _ptr(o), _ptr(lse), _stream(stream)))
 
 
-def dh_attn_bwd(dtype, batch, seq, nq, nkv, d, qkv, o, dout, lse, dqkv, delta, stream=None):
+def dh_attn_bwd(dtype, batch, seq, nq, nkv, d, qkv, o, dout, lse, dqkv, delta, ws=None, ws_bytes=0, stream=None):
     _check(lib.dh_attn_bwd(dtype, batch, seq, nq, nkv, d, _ptr(qkv), _ptr(o), _ptr(dout), _ptr(lse), _ptr(dqkv),
-                           _ptr(delta), _stream(stream)))
+                           _ptr(delta), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def dh_attn_bwd_workspace_bytes(dtype, batch, seq, nq, nkv, d):
+    return lib.dh_attn_bwd_workspace_bytes(dtype, batch, seq, nq, nkv, d)

@@ -121,7 +121,7 @@ def test_si_step_bitwise_equals_sequential_and_matches_oracle(name):
             "sequential": dh.dh_plan_sequential(run.layer),
             "one_pair": dh.make_plan(list(range(nf)), list(range(nb)), [(0, nf, 0, nb)]),
             "op_by_op": dh.make_plan(list(range(nf)), list(range(nb)),
-                                     [(i, min(i + 1, nf), i, min(i + 1, nb)) for i in range(max(nf, nb))]),
+                                     [(min(i, nf), min(i + 1, nf), min(i, nb), min(i + 1, nb)) for i in range(max(nf, nb))]),
             "random_a": random_legal_plan(dh, run, rng),
             "random_b": random_legal_plan(dh, run, rng),
         }

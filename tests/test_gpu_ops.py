@@ -243,12 +243,15 @@ def test_attention_fwd_bwd(dh, bf16, batch, seq, nq, nkv, d):
     assert np.max(np.abs(host(lse) - lse_ref)) <= (2e-2 if bf16 else 1e-5)
     dqkv = torch.zeros(T, nqkv, dtype=tdtype(bf16), device="cuda")
     delta = torch.empty(nq, T, dtype=torch.float32, device="cuda")
-    dh.dh_attn_bwd(dt(dh, bf16), batch, seq, nq, nkv, d, qd, o, dod, lse, dqkv, delta)
+    wsb = dh.dh_attn_bwd_workspace_bytes(dt(dh, bf16), batch, seq, nq, nkv, d)
+    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+    dh.dh_attn_bwd(dt(dh, bf16), batch, seq, nq, nkv, d, qd, o, dod, lse, dqkv, delta, ws, wsb)
     dq, dk, dv = R.attention_bwd(do.astype(np.float64).reshape(T, nq, d), q64, k64, v64, batch, seq)
     got = host(dqkv)
     tol = 2e-2 if bf16 else 1e-5
-    # dq, dk vanish identically when a row sees a single key (seq = 1): measure against dv's scale then
-    floor = 1e-2 * np.linalg.norm(dv)
+    # dq, dk vanish identically when every row sees a single key (seq = 1): what is left is the rounding
+    # of dP - delta, two equal sums taken in different orders, so measure against dv's scale then
+    floor = np.linalg.norm(dv) if seq == 1 else 0.0
 
     def relf(a, b):
         return np.linalg.norm(a - b) / max(np.linalg.norm(b), floor)
