@@ -6,40 +6,36 @@
 // The forward projections use (TA=0,TB=0) with weights [in,out]; data gradients (dY * W^T) use
 // (TA=0,TB=1); weight gradients (X^T * dY) use (TA=1,TB=0) and add into a float32 buffer.
 //
-// A 256-thread block (4 waves, 2x2) owns a BM x BN tile of C; a wave owns (BM/2) x (BN/2) as
-// 32x32 MFMA tiles.  K is consumed BK = 64 at a time through double-buffered LDS: while the matrix
-// cores work on stage s the next tile travels global -> registers -> LDS stage s^1, one barrier per
-// step.  The MFMA wants, per lane, 8 consecutive k of one row (A) or one column (B):
-//   * operands whose K is contiguous are stored [row][BK+8] and read with one 16-byte LDS read
-//     (the 8-element pad spreads 16 consecutive rows over all banks);
-//   * operands whose K is the slow dimension are stored as they come, [k][rows+32], and read with
-//     the transposing LDS load ds_read_b64_tr_b16: 16 lanes fetch a 4(k) x 16(row) patch and each
-//     gets the 4 k-values of one row -- two such reads make one 8-k fragment.  The 32-element pad
-//     puts 4 consecutive k-rows on disjoint banks.
-// Split-K (grid.z > 1) writes float32 partial tiles to a workspace that a second kernel adds in
+// Tiling.  A block of WM x WN waves owns a BM x BN tile of C; a wave owns (BM/WM) x (BN/WN) as 32x32
+// MFMA tiles.  K is consumed BK = 64 at a time through two LDS stages.  Tiles travel global -> LDS
+// directly (global_load_lds_dwordx4: each lane moves 16 bytes, a wave fills 1 KiB of consecutive
+// LDS), so no registers or LDS-write instructions are spent on staging; the loads of stage s+1 are
+// issued right after the barrier that releases stage s and land while the matrix cores work.
+// Because a wave's 1 KiB lands linearly in LDS, bank conflicts are avoided by permuting which global
+// 16-byte chunk each lane fetches (XOR swizzle), not by padding:
+//   * K-contiguous operand, tile [rows][64]: 8 chunks per row; chunk c of row r sits at position
+//     c ^ ((r>>1)&7).  The MFMA fragment read (16 lanes = 16 consecutive rows, one 16-byte chunk each)
+//     then touches 16 different 16-byte bank groups.
+//   * K-major operand (K is the slow dimension in memory), tile [64][cols]: chunk c of k-row r sits at
+//     c ^ ((r&3)<<2).  Fragments come out of LDS through the transposing load ds_read_b64_tr_b16
+//     (16 lanes fetch a 4(k) x 16(col) patch, each lane receives the 4 k-values of one column; two
+//     such reads make one 8-k fragment); the swizzle puts the 4 k-rows of a patch on disjoint banks.
+// Lanes whose chunk lies outside the matrix fetch from a 16-byte zero constant instead, which
+// zero-fills ragged edges without branches.
+// The tile -> block mapping is XCD-aware: consecutive block ids go round-robin to the 8 XCDs, so
+// block b works on logical tile (b%8)*ceil(tiles/8) + b/8, and logical tiles are ordered in groups
+// of 4 tile-rows, column by column; each XCD's L2 then serves a compact 4 x n patch of tiles.
+// Split-K (grid.y > 1) writes float32 partial tiles to a workspace that a second kernel adds in
 // split order, so results never depend on scheduling (no atomics anywhere).
-// Requirements: K-contiguous operands need K % 8 == 0, M/N-contiguous ones need M % 8 / N % 8 == 0
-// (16-byte loads); otherwise any size, edges are zero-filled / predicated.
+// Requirements: N % 8 == 0 and every contiguous operand dimension % 8 == 0 (16-byte chunks).
 #include "common.h"
 
 #define GB_BK 64
-#define GB_THREADS 256
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
 
-__device__ __forceinline__ bf16x8 lds_read_direct(const bf16_t* p) { return *reinterpret_cast<const bf16x8*>(p); }
-
-// Two transposing reads -> the 8 k-values (k0..k0+7) of row `m` for this lane.  `tile` is [k][ld].
-// Lane s of each 16-lane group points at (k0 + s/4, m16 + 4*(s%4)) and receives row m16 + s.
-__device__ __forceinline__ bf16x8 lds_read_tr(const bf16_t* tile, int ld, int k0, int m16, int s) {
-  const bf16_t* p0 = tile + (k0 + (s >> 2)) * ld + m16 + ((s & 3) << 2);
-  const bf16_t* p1 = p0 + 4 * ld;
-  s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(__attribute__((address_space(3))) void*)p0);
-  s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(__attribute__((address_space(3))) void*)p1);
-  typedef __attribute__((ext_vector_type(8))) short s16x8;
-  s16x8 r = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, r);
-}
+__device__ __attribute__((aligned(16))) const uint32_t dh_zero_chunk[4] = {0, 0, 0, 0};
 
 enum { EPI_STORE_BF16 = 0, EPI_ACC_F32 = 1, EPI_PARTIAL_F32 = 2 };
 
@@ -47,67 +43,91 @@ struct GemmArgs {
   int M, N, K;
   const bf16_t* A;
   const bf16_t* B;
-  void* C;         // bf16 (EPI_STORE_BF16), float (EPI_ACC_F32) or float partial base (EPI_PARTIAL_F32)
+  void* C;  // bf16 (EPI_STORE_BF16), float (EPI_ACC_F32) or float partial base (EPI_PARTIAL_F32)
   int epi;
-  int kt_per_split;  // K tiles handled by one grid.z slice
+  int kt_per_split;  // K tiles handled by one split
+  int tiles_m, tiles_n, tiles_per_xcd;
 };
 
-template <int BM, int BN, bool TA, bool TB>
-struct GemmTile {
-  // LDS footprint of one stage, in elements.  A is K-contiguous when !TA, B when TB.
-  static constexpr int A_LD = TA ? (BM + 32) : (GB_BK + 8);
-  static constexpr int A_ELEMS = TA ? GB_BK * A_LD : BM * A_LD;
-  static constexpr int B_LD = TB ? (GB_BK + 8) : (BN + 32);
-  static constexpr int B_ELEMS = TB ? BN * B_LD : GB_BK * B_LD;
-  static constexpr int STAGE = A_ELEMS + B_ELEMS;
-  static constexpr size_t LDS_BYTES = 2 * (size_t)STAGE * sizeof(bf16_t);
-  static constexpr int A_CHUNKS = BM * GB_BK / 8 / GB_THREADS;  // 16-byte chunks per thread
-  static constexpr int B_CHUNKS = BN * GB_BK / 8 / GB_THREADS;
-};
+// One 16-byte chunk per lane, global -> LDS.  lds_wave_base must be wave-uniform.  Written as inline
+// assembly so that the compiler does not order later LDS reads behind the transfer with a full
+// vmcnt(0) wait (it cannot tell the stages apart); the kernel waits for the transfers itself, once per
+// K step, before the barrier that publishes a stage.
+__device__ __forceinline__ void dma16(const void* gptr, bf16_t* lds_wave_base) {
+  const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds_wave_base;
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
+}
 
-// Global -> register fetch of one operand tile.  ROWS = extent of the tile along the operand's
-// non-K dimension, KMAJOR = memory rows are k (the non-K dimension is contiguous).
-template <int ROWS, int NCH, bool KMAJOR>
-__device__ __forceinline__ void fetch_tile(bf16x8 (&reg)[NCH], const bf16_t* __restrict__ base, int r0, int k0, int R,
-                                           int K) {
-  // base[(r, k)] = KMAJOR ? base[k*R + r] : base[r*K + k]
+// Issues this wave's share of one operand tile.  ROWS = tile extent along the operand's non-K
+// dimension; KMAJOR = memory rows are k.  R/K = full matrix extents (non-K dimension, K dimension).
+template <int ROWS, int NWAVES, bool KMAJOR>
+__device__ __forceinline__ void issue_tile(bf16_t* lds_tile, const bf16_t* __restrict__ base, int r0, int k0, int R, int K,
+                                           int wave, int lane) {
+  constexpr int INSTS = ROWS * GB_BK / 8 / 64;  // wave-level loads per tile
+  static_assert(INSTS % NWAVES == 0, "tile must split evenly over the waves");
+  constexpr int IPW = INSTS / NWAVES;
 #pragma unroll
-  for (int i = 0; i < NCH; i++) {
-    int id = threadIdx.x + i * GB_THREADS;
-    bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int j = 0; j < IPW; j++) {
+    const int inst = wave * IPW + j;
+    const int p = inst * 64 + lane;  // chunk position inside the LDS tile
+    const bf16_t* src;
     if (KMAJOR) {
-      int k = k0 + id / (ROWS / 8), r = r0 + (id % (ROWS / 8)) * 8;
-      if (k < K && r < R) v = *reinterpret_cast<const bf16x8*>(base + (size_t)k * R + r);
+      constexpr int CPR = ROWS / 8;
+      const int kr = p / CPR, c = (p % CPR) ^ ((kr & 3) << 2);
+      const int k = k0 + kr, r = r0 + c * 8;
+      src = (k < K && r < R) ? base + (size_t)k * R + r : reinterpret_cast<const bf16_t*>(dh_zero_chunk);
     } else {
-      int r = r0 + id / (GB_BK / 8), k = k0 + (id % (GB_BK / 8)) * 8;
-      if (r < R && k < K) v = *reinterpret_cast<const bf16x8*>(base + (size_t)r * K + k);
+      const int row = p >> 3, c = (p & 7) ^ ((row >> 1) & 7);
+      const int r = r0 + row, k = k0 + c * 8;
+      src = (r < R && k < K) ? base + (size_t)r * K + k : reinterpret_cast<const bf16_t*>(dh_zero_chunk);
     }
-    reg[i] = v;
+    dma16(src, lds_tile + inst * 512);
   }
 }
 
-template <int ROWS, int NCH, bool KMAJOR, int LD>
-__device__ __forceinline__ void stash_tile(const bf16x8 (&reg)[NCH], bf16_t* lds) {
-#pragma unroll
-  for (int i = 0; i < NCH; i++) {
-    int id = threadIdx.x + i * GB_THREADS;
-    int off = KMAJOR ? (id / (ROWS / 8)) * LD + (id % (ROWS / 8)) * 8 : (id / (GB_BK / 8)) * LD + (id % (GB_BK / 8)) * 8;
-    *reinterpret_cast<bf16x8*>(lds + off) = reg[i];
-  }
+// Fragment (8 consecutive k of one row) from a K-contiguous tile.
+__device__ __forceinline__ bf16x8 frag_kc(const bf16_t* tile, int row, int kchunk) {
+  return *reinterpret_cast<const bf16x8*>(tile + row * GB_BK + ((kchunk ^ ((row >> 1) & 7)) << 3));
+}
+// Fragment from a K-major tile [64][COLS]: k0..k0+7 of column c16 + s (s = lane%16, c16 % 16 == 0).
+template <int COLS>
+__device__ __forceinline__ bf16x8 frag_km(const bf16_t* tile, int k0, int c16, int s) {
+  const int kr = k0 + (s >> 2);                 // k0 % 8 == 0, so (kr & 3) == (s >> 2) for both reads
+  const int col = c16 + ((s & 3) << 2);
+  const int off = kr * COLS + ((((col >> 3) ^ ((kr & 3) << 2)) << 3) | (col & 7));
+  const bf16_t* p0 = tile + off;
+  const bf16_t* p1 = p0 + 4 * COLS;             // k-row + 4: same (kr & 3), same swizzle
+  s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(__attribute__((address_space(3))) void*)p0);
+  s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(__attribute__((address_space(3))) void*)p1);
+  return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
-template <int BM, int BN, bool TA, bool TB>
-__global__ __launch_bounds__(GB_THREADS) void gemm_bf16_kernel(GemmArgs g) {
-  using TL = GemmTile<BM, BN, TA, TB>;
-  constexpr int WTM = BM / 2, WTN = BN / 2, MT = WTM / 32, NT = WTN / 32;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+template <int BM, int BN, int WM, int WN, bool TA, bool TB>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmArgs g) {
+  constexpr int NW = WM * WN;
+  constexpr int WTM = BM / WM, WTN = BN / WN, MT = WTM / 32, NT = WTN / 32;
+  constexpr int A_ELEMS = BM * GB_BK, B_ELEMS = BN * GB_BK, STAGE = A_ELEMS + B_ELEMS;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
   bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm0 = (wave >> 1) * WTM, wn0 = (wave & 1) * WTN;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm0 = (wave / WN) * WTM, wn0 = (wave % WN) * WTN;
+
+  // XCD-aware tile mapping (see the header comment)
+  const int logical = (blockIdx.x & 7) * g.tiles_per_xcd + (blockIdx.x >> 3);
+  if (logical >= g.tiles_m * g.tiles_n) return;
+  int tm, tn;
+  {
+    const int group = logical / (4 * g.tiles_n);
+    const int rows_in_group = min(4, g.tiles_m - group * 4);
+    const int in_group = logical - group * 4 * g.tiles_n;
+    tm = group * 4 + in_group % rows_in_group;
+    tn = in_group / rows_in_group;
+  }
+  const int m0 = tm * BM, n0 = tn * BN;
   const int nkt_total = (g.K + GB_BK - 1) / GB_BK;
-  const int kt_begin = blockIdx.z * g.kt_per_split;
+  const int kt_begin = blockIdx.y * g.kt_per_split;
   const int kt_end = min(nkt_total, kt_begin + g.kt_per_split);
 
   f32x16 acc[MT][NT];
@@ -118,96 +138,89 @@ __global__ __launch_bounds__(GB_THREADS) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
 
-  bf16x8 ra[TL::A_CHUNKS], rb[TL::B_CHUNKS];
-  if (kt_begin < kt_end) {
-    fetch_tile<BM, TL::A_CHUNKS, TA>(ra, g.A, m0, kt_begin * GB_BK, g.M, g.K);
-    fetch_tile<BN, TL::B_CHUNKS, !TB>(rb, g.B, n0, kt_begin * GB_BK, g.N, g.K);
-    stash_tile<BM, TL::A_CHUNKS, TA, TL::A_LD>(ra, smem);
-    stash_tile<BN, TL::B_CHUNKS, !TB, TL::B_LD>(rb, smem + TL::A_ELEMS);
-  }
-  __syncthreads();
+  auto issue = [&](int kt) {
+    bf16_t* st = smem + ((kt - kt_begin) & 1) * STAGE;
+    issue_tile<BM, NW, TA>(st, g.A, m0, kt * GB_BK, g.M, g.K, wave, lane);
+    issue_tile<BN, NW, !TB>(st + A_ELEMS, g.B, n0, kt * GB_BK, g.N, g.K, wave, lane);
+  };
+  if (kt_begin < kt_end) issue(kt_begin);
 
   const int l32 = lane & 31, kg = lane >> 5, s16 = lane & 15, h16 = (lane >> 4) & 1;
   for (int kt = kt_begin; kt < kt_end; kt++) {
-    const int st = (kt - kt_begin) & 1;
-    const bf16_t* As = smem + st * TL::STAGE;
-    const bf16_t* Bs = As + TL::A_ELEMS;
-    const bool more = kt + 1 < kt_end;
-    if (more) {
-      fetch_tile<BM, TL::A_CHUNKS, TA>(ra, g.A, m0, (kt + 1) * GB_BK, g.M, g.K);
-      fetch_tile<BN, TL::B_CHUNKS, !TB>(rb, g.B, n0, (kt + 1) * GB_BK, g.N, g.K);
-    }
+    // stage kt has landed (vmcnt 0) for every wave, and every wave is done reading stage kt-1
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (kt + 1 < kt_end) issue(kt + 1);
+    const bf16_t* As = smem + ((kt - kt_begin) & 1) * STAGE;
+    const bf16_t* Bs = As + A_ELEMS;
 #pragma unroll
     for (int ks = 0; ks < GB_BK / 16; ks++) {
       bf16x8 fa[MT], fb[NT];
 #pragma unroll
       for (int i = 0; i < MT; i++) {
-        if (TA) fa[i] = lds_read_tr(As, TL::A_LD, ks * 16 + kg * 8, wm0 + i * 32 + h16 * 16, s16);
-        else fa[i] = lds_read_direct(As + (wm0 + i * 32 + l32) * TL::A_LD + ks * 16 + kg * 8);
+        if (TA) fa[i] = frag_km<BM>(As, ks * 16 + kg * 8, wm0 + i * 32 + h16 * 16, s16);
+        else fa[i] = frag_kc(As, wm0 + i * 32 + l32, ks * 2 + kg);
       }
 #pragma unroll
       for (int j = 0; j < NT; j++) {
-        if (!TB) fb[j] = lds_read_tr(Bs, TL::B_LD, ks * 16 + kg * 8, wn0 + j * 32 + h16 * 16, s16);
-        else fb[j] = lds_read_direct(Bs + (wn0 + j * 32 + l32) * TL::B_LD + ks * 16 + kg * 8);
+        if (!TB) fb[j] = frag_km<BN>(Bs, ks * 16 + kg * 8, wn0 + j * 32 + h16 * 16, s16);
+        else fb[j] = frag_kc(Bs, wn0 + j * 32 + l32, ks * 2 + kg);
       }
+      // operands swapped: the result tile is C^T, so a lane holds 4 consecutive columns of one row
 #pragma unroll
       for (int i = 0; i < MT; i++)
 #pragma unroll
-        for (int j = 0; j < NT; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < NT; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
     }
-    if (more) {
-      bf16_t* nx = smem + (st ^ 1) * TL::STAGE;
-      stash_tile<BM, TL::A_CHUNKS, TA, TL::A_LD>(ra, nx);
-      stash_tile<BN, TL::B_CHUNKS, !TB, TL::B_LD>(rb, nx + TL::A_ELEMS);
-    }
-    __syncthreads();
   }
 
-  // Epilogue.  acc[i][j][r] is C[row][col] with row = 8*(r/4) + 4*(lane/32) + r%4, col = lane%32.
+  // Epilogue.  acc[i][j][4q+e] = C[row][col], row = lane%32, col = 8q + 4*(lane/32) + e within the 32x32 tile.
   float* Cf = reinterpret_cast<float*>(g.C);
   bf16_t* Cb = reinterpret_cast<bf16_t*>(g.C);
-  if (g.epi == EPI_PARTIAL_F32) Cf += (size_t)blockIdx.z * g.M * g.N;
+  if (g.epi == EPI_PARTIAL_F32) Cf += (size_t)blockIdx.y * g.M * g.N;
 #pragma unroll
-  for (int i = 0; i < MT; i++)
+  for (int i = 0; i < MT; i++) {
+    const int row = m0 + wm0 + i * 32 + l32;
+    if (row >= g.M) continue;
 #pragma unroll
-    for (int j = 0; j < NT; j++) {
-      int col = n0 + wn0 + j * 32 + l32;
-      if (col >= g.N) continue;
+    for (int j = 0; j < NT; j++)
 #pragma unroll
-      for (int r = 0; r < 16; r++) {
-        int row = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * kg + (r & 3);
-        if (row >= g.M) continue;
-        size_t o = (size_t)row * g.N + col;
-        float v = acc[i][j][r];
-        if (g.epi == EPI_STORE_BF16) Cb[o] = (bf16_t)v;
-        else if (g.epi == EPI_ACC_F32) Cf[o] += v;
-        else Cf[o] = v;
+      for (int q = 0; q < 4; q++) {
+        const int col = n0 + wn0 + j * 32 + 8 * q + 4 * kg;
+        if (col >= g.N) continue;  // N % 8 == 0: a group of 4 columns is entirely in or out
+        const size_t o = (size_t)row * g.N + col;
+        f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+        if (g.epi == EPI_STORE_BF16) {
+          bf16x4 b = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+          *reinterpret_cast<bf16x4*>(Cb + o) = b;
+        } else if (g.epi == EPI_ACC_F32) {
+          f32x4* p = reinterpret_cast<f32x4*>(Cf + o);
+          *p = *p + v;
+        } else {
+          *reinterpret_cast<f32x4*>(Cf + o) = v;
+        }
       }
-    }
+  }
 }
 
 // Adds the split-K partials in split order; writes bf16 or accumulates into float32.
 __global__ void splitk_reduce_kernel(const float* __restrict__ part, int splits, size_t mn, void* __restrict__ C, int epi) {
   size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
   if (i >= mn) return;
-  float4 s = *reinterpret_cast<const float4*>(part + i);
-  for (int z = 1; z < splits; z++) {
-    float4 v = *reinterpret_cast<const float4*>(part + (size_t)z * mn + i);
-    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
-  }
+  f32x4 s = *reinterpret_cast<const f32x4*>(part + i);
+  for (int z = 1; z < splits; z++) s += *reinterpret_cast<const f32x4*>(part + (size_t)z * mn + i);
   if (epi == EPI_STORE_BF16) {
-    bf16x4 o = {(bf16_t)s.x, (bf16_t)s.y, (bf16_t)s.z, (bf16_t)s.w};
+    bf16x4 o = {(bf16_t)s[0], (bf16_t)s[1], (bf16_t)s[2], (bf16_t)s[3]};
     *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16_t*>(C) + i) = o;
   } else {
-    float4* c = reinterpret_cast<float4*>(reinterpret_cast<float*>(C) + i);
-    float4 o = *c;
-    o.x += s.x; o.y += s.y; o.z += s.z; o.w += s.w;
-    *c = o;
+    f32x4* c = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(C) + i);
+    *c = *c + s;
   }
 }
 
 // ------------------------------------------------------------------------------------ host side
 struct GemmPlan {
+  int cfg;  // 0: 256x256 (8 waves), 1: 128x128 (4 waves)
   int bm, bn, splits, kt_per_split;
 };
 
@@ -219,33 +232,32 @@ static int num_cus() {
       g_num_cus = n;
     else
       g_num_cus = 256;
+    (void)hipGetLastError();
   }
   return g_num_cus;
 }
 
-// Tile and split-K choice: prefer the largest tile that still gives every compute unit a block;
-// when even 128x128 tiles leave units idle and K is long, split K (bounded by the workspace).
+// Tile and split-K choice.  256x256 tiles when they give most compute units a block, else 128x128;
+// if a single wave of blocks still leaves units idle and K is long, split K (bounded by the
+// workspace) so that about one block per unit exists.
 static GemmPlan choose_plan(int M, int N, int K, size_t ws_bytes) {
   const int cus = num_cus();
   auto tiles = [&](int bm, int bn) { return (long long)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
   GemmPlan p;
-  if (tiles(256, 256) >= cus * 3 / 4) { p.bm = 256; p.bn = 256; }
-  else if (tiles(256, 128) >= cus * 3 / 4) { p.bm = 256; p.bn = 128; }
-  else { p.bm = 128; p.bn = 128; }
-  int nkt = (K + GB_BK - 1) / GB_BK;
-  long long t = tiles(p.bm, p.bn);
+  if (tiles(256, 256) * 2 >= cus) { p.cfg = 0; p.bm = 256; p.bn = 256; }
+  else { p.cfg = 1; p.bm = 128; p.bn = 128; }
+  const int nkt = (K + GB_BK - 1) / GB_BK;
+  const long long t = tiles(p.bm, p.bn);
   int splits = 1;
-  if (t < cus * 3 / 4 && nkt >= 8) {
-    splits = (int)((cus + t - 1) / t);
-    if (splits > nkt / 4) splits = nkt / 4;
-    size_t per = (size_t)M * N * sizeof(float);
+  if (t * 4 <= cus * 3 && nkt >= 16) {
+    splits = (int)(cus / t);
+    if (splits > nkt / 8) splits = nkt / 8;
+    const size_t per = (size_t)M * N * sizeof(float);
     if (per == 0 || ws_bytes / per < (size_t)splits) splits = per ? (int)(ws_bytes / per) : 1;
     if (splits < 2) splits = 1;
   }
-  p.splits = splits;
-  p.kt_per_split = (nkt + splits - 1) / splits;
+  p.kt_per_split = nkt == 0 ? 1 : (nkt + splits - 1) / splits;
   p.splits = nkt == 0 ? 1 : (nkt + p.kt_per_split - 1) / p.kt_per_split;
-  if (p.kt_per_split == 0) p.kt_per_split = 1;
   return p;
 }
 
@@ -255,48 +267,52 @@ size_t dh_gemm_bf16_ws_bytes(bool ta, bool tb, int M, int N, int K) {
   return p.splits > 1 ? (size_t)p.splits * M * N * sizeof(float) : 0;
 }
 
-template <int BM, int BN, bool TA, bool TB>
-static int launch_cfg(const GemmArgs& g, int splits, hipStream_t stream) {
-  using TL = GemmTile<BM, BN, TA, TB>;
+template <int BM, int BN, int WM, int WN, bool TA, bool TB>
+static int launch_cfg(GemmArgs g, int splits, hipStream_t stream) {
+  constexpr size_t LDS_BYTES = 2 * (size_t)(BM + BN) * GB_BK * sizeof(bf16_t);
   static bool attr_set = false;
   if (!attr_set) {
-    DH_HIP(hipFuncSetAttribute((const void*)gemm_bf16_kernel<BM, BN, TA, TB>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                               (int)TL::LDS_BYTES));
+    DH_HIP(hipFuncSetAttribute((const void*)gemm_bf16_kernel<BM, BN, WM, WN, TA, TB>,
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES));
     attr_set = true;
   }
-  dim3 grid((g.N + BN - 1) / BN, (g.M + BM - 1) / BM, splits);
-  gemm_bf16_kernel<BM, BN, TA, TB><<<grid, GB_THREADS, TL::LDS_BYTES, stream>>>(g);
+  g.tiles_m = (g.M + BM - 1) / BM;
+  g.tiles_n = (g.N + BN - 1) / BN;
+  g.tiles_per_xcd = (g.tiles_m * g.tiles_n + 7) / 8;
+  dim3 grid(g.tiles_per_xcd * 8, splits);
+  gemm_bf16_kernel<BM, BN, WM, WN, TA, TB><<<grid, 64 * WM * WN, LDS_BYTES, stream>>>(g);
   DH_LAUNCH_CHECK();
   return DH_OK;
 }
 
 template <bool TA, bool TB>
 static int launch_layout(const GemmArgs& g, const GemmPlan& p, hipStream_t stream) {
-  if (p.bm == 256 && p.bn == 256) return launch_cfg<256, 256, TA, TB>(g, p.splits, stream);
-  if (p.bm == 256 && p.bn == 128) return launch_cfg<256, 128, TA, TB>(g, p.splits, stream);
-  return launch_cfg<128, 128, TA, TB>(g, p.splits, stream);
+  if (p.cfg == 0) return launch_cfg<256, 256, 2, 4, TA, TB>(g, p.splits, stream);
+  return launch_cfg<128, 128, 2, 2, TA, TB>(g, p.splits, stream);
 }
 
 int dh_launch_gemm_bf16(bool ta, bool tb, int M, int N, int K, const bf16_t* A, const bf16_t* B, void* C,
                         bool out_f32_accumulate, void* ws, size_t ws_bytes, hipStream_t stream) {
   if (M < 0 || N < 0 || K < 0) DH_FAIL(DH_ERR_SHAPE, "gemm: negative dimension");
-  if ((ta ? M : K) % 8 || (tb ? K : N) % 8)
-    DH_FAIL(DH_ERR_SHAPE, "gemm (bf16): contiguous dimensions must be multiples of 8 (M=%d N=%d K=%d ta=%d tb=%d)", M, N, K, ta, tb);
+  if (N % 8 || (ta ? M : K) % 8 || (tb ? K : N) % 8)
+    DH_FAIL(DH_ERR_SHAPE, "gemm (bf16): N and the contiguous operand dimensions must be multiples of 8 (M=%d N=%d K=%d ta=%d tb=%d)", M, N, K, ta, tb);
+  if (ta && tb) DH_FAIL(DH_ERR_UNSUPPORTED, "gemm (bf16): trans_a with trans_b is not used by the layer and not built");
   if (M == 0 || N == 0) return DH_OK;
+  if ((long long)M * N >= (1ll << 40) || (long long)M * K >= (1ll << 40)) DH_FAIL(DH_ERR_SHAPE, "gemm: matrix too large");
   GemmPlan p = choose_plan(M, N, K, ws ? ws_bytes : 0);
   GemmArgs g;
   g.M = M; g.N = N; g.K = K; g.A = A; g.B = B;
   g.kt_per_split = p.kt_per_split;
-  int final_epi = out_f32_accumulate ? EPI_ACC_F32 : EPI_STORE_BF16;
+  g.tiles_m = g.tiles_n = g.tiles_per_xcd = 0;
+  const int final_epi = out_f32_accumulate ? EPI_ACC_F32 : EPI_STORE_BF16;
   if (p.splits > 1) { g.C = ws; g.epi = EPI_PARTIAL_F32; } else { g.C = C; g.epi = final_epi; }
   int rc;
   if (!ta && !tb) rc = launch_layout<false, false>(g, p, stream);
   else if (!ta && tb) rc = launch_layout<false, true>(g, p, stream);
-  else if (ta && !tb) rc = launch_layout<true, false>(g, p, stream);
-  else DH_FAIL(DH_ERR_UNSUPPORTED, "gemm (bf16): trans_a with trans_b is not used by the layer and not built");
+  else rc = launch_layout<true, false>(g, p, stream);
   if (rc != DH_OK) return rc;
   if (p.splits > 1) {
-    size_t mn = (size_t)M * N;  // multiple of 8 because N is
+    const size_t mn = (size_t)M * N;  // multiple of 8 because N is
     splitk_reduce_kernel<<<(unsigned)((mn / 4 + 255) / 256), 256, 0, stream>>>((const float*)ws, p.splits, mn, C, final_epi);
     DH_LAUNCH_CHECK();
   }
