@@ -15,7 +15,7 @@ SOURCES = ["api.cpp", "plan.cpp", "rowops.hip", "standin.hip", "gemm_f32.hip", "
            "attn_bf16.hip", "layer.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
-         "-Wno-unknown-warning-option"]
+         "-Wno-unknown-warning-option", "-Wno-inline-asm"]
 
 
 def _deps_mtime():

@@ -7,16 +7,17 @@
 // (TA=0,TB=1); weight gradients (X^T * dY) use (TA=1,TB=0) and add into a float32 buffer.
 //
 // Tiling.  A block of WM x WN waves owns a BM x BN tile of C; a wave owns (BM/WM) x (BN/WN) as 32x32
-// MFMA tiles.  K is consumed BK = 64 at a time through two LDS stages.  Tiles travel global -> LDS
-// directly (global_load_lds_dwordx4: each lane moves 16 bytes, a wave fills 1 KiB of consecutive
-// LDS), so no registers or LDS-write instructions are spent on staging; the loads of stage s+1 are
-// issued right after the barrier that releases stage s and land while the matrix cores work.
+// MFMA tiles.  K is consumed BK = 32 at a time through a ring of 4 LDS stages.  Tiles travel global
+// -> LDS directly (global_load_lds_dwordx4: each lane moves 16 bytes, a wave fills 1 KiB of consecutive
+// LDS), so no registers or LDS-write instructions are spent on staging; the loads of stage s+3 are
+// issued right after the barrier that releases stage s, i.e. three K steps of matrix work cover the
+// memory latency, and a step only waits (vmcnt) for the oldest stage in flight.
 // Because a wave's 1 KiB lands linearly in LDS, bank conflicts are avoided by permuting which global
 // 16-byte chunk each lane fetches (XOR swizzle), not by padding:
-//   * K-contiguous operand, tile [rows][64]: 8 chunks per row; chunk c of row r sits at position
-//     c ^ ((r>>1)&7).  The MFMA fragment read (16 lanes = 16 consecutive rows, one 16-byte chunk each)
+//   * K-contiguous operand, tile [rows][32]: 4 chunks per row; chunk c of row r sits at position
+//     c ^ ((r>>2)&3).  The MFMA fragment read (16 lanes = 16 consecutive rows, one 16-byte chunk each)
 //     then touches 16 different 16-byte bank groups.
-//   * K-major operand (K is the slow dimension in memory), tile [64][cols]: chunk c of k-row r sits at
+//   * K-major operand (K is the slow dimension in memory), tile [32][cols]: chunk c of k-row r sits at
 //     c ^ ((r&3)<<2).  Fragments come out of LDS through the transposing load ds_read_b64_tr_b16
 //     (16 lanes fetch a 4(k) x 16(col) patch, each lane receives the 4 k-values of one column; two
 //     such reads make one 8-k fragment); the swizzle puts the 4 k-rows of a patch on disjoint banks.
@@ -30,7 +31,8 @@
 // Requirements: N % 8 == 0 and every contiguous operand dimension % 8 == 0 (16-byte chunks).
 #include "common.h"
 
-#define GB_BK 64
+#define GB_BK 32
+#define GB_STAGES 4
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
@@ -58,7 +60,36 @@ __device__ __forceinline__ void dma16(const void* gptr, bf16_t* lds_wave_base) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
 }
 
-// Issues this wave's share of one operand tile.  ROWS = tile extent along the operand's non-K
+// Same with a wave-uniform 64-bit base (SGPR pair) and a per-lane 32-bit byte offset: the offsets of a
+// tile do not change from one K step to the next, only the base advances.
+__device__ __forceinline__ void dma16_base(const void* sbase, uint32_t voff, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(sbase) : "memory", "m0");
+}
+
+// Per-lane byte offsets of this wave's chunks relative to the tile origin (row r0, k = tile start).
+// Rows/columns beyond the matrix are clamped to the last valid one: they only feed rows/columns of C
+// that are never stored.  (K must not be clamped; ragged K tiles take issue_tile below.)
+template <int ROWS, int NWAVES, bool KMAJOR>
+__device__ __forceinline__ void tile_offsets(uint32_t (&voff)[ROWS * GB_BK / 8 / 64 / NWAVES], int r0, int R, int K, int wave,
+                                             int lane) {
+  constexpr int IPW = ROWS * GB_BK / 8 / 64 / NWAVES;
+#pragma unroll
+  for (int j = 0; j < IPW; j++) {
+    const int p = (wave * IPW + j) * 64 + lane;
+    if (KMAJOR) {
+      constexpr int CPR = ROWS / 8;
+      const int kr = p / CPR, c = (p % CPR) ^ ((kr & 3) << 2);
+      const int col = min(r0 + c * 8, R - 8) - r0;
+      voff[j] = (uint32_t)(((size_t)kr * R + col) * sizeof(bf16_t));
+    } else {
+      const int row = p >> 2, c = (p & 3) ^ ((row >> 2) & 3);
+      const int rr = min(r0 + row, R - 1) - r0;
+      voff[j] = (uint32_t)(((size_t)rr * K + c * 8) * sizeof(bf16_t));
+    }
+  }
+}
+
+// Issues this wave's share of one operand tile (general path with per-chunk bounds checks).  ROWS = tile extent along the operand's non-K
 // dimension; KMAJOR = memory rows are k.  R/K = full matrix extents (non-K dimension, K dimension).
 template <int ROWS, int NWAVES, bool KMAJOR>
 __device__ __forceinline__ void issue_tile(bf16_t* lds_tile, const bf16_t* __restrict__ base, int r0, int k0, int R, int K,
@@ -77,7 +108,7 @@ __device__ __forceinline__ void issue_tile(bf16_t* lds_tile, const bf16_t* __res
       const int k = k0 + kr, r = r0 + c * 8;
       src = (k < K && r < R) ? base + (size_t)k * R + r : reinterpret_cast<const bf16_t*>(dh_zero_chunk);
     } else {
-      const int row = p >> 3, c = (p & 7) ^ ((row >> 1) & 7);
+      const int row = p >> 2, c = (p & 3) ^ ((row >> 2) & 3);
       const int r = r0 + row, k = k0 + c * 8;
       src = (r < R && k < K) ? base + (size_t)r * K + k : reinterpret_cast<const bf16_t*>(dh_zero_chunk);
     }
@@ -87,9 +118,9 @@ __device__ __forceinline__ void issue_tile(bf16_t* lds_tile, const bf16_t* __res
 
 // Fragment (8 consecutive k of one row) from a K-contiguous tile.
 __device__ __forceinline__ bf16x8 frag_kc(const bf16_t* tile, int row, int kchunk) {
-  return *reinterpret_cast<const bf16x8*>(tile + row * GB_BK + ((kchunk ^ ((row >> 1) & 7)) << 3));
+  return *reinterpret_cast<const bf16x8*>(tile + row * GB_BK + ((kchunk ^ ((row >> 2) & 3)) << 3));
 }
-// Fragment from a K-major tile [64][COLS]: k0..k0+7 of column c16 + s (s = lane%16, c16 % 16 == 0).
+// Fragment from a K-major tile [GB_BK][COLS]: k0..k0+7 of column c16 + s (s = lane%16, c16 % 16 == 0).
 template <int COLS>
 __device__ __forceinline__ bf16x8 frag_km(const bf16_t* tile, int k0, int c16, int s) {
   const int kr = k0 + (s >> 2);                 // k0 % 8 == 0, so (kr & 3) == (s >> 2) for both reads
@@ -138,20 +169,37 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
 
-  auto issue = [&](int kt) {
-    bf16_t* st = smem + ((kt - kt_begin) & 1) * STAGE;
-    issue_tile<BM, NW, TA>(st, g.A, m0, kt * GB_BK, g.M, g.K, wave, lane);
-    issue_tile<BN, NW, !TB>(st + A_ELEMS, g.B, n0, kt * GB_BK, g.N, g.K, wave, lane);
+  constexpr int IPA = BM * GB_BK / 8 / 64 / NW, IPB = BN * GB_BK / 8 / 64 / NW, IPS = IPA + IPB;
+  uint32_t voa[IPA], vob[IPB];
+  tile_offsets<BM, NW, TA>(voa, m0, g.M, g.K, wave, lane);
+  tile_offsets<BN, NW, !TB>(vob, n0, g.N, g.K, wave, lane);
+  // tile origins at k = 0 and the byte stride of one K step
+  const char* a0 = reinterpret_cast<const char*>(g.A + (TA ? (size_t)m0 : (size_t)m0 * g.K));
+  const char* b0 = reinterpret_cast<const char*>(g.B + (TB ? (size_t)n0 * g.K : (size_t)n0));
+  const size_t sa = (TA ? (size_t)GB_BK * g.M : (size_t)GB_BK) * sizeof(bf16_t);
+  const size_t sb = (TB ? (size_t)GB_BK : (size_t)GB_BK * g.N) * sizeof(bf16_t);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem;
+  auto issue_full = [&](int stage, const char* ab, const char* bb) {  // full K tile: precomputed offsets, uniform base
+    const uint32_t la = lds0 + (uint32_t)(stage * STAGE * sizeof(bf16_t)) + wave * IPA * 1024;
+    const uint32_t lb = lds0 + (uint32_t)((stage * STAGE + A_ELEMS) * sizeof(bf16_t)) + wave * IPB * 1024;
+#pragma unroll
+    for (int j = 0; j < IPA; j++) dma16_base(ab, voa[j], la + j * 1024);
+#pragma unroll
+    for (int j = 0; j < IPB; j++) dma16_base(bb, vob[j], lb + j * 1024);
   };
-  if (kt_begin < kt_end) issue(kt_begin);
-
+  auto issue = [&](int kt) {
+    const int stage = (kt - kt_begin) % GB_STAGES;
+    if ((kt + 1) * GB_BK <= g.K) {
+      issue_full(stage, a0 + (size_t)kt * sa, b0 + (size_t)kt * sb);
+    } else {
+      bf16_t* st = smem + stage * STAGE;
+      issue_tile<BM, NW, TA>(st, g.A, m0, kt * GB_BK, g.M, g.K, wave, lane);
+      issue_tile<BN, NW, !TB>(st + A_ELEMS, g.B, n0, kt * GB_BK, g.N, g.K, wave, lane);
+    }
+  };
   const int l32 = lane & 31, kg = lane >> 5, s16 = lane & 15, h16 = (lane >> 4) & 1;
-  for (int kt = kt_begin; kt < kt_end; kt++) {
-    // stage kt has landed (vmcnt 0) for every wave, and every wave is done reading stage kt-1
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (kt + 1 < kt_end) issue(kt + 1);
-    const bf16_t* As = smem + ((kt - kt_begin) & 1) * STAGE;
+  auto compute = [&](int stage) {
+    const bf16_t* As = smem + stage * STAGE;
     const bf16_t* Bs = As + A_ELEMS;
 #pragma unroll
     for (int ks = 0; ks < GB_BK / 16; ks++) {
@@ -172,6 +220,41 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
         for (int j = 0; j < NT; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
     }
+  };
+
+#pragma unroll
+  for (int s = 0; s < GB_STAGES - 1; s++)
+    if (kt_begin + s < kt_end) issue(kt_begin + s);
+
+  // Step `it` (K tile kt_begin+it, stage it%4): wait until that stage has landed -- the GB_STAGES-2
+  // younger stages may stay in flight --, barrier (which also tells that every wave is done reading
+  // stage it-1), issue the transfer of tile it+3 into stage it-1's buffer, then multiply.
+  const int n = kt_end - kt_begin;
+  const int n_full = min(kt_end, g.K / GB_BK) - kt_begin;  // leading steps whose tile is a full K tile
+  int it = 0;
+  {
+    // steady state, four steps per trip so that stage numbers are constants; every tile issued here
+    // (up to it+6) is a full tile inside this block's K range
+    const char* ap = a0 + (size_t)(kt_begin + GB_STAGES - 1) * sa;
+    const char* bp = b0 + (size_t)(kt_begin + GB_STAGES - 1) * sb;
+    for (; it + 2 * GB_STAGES - 1 <= n_full; it += GB_STAGES) {
+#pragma unroll
+      for (int u = 0; u < GB_STAGES; u++) {
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((GB_STAGES - 2) * IPS) : "memory");
+        __syncthreads();
+        issue_full((u + GB_STAGES - 1) % GB_STAGES, ap, bp);
+        ap += sa;
+        bp += sb;
+        compute(u);
+      }
+    }
+  }
+  for (; it < n; it++) {  // tail (and short K ranges): same steps with the checks spelled out
+    if (it + GB_STAGES - 2 < n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((GB_STAGES - 2) * IPS) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (it + GB_STAGES - 1 < n) issue(kt_begin + it + GB_STAGES - 1);
+    compute(it % GB_STAGES);
   }
 
   // Epilogue.  acc[i][j][4q+e] = C[row][col], row = lane%32, col = 8q + 4*(lane/32) + e within the 32x32 tile.
@@ -249,9 +332,9 @@ static GemmPlan choose_plan(int M, int N, int K, size_t ws_bytes) {
   const int nkt = (K + GB_BK - 1) / GB_BK;
   const long long t = tiles(p.bm, p.bn);
   int splits = 1;
-  if (t * 4 <= cus * 3 && nkt >= 16) {
+  if (t * 4 <= cus * 3 && nkt >= 32) {
     splits = (int)(cus / t);
-    if (splits > nkt / 8) splits = nkt / 8;
+    if (splits > nkt / 16) splits = nkt / 16;
     const size_t per = (size_t)M * N * sizeof(float);
     if (per == 0 || ws_bytes / per < (size_t)splits) splits = per ? (int)(ws_bytes / per) : 1;
     if (splits < 2) splits = 1;
@@ -269,7 +352,7 @@ size_t dh_gemm_bf16_ws_bytes(bool ta, bool tb, int M, int N, int K) {
 
 template <int BM, int BN, int WM, int WN, bool TA, bool TB>
 static int launch_cfg(GemmArgs g, int splits, hipStream_t stream) {
-  constexpr size_t LDS_BYTES = 2 * (size_t)(BM + BN) * GB_BK * sizeof(bf16_t);
+  constexpr size_t LDS_BYTES = GB_STAGES * (size_t)(BM + BN) * GB_BK * sizeof(bf16_t);
   static bool attr_set = false;
   if (!attr_set) {
     DH_HIP(hipFuncSetAttribute((const void*)gemm_bf16_kernel<BM, BN, WM, WN, TA, TB>,
