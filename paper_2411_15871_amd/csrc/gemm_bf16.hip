@@ -198,39 +198,51 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmArgs g) {
     }
   };
   const int l32 = lane & 31, kg = lane >> 5, s16 = lane & 15, h16 = (lane >> 4) & 1;
-  auto compute = [&](int stage) {
+  struct Frags {
+    bf16x8 a[MT], b[NT];
+  };
+  auto load_frags = [&](Frags& f, int stage, int ks) {
     const bf16_t* As = smem + stage * STAGE;
     const bf16_t* Bs = As + A_ELEMS;
 #pragma unroll
-    for (int ks = 0; ks < GB_BK / 16; ks++) {
-      bf16x8 fa[MT], fb[NT];
+    for (int i = 0; i < MT; i++) {
+      if (TA) f.a[i] = frag_km<BM>(As, ks * 16 + kg * 8, wm0 + i * 32 + h16 * 16, s16);
+      else f.a[i] = frag_kc(As, wm0 + i * 32 + l32, ks * 2 + kg);
+    }
 #pragma unroll
-      for (int i = 0; i < MT; i++) {
-        if (TA) fa[i] = frag_km<BM>(As, ks * 16 + kg * 8, wm0 + i * 32 + h16 * 16, s16);
-        else fa[i] = frag_kc(As, wm0 + i * 32 + l32, ks * 2 + kg);
-      }
-#pragma unroll
-      for (int j = 0; j < NT; j++) {
-        if (!TB) fb[j] = frag_km<BN>(Bs, ks * 16 + kg * 8, wn0 + j * 32 + h16 * 16, s16);
-        else fb[j] = frag_kc(Bs, wn0 + j * 32 + l32, ks * 2 + kg);
-      }
-      // operands swapped: the result tile is C^T, so a lane holds 4 consecutive columns of one row
-#pragma unroll
-      for (int i = 0; i < MT; i++)
-#pragma unroll
-        for (int j = 0; j < NT; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    for (int j = 0; j < NT; j++) {
+      if (!TB) f.b[j] = frag_km<BN>(Bs, ks * 16 + kg * 8, wn0 + j * 32 + h16 * 16, s16);
+      else f.b[j] = frag_kc(Bs, wn0 + j * 32 + l32, ks * 2 + kg);
     }
   };
+  // operands swapped: the result tile is C^T, so a lane holds 4 consecutive columns of one row
+  auto mma = [&](const Frags& f) {
+#pragma unroll
+    for (int i = 0; i < MT; i++)
+#pragma unroll
+      for (int j = 0; j < NT; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
+  };
+  static_assert(GB_BK == 32, "the step below is written for two 16-wide MFMA sub-steps per stage");
 
 #pragma unroll
   for (int s = 0; s < GB_STAGES - 1; s++)
     if (kt_begin + s < kt_end) issue(kt_begin + s);
 
-  // Step `it` (K tile kt_begin+it, stage it%4): wait until that stage has landed -- the GB_STAGES-2
-  // younger stages may stay in flight --, barrier (which also tells that every wave is done reading
-  // stage it-1), issue the transfer of tile it+3 into stage it-1's buffer, then multiply.
+  // Step `it` works on K tile kt_begin+it held in stage it%4.  The fragments of its first sub-step were
+  // read at the end of step it-1; the step reads the second sub-step's fragments, multiplies the first,
+  // then waits until stage it+1 has landed (the GB_STAGES-2 younger stages may stay in flight) and
+  // passes the barrier -- after which every wave is also done reading stage it-1 --, issues the
+  // transfer of tile it+3 into that buffer, reads the first fragments of stage it+1 and multiplies the
+  // second sub-step.  The matrix cores thus have work queued across the barrier and the LDS latency.
   const int n = kt_end - kt_begin;
   const int n_full = min(kt_end, g.K / GB_BK) - kt_begin;  // leading steps whose tile is a full K tile
+  Frags f0, f1;
+  if (n > 0) {
+    if (n > GB_STAGES - 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((GB_STAGES - 2) * IPS) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    load_frags(f0, 0, 0);
+  }
   int it = 0;
   {
     // steady state, four steps per trip so that stage numbers are constants; every tile issued here
@@ -240,21 +252,29 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmArgs g) {
     for (; it + 2 * GB_STAGES - 1 <= n_full; it += GB_STAGES) {
 #pragma unroll
       for (int u = 0; u < GB_STAGES; u++) {
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((GB_STAGES - 2) * IPS) : "memory");
+        load_frags(f1, u, 1);
+        mma(f0);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((GB_STAGES - 3) * IPS) : "memory");
         __syncthreads();
         issue_full((u + GB_STAGES - 1) % GB_STAGES, ap, bp);
         ap += sa;
         bp += sb;
-        compute(u);
+        load_frags(f0, (u + 1) % GB_STAGES, 0);
+        mma(f1);
       }
     }
   }
   for (; it < n; it++) {  // tail (and short K ranges): same steps with the checks spelled out
-    if (it + GB_STAGES - 2 < n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((GB_STAGES - 2) * IPS) : "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (it + GB_STAGES - 1 < n) issue(kt_begin + it + GB_STAGES - 1);
-    compute(it % GB_STAGES);
+    load_frags(f1, it % GB_STAGES, 1);
+    mma(f0);
+    if (it + 1 < n) {
+      if (it + GB_STAGES - 2 < n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((GB_STAGES - 3) * IPS) : "memory");
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      if (it + GB_STAGES - 1 < n) issue(kt_begin + it + GB_STAGES - 1);
+      load_frags(f0, (it + 1) % GB_STAGES, 0);
+    }
+    mma(f1);
   }
 
   // Epilogue.  acc[i][j][4q+e] = C[row][col], row = lane%32, col = 8q + 4*(lane/32) + e within the 32x32 tile.
