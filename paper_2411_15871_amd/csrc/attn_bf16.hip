@@ -7,67 +7,89 @@
 // lane-local: v_mfma_f32_32x32x16_bf16 leaves column j of its result in lane j%32, so
 //   forward / dQ : S^T = K Q^T        (column = query  -> running max/sum, lse, delta live in the lane)
 //   dK/dV        : S   = Q K^T        (column = key    -> the dK^T, dV^T accumulators keep their column)
-// and the probability tile can be fed back as the B operand of the next product straight from
-// registers (the 8 k-slots of a lane are rows 8*(r/4)+4*(lane/32)+r%4 of two adjacent register
-// quads).  The matching A operand (V^T, K^T, dO^T, Q^T: "k" is the token index, which is the slow
-// dimension in memory) comes from LDS through the transposing load ds_read_b64_tr_b16.
-// No atomics: dQ is produced per query block, dK/dV per key block, each summed in a fixed order.
+// and the probability tile is fed back as the B operand of the next product straight from registers
+// (the 8 k-slots of a lane are rows 8*(r/4)+4*(lane/32)+r%4 of two adjacent register quads).  The
+// matching A operand (V^T, K^T, dO^T, Q^T: "k" is the token index, the slow dimension in memory)
+// comes from LDS through the transposing load ds_read_b64_tr_b16.
+//
+// 64-token tiles stream global -> LDS directly (see dma.h) through a ring of three slots: the
+// transfer of tile t+2 is issued right after the barrier that publishes tile t.  A tile is stored
+// [token][D] unpadded; the 16-byte chunk c of row r sits at chunk position c ^ swz(r), which makes
+// the 16-byte fragment reads (16 consecutive rows, one chunk) and the transposing reads (4
+// consecutive rows x 64 bytes) both bank-conflict free for 256-byte rows (D = 128).
+// Blocks are launched heaviest first (the causal work per block grows with its position).
+// No atomics: dQ is produced per query block, dK/dV per (key block, query head), then the heads of
+// a group are added in index order.
 #include "common.h"
+#include "dma.h"
 
 #define AB_THREADS 256
-#define AB_KT 64  // tokens per LDS tile
+#define AB_KT 64   // tokens per LDS tile
+#define AB_RING 3  // tile slots
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 
-// A 64-token tile is stored [token][D] without padding; the 16-byte chunk c of row r sits at chunk
-// position c ^ swz(r).  With 256-byte rows (D = 128) this makes both access patterns conflict-free:
-// the 16-byte reads of 16 consecutive rows at one chunk index (swz is a bijection on r%16) and the
-// transposing reads of 4 consecutive rows x 64 bytes (r%4 lands in the upper two chunk bits).
+#define LOG2E 1.4426950408889634f
+#define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
+
 template <int D>
 struct ATile {
   static constexpr int LD = D;
-  static constexpr int ELEMS = AB_KT * LD;  // one 64-token tile
-  static constexpr int CHUNKS = AB_KT * D / 8 / AB_THREADS;
-  static constexpr int CPR = D / 8;         // chunks per row
+  static constexpr int ELEMS = AB_KT * D;
+  static constexpr int BYTES = ELEMS * 2;
+  static constexpr int CPR = D / 8;   // 16-byte chunks per row
+  static constexpr int IPW = D / 32;  // transfers per wave per tile (4 waves)
   __device__ static __forceinline__ int swz(int r) { return (((r & 3) << 2) | ((r >> 2) & 3)) & (CPR - 1); }
-  // element offset of (row r, column c) for c a multiple of 4 (stays inside one chunk)
+  // element offset of (row r, column c), c a multiple of 4
   __device__ static __forceinline__ int off(int r, int c) { return r * LD + ((((c >> 3) ^ swz(r)) << 3) | (c & 7)); }
 };
 
-// fetch a [64 tokens][D] tile (row stride ld elements) into registers; rows >= limit read as zero.
+// Per-lane byte offsets (relative to the tile's first row in global memory, row stride ld elements)
+// of the chunks this wave transfers; rows >= rows_valid are clamped to the last valid row.
 template <int D>
-__device__ __forceinline__ void afetch(bf16x8 (&reg)[ATile<D>::CHUNKS], const bf16_t* __restrict__ base, int ld, int row0,
-                                       int limit) {
+__device__ __forceinline__ void tile_voff(uint32_t (&v)[ATile<D>::IPW], int ld, int wave, int lane, int rows_valid) {
+  using TL = ATile<D>;
 #pragma unroll
-  for (int i = 0; i < ATile<D>::CHUNKS; i++) {
-    int id = threadIdx.x + i * AB_THREADS;
-    int r = row0 + id / (D / 8), c = (id % (D / 8)) * 8;
-    bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (r < limit) v = *reinterpret_cast<const bf16x8*>(base + (size_t)r * ld + c);
-    reg[i] = v;
+  for (int j = 0; j < TL::IPW; j++) {
+    const int p = (wave * TL::IPW + j) * 64 + lane;
+    const int row = p / TL::CPR, c = (p % TL::CPR) ^ TL::swz(row);
+    v[j] = (uint32_t)(((size_t)min(row, rows_valid - 1) * ld + c * 8) * sizeof(bf16_t));
   }
 }
 template <int D>
-__device__ __forceinline__ void astash(const bf16x8 (&reg)[ATile<D>::CHUNKS], bf16_t* lds) {
+__device__ __forceinline__ void tile_dma(const char* base, const uint32_t (&v)[ATile<D>::IPW], uint32_t lds_tile, int wave) {
 #pragma unroll
-  for (int i = 0; i < ATile<D>::CHUNKS; i++) {
-    int id = threadIdx.x + i * AB_THREADS;
-    *reinterpret_cast<bf16x8*>(lds + ATile<D>::off(id / (D / 8), (id % (D / 8)) * 8)) = reg[i];
+  for (int j = 0; j < ATile<D>::IPW; j++) dma16_base(base, v[j], lds_tile + (wave * ATile<D>::IPW + j) * 1024);
+}
+
+// Byte offsets inside a tile of the two kinds of fragment reads, precomputed per lane.
+//   direct: row l32 (+32*mt), columns ks*16 + kg*8 .. +7              -> kdir[ks] (+ mt*32*LD*2)
+//   transposed: rows 4*kg + s/4 (+8 for the second read) (+ mt*32 + 16*c), column dt*32 + h16*16 + (s%4)*4
+//                                                                      -> tr0[dt], tr1[dt] (+ (mt*32+16c)*LD*2)
+// The swizzle of a row only depends on row%16 through bits that the added multiples of 16 (and, for
+// the direct reads, 32) leave untouched, so the additions are plain constants.
+template <int D>
+struct FragAddr {
+  int kdir[D / 16], tr0[D / 32], tr1[D / 32];
+  __device__ __forceinline__ void init(int lane) {
+    using TL = ATile<D>;
+    const int l32 = lane & 31, kg = lane >> 5, s16 = lane & 15, h16 = (lane >> 4) & 1;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ks++) kdir[ks] = TL::off(l32, ks * 16 + kg * 8) * 2;
+#pragma unroll
+    for (int dt = 0; dt < D / 32; dt++) {
+      tr0[dt] = TL::off(4 * kg + (s16 >> 2), dt * 32 + h16 * 16 + ((s16 & 3) << 2)) * 2;
+      tr1[dt] = TL::off(8 + 4 * kg + (s16 >> 2), dt * 32 + h16 * 16 + ((s16 & 3) << 2)) * 2;
+    }
   }
+};
+__device__ __forceinline__ bf16x8 lds_frag(const char* tile, int byte_off) {
+  return *reinterpret_cast<const bf16x8*>(tile + byte_off);
 }
-// A/B fragment whose 8 k-values are contiguous in the tile row: row `r`, columns c0..c0+7.
-template <int D>
-__device__ __forceinline__ bf16x8 frag_direct(const bf16_t* tile, int r, int c0) {
-  return *reinterpret_cast<const bf16x8*>(tile + ATile<D>::off(r, c0));
-}
-// Fragment whose k runs down the tile's rows: column c16+s (s = lane%16), rows ka..ka+3 and kb..kb+3.
-template <int D>
-__device__ __forceinline__ bf16x8 frag_tr(const bf16_t* tile, int ka, int kb, int c16, int s) {
-  const bf16_t* p0 = tile + ATile<D>::off(ka + (s >> 2), c16 + ((s & 3) << 2));
-  const bf16_t* p1 = tile + ATile<D>::off(kb + (s >> 2), c16 + ((s & 3) << 2));
-  s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(__attribute__((address_space(3))) void*)p0);
-  s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(__attribute__((address_space(3))) void*)p1);
+__device__ __forceinline__ bf16x8 lds_frag_tr(const char* tile, int off0, int off1) {
+  s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(__attribute__((address_space(3))) void*)(tile + off0));
+  s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(__attribute__((address_space(3))) void*)(tile + off1));
   return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 // Registers 8c..8c+7 of a 32x32 result tile as a bf16 B fragment (k-slots = rows 16c+4g+{0..3}, 16c+8+4g+{0..3}).
@@ -77,33 +99,37 @@ __device__ __forceinline__ bf16x8 pack_rows(const f32x16& t, int c) {
   for (int i = 0; i < 8; i++) f[i] = (bf16_t)t[8 * c + i];
   return f;
 }
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-#define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
+template <int D>
+__device__ __forceinline__ void load_row_frags(bf16x8 (&f)[D / 16], const bf16_t* row, bool valid, int kg) {
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ks++) {
+    bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+    f[ks] = valid ? *reinterpret_cast<const bf16x8*>(row + ks * 16 + kg * 8) : z;
+  }
+}
 
 // ================================================================================ forward
 // grid (ceil(seq/128), nq, batch); wave w owns query rows i0 + 32w .. +31.
 template <int D>
-__global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(int seq, int nq, int nkv, const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(AB_THREADS) void attn_fwd_bf16_kernel(int seq, int nq, int nkv, const bf16_t* __restrict__ qkv,
                                                                    bf16_t* __restrict__ o, float* __restrict__ lse, int T,
                                                                    float scale_log2) {
   using TL = ATile<D>;
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[TL::ELEMS];
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[TL::ELEMS];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int l32 = lane & 31, kg = lane >> 5, s16 = lane & 15, h16 = (lane >> 4) & 1;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];  // K ring, then V ring
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int l32 = lane & 31, kg = lane >> 5;
   const int h = blockIdx.y, b = blockIdx.z, hk = h / (nq / nkv);
   const int ld = (nq + 2 * nkv) * D;
-  const int i0 = blockIdx.x * 128, iw = i0 + wave * 32, iq = iw + l32;  // positions within the sequence
+  const int i0 = (gridDim.x - 1 - blockIdx.x) * 128, iw = i0 + wave * 32, iq = iw + l32;  // positions in the sequence
   const size_t tok0 = (size_t)b * seq;
-  const bf16_t* kbase = qkv + tok0 * ld + (size_t)(nq + hk) * D;
-  const bf16_t* vbase = qkv + tok0 * ld + (size_t)(nq + nkv + hk) * D;
+  const char* kbase = reinterpret_cast<const char*>(qkv + tok0 * ld + (size_t)(nq + hk) * D);
+  const char* vbase = reinterpret_cast<const char*>(qkv + tok0 * ld + (size_t)(nq + nkv + hk) * D);
+  const size_t tstride = (size_t)AB_KT * ld * sizeof(bf16_t);
 
   bf16x8 qf[D / 16];
-#pragma unroll
-  for (int ks = 0; ks < D / 16; ks++) {
-    bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-    qf[ks] = iq < seq ? *reinterpret_cast<const bf16x8*>(qkv + (tok0 + iq) * ld + (size_t)h * D + ks * 16 + kg * 8) : z;
-  }
+  load_row_frags<D>(qf, qkv + (tok0 + min(iq, seq - 1)) * ld + (size_t)h * D, iq < seq, kg);
   f32x16 ot[D / 32];
 #pragma unroll
   for (int dt = 0; dt < D / 32; dt++)
@@ -111,74 +137,82 @@ __global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(int seq, i
     for (int r = 0; r < 16; r++) ot[dt][r] = 0.f;
   float m = -INFINITY, l = 0.f;
 
-  const int kend = min(seq, i0 + 128);  // keys needed by this block: [0, kend)
-  bf16x8 rk[TL::CHUNKS], rv[TL::CHUNKS];
-  afetch<D>(rk, kbase, ld, 0, seq);
-  afetch<D>(rv, vbase, ld, 0, seq);
-  astash<D>(rk, Ks);
-  astash<D>(rv, Vs);
-  __syncthreads();
-  for (int kb = 0; kb < kend; kb += AB_KT) {
-    const bool more = kb + AB_KT < kend;
-    if (more) {
-      afetch<D>(rk, kbase, ld, kb + AB_KT, seq);
-      afetch<D>(rv, vbase, ld, kb + AB_KT, seq);
+  FragAddr<D> fa;
+  fa.init(lane);
+  uint32_t voff[TL::IPW];
+  tile_voff<D>(voff, ld, wave, lane, AB_KT);
+  const uint32_t ldsK = lds_address(smem), ldsV = ldsK + AB_RING * TL::BYTES;
+  const int ntiles = (min(seq, i0 + 128) + AB_KT - 1) / AB_KT;  // keys needed by this block: [0, 64*ntiles)
+  auto issue = [&](int t) {
+    const int slot = t % AB_RING, valid = seq - t * AB_KT;
+    if (valid >= AB_KT) {
+      tile_dma<D>(kbase + t * tstride, voff, ldsK + slot * TL::BYTES, wave);
+      tile_dma<D>(vbase + t * tstride, voff, ldsV + slot * TL::BYTES, wave);
+    } else {
+      uint32_t vc[TL::IPW];
+      tile_voff<D>(vc, ld, wave, lane, valid);
+      tile_dma<D>(kbase + t * tstride, vc, ldsK + slot * TL::BYTES, wave);
+      tile_dma<D>(vbase + t * tstride, vc, ldsV + slot * TL::BYTES, wave);
     }
-    if (kb <= iw + 31) {  // some key of the tile is visible to some row of this wave
-      f32x16 st[2];
+  };
+  issue(0);
+  if (ntiles > 1) issue(1);
+  for (int t = 0; t < ntiles; t++) {
+    if (t + 1 < ntiles) dma_wait<2 * TL::IPW>(); else dma_wait<0>();
+    __syncthreads();  // tile t is visible; every wave is done with tile t-1, whose slot tile t+2 reuses
+    if (t + 2 < ntiles) issue(t + 2);
+    const int kb = t * AB_KT;
+    if (kb > iw + 31) continue;  // no key of the tile is visible to any row of this wave
+    const char* Ks = smem + (t % AB_RING) * TL::BYTES;
+    const char* Vs = Ks + AB_RING * TL::BYTES;
+    f32x16 st[2];
 #pragma unroll
-      for (int mt = 0; mt < 2; mt++) {
+    for (int mt = 0; mt < 2; mt++) {
 #pragma unroll
-        for (int r = 0; r < 16; r++) st[mt][r] = 0.f;
+      for (int r = 0; r < 16; r++) st[mt][r] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < D / 16; ks++) st[mt] = MFMA(frag_direct<D>(Ks, mt * 32 + l32, ks * 16 + kg * 8), qf[ks], st[mt]);
+      for (int ks = 0; ks < D / 16; ks++) st[mt] = MFMA(lds_frag(Ks, fa.kdir[ks] + mt * 32 * TL::LD * 2), qf[ks], st[mt]);
+    }
+    if (kb + AB_KT - 1 > iw) {  // the tile crosses the diagonal for this wave: mask keys above the row
+#pragma unroll
+      for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+        for (int r = 0; r < 16; r++)
+          if (kb + mt * 32 + 8 * (r >> 2) + 4 * kg + (r & 3) > iq) st[mt][r] = -INFINITY;
+    }
+    float mx = fmaxf(st[0][0], st[1][0]);
+#pragma unroll
+    for (int r = 1; r < 16; r++) mx = fmaxf(mx, fmaxf(st[0][r], st[1][r]));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float mn = fmaxf(m, mx * scale_log2);  // finite from the first tile on: key 0 is visible to every row
+    const float alpha = fast_exp2(m - mn);
+    float rs = 0.f;
+#pragma unroll
+    for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const float p = fast_exp2(fmaf(st[mt][r], scale_log2, -mn));
+        st[mt][r] = p;
+        rs += p;
       }
-      const bool diag = kb + AB_KT - 1 > iw;
-      float mx = -INFINITY;
-#pragma unroll
-      for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-        for (int r = 0; r < 16; r++) {
-          float s = st[mt][r] * scale_log2;
-          if (diag && kb + mt * 32 + 8 * (r >> 2) + 4 * kg + (r & 3) > iq) s = -INFINITY;
-          st[mt][r] = s;
-          mx = fmaxf(mx, s);
-        }
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float mn = fmaxf(m, mx);
-      const float alpha = exp2f(m - mn);
-      float rs = 0.f;
-#pragma unroll
-      for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-        for (int r = 0; r < 16; r++) {
-          float p = exp2f(st[mt][r] - mn);
-          st[mt][r] = p;
-          rs += p;
-        }
-      rs += __shfl_xor(rs, 32, 64);
-      l = l * alpha + rs;
-      m = mn;
+    rs += __shfl_xor(rs, 32, 64);
+    l = l * alpha + rs;
+    m = mn;
+    if (__any(alpha != 1.0f)) {
 #pragma unroll
       for (int dt = 0; dt < D / 32; dt++)
 #pragma unroll
         for (int r = 0; r < 16; r++) ot[dt][r] *= alpha;
-#pragma unroll
-      for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-        for (int c = 0; c < 2; c++) {
-          bf16x8 pf = pack_rows(st[mt], c);
-          const int ka = mt * 32 + 16 * c + 4 * kg;
-#pragma unroll
-          for (int dt = 0; dt < D / 32; dt++) ot[dt] = MFMA(frag_tr<D>(Vs, ka, ka + 8, dt * 32 + h16 * 16, s16), pf, ot[dt]);
-        }
     }
-    __syncthreads();
-    if (more) {
-      astash<D>(rk, Ks);
-      astash<D>(rv, Vs);
-    }
-    __syncthreads();
+#pragma unroll
+    for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+      for (int c = 0; c < 2; c++) {
+        const bf16x8 pf = pack_rows(st[mt], c);
+        const int ro = (mt * 32 + 16 * c) * TL::LD * 2;
+#pragma unroll
+        for (int dt = 0; dt < D / 32; dt++) ot[dt] = MFMA(lds_frag_tr(Vs, fa.tr0[dt] + ro, fa.tr1[dt] + ro), pf, ot[dt]);
+      }
   }
   if (iq < seq) {
     const float inv = 1.0f / l;
@@ -196,93 +230,131 @@ __global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(int seq, i
   }
 }
 
+// ================================================================================ backward prologue
+// delta[h,t] = sum_c dO[t,h,c]*O[t,h,c]; lse2[h,t] = lse[h,t]*log2(e).  One wave per (token, head).
+template <int D>
+__global__ __launch_bounds__(256) void attn_bwd_prep_kernel(int nq, const bf16_t* __restrict__ o, const bf16_t* __restrict__ dout,
+                                                            const float* __restrict__ lse, float* __restrict__ delta,
+                                                            float* __restrict__ lse2, int T) {
+  const int lane = threadIdx.x & 63;
+  const size_t pair = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // (token, head) index
+  if (pair >= (size_t)T * nq) return;
+  const size_t tok = pair / nq;
+  const int h = (int)(pair % nq);
+  const size_t base = tok * (size_t)nq * D + (size_t)h * D;
+  float s = 0.f;
+  if (D == 128) {
+    bf16x2 a = *reinterpret_cast<const bf16x2*>(o + base + lane * 2), c = *reinterpret_cast<const bf16x2*>(dout + base + lane * 2);
+    s = (float)a[0] * (float)c[0] + (float)a[1] * (float)c[1];
+  } else {
+    s = (float)o[base + lane] * (float)dout[base + lane];
+  }
+  s = wave_sum(s);
+  if (lane == 0) {
+    delta[(size_t)h * T + tok] = s;
+    lse2[(size_t)h * T + tok] = lse[(size_t)h * T + tok] * LOG2E;
+  }
+}
+
 // ================================================================================ backward: dQ
 // Same tiling as the forward kernel.  dQ^T = sum over key tiles of K^T dS^T, dS^T = P^T (dP^T - delta),
-// P^T = exp2(S^T*scale_log2 - lse*log2e), dP^T = V dO^T.
+// P^T = exp2(S^T*scale_log2 - lse2), dP^T = V dO^T.
 template <int D>
 __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(int seq, int nq, int nkv, const bf16_t* __restrict__ qkv,
                                                                       const bf16_t* __restrict__ dout,
-                                                                      const float* __restrict__ lse,
+                                                                      const float* __restrict__ lse2,
                                                                       const float* __restrict__ delta,
                                                                       bf16_t* __restrict__ dqkv, int T, float scale,
                                                                       float scale_log2) {
   using TL = ATile<D>;
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[TL::ELEMS];
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[TL::ELEMS];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int l32 = lane & 31, kg = lane >> 5, s16 = lane & 15, h16 = (lane >> 4) & 1;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];  // K ring, then V ring
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int l32 = lane & 31, kg = lane >> 5;
   const int h = blockIdx.y, b = blockIdx.z, hk = h / (nq / nkv);
   const int ld = (nq + 2 * nkv) * D;
-  const int i0 = blockIdx.x * 128, iw = i0 + wave * 32, iq = iw + l32;
+  const int i0 = (gridDim.x - 1 - blockIdx.x) * 128, iw = i0 + wave * 32, iq = iw + l32;
   const size_t tok0 = (size_t)b * seq;
-  const bf16_t* kbase = qkv + tok0 * ld + (size_t)(nq + hk) * D;
-  const bf16_t* vbase = qkv + tok0 * ld + (size_t)(nq + nkv + hk) * D;
+  const char* kbase = reinterpret_cast<const char*>(qkv + tok0 * ld + (size_t)(nq + hk) * D);
+  const char* vbase = reinterpret_cast<const char*>(qkv + tok0 * ld + (size_t)(nq + nkv + hk) * D);
+  const size_t tstride = (size_t)AB_KT * ld * sizeof(bf16_t);
 
   bf16x8 qf[D / 16], dof[D / 16];
-#pragma unroll
-  for (int ks = 0; ks < D / 16; ks++) {
-    bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-    qf[ks] = iq < seq ? *reinterpret_cast<const bf16x8*>(qkv + (tok0 + iq) * ld + (size_t)h * D + ks * 16 + kg * 8) : z;
-    dof[ks] = iq < seq ? *reinterpret_cast<const bf16x8*>(dout + (tok0 + iq) * (size_t)nq * D + (size_t)h * D + ks * 16 + kg * 8) : z;
-  }
-  const float lse2 = iq < seq ? lse[(size_t)h * T + tok0 + iq] * 1.4426950408889634f : 0.f;
-  const float dl = iq < seq ? delta[(size_t)h * T + tok0 + iq] : 0.f;
+  const int iqc = min(iq, seq - 1);
+  load_row_frags<D>(qf, qkv + (tok0 + iqc) * ld + (size_t)h * D, iq < seq, kg);
+  load_row_frags<D>(dof, dout + (tok0 + iqc) * (size_t)nq * D + (size_t)h * D, iq < seq, kg);
+  const float l2 = lse2[(size_t)h * T + tok0 + iqc];
+  const float dl = delta[(size_t)h * T + tok0 + iqc];
   f32x16 dqt[D / 32];
 #pragma unroll
   for (int dt = 0; dt < D / 32; dt++)
 #pragma unroll
     for (int r = 0; r < 16; r++) dqt[dt][r] = 0.f;
 
-  const int kend = min(seq, i0 + 128);
-  bf16x8 rk[TL::CHUNKS], rv[TL::CHUNKS];
-  afetch<D>(rk, kbase, ld, 0, seq);
-  afetch<D>(rv, vbase, ld, 0, seq);
-  astash<D>(rk, Ks);
-  astash<D>(rv, Vs);
-  __syncthreads();
-  for (int kb = 0; kb < kend; kb += AB_KT) {
-    const bool more = kb + AB_KT < kend;
-    if (more) {
-      afetch<D>(rk, kbase, ld, kb + AB_KT, seq);
-      afetch<D>(rv, vbase, ld, kb + AB_KT, seq);
+  FragAddr<D> fa;
+  fa.init(lane);
+  uint32_t voff[TL::IPW];
+  tile_voff<D>(voff, ld, wave, lane, AB_KT);
+  const uint32_t ldsK = lds_address(smem), ldsV = ldsK + AB_RING * TL::BYTES;
+  const int ntiles = (min(seq, i0 + 128) + AB_KT - 1) / AB_KT;
+  auto issue = [&](int t) {
+    const int slot = t % AB_RING, valid = seq - t * AB_KT;
+    if (valid >= AB_KT) {
+      tile_dma<D>(kbase + t * tstride, voff, ldsK + slot * TL::BYTES, wave);
+      tile_dma<D>(vbase + t * tstride, voff, ldsV + slot * TL::BYTES, wave);
+    } else {
+      uint32_t vc[TL::IPW];
+      tile_voff<D>(vc, ld, wave, lane, valid);
+      tile_dma<D>(kbase + t * tstride, vc, ldsK + slot * TL::BYTES, wave);
+      tile_dma<D>(vbase + t * tstride, vc, ldsV + slot * TL::BYTES, wave);
     }
-    if (kb <= iw + 31) {
-      f32x16 st[2], dp[2];
+  };
+  issue(0);
+  if (ntiles > 1) issue(1);
+  for (int t = 0; t < ntiles; t++) {
+    if (t + 1 < ntiles) dma_wait<2 * TL::IPW>(); else dma_wait<0>();
+    __syncthreads();
+    if (t + 2 < ntiles) issue(t + 2);
+    const int kb = t * AB_KT;
+    if (kb > iw + 31) continue;
+    const char* Ks = smem + (t % AB_RING) * TL::BYTES;
+    const char* Vs = Ks + AB_RING * TL::BYTES;
+    f32x16 st[2], dp[2];
 #pragma unroll
-      for (int mt = 0; mt < 2; mt++) {
+    for (int mt = 0; mt < 2; mt++) {
 #pragma unroll
-        for (int r = 0; r < 16; r++) { st[mt][r] = 0.f; dp[mt][r] = 0.f; }
+      for (int r = 0; r < 16; r++) { st[mt][r] = 0.f; dp[mt][r] = 0.f; }
 #pragma unroll
-        for (int ks = 0; ks < D / 16; ks++) {
-          st[mt] = MFMA(frag_direct<D>(Ks, mt * 32 + l32, ks * 16 + kg * 8), qf[ks], st[mt]);
-          dp[mt] = MFMA(frag_direct<D>(Vs, mt * 32 + l32, ks * 16 + kg * 8), dof[ks], dp[mt]);
-        }
+      for (int ks = 0; ks < D / 16; ks++) st[mt] = MFMA(lds_frag(Ks, fa.kdir[ks] + mt * 32 * TL::LD * 2), qf[ks], st[mt]);
+    }
+#pragma unroll
+    for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+      for (int ks = 0; ks < D / 16; ks++) dp[mt] = MFMA(lds_frag(Vs, fa.kdir[ks] + mt * 32 * TL::LD * 2), dof[ks], dp[mt]);
+    // P^T from S^T while the dP^T products are still in the matrix pipeline
+#pragma unroll
+    for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) st[mt][r] = fast_exp2(fmaf(st[mt][r], scale_log2, -l2));
+    if (kb + AB_KT - 1 > iw) {
+#pragma unroll
+      for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+        for (int r = 0; r < 16; r++)
+          if (kb + mt * 32 + 8 * (r >> 2) + 4 * kg + (r & 3) > iq) st[mt][r] = 0.f;
+    }
+#pragma unroll
+    for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) st[mt][r] *= dp[mt][r] - dl;
+#pragma unroll
+    for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+      for (int c = 0; c < 2; c++) {
+        const bf16x8 df = pack_rows(st[mt], c);
+        const int ro = (mt * 32 + 16 * c) * TL::LD * 2;
+#pragma unroll
+        for (int dt = 0; dt < D / 32; dt++) dqt[dt] = MFMA(lds_frag_tr(Ks, fa.tr0[dt] + ro, fa.tr1[dt] + ro), df, dqt[dt]);
       }
-      const bool diag = kb + AB_KT - 1 > iw;
-#pragma unroll
-      for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-        for (int r = 0; r < 16; r++) {
-          float p = exp2f(st[mt][r] * scale_log2 - lse2);
-          if (diag && kb + mt * 32 + 8 * (r >> 2) + 4 * kg + (r & 3) > iq) p = 0.f;
-          st[mt][r] = p * (dp[mt][r] - dl);
-        }
-#pragma unroll
-      for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-        for (int c = 0; c < 2; c++) {
-          bf16x8 df = pack_rows(st[mt], c);
-          const int ka = mt * 32 + 16 * c + 4 * kg;
-#pragma unroll
-          for (int dt = 0; dt < D / 32; dt++) dqt[dt] = MFMA(frag_tr<D>(Ks, ka, ka + 8, dt * 32 + h16 * 16, s16), df, dqt[dt]);
-        }
-    }
-    __syncthreads();
-    if (more) {
-      astash<D>(rk, Ks);
-      astash<D>(rv, Vs);
-    }
-    __syncthreads();
   }
   if (iq < seq) {
     bf16_t* row = dqkv + (tok0 + iq) * ld + (size_t)h * D;
@@ -307,98 +379,136 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(int seq, i
 template <int D>
 __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, int nq, int nkv, const bf16_t* __restrict__ qkv,
                                                                        const bf16_t* __restrict__ dout,
-                                                                       const float* __restrict__ lse,
+                                                                       const float* __restrict__ lse2,
                                                                        const float* __restrict__ delta,
                                                                        bf16_t* __restrict__ dqkv, float* __restrict__ part,
                                                                        int T, float scale, float scale_log2) {
   using TL = ATile<D>;
-  __shared__ __attribute__((aligned(16))) bf16_t Qs[TL::ELEMS];
-  __shared__ __attribute__((aligned(16))) bf16_t Os[TL::ELEMS];
-  __shared__ float lse_s[AB_KT], del_s[AB_KT];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int l32 = lane & 31, kg = lane >> 5, s16 = lane & 15, h16 = (lane >> 4) & 1;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];  // Q ring, dO ring, lse2 ring, delta ring
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int l32 = lane & 31, kg = lane >> 5;
   const int hq = blockIdx.y, b = blockIdx.z, grp = nq / nkv, hk = hq / grp;
-  const int ld = (nq + 2 * nkv) * D;
-  const int j0 = blockIdx.x * 128, jw = j0 + wave * 32, jk = jw + l32;  // key positions within the sequence
+  const int ld = (nq + 2 * nkv) * D, ldo = nq * D;
+  const int j0 = blockIdx.x * 128, jw = j0 + wave * 32, jk = jw + l32;  // key positions in the sequence (block 0 is the heaviest)
   const size_t tok0 = (size_t)b * seq;
+  const char* qbase = reinterpret_cast<const char*>(qkv + tok0 * ld + (size_t)hq * D);
+  const char* obase = reinterpret_cast<const char*>(dout + tok0 * ldo + (size_t)hq * D);
+  const float* lrow = lse2 + (size_t)hq * T + tok0;
+  const float* drow = delta + (size_t)hq * T + tok0;
+  float* lse_s = reinterpret_cast<float*>(smem + 2 * AB_RING * TL::BYTES);
+  float* del_s = lse_s + AB_RING * AB_KT;
 
   bf16x8 kf[D / 16], vf[D / 16];
-#pragma unroll
-  for (int ks = 0; ks < D / 16; ks++) {
-    bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-    kf[ks] = jk < seq ? *reinterpret_cast<const bf16x8*>(qkv + (tok0 + jk) * ld + (size_t)(nq + hk) * D + ks * 16 + kg * 8) : z;
-    vf[ks] = jk < seq ? *reinterpret_cast<const bf16x8*>(qkv + (tok0 + jk) * ld + (size_t)(nq + nkv + hk) * D + ks * 16 + kg * 8) : z;
-  }
+  const int jkc = min(jk, seq - 1);
+  load_row_frags<D>(kf, qkv + (tok0 + jkc) * ld + (size_t)(nq + hk) * D, jk < seq, kg);
+  load_row_frags<D>(vf, qkv + (tok0 + jkc) * ld + (size_t)(nq + nkv + hk) * D, jk < seq, kg);
   f32x16 dkt[D / 32], dvt[D / 32];
 #pragma unroll
   for (int dt = 0; dt < D / 32; dt++)
 #pragma unroll
     for (int r = 0; r < 16; r++) { dkt[dt][r] = 0.f; dvt[dt][r] = 0.f; }
 
-  const int qstart = j0 / AB_KT * AB_KT;
-  const int total = (seq - qstart + AB_KT - 1) / AB_KT;  // query tiles
-  bf16x8 rq[TL::CHUNKS], ro[TL::CHUNKS];
-  float rl = 0.f, rd = 0.f;
-  auto fetch = [&](int it) {
-    int qb = qstart + it * AB_KT;
-    afetch<D>(rq, qkv + tok0 * ld + (size_t)hq * D, ld, qb, seq);
-    afetch<D>(ro, dout + tok0 * (size_t)nq * D + (size_t)hq * D, nq * D, qb, seq);
-    if (threadIdx.x < AB_KT) {
-      int qi = qb + threadIdx.x;
-      rl = qi < seq ? lse[(size_t)hq * T + tok0 + qi] * 1.4426950408889634f : 0.f;
-      rd = qi < seq ? delta[(size_t)hq * T + tok0 + qi] : 0.f;
+  FragAddr<D> fa;
+  fa.init(lane);
+  uint32_t vq[TL::IPW], vo[TL::IPW];
+  tile_voff<D>(vq, ld, wave, lane, AB_KT);
+  tile_voff<D>(vo, ldo, wave, lane, AB_KT);
+  const uint32_t ldsQ = lds_address(smem), ldsO = ldsQ + AB_RING * TL::BYTES;
+  const int ntiles = (seq - j0 + AB_KT - 1) / AB_KT;  // query tiles j0, j0+64, ...
+  const size_t qstride = (size_t)AB_KT * ld * sizeof(bf16_t), ostride = (size_t)AB_KT * ldo * sizeof(bf16_t);
+  auto issue = [&](int t) {
+    const int slot = t % AB_RING, row0 = j0 + t * AB_KT, valid = seq - row0;
+    const char* qp = qbase + (size_t)j0 * ld * sizeof(bf16_t) + t * qstride;
+    const char* op = obase + (size_t)j0 * ldo * sizeof(bf16_t) + t * ostride;
+    if (valid >= AB_KT) {
+      tile_dma<D>(qp, vq, ldsQ + slot * TL::BYTES, wave);
+      tile_dma<D>(op, vo, ldsO + slot * TL::BYTES, wave);
+    } else {
+      uint32_t vc[TL::IPW];
+      tile_voff<D>(vc, ld, wave, lane, valid);
+      tile_dma<D>(qp, vc, ldsQ + slot * TL::BYTES, wave);
+      tile_voff<D>(vc, ldo, wave, lane, valid);
+      tile_dma<D>(op, vc, ldsO + slot * TL::BYTES, wave);
     }
   };
-  auto stash = [&]() {
-    astash<D>(rq, Qs);
-    astash<D>(ro, Os);
-    if (threadIdx.x < AB_KT) { lse_s[threadIdx.x] = rl; del_s[threadIdx.x] = rd; }
+  // per-row statistics of a tile (64 floats each): even waves transfer lse2, odd waves delta (waves 2 and 3
+  // repeat what waves 0 and 1 transfer, which keeps the transfer count of all waves equal)
+  const uint32_t ldsS = ldsQ + 2 * AB_RING * TL::BYTES + (wave & 1) * AB_RING * AB_KT * sizeof(float);
+  const float* srow = (wave & 1) ? drow : lrow;
+  auto issue_stat = [&](int t) {
+    const int row0 = j0 + t * AB_KT;
+    dma4_base(srow + row0, (uint32_t)((min(row0 + lane, seq - 1) - row0) * sizeof(float)),
+              ldsS + (t % AB_RING) * AB_KT * sizeof(float));
   };
-  if (total > 0) { fetch(0); stash(); }
-  __syncthreads();
-  for (int it = 0; it < total; it++) {
-    const int qb = qstart + it * AB_KT;
-    const bool more = it + 1 < total;
-    if (more) fetch(it + 1);
-    if (qb + AB_KT - 1 >= jw) {  // some query of the tile sees some key of this wave
-      f32x16 st[2], dp[2];
+  issue(0);
+  issue_stat(0);
+  if (ntiles > 1) { issue(1); issue_stat(1); }
+  for (int t = 0; t < ntiles; t++) {
+    if (t + 1 < ntiles) dma_wait<2 * TL::IPW + 1>(); else dma_wait<0>();
+    __syncthreads();
+    if (t + 2 < ntiles) { issue(t + 2); issue_stat(t + 2); }
+    const int qb = j0 + t * AB_KT;
+    if (qb + AB_KT - 1 < jw) continue;  // every query of the tile precedes every key of this wave
+    const char* Qs = smem + (t % AB_RING) * TL::BYTES;
+    const char* Os = Qs + AB_RING * TL::BYTES;
+    const float* ls = lse_s + (t % AB_RING) * AB_KT;
+    const float* ds = del_s + (t % AB_RING) * AB_KT;
+    f32x16 st[2], dp[2];
 #pragma unroll
-      for (int mt = 0; mt < 2; mt++) {
+    for (int mt = 0; mt < 2; mt++) {
 #pragma unroll
-        for (int r = 0; r < 16; r++) { st[mt][r] = 0.f; dp[mt][r] = 0.f; }
+      for (int r = 0; r < 16; r++) { st[mt][r] = 0.f; dp[mt][r] = 0.f; }
 #pragma unroll
-        for (int ks = 0; ks < D / 16; ks++) {
-          st[mt] = MFMA(frag_direct<D>(Qs, mt * 32 + l32, ks * 16 + kg * 8), kf[ks], st[mt]);
-          dp[mt] = MFMA(frag_direct<D>(Os, mt * 32 + l32, ks * 16 + kg * 8), vf[ks], dp[mt]);
-        }
+      for (int ks = 0; ks < D / 16; ks++) st[mt] = MFMA(lds_frag(Qs, fa.kdir[ks] + mt * 32 * TL::LD * 2), kf[ks], st[mt]);
+    }
+#pragma unroll
+    for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+      for (int ks = 0; ks < D / 16; ks++) dp[mt] = MFMA(lds_frag(Os, fa.kdir[ks] + mt * 32 * TL::LD * 2), vf[ks], dp[mt]);
+    // P from S (rows 8*q4 + 4*kg + e of each 32-row half) while dP is in the matrix pipeline
+#pragma unroll
+    for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; q4++) {
+        const f32x4 lv = *reinterpret_cast<const f32x4*>(ls + mt * 32 + 8 * q4 + 4 * kg);
+#pragma unroll
+        for (int e = 0; e < 4; e++) st[mt][4 * q4 + e] = fast_exp2(fmaf(st[mt][4 * q4 + e], scale_log2, -lv[e]));
       }
+    if (qb < jw + 32 || qb + AB_KT > seq) {  // diagonal tile, or rows past the end of the sequence
 #pragma unroll
       for (int mt = 0; mt < 2; mt++)
 #pragma unroll
         for (int r = 0; r < 16; r++) {
-          const int qr = mt * 32 + 8 * (r >> 2) + 4 * kg + (r & 3);  // row within the tile
-          const int qi = qb + qr;
-          float p = exp2f(st[mt][r] * scale_log2 - lse_s[qr]);
-          if (qi < jk || qi >= seq) p = 0.f;
-          dp[mt][r] = p * (dp[mt][r] - del_s[qr]);
-          st[mt][r] = p;
-        }
-#pragma unroll
-      for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-        for (int c = 0; c < 2; c++) {
-          bf16x8 pf = pack_rows(st[mt], c), df = pack_rows(dp[mt], c);
-          const int ka = mt * 32 + 16 * c + 4 * kg;
-#pragma unroll
-          for (int dt = 0; dt < D / 32; dt++) {
-            dvt[dt] = MFMA(frag_tr<D>(Os, ka, ka + 8, dt * 32 + h16 * 16, s16), pf, dvt[dt]);
-            dkt[dt] = MFMA(frag_tr<D>(Qs, ka, ka + 8, dt * 32 + h16 * 16, s16), df, dkt[dt]);
-          }
+          const int qi = qb + mt * 32 + 8 * (r >> 2) + 4 * kg + (r & 3);
+          if (qi < jk || qi >= seq) st[mt][r] = 0.f;
         }
     }
-    __syncthreads();
-    if (more) stash();
-    __syncthreads();
+#pragma unroll
+    for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+      for (int c = 0; c < 2; c++) {
+        const bf16x8 pf = pack_rows(st[mt], c);
+        const int ro = (mt * 32 + 16 * c) * TL::LD * 2;
+#pragma unroll
+        for (int dt = 0; dt < D / 32; dt++) dvt[dt] = MFMA(lds_frag_tr(Os, fa.tr0[dt] + ro, fa.tr1[dt] + ro), pf, dvt[dt]);
+      }
+#pragma unroll
+    for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; q4++) {
+        const f32x4 dv4 = *reinterpret_cast<const f32x4*>(ds + mt * 32 + 8 * q4 + 4 * kg);
+#pragma unroll
+        for (int e = 0; e < 4; e++) st[mt][4 * q4 + e] *= dp[mt][4 * q4 + e] - dv4[e];
+      }
+#pragma unroll
+    for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+      for (int c = 0; c < 2; c++) {
+        const bf16x8 df = pack_rows(st[mt], c);
+        const int ro = (mt * 32 + 16 * c) * TL::LD * 2;
+#pragma unroll
+        for (int dt = 0; dt < D / 32; dt++) dkt[dt] = MFMA(lds_frag_tr(Qs, fa.tr0[dt] + ro, fa.tr1[dt] + ro), df, dkt[dt]);
+      }
   }
   if (jk < seq && part != nullptr) {
     float* prow = part + ((size_t)hq * T + tok0 + jk) * (2 * D);  // hq = hk*grp + head-in-group
@@ -451,47 +561,76 @@ __global__ void attn_bwd_group_reduce_kernel(const float* __restrict__ part, bf1
 }
 
 // ------------------------------------------------------------------------------------ host side
-int dh_launch_attn_delta_bf16(int T, int nq, int d, const bf16_t* o, const bf16_t* dout, float* delta, hipStream_t stream);
+template <typename K>
+static int set_lds(K kernel, size_t bytes) {
+  DH_HIP(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+  return DH_OK;
+}
 
 int dh_launch_attn_fwd_bf16(int batch, int seq, int nq, int nkv, int d, const bf16_t* qkv, bf16_t* o, float* lse,
                             hipStream_t stream) {
   if (d != 64 && d != 128) DH_FAIL(DH_ERR_SHAPE, "attention (bf16): head_dim %d must be 64 or 128", d);
   if (batch * seq == 0) return DH_OK;
   dim3 grid((seq + 127) / 128, nq, batch);
-  float sl2 = (float)(1.4426950408889634 / sqrt((double)d));
-  if (d == 128) attn_fwd_bf16_kernel<128><<<grid, AB_THREADS, 0, stream>>>(seq, nq, nkv, qkv, o, lse, batch * seq, sl2);
-  else attn_fwd_bf16_kernel<64><<<grid, AB_THREADS, 0, stream>>>(seq, nq, nkv, qkv, o, lse, batch * seq, sl2);
+  const float sl2 = (float)(1.4426950408889634 / sqrt((double)d));
+  const size_t lds = 2 * AB_RING * (size_t)AB_KT * d * 2;
+  static bool ready[2] = {false, false};
+  int rc;
+  if (d == 128) {
+    if (!ready[0]) { if ((rc = set_lds(attn_fwd_bf16_kernel<128>, lds))) return rc; ready[0] = true; }
+    attn_fwd_bf16_kernel<128><<<grid, AB_THREADS, lds, stream>>>(seq, nq, nkv, qkv, o, lse, batch * seq, sl2);
+  } else {
+    if (!ready[1]) { if ((rc = set_lds(attn_fwd_bf16_kernel<64>, lds))) return rc; ready[1] = true; }
+    attn_fwd_bf16_kernel<64><<<grid, AB_THREADS, lds, stream>>>(seq, nq, nkv, qkv, o, lse, batch * seq, sl2);
+  }
   DH_LAUNCH_CHECK();
   return DH_OK;
 }
 
+// workspace: lse2[nq*T] floats, then (nq > nkv) the per-head dK/dV partials [nq][T][2d] floats
 size_t dh_attn_bwd_bf16_ws_bytes(int batch, int seq, int nq, int nkv, int d) {
-  return nq > nkv ? (size_t)nq * batch * seq * 2 * d * sizeof(float) : 0;
+  const size_t T = (size_t)batch * seq;
+  return dh_align_up(nq * T * sizeof(float), 256) + (nq > nkv ? (size_t)nq * T * 2 * d * sizeof(float) : 0);
 }
 
 int dh_launch_attn_bwd_bf16(int batch, int seq, int nq, int nkv, int d, const bf16_t* qkv, const bf16_t* o,
                             const bf16_t* dout, const float* lse, bf16_t* dqkv, float* delta, void* ws, size_t ws_bytes,
                             hipStream_t stream) {
   if (d != 64 && d != 128) DH_FAIL(DH_ERR_SHAPE, "attention (bf16): head_dim %d must be 64 or 128", d);
-  int T = batch * seq;
+  const int T = batch * seq;
   if (T == 0) return DH_OK;
-  size_t need = dh_attn_bwd_bf16_ws_bytes(batch, seq, nq, nkv, d);
-  if (need > 0 && (!ws || ws_bytes < need)) DH_FAIL(DH_ERR_WORKSPACE_TOO_SMALL, "attn_bwd: workspace %zu < %zu bytes", ws_bytes, need);
-  float* part = need > 0 ? (float*)ws : nullptr;
-  int rc = dh_launch_attn_delta_bf16(T, nq, d, o, dout, delta, stream);
-  if (rc != DH_OK) return rc;
-  float sc = (float)(1.0 / sqrt((double)d)), sl2 = (float)(1.4426950408889634 / sqrt((double)d));
-  dim3 gq((seq + 127) / 128, nq, batch), gk((seq + 127) / 128, nq, batch);
+  const size_t need = dh_attn_bwd_bf16_ws_bytes(batch, seq, nq, nkv, d);
+  if (!ws || ws_bytes < need) DH_FAIL(DH_ERR_WORKSPACE_TOO_SMALL, "attn_bwd: workspace %zu < %zu bytes", ws_bytes, need);
+  float* lse2 = (float*)ws;
+  float* part = nq > nkv ? (float*)((char*)ws + dh_align_up((size_t)nq * T * sizeof(float), 256)) : nullptr;
+  const float sc = (float)(1.0 / sqrt((double)d)), sl2 = (float)(1.4426950408889634 / sqrt((double)d));
+  dim3 gq((seq + 127) / 128, nq, batch);
+  const unsigned nprep = (unsigned)(((size_t)T * nq + 3) / 4);
   const unsigned nred = (unsigned)(((size_t)T * nkv * (2 * d / 4) + 255) / 256);
+  const size_t lds_dq = 2 * AB_RING * (size_t)AB_KT * d * 2, lds_dkv = lds_dq + 2 * AB_RING * AB_KT * sizeof(float);
+  static bool ready[2] = {false, false};
+  int rc;
   if (d == 128) {
-    attn_bwd_dq_bf16_kernel<128><<<gq, AB_THREADS, 0, stream>>>(seq, nq, nkv, qkv, dout, lse, delta, dqkv, T, sc, sl2);
+    if (!ready[0]) {
+      if ((rc = set_lds(attn_bwd_dq_bf16_kernel<128>, lds_dq)) || (rc = set_lds(attn_bwd_dkv_bf16_kernel<128>, lds_dkv))) return rc;
+      ready[0] = true;
+    }
+    attn_bwd_prep_kernel<128><<<nprep, 256, 0, stream>>>(nq, o, dout, lse, delta, lse2, T);
     DH_LAUNCH_CHECK();
-    attn_bwd_dkv_bf16_kernel<128><<<gk, AB_THREADS, 0, stream>>>(seq, nq, nkv, qkv, dout, lse, delta, dqkv, part, T, sc, sl2);
+    attn_bwd_dq_bf16_kernel<128><<<gq, AB_THREADS, lds_dq, stream>>>(seq, nq, nkv, qkv, dout, lse2, delta, dqkv, T, sc, sl2);
+    DH_LAUNCH_CHECK();
+    attn_bwd_dkv_bf16_kernel<128><<<gq, AB_THREADS, lds_dkv, stream>>>(seq, nq, nkv, qkv, dout, lse2, delta, dqkv, part, T, sc, sl2);
     if (part) { DH_LAUNCH_CHECK(); attn_bwd_group_reduce_kernel<128><<<nred, 256, 0, stream>>>(part, dqkv, T, nq, nkv); }
   } else {
-    attn_bwd_dq_bf16_kernel<64><<<gq, AB_THREADS, 0, stream>>>(seq, nq, nkv, qkv, dout, lse, delta, dqkv, T, sc, sl2);
+    if (!ready[1]) {
+      if ((rc = set_lds(attn_bwd_dq_bf16_kernel<64>, lds_dq)) || (rc = set_lds(attn_bwd_dkv_bf16_kernel<64>, lds_dkv))) return rc;
+      ready[1] = true;
+    }
+    attn_bwd_prep_kernel<64><<<nprep, 256, 0, stream>>>(nq, o, dout, lse, delta, lse2, T);
     DH_LAUNCH_CHECK();
-    attn_bwd_dkv_bf16_kernel<64><<<gk, AB_THREADS, 0, stream>>>(seq, nq, nkv, qkv, dout, lse, delta, dqkv, part, T, sc, sl2);
+    attn_bwd_dq_bf16_kernel<64><<<gq, AB_THREADS, lds_dq, stream>>>(seq, nq, nkv, qkv, dout, lse2, delta, dqkv, T, sc, sl2);
+    DH_LAUNCH_CHECK();
+    attn_bwd_dkv_bf16_kernel<64><<<gq, AB_THREADS, lds_dkv, stream>>>(seq, nq, nkv, qkv, dout, lse2, delta, dqkv, part, T, sc, sl2);
     if (part) { DH_LAUNCH_CHECK(); attn_bwd_group_reduce_kernel<64><<<nred, 256, 0, stream>>>(part, dqkv, T, nq, nkv); }
   }
   DH_LAUNCH_CHECK();
