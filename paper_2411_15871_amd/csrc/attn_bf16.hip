@@ -84,14 +84,31 @@ struct FragAddr {
     }
   }
 };
-__device__ __forceinline__ bf16x8 lds_frag(const char* tile, int byte_off) {
-  return *reinterpret_cast<const bf16x8*>(tile + byte_off);
+// Fragment reads take a per-lane pointer (tile base + precomputed lane offset) and a compile-time
+// constant byte offset, which the compiler folds into the offset field of the LDS instruction.
+typedef __attribute__((address_space(3))) char lds_char;
+typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
+__device__ __forceinline__ bf16x8 lds_frag(const lds_char* lane_ptr, int const_off) {
+  return *reinterpret_cast<const lds_bf16x8*>(lane_ptr + const_off);
 }
-__device__ __forceinline__ bf16x8 lds_frag_tr(const char* tile, int off0, int off1) {
-  s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(__attribute__((address_space(3))) void*)(tile + off0));
-  s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(__attribute__((address_space(3))) void*)(tile + off1));
+__device__ __forceinline__ bf16x8 lds_frag_tr(const lds_char* lane_ptr0, const lds_char* lane_ptr1, int const_off) {
+  s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(lane_ptr0 + const_off));
+  s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(lane_ptr1 + const_off));
   return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7));
 }
+// Per-tile lane pointers for one LDS tile.
+template <int D>
+struct TilePtrs {
+  const lds_char* dir[D / 16];
+  const lds_char* t0[D / 32];
+  const lds_char* t1[D / 32];
+  __device__ __forceinline__ void set(const lds_char* tile, const FragAddr<D>& fa) {
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ks++) dir[ks] = tile + fa.kdir[ks];
+#pragma unroll
+    for (int dt = 0; dt < D / 32; dt++) { t0[dt] = tile + fa.tr0[dt]; t1[dt] = tile + fa.tr1[dt]; }
+  }
+};
 // Registers 8c..8c+7 of a 32x32 result tile as a bf16 B fragment (k-slots = rows 16c+4g+{0..3}, 16c+8+4g+{0..3}).
 __device__ __forceinline__ bf16x8 pack_rows(const f32x16& t, int c) {
   bf16x8 f;
@@ -110,14 +127,25 @@ __device__ __forceinline__ void load_row_frags(bf16x8 (&f)[D / 16], const bf16_t
   }
 }
 
+// Makes the compiler wait here for the global loads that produced the fragments: their first use would
+// otherwise be inside the tile loop, and the wait it would place there (a vmcnt count that knows nothing
+// of the asynchronous tile transfers) would drain the transfer ring on every step.
+template <int N>
+__device__ __forceinline__ void pin_frags(const bf16x8 (&f)[N]) {
+#pragma unroll
+  for (int i = 0; i < N; i++) asm volatile("" ::"v"(f[i]));
+}
+__device__ __forceinline__ void pin_scalar(float v) { asm volatile("" ::"v"(v)); }
+
 // ================================================================================ forward
 // grid (ceil(seq/128), nq, batch); wave w owns query rows i0 + 32w .. +31.
 template <int D>
-__global__ __launch_bounds__(AB_THREADS) void attn_fwd_bf16_kernel(int seq, int nq, int nkv, const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(int seq, int nq, int nkv, const bf16_t* __restrict__ qkv,
                                                                    bf16_t* __restrict__ o, float* __restrict__ lse, int T,
                                                                    float scale_log2) {
   using TL = ATile<D>;
   extern __shared__ __attribute__((aligned(1024))) char smem[];  // K ring, then V ring
+  const lds_char* sm = (const lds_char*)smem;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l32 = lane & 31, kg = lane >> 5;
   const int h = blockIdx.y, b = blockIdx.z, hk = h / (nq / nkv);
@@ -155,23 +183,26 @@ __global__ __launch_bounds__(AB_THREADS) void attn_fwd_bf16_kernel(int seq, int 
       tile_dma<D>(vbase + t * tstride, vc, ldsV + slot * TL::BYTES, wave);
     }
   };
+  pin_frags(qf);
   issue(0);
   if (ntiles > 1) issue(1);
-  for (int t = 0; t < ntiles; t++) {
+  int slot = 0;
+  for (int t = 0; t < ntiles; t++, slot = slot == AB_RING - 1 ? 0 : slot + 1) {
     if (t + 1 < ntiles) dma_wait<2 * TL::IPW>(); else dma_wait<0>();
     __syncthreads();  // tile t is visible; every wave is done with tile t-1, whose slot tile t+2 reuses
     if (t + 2 < ntiles) issue(t + 2);
     const int kb = t * AB_KT;
     if (kb > iw + 31) continue;  // no key of the tile is visible to any row of this wave
-    const char* Ks = smem + (t % AB_RING) * TL::BYTES;
-    const char* Vs = Ks + AB_RING * TL::BYTES;
+    TilePtrs<D> Kp, Vp;
+    Kp.set(sm + slot * TL::BYTES, fa);
+    Vp.set(sm + (AB_RING + slot) * TL::BYTES, fa);
     f32x16 st[2];
 #pragma unroll
     for (int mt = 0; mt < 2; mt++) {
 #pragma unroll
       for (int r = 0; r < 16; r++) st[mt][r] = 0.f;
 #pragma unroll
-      for (int ks = 0; ks < D / 16; ks++) st[mt] = MFMA(lds_frag(Ks, fa.kdir[ks] + mt * 32 * TL::LD * 2), qf[ks], st[mt]);
+      for (int ks = 0; ks < D / 16; ks++) st[mt] = MFMA(lds_frag(Kp.dir[ks], mt * 32 * TL::LD * 2), qf[ks], st[mt]);
     }
     if (kb + AB_KT - 1 > iw) {  // the tile crosses the diagonal for this wave: mask keys above the row
 #pragma unroll
@@ -211,7 +242,7 @@ __global__ __launch_bounds__(AB_THREADS) void attn_fwd_bf16_kernel(int seq, int 
         const bf16x8 pf = pack_rows(st[mt], c);
         const int ro = (mt * 32 + 16 * c) * TL::LD * 2;
 #pragma unroll
-        for (int dt = 0; dt < D / 32; dt++) ot[dt] = MFMA(lds_frag_tr(Vs, fa.tr0[dt] + ro, fa.tr1[dt] + ro), pf, ot[dt]);
+        for (int dt = 0; dt < D / 32; dt++) ot[dt] = MFMA(lds_frag_tr(Vp.t0[dt], Vp.t1[dt], ro), pf, ot[dt]);
       }
   }
   if (iq < seq) {
@@ -268,6 +299,7 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(int seq, i
                                                                       float scale_log2) {
   using TL = ATile<D>;
   extern __shared__ __attribute__((aligned(1024))) char smem[];  // K ring, then V ring
+  const lds_char* sm = (const lds_char*)smem;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l32 = lane & 31, kg = lane >> 5;
   const int h = blockIdx.y, b = blockIdx.z, hk = h / (nq / nkv);
@@ -308,28 +340,34 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(int seq, i
       tile_dma<D>(vbase + t * tstride, vc, ldsV + slot * TL::BYTES, wave);
     }
   };
+  pin_frags(qf);
+  pin_frags(dof);
+  pin_scalar(l2);
+  pin_scalar(dl);
   issue(0);
   if (ntiles > 1) issue(1);
-  for (int t = 0; t < ntiles; t++) {
+  int slot = 0;
+  for (int t = 0; t < ntiles; t++, slot = slot == AB_RING - 1 ? 0 : slot + 1) {
     if (t + 1 < ntiles) dma_wait<2 * TL::IPW>(); else dma_wait<0>();
     __syncthreads();
     if (t + 2 < ntiles) issue(t + 2);
     const int kb = t * AB_KT;
     if (kb > iw + 31) continue;
-    const char* Ks = smem + (t % AB_RING) * TL::BYTES;
-    const char* Vs = Ks + AB_RING * TL::BYTES;
+    TilePtrs<D> Kp, Vp;
+    Kp.set(sm + slot * TL::BYTES, fa);
+    Vp.set(sm + (AB_RING + slot) * TL::BYTES, fa);
     f32x16 st[2], dp[2];
 #pragma unroll
     for (int mt = 0; mt < 2; mt++) {
 #pragma unroll
       for (int r = 0; r < 16; r++) { st[mt][r] = 0.f; dp[mt][r] = 0.f; }
 #pragma unroll
-      for (int ks = 0; ks < D / 16; ks++) st[mt] = MFMA(lds_frag(Ks, fa.kdir[ks] + mt * 32 * TL::LD * 2), qf[ks], st[mt]);
+      for (int ks = 0; ks < D / 16; ks++) st[mt] = MFMA(lds_frag(Kp.dir[ks], mt * 32 * TL::LD * 2), qf[ks], st[mt]);
     }
 #pragma unroll
     for (int mt = 0; mt < 2; mt++)
 #pragma unroll
-      for (int ks = 0; ks < D / 16; ks++) dp[mt] = MFMA(lds_frag(Vs, fa.kdir[ks] + mt * 32 * TL::LD * 2), dof[ks], dp[mt]);
+      for (int ks = 0; ks < D / 16; ks++) dp[mt] = MFMA(lds_frag(Vp.dir[ks], mt * 32 * TL::LD * 2), dof[ks], dp[mt]);
     // P^T from S^T while the dP^T products are still in the matrix pipeline
 #pragma unroll
     for (int mt = 0; mt < 2; mt++)
@@ -353,7 +391,7 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(int seq, i
         const bf16x8 df = pack_rows(st[mt], c);
         const int ro = (mt * 32 + 16 * c) * TL::LD * 2;
 #pragma unroll
-        for (int dt = 0; dt < D / 32; dt++) dqt[dt] = MFMA(lds_frag_tr(Ks, fa.tr0[dt] + ro, fa.tr1[dt] + ro), df, dqt[dt]);
+        for (int dt = 0; dt < D / 32; dt++) dqt[dt] = MFMA(lds_frag_tr(Kp.t0[dt], Kp.t1[dt], ro), df, dqt[dt]);
       }
   }
   if (iq < seq) {
@@ -385,6 +423,7 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, 
                                                                        int T, float scale, float scale_log2) {
   using TL = ATile<D>;
   extern __shared__ __attribute__((aligned(1024))) char smem[];  // Q ring, dO ring, lse2 ring, delta ring
+  const lds_char* sm = (const lds_char*)smem;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l32 = lane & 31, kg = lane >> 5;
   const int hq = blockIdx.y, b = blockIdx.z, grp = nq / nkv, hk = hq / grp;
@@ -440,31 +479,35 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, 
     dma4_base(srow + row0, (uint32_t)((min(row0 + lane, seq - 1) - row0) * sizeof(float)),
               ldsS + (t % AB_RING) * AB_KT * sizeof(float));
   };
+  pin_frags(kf);
+  pin_frags(vf);
   issue(0);
   issue_stat(0);
   if (ntiles > 1) { issue(1); issue_stat(1); }
-  for (int t = 0; t < ntiles; t++) {
+  int slot = 0;
+  for (int t = 0; t < ntiles; t++, slot = slot == AB_RING - 1 ? 0 : slot + 1) {
     if (t + 1 < ntiles) dma_wait<2 * TL::IPW + 1>(); else dma_wait<0>();
     __syncthreads();
     if (t + 2 < ntiles) { issue(t + 2); issue_stat(t + 2); }
     const int qb = j0 + t * AB_KT;
     if (qb + AB_KT - 1 < jw) continue;  // every query of the tile precedes every key of this wave
-    const char* Qs = smem + (t % AB_RING) * TL::BYTES;
-    const char* Os = Qs + AB_RING * TL::BYTES;
-    const float* ls = lse_s + (t % AB_RING) * AB_KT;
-    const float* ds = del_s + (t % AB_RING) * AB_KT;
+    TilePtrs<D> Qp, Op;
+    Qp.set(sm + slot * TL::BYTES, fa);
+    Op.set(sm + (AB_RING + slot) * TL::BYTES, fa);
+    const float* ls = lse_s + slot * AB_KT;
+    const float* ds = del_s + slot * AB_KT;
     f32x16 st[2], dp[2];
 #pragma unroll
     for (int mt = 0; mt < 2; mt++) {
 #pragma unroll
       for (int r = 0; r < 16; r++) { st[mt][r] = 0.f; dp[mt][r] = 0.f; }
 #pragma unroll
-      for (int ks = 0; ks < D / 16; ks++) st[mt] = MFMA(lds_frag(Qs, fa.kdir[ks] + mt * 32 * TL::LD * 2), kf[ks], st[mt]);
+      for (int ks = 0; ks < D / 16; ks++) st[mt] = MFMA(lds_frag(Qp.dir[ks], mt * 32 * TL::LD * 2), kf[ks], st[mt]);
     }
 #pragma unroll
     for (int mt = 0; mt < 2; mt++)
 #pragma unroll
-      for (int ks = 0; ks < D / 16; ks++) dp[mt] = MFMA(lds_frag(Os, fa.kdir[ks] + mt * 32 * TL::LD * 2), vf[ks], dp[mt]);
+      for (int ks = 0; ks < D / 16; ks++) dp[mt] = MFMA(lds_frag(Op.dir[ks], mt * 32 * TL::LD * 2), vf[ks], dp[mt]);
     // P from S (rows 8*q4 + 4*kg + e of each 32-row half) while dP is in the matrix pipeline
 #pragma unroll
     for (int mt = 0; mt < 2; mt++)
@@ -490,7 +533,7 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, 
         const bf16x8 pf = pack_rows(st[mt], c);
         const int ro = (mt * 32 + 16 * c) * TL::LD * 2;
 #pragma unroll
-        for (int dt = 0; dt < D / 32; dt++) dvt[dt] = MFMA(lds_frag_tr(Os, fa.tr0[dt] + ro, fa.tr1[dt] + ro), pf, dvt[dt]);
+        for (int dt = 0; dt < D / 32; dt++) dvt[dt] = MFMA(lds_frag_tr(Op.t0[dt], Op.t1[dt], ro), pf, dvt[dt]);
       }
 #pragma unroll
     for (int mt = 0; mt < 2; mt++)
@@ -507,7 +550,7 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, 
         const bf16x8 df = pack_rows(st[mt], c);
         const int ro = (mt * 32 + 16 * c) * TL::LD * 2;
 #pragma unroll
-        for (int dt = 0; dt < D / 32; dt++) dkt[dt] = MFMA(lds_frag_tr(Qs, fa.tr0[dt] + ro, fa.tr1[dt] + ro), df, dkt[dt]);
+        for (int dt = 0; dt < D / 32; dt++) dkt[dt] = MFMA(lds_frag_tr(Qp.t0[dt], Qp.t1[dt], ro), df, dkt[dt]);
       }
   }
   if (jk < seq && part != nullptr) {
