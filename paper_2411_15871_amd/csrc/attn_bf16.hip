@@ -26,6 +26,42 @@
 #define AB_THREADS 256
 #define AB_KT 64   // tokens per LDS tile
 #define AB_RING 3  // tile slots
+#define AB_CH 16   // backward: a block walks at most this many 64-token tiles (longer causal rows are split
+                   // into chunks whose float32 partial results a second kernel adds in chunk order)
+
+// Work split of the backward kernels.  Along the block's own dimension there are ceil(seq/128) blocks;
+// block i has tiles_of(i) tiles to walk and is cut into ceil(tiles/AB_CH) chunks.  A launch index is
+// mapped to (block, chunk) heaviest block first; `pair` numbers the (block, chunk) pairs in natural order.
+struct ChunkMap { int blk, chunk, pair, chunks; };
+__host__ __device__ static inline int dq_tiles(int i, int seq) { int e = (i + 1) * 128; return ((e < seq ? e : seq) + AB_KT - 1) / AB_KT; }
+__host__ __device__ static inline int dkv_tiles(int i, int seq) { return (seq - i * 128 + AB_KT - 1) / AB_KT; }
+__host__ __device__ static inline int chunks_of(int tiles) { return (tiles + AB_CH - 1) / AB_CH; }
+static int total_pairs_dq(int seq) {
+  int n = 0;
+  for (int i = 0; i < (seq + 127) / 128; i++) n += chunks_of(dq_tiles(i, seq));
+  return n;
+}
+static int total_pairs_dkv(int seq) {
+  int n = 0;
+  for (int i = 0; i < (seq + 127) / 128; i++) n += chunks_of(dkv_tiles(i, seq));
+  return n;
+}
+template <bool DKV>
+__device__ __forceinline__ ChunkMap map_chunk(int id, int seq, int total) {
+  const int nblk = (seq + 127) / 128;
+  ChunkMap m;
+  int rem = id, after = 0;  // `after` = pairs of the blocks visited before this one
+  if (DKV) {  // heaviest = block 0; natural pair order = visiting order
+    int i = 0;
+    for (;; i++) { int ch = chunks_of(dkv_tiles(i, seq)); if (rem < ch || i == nblk - 1) { m.chunks = ch; break; } rem -= ch; after += ch; }
+    m.blk = i; m.chunk = rem; m.pair = after + rem;
+  } else {    // heaviest = last block
+    int i = nblk - 1;
+    for (;; i--) { int ch = chunks_of(dq_tiles(i, seq)); if (rem < ch || i == 0) { m.chunks = ch; break; } rem -= ch; after += ch; }
+    m.blk = i; m.chunk = rem; m.pair = total - after - m.chunks + rem;
+  }
+  return m;
+}
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
@@ -295,8 +331,8 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(int seq, i
                                                                       const bf16_t* __restrict__ dout,
                                                                       const float* __restrict__ lse2,
                                                                       const float* __restrict__ delta,
-                                                                      bf16_t* __restrict__ dqkv, int T, float scale,
-                                                                      float scale_log2) {
+                                                                      bf16_t* __restrict__ dqkv, float* __restrict__ part,
+                                                                      int pairs, int T, float scale, float scale_log2) {
   using TL = ATile<D>;
   extern __shared__ __attribute__((aligned(1024))) char smem[];  // K ring, then V ring
   const lds_char* sm = (const lds_char*)smem;
@@ -304,7 +340,8 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(int seq, i
   const int l32 = lane & 31, kg = lane >> 5;
   const int h = blockIdx.y, b = blockIdx.z, hk = h / (nq / nkv);
   const int ld = (nq + 2 * nkv) * D;
-  const int i0 = (gridDim.x - 1 - blockIdx.x) * 128, iw = i0 + wave * 32, iq = iw + l32;
+  const ChunkMap cm = map_chunk<false>(blockIdx.x, seq, pairs);
+  const int i0 = cm.blk * 128, iw = i0 + wave * 32, iq = iw + l32;
   const size_t tok0 = (size_t)b * seq;
   const char* kbase = reinterpret_cast<const char*>(qkv + tok0 * ld + (size_t)(nq + hk) * D);
   const char* vbase = reinterpret_cast<const char*>(qkv + tok0 * ld + (size_t)(nq + nkv + hk) * D);
@@ -327,9 +364,9 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(int seq, i
   uint32_t voff[TL::IPW];
   tile_voff<D>(voff, ld, wave, lane, AB_KT);
   const uint32_t ldsK = lds_address(smem), ldsV = ldsK + AB_RING * TL::BYTES;
-  const int ntiles = (min(seq, i0 + 128) + AB_KT - 1) / AB_KT;
-  auto issue = [&](int t) {
-    const int slot = t % AB_RING, valid = seq - t * AB_KT;
+  const int t0 = cm.chunk * AB_CH, ntiles = min(dq_tiles(cm.blk, seq), t0 + AB_CH);  // this block walks key tiles [t0, ntiles)
+  auto issue = [&](int t, int slot) {
+    const int valid = seq - t * AB_KT;
     if (valid >= AB_KT) {
       tile_dma<D>(kbase + t * tstride, voff, ldsK + slot * TL::BYTES, wave);
       tile_dma<D>(vbase + t * tstride, voff, ldsV + slot * TL::BYTES, wave);
@@ -344,13 +381,13 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(int seq, i
   pin_frags(dof);
   pin_scalar(l2);
   pin_scalar(dl);
-  issue(0);
-  if (ntiles > 1) issue(1);
+  issue(t0, 0);
+  if (t0 + 1 < ntiles) issue(t0 + 1, 1);
   int slot = 0;
-  for (int t = 0; t < ntiles; t++, slot = slot == AB_RING - 1 ? 0 : slot + 1) {
+  for (int t = t0; t < ntiles; t++, slot = slot == AB_RING - 1 ? 0 : slot + 1) {
     if (t + 1 < ntiles) dma_wait<2 * TL::IPW>(); else dma_wait<0>();
     __syncthreads();
-    if (t + 2 < ntiles) issue(t + 2);
+    if (t + 2 < ntiles) issue(t + 2, slot == 0 ? AB_RING - 1 : slot - 1);
     const int kb = t * AB_KT;
     if (kb > iw + 31) continue;
     TilePtrs<D> Kp, Vp;
@@ -394,7 +431,16 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(int seq, i
         for (int dt = 0; dt < D / 32; dt++) dqt[dt] = MFMA(lds_frag_tr(Kp.t0[dt], Kp.t1[dt], ro), df, dqt[dt]);
       }
   }
-  if (iq < seq) {
+  if (part != nullptr) {  // float32 partial of this chunk: part[batch][head][pair][128 rows][D], unscaled
+    float* row = part + ((((size_t)b * nq + h) * pairs + cm.pair) * 128 + wave * 32 + l32) * D;
+#pragma unroll
+    for (int dt = 0; dt < D / 32; dt++)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; q4++) {
+        f32x4 v = {dqt[dt][4 * q4], dqt[dt][4 * q4 + 1], dqt[dt][4 * q4 + 2], dqt[dt][4 * q4 + 3]};
+        *reinterpret_cast<f32x4*>(row + dt * 32 + 8 * q4 + 4 * kg) = v;
+      }
+  } else if (iq < seq) {
     bf16_t* row = dqkv + (tok0 + iq) * ld + (size_t)h * D;
 #pragma unroll
     for (int dt = 0; dt < D / 32; dt++)
@@ -408,19 +454,40 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(int seq, i
   }
 }
 
+// dq[token][head] = scale * sum over the chunks of the token's query block (ascending) of the partials.
+// grid (8*ceil(seq/128), nq, batch), 256 threads: a block owns 16 rows of a query block, thread = (row, 4 columns).
+template <int D>
+__global__ __launch_bounds__(256) void attn_bwd_dq_reduce_kernel(const float* __restrict__ part, bf16_t* __restrict__ dqkv, int seq,
+                                                                 int nq, int nkv, int pairs, float scale) {
+  const int i = blockIdx.x >> 3, r0 = (blockIdx.x & 7) * 16, h = blockIdx.y, b = blockIdx.z, ld = (nq + 2 * nkv) * D;
+  int base = 0;
+  for (int k = 0; k < i; k++) base += chunks_of(dq_tiles(k, seq));
+  const int ch = chunks_of(dq_tiles(i, seq));
+  const float* p0 = part + (((size_t)b * nq + h) * pairs + base) * 128 * D;
+  for (int e = threadIdx.x; e < 16 * D / 4; e += 256) {
+    const int row = r0 + e / (D / 4), c4 = (e % (D / 4)) * 4;
+    if (i * 128 + row >= seq) continue;
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < ch; c++) s += *reinterpret_cast<const f32x4*>(p0 + ((size_t)c * 128 + row) * D + c4);
+    bf16x4 o = {(bf16_t)(s[0] * scale), (bf16_t)(s[1] * scale), (bf16_t)(s[2] * scale), (bf16_t)(s[3] * scale)};
+    *reinterpret_cast<bf16x4*>(dqkv + ((size_t)b * seq + i * 128 + row) * ld + (size_t)h * D + c4) = o;
+  }
+}
+
 // ================================================================================ backward: dK, dV
 // grid (ceil(seq/128), nq, batch): one block per (key block, query head); wave w owns keys
 // j0 + 32w .. +31 and keeps their K, V fragments and the dK^T, dV^T accumulators in registers while
 // 64-query tiles of that head's Q and dO stream through LDS.  With grouped heads (nq > nkv) the
-// block writes float32 partials part[query head][token][dK | dV] and attn_bwd_group_reduce_kernel
-// adds the group's heads in index order; with nq == nkv it writes dK, dV directly.
+// block writes float32 partials part[batch][query head][pair][128 keys][dK | dV] and
+// attn_bwd_group_reduce_kernel adds the group's heads and the key block's chunks in index order; with
+// nq == nkv and no block longer than one chunk it writes dK, dV directly.
 template <int D>
 __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, int nq, int nkv, const bf16_t* __restrict__ qkv,
                                                                        const bf16_t* __restrict__ dout,
                                                                        const float* __restrict__ lse2,
                                                                        const float* __restrict__ delta,
                                                                        bf16_t* __restrict__ dqkv, float* __restrict__ part,
-                                                                       int T, float scale, float scale_log2) {
+                                                                       int pairs, int T, float scale, float scale_log2) {
   using TL = ATile<D>;
   extern __shared__ __attribute__((aligned(1024))) char smem[];  // Q ring, dO ring, lse2 ring, delta ring
   const lds_char* sm = (const lds_char*)smem;
@@ -428,7 +495,8 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, 
   const int l32 = lane & 31, kg = lane >> 5;
   const int hq = blockIdx.y, b = blockIdx.z, grp = nq / nkv, hk = hq / grp;
   const int ld = (nq + 2 * nkv) * D, ldo = nq * D;
-  const int j0 = blockIdx.x * 128, jw = j0 + wave * 32, jk = jw + l32;  // key positions in the sequence (block 0 is the heaviest)
+  const ChunkMap cm = map_chunk<true>(blockIdx.x, seq, pairs);
+  const int j0 = cm.blk * 128, jw = j0 + wave * 32, jk = jw + l32;  // key positions in the sequence (block 0 is the heaviest)
   const size_t tok0 = (size_t)b * seq;
   const char* qbase = reinterpret_cast<const char*>(qkv + tok0 * ld + (size_t)hq * D);
   const char* obase = reinterpret_cast<const char*>(dout + tok0 * ldo + (size_t)hq * D);
@@ -453,10 +521,10 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, 
   tile_voff<D>(vq, ld, wave, lane, AB_KT);
   tile_voff<D>(vo, ldo, wave, lane, AB_KT);
   const uint32_t ldsQ = lds_address(smem), ldsO = ldsQ + AB_RING * TL::BYTES;
-  const int ntiles = (seq - j0 + AB_KT - 1) / AB_KT;  // query tiles j0, j0+64, ...
+  const int t0 = cm.chunk * AB_CH, ntiles = min(dkv_tiles(cm.blk, seq), t0 + AB_CH);  // query tiles j0 + 64*[t0, ntiles)
   const size_t qstride = (size_t)AB_KT * ld * sizeof(bf16_t), ostride = (size_t)AB_KT * ldo * sizeof(bf16_t);
-  auto issue = [&](int t) {
-    const int slot = t % AB_RING, row0 = j0 + t * AB_KT, valid = seq - row0;
+  auto issue = [&](int t, int slot) {
+    const int row0 = j0 + t * AB_KT, valid = seq - row0;
     const char* qp = qbase + (size_t)j0 * ld * sizeof(bf16_t) + t * qstride;
     const char* op = obase + (size_t)j0 * ldo * sizeof(bf16_t) + t * ostride;
     if (valid >= AB_KT) {
@@ -474,21 +542,21 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, 
   // repeat what waves 0 and 1 transfer, which keeps the transfer count of all waves equal)
   const uint32_t ldsS = ldsQ + 2 * AB_RING * TL::BYTES + (wave & 1) * AB_RING * AB_KT * sizeof(float);
   const float* srow = (wave & 1) ? drow : lrow;
-  auto issue_stat = [&](int t) {
-    const int row0 = j0 + t * AB_KT;
-    dma4_base(srow + row0, (uint32_t)((min(row0 + lane, seq - 1) - row0) * sizeof(float)),
-              ldsS + (t % AB_RING) * AB_KT * sizeof(float));
-  };
   pin_frags(kf);
   pin_frags(vf);
-  issue(0);
-  issue_stat(0);
-  if (ntiles > 1) { issue(1); issue_stat(1); }
+  auto issue_stat = [&](int t, int slot) {
+    const int row0 = j0 + t * AB_KT;
+    dma4_base(srow + row0, (uint32_t)((min(row0 + lane, seq - 1) - row0) * sizeof(float)),
+              ldsS + slot * AB_KT * sizeof(float));
+  };
+  issue(t0, 0);
+  issue_stat(t0, 0);
+  if (t0 + 1 < ntiles) { issue(t0 + 1, 1); issue_stat(t0 + 1, 1); }
   int slot = 0;
-  for (int t = 0; t < ntiles; t++, slot = slot == AB_RING - 1 ? 0 : slot + 1) {
+  for (int t = t0; t < ntiles; t++, slot = slot == AB_RING - 1 ? 0 : slot + 1) {
     if (t + 1 < ntiles) dma_wait<2 * TL::IPW + 1>(); else dma_wait<0>();
     __syncthreads();
-    if (t + 2 < ntiles) { issue(t + 2); issue_stat(t + 2); }
+    if (t + 2 < ntiles) { const int ns = slot == 0 ? AB_RING - 1 : slot - 1; issue(t + 2, ns); issue_stat(t + 2, ns); }
     const int qb = j0 + t * AB_KT;
     if (qb + AB_KT - 1 < jw) continue;  // every query of the tile precedes every key of this wave
     TilePtrs<D> Qp, Op;
@@ -553,8 +621,8 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, 
         for (int dt = 0; dt < D / 32; dt++) dkt[dt] = MFMA(lds_frag_tr(Qp.t0[dt], Qp.t1[dt], ro), df, dkt[dt]);
       }
   }
-  if (jk < seq && part != nullptr) {
-    float* prow = part + ((size_t)hq * T + tok0 + jk) * (2 * D);  // hq = hk*grp + head-in-group
+  if (part != nullptr) {
+    float* prow = part + ((((size_t)b * nq + hq) * pairs + cm.pair) * 128 + wave * 32 + l32) * (2 * D);
 #pragma unroll
     for (int dt = 0; dt < D / 32; dt++)
 #pragma unroll
@@ -584,23 +652,29 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, 
   }
 }
 
-// dk,dv[token][kv head] = sum over the group's query heads (ascending) of the float32 partials
-// part[query head][token][dK | dV].
+// dk,dv[token][kv head] = sum over the group's query heads (ascending) and, inside a head, over the
+// chunks of the token's key block (ascending) of the float32 partials.
+// grid (8*ceil(seq/128), nkv, batch), 256 threads: a block owns 16 rows of a key block, thread = (key row, 4
+// columns of [dK | dV]).
 template <int D>
-__global__ void attn_bwd_group_reduce_kernel(const float* __restrict__ part, bf16_t* __restrict__ dqkv, int T, int nq,
-                                             int nkv) {
-  const int grp = nq / nkv, ld = (nq + 2 * nkv) * D;
-  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // over T * nkv * (2D/4)
-  const int per_tok = 2 * D / 4;
-  if (idx >= (size_t)T * nkv * per_tok) return;
-  int c4 = (int)(idx % per_tok) * 4;
-  int hk = (int)((idx / per_tok) % nkv);
-  size_t tok = idx / ((size_t)per_tok * nkv);
-  f32x4 s = {0.f, 0.f, 0.f, 0.f};
-  for (int g = 0; g < grp; g++) s += *reinterpret_cast<const f32x4*>(part + (((size_t)hk * grp + g) * T + tok) * (2 * D) + c4);
-  bf16x4 o = {(bf16_t)s[0], (bf16_t)s[1], (bf16_t)s[2], (bf16_t)s[3]};
-  bf16_t* dst = dqkv + tok * ld + (c4 < D ? (size_t)(nq + hk) * D + c4 : (size_t)(nq + nkv + hk) * D + (c4 - D));
-  *reinterpret_cast<bf16x4*>(dst) = o;
+__global__ __launch_bounds__(256) void attn_bwd_group_reduce_kernel(const float* __restrict__ part, bf16_t* __restrict__ dqkv,
+                                                                    int seq, int nq, int nkv, int pairs) {
+  const int i = blockIdx.x >> 3, r0 = (blockIdx.x & 7) * 16, hk = blockIdx.y, b = blockIdx.z, grp = nq / nkv, ld = (nq + 2 * nkv) * D;
+  int base = 0;
+  for (int k = 0; k < i; k++) base += chunks_of(dkv_tiles(k, seq));
+  const int ch = chunks_of(dkv_tiles(i, seq));
+  for (int e = threadIdx.x; e < 16 * 2 * D / 4; e += 256) {
+    const int row = r0 + e / (2 * D / 4), c4 = (e % (2 * D / 4)) * 4;
+    if (i * 128 + row >= seq) continue;
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    for (int g = 0; g < grp; g++) {
+      const float* p0 = part + (((size_t)b * nq + hk * grp + g) * pairs + base) * 128 * (2 * D);
+      for (int c = 0; c < ch; c++) s += *reinterpret_cast<const f32x4*>(p0 + ((size_t)c * 128 + row) * (2 * D) + c4);
+    }
+    bf16x4 o = {(bf16_t)s[0], (bf16_t)s[1], (bf16_t)s[2], (bf16_t)s[3]};
+    bf16_t* dst = dqkv + ((size_t)b * seq + i * 128 + row) * ld + (c4 < D ? (size_t)(nq + hk) * D + c4 : (size_t)(nq + nkv + hk) * D + (c4 - D));
+    *reinterpret_cast<bf16x4*>(dst) = o;
+  }
 }
 
 // ------------------------------------------------------------------------------------ host side
@@ -630,10 +704,26 @@ int dh_launch_attn_fwd_bf16(int batch, int seq, int nq, int nkv, int d, const bf
   return DH_OK;
 }
 
-// workspace: lse2[nq*T] floats, then (nq > nkv) the per-head dK/dV partials [nq][T][2d] floats
-size_t dh_attn_bwd_bf16_ws_bytes(int batch, int seq, int nq, int nkv, int d) {
+// workspace: lse2[nq*T] floats; dK/dV partials [batch][nq][pairs][128][2d] floats when heads are grouped
+// or some block needs more than one chunk; dQ partials [batch][nq][pairs][128][d] floats in the latter case
+static void bwd_ws_layout(int batch, int seq, int nq, int nkv, int d, size_t& o_lse2, size_t& o_dkv, size_t& o_dq, size_t& total,
+                          int& pairs, bool& chunked) {
   const size_t T = (size_t)batch * seq;
-  return dh_align_up(nq * T * sizeof(float), 256) + (nq > nkv ? (size_t)nq * T * 2 * d * sizeof(float) : 0);
+  pairs = total_pairs_dq(seq);  // equals total_pairs_dkv(seq): the two tile counts mirror each other up to the ragged tail
+  const int pk = total_pairs_dkv(seq);
+  if (pk > pairs) pairs = pk;
+  chunked = pairs > (seq + 127) / 128;
+  size_t cur = 0;
+  o_lse2 = cur; cur += dh_align_up(nq * T * sizeof(float), 256);
+  o_dkv = cur; if (nq > nkv || chunked) cur += dh_align_up((size_t)batch * nq * pairs * 128 * 2 * d * sizeof(float), 256);
+  o_dq = cur; if (chunked) cur += dh_align_up((size_t)batch * nq * pairs * 128 * d * sizeof(float), 256);
+  total = cur;
+}
+
+size_t dh_attn_bwd_bf16_ws_bytes(int batch, int seq, int nq, int nkv, int d) {
+  size_t a, b, c, total; int pairs; bool chunked;
+  bwd_ws_layout(batch, seq, nq, nkv, d, a, b, c, total, pairs, chunked);
+  return total;
 }
 
 int dh_launch_attn_bwd_bf16(int batch, int seq, int nq, int nkv, int d, const bf16_t* qkv, const bf16_t* o,
@@ -642,40 +732,35 @@ int dh_launch_attn_bwd_bf16(int batch, int seq, int nq, int nkv, int d, const bf
   if (d != 64 && d != 128) DH_FAIL(DH_ERR_SHAPE, "attention (bf16): head_dim %d must be 64 or 128", d);
   const int T = batch * seq;
   if (T == 0) return DH_OK;
-  const size_t need = dh_attn_bwd_bf16_ws_bytes(batch, seq, nq, nkv, d);
+  size_t o_lse2, o_dkv, o_dq, need; int pairs_max; bool chunked;
+  bwd_ws_layout(batch, seq, nq, nkv, d, o_lse2, o_dkv, o_dq, need, pairs_max, chunked);
   if (!ws || ws_bytes < need) DH_FAIL(DH_ERR_WORKSPACE_TOO_SMALL, "attn_bwd: workspace %zu < %zu bytes", ws_bytes, need);
-  float* lse2 = (float*)ws;
-  float* part = nq > nkv ? (float*)((char*)ws + dh_align_up((size_t)nq * T * sizeof(float), 256)) : nullptr;
+  float* lse2 = (float*)((char*)ws + o_lse2);
+  float* part_kv = (nq > nkv || chunked) ? (float*)((char*)ws + o_dkv) : nullptr;
+  float* part_q = chunked ? (float*)((char*)ws + o_dq) : nullptr;
   const float sc = (float)(1.0 / sqrt((double)d)), sl2 = (float)(1.4426950408889634 / sqrt((double)d));
-  dim3 gq((seq + 127) / 128, nq, batch);
+  const int nblk = (seq + 127) / 128, pq = total_pairs_dq(seq), pk = total_pairs_dkv(seq);
+  dim3 gwq(pq, nq, batch), gwk(pk, nq, batch), gq(nblk * 8, nq, batch), gk(nblk * 8, nkv, batch);
   const unsigned nprep = (unsigned)(((size_t)T * nq + 3) / 4);
-  const unsigned nred = (unsigned)(((size_t)T * nkv * (2 * d / 4) + 255) / 256);
   const size_t lds_dq = 2 * AB_RING * (size_t)AB_KT * d * 2, lds_dkv = lds_dq + 2 * AB_RING * AB_KT * sizeof(float);
   static bool ready[2] = {false, false};
   int rc;
-  if (d == 128) {
-    if (!ready[0]) {
-      if ((rc = set_lds(attn_bwd_dq_bf16_kernel<128>, lds_dq)) || (rc = set_lds(attn_bwd_dkv_bf16_kernel<128>, lds_dkv))) return rc;
-      ready[0] = true;
-    }
-    attn_bwd_prep_kernel<128><<<nprep, 256, 0, stream>>>(nq, o, dout, lse, delta, lse2, T);
-    DH_LAUNCH_CHECK();
-    attn_bwd_dq_bf16_kernel<128><<<gq, AB_THREADS, lds_dq, stream>>>(seq, nq, nkv, qkv, dout, lse2, delta, dqkv, T, sc, sl2);
-    DH_LAUNCH_CHECK();
-    attn_bwd_dkv_bf16_kernel<128><<<gq, AB_THREADS, lds_dkv, stream>>>(seq, nq, nkv, qkv, dout, lse2, delta, dqkv, part, T, sc, sl2);
-    if (part) { DH_LAUNCH_CHECK(); attn_bwd_group_reduce_kernel<128><<<nred, 256, 0, stream>>>(part, dqkv, T, nq, nkv); }
-  } else {
-    if (!ready[1]) {
-      if ((rc = set_lds(attn_bwd_dq_bf16_kernel<64>, lds_dq)) || (rc = set_lds(attn_bwd_dkv_bf16_kernel<64>, lds_dkv))) return rc;
-      ready[1] = true;
-    }
-    attn_bwd_prep_kernel<64><<<nprep, 256, 0, stream>>>(nq, o, dout, lse, delta, lse2, T);
-    DH_LAUNCH_CHECK();
-    attn_bwd_dq_bf16_kernel<64><<<gq, AB_THREADS, lds_dq, stream>>>(seq, nq, nkv, qkv, dout, lse2, delta, dqkv, T, sc, sl2);
-    DH_LAUNCH_CHECK();
-    attn_bwd_dkv_bf16_kernel<64><<<gq, AB_THREADS, lds_dkv, stream>>>(seq, nq, nkv, qkv, dout, lse2, delta, dqkv, part, T, sc, sl2);
-    if (part) { DH_LAUNCH_CHECK(); attn_bwd_group_reduce_kernel<64><<<nred, 256, 0, stream>>>(part, dqkv, T, nq, nkv); }
-  }
-  DH_LAUNCH_CHECK();
+#define DH_ATTN_BWD(DD, IDX)                                                                                                   \
+  do {                                                                                                                         \
+    if (!ready[IDX]) {                                                                                                         \
+      if ((rc = set_lds(attn_bwd_dq_bf16_kernel<DD>, lds_dq)) || (rc = set_lds(attn_bwd_dkv_bf16_kernel<DD>, lds_dkv))) return rc; \
+      ready[IDX] = true;                                                                                                       \
+    }                                                                                                                          \
+    attn_bwd_prep_kernel<DD><<<nprep, 256, 0, stream>>>(nq, o, dout, lse, delta, lse2, T);                                       \
+    DH_LAUNCH_CHECK();                                                                                                         \
+    attn_bwd_dq_bf16_kernel<DD><<<gwq, AB_THREADS, lds_dq, stream>>>(seq, nq, nkv, qkv, dout, lse2, delta, dqkv, part_q, pq, T, sc, sl2); \
+    DH_LAUNCH_CHECK();                                                                                                         \
+    if (part_q) { attn_bwd_dq_reduce_kernel<DD><<<gq, 256, 0, stream>>>(part_q, dqkv, seq, nq, nkv, pq, sc); DH_LAUNCH_CHECK(); } \
+    attn_bwd_dkv_bf16_kernel<DD><<<gwk, AB_THREADS, lds_dkv, stream>>>(seq, nq, nkv, qkv, dout, lse2, delta, dqkv, part_kv, pk, T, sc, sl2); \
+    DH_LAUNCH_CHECK();                                                                                                         \
+    if (part_kv) { attn_bwd_group_reduce_kernel<DD><<<gk, 256, 0, stream>>>(part_kv, dqkv, seq, nq, nkv, pk); DH_LAUNCH_CHECK(); } \
+  } while (0)
+  if (d == 128) DH_ATTN_BWD(128, 0); else DH_ATTN_BWD(64, 1);
+#undef DH_ATTN_BWD
   return DH_OK;
 }
