@@ -256,3 +256,125 @@ def llama_bwd(cfg, W, saved, dout, peers=None):
     grads = dict(dWqkv=dWqkv, dWo=dWo, dWgu=dWgu, dWd=dWd, dg1=dg1, dg2=dg2)
     inter = dict(da=da, dgu=dgu, dh2=dh2, dx2=dx2, do=do, dqkv=dqkv, dh1=dh1)
     return dx, grads, inter
+
+
+# --------------------------------------------------------------------------- MoE (top-2, Sec. 6.1 "LLM/MoE Models")
+def router_top2(logits):
+    """Top-2 gate: softmax over the experts, keep the two largest (ties: lower expert id first), renormalise
+    the two kept probabilities to sum 1 (= softmax over the two kept logits).  logits[T,E] ->
+    idx[T,2] (descending logit), prob[T,2]."""
+    T, E = logits.shape
+    idx = np.zeros((T, 2), dtype=np.int64)
+    prob = np.zeros((T, 2))
+    for t in range(T):
+        order = sorted(range(E), key=lambda e: (-logits[t, e], e))
+        i, j = order[0], order[1]
+        ei, ej = np.exp(logits[t, i] - logits[t, i]), np.exp(logits[t, j] - logits[t, i])
+        idx[t] = (i, j)
+        prob[t] = (ei / (ei + ej), ej / (ei + ej))
+    return idx, prob
+
+
+def router_top2_bwd(dprob, idx, prob, E):
+    """Gradient w.r.t. the logits; only the two selected logits receive any."""
+    T = idx.shape[0]
+    dl = np.zeros((T, E))
+    s = np.sum(dprob * prob, axis=1)
+    for k in range(2):
+        dl[np.arange(T), idx[:, k]] = prob[:, k] * (dprob[:, k] - s)
+    return dl
+
+
+def permute_rows(idx, E):
+    """Stable grouping of the 2T (token, k) assignments by expert id: row order = expert ascending, then
+    token ascending, then k.  Returns dest[T,2] (row of each assignment), src_tok[2T], counts[E]."""
+    T = idx.shape[0]
+    keys = [(int(idx[t, k]), t, k) for t in range(T) for k in range(2)]
+    keys.sort()
+    dest = np.zeros((T, 2), dtype=np.int64)
+    src = np.zeros(2 * T, dtype=np.int64)
+    counts = np.zeros(E, dtype=np.int64)
+    for row, (e, t, k) in enumerate(keys):
+        dest[t, k] = row
+        src[row] = t
+        counts[e] += 1
+    return dest, src, counts
+
+
+def a2a_dispatch_order(counts, n_local):
+    """One-GPU stand-in of the expert-parallel all-to-all: the send buffer is ordered by logical expert
+    e = src_rank*n_local + local_expert; the receive buffer is ordered [local_expert][src_rank].  Returns for
+    every receive row the send row it copies (a permutation), and the rows per local expert."""
+    E = len(counts)
+    start = np.concatenate([[0], np.cumsum(counts)])
+    rows = []
+    group_rows = []
+    for le in range(n_local):
+        n = 0
+        for src in range(E // n_local):
+            e = src * n_local + le
+            rows.extend(range(start[e], start[e + 1]))
+            n += counts[e]
+        group_rows.append(n)
+    return np.array(rows, dtype=np.int64), group_rows
+
+
+def moe_ffn_fwd(h2, logits, Wgu, Wd, n_local):
+    """Weight-tied MoE block: y_t = sum_k p_tk * FFN_{e_k % n_local}(h2_t), FFN = SwiGLU MLP.
+    Wgu[n_local,H,2F], Wd[n_local,F,H].  Goes through the same data movement as the GPU path
+    (permute, dispatch, per-expert FFN, combine, weighted un-permute) so intermediates can be compared."""
+    T, H = h2.shape
+    E = logits.shape[1]
+    F = Wd.shape[1]
+    idx, prob = router_top2(logits)
+    dest, src, counts = permute_rows(idx, E)
+    xp = h2[src]                              # permute
+    order, group_rows = a2a_dispatch_order(counts, n_local)
+    xg = xp[order]                            # all-to-all dispatch
+    yg = np.zeros_like(xg)
+    gu = np.zeros((2 * T, 2 * F))
+    r0 = 0
+    for le in range(n_local):
+        r1 = r0 + group_rows[le]
+        gu[r0:r1] = xg[r0:r1] @ Wgu[le]
+        yg[r0:r1] = swiglu_fwd(gu[r0:r1, :F], gu[r0:r1, F:]) @ Wd[le]
+        r0 = r1
+    yp = np.zeros_like(yg)
+    yp[order] = yg                            # all-to-all combine
+    y = prob[:, 0:1] * yp[dest[:, 0]] + prob[:, 1:2] * yp[dest[:, 1]]
+    saved = dict(idx=idx, prob=prob, dest=dest, src=src, counts=counts, order=order, group_rows=group_rows,
+                 xg=xg, gu=gu, yp=yp)
+    return y, saved
+
+
+def moe_ffn_bwd(dy, h2, Wgu, Wd, saved, n_local):
+    """Backward of moe_ffn_fwd: returns dh2, dlogits, dWgu, dWd."""
+    T, H = h2.shape
+    F = Wd.shape[1]
+    s = saved
+    E = len(s["counts"])
+    dprob = np.stack([np.sum(dy * s["yp"][s["dest"][:, k]], axis=1) for k in range(2)], axis=1)
+    dyp = np.zeros_like(s["yp"])
+    for k in range(2):
+        dyp[s["dest"][:, k]] = s["prob"][:, k:k + 1] * dy
+    dyg = dyp[s["order"]]
+    dxg = np.zeros_like(dyg)
+    dWgu = np.zeros_like(Wgu)
+    dWd = np.zeros_like(Wd)
+    r0 = 0
+    for le in range(n_local):
+        r1 = r0 + s["group_rows"][le]
+        g, u = s["gu"][r0:r1, :F], s["gu"][r0:r1, F:]
+        a = swiglu_fwd(g, u)
+        da = dyg[r0:r1] @ Wd[le].T
+        dWd[le] = a.T @ dyg[r0:r1]
+        dg, du = swiglu_bwd(da, g, u)
+        dgu = np.concatenate([dg, du], axis=1)
+        dWgu[le] = s["xg"][r0:r1].T @ dgu
+        dxg[r0:r1] = dgu @ Wgu[le].T
+        r0 = r1
+    dxp = np.zeros_like(dxg)
+    dxp[s["order"]] = dxg
+    dh2 = dxp[s["dest"][:, 0]] + dxp[s["dest"][:, 1]]
+    dlogits = router_top2_bwd(dprob, s["idx"], s["prob"], E)
+    return dh2, dlogits, dWgu, dWd
