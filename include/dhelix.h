@@ -303,6 +303,63 @@ int dh_attn_bwd(int dtype, int batch, int seq, int nq, int nkv, int d, const voi
                 void* stream);
 size_t dh_attn_bwd_workspace_bytes(int dtype, int batch, int seq, int nq, int nkv, int d);
 
+/* ------------------------------------------------------------------------------------------
+ * Mixture-of-experts operators (Sec. 6.1, top-2 gating; operator bases Router, Permute, AlltoAll and
+ * Group-GEMM of Table 2).  Expert parallelism on one GPU: the E logical experts are
+ * e = source_rank * n_local + local_expert; this GPU holds the n_local local experts and receives
+ * every source rank's rows for them.  All index work is integer and deterministic.
+ * ------------------------------------------------------------------------------------------ */
+
+/* Router: logits[T,E] float32 -> idx[T,2] (largest logit first; ties go to the lower expert id) and
+ * prob[T,2] = softmax over the two kept logits.  2 <= E <= 256. */
+int dh_moe_route(int T, int E, const float* logits, int32_t* idx, float* prob, void* stream);
+/* dlogits[T,E] = gradient of the router given dprob[T,2]; zero outside the two kept experts. */
+int dh_moe_route_bwd(int T, int E, const float* dprob, const int32_t* idx, const float* prob,
+                     float* dlogits, void* stream);
+
+/* Index tables of one routing decision, all int32 device arrays owned by the caller.  "Assignment"
+ * a = 2t+k is token t's k-th expert.  Send order: assignments grouped by expert ascending, inside an
+ * expert by a ascending (stable).  Receive order: [local expert][source rank], same order inside. */
+typedef struct {
+  int32_t* rank;         /* [2T]   scratch: position of assignment a among its expert's rows     */
+  int32_t* dest;         /* [2T]   send row of assignment a                                      */
+  int32_t* src_tok;      /* [2T]   token of send row r                                           */
+  int32_t* send_of_recv; /* [2T]   send row copied into receive row j (all-to-all dispatch map)  */
+  int32_t* recv_of_send; /* [2T]   receive row of send row r (all-to-all combine map)            */
+  int32_t* counts;       /* [E]    rows per logical expert                                       */
+  int32_t* offsets;      /* [E+1]  first send row of each logical expert                         */
+  int32_t* recv_start;   /* [E]    first receive row of each logical expert                      */
+  int32_t* group_rows;   /* [n_local] rows per local expert (copy to the host for dh_gemm_grouped) */
+} dh_moe_tables;
+/* Fills every table from idx[T,2].  E % n_local must be 0. */
+int dh_moe_plan(int T, int E, int n_local, const int32_t* idx, const dh_moe_tables* tables,
+                void* stream);
+
+/* out[r,:] = in[map[r],:] for r < n_rows, rows of H elements (H % 8 == 0); map must be in range of
+ * `in`.  Serves as the token permute (map = src_tok) and as the all-to-all stand-in: a memory-bound
+ * copy of exactly the payload (dispatch: map = send_of_recv, combine: map = recv_of_send).
+ * n_blocks: 256-thread blocks it may use (0 = cover the payload, at most 4096). */
+int dh_moe_gather_rows(int dtype, int n_rows, int H, const void* in, const int32_t* map, void* out,
+                       int n_blocks, void* stream);
+
+/* Un-permute: y[t,:] = prob[t,0]*yp[dest[2t],:] + prob[t,1]*yp[dest[2t+1],:]; prob == NULL means
+ * weights 1 (the backward of the token permute). */
+int dh_moe_combine(int dtype, int T, int H, const void* yp, const int32_t* dest, const float* prob,
+                   void* y, void* stream);
+/* Backward of the weighted un-permute: dyp[dest[2t+k],:] = prob[t,k]*dy[t,:] and
+ * dprob[t,k] = <dy[t,:], yp[dest[2t+k],:]> (float32). */
+int dh_moe_combine_bwd(int dtype, int T, int H, const void* dy, const void* yp, const int32_t* dest,
+                       const float* prob, void* dyp, float* dprob, void* stream);
+
+/* Grouped GEMM over row groups that are stored back to back; group g has group_rows[g] rows
+ * (HOST array: the counts depend on the routing, the caller reads them back once per routing).
+ *   mode 0  C[rows_g, dim_b]  = A[rows_g, dim_a]   * B_g[dim_a, dim_b]          (expert forward)
+ *   mode 1  C[rows_g, dim_b]  = A[rows_g, dim_a]   * B_g[dim_b, dim_a]^T        (data gradient)
+ *   mode 2  C_g[dim_a, dim_b] += A[rows_g, dim_a]^T * B[rows_g, dim_b], float32 (weight gradient)
+ * Constraints per group as for dh_gemm; ws as for dh_gemm (sized for the largest group). */
+int dh_gemm_grouped(int dtype, int mode, int n_groups, const int* group_rows, int dim_a, int dim_b,
+                    const void* A, const void* B, void* C, void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -73,6 +73,13 @@ class dh_seg_pair(C.Structure):
     _fields_ = [("f_begin", C.c_int), ("f_end", C.c_int), ("b_begin", C.c_int), ("b_end", C.c_int)]
 
 
+MOE_TABLES = ("rank", "dest", "src_tok", "send_of_recv", "recv_of_send", "counts", "offsets", "recv_start", "group_rows")
+
+
+class dh_moe_tables(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in MOE_TABLES]
+
+
 class dh_plan(C.Structure):
     _fields_ = [("n_fwd", C.c_int), ("n_bwd", C.c_int), ("n_pairs", C.c_int), ("fwd_order", C.c_int * DH_MAX_OPS),
                 ("bwd_order", C.c_int * DH_MAX_OPS), ("pairs", dh_seg_pair * (2 * DH_MAX_OPS))]
@@ -117,6 +124,13 @@ SIGNATURES = {
     "dh_attn_fwd": (_I, [_I, _I, _I, _I, _I, _I, _P, _P, _P, _P]),
     "dh_attn_bwd": (_I, [_I, _I, _I, _I, _I, _I, _P, _P, _P, _P, _P, _P, _P, _Z, _P]),
     "dh_attn_bwd_workspace_bytes": (_Z, [_I, _I, _I, _I, _I, _I]),
+    "dh_moe_route": (_I, [_I, _I, _P, _P, _P, _P]),
+    "dh_moe_route_bwd": (_I, [_I, _I, _P, _P, _P, _P, _P]),
+    "dh_moe_plan": (_I, [_I, _I, _I, _P, C.POINTER(dh_moe_tables), _P]),
+    "dh_moe_gather_rows": (_I, [_I, _I, _I, _P, _P, _P, _I, _P]),
+    "dh_moe_combine": (_I, [_I, _I, _I, _P, _P, _P, _P, _P]),
+    "dh_moe_combine_bwd": (_I, [_I, _I, _I, _P, _P, _P, _P, _P, _P, _P]),
+    "dh_gemm_grouped": (_I, [_I, _I, _I, C.POINTER(_I), _I, _I, _P, _P, _P, _P, _Z, _P]),
 }
 for _name, (_res, _args) in SIGNATURES.items():
     _fn = getattr(lib, _name)
@@ -369,3 +383,39 @@ def dh_attn_bwd(dtype, batch, seq, nq, nkv, d, qkv, o, dout, lse, dqkv, delta, w
 
 def dh_attn_bwd_workspace_bytes(dtype, batch, seq, nq, nkv, d):
     return lib.dh_attn_bwd_workspace_bytes(dtype, batch, seq, nq, nkv, d)
+
+
+def dh_moe_route(T, E, logits, idx, prob, stream=None):
+    _check(lib.dh_moe_route(T, E, _ptr(logits), _ptr(idx), _ptr(prob), _stream(stream)))
+
+
+def dh_moe_route_bwd(T, E, dprob, idx, prob, dlogits, stream=None):
+    _check(lib.dh_moe_route_bwd(T, E, _ptr(dprob), _ptr(idx), _ptr(prob), _ptr(dlogits), _stream(stream)))
+
+
+def moe_tables(**tensors):
+    """dh_moe_tables from int32 device tensors named as the struct's fields."""
+    return dh_moe_tables(**{n: _ptr(tensors[n]) for n in MOE_TABLES})
+
+
+def dh_moe_plan(T, E, n_local, idx, tables, stream=None):
+    _check(lib.dh_moe_plan(T, E, n_local, _ptr(idx), C.byref(tables), _stream(stream)))
+
+
+def dh_moe_gather_rows(dtype, n_rows, H, inp, row_map, out, n_blocks=0, stream=None):
+    _check(lib.dh_moe_gather_rows(dtype, n_rows, H, _ptr(inp), _ptr(row_map), _ptr(out), n_blocks, _stream(stream)))
+
+
+def dh_moe_combine(dtype, T, H, yp, dest, prob, y, stream=None):
+    _check(lib.dh_moe_combine(dtype, T, H, _ptr(yp), _ptr(dest), _ptr(prob), _ptr(y), _stream(stream)))
+
+
+def dh_moe_combine_bwd(dtype, T, H, dy, yp, dest, prob, dyp, dprob, stream=None):
+    _check(lib.dh_moe_combine_bwd(dtype, T, H, _ptr(dy), _ptr(yp), _ptr(dest), _ptr(prob), _ptr(dyp), _ptr(dprob),
+                                  _stream(stream)))
+
+
+def dh_gemm_grouped(dtype, mode, group_rows, dim_a, dim_b, A, B, Cout, ws=None, ws_bytes=0, stream=None):
+    rows = (_I * len(group_rows))(*[int(r) for r in group_rows])
+    _check(lib.dh_gemm_grouped(dtype, mode, len(group_rows), rows, dim_a, dim_b, _ptr(A), _ptr(B), _ptr(Cout), _ptr(ws),
+                               ws_bytes, _stream(stream)))
