@@ -378,3 +378,127 @@ def moe_ffn_bwd(dy, h2, Wgu, Wd, saved, n_local):
     dh2 = dxp[s["dest"][:, 0]] + dxp[s["dest"][:, 1]]
     dlogits = router_top2_bwd(dprob, s["idx"], s["prob"], E)
     return dh2, dlogits, dWgu, dWd
+
+
+# --------------------------------------------------------------------------- GPT-style layer with sequence parallelism
+def allgather_standin(own, peers):
+    """One-GPU stand-in of a sequence-parallel all-gather (Sec. 2.1): this rank's rows first, then the frozen
+    peer shards in rank order.  own[Ts,H], peers[R-1,Ts,H] -> [R*Ts,H]."""
+    parts = [np.asarray(own, dtype=np.float64)]
+    if peers is not None:
+        parts += [peers[r].astype(np.float64) for r in range(len(peers))]
+    return np.concatenate(parts, axis=0)
+
+
+def reducescatter_standin(part, peers):
+    """Stand-in of the reduce-scatter: this rank's row slice (the first Ts rows) of the sum over ranks.  part[T,H] is
+    this rank's full partial, peers[R-1,Ts,H] the other ranks' partials restricted to this rank's slice."""
+    Ts = part.shape[0] if peers is None else peers.shape[1]
+    return standin_sum(part[:Ts], peers)
+
+
+def gpt_fwd(cfg, W, x_s, peers=None):
+    """Forward of one pre-norm GPT-style layer shard under tensor + sequence parallelism (Sec. 2.1): LayerNorm on
+    the sequence shard, all-gather, column-parallel GEMM (+bias), causal attention without rotary embedding,
+    row-parallel GEMM, reduce-scatter, bias + residual; the same for the GeLU MLP.
+    x_s[Ts,H] with Ts = T / R.  W: g1,b1[H], Wqkv[H,n_qkv], bqkv[n_qkv], Wo[nq*d,H], bo[H], g2,b2[H], W1[H,F],
+    bf1[F], W2[F,H], bf2[H].  peers: 'ag1','ag2' [R-1,Ts,H] (peer LayerNorm outputs), 'rs1','rs2' [R-1,Ts,H]."""
+    peers = peers or {}
+    T, nq, nkv, d = cfg.T, cfg.nq, cfg.nkv, cfg.d
+    h1_s, mu1, r1 = layernorm_fwd(x_s, W["g1"], W["b1"], cfg.eps)
+    h1 = allgather_standin(h1_s, peers.get("ag1"))
+    qkv = h1 @ W["Wqkv"] + W["bqkv"]
+    q = qkv[:, : nq * d].reshape(T, nq, d)
+    k = qkv[:, nq * d: (nq + nkv) * d].reshape(T, nkv, d)
+    v = qkv[:, (nq + nkv) * d:].reshape(T, nkv, d)
+    o, lse = attention_fwd(q, k, v, cfg.batch, cfg.seq)
+    o2 = o.reshape(T, nq * d)
+    y_s = reducescatter_standin(o2 @ W["Wo"], peers.get("rs1"))
+    x2_s = x_s + y_s + W["bo"]
+    h2_s, mu2, r2 = layernorm_fwd(x2_s, W["g2"], W["b2"], cfg.eps)
+    h2 = allgather_standin(h2_s, peers.get("ag2"))
+    f = h2 @ W["W1"] + W["bf1"]
+    a = gelu_fwd(f)
+    z_s = reducescatter_standin(a @ W["W2"], peers.get("rs2"))
+    out_s = x2_s + z_s + W["bf2"]
+    saved = dict(x=x_s, mu1=mu1, r1=r1, h1=h1, q=q, k=k, v=v, o=o2, lse=lse, x2=x2_s, mu2=mu2, r2=r2, h2=h2, f=f, a=a)
+    return out_s, saved
+
+
+def gpt_bwd(cfg, W, saved, dout_s, peers=None):
+    """Backward of gpt_fwd: every all-gather turns into a reduce-scatter and vice versa (Sec. 2.1).
+    peers: 'ag3','ag4' [R-1,Ts,H] = the peers' gradient shards entering the two backward all-gathers,
+    'rs3','rs4' [R-1,Ts,H] = the peers' partial gradients for this rank's rows.  Weight and bias gradients of
+    the sharded linears sum over all T rows; LayerNorm and row-parallel-bias gradients over this rank's rows."""
+    peers = peers or {}
+    T, nq, nkv, d = cfg.T, cfg.nq, cfg.nkv, cfg.d
+    s = saved
+    Ts = dout_s.shape[0]
+    dbf2 = dout_s.sum(axis=0)
+    dz = allgather_standin(dout_s, peers.get("ag3"))
+    da = dz @ W["W2"].T
+    dW2 = s["a"].T @ dz
+    df = gelu_bwd(da, s["f"])
+    dbf1 = df.sum(axis=0)
+    dW1 = s["h2"].T @ df
+    dh2_s = reducescatter_standin(df @ W["W1"].T, peers.get("rs3"))
+    dx2n, dg2, db2 = layernorm_bwd(dh2_s, s["x2"], W["g2"], s["mu2"], s["r2"])
+    dx2_s = dout_s + dx2n
+    dbo = dx2_s.sum(axis=0)
+    dy = allgather_standin(dx2_s, peers.get("ag4"))
+    do = dy @ W["Wo"].T
+    dWo = s["o"].T @ dy
+    dq, dk, dv = attention_bwd(do.reshape(T, nq, d), s["q"], s["k"], s["v"], cfg.batch, cfg.seq)
+    dqkv = np.concatenate([dq.reshape(T, -1), dk.reshape(T, -1), dv.reshape(T, -1)], axis=1)
+    dbqkv = dqkv.sum(axis=0)
+    dWqkv = s["h1"].T @ dqkv
+    dh1_s = reducescatter_standin(dqkv @ W["Wqkv"].T, peers.get("rs4"))
+    dxn, dg1, db1 = layernorm_bwd(dh1_s, s["x"], W["g1"], s["mu1"], s["r1"])
+    dx_s = dx2_s + dxn
+    grads = dict(dWqkv=dWqkv, dbqkv=dbqkv, dWo=dWo, dbo=dbo, dW1=dW1, dbf1=dbf1, dW2=dW2, dbf2=dbf2,
+                 dg1=dg1, db1=db1, dg2=dg2, db2=db2)
+    inter = dict(dz=dz, da=da, df=df, dh2=dh2_s, dx2=dx2_s, do=do, dqkv=dqkv, dh1=dh1_s)
+    assert dx_s.shape[0] == Ts
+    return dx_s, grads, inter
+
+
+# --------------------------------------------------------------------------- MoE layer (attention + expert-parallel FFN)
+def moe_layer_fwd(cfg, W, x, logits, n_local):
+    """Forward of a pre-norm layer whose FFN is the top-2 MoE block above; attention is not sharded (expert
+    parallelism lives inside data parallelism, Sec. 2.1), so the only communication is the two all-to-alls.
+    W: g1, Wqkv, Wo, g2, Wgu[n_local,H,2F], Wd[n_local,F,H].  logits[T,E] are an input."""
+    T, nq, nkv, d = cfg.T, cfg.nq, cfg.nkv, cfg.d
+    h1, r1 = rmsnorm_fwd(x, W["g1"], cfg.eps)
+    qkv = h1 @ W["Wqkv"]
+    q = rope(qkv[:, : nq * d].reshape(T, nq, d), cfg.seq, cfg.rope_base)
+    k = rope(qkv[:, nq * d: (nq + nkv) * d].reshape(T, nkv, d), cfg.seq, cfg.rope_base)
+    v = qkv[:, (nq + nkv) * d:].reshape(T, nkv, d)
+    o, lse = attention_fwd(q, k, v, cfg.batch, cfg.seq)
+    o2 = o.reshape(T, nq * d)
+    x2 = x + o2 @ W["Wo"]
+    h2, r2 = rmsnorm_fwd(x2, W["g2"], cfg.eps)
+    m, msaved = moe_ffn_fwd(h2, logits, W["Wgu"], W["Wd"], n_local)
+    out = x2 + m
+    saved = dict(x=x, r1=r1, h1=h1, q=q, k=k, v=v, o=o2, lse=lse, x2=x2, r2=r2, h2=h2, moe=msaved)
+    return out, saved
+
+
+def moe_layer_bwd(cfg, W, saved, dout, n_local):
+    """Backward of moe_layer_fwd; dlogits is an output next to dx and the weight gradients."""
+    T, nq, nkv, d = cfg.T, cfg.nq, cfg.nkv, cfg.d
+    s = saved
+    dh2, dlogits, dWgu, dWd = moe_ffn_bwd(dout, s["h2"], W["Wgu"], W["Wd"], s["moe"], n_local)
+    dx2n, dg2 = rmsnorm_bwd(dh2, s["x2"], W["g2"], s["r2"])
+    dx2 = dout + dx2n
+    do = dx2 @ W["Wo"].T
+    dWo = s["o"].T @ dx2
+    dq, dk, dv = attention_bwd(do.reshape(T, nq, d), s["q"], s["k"], s["v"], cfg.batch, cfg.seq)
+    dq = rope(dq, cfg.seq, cfg.rope_base, inverse=True)
+    dk = rope(dk, cfg.seq, cfg.rope_base, inverse=True)
+    dqkv = np.concatenate([dq.reshape(T, -1), dk.reshape(T, -1), dv.reshape(T, -1)], axis=1)
+    dWqkv = s["h1"].T @ dqkv
+    dh1 = dqkv @ W["Wqkv"].T
+    dxn, dg1 = rmsnorm_bwd(dh1, s["x"], W["g1"], s["r1"])
+    dx = dx2 + dxn
+    grads = dict(dWqkv=dWqkv, dWo=dWo, dWgu=dWgu, dWd=dWd, dg1=dg1, dg2=dg2, dlogits=dlogits)
+    return dx, grads
