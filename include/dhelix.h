@@ -233,14 +233,19 @@ int dh_si_step(dh_layer* layer, const dh_fwd_args* alpha, const dh_bwd_args* bet
                void* stream_beta, void* stream_comm);
 
 /* ------------------------------------------------------------------------------------------
- * Collective stand-in (Sec. 2.1, "Collective Communication"): a memory-bound local kernel with
- * the payload of the collective it replaces.  DH_COMM_ALLREDUCE: out[i] = sum_r parts[r][i],
- * added in index order in fp32.  parts: host array of n_ranks device pointers, each `elems`
- * elements of `dtype`; out: device, elems elements.  n_blocks: 256-thread blocks the kernel may use
- * (the analogue of a collective library's channel/thread limit, Sec. 5); 0 = enough to cover the
- * payload (at most 2048).  Enqueued on `stream`.
+ * Collective stand-ins (Sec. 2.1, "Collective Communication"): memory-bound local kernels with the
+ * payload of the collective they replace.  parts: host array of n_ranks device pointers, each `elems`
+ * elements of `dtype`; parts[0] is this GPU's own buffer, parts[1..] the frozen peers' buffers.
+ *   DH_COMM_ALLREDUCE      out[i] = sum_r parts[r][i], added in rank order in fp32; out: elems.
+ *   DH_COMM_REDUCESCATTER  the same sum over this rank's slice: parts[0] points at the slice of the own
+ *                          partial this rank keeps, parts[r] at peer r's partial for that slice; out: elems.
+ *                          (Receive side only: the own partial's other slices, which a real
+ *                          reduce-scatter sends away, are not touched.)
+ *   DH_COMM_ALLGATHER      out = [parts[0] | parts[1] | ...]; out: n_ranks*elems.
+ * n_blocks: 256-thread blocks the kernel may use (the analogue of a collective library's
+ * channel/thread limit, Sec. 5); 0 = enough to cover the payload (at most 2048).  Enqueued on `stream`.
  * ------------------------------------------------------------------------------------------ */
-typedef enum { DH_COMM_ALLREDUCE = 0 } dh_comm_kind;
+typedef enum { DH_COMM_ALLREDUCE = 0, DH_COMM_ALLGATHER = 1, DH_COMM_REDUCESCATTER = 2 } dh_comm_kind;
 int dh_comm_standin(int kind, int n_ranks, const void* const* parts, void* out, size_t elems,
                     int dtype, int n_blocks, void* stream);
 
@@ -351,14 +356,51 @@ int dh_moe_combine(int dtype, int T, int H, const void* yp, const int32_t* dest,
 int dh_moe_combine_bwd(int dtype, int T, int H, const void* dy, const void* yp, const int32_t* dest,
                        const float* prob, void* dyp, float* dprob, void* stream);
 
-/* Grouped GEMM over row groups that are stored back to back; group g has group_rows[g] rows
- * (HOST array: the counts depend on the routing, the caller reads them back once per routing).
+/* Grouped GEMM over row groups that are stored back to back; group g has group_rows[g] rows, a DEVICE
+ * int32 array (the counts come out of the routing, no host round trip); max_rows is a host-side upper
+ * bound on any group's rows (e.g. the total row count) that sizes the grid.
  *   mode 0  C[rows_g, dim_b]  = A[rows_g, dim_a]   * B_g[dim_a, dim_b]          (expert forward)
  *   mode 1  C[rows_g, dim_b]  = A[rows_g, dim_a]   * B_g[dim_b, dim_a]^T        (data gradient)
  *   mode 2  C_g[dim_a, dim_b] += A[rows_g, dim_a]^T * B[rows_g, dim_b], float32 (weight gradient)
- * Constraints per group as for dh_gemm; ws as for dh_gemm (sized for the largest group). */
-int dh_gemm_grouped(int dtype, int mode, int n_groups, const int* group_rows, int dim_a, int dim_b,
-                    const void* A, const void* B, void* C, void* ws, size_t ws_bytes, void* stream);
+ * dim_a, dim_b multiples of 8 for DH_BF16; at most 64 groups. */
+int dh_gemm_grouped(int dtype, int mode, int n_groups, const int32_t* group_rows, int max_rows,
+                    int dim_a, int dim_b, const void* A, const void* B, void* C, void* stream);
+
+/* dh_gemm with a bias row: C = opA(A)*opB(B) + bias[N] (bias in the operand dtype; stored results only). */
+int dh_gemm_bias(int dtype, int trans_a, int trans_b, int M, int N, int K, const void* A, const void* B,
+                 const void* bias, void* C, int out_f32_accumulate, void* ws, size_t ws_bytes,
+                 void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Operators of the GPT-style dense layer (Table 2: LayerNorm, GeLU activation, fused
+ * bias-dropout-add with p = 0).
+ * ------------------------------------------------------------------------------------------ */
+/* LayerNorm forward.  If residual != NULL: x_out = x + residual (+ residual_bias[H] if not NULL) is
+ * stored and normalised, else x is.  h = gamma*(x-mu)*rstd + beta; mu[T], rstd[T] float32 (biased
+ * variance). */
+int dh_layernorm_fwd(int dtype, int T, int H, const void* x, const void* residual,
+                     const void* residual_bias, const void* gamma, const void* beta, float eps,
+                     void* x_out, void* h, float* mu, float* rstd, void* stream);
+/* LayerNorm backward: dx = rstd*(gh - mean(gh) - xh*mean(gh*xh)) (+ dres if not NULL), gh = gamma*dy,
+ * xh = (x-mu)*rstd; dgamma[H] += sum_t dy*xh, dbeta[H] += sum_t dy (float32, fixed order). */
+int dh_layernorm_bwd(int dtype, int T, int H, const void* dy, const void* x, const void* gamma,
+                     const float* mu, const float* rstd, const void* dres, void* dx, float* dgamma,
+                     float* dbeta, void* ws, size_t ws_bytes, void* stream);
+size_t dh_layernorm_bwd_ws_bytes(int T, int H);
+
+/* GeLU, tanh form: a = 0.5 f (1 + tanh(sqrt(2/pi)(f + 0.044715 f^3))); backward df = da * gelu'(f).
+ * n elements, n % 8 == 0. */
+int dh_gelu_fwd(int dtype, size_t n, const void* f, void* a, void* stream);
+int dh_gelu_bwd(int dtype, size_t n, const void* f, const void* da, void* df, void* stream);
+
+/* out[t,:] = a[t,:] + b[t,:] + bias[:]: bias-dropout-add with p = 0 and the residual. */
+int dh_bias_residual_add(int dtype, int T, int H, const void* a, const void* b, const void* bias,
+                         void* out, void* stream);
+
+/* out[N] += sum_t x[t,:] in float32, fixed summation order (bias gradients). */
+int dh_colsum(int dtype, int T, int N, const void* x, float* out, void* ws, size_t ws_bytes,
+              void* stream);
+size_t dh_colsum_ws_bytes(int T, int N);
 
 #ifdef __cplusplus
 }

@@ -15,17 +15,38 @@ int dh_set_error(int code, const char* fmt, ...) {
 
 extern "C" const char* dh_last_error(void) { return g_err; }
 
-extern "C" int dh_gemm(int dtype, int trans_a, int trans_b, int M, int N, int K, const void* A, const void* B, void* C,
-                       int out_f32_accumulate, void* ws, size_t ws_bytes, void* stream) {
+extern "C" int dh_gemm_bias(int dtype, int trans_a, int trans_b, int M, int N, int K, const void* A, const void* B,
+                            const void* bias, void* C, int out_f32_accumulate, void* ws, size_t ws_bytes, void* stream) {
   if (M < 0 || N < 0 || K < 0) DH_FAIL(DH_ERR_SHAPE, "gemm: negative dimension");
   if (M > 0 && N > 0 && (!C || (K > 0 && (!A || !B)))) DH_FAIL(DH_ERR_INVALID_ARG, "gemm: null pointer");
+  if (bias && out_f32_accumulate) DH_FAIL(DH_ERR_INVALID_ARG, "gemm: a bias goes with a stored result only");
   if (dtype == DH_F32)
     return dh_launch_gemm_f32(trans_a != 0, trans_b != 0, M, N, K, (const float*)A, (const float*)B, (float*)C,
-                              out_f32_accumulate != 0, (hipStream_t)stream);
+                              out_f32_accumulate != 0, (const float*)bias, (hipStream_t)stream);
   if (dtype == DH_BF16)
     return dh_launch_gemm_bf16(trans_a != 0, trans_b != 0, M, N, K, (const bf16_t*)A, (const bf16_t*)B, C,
-                               out_f32_accumulate != 0, ws, ws_bytes, (hipStream_t)stream);
+                               out_f32_accumulate != 0, (const bf16_t*)bias, ws, ws_bytes, (hipStream_t)stream);
   DH_FAIL(DH_ERR_INVALID_ARG, "gemm: unknown dtype %d", dtype);
+}
+
+extern "C" int dh_gemm(int dtype, int trans_a, int trans_b, int M, int N, int K, const void* A, const void* B, void* C,
+                       int out_f32_accumulate, void* ws, size_t ws_bytes, void* stream) {
+  return dh_gemm_bias(dtype, trans_a, trans_b, M, N, K, A, B, nullptr, C, out_f32_accumulate, ws, ws_bytes, stream);
+}
+
+extern "C" int dh_gemm_grouped(int dtype, int mode, int n_groups, const int32_t* group_rows, int max_rows, int dim_a, int dim_b,
+                               const void* A, const void* B, void* C, void* stream) {
+  if (mode < 0 || mode > 2 || n_groups < 1 || n_groups > 64 || max_rows < 0 || dim_a <= 0 || dim_b <= 0)
+    DH_FAIL(DH_ERR_INVALID_ARG, "gemm_grouped: mode=%d groups=%d max_rows=%d dims=%d,%d", mode, n_groups, max_rows, dim_a, dim_b);
+  if (max_rows == 0) return DH_OK;
+  if (!group_rows || !A || !B || !C) DH_FAIL(DH_ERR_INVALID_ARG, "gemm_grouped: null pointer");
+  if (dtype == DH_F32)
+    return dh_launch_gemm_grouped_f32(mode, n_groups, group_rows, max_rows, dim_a, dim_b, (const float*)A, (const float*)B,
+                                      (float*)C, (hipStream_t)stream);
+  if (dtype == DH_BF16)
+    return dh_launch_gemm_grouped_bf16(mode, n_groups, group_rows, max_rows, dim_a, dim_b, (const bf16_t*)A, (const bf16_t*)B, C,
+                                       (hipStream_t)stream);
+  DH_FAIL(DH_ERR_INVALID_ARG, "gemm_grouped: unknown dtype %d", dtype);
 }
 
 extern "C" size_t dh_gemm_workspace_bytes(int dtype, int trans_a, int trans_b, int M, int N, int K) {

@@ -91,10 +91,15 @@ __device__ __forceinline__ float block256_sum(float v, float* red) {
 
 // ---- internal launchers (host, defined in the .hip files) ------------------------------------
 // All return a dh_status and only enqueue work on `stream`.
+// bias: optional [N] in the operand type, added to a result that is stored (not accumulated).
 int dh_launch_gemm_f32(bool ta, bool tb, int M, int N, int K, const float* A, const float* B, float* C,
-                       bool accumulate, hipStream_t stream);
+                       bool accumulate, const float* bias, hipStream_t stream);
 int dh_launch_gemm_bf16(bool ta, bool tb, int M, int N, int K, const bf16_t* A, const bf16_t* B, void* C,
-                        bool out_f32_accumulate, void* ws, size_t ws_bytes, hipStream_t stream);
+                        bool out_f32_accumulate, const bf16_t* bias, void* ws, size_t ws_bytes, hipStream_t stream);
+int dh_launch_gemm_grouped_f32(int mode, int n_groups, const int32_t* group_rows, int max_rows, int dim_a, int dim_b,
+                               const float* A, const float* B, float* C, hipStream_t stream);
+int dh_launch_gemm_grouped_bf16(int mode, int n_groups, const int32_t* group_rows, int max_rows, int dim_a, int dim_b,
+                                const bf16_t* A, const bf16_t* B, void* C, hipStream_t stream);
 size_t dh_gemm_bf16_ws_bytes(bool ta, bool tb, int M, int N, int K);
 int dh_launch_attn_fwd_f32(int batch, int seq, int nq, int nkv, int d, const float* qkv, float* o, float* lse,
                            hipStream_t stream);

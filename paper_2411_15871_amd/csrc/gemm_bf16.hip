@@ -29,6 +29,7 @@
 // Split-K (grid.y > 1) writes float32 partial tiles to a workspace that a second kernel adds in
 // split order, so results never depend on scheduling (no atomics anywhere).
 // Requirements: N % 8 == 0 and every contiguous operand dimension % 8 == 0 (16-byte chunks).
+#include <algorithm>
 #include "common.h"
 
 #define GB_BK 32
@@ -49,6 +50,9 @@ struct GemmArgs {
   int epi;
   int kt_per_split;  // K tiles handled by one split
   int tiles_m, tiles_n, tiles_per_xcd;
+  const bf16_t* bias;          // optional [N], added before the bf16 store
+  const int32_t* group_rows;   // grouped GEMM: device array of row counts (blockIdx.z = group), else nullptr
+  int group_mode;              // 0/1: groups split M (A and C rows), B per group; 2: groups split K, C per group
 };
 
 // One 16-byte chunk per lane, global -> LDS.  lds_wave_base must be wave-uniform.  Written as inline
@@ -136,6 +140,29 @@ __device__ __forceinline__ bf16x8 frag_km(const bf16_t* tile, int k0, int c16, i
 template <int BM, int BN, int WM, int WN, bool TA, bool TB>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmArgs g) {
   constexpr int NW = WM * WN;
+  if (g.group_rows != nullptr) {
+    // Grouped: the groups' rows lie behind one another; this block's group is blockIdx.z.  The row
+    // counts are data (expert routing), so the extents are fixed up here from device memory and the
+    // grid is sized for the largest possible group; surplus blocks leave at the tile check below.
+    int row0 = 0;
+    for (int i = 0; i < (int)blockIdx.z; i++) row0 += g.group_rows[i];
+    const int rows = g.group_rows[blockIdx.z];
+    if (rows == 0) return;
+    if (g.group_mode == 2) {
+      g.A += (size_t)row0 * g.M;
+      g.B += (size_t)row0 * g.N;
+      g.C = reinterpret_cast<float*>(g.C) + (size_t)blockIdx.z * g.M * g.N;
+      g.K = rows;
+      g.kt_per_split = (rows + GB_BK - 1) / GB_BK;
+    } else {
+      g.A += (size_t)row0 * g.K;
+      g.B += (size_t)blockIdx.z * g.K * g.N;
+      g.C = reinterpret_cast<bf16_t*>(g.C) + (size_t)row0 * g.N;
+      g.M = rows;
+      g.tiles_m = (rows + BM - 1) / BM;
+      g.tiles_per_xcd = (g.tiles_m * g.tiles_n + 7) / 8;
+    }
+  }
   constexpr int WTM = BM / WM, WTN = BN / WN, MT = WTM / 32, NT = WTN / 32;
   constexpr int A_ELEMS = BM * GB_BK, B_ELEMS = BN * GB_BK, STAGE = A_ELEMS + B_ELEMS;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
@@ -146,6 +173,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmArgs g) {
   const int wm0 = (wave / WN) * WTM, wn0 = (wave % WN) * WTN;
 
   // XCD-aware tile mapping (see the header comment)
+  if ((int)(blockIdx.x >> 3) >= g.tiles_per_xcd) return;  // only in grouped launches (grid sized for the largest group)
   const int logical = (blockIdx.x & 7) * g.tiles_per_xcd + (blockIdx.x >> 3);
   if (logical >= g.tiles_m * g.tiles_n) return;
   int tm, tn;
@@ -294,6 +322,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmArgs g) {
         const size_t o = (size_t)row * g.N + col;
         f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
         if (g.epi == EPI_STORE_BF16) {
+          if (g.bias != nullptr) {
+            const bf16x4 bb = *reinterpret_cast<const bf16x4*>(g.bias + col);
+            v += f32x4{(float)bb[0], (float)bb[1], (float)bb[2], (float)bb[3]};
+          }
           bf16x4 b = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
           *reinterpret_cast<bf16x4*>(Cb + o) = b;
         } else if (g.epi == EPI_ACC_F32) {
@@ -307,12 +339,17 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmArgs g) {
 }
 
 // Adds the split-K partials in split order; writes bf16 or accumulates into float32.
-__global__ void splitk_reduce_kernel(const float* __restrict__ part, int splits, size_t mn, void* __restrict__ C, int epi) {
+__global__ void splitk_reduce_kernel(const float* __restrict__ part, int splits, size_t mn, void* __restrict__ C, int epi,
+                                     const bf16_t* __restrict__ bias, int N) {
   size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
   if (i >= mn) return;
   f32x4 s = *reinterpret_cast<const f32x4*>(part + i);
   for (int z = 1; z < splits; z++) s += *reinterpret_cast<const f32x4*>(part + (size_t)z * mn + i);
   if (epi == EPI_STORE_BF16) {
+    if (bias != nullptr) {
+      const bf16x4 bb = *reinterpret_cast<const bf16x4*>(bias + i % N);
+      s += f32x4{(float)bb[0], (float)bb[1], (float)bb[2], (float)bb[3]};
+    }
     bf16x4 o = {(bf16_t)s[0], (bf16_t)s[1], (bf16_t)s[2], (bf16_t)s[3]};
     *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16_t*>(C) + i) = o;
   } else {
@@ -371,7 +408,7 @@ size_t dh_gemm_bf16_ws_bytes(bool ta, bool tb, int M, int N, int K) {
 }
 
 template <int BM, int BN, int WM, int WN, bool TA, bool TB>
-static int launch_cfg(GemmArgs g, int splits, hipStream_t stream) {
+static int launch_cfg(GemmArgs g, int splits, hipStream_t stream, int n_groups = 1) {
   constexpr size_t LDS_BYTES = GB_STAGES * (size_t)(BM + BN) * GB_BK * sizeof(bf16_t);
   static bool attr_set = false;
   if (!attr_set) {
@@ -382,24 +419,25 @@ static int launch_cfg(GemmArgs g, int splits, hipStream_t stream) {
   g.tiles_m = (g.M + BM - 1) / BM;
   g.tiles_n = (g.N + BN - 1) / BN;
   g.tiles_per_xcd = (g.tiles_m * g.tiles_n + 7) / 8;
-  dim3 grid(g.tiles_per_xcd * 8, splits);
+  dim3 grid(g.tiles_per_xcd * 8, splits, n_groups);
   gemm_bf16_kernel<BM, BN, WM, WN, TA, TB><<<grid, 64 * WM * WN, LDS_BYTES, stream>>>(g);
   DH_LAUNCH_CHECK();
   return DH_OK;
 }
 
 template <bool TA, bool TB>
-static int launch_layout(const GemmArgs& g, const GemmPlan& p, hipStream_t stream) {
-  if (p.cfg == 0) return launch_cfg<256, 256, 2, 4, TA, TB>(g, p.splits, stream);
-  return launch_cfg<128, 128, 2, 2, TA, TB>(g, p.splits, stream);
+static int launch_layout(const GemmArgs& g, const GemmPlan& p, hipStream_t stream, int n_groups = 1) {
+  if (p.cfg == 0) return launch_cfg<256, 256, 2, 4, TA, TB>(g, p.splits, stream, n_groups);
+  return launch_cfg<128, 128, 2, 2, TA, TB>(g, p.splits, stream, n_groups);
 }
 
 int dh_launch_gemm_bf16(bool ta, bool tb, int M, int N, int K, const bf16_t* A, const bf16_t* B, void* C,
-                        bool out_f32_accumulate, void* ws, size_t ws_bytes, hipStream_t stream) {
+                        bool out_f32_accumulate, const bf16_t* bias, void* ws, size_t ws_bytes, hipStream_t stream) {
   if (M < 0 || N < 0 || K < 0) DH_FAIL(DH_ERR_SHAPE, "gemm: negative dimension");
   if (N % 8 || (ta ? M : K) % 8 || (tb ? K : N) % 8)
     DH_FAIL(DH_ERR_SHAPE, "gemm (bf16): N and the contiguous operand dimensions must be multiples of 8 (M=%d N=%d K=%d ta=%d tb=%d)", M, N, K, ta, tb);
   if (ta && tb) DH_FAIL(DH_ERR_UNSUPPORTED, "gemm (bf16): trans_a with trans_b is not used by the layer and not built");
+  if (bias && out_f32_accumulate) DH_FAIL(DH_ERR_INVALID_ARG, "gemm (bf16): a bias goes with a bf16 result only");
   if (M == 0 || N == 0) return DH_OK;
   if ((long long)M * N >= (1ll << 40) || (long long)M * K >= (1ll << 40)) DH_FAIL(DH_ERR_SHAPE, "gemm: matrix too large");
   GemmPlan p = choose_plan(M, N, K, ws ? ws_bytes : 0);
@@ -407,6 +445,7 @@ int dh_launch_gemm_bf16(bool ta, bool tb, int M, int N, int K, const bf16_t* A, 
   g.M = M; g.N = N; g.K = K; g.A = A; g.B = B;
   g.kt_per_split = p.kt_per_split;
   g.tiles_m = g.tiles_n = g.tiles_per_xcd = 0;
+  g.bias = bias; g.group_rows = nullptr; g.group_mode = 0;
   const int final_epi = out_f32_accumulate ? EPI_ACC_F32 : EPI_STORE_BF16;
   if (p.splits > 1) { g.C = ws; g.epi = EPI_PARTIAL_F32; } else { g.C = C; g.epi = final_epi; }
   int rc;
@@ -416,8 +455,32 @@ int dh_launch_gemm_bf16(bool ta, bool tb, int M, int N, int K, const bf16_t* A, 
   if (rc != DH_OK) return rc;
   if (p.splits > 1) {
     const size_t mn = (size_t)M * N;  // multiple of 8 because N is
-    splitk_reduce_kernel<<<(unsigned)((mn / 4 + 255) / 256), 256, 0, stream>>>((const float*)ws, p.splits, mn, C, final_epi);
+    splitk_reduce_kernel<<<(unsigned)((mn / 4 + 255) / 256), 256, 0, stream>>>((const float*)ws, p.splits, mn, C, final_epi, bias, N);
     DH_LAUNCH_CHECK();
   }
   return DH_OK;
+}
+
+// Grouped GEMM with device-side row counts (expert routing is data): group z owns group_rows[z] consecutive
+// rows, max_rows bounds any group (the grid is sized for it).  mode 0: C[rows,dim_b] = A[rows,dim_a] B_z[dim_a,dim_b];
+// mode 1: C[rows,dim_b] = A[rows,dim_a] B_z[dim_b,dim_a]^T; mode 2: C_z[dim_a,dim_b] += A[rows,dim_a]^T B[rows,dim_b]
+// (float32).  No split-K: every group is one launch slice of the same grid.
+int dh_launch_gemm_grouped_bf16(int mode, int n_groups, const int32_t* group_rows, int max_rows, int dim_a, int dim_b,
+                                const bf16_t* A, const bf16_t* B, void* C, hipStream_t stream) {
+  if (dim_a % 8 || dim_b % 8) DH_FAIL(DH_ERR_SHAPE, "gemm_grouped (bf16): feature dimensions must be multiples of 8 (%d, %d)", dim_a, dim_b);
+  if (max_rows == 0) return DH_OK;
+  GemmArgs g;
+  g.A = A; g.B = B; g.C = C;
+  g.bias = nullptr; g.group_rows = group_rows; g.group_mode = mode;
+  g.tiles_m = g.tiles_n = g.tiles_per_xcd = 0;
+  const int avg = std::max(1, max_rows / n_groups);
+  GemmPlan p;
+  if (mode == 2) { g.M = dim_a; g.N = dim_b; g.K = max_rows; p = choose_plan(dim_a, dim_b, avg, 0); }
+  else { g.M = max_rows; g.N = dim_b; g.K = dim_a; p = choose_plan(avg, dim_b, dim_a, 0); }
+  p.splits = 1;
+  g.kt_per_split = (g.K + GB_BK - 1) / GB_BK;
+  g.epi = mode == 2 ? EPI_ACC_F32 : EPI_STORE_BF16;
+  if (mode == 0) return launch_layout<false, false>(g, p, stream, n_groups);
+  if (mode == 1) return launch_layout<false, true>(g, p, stream, n_groups);
+  return launch_layout<true, false>(g, p, stream, n_groups);
 }

@@ -195,8 +195,8 @@ extern "C" size_t dh_layer_workspace_bytes(const dh_layer* L, int kind) {
 static int gemm(const dh_layer* L, bool ta, bool tb, int M, int N, int K, const void* A, const void* B, void* C, bool acc,
                 void* ws, size_t ws_bytes, hipStream_t s) {
   if (L->c.dtype == DH_BF16)
-    return dh_launch_gemm_bf16(ta, tb, M, N, K, (const bf16_t*)A, (const bf16_t*)B, C, acc, ws, ws_bytes, s);
-  return dh_launch_gemm_f32(ta, tb, M, N, K, (const float*)A, (const float*)B, (float*)C, acc, s);
+    return dh_launch_gemm_bf16(ta, tb, M, N, K, (const bf16_t*)A, (const bf16_t*)B, C, acc, nullptr, ws, ws_bytes, s);
+  return dh_launch_gemm_f32(ta, tb, M, N, K, (const float*)A, (const float*)B, (float*)C, acc, nullptr, s);
 }
 
 static int allreduce(const dh_layer* L, const void* own, const void* peers, void* out, hipStream_t s) {

@@ -243,34 +243,3 @@ extern "C" int dh_moe_combine_bwd(int dtype, int T, int H, const void* dy, const
   DH_LAUNCH_CHECK();
   return DH_OK;
 }
-
-// Grouped GEMM (Group-GEMM operator base): one GEMM per local expert over that expert's rows.
-//   mode 0 (forward)   C[rows_g, N] = A[rows_g, K]   * B_g[K, N]
-//   mode 1 (dgrad)     C[rows_g, N] = A[rows_g, K]   * B_g[N, K]^T
-//   mode 2 (wgrad)     C_g[M, N]   += A[rows_g, M]^T * B[rows_g, N]     (float32 accumulate)
-// group_rows is a HOST array: the row counts are data dependent, the caller reads them back once per routing.
-extern "C" int dh_gemm_grouped(int dtype, int mode, int n_groups, const int* group_rows, int dim_a, int dim_b, const void* A,
-                               const void* B, void* C, void* ws, size_t ws_bytes, void* stream) {
-  if (mode < 0 || mode > 2 || n_groups < 1 || !group_rows || dim_a <= 0 || dim_b <= 0) DH_FAIL(DH_ERR_INVALID_ARG, "gemm_grouped: bad arguments");
-  const size_t es = dh_elem_size(dtype);
-  size_t row0 = 0;
-  for (int g = 0; g < n_groups; g++) {
-    const int rows = group_rows[g];
-    if (rows < 0) DH_FAIL(DH_ERR_INVALID_ARG, "gemm_grouped: negative row count");
-    if (rows == 0) continue;  // nothing to write; a weight gradient gets no contribution
-    int rc = DH_OK;
-    if (mode == 0) {  // dim_a = K, dim_b = N
-      rc = dh_gemm(dtype, 0, 0, rows, dim_b, dim_a, (const char*)A + row0 * dim_a * es, (const char*)B + (size_t)g * dim_a * dim_b * es,
-                   (char*)C + row0 * dim_b * es, 0, ws, ws_bytes, stream);
-    } else if (mode == 1) {  // dim_a = K (columns of A), dim_b = N (columns of C); B_g is [N, K]
-      rc = dh_gemm(dtype, 0, 1, rows, dim_b, dim_a, (const char*)A + row0 * dim_a * es, (const char*)B + (size_t)g * dim_a * dim_b * es,
-                   (char*)C + row0 * dim_b * es, 0, ws, ws_bytes, stream);
-    } else {  // dim_a = M (columns of A), dim_b = N (columns of B); C_g is [M, N] float32
-      rc = dh_gemm(dtype, 1, 0, dim_a, dim_b, rows, (const char*)A + row0 * dim_a * es, (const char*)B + row0 * dim_b * es,
-                   (char*)C + (size_t)g * dim_a * dim_b * sizeof(float), 1, ws, ws_bytes, stream);
-    }
-    if (rc != DH_OK) return rc;
-    row0 += rows;
-  }
-  return DH_OK;
-}

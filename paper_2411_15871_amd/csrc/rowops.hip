@@ -152,12 +152,12 @@ __global__ void colsum_group_kernel(const float* __restrict__ partial, float* __
   out[(size_t)blockIdx.y * H + col] = s;
 }
 
-// dst[col] += sum_b partial[b][col], b ascending.
-__global__ void colsum_accumulate_kernel(const float* __restrict__ partial, float* __restrict__ dst, int nblk, int H) {
+// dst[col] += sum_b partial[b*ld + col], b ascending.
+__global__ void colsum_accumulate_kernel(const float* __restrict__ partial, float* __restrict__ dst, int nblk, int H, int ld) {
   int col = blockIdx.x * blockDim.x + threadIdx.x;
   if (col >= H) return;
   float s = 0.f;
-  for (int b = 0; b < nblk; b++) s += partial[(size_t)b * H + col];
+  for (int b = 0; b < nblk; b++) s += partial[(size_t)b * ld + col];
   dst[col] += s;
 }
 
@@ -301,7 +301,7 @@ static int rmsnorm_bwd_t(int rows, int H, const void* dy, const void* x, const v
   float* grouped = partial + (size_t)nblk * H;
   colsum_group_kernel<<<dim3((H + 255) / 256, ngrp), 256, 0, s>>>(partial, grouped, nblk, H);
   DH_LAUNCH_CHECK();
-  colsum_accumulate_kernel<<<(H + 255) / 256, 256, 0, s>>>(grouped, dgamma, ngrp, H);
+  colsum_accumulate_kernel<<<(H + 255) / 256, 256, 0, s>>>(grouped, dgamma, ngrp, H, H);
   DH_LAUNCH_CHECK();
   return DH_OK;
 }
@@ -381,6 +381,341 @@ extern "C" int dh_add(int dtype, size_t n, const void* a, const void* b, void* o
     add_kernel<bf16_t><<<g, bl, 0, (hipStream_t)stream>>>((const bf16_t*)a, (const bf16_t*)b, (bf16_t*)out, n8);
   else
     add_kernel<float><<<g, bl, 0, (hipStream_t)stream>>>((const float*)a, (const float*)b, (float*)out, n8);
+  DH_LAUNCH_CHECK();
+  return DH_OK;
+}
+
+// ------------------------------------------------------------------------------------ LayerNorm fwd
+// As the RMSNorm kernel, with mean removal and a shift: optional fused x_out = x + res (+ bias), then
+// mu = mean(x_out), rstd = (mean((x_out-mu)^2) + eps)^(-1/2) (two passes over the registers, so the
+// variance is formed from centred values), h = gamma*(x_out-mu)*rstd + beta.
+template <typename T, int NCH>
+__global__ __launch_bounds__(ROW_THREADS) void layernorm_fwd_kernel(const T* __restrict__ x, const T* __restrict__ res,
+                                                                    const T* __restrict__ res_bias, const T* __restrict__ gamma,
+                                                                    const T* __restrict__ beta, float eps, T* __restrict__ x_out,
+                                                                    T* __restrict__ h, float* __restrict__ mu_out,
+                                                                    float* __restrict__ rstd, int H) {
+  __shared__ float red[8];
+  const size_t row = blockIdx.x;
+  Vec8<T> v[NCH];
+  float sum = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; c++) {
+    int col = (threadIdx.x + ROW_THREADS * c) * 8;
+    if (col < H) {
+      v[c].load(x + row * H + col);
+      if (res != nullptr) {
+        Vec8<T> r;
+        r.load(res + row * H + col);
+        if (res_bias != nullptr) {
+          Vec8<T> bb;
+          bb.load(res_bias + col);
+#pragma unroll
+          for (int i = 0; i < 8; i++) r.v[i] += bb.v[i];
+        }
+#pragma unroll
+        for (int i = 0; i < 8; i++) v[c].v[i] = to_f32(from_f32<T>(v[c].v[i] + r.v[i]));
+        v[c].store(x_out + row * H + col);
+      }
+#pragma unroll
+      for (int i = 0; i < 8; i++) sum += v[c].v[i];
+    }
+  }
+  const float mu = block256_sum(sum, red) / (float)H;
+  float ss = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; c++) {
+    int col = (threadIdx.x + ROW_THREADS * c) * 8;
+    if (col < H) {
+#pragma unroll
+      for (int i = 0; i < 8; i++) {
+        v[c].v[i] -= mu;
+        ss += v[c].v[i] * v[c].v[i];
+      }
+    }
+  }
+  ss = block256_sum(ss, red);
+  const float r = 1.0f / sqrtf(ss / (float)H + eps);
+  if (threadIdx.x == 0) { mu_out[row] = mu; rstd[row] = r; }
+#pragma unroll
+  for (int c = 0; c < NCH; c++) {
+    int col = (threadIdx.x + ROW_THREADS * c) * 8;
+    if (col < H) {
+      Vec8<T> g, b;
+      g.load(gamma + col);
+      b.load(beta + col);
+#pragma unroll
+      for (int i = 0; i < 8; i++) g.v[i] = g.v[i] * v[c].v[i] * r + b.v[i];
+      g.store(h + row * H + col);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------ LayerNorm bwd
+// dx = rstd*(gh - mean(gh) - xh*mean(gh*xh)) (+ dres), gh = gamma*dy, xh = (x-mu)*rstd.  Per block one
+// partial row [dgamma | dbeta] of 2H floats, reduced in fixed order by the column-sum kernels.
+template <typename T, int NCH>
+__global__ __launch_bounds__(ROW_THREADS) void layernorm_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                                    const T* __restrict__ gamma, const float* __restrict__ mu,
+                                                                    const float* __restrict__ rstd, const T* __restrict__ dres,
+                                                                    T* __restrict__ dx, float* __restrict__ partial, int rows, int H) {
+  __shared__ float red[8];
+  Vec8<T> g[NCH];
+  float dg[NCH][8], db[NCH][8];
+#pragma unroll
+  for (int c = 0; c < NCH; c++) {
+    int col = (threadIdx.x + ROW_THREADS * c) * 8;
+    if (col < H) g[c].load(gamma + col);
+#pragma unroll
+    for (int i = 0; i < 8; i++) dg[c][i] = db[c][i] = 0.f;
+  }
+  const size_t row0 = (size_t)blockIdx.x * NORM_BWD_RPB;
+  const int nrows = min(NORM_BWD_RPB, rows - (int)row0);
+  for (int rr = 0; rr < nrows; rr++) {
+    const size_t row = row0 + rr;
+    const float r = rstd[row], m = mu[row];
+    Vec8<T> gh[NCH], xh[NCH];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int c = 0; c < NCH; c++) {
+      int col = (threadIdx.x + ROW_THREADS * c) * 8;
+      if (col < H) {
+        gh[c].load(dy + row * H + col);
+        xh[c].load(x + row * H + col);
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+          xh[c].v[i] = (xh[c].v[i] - m) * r;
+          dg[c][i] += gh[c].v[i] * xh[c].v[i];
+          db[c][i] += gh[c].v[i];
+          gh[c].v[i] *= g[c].v[i];
+          s1 += gh[c].v[i];
+          s2 += gh[c].v[i] * xh[c].v[i];
+        }
+      }
+    }
+    s1 = block256_sum(s1, red) / (float)H;
+    s2 = block256_sum(s2, red) / (float)H;
+#pragma unroll
+    for (int c = 0; c < NCH; c++) {
+      int col = (threadIdx.x + ROW_THREADS * c) * 8;
+      if (col < H) {
+        Vec8<T> o;
+#pragma unroll
+        for (int i = 0; i < 8; i++) o.v[i] = r * (gh[c].v[i] - s1 - xh[c].v[i] * s2);
+        if (dres != nullptr) {
+          Vec8<T> rs;
+          rs.load(dres + row * H + col);
+#pragma unroll
+          for (int i = 0; i < 8; i++) o.v[i] += rs.v[i];
+        }
+        o.store(dx + row * H + col);
+      }
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < NCH; c++) {
+    int col = (threadIdx.x + ROW_THREADS * c) * 8;
+    if (col < H) {
+      float4* p = reinterpret_cast<float4*>(partial + (size_t)blockIdx.x * 2 * H + col);
+      p[0] = make_float4(dg[c][0], dg[c][1], dg[c][2], dg[c][3]);
+      p[1] = make_float4(dg[c][4], dg[c][5], dg[c][6], dg[c][7]);
+      float4* q = reinterpret_cast<float4*>(partial + (size_t)blockIdx.x * 2 * H + H + col);
+      q[0] = make_float4(db[c][0], db[c][1], db[c][2], db[c][3]);
+      q[1] = make_float4(db[c][4], db[c][5], db[c][6], db[c][7]);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------ GeLU (tanh form)
+__device__ __forceinline__ float gelu_tanh_inner(float x) { return 0.7978845608028654f * (x + 0.044715f * x * x * x); }
+
+template <typename T>
+__global__ void gelu_fwd_kernel(const T* __restrict__ f, T* __restrict__ a, size_t n8) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n8) return;
+  Vec8<T> x;
+  x.load(f + idx * 8);
+#pragma unroll
+  for (int i = 0; i < 8; i++) x.v[i] = 0.5f * x.v[i] * (1.0f + tanhf(gelu_tanh_inner(x.v[i])));
+  x.store(a + idx * 8);
+}
+
+template <typename T>
+__global__ void gelu_bwd_kernel(const T* __restrict__ f, const T* __restrict__ da, T* __restrict__ df, size_t n8) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n8) return;
+  Vec8<T> x, d;
+  x.load(f + idx * 8);
+  d.load(da + idx * 8);
+#pragma unroll
+  for (int i = 0; i < 8; i++) {
+    const float v = x.v[i], t = tanhf(gelu_tanh_inner(v));
+    d.v[i] *= 0.5f * (1.0f + t) + 0.5f * v * (1.0f - t * t) * 0.7978845608028654f * (1.0f + 3.0f * 0.044715f * v * v);
+  }
+  d.store(df + idx * 8);
+}
+
+// ------------------------------------------------------------------------------------ bias + residual, column sums
+// out[t,:] = a[t,:] + b[t,:] + bias[:]
+template <typename T>
+__global__ void bias_residual_add_kernel(const T* __restrict__ a, const T* __restrict__ b, const T* __restrict__ bias,
+                                         T* __restrict__ out, size_t n8, int chunks) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n8) return;
+  Vec8<T> x, y, z;
+  x.load(a + idx * 8);
+  y.load(b + idx * 8);
+  z.load(bias + (idx % chunks) * 8);
+#pragma unroll
+  for (int i = 0; i < 8; i++) x.v[i] += y.v[i] + z.v[i];
+  x.store(out + idx * 8);
+}
+
+// partial[by][col] = sum of rows by*COLSUM_ROWS .. +COLSUM_ROWS-1 of x (ascending); a thread owns 8 columns.
+#define COLSUM_ROWS 32
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_rows_kernel(const T* __restrict__ x, float* __restrict__ partial, int rows, int N) {
+  const int col = (blockIdx.x * 256 + threadIdx.x) * 8;
+  if (col >= N) return;
+  const int r0 = blockIdx.y * COLSUM_ROWS, r1 = min(rows, r0 + COLSUM_ROWS);
+  float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int r = r0; r < r1; r++) {
+    Vec8<T> v;
+    v.load(x + (size_t)r * N + col);
+#pragma unroll
+    for (int i = 0; i < 8; i++) s[i] += v.v[i];
+  }
+  float4* p = reinterpret_cast<float4*>(partial + (size_t)blockIdx.y * N + col);
+  p[0] = make_float4(s[0], s[1], s[2], s[3]);
+  p[1] = make_float4(s[4], s[5], s[6], s[7]);
+}
+
+// ------------------------------------------------------------------------------------ host side (GPT-style operators)
+extern "C" int dh_layernorm_fwd(int dtype, int T, int H, const void* x, const void* residual, const void* residual_bias,
+                                const void* gamma, const void* beta, float eps, void* x_out, void* h, float* mu, float* rstd,
+                                void* stream) {
+  if (T < 0 || H <= 0 || H % 8) DH_FAIL(DH_ERR_SHAPE, "layernorm_fwd: T=%d H=%d (H must be a positive multiple of 8)", T, H);
+  if (T == 0) return DH_OK;
+  if (!x || !gamma || !beta || !h || !mu || !rstd || (residual && !x_out) || (residual_bias && !residual))
+    DH_FAIL(DH_ERR_INVALID_ARG, "layernorm_fwd: null pointer (a residual bias needs a residual)");
+  const int nch = nch_for(H);
+  hipStream_t s = (hipStream_t)stream;
+#define GO(TT, N)                                                                                                           \
+  layernorm_fwd_kernel<TT, N><<<T, ROW_THREADS, 0, s>>>((const TT*)x, (const TT*)residual, (const TT*)residual_bias,         \
+                                                        (const TT*)gamma, (const TT*)beta, eps, (TT*)x_out, (TT*)h, mu, rstd, H)
+#define GO2(N) do { if (dtype == DH_BF16) GO(bf16_t, N); else GO(float, N); } while (0)
+  switch (nch) {
+    case 1: GO2(1); break;
+    case 2: GO2(2); break;
+    case 4: GO2(4); break;
+    case 8: GO2(8); break;
+    default: DH_FAIL(DH_ERR_SHAPE, "layernorm: hidden %d too large (max 16384)", H);
+  }
+#undef GO2
+#undef GO
+  DH_LAUNCH_CHECK();
+  return DH_OK;
+}
+
+extern "C" size_t dh_layernorm_bwd_ws_bytes(int T, int H) { return dh_rmsnorm_bwd_ws_bytes(T, 2 * H); }
+
+extern "C" int dh_layernorm_bwd(int dtype, int T, int H, const void* dy, const void* x, const void* gamma, const float* mu,
+                                const float* rstd, const void* dres, void* dx, float* dgamma, float* dbeta, void* ws,
+                                size_t ws_bytes, void* stream) {
+  if (T < 0 || H <= 0 || H % 8) DH_FAIL(DH_ERR_SHAPE, "layernorm_bwd: T=%d H=%d (H must be a positive multiple of 8)", T, H);
+  if (T == 0) return DH_OK;
+  if (!dy || !x || !gamma || !mu || !rstd || !dx || !dgamma || !dbeta) DH_FAIL(DH_ERR_INVALID_ARG, "layernorm_bwd: null pointer");
+  if (!ws || ws_bytes < dh_layernorm_bwd_ws_bytes(T, H))
+    DH_FAIL(DH_ERR_WORKSPACE_TOO_SMALL, "layernorm_bwd: workspace %zu < %zu bytes", ws_bytes, dh_layernorm_bwd_ws_bytes(T, H));
+  const int nch = nch_for(H);
+  const int nblk = (T + NORM_BWD_RPB - 1) / NORM_BWD_RPB;
+  float* partial = (float*)ws;
+  hipStream_t s = (hipStream_t)stream;
+#define GO(TT, N)                                                                                                          \
+  layernorm_bwd_kernel<TT, N><<<nblk, ROW_THREADS, 0, s>>>((const TT*)dy, (const TT*)x, (const TT*)gamma, mu, rstd,         \
+                                                           (const TT*)dres, (TT*)dx, partial, T, H)
+#define GO2(N) do { if (dtype == DH_BF16) GO(bf16_t, N); else GO(float, N); } while (0)
+  switch (nch) {
+    case 1: GO2(1); break;
+    case 2: GO2(2); break;
+    case 4: GO2(4); break;
+    case 8: GO2(8); break;
+    default: DH_FAIL(DH_ERR_SHAPE, "layernorm: hidden %d too large (max 16384)", H);
+  }
+#undef GO2
+#undef GO
+  DH_LAUNCH_CHECK();
+  const int ngrp = (nblk + COLSUM_GROUP - 1) / COLSUM_GROUP;
+  float* grouped = partial + (size_t)nblk * 2 * H;
+  colsum_group_kernel<<<dim3((2 * H + 255) / 256, ngrp), 256, 0, s>>>(partial, grouped, nblk, 2 * H);
+  DH_LAUNCH_CHECK();
+  colsum_accumulate_kernel<<<(H + 255) / 256, 256, 0, s>>>(grouped, dgamma, ngrp, H, 2 * H);
+  DH_LAUNCH_CHECK();
+  colsum_accumulate_kernel<<<(H + 255) / 256, 256, 0, s>>>(grouped + H, dbeta, ngrp, H, 2 * H);
+  DH_LAUNCH_CHECK();
+  return DH_OK;
+}
+
+extern "C" int dh_gelu_fwd(int dtype, size_t n, const void* f, void* a, void* stream) {
+  if (n % 8) DH_FAIL(DH_ERR_SHAPE, "gelu_fwd: element count %zu must be a multiple of 8", n);
+  if (n == 0) return DH_OK;
+  if (!f || !a) DH_FAIL(DH_ERR_INVALID_ARG, "gelu_fwd: null pointer");
+  const size_t n8 = n / 8;
+  dim3 g((unsigned)((n8 + 255) / 256)), b(256);
+  if (dtype == DH_BF16) gelu_fwd_kernel<bf16_t><<<g, b, 0, (hipStream_t)stream>>>((const bf16_t*)f, (bf16_t*)a, n8);
+  else gelu_fwd_kernel<float><<<g, b, 0, (hipStream_t)stream>>>((const float*)f, (float*)a, n8);
+  DH_LAUNCH_CHECK();
+  return DH_OK;
+}
+
+extern "C" int dh_gelu_bwd(int dtype, size_t n, const void* f, const void* da, void* df, void* stream) {
+  if (n % 8) DH_FAIL(DH_ERR_SHAPE, "gelu_bwd: element count %zu must be a multiple of 8", n);
+  if (n == 0) return DH_OK;
+  if (!f || !da || !df) DH_FAIL(DH_ERR_INVALID_ARG, "gelu_bwd: null pointer");
+  const size_t n8 = n / 8;
+  dim3 g((unsigned)((n8 + 255) / 256)), b(256);
+  if (dtype == DH_BF16) gelu_bwd_kernel<bf16_t><<<g, b, 0, (hipStream_t)stream>>>((const bf16_t*)f, (const bf16_t*)da, (bf16_t*)df, n8);
+  else gelu_bwd_kernel<float><<<g, b, 0, (hipStream_t)stream>>>((const float*)f, (const float*)da, (float*)df, n8);
+  DH_LAUNCH_CHECK();
+  return DH_OK;
+}
+
+extern "C" int dh_bias_residual_add(int dtype, int T, int H, const void* a, const void* b, const void* bias, void* out,
+                                    void* stream) {
+  if (T < 0 || H <= 0 || H % 8) DH_FAIL(DH_ERR_SHAPE, "bias_residual_add: T=%d H=%d (H must be a positive multiple of 8)", T, H);
+  if (T == 0) return DH_OK;
+  if (!a || !b || !bias || !out) DH_FAIL(DH_ERR_INVALID_ARG, "bias_residual_add: null pointer");
+  const size_t n8 = (size_t)T * (H / 8);
+  dim3 g((unsigned)((n8 + 255) / 256)), bl(256);
+  if (dtype == DH_BF16)
+    bias_residual_add_kernel<bf16_t><<<g, bl, 0, (hipStream_t)stream>>>((const bf16_t*)a, (const bf16_t*)b, (const bf16_t*)bias, (bf16_t*)out, n8, H / 8);
+  else
+    bias_residual_add_kernel<float><<<g, bl, 0, (hipStream_t)stream>>>((const float*)a, (const float*)b, (const float*)bias, (float*)out, n8, H / 8);
+  DH_LAUNCH_CHECK();
+  return DH_OK;
+}
+
+extern "C" size_t dh_colsum_ws_bytes(int T, int N) {
+  const size_t nblk = (size_t)(T + COLSUM_ROWS - 1) / COLSUM_ROWS, ngrp = (nblk + COLSUM_GROUP - 1) / COLSUM_GROUP;
+  return (nblk + ngrp) * N * sizeof(float);
+}
+
+extern "C" int dh_colsum(int dtype, int T, int N, const void* x, float* out, void* ws, size_t ws_bytes, void* stream) {
+  if (T < 0 || N <= 0 || N % 8) DH_FAIL(DH_ERR_SHAPE, "colsum: T=%d N=%d (N must be a positive multiple of 8)", T, N);
+  if (T == 0) return DH_OK;
+  if (!x || !out) DH_FAIL(DH_ERR_INVALID_ARG, "colsum: null pointer");
+  if (!ws || ws_bytes < dh_colsum_ws_bytes(T, N)) DH_FAIL(DH_ERR_WORKSPACE_TOO_SMALL, "colsum: workspace %zu < %zu bytes", ws_bytes, dh_colsum_ws_bytes(T, N));
+  const int nblk = (T + COLSUM_ROWS - 1) / COLSUM_ROWS, ngrp = (nblk + COLSUM_GROUP - 1) / COLSUM_GROUP;
+  float* partial = (float*)ws;
+  float* grouped = partial + (size_t)nblk * N;
+  hipStream_t s = (hipStream_t)stream;
+  dim3 g((N / 8 + 255) / 256, nblk);
+  if (dtype == DH_BF16) colsum_rows_kernel<bf16_t><<<g, 256, 0, s>>>((const bf16_t*)x, partial, T, N);
+  else colsum_rows_kernel<float><<<g, 256, 0, s>>>((const float*)x, partial, T, N);
+  DH_LAUNCH_CHECK();
+  colsum_group_kernel<<<dim3((N + 255) / 256, ngrp), 256, 0, s>>>(partial, grouped, nblk, N);
+  DH_LAUNCH_CHECK();
+  colsum_accumulate_kernel<<<(N + 255) / 256, 256, 0, s>>>(grouped, out, ngrp, N, N);
   DH_LAUNCH_CHECK();
   return DH_OK;
 }

@@ -1,6 +1,7 @@
-// One-GPU stand-ins for the collectives of the layer's critical path (tensor-parallel all-reduce).
-// A stand-in moves exactly the collective's payload through HBM: it reads the n_ranks partial
-// buffers and writes their sum.  It is meant to run on a stream restricted to a few compute units,
+// One-GPU stand-ins for the collectives of the layer's critical path (tensor-parallel all-reduce,
+// sequence-parallel all-gather and reduce-scatter).
+// A stand-in moves the collective's payload through HBM: the reductions read the n_ranks partial
+// buffers and write their sum, the all-gather copies the n_ranks shards behind one another.  It is meant to run on a stream restricted to a few compute units,
 // so the grid is small and grid-strided: each thread streams 16-byte vectors.
 #include "common.h"
 
@@ -25,9 +26,24 @@ __global__ __launch_bounds__(256) void allreduce_kernel(PartPtrs parts, int n_ra
   }
 }
 
+// out = [parts[0] | parts[1] | ... ], each part n8 vectors of 8 elements.
+template <typename T>
+__global__ __launch_bounds__(256) void allgather_kernel(PartPtrs parts, int n_ranks, T* __restrict__ out, size_t n8) {
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  const size_t total = n8 * n_ranks;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+    const int r = (int)(i / n8);
+    const size_t j = i - (size_t)r * n8;
+    Vec8<T> v;
+    v.load((const T*)parts.p[r] + j * 8);
+    v.store(out + i * 8);
+  }
+}
+
 extern "C" int dh_comm_standin(int kind, int n_ranks, const void* const* parts, void* out, size_t elems, int dtype,
                                int n_blocks, void* stream) {
-  if (kind != DH_COMM_ALLREDUCE) DH_FAIL(DH_ERR_UNSUPPORTED, "comm_standin: kind %d not supported", kind);
+  if (kind != DH_COMM_ALLREDUCE && kind != DH_COMM_ALLGATHER && kind != DH_COMM_REDUCESCATTER)
+    DH_FAIL(DH_ERR_UNSUPPORTED, "comm_standin: kind %d not supported", kind);
   if (n_ranks < 1 || n_ranks > DH_MAX_RANKS) DH_FAIL(DH_ERR_INVALID_ARG, "comm_standin: n_ranks %d outside 1..%d", n_ranks, DH_MAX_RANKS);
   if (elems % 8) DH_FAIL(DH_ERR_SHAPE, "comm_standin: element count %zu must be a multiple of 8", elems);
   if (!parts || !out) DH_FAIL(DH_ERR_INVALID_ARG, "comm_standin: null pointer");
@@ -39,9 +55,17 @@ extern "C" int dh_comm_standin(int kind, int n_ranks, const void* const* parts, 
   }
   if (elems == 0) return DH_OK;
   size_t n8 = elems / 8;
-  size_t want = (n8 + 255) / 256;
+  size_t want = (n8 * (kind == DH_COMM_ALLGATHER ? n_ranks : 1) + 255) / 256;
   size_t cap = n_blocks > 0 ? (size_t)n_blocks : 2048;
   unsigned grid = (unsigned)(want < cap ? want : cap);
+  if (kind == DH_COMM_ALLGATHER) {
+    if (dtype == DH_BF16)
+      allgather_kernel<bf16_t><<<grid, 256, 0, (hipStream_t)stream>>>(pp, n_ranks, (bf16_t*)out, n8);
+    else
+      allgather_kernel<float><<<grid, 256, 0, (hipStream_t)stream>>>(pp, n_ranks, (float*)out, n8);
+    DH_LAUNCH_CHECK();
+    return DH_OK;
+  }
   if (dtype == DH_BF16)
     allreduce_kernel<bf16_t><<<grid, 256, 0, (hipStream_t)stream>>>(pp, n_ranks, (bf16_t*)out, n8);
   else

@@ -21,7 +21,7 @@ DH_ERR_PLAN_INVALID, DH_ERR_HIP, DH_ERR_UNSUPPORTED = -4, -5, -6
 DH_F32, DH_BF16 = 0, 1
 DH_ARCH_LLAMA = 0
 DH_WS_FWD, DH_WS_BWD, DH_WS_SI = 0, 1, 2
-DH_COMM_ALLREDUCE = 0
+DH_COMM_ALLREDUCE, DH_COMM_ALLGATHER, DH_COMM_REDUCESCATTER = 0, 1, 2
 DH_MAX_OPS, DH_MAX_DEPS = 32, 96
 FWD_OPS = ["F_NORM1", "F_QKV", "F_ROPE", "F_ATTN", "F_PROJ", "F_AR1", "F_NORM2", "F_FC1", "F_ACT", "F_FC2", "F_AR2",
            "F_BDA2"]
@@ -130,7 +130,16 @@ SIGNATURES = {
     "dh_moe_gather_rows": (_I, [_I, _I, _I, _P, _P, _P, _I, _P]),
     "dh_moe_combine": (_I, [_I, _I, _I, _P, _P, _P, _P, _P]),
     "dh_moe_combine_bwd": (_I, [_I, _I, _I, _P, _P, _P, _P, _P, _P, _P]),
-    "dh_gemm_grouped": (_I, [_I, _I, _I, C.POINTER(_I), _I, _I, _P, _P, _P, _P, _Z, _P]),
+    "dh_gemm_grouped": (_I, [_I, _I, _I, _P, _I, _I, _I, _P, _P, _P, _P]),
+    "dh_gemm_bias": (_I, [_I, _I, _I, _I, _I, _I, _P, _P, _P, _P, _I, _P, _Z, _P]),
+    "dh_layernorm_fwd": (_I, [_I, _I, _I, _P, _P, _P, _P, _P, _F, _P, _P, _P, _P, _P]),
+    "dh_layernorm_bwd": (_I, [_I, _I, _I, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _Z, _P]),
+    "dh_layernorm_bwd_ws_bytes": (_Z, [_I, _I]),
+    "dh_gelu_fwd": (_I, [_I, _Z, _P, _P, _P]),
+    "dh_gelu_bwd": (_I, [_I, _Z, _P, _P, _P, _P]),
+    "dh_bias_residual_add": (_I, [_I, _I, _I, _P, _P, _P, _P, _P]),
+    "dh_colsum": (_I, [_I, _I, _I, _P, _P, _P, _Z, _P]),
+    "dh_colsum_ws_bytes": (_Z, [_I, _I]),
 }
 for _name, (_res, _args) in SIGNATURES.items():
     _fn = getattr(lib, _name)
@@ -415,7 +424,45 @@ def dh_moe_combine_bwd(dtype, T, H, dy, yp, dest, prob, dyp, dprob, stream=None)
                                   _stream(stream)))
 
 
-def dh_gemm_grouped(dtype, mode, group_rows, dim_a, dim_b, A, B, Cout, ws=None, ws_bytes=0, stream=None):
-    rows = (_I * len(group_rows))(*[int(r) for r in group_rows])
-    _check(lib.dh_gemm_grouped(dtype, mode, len(group_rows), rows, dim_a, dim_b, _ptr(A), _ptr(B), _ptr(Cout), _ptr(ws),
-                               ws_bytes, _stream(stream)))
+def dh_gemm_grouped(dtype, mode, n_groups, group_rows, max_rows, dim_a, dim_b, A, B, Cout, stream=None):
+    _check(lib.dh_gemm_grouped(dtype, mode, n_groups, _ptr(group_rows), max_rows, dim_a, dim_b, _ptr(A), _ptr(B), _ptr(Cout),
+                               _stream(stream)))
+
+
+def dh_gemm_bias(dtype, trans_a, trans_b, M, N, K, A, B, bias, Cout, out_f32_accumulate=False, ws=None, ws_bytes=0, stream=None):
+    _check(lib.dh_gemm_bias(dtype, int(trans_a), int(trans_b), M, N, K, _ptr(A), _ptr(B), _ptr(bias), _ptr(Cout),
+                            int(out_f32_accumulate), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def dh_layernorm_fwd(dtype, T, H, x, residual, residual_bias, gamma, beta, eps, x_out, h, mu, rstd, stream=None):
+    _check(lib.dh_layernorm_fwd(dtype, T, H, _ptr(x), _ptr(residual), _ptr(residual_bias), _ptr(gamma), _ptr(beta), eps,
+                                _ptr(x_out), _ptr(h), _ptr(mu), _ptr(rstd), _stream(stream)))
+
+
+def dh_layernorm_bwd_ws_bytes(T, H):
+    return lib.dh_layernorm_bwd_ws_bytes(T, H)
+
+
+def dh_layernorm_bwd(dtype, T, H, dy, x, gamma, mu, rstd, dres, dx, dgamma, dbeta, ws, ws_bytes, stream=None):
+    _check(lib.dh_layernorm_bwd(dtype, T, H, _ptr(dy), _ptr(x), _ptr(gamma), _ptr(mu), _ptr(rstd), _ptr(dres), _ptr(dx),
+                                _ptr(dgamma), _ptr(dbeta), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def dh_gelu_fwd(dtype, n, f, a, stream=None):
+    _check(lib.dh_gelu_fwd(dtype, n, _ptr(f), _ptr(a), _stream(stream)))
+
+
+def dh_gelu_bwd(dtype, n, f, da, df, stream=None):
+    _check(lib.dh_gelu_bwd(dtype, n, _ptr(f), _ptr(da), _ptr(df), _stream(stream)))
+
+
+def dh_bias_residual_add(dtype, T, H, a, b, bias, out, stream=None):
+    _check(lib.dh_bias_residual_add(dtype, T, H, _ptr(a), _ptr(b), _ptr(bias), _ptr(out), _stream(stream)))
+
+
+def dh_colsum_ws_bytes(T, N):
+    return lib.dh_colsum_ws_bytes(T, N)
+
+
+def dh_colsum(dtype, T, N, x, out, ws, ws_bytes, stream=None):
+    _check(lib.dh_colsum(dtype, T, N, _ptr(x), _ptr(out), _ptr(ws), ws_bytes, _stream(stream)))

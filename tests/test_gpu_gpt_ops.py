@@ -1,0 +1,155 @@
+"""GPU parity of the GPT-style layer's operators (LayerNorm, GeLU, bias handling, all-gather /
+reduce-scatter stand-ins, GEMM with bias) through the C ABI against the fp64 oracle.
+Tolerances: relative L2 <= 1e-5 (fp32 storage) and <= 2e-2 (bf16); copies are exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import layer_ref as R
+from paper_2411_15871_amd import inputs as gen
+
+pytestmark = pytest.mark.gpu
+
+TOL = {False: 1e-5, True: 2e-2}
+
+
+@pytest.fixture(scope="module")
+def dh():
+    from paper_2411_15871_amd import dhelix
+    assert torch.cuda.is_available()
+    return dhelix
+
+
+def dev(a, bf16):
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    return t.to(torch.bfloat16) if bf16 else t
+
+
+def host(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def rel(a, b):
+    return np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30)
+
+
+def dt(dh, bf16):
+    return dh.DH_BF16 if bf16 else dh.DH_F32
+
+
+def f32(*shape, fill=0.0):
+    return torch.full(shape, fill, dtype=torch.float32, device="cuda")
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("T,H", [(1, 8), (37, 256), (130, 4096), (19, 8192), (0, 64)])
+def test_layernorm_fwd_bwd(dh, bf16, T, H):
+    x = gen.normal(1, (T, H), 1.0, 0.3, bf16); res = gen.normal(2, (T, H), 0.5, 0.0, bf16)
+    rb = gen.normal(6, (H,), 0.1, 0.0, bf16)
+    g = gen.normal(3, (H,), 0.02, 1.0, bf16); b = gen.normal(7, (H,), 0.02, 0.0, bf16)
+    dy = gen.normal(4, (T, H), 1e-2, 0.0, bf16); dres = gen.normal(5, (T, H), 1e-2, 0.0, bf16)
+    xd, rd, rbd, gd, bd, dyd, dresd = (dev(a, bf16) for a in (x, res, rb, g, b, dy, dres))
+    x2 = torch.empty_like(xd); h = torch.empty_like(xd)
+    mu = f32(max(T, 1)); rstd = f32(max(T, 1))
+    dh.dh_layernorm_fwd(dt(dh, bf16), T, H, xd, rd, rbd, gd, bd, 1e-5, x2, h, mu, rstd)
+    dx = torch.empty_like(xd); dg = f32(H, fill=0.25); db = f32(H, fill=-0.5)
+    wsb = dh.dh_layernorm_bwd_ws_bytes(T, H)
+    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+    dh.dh_layernorm_bwd(dt(dh, bf16), T, H, dyd, x2, gd, mu, rstd, dresd, dx, dg, db, ws, wsb)
+    torch.cuda.synchronize()
+    if T == 0:
+        assert torch.all(dg == 0.25) and torch.all(db == -0.5)
+        return
+    x2_ref = x.astype(np.float64) + res + rb
+    assert rel(host(x2), x2_ref) <= TOL[bf16]
+    # statistics and output are checked at the stored (rounded) sum the kernel normalised
+    h_ref, mu_ref, r_ref = R.layernorm_fwd(host(x2), g.astype(np.float64), b.astype(np.float64), 1e-5)
+    assert rel(host(h), h_ref) <= TOL[bf16]
+    assert np.max(np.abs(host(mu)[:T] - mu_ref[:, 0])) <= 1e-5
+    assert rel(host(rstd)[:T], r_ref[:, 0]) <= 1e-5
+    dx_ref, dg_ref, db_ref = R.layernorm_bwd(dy.astype(np.float64), host(x2), g.astype(np.float64), host(mu)[:T, None],
+                                             host(rstd)[:T, None])
+    assert rel(host(dx), dx_ref + dres) <= TOL[bf16]
+    assert rel(host(dg) - 0.25, dg_ref) <= 1e-4
+    assert rel(host(db) + 0.5, db_ref) <= 1e-4
+    # without residual: normalises x itself and leaves x_out alone
+    h2 = torch.empty_like(xd)
+    dh.dh_layernorm_fwd(dt(dh, bf16), T, H, xd, None, None, gd, bd, 1e-5, None, h2, mu, rstd)
+    torch.cuda.synchronize()
+    assert rel(host(h2), R.layernorm_fwd(x.astype(np.float64), g.astype(np.float64), b.astype(np.float64), 1e-5)[0]) <= TOL[bf16]
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("n", [8, 1000 * 8, 4096 * 520, 0])
+def test_gelu(dh, bf16, n):
+    f = gen.normal(1, (n,), 2.0, 0.0, bf16); da = gen.normal(2, (n,), 1e-2, 0.0, bf16)
+    if n == 0:
+        dh.dh_gelu_fwd(dt(dh, bf16), 0, None, None)
+        dh.dh_gelu_bwd(dt(dh, bf16), 0, None, None, None)
+        return
+    fd, dad = dev(f, bf16), dev(da, bf16)
+    a = torch.empty_like(fd); df = torch.empty_like(fd)
+    dh.dh_gelu_fwd(dt(dh, bf16), n, fd, a)
+    dh.dh_gelu_bwd(dt(dh, bf16), n, fd, dad, df)
+    torch.cuda.synchronize()
+    assert rel(host(a), R.gelu_fwd(f.astype(np.float64))) <= TOL[bf16]
+    assert rel(host(df), R.gelu_bwd(da.astype(np.float64), f.astype(np.float64))) <= TOL[bf16]
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("T,N", [(1, 8), (33, 264), (4096, 3072), (1000, 8192), (0, 64)])
+def test_bias_residual_add_and_colsum(dh, bf16, T, N):
+    a = gen.normal(1, (T, N), 1.0, 0.0, bf16); b = gen.normal(2, (T, N), 1.0, 0.0, bf16); bias = gen.normal(3, (N,), 0.1, 0.0, bf16)
+    out_acc = f32(N, fill=1.5)
+    wsb = dh.dh_colsum_ws_bytes(T, N)
+    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+    if T == 0:
+        dh.dh_bias_residual_add(dt(dh, bf16), 0, N, None, None, None, None)
+        dh.dh_colsum(dt(dh, bf16), 0, N, None, out_acc, ws, wsb)
+        torch.cuda.synchronize()
+        assert torch.all(out_acc == 1.5)
+        return
+    ad, bd, biasd = dev(a, bf16), dev(b, bf16), dev(bias, bf16)
+    out = torch.empty_like(ad)
+    dh.dh_bias_residual_add(dt(dh, bf16), T, N, ad, bd, biasd, out)
+    dh.dh_colsum(dt(dh, bf16), T, N, ad, out_acc, ws, wsb)
+    torch.cuda.synchronize()
+    assert rel(host(out), a.astype(np.float64) + b + bias) <= TOL[bf16]
+    ref = a.astype(np.float64).sum(axis=0)
+    assert np.linalg.norm(host(out_acc) - 1.5 - ref) <= 1e-5 * np.linalg.norm(np.abs(a).sum(axis=0)) + 1e-6
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("M,N,K", [(5, 8, 16), (300, 264, 520), (64, 128, 4096), (1030, 1544, 72)])
+def test_gemm_bias(dh, bf16, M, N, K):
+    A = gen.normal(1, (M, K), 1.0, 0.0, bf16); B = gen.normal(2, (K, N), 0.05, 0.0, bf16); bias = gen.normal(3, (N,), 0.5, 0.0, bf16)
+    Ad, Bd, biasd = dev(A, bf16), dev(B, bf16), dev(bias, bf16)
+    C = torch.empty(M, N, dtype=Ad.dtype, device="cuda")
+    wsb = dh.dh_gemm_workspace_bytes(dt(dh, bf16), 0, 0, M, N, K)
+    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+    dh.dh_gemm_bias(dt(dh, bf16), 0, 0, M, N, K, Ad, Bd, biasd, C, False, ws, wsb)
+    torch.cuda.synchronize()
+    assert rel(host(C), A.astype(np.float64) @ B + bias) <= TOL[bf16]
+    with pytest.raises(dh.DhelixError):
+        dh.dh_gemm_bias(dt(dh, bf16), 0, 0, M, N, K, Ad, Bd, biasd, C, True, ws, wsb)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("Ts,H,Rk,n_blocks", [(4, 8, 1, 0), (37, 264, 4, 0), (512, 8192, 8, 0), (100, 512, 8, 7)])
+def test_allgather_reducescatter_standins(dh, bf16, Ts, H, Rk, n_blocks):
+    own = gen.normal(1, (Ts, H), 1.0, 0.0, bf16)
+    peers = gen.normal(2, (Rk - 1, Ts, H), 1.0, 0.0, bf16)
+    part_full = gen.normal(3, (Rk * Ts, H), 1.0, 0.0, bf16)
+    ownd, peersd, partd = dev(own, bf16), dev(peers, bf16), dev(part_full, bf16)
+    es = ownd.element_size()
+    peer_ptrs = [peersd.data_ptr() + r * Ts * H * es for r in range(Rk - 1)]
+    out = torch.empty(Rk * Ts, H, dtype=ownd.dtype, device="cuda")
+    dh.dh_comm_standin(dh.DH_COMM_ALLGATHER, [ownd] + peer_ptrs, out, Ts * H, dt(dh, bf16), n_blocks)
+    red = torch.empty(Ts, H, dtype=ownd.dtype, device="cuda")
+    dh.dh_comm_standin(dh.DH_COMM_REDUCESCATTER, [partd] + peer_ptrs, red, Ts * H, dt(dh, bf16), n_blocks)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(out), R.allgather_standin(own, peers if Rk > 1 else None))
+    ref = R.reducescatter_standin(part_full.astype(np.float64), peers if Rk > 1 else None)
+    if Rk == 1:
+        ref = part_full.astype(np.float64)[:Ts]
+    assert rel(host(red), ref) <= TOL[bf16]

@@ -151,10 +151,10 @@ def test_gemm_grouped(dh, bf16, rows, K, N):
     Cd = torch.zeros(max(Tt, 1), N, dtype=Ad.dtype, device="cuda")
     dAd = torch.zeros(max(Tt, 1), K, dtype=Ad.dtype, device="cuda")
     dW = torch.full((G, K, N), 0.5, dtype=torch.float32, device="cuda")
-    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
-    dh.dh_gemm_grouped(dt(dh, bf16), 0, rows, K, N, Ad, Wd, Cd, ws, ws.numel())
-    dh.dh_gemm_grouped(dt(dh, bf16), 1, rows, N, K, dCd, Wd, dAd, ws, ws.numel())
-    dh.dh_gemm_grouped(dt(dh, bf16), 2, rows, K, N, Ad, dCd, dW, ws, ws.numel())
+    rd = torch.tensor(rows, dtype=torch.int32, device="cuda")
+    dh.dh_gemm_grouped(dt(dh, bf16), 0, G, rd, Tt, K, N, Ad, Wd, Cd)
+    dh.dh_gemm_grouped(dt(dh, bf16), 1, G, rd, Tt, N, K, dCd, Wd, dAd)
+    dh.dh_gemm_grouped(dt(dh, bf16), 2, G, rd, Tt, K, N, Ad, dCd, dW)
     torch.cuda.synchronize()
     r0 = 0
     A64, W64, dC64 = A.astype(np.float64), W.astype(np.float64), dC.astype(np.float64)
@@ -184,7 +184,6 @@ def test_moe_block_fwd_bwd(dh, bf16, T, H, F, E, n_local):
     ld = torch.from_numpy(l).cuda(); h2d, Wgud, Wdd, dyd = dev(h2, bf16), dev(Wgu, bf16), dev(Wd, bf16), dev(dy, bf16)
     idx = i32(2 * T); prob = torch.zeros(2 * T, dtype=torch.float32, device="cuda")
     tb, tbs = make_tables(dh, T, E, n_local)
-    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
 
     def buf(r, c):
         return torch.empty(r, c, dtype=h2d.dtype, device="cuda")
@@ -198,9 +197,9 @@ def test_moe_block_fwd_bwd(dh, bf16, T, H, F, E, n_local):
     xp, xg, gu, a, yg, yp, y = buf(2 * T, H), buf(2 * T, H), buf(2 * T, 2 * F), buf(2 * T, F), buf(2 * T, H), buf(2 * T, H), buf(T, H)
     dh.dh_moe_gather_rows(d, 2 * T, H, h2d, tb["src_tok"], xp)
     dh.dh_moe_gather_rows(d, 2 * T, H, xp, tb["send_of_recv"], xg)
-    dh.dh_gemm_grouped(d, 0, rows, H, 2 * F, xg, Wgud, gu, ws, ws.numel())
+    dh.dh_gemm_grouped(d, 0, n_local, tb["group_rows"], 2 * T, H, 2 * F, xg, Wgud, gu)
     dh.dh_swiglu_fwd(d, 2 * T, F, gu, a)
-    dh.dh_gemm_grouped(d, 0, rows, F, H, a, Wdd, yg, ws, ws.numel())
+    dh.dh_gemm_grouped(d, 0, n_local, tb["group_rows"], 2 * T, F, H, a, Wdd, yg)
     dh.dh_moe_gather_rows(d, 2 * T, H, yg, tb["recv_of_send"], yp)
     dh.dh_moe_combine(d, T, H, yp, tb["dest"], prob, y)
     torch.cuda.synchronize()
@@ -212,11 +211,11 @@ def test_moe_block_fwd_bwd(dh, bf16, T, H, F, E, n_local):
     dh.dh_moe_combine_bwd(d, T, H, dyd, yp, tb["dest"], prob, dyp, dprob)
     dh.dh_moe_route_bwd(T, E, dprob, idx, prob, dl)
     dh.dh_moe_gather_rows(d, 2 * T, H, dyp, tb["send_of_recv"], dyg)
-    dh.dh_gemm_grouped(d, 1, rows, H, F, dyg, Wdd, da, ws, ws.numel())
-    dh.dh_gemm_grouped(d, 2, rows, F, H, a, dyg, dWd, ws, ws.numel())
+    dh.dh_gemm_grouped(d, 1, n_local, tb["group_rows"], 2 * T, H, F, dyg, Wdd, da)
+    dh.dh_gemm_grouped(d, 2, n_local, tb["group_rows"], 2 * T, F, H, a, dyg, dWd)
     dh.dh_swiglu_bwd(d, 2 * T, F, gu, da, dgu)
-    dh.dh_gemm_grouped(d, 2, rows, H, 2 * F, xg, dgu, dWgu, ws, ws.numel())
-    dh.dh_gemm_grouped(d, 1, rows, 2 * F, H, dgu, Wgud, dxg, ws, ws.numel())
+    dh.dh_gemm_grouped(d, 2, n_local, tb["group_rows"], 2 * T, H, 2 * F, xg, dgu, dWgu)
+    dh.dh_gemm_grouped(d, 1, n_local, tb["group_rows"], 2 * T, 2 * F, H, dgu, Wgud, dxg)
     dh.dh_moe_gather_rows(d, 2 * T, H, dxg, tb["recv_of_send"], dxp)
     dh.dh_moe_combine(d, T, H, dxp, tb["dest"], None, dh2)
     torch.cuda.synchronize()
