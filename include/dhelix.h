@@ -43,15 +43,26 @@ typedef enum {
 } dh_status;
 
 typedef enum { DH_F32 = 0, DH_BF16 = 1 } dh_dtype;
-typedef enum { DH_ARCH_LLAMA = 0 } dh_arch;
+/* DH_ARCH_LLAMA: RMSNorm, RoPE, SwiGLU, tensor parallel with all-reduce (Llama models of Table 3).
+ * DH_ARCH_GPT:   LayerNorm, biases, GeLU, tensor + sequence parallel (all-gather / reduce-scatter; GPT
+ *                models of Table 3).
+ * DH_ARCH_MOE:   Llama-style attention (not sharded) + top-2 mixture-of-experts SwiGLU FFN under expert
+ *                parallelism (all-to-all dispatch / combine; MoE models of Table 3). */
+typedef enum { DH_ARCH_LLAMA = 0, DH_ARCH_GPT = 1, DH_ARCH_MOE = 2 } dh_arch;
 
 /* Message of the last error raised on this thread ("" if none).  Host memory owned by the library. */
 const char* dh_last_error(void);
 
 /* ------------------------------------------------------------------------------------------
- * Layer description: one tensor-parallel shard of a pre-norm Llama-style layer (the dense models
- * of Sec. 6.1, Table 3): RMSNorm, QKV GEMM, RoPE, causal grouped-query attention, output GEMM,
- * collective, residual, RMSNorm, gate/up GEMM, SwiGLU, down GEMM, collective, residual.
+ * Layer description: one GPU's share of a pre-norm transformer layer (the models of Sec. 6.1,
+ * Table 3).  DH_ARCH_LLAMA: RMSNorm, QKV GEMM, RoPE, causal grouped-query attention, output GEMM,
+ * all-reduce, residual, RMSNorm, gate/up GEMM, SwiGLU, down GEMM, all-reduce, residual.
+ * DH_ARCH_GPT: the layer's input, output and norms live on this rank's sequence shard of
+ * Ts = T / n_ranks rows (the first Ts rows of the [T,H] row order); an all-gather precedes each
+ * column-parallel GEMM, a reduce-scatter follows each row-parallel one; no RoPE.
+ * DH_ARCH_MOE: no tensor parallelism; the FFN is routed: top-2 of n_experts logical experts, of which
+ * this GPU holds n_local_experts (logical expert e runs on local expert e % n_local_experts, the
+ * other factor of e standing for the source rank of an expert-parallel group).
  * ------------------------------------------------------------------------------------------ */
 typedef struct {
   int arch;        /* dh_arch */
@@ -62,24 +73,32 @@ typedef struct {
   int n_q_heads;   /* local query heads */
   int n_kv_heads;  /* local key/value heads; must divide n_q_heads */
   int head_dim;    /* d */
-  int ffn;         /* local SwiGLU width F */
+  int ffn;         /* local FFN width F (per expert for DH_ARCH_MOE) */
   float eps;       /* RMSNorm epsilon */
   float rope_base; /* RoPE base; pair (i, i+d/2) turns by position * base^(-2i/d) */
   int n_ranks;     /* R: partials summed by each collective stand-in (1 = no peers) */
   int comm_blocks; /* thread blocks a collective stand-in may use (its "channel" count); 0 = enough
                       to cover the payload */
+  int n_experts;       /* DH_ARCH_MOE: logical experts E (2..256); else 0 */
+  int n_local_experts; /* DH_ARCH_MOE: experts held by this GPU, divides E; else 0 */
 } dh_layer_config;
 
 /* Device pointers to the shard's weights (read only).  g1,g2: [H]; Wqkv: [H,(nq+2nkv)d] with columns
- * [q heads | k heads | v heads]; Wo: [nq*d,H]; Wgu: [H,2F] with columns [gate | up]; Wd: [F,H]. */
+ * [q heads | k heads | v heads]; Wo: [nq*d,H]; Wgu: [H,2F] with columns [gate | up]; Wd: [F,H].
+ * DH_ARCH_GPT: Wgu is the first MLP matrix [H,F], Wd the second [F,H]; b1,b2: LayerNorm shifts [H];
+ * bqkv [(nq+2nkv)d], bo [H], bfc1 [F], bfc2 [H]: biases of the four linears (bo and bfc2 are added
+ * after the reduce-scatter).  DH_ARCH_MOE: Wgu [n_local,H,2F], Wd [n_local,F,H].
+ * Pointers an architecture does not use are ignored. */
 typedef struct {
   const void *g1, *Wqkv, *Wo, *g2, *Wgu, *Wd;
+  const void *b1, *bqkv, *bo, *b2, *bfc1, *bfc2;
 } dh_weights;
 
 /* Device pointers to the float32 gradient buffers, same shapes as the weights.  The backward pass
  * ADDS into them; one set is shared by both strands (Sec. 3.3). */
 typedef struct {
   float *dg1, *dWqkv, *dWo, *dg2, *dWgu, *dWd;
+  float *db1, *dbqkv, *dbo, *db2, *dbfc1, *dbfc2;
 } dh_wgrads;
 
 typedef struct dh_layer dh_layer;
@@ -90,8 +109,9 @@ void dh_layer_destroy(dh_layer* layer);
 int dh_layer_bind_weights(dh_layer* layer, const dh_weights* w);
 int dh_layer_bind_wgrads(dh_layer* layer, const dh_wgrads* g);
 
-/* Bytes of one strand's saved-activation slot (written by forward, read by backward): rstd1, h1,
- * rotated qkv, o, lse, x2, rstd2, h2, gate/up, a. */
+/* Bytes of one strand's saved-activation slot (written by forward, read by backward): norm
+ * statistics, h1, (rotated) qkv, o, lse, x2, h2, FFN pre-activation, a; DH_ARCH_MOE adds the routing
+ * decision, its index tables and the dispatched rows. */
 size_t dh_layer_saved_bytes(const dh_layer* layer);
 
 typedef enum { DH_WS_FWD = 0, DH_WS_BWD = 1, DH_WS_SI = 2 } dh_ws_kind;
@@ -99,16 +119,23 @@ typedef enum { DH_WS_FWD = 0, DH_WS_BWD = 1, DH_WS_SI = 2 } dh_ws_kind;
  * backward region side by side, so the two strands never share a transient buffer). */
 size_t dh_layer_workspace_bytes(const dh_layer* layer, int kind);
 
-/* One strand's forward call.  x: device [T,H] input, must stay valid and unchanged until that
- * strand's backward has run.  out: device [T,H].  saved: device slot of dh_layer_saved_bytes.
- * peers_ar1/peers_ar2: device [R-1,T,H] frozen partials of the two forward collectives (the other
- * ranks' contributions; ignored when n_ranks == 1). */
+/* One strand's forward call.  x: device [T,H] input ([Ts,H] for DH_ARCH_GPT), must stay valid and
+ * unchanged until that strand's backward has run.  out: device, same shape.  saved: device slot of
+ * dh_layer_saved_bytes.
+ * peers_ar1/peers_ar2: frozen contributions of the other ranks to the two forward reductions
+ * (ignored when n_ranks == 1): DH_ARCH_LLAMA [R-1,T,H] partials of the all-reduces; DH_ARCH_GPT
+ * [R-1,Ts,H] partials of the reduce-scatters for this rank's rows.
+ * peers_ag1/peers_ag2: DH_ARCH_GPT only, [R-1,Ts,H] the other ranks' shards entering the all-gathers.
+ * logits: DH_ARCH_MOE only, float32 [T,n_experts] router logits (an input of the layer). */
 typedef struct {
   const void* x;
   void* out;
   void* saved;
   const void* peers_ar1;
   const void* peers_ar2;
+  const void* peers_ag1;
+  const void* peers_ag2;
+  const float* logits;
 } dh_fwd_args;
 
 /* One strand's backward call.  dout: device [T,H] upstream gradient; dx: device [T,H] result;
@@ -121,6 +148,9 @@ typedef struct {
   const void* saved;
   const void* peers_ar3;
   const void* peers_ar4;
+  const void* peers_ag3; /* DH_ARCH_GPT: [R-1,Ts,H] peers' gradient shards of the backward all-gathers */
+  const void* peers_ag4;
+  float* dlogits;        /* DH_ARCH_MOE: float32 [T,n_experts] gradient of the router logits (written) */
 } dh_bwd_args;
 
 /* Forward / backward of one strand, operators in their default order, all on `stream`
@@ -143,6 +173,29 @@ typedef enum {
   DH_B_QKV_WGRAD, DH_B_AR4, DH_B_NORM1, DH_B_NOPS
 } dh_bwd_op;
 
+/* DH_ARCH_GPT.  Bias gradients belong to the weight-gradient operator of their linear. */
+typedef enum {
+  DH_GF_NORM1 = 0, DH_GF_AG1, DH_GF_QKV, DH_GF_ATTN, DH_GF_PROJ, DH_GF_RS1, DH_GF_NORM2, DH_GF_AG2,
+  DH_GF_FC1, DH_GF_ACT, DH_GF_FC2, DH_GF_RS2, DH_GF_BDA2, DH_GF_NOPS
+} dh_gpt_fwd_op;
+typedef enum {
+  DH_GB_AG3 = 0, DH_GB_FC2_DGRAD, DH_GB_FC2_WGRAD, DH_GB_ACT, DH_GB_FC1_DGRAD, DH_GB_FC1_WGRAD,
+  DH_GB_RS3, DH_GB_NORM2, DH_GB_AG4, DH_GB_PROJ_DGRAD, DH_GB_PROJ_WGRAD, DH_GB_ATTN,
+  DH_GB_QKV_DGRAD, DH_GB_QKV_WGRAD, DH_GB_RS4, DH_GB_NORM1, DH_GB_NOPS
+} dh_gpt_bwd_op;
+/* DH_ARCH_MOE. */
+typedef enum {
+  DH_MF_NORM1 = 0, DH_MF_QKV, DH_MF_ROPE, DH_MF_ATTN, DH_MF_PROJ, DH_MF_NORM2, DH_MF_ROUTE,
+  DH_MF_PERMUTE, DH_MF_A2A_DISPATCH, DH_MF_FC1, DH_MF_ACT, DH_MF_FC2, DH_MF_A2A_COMBINE,
+  DH_MF_UNPERMUTE, DH_MF_NOPS
+} dh_moe_fwd_op;
+typedef enum {
+  DH_MB_UNPERMUTE = 0, DH_MB_ROUTE, DH_MB_A2A_DISPATCH, DH_MB_FC2_DGRAD, DH_MB_FC2_WGRAD, DH_MB_ACT,
+  DH_MB_FC1_DGRAD, DH_MB_FC1_WGRAD, DH_MB_A2A_COMBINE, DH_MB_PERMUTE, DH_MB_NORM2,
+  DH_MB_PROJ_DGRAD, DH_MB_PROJ_WGRAD, DH_MB_ATTN, DH_MB_ROPE, DH_MB_QKV_DGRAD, DH_MB_QKV_WGRAD,
+  DH_MB_NORM1, DH_MB_NOPS
+} dh_moe_bwd_op;
+
 #define DH_MAX_OPS 32
 #define DH_MAX_DEPS 96
 typedef struct {
@@ -155,8 +208,8 @@ typedef struct {
 
 /* Fills the forward (direction 0) or backward (direction 1) operator graph of the layer. */
 int dh_layer_op_graph(const dh_layer* layer, int direction, dh_op_graph* out);
-/* Static name of an operator ("F_QKV", "B_ATTN", ...), NULL if out of range. */
-const char* dh_op_name(int direction, int op);
+/* Static name of an operator of an architecture ("F_QKV", "B_ATTN", ...), NULL if out of range. */
+const char* dh_op_name(int arch, int direction, int op);
 
 /* ------------------------------------------------------------------------------------------
  * Overlap table (Sec. 3.2): solo time of every operator and, for every (forward, backward)
@@ -347,10 +400,10 @@ int dh_moe_plan(int T, int E, int n_local, const int32_t* idx, const dh_moe_tabl
 int dh_moe_gather_rows(int dtype, int n_rows, int H, const void* in, const int32_t* map, void* out,
                        int n_blocks, void* stream);
 
-/* Un-permute: y[t,:] = prob[t,0]*yp[dest[2t],:] + prob[t,1]*yp[dest[2t+1],:]; prob == NULL means
- * weights 1 (the backward of the token permute). */
+/* Un-permute: y[t,:] = prob[t,0]*yp[dest[2t],:] + prob[t,1]*yp[dest[2t+1],:] (+ residual[t,:] if not
+ * NULL); prob == NULL means weights 1 (the backward of the token permute). */
 int dh_moe_combine(int dtype, int T, int H, const void* yp, const int32_t* dest, const float* prob,
-                   void* y, void* stream);
+                   const void* residual, void* y, void* stream);
 /* Backward of the weighted un-permute: dyp[dest[2t+k],:] = prob[t,k]*dy[t,:] and
  * dprob[t,k] = <dy[t,:], yp[dest[2t+k],:]> (float32). */
 int dh_moe_combine_bwd(int dtype, int T, int H, const void* dy, const void* yp, const int32_t* dest,

@@ -1,46 +1,66 @@
-// The layer object, its operator table, single-strand forward/backward, the Strand-Interleaving
-// executor (paper Sec. 3.3 and 5) and the pairwise overlap profiler (Sec. 3.2).
+// The layer object, its operator tables for the three architectures, single-strand forward/backward,
+// the Strand-Interleaving executor (paper Sec. 3.3 and 5) and the pairwise overlap profiler (Sec. 3.2).
 #include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <vector>
 #include "common.h"
 
-extern "C" size_t dh_rmsnorm_bwd_ws_bytes(int T, int H);
-extern "C" int dh_add(int dtype, size_t n, const void* a, const void* b, void* out, void* stream);
-extern "C" int dh_plan_validate(const dh_op_graph* fwd, const dh_op_graph* bwd, const dh_plan* plan);
-
 #define DH_EVENT_POOL 256
 
 struct dh_layer {
   dh_layer_config c;
-  int T, n_qkv, n_o;
+  int T;      // tokens of the micro-batch
+  int Ts;     // rows of the layer's input/output (T, or T / n_ranks under sequence parallelism)
+  int Tf;     // rows entering the FFN GEMMs (T, or 2T routed rows for the MoE)
+  int n_qkv, n_o;
   size_t es;  // bytes per activation element
   dh_weights w;
   dh_wgrads g;
   bool have_w, have_g;
   // saved-slot offsets (bytes)
-  size_t s_rstd1, s_h1, s_qkv, s_o, s_lse, s_x2, s_rstd2, s_h2, s_gu, s_a, saved_bytes;
+  size_t s_mu1, s_rstd1, s_h1, s_qkv, s_o, s_lse, s_x2, s_mu2, s_rstd2, s_h2, s_gu, s_a;
+  size_t s_idx, s_prob, s_tab[9], s_xg, s_yp, saved_bytes;
   // forward workspace offsets
-  size_t f_part, f_red, f_gemm, f_gemm_bytes, fwd_bytes;
+  size_t f_hs, f_part, f_red, f_xp, f_yg, f_gemm, f_gemm_bytes, fwd_bytes;
   // backward workspace offsets
-  size_t b_da, b_dgu, b_part, b_red, b_dx2, b_do, b_dqkv, b_delta, b_attn, b_attn_bytes, b_norm, b_norm_bytes, b_gemm, b_gemm_bytes, bwd_bytes;
+  size_t b_dz, b_da, b_dgu, b_part, b_red, b_dx2, b_dy, b_do, b_dqkv, b_delta, b_attn, b_attn_bytes, b_norm, b_norm_bytes;
+  size_t b_colsum, b_colsum_bytes, b_dyp, b_dprob, b_dyg, b_dxg, b_gemm, b_gemm_bytes, bwd_bytes;
   hipEvent_t ev[DH_EVENT_POOL];  // created on the first SI step (needs a device)
   bool have_events;
   int ev_next;
   dh_op_graph gf, gb;
 };
 
-static const char* kFwdNames[DH_F_NOPS] = {"F_NORM1", "F_QKV", "F_ROPE", "F_ATTN", "F_PROJ", "F_AR1",
+static const char* kLlamaFwd[DH_F_NOPS] = {"F_NORM1", "F_QKV", "F_ROPE", "F_ATTN", "F_PROJ", "F_AR1",
                                            "F_NORM2", "F_FC1", "F_ACT", "F_FC2", "F_AR2", "F_BDA2"};
-static const char* kBwdNames[DH_B_NOPS] = {"B_FC2_DGRAD", "B_FC2_WGRAD", "B_ACT", "B_FC1_DGRAD", "B_FC1_WGRAD",
+static const char* kLlamaBwd[DH_B_NOPS] = {"B_FC2_DGRAD", "B_FC2_WGRAD", "B_ACT", "B_FC1_DGRAD", "B_FC1_WGRAD",
                                            "B_AR3", "B_NORM2", "B_PROJ_DGRAD", "B_PROJ_WGRAD", "B_ATTN",
                                            "B_ROPE", "B_QKV_DGRAD", "B_QKV_WGRAD", "B_AR4", "B_NORM1"};
+static const char* kGptFwd[DH_GF_NOPS] = {"F_NORM1", "F_AG1", "F_QKV", "F_ATTN", "F_PROJ", "F_RS1", "F_NORM2",
+                                          "F_AG2", "F_FC1", "F_ACT", "F_FC2", "F_RS2", "F_BDA2"};
+static const char* kGptBwd[DH_GB_NOPS] = {"B_AG3", "B_FC2_DGRAD", "B_FC2_WGRAD", "B_ACT", "B_FC1_DGRAD", "B_FC1_WGRAD",
+                                          "B_RS3", "B_NORM2", "B_AG4", "B_PROJ_DGRAD", "B_PROJ_WGRAD", "B_ATTN",
+                                          "B_QKV_DGRAD", "B_QKV_WGRAD", "B_RS4", "B_NORM1"};
+static const char* kMoeFwd[DH_MF_NOPS] = {"F_NORM1", "F_QKV", "F_ROPE", "F_ATTN", "F_PROJ", "F_NORM2", "F_ROUTE",
+                                          "F_PERMUTE", "F_A2A_DISPATCH", "F_FC1", "F_ACT", "F_FC2", "F_A2A_COMBINE",
+                                          "F_UNPERMUTE"};
+static const char* kMoeBwd[DH_MB_NOPS] = {"B_UNPERMUTE", "B_ROUTE", "B_A2A_DISPATCH", "B_FC2_DGRAD", "B_FC2_WGRAD", "B_ACT",
+                                          "B_FC1_DGRAD", "B_FC1_WGRAD", "B_A2A_COMBINE", "B_PERMUTE", "B_NORM2",
+                                          "B_PROJ_DGRAD", "B_PROJ_WGRAD", "B_ATTN", "B_ROPE", "B_QKV_DGRAD", "B_QKV_WGRAD",
+                                          "B_NORM1"};
 
-extern "C" const char* dh_op_name(int direction, int op) {
-  if (direction == 0) return op >= 0 && op < DH_F_NOPS ? kFwdNames[op] : nullptr;
-  if (direction == 1) return op >= 0 && op < DH_B_NOPS ? kBwdNames[op] : nullptr;
-  return nullptr;
+extern "C" const char* dh_op_name(int arch, int direction, int op) {
+  if (direction != 0 && direction != 1) return nullptr;
+  const char* const* names;
+  int n;
+  switch (arch) {
+    case DH_ARCH_LLAMA: names = direction ? kLlamaBwd : kLlamaFwd; n = direction ? DH_B_NOPS : DH_F_NOPS; break;
+    case DH_ARCH_GPT: names = direction ? kGptBwd : kGptFwd; n = direction ? DH_GB_NOPS : DH_GF_NOPS; break;
+    case DH_ARCH_MOE: names = direction ? kMoeBwd : kMoeFwd; n = direction ? DH_MB_NOPS : DH_MF_NOPS; break;
+    default: return nullptr;
+  }
+  return op >= 0 && op < n ? names[op] : nullptr;
 }
 
 static void add_dep(dh_op_graph& g, int s, int d) {
@@ -48,26 +68,63 @@ static void add_dep(dh_op_graph& g, int s, int d) {
   g.dep_dst[g.n_deps] = d;
   g.n_deps++;
 }
+static void add_chain(dh_op_graph& g, const int* chain, size_t n) {
+  for (size_t i = 0; i + 1 < n; i++) add_dep(g, chain[i], chain[i + 1]);
+}
+#define CHAIN(g, ...)                                       \
+  do {                                                      \
+    const int _c[] = {__VA_ARGS__};                         \
+    add_chain(g, _c, sizeof(_c) / sizeof(int));             \
+  } while (0)
 
-// Forward: a chain.  Backward: the data-gradient chain plus four weight-gradient GEMMs, each
-// depending only on the operator that produces its dY (Sec. 4.2: wgrad may move in the sequence).
+// Forward: a chain (the MoE router only needs the logits, so it hangs off nothing).  Backward: the
+// data-gradient chain plus the weight-gradient GEMMs, each depending only on the operator that
+// produces its dY (Sec. 4.2: wgrad may move in the sequence).
 static void build_graphs(dh_layer* L) {
   dh_op_graph& f = L->gf;
-  memset(&f, 0, sizeof(f));
-  f.n_ops = DH_F_NOPS;
-  for (int i = 0; i + 1 < DH_F_NOPS; i++) add_dep(f, i, i + 1);
-  f.is_comm[DH_F_AR1] = f.is_comm[DH_F_AR2] = 1;
   dh_op_graph& b = L->gb;
+  memset(&f, 0, sizeof(f));
   memset(&b, 0, sizeof(b));
-  b.n_ops = DH_B_NOPS;
-  const int chain[] = {DH_B_FC2_DGRAD, DH_B_ACT, DH_B_FC1_DGRAD, DH_B_AR3, DH_B_NORM2, DH_B_PROJ_DGRAD,
-                       DH_B_ATTN, DH_B_ROPE, DH_B_QKV_DGRAD, DH_B_AR4, DH_B_NORM1};
-  for (size_t i = 0; i + 1 < sizeof(chain) / sizeof(int); i++) add_dep(b, chain[i], chain[i + 1]);
-  add_dep(b, DH_B_ACT, DH_B_FC1_WGRAD);     // needs dgu
-  add_dep(b, DH_B_NORM2, DH_B_PROJ_WGRAD);  // needs dx2
-  add_dep(b, DH_B_ROPE, DH_B_QKV_WGRAD);    // needs dqkv
-  // FC2_WGRAD needs only the upstream gradient and the saved activation: no predecessor.
-  b.is_comm[DH_B_AR3] = b.is_comm[DH_B_AR4] = 1;
+  if (L->c.arch == DH_ARCH_LLAMA) {
+    f.n_ops = DH_F_NOPS;
+    for (int i = 0; i + 1 < DH_F_NOPS; i++) add_dep(f, i, i + 1);
+    f.is_comm[DH_F_AR1] = f.is_comm[DH_F_AR2] = 1;
+    b.n_ops = DH_B_NOPS;
+    CHAIN(b, DH_B_FC2_DGRAD, DH_B_ACT, DH_B_FC1_DGRAD, DH_B_AR3, DH_B_NORM2, DH_B_PROJ_DGRAD, DH_B_ATTN, DH_B_ROPE,
+          DH_B_QKV_DGRAD, DH_B_AR4, DH_B_NORM1);
+    add_dep(b, DH_B_ACT, DH_B_FC1_WGRAD);     // needs dgu
+    add_dep(b, DH_B_NORM2, DH_B_PROJ_WGRAD);  // needs dx2
+    add_dep(b, DH_B_ROPE, DH_B_QKV_WGRAD);    // needs dqkv
+    // FC2_WGRAD needs only the upstream gradient and the saved activation: no predecessor.
+    b.is_comm[DH_B_AR3] = b.is_comm[DH_B_AR4] = 1;
+  } else if (L->c.arch == DH_ARCH_GPT) {
+    f.n_ops = DH_GF_NOPS;
+    for (int i = 0; i + 1 < DH_GF_NOPS; i++) add_dep(f, i, i + 1);
+    f.is_comm[DH_GF_AG1] = f.is_comm[DH_GF_RS1] = f.is_comm[DH_GF_AG2] = f.is_comm[DH_GF_RS2] = 1;
+    b.n_ops = DH_GB_NOPS;
+    CHAIN(b, DH_GB_AG3, DH_GB_FC2_DGRAD, DH_GB_ACT, DH_GB_FC1_DGRAD, DH_GB_RS3, DH_GB_NORM2, DH_GB_AG4, DH_GB_PROJ_DGRAD,
+          DH_GB_ATTN, DH_GB_QKV_DGRAD, DH_GB_RS4, DH_GB_NORM1);
+    add_dep(b, DH_GB_AG3, DH_GB_FC2_WGRAD);   // needs the gathered dz
+    add_dep(b, DH_GB_ACT, DH_GB_FC1_WGRAD);   // needs df
+    add_dep(b, DH_GB_AG4, DH_GB_PROJ_WGRAD);  // needs the gathered dy
+    add_dep(b, DH_GB_ATTN, DH_GB_QKV_WGRAD);  // needs dqkv
+    b.is_comm[DH_GB_AG3] = b.is_comm[DH_GB_RS3] = b.is_comm[DH_GB_AG4] = b.is_comm[DH_GB_RS4] = 1;
+  } else {
+    f.n_ops = DH_MF_NOPS;
+    CHAIN(f, DH_MF_NORM1, DH_MF_QKV, DH_MF_ROPE, DH_MF_ATTN, DH_MF_PROJ, DH_MF_NORM2, DH_MF_PERMUTE, DH_MF_A2A_DISPATCH,
+          DH_MF_FC1, DH_MF_ACT, DH_MF_FC2, DH_MF_A2A_COMBINE, DH_MF_UNPERMUTE);
+    add_dep(f, DH_MF_ROUTE, DH_MF_PERMUTE);
+    f.is_comm[DH_MF_A2A_DISPATCH] = f.is_comm[DH_MF_A2A_COMBINE] = 1;
+    b.n_ops = DH_MB_NOPS;
+    CHAIN(b, DH_MB_UNPERMUTE, DH_MB_A2A_DISPATCH, DH_MB_FC2_DGRAD, DH_MB_ACT, DH_MB_FC1_DGRAD, DH_MB_A2A_COMBINE,
+          DH_MB_PERMUTE, DH_MB_NORM2, DH_MB_PROJ_DGRAD, DH_MB_ATTN, DH_MB_ROPE, DH_MB_QKV_DGRAD, DH_MB_NORM1);
+    add_dep(b, DH_MB_UNPERMUTE, DH_MB_ROUTE);          // needs dprob
+    add_dep(b, DH_MB_A2A_DISPATCH, DH_MB_FC2_WGRAD);   // needs the dispatched dy rows
+    add_dep(b, DH_MB_ACT, DH_MB_FC1_WGRAD);            // needs dgu
+    add_dep(b, DH_MB_NORM2, DH_MB_PROJ_WGRAD);         // needs dx2
+    add_dep(b, DH_MB_ROPE, DH_MB_QKV_WGRAD);           // needs dqkv
+    b.is_comm[DH_MB_A2A_DISPATCH] = b.is_comm[DH_MB_A2A_COMBINE] = 1;
+  }
 }
 
 extern "C" int dh_layer_op_graph(const dh_layer* layer, int direction, dh_op_graph* out) {
@@ -85,7 +142,8 @@ static size_t take(size_t& cur, size_t bytes) {
 extern "C" int dh_layer_create(const dh_layer_config* cfg, dh_layer** out) {
   if (!cfg || !out) DH_FAIL(DH_ERR_INVALID_ARG, "layer_create: null pointer");
   const dh_layer_config& c = *cfg;
-  if (c.arch != DH_ARCH_LLAMA) DH_FAIL(DH_ERR_UNSUPPORTED, "layer_create: arch %d not supported", c.arch);
+  if (c.arch != DH_ARCH_LLAMA && c.arch != DH_ARCH_GPT && c.arch != DH_ARCH_MOE)
+    DH_FAIL(DH_ERR_UNSUPPORTED, "layer_create: arch %d not supported", c.arch);
   if (c.dtype != DH_F32 && c.dtype != DH_BF16) DH_FAIL(DH_ERR_INVALID_ARG, "layer_create: dtype %d", c.dtype);
   if (c.batch < 0 || c.seq < 0 || c.hidden <= 0 || c.n_q_heads <= 0 || c.n_kv_heads <= 0 || c.head_dim <= 0 || c.ffn <= 0)
     DH_FAIL(DH_ERR_SHAPE, "layer_create: non-positive dimension");
@@ -97,52 +155,89 @@ extern "C" int dh_layer_create(const dh_layer_config* cfg, dh_layer** out) {
   if (c.n_ranks < 1 || c.n_ranks > 16) DH_FAIL(DH_ERR_INVALID_ARG, "layer_create: n_ranks %d outside 1..16", c.n_ranks);
   if (c.comm_blocks < 0 || c.comm_blocks > 65536) DH_FAIL(DH_ERR_INVALID_ARG, "layer_create: comm_blocks %d outside 0..65536", c.comm_blocks);
   if ((long long)c.batch * c.seq > (1 << 24)) DH_FAIL(DH_ERR_SHAPE, "layer_create: too many tokens");
+  if (c.arch == DH_ARCH_GPT && (c.batch * c.seq) % c.n_ranks)
+    DH_FAIL(DH_ERR_SHAPE, "layer_create: sequence parallelism needs tokens %d divisible by n_ranks %d", c.batch * c.seq, c.n_ranks);
+  if (c.arch == DH_ARCH_MOE) {
+    if (c.n_experts < 2 || c.n_experts > 256 || c.n_local_experts < 1 || c.n_local_experts > 64 || c.n_experts % c.n_local_experts)
+      DH_FAIL(DH_ERR_SHAPE, "layer_create: n_experts %d (2..256) must be a multiple of n_local_experts %d (1..64)", c.n_experts, c.n_local_experts);
+    if (c.n_ranks != 1) DH_FAIL(DH_ERR_INVALID_ARG, "layer_create: the MoE layer has no tensor-parallel peers (n_ranks must be 1)");
+  }
   dh_layer* L = new dh_layer();
   L->c = c;
   L->T = c.batch * c.seq;
+  L->Ts = c.arch == DH_ARCH_GPT ? L->T / c.n_ranks : L->T;
+  L->Tf = c.arch == DH_ARCH_MOE ? 2 * L->T : L->T;
   L->n_qkv = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
   L->n_o = c.n_q_heads * c.head_dim;
   L->es = dh_elem_size(c.dtype);
   L->have_w = L->have_g = false;
-  const size_t T = L->T, H = c.hidden, F = c.ffn, es = L->es;
+  const size_t T = L->T, Ts = L->Ts, Tf = L->Tf, H = c.hidden, F = c.ffn, es = L->es;
+  const size_t Fin = c.arch == DH_ARCH_GPT ? F : 2 * F;  // columns of the first FFN GEMM
+  const bool moe = c.arch == DH_ARCH_MOE, gpt = c.arch == DH_ARCH_GPT;
   size_t cur = 0;
-  L->s_rstd1 = take(cur, T * 4);
+  L->s_mu1 = take(cur, gpt ? Ts * 4 : 0);
+  L->s_rstd1 = take(cur, Ts * 4);
   L->s_h1 = take(cur, T * H * es);
   L->s_qkv = take(cur, T * L->n_qkv * es);
   L->s_o = take(cur, T * L->n_o * es);
   L->s_lse = take(cur, (size_t)c.n_q_heads * T * 4);
-  L->s_x2 = take(cur, T * H * es);
-  L->s_rstd2 = take(cur, T * 4);
+  L->s_x2 = take(cur, Ts * H * es);
+  L->s_mu2 = take(cur, gpt ? Ts * 4 : 0);
+  L->s_rstd2 = take(cur, Ts * 4);
   L->s_h2 = take(cur, T * H * es);
-  L->s_gu = take(cur, T * 2 * F * es);
-  L->s_a = take(cur, T * F * es);
+  L->s_gu = take(cur, Tf * Fin * es);
+  L->s_a = take(cur, Tf * F * es);
+  L->s_idx = take(cur, moe ? 2 * T * 4 : 0);
+  L->s_prob = take(cur, moe ? 2 * T * 4 : 0);
+  const size_t tab_ints[9] = {2 * T, 2 * T, 2 * T, 2 * T, 2 * T, (size_t)c.n_experts, (size_t)c.n_experts + 1,
+                              (size_t)c.n_experts, (size_t)c.n_local_experts};
+  for (int i = 0; i < 9; i++) L->s_tab[i] = take(cur, moe ? tab_ints[i] * 4 : 0);
+  L->s_xg = take(cur, moe ? Tf * H * es : 0);
+  L->s_yp = take(cur, moe ? Tf * H * es : 0);
   L->saved_bytes = cur;
   const bool bf = c.dtype == DH_BF16;
-  auto gw = [&](bool ta, bool tb, int M, int N, int K) { return bf ? dh_gemm_bf16_ws_bytes(ta, tb, M, N, K) : (size_t)0; };
+  auto gw = [&](bool ta, bool tb, size_t M, size_t N, size_t K) {
+    return bf ? dh_gemm_bf16_ws_bytes(ta, tb, (int)M, (int)N, (int)K) : (size_t)0;
+  };
   cur = 0;
+  L->f_hs = take(cur, gpt ? Ts * H * es : 0);
   L->f_part = take(cur, T * H * es);
-  L->f_red = take(cur, T * H * es);
-  L->f_gemm_bytes = std::max(std::max(gw(0, 0, T, L->n_qkv, H), gw(0, 0, T, H, L->n_o)), std::max(gw(0, 0, T, 2 * F, H), gw(0, 0, T, H, F)));
-  L->f_gemm = take(cur, L->f_gemm_bytes);
+  L->f_red = take(cur, moe ? 0 : Ts * H * es);
+  L->f_xp = take(cur, moe ? Tf * H * es : 0);
+  L->f_yg = take(cur, moe ? Tf * H * es : 0);
+  size_t fg = std::max(gw(0, 0, T, L->n_qkv, H), gw(0, 0, T, H, L->n_o));
+  if (!moe) fg = std::max(fg, std::max(gw(0, 0, T, Fin, H), gw(0, 0, T, H, F)));
+  L->f_gemm_bytes = fg;
+  L->f_gemm = take(cur, fg);
   L->fwd_bytes = cur;
   cur = 0;
-  L->b_da = take(cur, T * F * es);
-  L->b_dgu = take(cur, T * 2 * F * es);
+  L->b_dz = take(cur, gpt ? T * H * es : 0);
+  L->b_da = take(cur, Tf * F * es);
+  L->b_dgu = take(cur, Tf * Fin * es);
   L->b_part = take(cur, T * H * es);
-  L->b_red = take(cur, T * H * es);
-  L->b_dx2 = take(cur, T * H * es);
+  L->b_red = take(cur, Ts * H * es);
+  L->b_dx2 = take(cur, Ts * H * es);
+  L->b_dy = take(cur, gpt ? T * H * es : 0);
   L->b_do = take(cur, T * L->n_o * es);
   L->b_dqkv = take(cur, T * L->n_qkv * es);
   L->b_delta = take(cur, (size_t)c.n_q_heads * T * 4);
   L->b_attn_bytes = bf ? dh_attn_bwd_bf16_ws_bytes(c.batch, c.seq, c.n_q_heads, c.n_kv_heads, c.head_dim) : 0;
   L->b_attn = take(cur, L->b_attn_bytes);
-  L->b_norm_bytes = dh_rmsnorm_bwd_ws_bytes(L->T, c.hidden);
+  L->b_norm_bytes = gpt ? dh_layernorm_bwd_ws_bytes(L->Ts, c.hidden) : dh_rmsnorm_bwd_ws_bytes(L->Ts, c.hidden);
   L->b_norm = take(cur, L->b_norm_bytes);
+  L->b_colsum_bytes = gpt ? dh_colsum_ws_bytes(L->T, (int)std::max(std::max(H, F), (size_t)L->n_qkv)) : 0;
+  L->b_colsum = take(cur, L->b_colsum_bytes);
+  L->b_dyp = take(cur, moe ? Tf * H * es : 0);
+  L->b_dprob = take(cur, moe ? 2 * T * 4 : 0);
+  L->b_dyg = take(cur, moe ? Tf * H * es : 0);
+  L->b_dxg = take(cur, moe ? Tf * H * es : 0);
   size_t gb = 0;
-  gb = std::max(gb, gw(0, 1, T, F, H));           // da = dout * Wd^T
-  gb = std::max(gb, gw(1, 0, F, H, T));           // dWd
-  gb = std::max(gb, gw(0, 1, T, H, 2 * F));       // dh2 = dgu * Wgu^T
-  gb = std::max(gb, gw(1, 0, H, 2 * F, T));       // dWgu
+  if (!moe) {
+    gb = std::max(gb, gw(0, 1, T, F, H));      // da = dz * Wd^T
+    gb = std::max(gb, gw(1, 0, F, H, T));      // dWd
+    gb = std::max(gb, gw(0, 1, T, H, Fin));    // dh2 = dgu * Wgu^T
+    gb = std::max(gb, gw(1, 0, H, Fin, T));    // dWgu
+  }
   gb = std::max(gb, gw(0, 1, T, L->n_o, H));      // do = dx2 * Wo^T
   gb = std::max(gb, gw(1, 0, L->n_o, H, T));      // dWo
   gb = std::max(gb, gw(0, 1, T, H, L->n_qkv));    // dh1 = dqkv * Wqkv^T
@@ -168,6 +263,8 @@ extern "C" void dh_layer_destroy(dh_layer* L) {
 extern "C" int dh_layer_bind_weights(dh_layer* L, const dh_weights* w) {
   if (!L || !w) DH_FAIL(DH_ERR_INVALID_ARG, "bind_weights: null pointer");
   if (!w->g1 || !w->Wqkv || !w->Wo || !w->g2 || !w->Wgu || !w->Wd) DH_FAIL(DH_ERR_INVALID_ARG, "bind_weights: a weight pointer is null");
+  if (L->c.arch == DH_ARCH_GPT && (!w->b1 || !w->bqkv || !w->bo || !w->b2 || !w->bfc1 || !w->bfc2))
+    DH_FAIL(DH_ERR_INVALID_ARG, "bind_weights: a bias pointer is null");
   L->w = *w;
   L->have_w = true;
   return DH_OK;
@@ -176,6 +273,8 @@ extern "C" int dh_layer_bind_weights(dh_layer* L, const dh_weights* w) {
 extern "C" int dh_layer_bind_wgrads(dh_layer* L, const dh_wgrads* g) {
   if (!L || !g) DH_FAIL(DH_ERR_INVALID_ARG, "bind_wgrads: null pointer");
   if (!g->dg1 || !g->dWqkv || !g->dWo || !g->dg2 || !g->dWgu || !g->dWd) DH_FAIL(DH_ERR_INVALID_ARG, "bind_wgrads: a gradient pointer is null");
+  if (L->c.arch == DH_ARCH_GPT && (!g->db1 || !g->dbqkv || !g->dbo || !g->db2 || !g->dbfc1 || !g->dbfc2))
+    DH_FAIL(DH_ERR_INVALID_ARG, "bind_wgrads: a bias gradient pointer is null");
   L->g = *g;
   L->have_g = true;
   return DH_OK;
@@ -193,39 +292,70 @@ extern "C" size_t dh_layer_workspace_bytes(const dh_layer* L, int kind) {
 
 // ------------------------------------------------------------------------------------ operators
 static int gemm(const dh_layer* L, bool ta, bool tb, int M, int N, int K, const void* A, const void* B, void* C, bool acc,
-                void* ws, size_t ws_bytes, hipStream_t s) {
+                void* ws, size_t ws_bytes, hipStream_t s, const void* bias = nullptr) {
   if (L->c.dtype == DH_BF16)
-    return dh_launch_gemm_bf16(ta, tb, M, N, K, (const bf16_t*)A, (const bf16_t*)B, C, acc, nullptr, ws, ws_bytes, s);
-  return dh_launch_gemm_f32(ta, tb, M, N, K, (const float*)A, (const float*)B, (float*)C, acc, nullptr, s);
+    return dh_launch_gemm_bf16(ta, tb, M, N, K, (const bf16_t*)A, (const bf16_t*)B, C, acc, (const bf16_t*)bias, ws, ws_bytes, s);
+  return dh_launch_gemm_f32(ta, tb, M, N, K, (const float*)A, (const float*)B, (float*)C, acc, (const float*)bias, s);
 }
 
-static int allreduce(const dh_layer* L, const void* own, const void* peers, void* out, hipStream_t s) {
+// Collective stand-in over parts = {own, peers[0], ..., peers[R-2]}, each `elems` elements.
+static int collective(const dh_layer* L, int kind, const void* own, const void* peers, size_t elems, void* out, hipStream_t s) {
   const void* parts[16];
-  const size_t n = (size_t)L->T * L->c.hidden;
   parts[0] = own;
-  for (int r = 1; r < L->c.n_ranks; r++) parts[r] = (const char*)peers + (size_t)(r - 1) * n * L->es;
-  return dh_comm_standin(DH_COMM_ALLREDUCE, L->c.n_ranks, parts, out, n, L->c.dtype, L->c.comm_blocks, (void*)s);
+  for (int r = 1; r < L->c.n_ranks; r++) parts[r] = (const char*)peers + (size_t)(r - 1) * elems * L->es;
+  return dh_comm_standin(kind, L->c.n_ranks, parts, out, elems, L->c.dtype, L->c.comm_blocks, (void*)s);
 }
 
-static int run_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hipStream_t s) {
+static dh_moe_tables moe_tables_of(const dh_layer* L, const void* saved) {
+  char* sv = (char*)saved;
+  dh_moe_tables t;
+  t.rank = (int32_t*)(sv + L->s_tab[0]);
+  t.dest = (int32_t*)(sv + L->s_tab[1]);
+  t.src_tok = (int32_t*)(sv + L->s_tab[2]);
+  t.send_of_recv = (int32_t*)(sv + L->s_tab[3]);
+  t.recv_of_send = (int32_t*)(sv + L->s_tab[4]);
+  t.counts = (int32_t*)(sv + L->s_tab[5]);
+  t.offsets = (int32_t*)(sv + L->s_tab[6]);
+  t.recv_start = (int32_t*)(sv + L->s_tab[7]);
+  t.group_rows = (int32_t*)(sv + L->s_tab[8]);
+  return t;
+}
+
+// The attention block's operators are shared by the three architectures.
+static int op_attn_fwd(dh_layer* L, char* sv, hipStream_t s) {
+  const dh_layer_config& c = L->c;
+  return dh_attn_fwd(c.dtype, c.batch, c.seq, c.n_q_heads, c.n_kv_heads, c.head_dim, sv + L->s_qkv, sv + L->s_o,
+                     (float*)(sv + L->s_lse), s);
+}
+static int op_attn_bwd(dh_layer* L, const char* sv, char* ws, hipStream_t s) {
+  const dh_layer_config& c = L->c;
+  return dh_attn_bwd(c.dtype, c.batch, c.seq, c.n_q_heads, c.n_kv_heads, c.head_dim, sv + L->s_qkv, sv + L->s_o, ws + L->b_do,
+                     (const float*)(sv + L->s_lse), ws + L->b_dqkv, (float*)(ws + L->b_delta), ws + L->b_attn, L->b_attn_bytes, s);
+}
+static int op_rope(dh_layer* L, void* qkv, int inverse, hipStream_t s) {
+  const dh_layer_config& c = L->c;
+  return dh_rope(c.dtype, L->T, c.seq, c.n_q_heads + c.n_kv_heads, c.head_dim, L->n_qkv, c.rope_base, inverse, qkv, s);
+}
+
+static int llama_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hipStream_t s) {
   const dh_layer_config& c = L->c;
   const int T = L->T, H = c.hidden, F = c.ffn, dt = c.dtype;
   char* sv = (char*)a.saved;
   void* gws = ws + L->f_gemm;
+  const size_t n = (size_t)T * H;
   switch (op) {
     case DH_F_NORM1:
       return dh_rmsnorm_fwd(dt, T, H, a.x, nullptr, L->w.g1, c.eps, nullptr, sv + L->s_h1, (float*)(sv + L->s_rstd1), s);
     case DH_F_QKV:
       return gemm(L, false, false, T, L->n_qkv, H, sv + L->s_h1, L->w.Wqkv, sv + L->s_qkv, false, gws, L->f_gemm_bytes, s);
     case DH_F_ROPE:
-      return dh_rope(dt, T, c.seq, c.n_q_heads + c.n_kv_heads, c.head_dim, L->n_qkv, c.rope_base, 0, sv + L->s_qkv, s);
+      return op_rope(L, sv + L->s_qkv, 0, s);
     case DH_F_ATTN:
-      return dh_attn_fwd(dt, c.batch, c.seq, c.n_q_heads, c.n_kv_heads, c.head_dim, sv + L->s_qkv, sv + L->s_o,
-                         (float*)(sv + L->s_lse), s);
+      return op_attn_fwd(L, sv, s);
     case DH_F_PROJ:
       return gemm(L, false, false, T, H, L->n_o, sv + L->s_o, L->w.Wo, ws + L->f_part, false, gws, L->f_gemm_bytes, s);
     case DH_F_AR1:
-      return allreduce(L, ws + L->f_part, a.peers_ar1, ws + L->f_red, s);
+      return collective(L, DH_COMM_ALLREDUCE, ws + L->f_part, a.peers_ar1, n, ws + L->f_red, s);
     case DH_F_NORM2:  // x2 = x + y (residual of the bias-dropout-add operator), h2 = norm(x2)
       return dh_rmsnorm_fwd(dt, T, H, a.x, ws + L->f_red, L->w.g2, c.eps, sv + L->s_x2, sv + L->s_h2, (float*)(sv + L->s_rstd2), s);
     case DH_F_FC1:
@@ -235,19 +365,19 @@ static int run_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hipSt
     case DH_F_FC2:
       return gemm(L, false, false, T, H, F, sv + L->s_a, L->w.Wd, ws + L->f_part, false, gws, L->f_gemm_bytes, s);
     case DH_F_AR2:
-      return allreduce(L, ws + L->f_part, a.peers_ar2, ws + L->f_red, s);
+      return collective(L, DH_COMM_ALLREDUCE, ws + L->f_part, a.peers_ar2, n, ws + L->f_red, s);
     case DH_F_BDA2:
-      return dh_add(dt, (size_t)T * H, sv + L->s_x2, ws + L->f_red, a.out, s);
+      return dh_add(dt, n, sv + L->s_x2, ws + L->f_red, a.out, s);
   }
   DH_FAIL(DH_ERR_INVALID_ARG, "unknown forward operator %d", op);
 }
 
-static int run_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipStream_t s) {
+static int llama_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipStream_t s) {
   const dh_layer_config& c = L->c;
   const int T = L->T, H = c.hidden, F = c.ffn, dt = c.dtype;
   const char* sv = (const char*)b.saved;
   void* gws = ws + L->b_gemm;
-  const size_t gwb = L->b_gemm_bytes;
+  const size_t gwb = L->b_gemm_bytes, n = (size_t)T * H;
   switch (op) {
     case DH_B_FC2_DGRAD:
       return gemm(L, false, true, T, F, H, b.dout, L->w.Wd, ws + L->b_da, false, gws, gwb, s);
@@ -260,7 +390,7 @@ static int run_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipSt
     case DH_B_FC1_WGRAD:
       return gemm(L, true, false, H, 2 * F, T, sv + L->s_h2, ws + L->b_dgu, L->g.dWgu, true, gws, gwb, s);
     case DH_B_AR3:
-      return allreduce(L, ws + L->b_part, b.peers_ar3, ws + L->b_red, s);
+      return collective(L, DH_COMM_ALLREDUCE, ws + L->b_part, b.peers_ar3, n, ws + L->b_red, s);
     case DH_B_NORM2:  // dx2 = dout + norm2_bwd(dh2)
       return dh_rmsnorm_bwd(dt, T, H, ws + L->b_red, sv + L->s_x2, L->w.g2, (const float*)(sv + L->s_rstd2), b.dout,
                             ws + L->b_dx2, L->g.dg2, ws + L->b_norm, L->b_norm_bytes, s);
@@ -269,17 +399,15 @@ static int run_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipSt
     case DH_B_PROJ_WGRAD:
       return gemm(L, true, false, L->n_o, H, T, sv + L->s_o, ws + L->b_dx2, L->g.dWo, true, gws, gwb, s);
     case DH_B_ATTN:
-      return dh_attn_bwd(dt, c.batch, c.seq, c.n_q_heads, c.n_kv_heads, c.head_dim, sv + L->s_qkv, sv + L->s_o, ws + L->b_do,
-                         (const float*)(sv + L->s_lse), ws + L->b_dqkv, (float*)(ws + L->b_delta), ws + L->b_attn,
-                         L->b_attn_bytes, s);
+      return op_attn_bwd(L, sv, ws, s);
     case DH_B_ROPE:
-      return dh_rope(dt, T, c.seq, c.n_q_heads + c.n_kv_heads, c.head_dim, L->n_qkv, c.rope_base, 1, ws + L->b_dqkv, s);
+      return op_rope(L, ws + L->b_dqkv, 1, s);
     case DH_B_QKV_DGRAD:
       return gemm(L, false, true, T, H, L->n_qkv, ws + L->b_dqkv, L->w.Wqkv, ws + L->b_part, false, gws, gwb, s);
     case DH_B_QKV_WGRAD:
       return gemm(L, true, false, H, L->n_qkv, T, sv + L->s_h1, ws + L->b_dqkv, L->g.dWqkv, true, gws, gwb, s);
     case DH_B_AR4:
-      return allreduce(L, ws + L->b_part, b.peers_ar4, ws + L->b_red, s);
+      return collective(L, DH_COMM_ALLREDUCE, ws + L->b_part, b.peers_ar4, n, ws + L->b_red, s);
     case DH_B_NORM1:  // dx = dx2 + norm1_bwd(dh1)
       return dh_rmsnorm_bwd(dt, T, H, ws + L->b_red, b.x, L->w.g1, (const float*)(sv + L->s_rstd1), ws + L->b_dx2, b.dx,
                             L->g.dg1, ws + L->b_norm, L->b_norm_bytes, s);
@@ -287,18 +415,231 @@ static int run_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipSt
   DH_FAIL(DH_ERR_INVALID_ARG, "unknown backward operator %d", op);
 }
 
+// GPT-style layer under tensor + sequence parallelism (Sec. 2.1).  The norms, residuals and the
+// layer's input/output live on this rank's Ts = T/R rows; GEMMs and attention see all T rows.
+static int gpt_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hipStream_t s) {
+  const dh_layer_config& c = L->c;
+  const int T = L->T, Ts = L->Ts, H = c.hidden, F = c.ffn, dt = c.dtype;
+  char* sv = (char*)a.saved;
+  void* gws = ws + L->f_gemm;
+  const size_t ns = (size_t)Ts * H;
+  switch (op) {
+    case DH_GF_NORM1:
+      return dh_layernorm_fwd(dt, Ts, H, a.x, nullptr, nullptr, L->w.g1, L->w.b1, c.eps, nullptr, ws + L->f_hs,
+                              (float*)(sv + L->s_mu1), (float*)(sv + L->s_rstd1), s);
+    case DH_GF_AG1:
+      return collective(L, DH_COMM_ALLGATHER, ws + L->f_hs, a.peers_ag1, ns, sv + L->s_h1, s);
+    case DH_GF_QKV:
+      return gemm(L, false, false, T, L->n_qkv, H, sv + L->s_h1, L->w.Wqkv, sv + L->s_qkv, false, gws, L->f_gemm_bytes, s, L->w.bqkv);
+    case DH_GF_ATTN:
+      return op_attn_fwd(L, sv, s);
+    case DH_GF_PROJ:
+      return gemm(L, false, false, T, H, L->n_o, sv + L->s_o, L->w.Wo, ws + L->f_part, false, gws, L->f_gemm_bytes, s);
+    case DH_GF_RS1:
+      return collective(L, DH_COMM_REDUCESCATTER, ws + L->f_part, a.peers_ar1, ns, ws + L->f_red, s);
+    case DH_GF_NORM2:  // x2 = x + y + bo, h2 = norm(x2)
+      return dh_layernorm_fwd(dt, Ts, H, a.x, ws + L->f_red, L->w.bo, L->w.g2, L->w.b2, c.eps, sv + L->s_x2, ws + L->f_hs,
+                              (float*)(sv + L->s_mu2), (float*)(sv + L->s_rstd2), s);
+    case DH_GF_AG2:
+      return collective(L, DH_COMM_ALLGATHER, ws + L->f_hs, a.peers_ag2, ns, sv + L->s_h2, s);
+    case DH_GF_FC1:
+      return gemm(L, false, false, T, F, H, sv + L->s_h2, L->w.Wgu, sv + L->s_gu, false, gws, L->f_gemm_bytes, s, L->w.bfc1);
+    case DH_GF_ACT:
+      return dh_gelu_fwd(dt, (size_t)T * F, sv + L->s_gu, sv + L->s_a, s);
+    case DH_GF_FC2:
+      return gemm(L, false, false, T, H, F, sv + L->s_a, L->w.Wd, ws + L->f_part, false, gws, L->f_gemm_bytes, s);
+    case DH_GF_RS2:
+      return collective(L, DH_COMM_REDUCESCATTER, ws + L->f_part, a.peers_ar2, ns, ws + L->f_red, s);
+    case DH_GF_BDA2:
+      return dh_bias_residual_add(dt, Ts, H, sv + L->s_x2, ws + L->f_red, L->w.bfc2, a.out, s);
+  }
+  DH_FAIL(DH_ERR_INVALID_ARG, "unknown forward operator %d", op);
+}
+
+static int gpt_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipStream_t s) {
+  const dh_layer_config& c = L->c;
+  const int T = L->T, Ts = L->Ts, H = c.hidden, F = c.ffn, dt = c.dtype;
+  const char* sv = (const char*)b.saved;
+  void* gws = ws + L->b_gemm;
+  const size_t gwb = L->b_gemm_bytes, ns = (size_t)Ts * H;
+  int rc;
+  switch (op) {
+    case DH_GB_AG3:  // the backward of a reduce-scatter gathers the gradient shards
+      return collective(L, DH_COMM_ALLGATHER, b.dout, b.peers_ag3, ns, ws + L->b_dz, s);
+    case DH_GB_FC2_DGRAD:
+      return gemm(L, false, true, T, F, H, ws + L->b_dz, L->w.Wd, ws + L->b_da, false, gws, gwb, s);
+    case DH_GB_FC2_WGRAD:
+      if ((rc = gemm(L, true, false, F, H, T, sv + L->s_a, ws + L->b_dz, L->g.dWd, true, gws, gwb, s))) return rc;
+      return dh_colsum(dt, Ts, H, b.dout, L->g.dbfc2, ws + L->b_colsum, L->b_colsum_bytes, s);
+    case DH_GB_ACT:
+      return dh_gelu_bwd(dt, (size_t)T * F, sv + L->s_gu, ws + L->b_da, ws + L->b_dgu, s);
+    case DH_GB_FC1_DGRAD:
+      return gemm(L, false, true, T, H, F, ws + L->b_dgu, L->w.Wgu, ws + L->b_part, false, gws, gwb, s);
+    case DH_GB_FC1_WGRAD:
+      if ((rc = gemm(L, true, false, H, F, T, sv + L->s_h2, ws + L->b_dgu, L->g.dWgu, true, gws, gwb, s))) return rc;
+      return dh_colsum(dt, T, F, ws + L->b_dgu, L->g.dbfc1, ws + L->b_colsum, L->b_colsum_bytes, s);
+    case DH_GB_RS3:  // the backward of an all-gather reduce-scatters
+      return collective(L, DH_COMM_REDUCESCATTER, ws + L->b_part, b.peers_ar3, ns, ws + L->b_red, s);
+    case DH_GB_NORM2:  // dx2 = dout + norm2_bwd(dh2)
+      return dh_layernorm_bwd(dt, Ts, H, ws + L->b_red, sv + L->s_x2, L->w.g2, (const float*)(sv + L->s_mu2),
+                              (const float*)(sv + L->s_rstd2), b.dout, ws + L->b_dx2, L->g.dg2, L->g.db2, ws + L->b_norm,
+                              L->b_norm_bytes, s);
+    case DH_GB_AG4:
+      return collective(L, DH_COMM_ALLGATHER, ws + L->b_dx2, b.peers_ag4, ns, ws + L->b_dy, s);
+    case DH_GB_PROJ_DGRAD:
+      return gemm(L, false, true, T, L->n_o, H, ws + L->b_dy, L->w.Wo, ws + L->b_do, false, gws, gwb, s);
+    case DH_GB_PROJ_WGRAD:
+      if ((rc = gemm(L, true, false, L->n_o, H, T, sv + L->s_o, ws + L->b_dy, L->g.dWo, true, gws, gwb, s))) return rc;
+      return dh_colsum(dt, Ts, H, ws + L->b_dx2, L->g.dbo, ws + L->b_colsum, L->b_colsum_bytes, s);
+    case DH_GB_ATTN:
+      return op_attn_bwd(L, sv, ws, s);
+    case DH_GB_QKV_DGRAD:
+      return gemm(L, false, true, T, H, L->n_qkv, ws + L->b_dqkv, L->w.Wqkv, ws + L->b_part, false, gws, gwb, s);
+    case DH_GB_QKV_WGRAD:
+      if ((rc = gemm(L, true, false, H, L->n_qkv, T, sv + L->s_h1, ws + L->b_dqkv, L->g.dWqkv, true, gws, gwb, s))) return rc;
+      return dh_colsum(dt, T, L->n_qkv, ws + L->b_dqkv, L->g.dbqkv, ws + L->b_colsum, L->b_colsum_bytes, s);
+    case DH_GB_RS4:
+      return collective(L, DH_COMM_REDUCESCATTER, ws + L->b_part, b.peers_ar4, ns, ws + L->b_red, s);
+    case DH_GB_NORM1:  // dx = dx2 + norm1_bwd(dh1)
+      return dh_layernorm_bwd(dt, Ts, H, ws + L->b_red, b.x, L->w.g1, (const float*)(sv + L->s_mu1),
+                              (const float*)(sv + L->s_rstd1), ws + L->b_dx2, b.dx, L->g.dg1, L->g.db1, ws + L->b_norm,
+                              L->b_norm_bytes, s);
+  }
+  DH_FAIL(DH_ERR_INVALID_ARG, "unknown backward operator %d", op);
+}
+
+// MoE layer: attention as in the Llama layer without collectives; the FFN is routed (top-2), its rows
+// permuted by expert, exchanged by the all-to-all stand-in and run through grouped GEMMs.
+static int moe_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hipStream_t s) {
+  const dh_layer_config& c = L->c;
+  const int T = L->T, Tf = L->Tf, H = c.hidden, F = c.ffn, dt = c.dtype, E = c.n_experts, nl = c.n_local_experts;
+  char* sv = (char*)a.saved;
+  void* gws = ws + L->f_gemm;
+  const dh_moe_tables tb = moe_tables_of(L, sv);
+  int32_t* idx = (int32_t*)(sv + L->s_idx);
+  float* prob = (float*)(sv + L->s_prob);
+  int rc;
+  switch (op) {
+    case DH_MF_NORM1:
+      return dh_rmsnorm_fwd(dt, T, H, a.x, nullptr, L->w.g1, c.eps, nullptr, sv + L->s_h1, (float*)(sv + L->s_rstd1), s);
+    case DH_MF_QKV:
+      return gemm(L, false, false, T, L->n_qkv, H, sv + L->s_h1, L->w.Wqkv, sv + L->s_qkv, false, gws, L->f_gemm_bytes, s);
+    case DH_MF_ROPE:
+      return op_rope(L, sv + L->s_qkv, 0, s);
+    case DH_MF_ATTN:
+      return op_attn_fwd(L, sv, s);
+    case DH_MF_PROJ:
+      return gemm(L, false, false, T, H, L->n_o, sv + L->s_o, L->w.Wo, ws + L->f_part, false, gws, L->f_gemm_bytes, s);
+    case DH_MF_NORM2:
+      return dh_rmsnorm_fwd(dt, T, H, a.x, ws + L->f_part, L->w.g2, c.eps, sv + L->s_x2, sv + L->s_h2, (float*)(sv + L->s_rstd2), s);
+    case DH_MF_ROUTE:
+      if ((rc = dh_moe_route(T, E, a.logits, idx, prob, s))) return rc;
+      return dh_moe_plan(T, E, nl, idx, &tb, s);
+    case DH_MF_PERMUTE:
+      return dh_moe_gather_rows(dt, Tf, H, sv + L->s_h2, tb.src_tok, ws + L->f_xp, 0, s);
+    case DH_MF_A2A_DISPATCH:
+      return dh_moe_gather_rows(dt, Tf, H, ws + L->f_xp, tb.send_of_recv, sv + L->s_xg, c.comm_blocks, s);
+    case DH_MF_FC1:
+      return dh_gemm_grouped(dt, 0, nl, tb.group_rows, Tf, H, 2 * F, sv + L->s_xg, L->w.Wgu, sv + L->s_gu, s);
+    case DH_MF_ACT:
+      return dh_swiglu_fwd(dt, Tf, F, sv + L->s_gu, sv + L->s_a, s);
+    case DH_MF_FC2:
+      return dh_gemm_grouped(dt, 0, nl, tb.group_rows, Tf, F, H, sv + L->s_a, L->w.Wd, ws + L->f_yg, s);
+    case DH_MF_A2A_COMBINE:
+      return dh_moe_gather_rows(dt, Tf, H, ws + L->f_yg, tb.recv_of_send, sv + L->s_yp, c.comm_blocks, s);
+    case DH_MF_UNPERMUTE:  // out = x2 + sum_k p_k * (expert output of assignment k)
+      return dh_moe_combine(dt, T, H, sv + L->s_yp, tb.dest, prob, sv + L->s_x2, a.out, s);
+  }
+  DH_FAIL(DH_ERR_INVALID_ARG, "unknown forward operator %d", op);
+}
+
+static int moe_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipStream_t s) {
+  const dh_layer_config& c = L->c;
+  const int T = L->T, Tf = L->Tf, H = c.hidden, F = c.ffn, dt = c.dtype, E = c.n_experts, nl = c.n_local_experts;
+  const char* sv = (const char*)b.saved;
+  void* gws = ws + L->b_gemm;
+  const size_t gwb = L->b_gemm_bytes;
+  const dh_moe_tables tb = moe_tables_of(L, sv);
+  const int32_t* idx = (const int32_t*)(sv + L->s_idx);
+  const float* prob = (const float*)(sv + L->s_prob);
+  switch (op) {
+    case DH_MB_UNPERMUTE:
+      return dh_moe_combine_bwd(dt, T, H, b.dout, sv + L->s_yp, tb.dest, prob, ws + L->b_dyp, (float*)(ws + L->b_dprob), s);
+    case DH_MB_ROUTE:
+      return dh_moe_route_bwd(T, E, (const float*)(ws + L->b_dprob), idx, prob, b.dlogits, s);
+    case DH_MB_A2A_DISPATCH:
+      return dh_moe_gather_rows(dt, Tf, H, ws + L->b_dyp, tb.send_of_recv, ws + L->b_dyg, c.comm_blocks, s);
+    case DH_MB_FC2_DGRAD:
+      return dh_gemm_grouped(dt, 1, nl, tb.group_rows, Tf, H, F, ws + L->b_dyg, L->w.Wd, ws + L->b_da, s);
+    case DH_MB_FC2_WGRAD:
+      return dh_gemm_grouped(dt, 2, nl, tb.group_rows, Tf, F, H, sv + L->s_a, ws + L->b_dyg, L->g.dWd, s);
+    case DH_MB_ACT:
+      return dh_swiglu_bwd(dt, Tf, F, sv + L->s_gu, ws + L->b_da, ws + L->b_dgu, s);
+    case DH_MB_FC1_DGRAD:
+      return dh_gemm_grouped(dt, 1, nl, tb.group_rows, Tf, 2 * F, H, ws + L->b_dgu, L->w.Wgu, ws + L->b_dxg, s);
+    case DH_MB_FC1_WGRAD:
+      return dh_gemm_grouped(dt, 2, nl, tb.group_rows, Tf, H, 2 * F, sv + L->s_xg, ws + L->b_dgu, L->g.dWgu, s);
+    case DH_MB_A2A_COMBINE:  // the un-dispatched rows reuse the buffer of the dispatched upstream gradient
+      return dh_moe_gather_rows(dt, Tf, H, ws + L->b_dxg, tb.recv_of_send, ws + L->b_dyp, c.comm_blocks, s);
+    case DH_MB_PERMUTE:  // dh2[t] = sum of the gradients of token t's two permuted copies
+      return dh_moe_combine(dt, T, H, ws + L->b_dyp, tb.dest, nullptr, nullptr, ws + L->b_red, s);
+    case DH_MB_NORM2:
+      return dh_rmsnorm_bwd(dt, T, H, ws + L->b_red, sv + L->s_x2, L->w.g2, (const float*)(sv + L->s_rstd2), b.dout,
+                            ws + L->b_dx2, L->g.dg2, ws + L->b_norm, L->b_norm_bytes, s);
+    case DH_MB_PROJ_DGRAD:
+      return gemm(L, false, true, T, L->n_o, H, ws + L->b_dx2, L->w.Wo, ws + L->b_do, false, gws, gwb, s);
+    case DH_MB_PROJ_WGRAD:
+      return gemm(L, true, false, L->n_o, H, T, sv + L->s_o, ws + L->b_dx2, L->g.dWo, true, gws, gwb, s);
+    case DH_MB_ATTN:
+      return op_attn_bwd(L, sv, ws, s);
+    case DH_MB_ROPE:
+      return op_rope(L, ws + L->b_dqkv, 1, s);
+    case DH_MB_QKV_DGRAD:
+      return gemm(L, false, true, T, H, L->n_qkv, ws + L->b_dqkv, L->w.Wqkv, ws + L->b_part, false, gws, gwb, s);
+    case DH_MB_QKV_WGRAD:
+      return gemm(L, true, false, H, L->n_qkv, T, sv + L->s_h1, ws + L->b_dqkv, L->g.dWqkv, true, gws, gwb, s);
+    case DH_MB_NORM1:
+      return dh_rmsnorm_bwd(dt, T, H, ws + L->b_part, b.x, L->w.g1, (const float*)(sv + L->s_rstd1), ws + L->b_dx2, b.dx,
+                            L->g.dg1, ws + L->b_norm, L->b_norm_bytes, s);
+  }
+  DH_FAIL(DH_ERR_INVALID_ARG, "unknown backward operator %d", op);
+}
+
+static int run_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hipStream_t s) {
+  switch (L->c.arch) {
+    case DH_ARCH_GPT: return gpt_fwd_op(L, op, a, ws, s);
+    case DH_ARCH_MOE: return moe_fwd_op(L, op, a, ws, s);
+    default: return llama_fwd_op(L, op, a, ws, s);
+  }
+}
+static int run_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipStream_t s) {
+  switch (L->c.arch) {
+    case DH_ARCH_GPT: return gpt_bwd_op(L, op, b, ws, s);
+    case DH_ARCH_MOE: return moe_bwd_op(L, op, b, ws, s);
+    default: return llama_bwd_op(L, op, b, ws, s);
+  }
+}
+
 static int check_fwd_args(const dh_layer* L, const dh_fwd_args* a) {
   if (!L || !a) DH_FAIL(DH_ERR_INVALID_ARG, "forward: null pointer");
   if (!L->have_w) DH_FAIL(DH_ERR_INVALID_ARG, "forward: weights not bound");
-  if (L->T > 0 && (!a->x || !a->out || !a->saved)) DH_FAIL(DH_ERR_INVALID_ARG, "forward: x/out/saved is null");
-  if (L->T > 0 && L->c.n_ranks > 1 && (!a->peers_ar1 || !a->peers_ar2)) DH_FAIL(DH_ERR_INVALID_ARG, "forward: peer partials are null but n_ranks > 1");
+  if (L->T == 0) return DH_OK;
+  if (!a->x || !a->out || !a->saved) DH_FAIL(DH_ERR_INVALID_ARG, "forward: x/out/saved is null");
+  if (L->c.n_ranks > 1 && (!a->peers_ar1 || !a->peers_ar2)) DH_FAIL(DH_ERR_INVALID_ARG, "forward: peer partials are null but n_ranks > 1");
+  if (L->c.arch == DH_ARCH_GPT && L->c.n_ranks > 1 && (!a->peers_ag1 || !a->peers_ag2))
+    DH_FAIL(DH_ERR_INVALID_ARG, "forward: all-gather peer shards are null but n_ranks > 1");
+  if (L->c.arch == DH_ARCH_MOE && !a->logits) DH_FAIL(DH_ERR_INVALID_ARG, "forward: router logits are null");
   return DH_OK;
 }
 static int check_bwd_args(const dh_layer* L, const dh_bwd_args* b) {
   if (!L || !b) DH_FAIL(DH_ERR_INVALID_ARG, "backward: null pointer");
   if (!L->have_w || !L->have_g) DH_FAIL(DH_ERR_INVALID_ARG, "backward: weights or gradient buffers not bound");
-  if (L->T > 0 && (!b->dout || !b->dx || !b->x || !b->saved)) DH_FAIL(DH_ERR_INVALID_ARG, "backward: dout/dx/x/saved is null");
-  if (L->T > 0 && L->c.n_ranks > 1 && (!b->peers_ar3 || !b->peers_ar4)) DH_FAIL(DH_ERR_INVALID_ARG, "backward: peer partials are null but n_ranks > 1");
+  if (L->T == 0) return DH_OK;
+  if (!b->dout || !b->dx || !b->x || !b->saved) DH_FAIL(DH_ERR_INVALID_ARG, "backward: dout/dx/x/saved is null");
+  if (L->c.n_ranks > 1 && (!b->peers_ar3 || !b->peers_ar4)) DH_FAIL(DH_ERR_INVALID_ARG, "backward: peer partials are null but n_ranks > 1");
+  if (L->c.arch == DH_ARCH_GPT && L->c.n_ranks > 1 && (!b->peers_ag3 || !b->peers_ag4))
+    DH_FAIL(DH_ERR_INVALID_ARG, "backward: all-gather peer shards are null but n_ranks > 1");
+  if (L->c.arch == DH_ARCH_MOE && !b->dlogits) DH_FAIL(DH_ERR_INVALID_ARG, "backward: dlogits is null");
   return DH_OK;
 }
 static int check_ws(const dh_layer* L, int kind, const void* ws, size_t ws_bytes) {
@@ -308,13 +649,32 @@ static int check_ws(const dh_layer* L, int kind, const void* ws, size_t ws_bytes
   return DH_OK;
 }
 
+// Default operator order of a strand: a topological order taking the smallest ready operator id first
+// (the ids are numbered so that this is simply 0, 1, 2, ... for every architecture).
+static void default_order(const dh_op_graph& g, int* order) {
+  int indeg[DH_MAX_OPS] = {0};
+  bool done[DH_MAX_OPS] = {false};
+  for (int e = 0; e < g.n_deps; e++) indeg[g.dep_dst[e]]++;
+  for (int k = 0; k < g.n_ops; k++) {
+    int pick = -1;
+    for (int i = 0; i < g.n_ops && pick < 0; i++)
+      if (!done[i] && indeg[i] == 0) pick = i;
+    order[k] = pick;
+    done[pick] = true;
+    for (int e = 0; e < g.n_deps; e++)
+      if (g.dep_src[e] == pick) indeg[g.dep_dst[e]]--;
+  }
+}
+
 extern "C" int dh_layer_fwd(dh_layer* L, const dh_fwd_args* a, void* ws, size_t ws_bytes, void* stream) {
   int rc = check_fwd_args(L, a);
   if (rc) return rc;
   if ((rc = check_ws(L, DH_WS_FWD, ws, ws_bytes))) return rc;
   if (L->T == 0) return DH_OK;
-  for (int op = 0; op < DH_F_NOPS; op++)
-    if ((rc = run_fwd_op(L, op, *a, (char*)ws, (hipStream_t)stream))) return rc;
+  int order[DH_MAX_OPS];
+  default_order(L->gf, order);
+  for (int k = 0; k < L->gf.n_ops; k++)
+    if ((rc = run_fwd_op(L, order[k], *a, (char*)ws, (hipStream_t)stream))) return rc;
   return DH_OK;
 }
 
@@ -323,21 +683,24 @@ extern "C" int dh_layer_bwd(dh_layer* L, const dh_bwd_args* b, void* ws, size_t 
   if (rc) return rc;
   if ((rc = check_ws(L, DH_WS_BWD, ws, ws_bytes))) return rc;
   if (L->T == 0) return DH_OK;
-  for (int op = 0; op < DH_B_NOPS; op++)
-    if ((rc = run_bwd_op(L, op, *b, (char*)ws, (hipStream_t)stream))) return rc;
+  int order[DH_MAX_OPS];
+  default_order(L->gb, order);
+  for (int k = 0; k < L->gb.n_ops; k++)
+    if ((rc = run_bwd_op(L, order[k], *b, (char*)ws, (hipStream_t)stream))) return rc;
   return DH_OK;
 }
 
 extern "C" int dh_plan_sequential(const dh_layer* L, dh_plan* out) {
   if (!L || !out) DH_FAIL(DH_ERR_INVALID_ARG, "plan_sequential: null pointer");
   memset(out, 0, sizeof(*out));
-  out->n_fwd = DH_F_NOPS;
-  out->n_bwd = DH_B_NOPS;
-  for (int i = 0; i < DH_F_NOPS; i++) out->fwd_order[i] = i;
-  for (int j = 0; j < DH_B_NOPS; j++) out->bwd_order[j] = j;
+  const int nf = L->gf.n_ops, nb = L->gb.n_ops;
+  out->n_fwd = nf;
+  out->n_bwd = nb;
+  default_order(L->gf, out->fwd_order);
+  default_order(L->gb, out->bwd_order);
   out->n_pairs = 2;
-  out->pairs[0] = {0, DH_F_NOPS, 0, 0};
-  out->pairs[1] = {DH_F_NOPS, DH_F_NOPS, 0, DH_B_NOPS};
+  out->pairs[0] = {0, nf, 0, 0};
+  out->pairs[1] = {nf, nf, 0, nb};
   return DH_OK;
 }
 
@@ -441,8 +804,9 @@ extern "C" int dh_profile_pairs(dh_layer* L, const dh_fwd_args* alpha, const dh_
   char* ws_f = (char*)ws;
   char* ws_b = (char*)ws + L->fwd_bytes;
   memset(out, 0, sizeof(*out));
-  out->n_fwd = DH_F_NOPS;
-  out->n_bwd = DH_B_NOPS;
+  const int NF = L->gf.n_ops, NB = L->gb.n_ops;
+  out->n_fwd = NF;
+  out->n_bwd = NB;
   if (L->T == 0) return DH_OK;
   hipEvent_t e0, e1, e2, e3, gate;
   DH_HIP(hipEventCreate(&e0));
@@ -461,7 +825,7 @@ extern "C" int dh_profile_pairs(dh_layer* L, const dh_fwd_args* alpha, const dh_
   };
   // solo times
   for (int dir = 0; dir < 2; dir++) {
-    const int n = dir == 0 ? DH_F_NOPS : DH_B_NOPS;
+    const int n = dir == 0 ? NF : NB;
     for (int op = 0; op < n; op++) {
       hipStream_t s = stream_of(dir, op);
       TimedOp t{dir, op};
@@ -478,8 +842,8 @@ extern "C" int dh_profile_pairs(dh_layer* L, const dh_fwd_args* alpha, const dh_
     }
   }
   // pairs: both operators repeated so that the two streams stay busy for about the same window
-  for (int i = 0; i < DH_F_NOPS; i++)
-    for (int j = 0; j < DH_B_NOPS; j++) {
+  for (int i = 0; i < NF; i++)
+    for (int j = 0; j < NB; j++) {
       const double ta = out->t_fwd[i], tb = out->t_bwd[j];
       const double window = std::max(ta, tb) * reps;
       const int ra = std::max(1, (int)std::lround(window / ta)), rb = std::max(1, (int)std::lround(window / tb));

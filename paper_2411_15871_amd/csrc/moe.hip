@@ -117,10 +117,10 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(int n_rows, int H, con
   }
 }
 
-// y[t,:] = w0*yp[dest[t,0],:] + w1*yp[dest[t,1],:]; weights = prob[t,:] or 1 when prob == nullptr.
+// y[t,:] = w0*yp[dest[t,0],:] + w1*yp[dest[t,1],:] (+ res[t,:]); weights = prob[t,:] or 1 when prob == nullptr.
 template <typename T>
 __global__ __launch_bounds__(256) void combine_kernel(int Ttok, int H, const T* __restrict__ yp, const int32_t* __restrict__ dest,
-                                                      const float* __restrict__ prob, T* __restrict__ y) {
+                                                      const float* __restrict__ prob, const T* __restrict__ res, T* __restrict__ y) {
   const int chunks = H / 8;
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (size_t)Ttok * chunks) return;
@@ -132,6 +132,11 @@ __global__ __launch_bounds__(256) void combine_kernel(int Ttok, int H, const T* 
   b.load(yp + (size_t)dest[2 * t + 1] * H + c);
 #pragma unroll
   for (int k = 0; k < 8; k++) a.v[k] = w0 * a.v[k] + w1 * b.v[k];
+  if (res != nullptr) {
+    b.load(res + t * H + c);
+#pragma unroll
+    for (int k = 0; k < 8; k++) a.v[k] += b.v[k];
+  }
   a.store(y + t * H + c);
 }
 
@@ -219,14 +224,14 @@ extern "C" int dh_moe_gather_rows(int dtype, int n_rows, int H, const void* in, 
   return DH_OK;
 }
 
-extern "C" int dh_moe_combine(int dtype, int T, int H, const void* yp, const int32_t* dest, const float* prob, void* y,
-                              void* stream) {
+extern "C" int dh_moe_combine(int dtype, int T, int H, const void* yp, const int32_t* dest, const float* prob,
+                              const void* residual, void* y, void* stream) {
   if (T < 0 || H <= 0 || H % 8) DH_FAIL(DH_ERR_SHAPE, "moe_combine: T=%d H=%d (H must be a positive multiple of 8)", T, H);
   if (T == 0) return DH_OK;
   if (!yp || !dest || !y) DH_FAIL(DH_ERR_INVALID_ARG, "moe_combine: null pointer");
   unsigned grid = (unsigned)(((size_t)T * (H / 8) + 255) / 256);
-  if (dtype == DH_BF16) combine_kernel<bf16_t><<<grid, 256, 0, (hipStream_t)stream>>>(T, H, (const bf16_t*)yp, dest, prob, (bf16_t*)y);
-  else combine_kernel<float><<<grid, 256, 0, (hipStream_t)stream>>>(T, H, (const float*)yp, dest, prob, (float*)y);
+  if (dtype == DH_BF16) combine_kernel<bf16_t><<<grid, 256, 0, (hipStream_t)stream>>>(T, H, (const bf16_t*)yp, dest, prob, (const bf16_t*)residual, (bf16_t*)y);
+  else combine_kernel<float><<<grid, 256, 0, (hipStream_t)stream>>>(T, H, (const float*)yp, dest, prob, (const float*)residual, (float*)y);
   DH_LAUNCH_CHECK();
   return DH_OK;
 }

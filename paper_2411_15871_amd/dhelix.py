@@ -19,14 +19,20 @@ lib = C.CDLL(_LIB_PATH)
 DH_OK, DH_ERR_INVALID_ARG, DH_ERR_SHAPE, DH_ERR_WORKSPACE_TOO_SMALL = 0, -1, -2, -3
 DH_ERR_PLAN_INVALID, DH_ERR_HIP, DH_ERR_UNSUPPORTED = -4, -5, -6
 DH_F32, DH_BF16 = 0, 1
-DH_ARCH_LLAMA = 0
+DH_ARCH_LLAMA, DH_ARCH_GPT, DH_ARCH_MOE = 0, 1, 2
 DH_WS_FWD, DH_WS_BWD, DH_WS_SI = 0, 1, 2
 DH_COMM_ALLREDUCE, DH_COMM_ALLGATHER, DH_COMM_REDUCESCATTER = 0, 1, 2
 DH_MAX_OPS, DH_MAX_DEPS = 32, 96
-FWD_OPS = ["F_NORM1", "F_QKV", "F_ROPE", "F_ATTN", "F_PROJ", "F_AR1", "F_NORM2", "F_FC1", "F_ACT", "F_FC2", "F_AR2",
-           "F_BDA2"]
-BWD_OPS = ["B_FC2_DGRAD", "B_FC2_WGRAD", "B_ACT", "B_FC1_DGRAD", "B_FC1_WGRAD", "B_AR3", "B_NORM2", "B_PROJ_DGRAD",
-           "B_PROJ_WGRAD", "B_ATTN", "B_ROPE", "B_QKV_DGRAD", "B_QKV_WGRAD", "B_AR4", "B_NORM1"]
+
+
+def op_names(arch, direction):
+    """Operator names of an architecture's forward (0) or backward (1) graph, in id order."""
+    out = []
+    while True:
+        r = lib.dh_op_name(arch, direction, len(out))
+        if r is None:
+            return out
+        out.append(r.decode())
 
 
 class DhelixError(RuntimeError):
@@ -38,23 +44,26 @@ class DhelixError(RuntimeError):
 class dh_layer_config(C.Structure):
     _fields_ = [("arch", C.c_int), ("dtype", C.c_int), ("batch", C.c_int), ("seq", C.c_int), ("hidden", C.c_int),
                 ("n_q_heads", C.c_int), ("n_kv_heads", C.c_int), ("head_dim", C.c_int), ("ffn", C.c_int),
-                ("eps", C.c_float), ("rope_base", C.c_float), ("n_ranks", C.c_int), ("comm_blocks", C.c_int)]
+                ("eps", C.c_float), ("rope_base", C.c_float), ("n_ranks", C.c_int), ("comm_blocks", C.c_int),
+                ("n_experts", C.c_int), ("n_local_experts", C.c_int)]
 
 
 class dh_weights(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("g1", "Wqkv", "Wo", "g2", "Wgu", "Wd")]
+    _fields_ = [(n, C.c_void_p) for n in ("g1", "Wqkv", "Wo", "g2", "Wgu", "Wd", "b1", "bqkv", "bo", "b2", "bfc1", "bfc2")]
 
 
 class dh_wgrads(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("dg1", "dWqkv", "dWo", "dg2", "dWgu", "dWd")]
+    _fields_ = [(n, C.c_void_p) for n in ("dg1", "dWqkv", "dWo", "dg2", "dWgu", "dWd", "db1", "dbqkv", "dbo", "db2", "dbfc1",
+                                          "dbfc2")]
 
 
 class dh_fwd_args(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("x", "out", "saved", "peers_ar1", "peers_ar2")]
+    _fields_ = [(n, C.c_void_p) for n in ("x", "out", "saved", "peers_ar1", "peers_ar2", "peers_ag1", "peers_ag2", "logits")]
 
 
 class dh_bwd_args(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("dout", "dx", "x", "saved", "peers_ar3", "peers_ar4")]
+    _fields_ = [(n, C.c_void_p) for n in ("dout", "dx", "x", "saved", "peers_ar3", "peers_ar4", "peers_ag3", "peers_ag4",
+                                          "dlogits")]
 
 
 class dh_op_graph(C.Structure):
@@ -98,7 +107,7 @@ SIGNATURES = {
     "dh_layer_fwd": (_I, [_P, C.POINTER(dh_fwd_args), _P, _Z, _P]),
     "dh_layer_bwd": (_I, [_P, C.POINTER(dh_bwd_args), _P, _Z, _P]),
     "dh_layer_op_graph": (_I, [_P, _I, C.POINTER(dh_op_graph)]),
-    "dh_op_name": (C.c_char_p, [_I, _I]),
+    "dh_op_name": (C.c_char_p, [_I, _I, _I]),
     "dh_oef": (_D, [_D, _D, _D]),
     "dh_segment_cost": (_D, [C.POINTER(dh_overlap_table), C.POINTER(_I), _I, C.POINTER(_I), _I]),
     "dh_profile_pairs": (_I, [_P, C.POINTER(dh_fwd_args), C.POINTER(dh_bwd_args), _P, _Z, _P, _P, _P, _I,
@@ -128,7 +137,7 @@ SIGNATURES = {
     "dh_moe_route_bwd": (_I, [_I, _I, _P, _P, _P, _P, _P]),
     "dh_moe_plan": (_I, [_I, _I, _I, _P, C.POINTER(dh_moe_tables), _P]),
     "dh_moe_gather_rows": (_I, [_I, _I, _I, _P, _P, _P, _I, _P]),
-    "dh_moe_combine": (_I, [_I, _I, _I, _P, _P, _P, _P, _P]),
+    "dh_moe_combine": (_I, [_I, _I, _I, _P, _P, _P, _P, _P, _P]),
     "dh_moe_combine_bwd": (_I, [_I, _I, _I, _P, _P, _P, _P, _P, _P, _P]),
     "dh_gemm_grouped": (_I, [_I, _I, _I, _P, _I, _I, _I, _P, _P, _P, _P]),
     "dh_gemm_bias": (_I, [_I, _I, _I, _I, _I, _I, _P, _P, _P, _P, _I, _P, _Z, _P]),
@@ -201,12 +210,14 @@ def dh_layer_workspace_bytes(layer, kind):
     return lib.dh_layer_workspace_bytes(layer, kind)
 
 
-def fwd_args(x, out, saved, peers_ar1=None, peers_ar2=None):
-    return dh_fwd_args(_ptr(x), _ptr(out), _ptr(saved), _ptr(peers_ar1), _ptr(peers_ar2))
+def fwd_args(x, out, saved, peers_ar1=None, peers_ar2=None, peers_ag1=None, peers_ag2=None, logits=None):
+    return dh_fwd_args(_ptr(x), _ptr(out), _ptr(saved), _ptr(peers_ar1), _ptr(peers_ar2), _ptr(peers_ag1), _ptr(peers_ag2),
+                       _ptr(logits))
 
 
-def bwd_args(dout, dx, x, saved, peers_ar3=None, peers_ar4=None):
-    return dh_bwd_args(_ptr(dout), _ptr(dx), _ptr(x), _ptr(saved), _ptr(peers_ar3), _ptr(peers_ar4))
+def bwd_args(dout, dx, x, saved, peers_ar3=None, peers_ar4=None, peers_ag3=None, peers_ag4=None, dlogits=None):
+    return dh_bwd_args(_ptr(dout), _ptr(dx), _ptr(x), _ptr(saved), _ptr(peers_ar3), _ptr(peers_ar4), _ptr(peers_ag3),
+                       _ptr(peers_ag4), _ptr(dlogits))
 
 
 def dh_layer_fwd(layer, args, ws, ws_bytes, stream=None):
@@ -223,8 +234,8 @@ def dh_layer_op_graph(layer, direction):
     return g
 
 
-def dh_op_name(direction, op):
-    r = lib.dh_op_name(direction, op)
+def dh_op_name(arch, direction, op):
+    r = lib.dh_op_name(arch, direction, op)
     return r.decode() if r else None
 
 
@@ -415,8 +426,8 @@ def dh_moe_gather_rows(dtype, n_rows, H, inp, row_map, out, n_blocks=0, stream=N
     _check(lib.dh_moe_gather_rows(dtype, n_rows, H, _ptr(inp), _ptr(row_map), _ptr(out), n_blocks, _stream(stream)))
 
 
-def dh_moe_combine(dtype, T, H, yp, dest, prob, y, stream=None):
-    _check(lib.dh_moe_combine(dtype, T, H, _ptr(yp), _ptr(dest), _ptr(prob), _ptr(y), _stream(stream)))
+def dh_moe_combine(dtype, T, H, yp, dest, prob, residual, y, stream=None):
+    _check(lib.dh_moe_combine(dtype, T, H, _ptr(yp), _ptr(dest), _ptr(prob), _ptr(residual), _ptr(y), _stream(stream)))
 
 
 def dh_moe_combine_bwd(dtype, T, H, dy, yp, dest, prob, dyp, dprob, stream=None):
@@ -466,3 +477,7 @@ def dh_colsum_ws_bytes(T, N):
 
 def dh_colsum(dtype, T, N, x, out, ws, ws_bytes, stream=None):
     _check(lib.dh_colsum(dtype, T, N, _ptr(x), _ptr(out), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+FWD_OPS = op_names(DH_ARCH_LLAMA, 0)
+BWD_OPS = op_names(DH_ARCH_LLAMA, 1)

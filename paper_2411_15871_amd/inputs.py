@@ -5,9 +5,9 @@ the method's arithmetic and is shared by the tests' oracle side and GPU side so 
 see bit-identical inputs.
 
 Recipe (the paper trains on unspecified token streams and reports throughput only, so all
-inputs are synthetic): weights ~ N(0, 0.02), norm gains 1 + N(0, 0.02), layer inputs
-~ N(0, 1), upstream gradients ~ N(0, 1e-2), frozen peer partials ~ N(0, 1e-2), router logits
-~ N(0, 1).  Values are drawn in float64 from numpy's Philox generator, cast to float32 and, for
+inputs are synthetic): weights and biases ~ N(0, 0.02), norm gains 1 + N(0, 0.02), layer inputs
+~ N(0, 1), upstream gradients ~ N(0, 1e-2), frozen peer partials ~ N(0, 1e-2) (peer shards entering a
+forward all-gather are normalised activations, ~ N(0, 1)), router logits ~ N(0, 1).  Values are drawn in float64 from numpy's Philox generator, cast to float32 and, for
 the bf16 configurations, rounded to the nearest-even bf16 value (still held as float32).
 """
 import numpy as np
@@ -46,6 +46,27 @@ def llama_weights(H, n_qkv, n_o, F, bf16, seed=SEED_WEIGHTS):
     }
 
 
+def gpt_weights(H, n_qkv, n_o, F, bf16, seed=SEED_WEIGHTS):
+    """Weights of one GPT-style layer shard: LayerNorm gains/shifts, two-matrix GeLU MLP (Wgu = first matrix [H,F],
+    Wd = second [F,H]) and a bias per linear."""
+    return {
+        "g1": normal(seed + 0, (H,), 0.02, 1.0, bf16), "b1": normal(seed + 6, (H,), 0.02, 0.0, bf16),
+        "Wqkv": normal(seed + 1, (H, n_qkv), 0.02, 0.0, bf16), "bqkv": normal(seed + 7, (n_qkv,), 0.02, 0.0, bf16),
+        "Wo": normal(seed + 2, (n_o, H), 0.02, 0.0, bf16), "bo": normal(seed + 8, (H,), 0.02, 0.0, bf16),
+        "g2": normal(seed + 3, (H,), 0.02, 1.0, bf16), "b2": normal(seed + 9, (H,), 0.02, 0.0, bf16),
+        "Wgu": normal(seed + 4, (H, F), 0.02, 0.0, bf16), "bfc1": normal(seed + 10, (F,), 0.02, 0.0, bf16),
+        "Wd": normal(seed + 5, (F, H), 0.02, 0.0, bf16), "bfc2": normal(seed + 11, (H,), 0.02, 0.0, bf16),
+    }
+
+
+def moe_weights(H, n_qkv, n_o, F, n_local, bf16, seed=SEED_WEIGHTS):
+    """Weights of one MoE layer share: attention as the Llama layer, n_local SwiGLU experts."""
+    w = llama_weights(H, n_qkv, n_o, 8, bf16, seed)
+    w["Wgu"] = normal(seed + 4, (n_local, H, 2 * F), 0.02, 0.0, bf16)
+    w["Wd"] = normal(seed + 5, (n_local, F, H), 0.02, 0.0, bf16)
+    return w
+
+
 def strand_input(seed, T, H, bf16):
     return normal(1000 + seed, (T, H), 1.0, 0.0, bf16)
 
@@ -54,12 +75,13 @@ def strand_upstream_grad(seed, T, H, bf16):
     return normal(2000 + seed, (T, H), 1e-2, 0.0, bf16)
 
 
-def peer_partials(seed_base, n_peers, T, H, bf16):
+def peer_partials(seed_base, n_peers, T, H, bf16, std=1e-2):
     """Frozen contributions of the other ranks of a collective: [n_peers, T, H]."""
     if n_peers == 0:
         return np.zeros((0, T, H), dtype=np.float32)
-    return np.stack([normal(seed_base + r, (T, H), 1e-2, 0.0, bf16) for r in range(1, n_peers + 1)])
+    return np.stack([normal(seed_base + r, (T, H), std, 0.0, bf16) for r in range(1, n_peers + 1)])
 
 
 def router_logits(T, E, seed=SEED_ROUTER):
+    """Router logits [T, E], float32 whatever the activation type (an input of the MoE layer)."""
     return normal(seed, (T, E), 1.0, 0.0, False)

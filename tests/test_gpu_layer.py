@@ -17,7 +17,19 @@ CASES = {
     "bf16_mid_ragged": (dict(batch=2, seq=330, hidden=520, nq=4, nkv=1, d=128, ffn=1000, n_ranks=4, bf16=True), 2e-2),
     "bf16_d64_mha": (dict(batch=1, seq=257, hidden=256, nq=4, nkv=4, d=64, ffn=344, n_ranks=1, bf16=True), 2e-2),
     "c2_llama8b_tp8": (H.CONFIGS["c2_llama8b_tp8"], 2e-2),
+    "gpt_fp32_small": (dict(arch="gpt", batch=2, seq=40, hidden=136, nq=4, nkv=4, d=32, ffn=200, n_ranks=4, bf16=False), 1e-5),
+    "gpt_bf16_mid": (dict(arch="gpt", batch=2, seq=264, hidden=520, nq=4, nkv=4, d=128, ffn=1000, n_ranks=4, bf16=True), 2e-2),
+    "gpt_fp32_one_rank": (dict(arch="gpt", batch=1, seq=33, hidden=64, nq=2, nkv=1, d=32, ffn=72, n_ranks=1, bf16=False), 1e-5),
+    "moe_fp32_small": (dict(arch="moe", batch=2, seq=75, hidden=136, nq=4, nkv=2, d=32, ffn=96, n_ranks=1, bf16=False,
+                            n_experts=8, n_local=2), 1e-5),
+    "moe_bf16_mid": (dict(arch="moe", batch=1, seq=600, hidden=520, nq=4, nkv=2, d=128, ffn=328, n_ranks=1, bf16=True,
+                          n_experts=16, n_local=2), 2e-2),
+    "moe_bf16_all_local": (dict(arch="moe", batch=1, seq=130, hidden=128, nq=2, nkv=2, d=64, ffn=64, n_ranks=1, bf16=True,
+                                n_experts=4, n_local=4), 2e-2),
+    "c3_gpt_tp8_sp": (H.CONFIGS["c3_gpt_tp8_sp"], 2e-2),
+    "c5_phimoe_ep8": (H.CONFIGS["c5_phimoe_ep8"], 2e-2),
 }
+GPT_NAMES = dict(Wgu="W1", Wd="W2", bfc1="bf1", bfc2="bf2")  # harness / C-struct name -> oracle name
 
 
 def rel(a, b):
@@ -29,9 +41,35 @@ def oracle_run(run, s):
     cfg = R.LayerCfg(batch=c["batch"], seq=c["seq"], H=c["hidden"], nq=c["nq"], nkv=c["nkv"], d=c["d"], F=c["ffn"],
                      eps=c["eps"], rope_base=c["rope_base"])
     W = {k: v.astype(np.float64) for k, v in run.w_np.items()}
-    out, saved = R.llama_fwd(cfg, W, s.x_np.astype(np.float64), s.peers_np)
-    dx, grads, _ = R.llama_bwd(cfg, W, saved, s.dout_np.astype(np.float64), s.peers_np)
+    x, dout = s.x_np.astype(np.float64), s.dout_np.astype(np.float64)
+    if c["arch"] == "gpt":
+        W = {GPT_NAMES.get(k, k): v for k, v in W.items()}
+        pf = {"ag1": s.peers_np["ag1"], "ag2": s.peers_np["ag2"], "rs1": s.peers_np["ar1"], "rs2": s.peers_np["ar2"]}
+        pb = {"ag3": s.peers_np["ag3"], "ag4": s.peers_np["ag4"], "rs3": s.peers_np["ar3"], "rs4": s.peers_np["ar4"]}
+        if c["n_ranks"] == 1:
+            pf = pb = None
+        out, saved = R.gpt_fwd(cfg, W, x, pf)
+        dx, grads, _ = R.gpt_bwd(cfg, W, saved, dout, pb)
+        back = {v: k for k, v in GPT_NAMES.items()}
+        grads = {"d" + back.get(k[1:], k[1:]): v for k, v in grads.items()}
+        return out, dx, grads
+    if c["arch"] == "moe":
+        out, saved = R.moe_layer_fwd(cfg, W, x, s.logits_np.astype(np.float64), c["n_local"])
+        dx, grads = R.moe_layer_bwd(cfg, W, saved, dout, c["n_local"])
+        return out, dx, grads
+    out, saved = R.llama_fwd(cfg, W, x, s.peers_np)
+    dx, grads, _ = R.llama_bwd(cfg, W, saved, dout, s.peers_np)
     return out, dx, grads
+
+
+def check_grads(run, s, grads, tol):
+    got = run.grads_np()
+    assert sorted(got) == sorted(k for k in grads if k != "dlogits")
+    for k, v in got.items():
+        assert rel(v, grads[k]) <= tol, k
+    if "dlogits" in grads:
+        assert rel(H.to_np(s.dlogits), grads["dlogits"]) <= tol, "dlogits"
+    return got
 
 
 @pytest.mark.parametrize("name", list(CASES))
@@ -47,9 +85,7 @@ def test_layer_fwd_bwd_matches_oracle(name):
         out, dx, grads = oracle_run(run, s)
         assert rel(H.to_np(s.out), out) <= tol, "out"
         assert rel(H.to_np(s.dx), dx) <= tol, "dx"
-        got = run.grads_np()
-        for k in ("dWqkv", "dWo", "dWgu", "dWd", "dg1", "dg2"):
-            assert rel(got[k], grads[k]) <= tol, k
+        got = check_grads(run, s, grads, tol)
         # gradient buffers accumulate: a second backward doubles them
         run.bwd(s)
         torch.cuda.synchronize()
@@ -62,7 +98,8 @@ def test_layer_fwd_bwd_matches_oracle(name):
 
 def snapshot(run, alpha, beta):
     torch.cuda.synchronize()
-    return [alpha.out.clone(), alpha.saved.clone(), beta.dx.clone()] + [g.clone() for g in run.g.values()]
+    extra = [beta.dlogits.clone()] if beta.dlogits is not None else []
+    return [alpha.out.clone(), alpha.saved.clone(), beta.dx.clone()] + extra + [g.clone() for g in run.g.values()]
 
 
 def random_legal_plan(dh, run, rng):
@@ -91,7 +128,8 @@ def random_legal_plan(dh, run, rng):
     return plan
 
 
-@pytest.mark.parametrize("name", ["c1_tiny_fp32", "bf16_mid_ragged"])
+@pytest.mark.parametrize("name", ["c1_tiny_fp32", "bf16_mid_ragged", "gpt_fp32_small", "gpt_bf16_mid", "moe_fp32_small",
+                                  "moe_bf16_mid"])
 def test_si_step_bitwise_equals_sequential_and_matches_oracle(name):
     from paper_2411_15871_amd import dhelix as dh
     cfg, tol = CASES[name]
@@ -112,8 +150,7 @@ def test_si_step_bitwise_equals_sequential_and_matches_oracle(name):
         out_o, _, _ = oracle_run(run, alpha)
         _, dx_o, grads_o = oracle_run(run, beta)
         assert rel(H.to_np(alpha.out), out_o) <= tol and rel(H.to_np(beta.dx), dx_o) <= tol
-        for k, v in run.grads_np().items():
-            assert rel(v, grads_o[k]) <= tol, k
+        check_grads(run, beta, grads_o, tol)
         gf, gb = dh.dh_layer_op_graph(run.layer, 0), dh.dh_layer_op_graph(run.layer, 1)
         nf, nb = gf.n_ops, gb.n_ops
         rng = random.Random(5)

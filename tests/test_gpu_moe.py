@@ -105,7 +105,7 @@ def test_gather_combine(dh, bf16, T, H, n_blocks):
     x = gen.normal(21, (T, H), 1.0, 0.0, bf16)
     if T == 0:
         dh.dh_moe_gather_rows(dt(dh, bf16), 0, H, None, None, None, n_blocks)
-        dh.dh_moe_combine(dt(dh, bf16), 0, H, None, None, None, None)
+        dh.dh_moe_combine(dt(dh, bf16), 0, H, None, None, None, None, None)
         dh.dh_moe_combine_bwd(dt(dh, bf16), 0, H, None, None, None, None, None, None)
         return
     ridx, rprob = R.router_top2(l.astype(np.float64))
@@ -121,14 +121,14 @@ def test_gather_combine(dh, bf16, T, H, n_blocks):
     yp = gen.normal(22, (2 * T, H), 1.0, 0.0, bf16)
     ypd = dev(yp, bf16)
     y = torch.empty_like(xd)
-    dh.dh_moe_combine(dt(dh, bf16), T, H, ypd, destd, probd, y)
+    dh.dh_moe_combine(dt(dh, bf16), T, H, ypd, destd, probd, None, y)
     y1 = torch.empty_like(xd)
-    dh.dh_moe_combine(dt(dh, bf16), T, H, ypd, destd, None, y1)
+    dh.dh_moe_combine(dt(dh, bf16), T, H, ypd, destd, None, xd, y1)
     torch.cuda.synchronize()
     p32 = rprob.astype(np.float32).astype(np.float64)
     y_ref = p32[:, 0:1] * yp[dest[:, 0]] + p32[:, 1:2] * yp[dest[:, 1]]
     assert rel(host(y), y_ref) <= TOL[bf16]
-    assert rel(host(y1), yp[dest[:, 0]].astype(np.float64) + yp[dest[:, 1]]) <= TOL[bf16]
+    assert rel(host(y1), yp[dest[:, 0]].astype(np.float64) + yp[dest[:, 1]] + x) <= TOL[bf16]
     dy = gen.normal(23, (T, H), 1e-2, 0.0, bf16)
     dyp = torch.zeros_like(ypd); dprob = torch.zeros(2 * T, dtype=torch.float32, device="cuda")
     dh.dh_moe_combine_bwd(dt(dh, bf16), T, H, dev(dy, bf16), ypd, destd, probd, dyp, dprob)
@@ -201,7 +201,7 @@ def test_moe_block_fwd_bwd(dh, bf16, T, H, F, E, n_local):
     dh.dh_swiglu_fwd(d, 2 * T, F, gu, a)
     dh.dh_gemm_grouped(d, 0, n_local, tb["group_rows"], 2 * T, F, H, a, Wdd, yg)
     dh.dh_moe_gather_rows(d, 2 * T, H, yg, tb["recv_of_send"], yp)
-    dh.dh_moe_combine(d, T, H, yp, tb["dest"], prob, y)
+    dh.dh_moe_combine(d, T, H, yp, tb["dest"], prob, None, y)
     torch.cuda.synchronize()
     assert rel(host(y), y_ref) <= TOL[bf16]
     # backward
@@ -217,7 +217,7 @@ def test_moe_block_fwd_bwd(dh, bf16, T, H, F, E, n_local):
     dh.dh_gemm_grouped(d, 2, n_local, tb["group_rows"], 2 * T, H, 2 * F, xg, dgu, dWgu)
     dh.dh_gemm_grouped(d, 1, n_local, tb["group_rows"], 2 * T, 2 * F, H, dgu, Wgud, dxg)
     dh.dh_moe_gather_rows(d, 2 * T, H, dxg, tb["recv_of_send"], dxp)
-    dh.dh_moe_combine(d, T, H, dxp, tb["dest"], None, dh2)
+    dh.dh_moe_combine(d, T, H, dxp, tb["dest"], None, None, dh2)
     torch.cuda.synchronize()
     assert rel(host(dh2), dh2_ref) <= TOL[bf16]
     assert rel(host(dl), dl_ref) <= TOL[bf16]
