@@ -19,6 +19,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+# HBM bytes per launch of the dominant GEMM from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (scaled by a copy kernel of
+# known size); the summary with the commands is profiles/gemm_gateup_c2_hbm_traffic.txt.  Re-measure when the GEMM changes.
+HBM_TRAFFIC_BYTES = {"c2_llama8b_tp8": (176.2 + 28.6) * 2 ** 20}
 
 
 def log(*a):
@@ -104,40 +107,43 @@ def main():
     t_f = [table.t_fwd[i] for i in range(gf.n_ops)]
     t_b = [table.t_bwd[j] for j in range(gb.n_ops)]
     log("profile %.2fs, search %.2fs, predicted makespan %.1f us, sum solo %.1f us" % (t_prof, t_search, predicted * 1e6, (sum(t_f) + sum(t_b)) * 1e6))
-    log("fwd solo us:", {dh.FWD_OPS[i]: round(t_f[i] * 1e6, 1) for i in range(gf.n_ops)})
-    log("bwd solo us:", {dh.BWD_OPS[j]: round(t_b[j] * 1e6, 1) for j in range(gb.n_ops)})
-    log("plan:", [([dh.FWD_OPS[o] for o in fo[a:b]], [dh.BWD_OPS[o] for o in bo[c:d]]) for a, b, c, d in pairs])
+    fnames, bnames = dh.op_names(H.ARCH[cfg["arch"]], 0), dh.op_names(H.ARCH[cfg["arch"]], 1)
+    log("fwd solo us:", {fnames[i]: round(t_f[i] * 1e6, 1) for i in range(gf.n_ops)})
+    log("bwd solo us:", {bnames[j]: round(t_b[j] * 1e6, 1) for j in range(gb.n_ops)})
+    log("plan:", [([fnames[o] for o in fo[a:b]], [bnames[o] for o in bo[c:d]]) for a, b, c, d in pairs])
 
     nf, nb = gf.n_ops, gb.n_ops
     seq_plan = dh.dh_plan_sequential(run.layer)
-    free_plan = dh.make_plan(list(range(nf)), list(range(nb)), [(0, nf, 0, nb)])
+    free_plan = dh.make_plan(list(seq_plan.fwd_order[:nf]), list(seq_plan.bwd_order[:nb]), [(0, nf, 0, nb)])
     t_seq = time_steps(lambda: run.si_step(alpha, beta, seq_plan, sa, sb, sc), args.steps, args.warmup, torch)
     t_free = time_steps(lambda: run.si_step(alpha, beta, free_plan, sa, sb, sc), args.steps, args.warmup, torch)
     t_si = time_steps(lambda: run.si_step(alpha, beta, plan, sa, sb, sc), args.steps, args.warmup, torch)
     t_comm = sum(t_f[i] for i in range(nf) if gf.is_comm[i]) + sum(t_b[j] for j in range(nb) if gb.is_comm[j])
     log("T_seq %.1f us, T_free-running %.1f us, T_SI(plan) %.1f us, stand-ins solo %.1f us" % (t_seq * 1e6, t_free * 1e6, t_si * 1e6, t_comm * 1e6))
 
-    # roofline of the dominant kernel: the gate/up projection GEMM (largest share of the FLOPs), timed
-    # alone with events on the stream it is launched on
-    T, Hd, F = run.T, cfg["hidden"], cfg["ffn"]
+    # roofline of the dominant kernel: the first FFN GEMM (gate/up projection; largest share of the FLOPs), timed
+    # alone with events on the stream it is launched on.  MoE: one local expert's balanced share of the rows.
+    Hd = cfg["hidden"]
+    T = run.T if cfg["arch"] != "moe" else 2 * run.T // cfg["n_local"]
+    F2 = cfg["ffn"] if cfg["arch"] == "gpt" else 2 * cfg["ffn"]
     a_mat = torch.empty(T, Hd, dtype=torch.bfloat16, device="cuda").normal_()
-    b_mat = torch.empty(Hd, 2 * F, dtype=torch.bfloat16, device="cuda").normal_(0, 0.02)
-    c_mat = torch.empty(T, 2 * F, dtype=torch.bfloat16, device="cuda")
-    wsb = dh.dh_gemm_workspace_bytes(dh.DH_BF16, 0, 0, T, 2 * F, Hd)
+    b_mat = torch.empty(Hd, F2, dtype=torch.bfloat16, device="cuda").normal_(0, 0.02)
+    c_mat = torch.empty(T, F2, dtype=torch.bfloat16, device="cuda")
+    wsb = dh.dh_gemm_workspace_bytes(dh.DH_BF16, 0, 0, T, F2, Hd)
     gws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
     torch.cuda.synchronize()
     reps = 50
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     for _ in range(5):
-        dh.dh_gemm(dh.DH_BF16, 0, 0, T, 2 * F, Hd, a_mat, b_mat, c_mat, False, gws, wsb, sa)
+        dh.dh_gemm(dh.DH_BF16, 0, 0, T, F2, Hd, a_mat, b_mat, c_mat, False, gws, wsb, sa)
     e0.record(sa)
     for _ in range(reps):
-        dh.dh_gemm(dh.DH_BF16, 0, 0, T, 2 * F, Hd, a_mat, b_mat, c_mat, False, gws, wsb, sa)
+        dh.dh_gemm(dh.DH_BF16, 0, 0, T, F2, Hd, a_mat, b_mat, c_mat, False, gws, wsb, sa)
     e1.record(sa)
     torch.cuda.synchronize()
     gemm_s = e0.elapsed_time(e1) * 1e-3 / reps
-    gemm_tflops = 2.0 * T * 2 * F * Hd / gemm_s / 1e12
-    log("dominant GEMM [%d x %d x %d]: %.1f us, %.1f TFLOP/s" % (T, 2 * F, Hd, gemm_s * 1e6, gemm_tflops))
+    gemm_tflops = 2.0 * T * F2 * Hd / gemm_s / 1e12
+    log("dominant GEMM [%d x %d x %d]: %.1f us, %.1f TFLOP/s" % (T, F2, Hd, gemm_s * 1e6, gemm_tflops))
 
     value = flops / t_si / 1e12
     out = {
@@ -145,7 +151,7 @@ def main():
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": t_si * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg["bf16"] else "f32", "data": "synthetic",
-        "config": {"workload": args.workload, "tokens_per_strand": run.T, "comm_blocks": args.comm_blocks,
+        "config": {"workload": args.workload, "arch": cfg["arch"], "tokens_per_strand": run.T, "comm_blocks": args.comm_blocks,
                    "plan_pairs": len(pairs)},
         "pct_bf16_peak": 100.0 * value / BF16_MFMA_PEAK_TFLOPS,
         "tokens_per_s": run.T / t_si,
@@ -153,10 +159,11 @@ def main():
         "ms_sequential": t_seq * 1e3, "ms_free_running": t_free * 1e3,
         "comm_hidden_frac": (t_seq - t_si) / t_comm if t_comm > 0 else None,
         "roofline": {"bound": "mfma", "achieved": gemm_tflops, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": gemm_tflops / BF16_MFMA_PEAK_TFLOPS, "traffic": None,
-                     "kernel": "gemm_bf16_kernel (gate/up projection %dx%dx%d)" % (T, 2 * F, Hd)},
+                     "frac": gemm_tflops / BF16_MFMA_PEAK_TFLOPS, "traffic": HBM_TRAFFIC_BYTES.get(args.workload),
+                     "traffic_unit": "bytes/launch", "algorithmic_bytes": 2.0 * (T * Hd + Hd * F2 + T * F2),
+                     "kernel": "gemm_bf16_kernel (first FFN projection %dx%dx%d)" % (T, F2, Hd)},
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and cfg["arch"] == "llama":
         out["cpu_baseline"] = cpu_baseline(cfg, flops)
     run.close()
     print(json.dumps(out), flush=True)
