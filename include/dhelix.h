@@ -353,9 +353,12 @@ int dh_add(int dtype, size_t n, const void* a, const void* b, void* out, void* s
  * scaled masked scores; attention is per sequence (T = batch*seq).  Backward writes dqkv (same
  * layout as qkv; dk,dv summed over the query heads of each group in head order) and uses
  * delta[nq,T] and ws (dh_attn_bwd_workspace_bytes; per-head float32 dk,dv partials when nq > nkv)
- * as scratch. */
+ * as scratch.  Forward: ws (dh_attn_fwd_workspace_bytes) lets long causal rows be split over several
+ * blocks whose float32 partial results are merged in a fixed order; with ws == NULL (or too small) the
+ * rows are not split and results differ in rounding only. */
 int dh_attn_fwd(int dtype, int batch, int seq, int nq, int nkv, int d, const void* qkv, void* o,
-                float* lse, void* stream);
+                float* lse, void* ws, size_t ws_bytes, void* stream);
+size_t dh_attn_fwd_workspace_bytes(int dtype, int batch, int seq, int nq, int nkv, int d);
 int dh_attn_bwd(int dtype, int batch, int seq, int nq, int nkv, int d, const void* qkv, const void* o,
                 const void* dout, const float* lse, void* dqkv, float* delta, void* ws, size_t ws_bytes,
                 void* stream);

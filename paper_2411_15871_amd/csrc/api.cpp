@@ -60,13 +60,18 @@ static int check_attn(const char* who, int batch, int seq, int nq, int nkv, int 
   return DH_OK;
 }
 
+extern "C" size_t dh_attn_fwd_workspace_bytes(int dtype, int batch, int seq, int nq, int nkv, int d) {
+  if (dtype != DH_BF16 || batch <= 0 || seq <= 0 || nq <= 0 || nkv <= 0 || d <= 0) return 0;
+  return dh_attn_fwd_bf16_ws_bytes(batch, seq, nq, nkv, d);
+}
+
 extern "C" int dh_attn_fwd(int dtype, int batch, int seq, int nq, int nkv, int d, const void* qkv, void* o, float* lse,
-                           void* stream) {
+                           void* ws, size_t ws_bytes, void* stream) {
   int rc = check_attn("attn_fwd", batch, seq, nq, nkv, d);
   if (rc) return rc;
   if (batch * seq > 0 && (!qkv || !o || !lse)) DH_FAIL(DH_ERR_INVALID_ARG, "attn_fwd: null pointer");
   if (dtype == DH_F32) return dh_launch_attn_fwd_f32(batch, seq, nq, nkv, d, (const float*)qkv, (float*)o, lse, (hipStream_t)stream);
-  if (dtype == DH_BF16) return dh_launch_attn_fwd_bf16(batch, seq, nq, nkv, d, (const bf16_t*)qkv, (bf16_t*)o, lse, (hipStream_t)stream);
+  if (dtype == DH_BF16) return dh_launch_attn_fwd_bf16(batch, seq, nq, nkv, d, (const bf16_t*)qkv, (bf16_t*)o, lse, ws, ws_bytes, (hipStream_t)stream);
   DH_FAIL(DH_ERR_INVALID_ARG, "attn_fwd: unknown dtype %d", dtype);
 }
 

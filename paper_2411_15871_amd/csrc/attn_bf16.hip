@@ -69,6 +69,48 @@ typedef __attribute__((ext_vector_type(8))) short s16x8;
 #define LOG2E 1.4426950408889634f
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
 
+// acc += A * B with the accumulator held in the accumulation half of the register file (AGPRs) for the whole
+// tile loop: the long-lived gradient accumulators then cost no ordinary registers and no copies.  (This file
+// is built with -amdgpu-mfma-vgpr-form, so the short-lived score tiles that the vector ALU post-processes are
+// produced in ordinary registers by the intrinsic, with the compiler's own hazard handling.)  The hardware
+// interlocks back-to-back accumulation into the same registers; the wait states the compiler would otherwise
+// insert around a matrix instruction are written out by hand, since it cannot see into the assembly statement:
+// before the instruction (see mfma_acc) and, before anything else reads an accumulator, mfma_acc_settle().
+__device__ __forceinline__ void mfma_acc(f32x16& acc, bf16x8 a, bf16x8 b) {
+  // two wait states first: an operand fragment may have been written by the vector ALU (the bf16 packing) in the
+  // instruction just before, and a matrix instruction must not read such a register that early
+  asm("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+// acc = 0, produced by the matrix unit so that the accumulator is born in an AGPR; the trailing wait states let
+// the result land before any register copy the compiler may place behind this statement.
+__device__ __forceinline__ void mfma_acc_zero(f32x16& acc) {
+  const bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+  asm volatile("s_nop 3\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %1, 0\n\ts_nop 15\n\ts_nop 15" : "=a"(acc) : "v"(z));
+}
+__device__ __forceinline__ void mfma_acc_settle(f32x16 (&a)[2]) {
+  asm volatile("s_nop 15\n\ts_nop 15" : "+a"(a[0]), "+a"(a[1]));
+}
+__device__ __forceinline__ void mfma_acc_settle(f32x16 (&a)[4]) {
+  asm volatile("s_nop 15\n\ts_nop 15" : "+a"(a[0]), "+a"(a[1]), "+a"(a[2]), "+a"(a[3]));
+}
+// The AGPR placement pays where ordinary registers are short (D = 128: 64 or 128 accumulator registers next to
+// the operand fragments and two score tiles).  With D = 64 everything fits the ordinary registers, where the
+// compiler would only shuttle an AGPR-constrained value back and forth, so those kernels use the intrinsic.
+template <int D> __device__ __forceinline__ void acc_zero(f32x16& acc) {
+  if constexpr (D == 128) mfma_acc_zero(acc);
+  else {
+#pragma unroll
+    for (int r = 0; r < 16; r++) acc[r] = 0.f;
+  }
+}
+template <int D> __device__ __forceinline__ void acc_mfma(f32x16& acc, bf16x8 a, bf16x8 b) {
+  if constexpr (D == 128) mfma_acc(acc, a, b);
+  else acc = MFMA(a, b, acc);
+}
+template <int D, int N> __device__ __forceinline__ void acc_settle(f32x16 (&a)[N]) {
+  if constexpr (D == 128) mfma_acc_settle(a);
+}
+
 template <int D>
 struct ATile {
   static constexpr int LD = D;
@@ -174,11 +216,28 @@ __device__ __forceinline__ void pin_frags(const bf16x8 (&f)[N]) {
 __device__ __forceinline__ void pin_scalar(float v) { asm volatile("" ::"v"(v)); }
 
 // ================================================================================ forward
-// grid (ceil(seq/128), nq, batch); wave w owns query rows i0 + 32w .. +31.
+// Work units of the forward kernel: query block i (128 rows) needs fwd_tiles(i) key tiles; with ch > 0 they
+// are cut into chunks of ch tiles (ch even, so that every chunk starts at a tile each of the block's waves
+// can see), one launch index per (block, chunk), heaviest block first.  A block with a single chunk writes
+// o and lse itself; otherwise every chunk writes its unnormalised float32 output rows with their running
+// maximum and sum, and a combine kernel merges the chunks in chunk order.
+__host__ __device__ static inline int fwd_tiles(int i, int seq) { int e = (i + 1) * 128; return ((e < seq ? e : seq) + AB_KT - 1) / AB_KT; }
+__host__ __device__ static inline int fwd_chunks(int i, int seq, int ch) { return ch > 0 ? (fwd_tiles(i, seq) + ch - 1) / ch : 1; }
+static int fwd_units(int seq, int ch) {
+  int n = 0;
+  for (int i = 0; i < (seq + 127) / 128; i++) n += fwd_chunks(i, seq, ch);
+  return n;
+}
+
+// grid (units, nq, batch); wave w owns query rows i0 + 32w .. +31.  The K and V tiles go through two LDS
+// slots each (64 KiB per block at D = 128), so that two blocks fit a compute unit: the matrix work of
+// one block's waves then overlaps the softmax arithmetic of the other's.
+#define AF_RING 2
 template <int D>
 __global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(int seq, int nq, int nkv, const bf16_t* __restrict__ qkv,
                                                                    bf16_t* __restrict__ o, float* __restrict__ lse, int T,
-                                                                   float scale_log2) {
+                                                                   float scale_log2, int ch, int units,
+                                                                   float* __restrict__ part_o, float* __restrict__ part_ml) {
   using TL = ATile<D>;
   extern __shared__ __attribute__((aligned(1024))) char smem[];  // K ring, then V ring
   const lds_char* sm = (const lds_char*)smem;
@@ -186,7 +245,23 @@ __global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(int seq, i
   const int l32 = lane & 31, kg = lane >> 5;
   const int h = blockIdx.y, b = blockIdx.z, hk = h / (nq / nkv);
   const int ld = (nq + 2 * nkv) * D;
-  const int i0 = (gridDim.x - 1 - blockIdx.x) * 128, iw = i0 + wave * 32, iq = iw + l32;  // positions in the sequence
+  int blk, chunk = 0, nchunks = 1, pair;
+  if (ch == 0) {
+    blk = gridDim.x - 1 - blockIdx.x;
+    pair = blk;
+  } else {  // heaviest block first; `pair` numbers the (block, chunk) units in natural order
+    int rem = blockIdx.x, after = 0;
+    blk = (seq + 127) / 128 - 1;
+    for (;; blk--) {
+      nchunks = fwd_chunks(blk, seq, ch);
+      if (rem < nchunks || blk == 0) break;
+      rem -= nchunks;
+      after += nchunks;
+    }
+    chunk = rem;
+    pair = units - after - nchunks + rem;
+  }
+  const int i0 = blk * 128, iw = i0 + wave * 32, iq = iw + l32;  // positions in the sequence
   const size_t tok0 = (size_t)b * seq;
   const char* kbase = reinterpret_cast<const char*>(qkv + tok0 * ld + (size_t)(nq + hk) * D);
   const char* vbase = reinterpret_cast<const char*>(qkv + tok0 * ld + (size_t)(nq + nkv + hk) * D);
@@ -205,10 +280,11 @@ __global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(int seq, i
   fa.init(lane);
   uint32_t voff[TL::IPW];
   tile_voff<D>(voff, ld, wave, lane, AB_KT);
-  const uint32_t ldsK = lds_address(smem), ldsV = ldsK + AB_RING * TL::BYTES;
-  const int ntiles = (min(seq, i0 + 128) + AB_KT - 1) / AB_KT;  // keys needed by this block: [0, 64*ntiles)
+  const uint32_t ldsK = lds_address(smem), ldsV = ldsK + AF_RING * TL::BYTES;
+  const int tiles_all = (min(seq, i0 + 128) + AB_KT - 1) / AB_KT;  // keys needed by this block: [0, 64*tiles_all)
+  const int t_begin = chunk * ch, ntiles = ch == 0 ? tiles_all : min(tiles_all, t_begin + ch);  // this unit: [t_begin, ntiles)
   auto issue = [&](int t) {
-    const int slot = t % AB_RING, valid = seq - t * AB_KT;
+    const int slot = (t - t_begin) % AF_RING, valid = seq - t * AB_KT;
     if (valid >= AB_KT) {
       tile_dma<D>(kbase + t * tstride, voff, ldsK + slot * TL::BYTES, wave);
       tile_dma<D>(vbase + t * tstride, voff, ldsV + slot * TL::BYTES, wave);
@@ -220,18 +296,17 @@ __global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(int seq, i
     }
   };
   pin_frags(qf);
-  issue(0);
-  if (ntiles > 1) issue(1);
+  issue(t_begin);
   int slot = 0;
-  for (int t = 0; t < ntiles; t++, slot = slot == AB_RING - 1 ? 0 : slot + 1) {
-    if (t + 1 < ntiles) dma_wait<2 * TL::IPW>(); else dma_wait<0>();
-    __syncthreads();  // tile t is visible; every wave is done with tile t-1, whose slot tile t+2 reuses
-    if (t + 2 < ntiles) issue(t + 2);
+  for (int t = t_begin; t < ntiles; t++, slot ^= 1) {
+    dma_wait<0>();
+    __syncthreads();  // tile t is visible; every wave is done with tile t-1, whose slot tile t+1 reuses
+    if (t + 1 < ntiles) issue(t + 1);
     const int kb = t * AB_KT;
     if (kb > iw + 31) continue;  // no key of the tile is visible to any row of this wave
     TilePtrs<D> Kp, Vp;
     Kp.set(sm + slot * TL::BYTES, fa);
-    Vp.set(sm + (AB_RING + slot) * TL::BYTES, fa);
+    Vp.set(sm + (AF_RING + slot) * TL::BYTES, fa);
     f32x16 st[2];
 #pragma unroll
     for (int mt = 0; mt < 2; mt++) {
@@ -251,7 +326,7 @@ __global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(int seq, i
 #pragma unroll
     for (int r = 1; r < 16; r++) mx = fmaxf(mx, fmaxf(st[0][r], st[1][r]));
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float mn = fmaxf(m, mx * scale_log2);  // finite from the first tile on: key 0 is visible to every row
+    const float mn = fmaxf(m, mx * scale_log2);  // finite from the unit's first tile on: its first key is visible to every row
     const float alpha = fast_exp2(m - mn);
     float rs = 0.f;
 #pragma unroll
@@ -281,6 +356,24 @@ __global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(int seq, i
         for (int dt = 0; dt < D / 32; dt++) ot[dt] = MFMA(lds_frag_tr(Vp.t0[dt], Vp.t1[dt], ro), pf, ot[dt]);
       }
   }
+  if (nchunks > 1) {  // partial result of this chunk
+    if (iq < seq) {
+      const size_t unit = ((size_t)b * nq + h) * units + pair;
+      float* prow = part_o + (unit * 128 + (iq - i0)) * D;
+#pragma unroll
+      for (int dt = 0; dt < D / 32; dt++)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; q4++) {
+          f32x4 v = {ot[dt][4 * q4], ot[dt][4 * q4 + 1], ot[dt][4 * q4 + 2], ot[dt][4 * q4 + 3]};
+          *reinterpret_cast<f32x4*>(prow + dt * 32 + 8 * q4 + 4 * kg) = v;
+        }
+      if (kg == 0) {
+        part_ml[(unit * 128 + (iq - i0)) * 2] = m;
+        part_ml[(unit * 128 + (iq - i0)) * 2 + 1] = l;
+      }
+    }
+    return;
+  }
   if (iq < seq) {
     const float inv = 1.0f / l;
     bf16_t* orow = o + (tok0 + iq) * (size_t)nq * D + (size_t)h * D;
@@ -295,6 +388,50 @@ __global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(int seq, i
       }
     if (kg == 0) lse[(size_t)h * T + tok0 + iq] = (m + log2f(l)) * 0.6931471805599453f;
   }
+}
+
+// Merges the chunks of the query blocks that were split: with M = max_c m_c, o = sum_c 2^(m_c-M) o_c / L,
+// L = sum_c 2^(m_c-M) l_c, lse = (M + log2 L) ln 2; chunks are added in chunk order.
+// grid (8 * blocks, nq, batch): a 256-thread block merges 16 rows, a thread D/16 columns of one row.
+template <int D>
+__global__ __launch_bounds__(256) void attn_fwd_combine_kernel(int seq, int nq, int ch, int units, const float* __restrict__ part_o,
+                                                               const float* __restrict__ part_ml, bf16_t* __restrict__ o,
+                                                               float* __restrict__ lse, int T) {
+  const int blk = blockIdx.x >> 3, h = blockIdx.y, b = blockIdx.z;
+  const int nchunks = fwd_chunks(blk, seq, ch);
+  if (nchunks == 1) return;
+  const int r = (blockIdx.x & 7) * 16 + (threadIdx.x >> 4), pos = blk * 128 + r;
+  if (pos >= seq) return;
+  int pair0 = 0;
+  for (int i = 0; i < blk; i++) pair0 += fwd_chunks(i, seq, ch);
+  const size_t unit0 = ((size_t)b * nq + h) * units + pair0;
+  constexpr int CPT = D / 16;  // columns per thread
+  const int c0 = (threadIdx.x & 15) * CPT;
+  const float* ml = part_ml + (unit0 * 128 + r) * 2;
+  float M = -INFINITY;
+  for (int c = 0; c < nchunks; c++) M = fmaxf(M, ml[(size_t)c * 256]);
+  float L = 0.f, acc[CPT];
+#pragma unroll
+  for (int i = 0; i < CPT; i++) acc[i] = 0.f;
+  for (int c = 0; c < nchunks; c++) {
+    const float w = exp2f(ml[(size_t)c * 256] - M);
+    L += w * ml[(size_t)c * 256 + 1];
+    const float* po = part_o + ((unit0 + c) * 128 + r) * D + c0;
+#pragma unroll
+    for (int i = 0; i < CPT; i += 4) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(po + i);
+      acc[i] += w * v[0]; acc[i + 1] += w * v[1]; acc[i + 2] += w * v[2]; acc[i + 3] += w * v[3];
+    }
+  }
+  const float inv = 1.0f / L;
+  const size_t tok = (size_t)b * seq + pos;
+  bf16_t* orow = o + tok * (size_t)nq * D + (size_t)h * D + c0;
+#pragma unroll
+  for (int i = 0; i < CPT; i += 4) {
+    bf16x4 v = {(bf16_t)(acc[i] * inv), (bf16_t)(acc[i + 1] * inv), (bf16_t)(acc[i + 2] * inv), (bf16_t)(acc[i + 3] * inv)};
+    *reinterpret_cast<bf16x4*>(orow + i) = v;
+  }
+  if (c0 == 0) lse[(size_t)h * T + tok] = (M + log2f(L)) * 0.6931471805599453f;
 }
 
 // ================================================================================ backward prologue
@@ -355,9 +492,7 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(int seq, i
   const float dl = delta[(size_t)h * T + tok0 + iqc];
   f32x16 dqt[D / 32];
 #pragma unroll
-  for (int dt = 0; dt < D / 32; dt++)
-#pragma unroll
-    for (int r = 0; r < 16; r++) dqt[dt][r] = 0.f;
+  for (int dt = 0; dt < D / 32; dt++) acc_zero<D>(dqt[dt]);
 
   FragAddr<D> fa;
   fa.init(lane);
@@ -428,9 +563,10 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(int seq, i
         const bf16x8 df = pack_rows(st[mt], c);
         const int ro = (mt * 32 + 16 * c) * TL::LD * 2;
 #pragma unroll
-        for (int dt = 0; dt < D / 32; dt++) dqt[dt] = MFMA(lds_frag_tr(Kp.t0[dt], Kp.t1[dt], ro), df, dqt[dt]);
+        for (int dt = 0; dt < D / 32; dt++) acc_mfma<D>(dqt[dt], lds_frag_tr(Kp.t0[dt], Kp.t1[dt], ro), df);
       }
   }
+  acc_settle<D>(dqt);
   if (part != nullptr) {  // float32 partial of this chunk: part[batch][head][pair][128 rows][D], unscaled
     float* row = part + ((((size_t)b * nq + h) * pairs + cm.pair) * 128 + wave * 32 + l32) * D;
 #pragma unroll
@@ -511,9 +647,7 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, 
   load_row_frags<D>(vf, qkv + (tok0 + jkc) * ld + (size_t)(nq + nkv + hk) * D, jk < seq, kg);
   f32x16 dkt[D / 32], dvt[D / 32];
 #pragma unroll
-  for (int dt = 0; dt < D / 32; dt++)
-#pragma unroll
-    for (int r = 0; r < 16; r++) { dkt[dt][r] = 0.f; dvt[dt][r] = 0.f; }
+  for (int dt = 0; dt < D / 32; dt++) { acc_zero<D>(dkt[dt]); acc_zero<D>(dvt[dt]); }
 
   FragAddr<D> fa;
   fa.init(lane);
@@ -601,7 +735,7 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, 
         const bf16x8 pf = pack_rows(st[mt], c);
         const int ro = (mt * 32 + 16 * c) * TL::LD * 2;
 #pragma unroll
-        for (int dt = 0; dt < D / 32; dt++) dvt[dt] = MFMA(lds_frag_tr(Op.t0[dt], Op.t1[dt], ro), pf, dvt[dt]);
+        for (int dt = 0; dt < D / 32; dt++) acc_mfma<D>(dvt[dt], lds_frag_tr(Op.t0[dt], Op.t1[dt], ro), pf);
       }
 #pragma unroll
     for (int mt = 0; mt < 2; mt++)
@@ -618,9 +752,11 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, 
         const bf16x8 df = pack_rows(st[mt], c);
         const int ro = (mt * 32 + 16 * c) * TL::LD * 2;
 #pragma unroll
-        for (int dt = 0; dt < D / 32; dt++) dkt[dt] = MFMA(lds_frag_tr(Qp.t0[dt], Qp.t1[dt], ro), df, dkt[dt]);
+        for (int dt = 0; dt < D / 32; dt++) acc_mfma<D>(dkt[dt], lds_frag_tr(Qp.t0[dt], Qp.t1[dt], ro), df);
       }
   }
+  acc_settle<D>(dkt);
+  acc_settle<D>(dvt);
   if (part != nullptr) {
     float* prow = part + ((((size_t)b * nq + hq) * pairs + cm.pair) * 128 + wave * 32 + l32) * (2 * D);
 #pragma unroll
@@ -684,21 +820,62 @@ static int set_lds(K kernel, size_t bytes) {
   return DH_OK;
 }
 
-int dh_launch_attn_fwd_bf16(int batch, int seq, int nq, int nkv, int d, const bf16_t* qkv, bf16_t* o, float* lse,
-                            hipStream_t stream) {
+static int attn_num_cus() {
+  static int n_cus = 0;
+  if (n_cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) n_cus = n;
+    else n_cus = 256;
+    (void)hipGetLastError();
+  }
+  return n_cus;
+}
+
+// Tiles per chunk of the forward kernel: the largest of 64, 32, 16, 8 that still gives about three work
+// units per resident block slot (two per compute unit); 0 = blocks are not split.
+static int fwd_chunk_tiles(int batch, int seq, int nq) {
+  const long long target = 6ll * attn_num_cus();
+  const int max_tiles = fwd_tiles((seq + 127) / 128 - 1, seq);
+  for (int ch = 64; ch >= 8; ch /= 2) {
+    if (ch >= max_tiles) continue;
+    if ((long long)fwd_units(seq, ch) * nq * batch >= target || ch == 8) return ch;
+  }
+  return 0;
+}
+
+size_t dh_attn_fwd_bf16_ws_bytes(int batch, int seq, int nq, int nkv, int d) {
+  (void)nkv;
+  if (batch * seq == 0) return 0;
+  const int ch = fwd_chunk_tiles(batch, seq, nq);
+  if (ch == 0) return 0;
+  return (size_t)batch * nq * fwd_units(seq, ch) * 128 * ((size_t)d + 2) * sizeof(float);
+}
+
+int dh_launch_attn_fwd_bf16(int batch, int seq, int nq, int nkv, int d, const bf16_t* qkv, bf16_t* o, float* lse, void* ws,
+                            size_t ws_bytes, hipStream_t stream) {
   if (d != 64 && d != 128) DH_FAIL(DH_ERR_SHAPE, "attention (bf16): head_dim %d must be 64 or 128", d);
   if (batch * seq == 0) return DH_OK;
-  dim3 grid((seq + 127) / 128, nq, batch);
+  const int nblk = (seq + 127) / 128;
+  int ch = fwd_chunk_tiles(batch, seq, nq);
+  if (ch > 0 && (!ws || ws_bytes < dh_attn_fwd_bf16_ws_bytes(batch, seq, nq, nkv, d))) ch = 0;  // no room for partial results
+  const int units = ch > 0 ? fwd_units(seq, ch) : nblk;
+  float* part_o = (float*)ws;
+  float* part_ml = ch > 0 ? part_o + (size_t)batch * nq * units * 128 * d : nullptr;
+  dim3 grid(units, nq, batch), cgrid(nblk * 8, nq, batch);
   const float sl2 = (float)(1.4426950408889634 / sqrt((double)d));
-  const size_t lds = 2 * AB_RING * (size_t)AB_KT * d * 2;
+  const size_t lds = 2 * AF_RING * (size_t)AB_KT * d * 2;
   static bool ready[2] = {false, false};
   int rc;
   if (d == 128) {
     if (!ready[0]) { if ((rc = set_lds(attn_fwd_bf16_kernel<128>, lds))) return rc; ready[0] = true; }
-    attn_fwd_bf16_kernel<128><<<grid, AB_THREADS, lds, stream>>>(seq, nq, nkv, qkv, o, lse, batch * seq, sl2);
+    attn_fwd_bf16_kernel<128><<<grid, AB_THREADS, lds, stream>>>(seq, nq, nkv, qkv, o, lse, batch * seq, sl2, ch, units, part_o, part_ml);
+    DH_LAUNCH_CHECK();
+    if (ch > 0) attn_fwd_combine_kernel<128><<<cgrid, 256, 0, stream>>>(seq, nq, ch, units, part_o, part_ml, o, lse, batch * seq);
   } else {
     if (!ready[1]) { if ((rc = set_lds(attn_fwd_bf16_kernel<64>, lds))) return rc; ready[1] = true; }
-    attn_fwd_bf16_kernel<64><<<grid, AB_THREADS, lds, stream>>>(seq, nq, nkv, qkv, o, lse, batch * seq, sl2);
+    attn_fwd_bf16_kernel<64><<<grid, AB_THREADS, lds, stream>>>(seq, nq, nkv, qkv, o, lse, batch * seq, sl2, ch, units, part_o, part_ml);
+    DH_LAUNCH_CHECK();
+    if (ch > 0) attn_fwd_combine_kernel<64><<<cgrid, 256, 0, stream>>>(seq, nq, ch, units, part_o, part_ml, o, lse, batch * seq);
   }
   DH_LAUNCH_CHECK();
   return DH_OK;

@@ -105,8 +105,9 @@ int dh_launch_attn_fwd_f32(int batch, int seq, int nq, int nkv, int d, const flo
                            hipStream_t stream);
 int dh_launch_attn_bwd_f32(int batch, int seq, int nq, int nkv, int d, const float* qkv, const float* o,
                            const float* dout, const float* lse, float* dqkv, float* delta, hipStream_t stream);
-int dh_launch_attn_fwd_bf16(int batch, int seq, int nq, int nkv, int d, const bf16_t* qkv, bf16_t* o, float* lse,
-                            hipStream_t stream);
+int dh_launch_attn_fwd_bf16(int batch, int seq, int nq, int nkv, int d, const bf16_t* qkv, bf16_t* o, float* lse, void* ws,
+                            size_t ws_bytes, hipStream_t stream);
+size_t dh_attn_fwd_bf16_ws_bytes(int batch, int seq, int nq, int nkv, int d);
 int dh_launch_attn_bwd_bf16(int batch, int seq, int nq, int nkv, int d, const bf16_t* qkv, const bf16_t* o,
                             const bf16_t* dout, const float* lse, bf16_t* dqkv, float* delta, void* ws, size_t ws_bytes,
                             hipStream_t stream);

@@ -22,7 +22,7 @@ struct dh_layer {
   size_t s_mu1, s_rstd1, s_h1, s_qkv, s_o, s_lse, s_x2, s_mu2, s_rstd2, s_h2, s_gu, s_a;
   size_t s_idx, s_prob, s_tab[9], s_xg, s_yp, saved_bytes;
   // forward workspace offsets
-  size_t f_hs, f_part, f_red, f_xp, f_yg, f_gemm, f_gemm_bytes, fwd_bytes;
+  size_t f_hs, f_part, f_red, f_xp, f_yg, f_attn, f_attn_bytes, f_gemm, f_gemm_bytes, fwd_bytes;
   // backward workspace offsets
   size_t b_dz, b_da, b_dgu, b_part, b_red, b_dx2, b_dy, b_do, b_dqkv, b_delta, b_attn, b_attn_bytes, b_norm, b_norm_bytes;
   size_t b_colsum, b_colsum_bytes, b_dyp, b_dprob, b_dyg, b_dxg, b_gemm, b_gemm_bytes, bwd_bytes;
@@ -205,6 +205,8 @@ extern "C" int dh_layer_create(const dh_layer_config* cfg, dh_layer** out) {
   L->f_red = take(cur, moe ? 0 : Ts * H * es);
   L->f_xp = take(cur, moe ? Tf * H * es : 0);
   L->f_yg = take(cur, moe ? Tf * H * es : 0);
+  L->f_attn_bytes = bf ? dh_attn_fwd_bf16_ws_bytes(c.batch, c.seq, c.n_q_heads, c.n_kv_heads, c.head_dim) : 0;
+  L->f_attn = take(cur, L->f_attn_bytes);
   size_t fg = std::max(gw(0, 0, T, L->n_qkv, H), gw(0, 0, T, H, L->n_o));
   if (!moe) fg = std::max(fg, std::max(gw(0, 0, T, Fin, H), gw(0, 0, T, H, F)));
   L->f_gemm_bytes = fg;
@@ -322,10 +324,10 @@ static dh_moe_tables moe_tables_of(const dh_layer* L, const void* saved) {
 }
 
 // The attention block's operators are shared by the three architectures.
-static int op_attn_fwd(dh_layer* L, char* sv, hipStream_t s) {
+static int op_attn_fwd(dh_layer* L, char* sv, char* ws, hipStream_t s) {
   const dh_layer_config& c = L->c;
   return dh_attn_fwd(c.dtype, c.batch, c.seq, c.n_q_heads, c.n_kv_heads, c.head_dim, sv + L->s_qkv, sv + L->s_o,
-                     (float*)(sv + L->s_lse), s);
+                     (float*)(sv + L->s_lse), ws + L->f_attn, L->f_attn_bytes, s);
 }
 static int op_attn_bwd(dh_layer* L, const char* sv, char* ws, hipStream_t s) {
   const dh_layer_config& c = L->c;
@@ -351,7 +353,7 @@ static int llama_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hip
     case DH_F_ROPE:
       return op_rope(L, sv + L->s_qkv, 0, s);
     case DH_F_ATTN:
-      return op_attn_fwd(L, sv, s);
+      return op_attn_fwd(L, sv, ws, s);
     case DH_F_PROJ:
       return gemm(L, false, false, T, H, L->n_o, sv + L->s_o, L->w.Wo, ws + L->f_part, false, gws, L->f_gemm_bytes, s);
     case DH_F_AR1:
@@ -432,7 +434,7 @@ static int gpt_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hipSt
     case DH_GF_QKV:
       return gemm(L, false, false, T, L->n_qkv, H, sv + L->s_h1, L->w.Wqkv, sv + L->s_qkv, false, gws, L->f_gemm_bytes, s, L->w.bqkv);
     case DH_GF_ATTN:
-      return op_attn_fwd(L, sv, s);
+      return op_attn_fwd(L, sv, ws, s);
     case DH_GF_PROJ:
       return gemm(L, false, false, T, H, L->n_o, sv + L->s_o, L->w.Wo, ws + L->f_part, false, gws, L->f_gemm_bytes, s);
     case DH_GF_RS1:
@@ -527,7 +529,7 @@ static int moe_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hipSt
     case DH_MF_ROPE:
       return op_rope(L, sv + L->s_qkv, 0, s);
     case DH_MF_ATTN:
-      return op_attn_fwd(L, sv, s);
+      return op_attn_fwd(L, sv, ws, s);
     case DH_MF_PROJ:
       return gemm(L, false, false, T, H, L->n_o, sv + L->s_o, L->w.Wo, ws + L->f_part, false, gws, L->f_gemm_bytes, s);
     case DH_MF_NORM2:

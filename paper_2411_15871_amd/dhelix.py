@@ -130,7 +130,8 @@ SIGNATURES = {
     "dh_swiglu_fwd": (_I, [_I, _I, _I, _P, _P, _P]),
     "dh_swiglu_bwd": (_I, [_I, _I, _I, _P, _P, _P, _P]),
     "dh_add": (_I, [_I, _Z, _P, _P, _P, _P]),
-    "dh_attn_fwd": (_I, [_I, _I, _I, _I, _I, _I, _P, _P, _P, _P]),
+    "dh_attn_fwd": (_I, [_I, _I, _I, _I, _I, _I, _P, _P, _P, _P, _Z, _P]),
+    "dh_attn_fwd_workspace_bytes": (_Z, [_I, _I, _I, _I, _I, _I]),
     "dh_attn_bwd": (_I, [_I, _I, _I, _I, _I, _I, _P, _P, _P, _P, _P, _P, _P, _Z, _P]),
     "dh_attn_bwd_workspace_bytes": (_Z, [_I, _I, _I, _I, _I, _I]),
     "dh_moe_route": (_I, [_I, _I, _P, _P, _P, _P]),
@@ -392,8 +393,12 @@ def dh_add(dtype, n, a, b, out, stream=None):
     _check(lib.dh_add(dtype, n, _ptr(a), _ptr(b), _ptr(out), _stream(stream)))
 
 
-def dh_attn_fwd(dtype, batch, seq, nq, nkv, d, qkv, o, lse, stream=None):
-    _check(lib.dh_attn_fwd(dtype, batch, seq, nq, nkv, d, _ptr(qkv), _ptr(o), _ptr(lse), _stream(stream)))
+def dh_attn_fwd(dtype, batch, seq, nq, nkv, d, qkv, o, lse, ws=None, ws_bytes=0, stream=None):
+    _check(lib.dh_attn_fwd(dtype, batch, seq, nq, nkv, d, _ptr(qkv), _ptr(o), _ptr(lse), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def dh_attn_fwd_workspace_bytes(dtype, batch, seq, nq, nkv, d):
+    return lib.dh_attn_fwd_workspace_bytes(dtype, batch, seq, nq, nkv, d)
 
 
 def dh_attn_bwd(dtype, batch, seq, nq, nkv, d, qkv, o, dout, lse, dqkv, delta, ws=None, ws_bytes=0, stream=None):

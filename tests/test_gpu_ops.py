@@ -221,7 +221,8 @@ def test_gemm_bf16_shape_errors(dh):
 
 
 ATTN_CASES = [  # batch, seq, nq, nkv, d
-    (1, 1, 2, 1, 64), (1, 128, 4, 4, 64), (2, 200, 4, 2, 64), (1, 333, 4, 1, 128), (2, 512, 2, 1, 128), (1, 1100, 8, 2, 128)]
+    (1, 1, 2, 1, 64), (1, 128, 4, 4, 64), (2, 200, 4, 2, 64), (1, 333, 4, 1, 128), (2, 512, 2, 1, 128), (1, 1100, 8, 2, 128),
+    (1, 2100, 2, 1, 64)]
 
 
 @pytest.mark.parametrize("bf16", [False, True])
@@ -233,7 +234,11 @@ def test_attention_fwd_bwd(dh, bf16, batch, seq, nq, nkv, d):
     qd, dod = dev(qkv, bf16), dev(do, bf16)
     o = torch.empty(T, nq * d, dtype=tdtype(bf16), device="cuda")
     lse = torch.empty(nq, T, dtype=torch.float32, device="cuda")
-    dh.dh_attn_fwd(dt(dh, bf16), batch, seq, nq, nkv, d, qd, o, lse)
+    fwsb = dh.dh_attn_fwd_workspace_bytes(dt(dh, bf16), batch, seq, nq, nkv, d)
+    fws = torch.empty(max(fwsb, 16), dtype=torch.uint8, device="cuda")
+    dh.dh_attn_fwd(dt(dh, bf16), batch, seq, nq, nkv, d, qd, o, lse, fws, fwsb)  # long rows split over several blocks
+    o_ns = torch.empty_like(o); lse_ns = torch.empty_like(lse)
+    dh.dh_attn_fwd(dt(dh, bf16), batch, seq, nq, nkv, d, qd, o_ns, lse_ns)       # no workspace: rows not split
     q64 = qkv[:, : nq * d].astype(np.float64).reshape(T, nq, d)
     k64 = qkv[:, nq * d: (nq + nkv) * d].astype(np.float64).reshape(T, nkv, d)
     v64 = qkv[:, (nq + nkv) * d:].astype(np.float64).reshape(T, nkv, d)
@@ -241,6 +246,9 @@ def test_attention_fwd_bwd(dh, bf16, batch, seq, nq, nkv, d):
     tol = 1e-2 if bf16 else 1e-5
     assert rel(host(o), o_ref.reshape(T, nq * d)) <= tol
     assert np.max(np.abs(host(lse) - lse_ref)) <= (2e-2 if bf16 else 1e-5)
+    assert rel(host(o_ns), o_ref.reshape(T, nq * d)) <= tol
+    assert np.max(np.abs(host(lse_ns) - lse_ref)) <= (2e-2 if bf16 else 1e-5)
+    assert (fwsb > 0) == (bf16 and seq > 512)
     dqkv = torch.zeros(T, nqkv, dtype=tdtype(bf16), device="cuda")
     delta = torch.empty(nq, T, dtype=torch.float32, device="cuda")
     wsb = dh.dh_attn_bwd_workspace_bytes(dt(dh, bf16), batch, seq, nq, nkv, d)
