@@ -111,6 +111,7 @@ template <int D, int N> __device__ __forceinline__ void acc_settle(f32x16 (&a)[N
   if constexpr (D == 128) mfma_acc_settle(a);
 }
 
+
 template <int D>
 struct ATile {
   static constexpr int LD = D;
@@ -195,6 +196,30 @@ __device__ __forceinline__ bf16x8 pack_rows(const f32x16& t, int c) {
   return f;
 }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// acc[dt] += T[64 x D]^T (transposed fragments of the LDS tile behind P) * src, src = a 64 x 32 score tile held as
+// two 32x32 register tiles.  The 64 "k" rows go in four groups of 16 (g = 2*mt + c); the transposed fragments
+// of group g+1 are fetched before the products of group g are issued, so no product waits for its own LDS
+// read, and between(g) runs after group g's products are issued (independent vector work to overlap them).
+template <int D, class F>
+__device__ __forceinline__ void acc_tile_tr(f32x16 (&acc)[D / 32], const TilePtrs<D>& P, const f32x16 (&src)[2], F between) {
+  using TL = ATile<D>;
+  bf16x8 fr[2][D / 32];
+#pragma unroll
+  for (int dt = 0; dt < D / 32; dt++) fr[0][dt] = lds_frag_tr(P.t0[dt], P.t1[dt], 0);
+#pragma unroll
+  for (int g = 0; g < 4; g++) {
+    if (g + 1 < 4) {
+      const int ro = (g + 1) * 16 * TL::LD * 2;
+#pragma unroll
+      for (int dt = 0; dt < D / 32; dt++) fr[(g + 1) & 1][dt] = lds_frag_tr(P.t0[dt], P.t1[dt], ro);
+    }
+    const bf16x8 pf = pack_rows(src[g >> 1], g & 1);
+#pragma unroll
+    for (int dt = 0; dt < D / 32; dt++) acc_mfma<D>(acc[dt], fr[g & 1][dt], pf);
+    between(g);
+  }
+}
 
 template <int D>
 __device__ __forceinline__ void load_row_frags(bf16x8 (&f)[D / 16], const bf16_t* row, bool valid, int kg) {
@@ -552,19 +577,13 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(int seq, i
         for (int r = 0; r < 16; r++)
           if (kb + mt * 32 + 8 * (r >> 2) + 4 * kg + (r & 3) > iq) st[mt][r] = 0.f;
     }
+    // dS^T = P^T (dP^T - delta), one quarter (8 registers of a tile) ahead of the products that consume it
+    auto ds_quarter = [&](int g) {
 #pragma unroll
-    for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-      for (int r = 0; r < 16; r++) st[mt][r] *= dp[mt][r] - dl;
-#pragma unroll
-    for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-      for (int c = 0; c < 2; c++) {
-        const bf16x8 df = pack_rows(st[mt], c);
-        const int ro = (mt * 32 + 16 * c) * TL::LD * 2;
-#pragma unroll
-        for (int dt = 0; dt < D / 32; dt++) acc_mfma<D>(dqt[dt], lds_frag_tr(Kp.t0[dt], Kp.t1[dt], ro), df);
-      }
+      for (int r = 0; r < 8; r++) st[g >> 1][8 * (g & 1) + r] *= dp[g >> 1][8 * (g & 1) + r] - dl;
+    };
+    ds_quarter(0);
+    acc_tile_tr<D>(dqt, Kp, st, [&](int g) { if (g + 1 < 4) ds_quarter(g + 1); });
   }
   acc_settle<D>(dqt);
   if (part != nullptr) {  // float32 partial of this chunk: part[batch][head][pair][128 rows][D], unscaled
@@ -728,32 +747,18 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, 
           if (qi < jk || qi >= seq) st[mt][r] = 0.f;
         }
     }
+    // dV^T += dO^T P; once a quarter of P (8 registers of a tile) is packed for its products, it is turned
+    // into dS = P (dP - delta) in place while those products run; then dK^T += Q^T dS.
+    acc_tile_tr<D>(dvt, Op, st, [&](int g) {
+      const int mt = g >> 1, c = g & 1;
 #pragma unroll
-    for (int mt = 0; mt < 2; mt++)
+      for (int q = 0; q < 2; q++) {
+        const f32x4 dv4 = *reinterpret_cast<const f32x4*>(ds + mt * 32 + 8 * (2 * c + q) + 4 * kg);
 #pragma unroll
-      for (int c = 0; c < 2; c++) {
-        const bf16x8 pf = pack_rows(st[mt], c);
-        const int ro = (mt * 32 + 16 * c) * TL::LD * 2;
-#pragma unroll
-        for (int dt = 0; dt < D / 32; dt++) acc_mfma<D>(dvt[dt], lds_frag_tr(Op.t0[dt], Op.t1[dt], ro), pf);
+        for (int e = 0; e < 4; e++) st[mt][8 * c + 4 * q + e] *= dp[mt][8 * c + 4 * q + e] - dv4[e];
       }
-#pragma unroll
-    for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; q4++) {
-        const f32x4 dv4 = *reinterpret_cast<const f32x4*>(ds + mt * 32 + 8 * q4 + 4 * kg);
-#pragma unroll
-        for (int e = 0; e < 4; e++) st[mt][4 * q4 + e] *= dp[mt][4 * q4 + e] - dv4[e];
-      }
-#pragma unroll
-    for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-      for (int c = 0; c < 2; c++) {
-        const bf16x8 df = pack_rows(st[mt], c);
-        const int ro = (mt * 32 + 16 * c) * TL::LD * 2;
-#pragma unroll
-        for (int dt = 0; dt < D / 32; dt++) acc_mfma<D>(dkt[dt], lds_frag_tr(Qp.t0[dt], Qp.t1[dt], ro), df);
-      }
+    });
+    acc_tile_tr<D>(dkt, Qp, st, [](int) {});
   }
   acc_settle<D>(dkt);
   acc_settle<D>(dvt);
