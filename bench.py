@@ -115,9 +115,25 @@ def main():
     nf, nb = gf.n_ops, gb.n_ops
     seq_plan = dh.dh_plan_sequential(run.layer)
     free_plan = dh.make_plan(list(seq_plan.fwd_order[:nf]), list(seq_plan.bwd_order[:nb]), [(0, nf, 0, nb)])
+    # Last offline step: the cost model ranks plans, measurement picks among its best few.  Candidates: the searched
+    # plan at three barrier prices (dearer barriers -> fewer, longer segment pairs), each also with its operator orders
+    # kept but all barriers dropped, and the default orders without barriers.
+    cands = [("default order, one pair", free_plan)]
+    for bc in (5e-6, 3e-5, 2e-4):
+        p_bc, _ = dh.dh_plan_search(gf, gb, table, bc, 256)
+        fo_c, bo_c, pairs_c = dh.plan_to_py(p_bc)
+        cands.append(("searched, barrier %.0e, %d pairs" % (bc, len(pairs_c)), p_bc))
+        cands.append(("searched orders (barrier %.0e), one pair" % bc, dh.make_plan(fo_c, bo_c, [(0, nf, 0, nb)])))
+    probe_steps = max(5, args.steps // 5)
+    timed = [(time_steps(lambda p=p: run.si_step(alpha, beta, p, sa, sb, sc), probe_steps, 2, torch), name, p) for name, p in cands]
+    for t, name, _ in timed:
+        log("  candidate %-48s %.1f us" % (name, t * 1e6))
+    _, best_name, best_plan = min(timed, key=lambda x: x[0])
+    fo, bo, pairs = dh.plan_to_py(best_plan)
+    log("chosen plan:", best_name, [([fnames[o] for o in fo[a:b]], [bnames[o] for o in bo[c:d]]) for a, b, c, d in pairs])
     t_seq = time_steps(lambda: run.si_step(alpha, beta, seq_plan, sa, sb, sc), args.steps, args.warmup, torch)
     t_free = time_steps(lambda: run.si_step(alpha, beta, free_plan, sa, sb, sc), args.steps, args.warmup, torch)
-    t_si = time_steps(lambda: run.si_step(alpha, beta, plan, sa, sb, sc), args.steps, args.warmup, torch)
+    t_si = time_steps(lambda: run.si_step(alpha, beta, best_plan, sa, sb, sc), args.steps, args.warmup, torch)
     t_comm = sum(t_f[i] for i in range(nf) if gf.is_comm[i]) + sum(t_b[j] for j in range(nb) if gb.is_comm[j])
     log("T_seq %.1f us, T_free-running %.1f us, T_SI(plan) %.1f us, stand-ins solo %.1f us" % (t_seq * 1e6, t_free * 1e6, t_si * 1e6, t_comm * 1e6))
 
@@ -152,7 +168,7 @@ def main():
         "ms_per_step": t_si * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg["bf16"] else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "arch": cfg["arch"], "tokens_per_strand": run.T, "comm_blocks": args.comm_blocks,
-                   "plan_pairs": len(pairs)},
+                   "plan_pairs": len(pairs), "plan": best_name},
         "pct_bf16_peak": 100.0 * value / BF16_MFMA_PEAK_TFLOPS,
         "tokens_per_s": run.T / t_si,
         "speedup_vs_sequential": t_seq / t_si,

@@ -33,7 +33,9 @@
 #include "common.h"
 
 #define GB_BK 32
+#ifndef GB_STAGES
 #define GB_STAGES 4
+#endif
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
