@@ -134,8 +134,13 @@ def main():
     t_seq = time_steps(lambda: run.si_step(alpha, beta, seq_plan, sa, sb, sc), args.steps, args.warmup, torch)
     t_free = time_steps(lambda: run.si_step(alpha, beta, free_plan, sa, sb, sc), args.steps, args.warmup, torch)
     t_si = time_steps(lambda: run.si_step(alpha, beta, best_plan, sa, sb, sc), args.steps, args.warmup, torch)
+    # the same step replayed from a HIP graph (one launch per step instead of one per operator)
+    graph = dh.dh_si_graph_create(run.layer, alpha.fwd_args, beta.bwd_args, best_plan, run.ws, run.ws_bytes, sa, sb)
+    t_graph = time_steps(lambda: dh.dh_si_graph_launch(graph, sa), args.steps, args.warmup, torch)
+    dh.dh_si_graph_destroy(graph)
     t_comm = sum(t_f[i] for i in range(nf) if gf.is_comm[i]) + sum(t_b[j] for j in range(nb) if gb.is_comm[j])
-    log("T_seq %.1f us, T_free-running %.1f us, T_SI(plan) %.1f us, stand-ins solo %.1f us" % (t_seq * 1e6, t_free * 1e6, t_si * 1e6, t_comm * 1e6))
+    log("T_seq %.1f us, T_free-running %.1f us, T_SI(plan) %.1f us, T_SI(plan, graph replay) %.1f us, stand-ins solo %.1f us"
+        % (t_seq * 1e6, t_free * 1e6, t_si * 1e6, t_graph * 1e6, t_comm * 1e6))
 
     # roofline of the dominant kernel: the first FFN GEMM (gate/up projection; largest share of the FLOPs), timed
     # alone with events on the stream it is launched on.  MoE: one local expert's balanced share of the rows.
@@ -172,7 +177,7 @@ def main():
         "pct_bf16_peak": 100.0 * value / BF16_MFMA_PEAK_TFLOPS,
         "tokens_per_s": run.T / t_si,
         "speedup_vs_sequential": t_seq / t_si,
-        "ms_sequential": t_seq * 1e3, "ms_free_running": t_free * 1e3,
+        "ms_sequential": t_seq * 1e3, "ms_free_running": t_free * 1e3, "ms_graph_replay": t_graph * 1e3,
         "comm_hidden_frac": (t_seq - t_si) / t_comm if t_comm > 0 else None,
         "roofline": {"bound": "mfma", "achieved": gemm_tflops, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": gemm_tflops / BF16_MFMA_PEAK_TFLOPS, "traffic": HBM_TRAFFIC_BYTES.get(args.workload),

@@ -285,6 +285,19 @@ int dh_si_step(dh_layer* layer, const dh_fwd_args* alpha, const dh_bwd_args* bet
                const dh_plan* plan, void* ws, size_t ws_bytes, void* stream_alpha,
                void* stream_beta, void* stream_comm);
 
+/* The same step recorded once into a HIP graph (stream capture on stream_alpha, which forks into
+ * stream_beta; nothing runs) and replayed with one launch per step, which removes the per-operator
+ * launch intervals (Sec. 6.4 names them as the remaining loss).  The two streams must be distinct and
+ * non-null.  A graph holds dependencies, not streams: every collective stand-in becomes a node in its
+ * strand's chain.  All buffers named by alpha, beta, ws and the bound weights/gradients must stay where
+ * they are while the graph is in use.  dh_si_graph_launch enqueues one step on `stream`. */
+typedef struct dh_si_graph dh_si_graph;
+int dh_si_graph_create(dh_layer* layer, const dh_fwd_args* alpha, const dh_bwd_args* beta,
+                       const dh_plan* plan, void* ws, size_t ws_bytes, void* stream_alpha,
+                       void* stream_beta, dh_si_graph** out);
+int dh_si_graph_launch(dh_si_graph* graph, void* stream);
+void dh_si_graph_destroy(dh_si_graph* graph);
+
 /* ------------------------------------------------------------------------------------------
  * Collective stand-ins (Sec. 2.1, "Collective Communication"): memory-bound local kernels with the
  * payload of the collective they replace.  parts: host array of n_ranks device pointers, each `elems`

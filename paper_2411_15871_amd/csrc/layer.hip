@@ -736,17 +736,22 @@ static int on_comm_stream(dh_layer* L, hipStream_t strand, hipStream_t comm, Fn 
   return DH_OK;
 }
 
-extern "C" int dh_si_step(dh_layer* L, const dh_fwd_args* alpha, const dh_bwd_args* beta, const dh_plan* plan, void* ws,
-                          size_t ws_bytes, void* stream_alpha, void* stream_beta, void* stream_comm) {
+static int check_si_args(dh_layer* L, const dh_fwd_args* alpha, const dh_bwd_args* beta, const dh_plan* plan, const void* ws,
+                         size_t ws_bytes) {
   int rc = check_fwd_args(L, alpha);
   if (rc) return rc;
   if ((rc = check_bwd_args(L, beta))) return rc;
   if (!plan) DH_FAIL(DH_ERR_INVALID_ARG, "si_step: plan is null");
   if ((rc = dh_plan_validate(&L->gf, &L->gb, plan))) return rc;
-  if ((rc = check_ws(L, DH_WS_SI, ws, ws_bytes))) return rc;
-  if (L->T == 0) return DH_OK;
-  if ((rc = ensure_events(L))) return rc;
-  hipStream_t sa = (hipStream_t)stream_alpha, sb = (hipStream_t)stream_beta, sc = (hipStream_t)stream_comm;
+  return check_ws(L, DH_WS_SI, ws, ws_bytes);
+}
+
+// Enqueues one SI step.  Stream beta (and the communication stream, through the events around each stand-in)
+// forks from stream alpha at the start and is joined back into it at the end, so the whole step is one
+// fork/join region of stream alpha -- which is also what stream capture requires.
+static int enqueue_si(dh_layer* L, const dh_fwd_args* alpha, const dh_bwd_args* beta, const dh_plan* plan, void* ws,
+                      hipStream_t sa, hipStream_t sb, hipStream_t sc) {
+  int rc;
   char* ws_f = (char*)ws;
   char* ws_b = (char*)ws + L->fwd_bytes;
   const bool two = sb != sa;
@@ -773,15 +778,85 @@ extern "C" int dh_si_step(dh_layer* L, const dh_fwd_args* alpha, const dh_bwd_ar
         if (rc) return rc;
       }
     }
-    if (two) {  // cross-strand barrier on the device
+    if (two) {  // cross-strand barrier on the device; after the last pair beta only joins alpha
       hipEvent_t ea = next_event(L), eb = next_event(L);
-      DH_HIP(hipEventRecord(ea, sa));
+      const bool last = k + 1 == plan->n_pairs;
+      if (!last) DH_HIP(hipEventRecord(ea, sa));
       DH_HIP(hipEventRecord(eb, sb));
       DH_HIP(hipStreamWaitEvent(sa, eb, 0));
-      DH_HIP(hipStreamWaitEvent(sb, ea, 0));
+      if (!last) DH_HIP(hipStreamWaitEvent(sb, ea, 0));
     }
   }
   return DH_OK;
+}
+
+extern "C" int dh_si_step(dh_layer* L, const dh_fwd_args* alpha, const dh_bwd_args* beta, const dh_plan* plan, void* ws,
+                          size_t ws_bytes, void* stream_alpha, void* stream_beta, void* stream_comm) {
+  int rc = check_si_args(L, alpha, beta, plan, ws, ws_bytes);
+  if (rc) return rc;
+  if (L->T == 0) return DH_OK;
+  if ((rc = ensure_events(L))) return rc;
+  return enqueue_si(L, alpha, beta, plan, ws, (hipStream_t)stream_alpha, (hipStream_t)stream_beta, (hipStream_t)stream_comm);
+}
+
+// ------------------------------------------------------------------------------------ captured SI step
+struct dh_si_graph {
+  hipGraph_t graph;
+  hipGraphExec_t exec;
+};
+
+extern "C" int dh_si_graph_create(dh_layer* L, const dh_fwd_args* alpha, const dh_bwd_args* beta, const dh_plan* plan, void* ws,
+                                  size_t ws_bytes, void* stream_alpha, void* stream_beta, dh_si_graph** out) {
+  if (!out) DH_FAIL(DH_ERR_INVALID_ARG, "si_graph_create: null pointer");
+  *out = nullptr;
+  int rc = check_si_args(L, alpha, beta, plan, ws, ws_bytes);
+  if (rc) return rc;
+  if (L->T == 0) DH_FAIL(DH_ERR_INVALID_ARG, "si_graph_create: empty micro-batch");
+  hipStream_t sa = (hipStream_t)stream_alpha, sb = (hipStream_t)stream_beta;
+  if (sa == nullptr || sb == nullptr || sb == sa)
+    DH_FAIL(DH_ERR_INVALID_ARG, "si_graph_create: needs two distinct, non-null strand streams");
+  if ((rc = ensure_events(L))) return rc;
+  // A graph holds dependencies, not streams.  A strand never runs past its own collective (its next operator
+  // consumes the result), so a stand-in is recorded as a node of its strand's chain; a separate communication
+  // stream would add nothing but an order among the two strands' collectives.
+  DH_HIP(hipStreamBeginCapture(sa, hipStreamCaptureModeThreadLocal));
+  rc = enqueue_si(L, alpha, beta, plan, ws, sa, sb, nullptr);
+  hipGraph_t graph = nullptr;
+  hipError_t e = hipStreamEndCapture(sa, &graph);  // always end the capture, also after a failed enqueue
+  if (rc != DH_OK) {
+    if (graph) (void)hipGraphDestroy(graph);
+    (void)hipGetLastError();
+    return rc;
+  }
+  if (e != hipSuccess || graph == nullptr) {
+    (void)hipGetLastError();
+    return dh_set_error(DH_ERR_HIP, "si_graph_create: stream capture failed: %s", hipGetErrorString(e));
+  }
+  hipGraphExec_t exec = nullptr;
+  e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+  if (e != hipSuccess) {
+    (void)hipGraphDestroy(graph);
+    (void)hipGetLastError();
+    return dh_set_error(DH_ERR_HIP, "si_graph_create: hipGraphInstantiate failed: %s", hipGetErrorString(e));
+  }
+  dh_si_graph* g = new dh_si_graph();
+  g->graph = graph;
+  g->exec = exec;
+  *out = g;
+  return DH_OK;
+}
+
+extern "C" int dh_si_graph_launch(dh_si_graph* g, void* stream) {
+  if (!g) DH_FAIL(DH_ERR_INVALID_ARG, "si_graph_launch: null graph");
+  DH_HIP(hipGraphLaunch(g->exec, (hipStream_t)stream));
+  return DH_OK;
+}
+
+extern "C" void dh_si_graph_destroy(dh_si_graph* g) {
+  if (!g) return;
+  (void)hipGraphExecDestroy(g->exec);
+  (void)hipGraphDestroy(g->graph);
+  delete g;
 }
 
 // ------------------------------------------------------------------------------------ profiler

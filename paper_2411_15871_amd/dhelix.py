@@ -118,6 +118,10 @@ SIGNATURES = {
     "dh_plan_validate": (_I, [C.POINTER(dh_op_graph), C.POINTER(dh_op_graph), C.POINTER(dh_plan)]),
     "dh_plan_sequential": (_I, [_P, C.POINTER(dh_plan)]),
     "dh_si_step": (_I, [_P, C.POINTER(dh_fwd_args), C.POINTER(dh_bwd_args), C.POINTER(dh_plan), _P, _Z, _P, _P, _P]),
+    "dh_si_graph_create": (_I, [_P, C.POINTER(dh_fwd_args), C.POINTER(dh_bwd_args), C.POINTER(dh_plan), _P, _Z, _P, _P,
+                                C.POINTER(_P)]),
+    "dh_si_graph_launch": (_I, [_P, _P]),
+    "dh_si_graph_destroy": (None, [_P]),
     "dh_comm_standin": (_I, [_I, _I, C.POINTER(_P), _P, _Z, _I, _I, _P]),
     "dh_stream_create_masked": (_I, [_I, C.POINTER(_P)]),
     "dh_stream_destroy": (_I, [_P]),
@@ -337,6 +341,21 @@ def dh_profile_pairs(layer, alpha, beta, ws, ws_bytes, stream_alpha, stream_beta
 def dh_si_step(layer, alpha, beta, plan, ws, ws_bytes, stream_alpha, stream_beta, stream_comm=None):
     _check(lib.dh_si_step(layer, C.byref(alpha), C.byref(beta), C.byref(plan), _ptr(ws), ws_bytes,
                           _stream(stream_alpha), _stream(stream_beta), _stream(stream_comm)))
+
+
+def dh_si_graph_create(layer, alpha, beta, plan, ws, ws_bytes, stream_alpha, stream_beta):
+    g = _P()
+    _check(lib.dh_si_graph_create(layer, C.byref(alpha), C.byref(beta), C.byref(plan), _ptr(ws), ws_bytes,
+                                  _stream(stream_alpha), _stream(stream_beta), C.byref(g)))
+    return g
+
+
+def dh_si_graph_launch(graph, stream=None):
+    _check(lib.dh_si_graph_launch(graph, _stream(stream)))
+
+
+def dh_si_graph_destroy(graph):
+    lib.dh_si_graph_destroy(graph)
 
 
 def dh_comm_standin(kind, parts, out, elems, dtype, n_blocks=0, stream=None):

@@ -194,3 +194,40 @@ def test_empty_micro_batch_is_a_no_op():
         assert all(float(g.abs().sum()) == 0.0 for g in run.g.values())
     finally:
         run.close()
+
+
+@pytest.mark.parametrize("name", ["c1_tiny_fp32", "gpt_bf16_mid", "moe_bf16_mid"])
+def test_captured_si_step_replays_bitwise(name):
+    """The SI step recorded into a HIP graph gives, on every replay, bitwise what the eager step gives; replays are
+    separated by eager work and synchronisations of the program's own."""
+    from paper_2411_15871_amd import dhelix as dh
+    cfg, _ = CASES[name]
+    run = H.LayerRun(cfg)
+    try:
+        alpha, beta = run.strand(0), run.strand(1)
+        sa, sb, sc = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+        run.fwd(beta)
+        torch.cuda.synchronize()
+        rng = random.Random(11)
+        for plan in (dh.dh_plan_sequential(run.layer), random_legal_plan(dh, run, rng)):
+            alpha.out.zero_(); alpha.saved.zero_(); beta.dx.zero_(); run.zero_grads()
+            run.si_step(alpha, beta, plan, sa, sb, sc)
+            ref = snapshot(run, alpha, beta)
+            graph = dh.dh_si_graph_create(run.layer, alpha.fwd_args, beta.bwd_args, plan, run.ws, run.ws_bytes, sa, sb)
+            try:
+                for rep in range(3):
+                    print("replay", rep, flush=True)
+                    alpha.out.zero_(); alpha.saved.zero_(); beta.dx.zero_(); run.zero_grads()
+                    torch.cuda.synchronize()
+                    dh.dh_si_graph_launch(graph, sa)
+                    got = snapshot(run, alpha, beta)
+                    for a, b in zip(got, ref):
+                        assert torch.equal(a, b), rep
+                    run.si_step(alpha, beta, plan, sa, sb, sc)  # eager work between the replays
+                    torch.cuda.synchronize()
+            finally:
+                dh.dh_si_graph_destroy(graph)
+        with pytest.raises(dh.DhelixError):
+            dh.dh_si_graph_create(run.layer, alpha.fwd_args, beta.bwd_args, plan, run.ws, run.ws_bytes, sa, sa)
+    finally:
+        run.close()
