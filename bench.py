@@ -134,6 +134,14 @@ def main():
     t_seq = time_steps(lambda: run.si_step(alpha, beta, seq_plan, sa, sb, sc), args.steps, args.warmup, torch)
     t_free = time_steps(lambda: run.si_step(alpha, beta, free_plan, sa, sb, sc), args.steps, args.warmup, torch)
     t_si = time_steps(lambda: run.si_step(alpha, beta, best_plan, sa, sb, sc), args.steps, args.warmup, torch)
+    # ablations of Sec. 6.1 / 6.4 through the same executor: round-robin interleaving ("Wavelet+"), and the searched plan
+    # with the weight-gradient operators left in their default places
+    rr_plan = dh.dh_plan_round_robin(gf, gb)
+    fixed_plan, _ = dh.dh_plan_search(gf, gb, table, 5e-6, 1)
+    probe = max(5, args.steps // 3)
+    t_rr = time_steps(lambda: run.si_step(alpha, beta, rr_plan, sa, sb, sc), probe, 2, torch)
+    t_fixed = time_steps(lambda: run.si_step(alpha, beta, fixed_plan, sa, sb, sc), probe, 2, torch)
+    log("ablations: round-robin %.1f us, weight gradients fixed %.1f us" % (t_rr * 1e6, t_fixed * 1e6))
     # the same step replayed from a HIP graph (one launch per step instead of one per operator)
     graph = dh.dh_si_graph_create(run.layer, alpha.fwd_args, beta.bwd_args, best_plan, run.ws, run.ws_bytes, sa, sb)
     t_graph = time_steps(lambda: dh.dh_si_graph_launch(graph, sa), args.steps, args.warmup, torch)
@@ -178,6 +186,7 @@ def main():
         "tokens_per_s": run.T / t_si,
         "speedup_vs_sequential": t_seq / t_si,
         "ms_sequential": t_seq * 1e3, "ms_free_running": t_free * 1e3, "ms_graph_replay": t_graph * 1e3,
+        "ms_round_robin": t_rr * 1e3, "ms_wgrad_fixed": t_fixed * 1e3,
         "comm_hidden_frac": (t_seq - t_si) / t_comm if t_comm > 0 else None,
         "roofline": {"bound": "mfma", "achieved": gemm_tflops, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": gemm_tflops / BF16_MFMA_PEAK_TFLOPS, "traffic": HBM_TRAFFIC_BYTES.get(args.workload),

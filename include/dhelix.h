@@ -273,6 +273,12 @@ int dh_plan_search(const dh_op_graph* fwd, const dh_op_graph* bwd, const dh_over
  * sequences.  Returns DH_OK or DH_ERR_PLAN_INVALID. */
 int dh_plan_validate(const dh_op_graph* fwd, const dh_op_graph* bwd, const dh_plan* plan);
 
+/* The round-robin comparison schedule of Sec. 6.1 ("Wavelet+"): default operator orders, one forward
+ * operator paired with one backward operator at a time, a barrier after every pair.  (The other
+ * ablation of Sec. 6.4, weight gradients left in their default places, is dh_plan_search with
+ * max_orders = 1.)  Host only. */
+int dh_plan_round_robin(const dh_op_graph* fwd, const dh_op_graph* bwd, dh_plan* out);
+
 /* The degenerate plan "all forward, then all backward" in default order (sequential baseline). */
 int dh_plan_sequential(const dh_layer* layer, dh_plan* out);
 

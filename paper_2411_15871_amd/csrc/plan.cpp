@@ -2,6 +2,7 @@
 // the pairing recurrence (Eq. 2), the segment-pair cost model, operator sequencing and barrier
 // placement.  No device code.
 #include <algorithm>
+#include <cstring>
 #include <limits>
 #include <vector>
 #include "common.h"
@@ -219,5 +220,27 @@ extern "C" int dh_plan_search(const dh_op_graph* fwd, const dh_op_graph* bwd, co
   out->n_pairs = (int)pairs.size();
   for (size_t k = 0; k < pairs.size(); k++) out->pairs[k] = pairs[k];
   *makespan = best;
+  return DH_OK;
+}
+
+// The comparison schedule of Sec. 6.1 ("Wavelet+"): the two strands' operators are interleaved one by one in
+// their default orders, with a barrier after every pair, and no operator is moved.
+extern "C" int dh_plan_round_robin(const dh_op_graph* fwd, const dh_op_graph* bwd, dh_plan* out) {
+  if (!fwd || !bwd || !out) DH_FAIL(DH_ERR_INVALID_ARG, "plan_round_robin: null pointer");
+  if (fwd->n_ops < 0 || fwd->n_ops > DH_MAX_OPS || bwd->n_ops < 0 || bwd->n_ops > DH_MAX_OPS)
+    DH_FAIL(DH_ERR_INVALID_ARG, "plan_round_robin: operator count out of range");
+  std::vector<std::vector<int>> of, ob;
+  enum_orders(*fwd, 1, of);
+  enum_orders(*bwd, 1, ob);
+  if (of.empty() || ob.empty()) DH_FAIL(DH_ERR_PLAN_INVALID, "plan_round_robin: an operator graph has a cycle");
+  memset(out, 0, sizeof(*out));
+  out->n_fwd = fwd->n_ops;
+  out->n_bwd = bwd->n_ops;
+  for (int i = 0; i < fwd->n_ops; i++) out->fwd_order[i] = of[0][i];
+  for (int j = 0; j < bwd->n_ops; j++) out->bwd_order[j] = ob[0][j];
+  const int n = std::max(fwd->n_ops, bwd->n_ops);
+  out->n_pairs = n;
+  for (int k = 0; k < n; k++)
+    out->pairs[k] = {std::min(k, fwd->n_ops), std::min(k + 1, fwd->n_ops), std::min(k, bwd->n_ops), std::min(k + 1, bwd->n_ops)};
   return DH_OK;
 }

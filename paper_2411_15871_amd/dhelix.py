@@ -116,6 +116,7 @@ SIGNATURES = {
     "dh_plan_search": (_I, [C.POINTER(dh_op_graph), C.POINTER(dh_op_graph), C.POINTER(dh_overlap_table), _D, _I,
                             C.POINTER(dh_plan), C.POINTER(_D)]),
     "dh_plan_validate": (_I, [C.POINTER(dh_op_graph), C.POINTER(dh_op_graph), C.POINTER(dh_plan)]),
+    "dh_plan_round_robin": (_I, [C.POINTER(dh_op_graph), C.POINTER(dh_op_graph), C.POINTER(dh_plan)]),
     "dh_plan_sequential": (_I, [_P, C.POINTER(dh_plan)]),
     "dh_si_step": (_I, [_P, C.POINTER(dh_fwd_args), C.POINTER(dh_bwd_args), C.POINTER(dh_plan), _P, _Z, _P, _P, _P]),
     "dh_si_graph_create": (_I, [_P, C.POINTER(dh_fwd_args), C.POINTER(dh_bwd_args), C.POINTER(dh_plan), _P, _Z, _P, _P,
@@ -323,6 +324,12 @@ def dh_plan_search(fwd_graph, bwd_graph, table, barrier_cost=0.0, max_orders=0):
 
 def dh_plan_validate(fwd_graph, bwd_graph, plan):
     _check(lib.dh_plan_validate(C.byref(fwd_graph), C.byref(bwd_graph), C.byref(plan)))
+
+
+def dh_plan_round_robin(fwd_graph, bwd_graph):
+    p = dh_plan()
+    _check(lib.dh_plan_round_robin(C.byref(fwd_graph), C.byref(bwd_graph), C.byref(p)))
+    return p
 
 
 def dh_plan_sequential(layer):

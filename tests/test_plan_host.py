@@ -108,5 +108,14 @@ def test_layer_graphs_and_sequential_plan():
         plan, mk = dh.dh_plan_search(gf, gb, tab, 0.0, 8)
         assert abs(mk - max(nf, nb)) < 1e-12
         dh.dh_plan_validate(gf, gb, plan)
+        # the round-robin comparison plan: default orders, one operator of each strand per pair
+        rr = dh.dh_plan_round_robin(gf, gb)
+        dh.dh_plan_validate(gf, gb, rr)
+        fo, bo, pairs = dh.plan_to_py(rr)
+        assert fo == list(range(nf)) and bo == list(range(nb)) and len(pairs) == max(nf, nb)
+        assert pairs[0] == (0, 1, 0, 1) and pairs[-1] == (nf, nf, nb - 1, nb)
+        # weight gradients left in their default places: one order per graph
+        fixed, mk_fixed = dh.dh_plan_search(gf, gb, tab, 0.0, 1)
+        assert dh.plan_to_py(fixed)[1] == list(range(nb)) and mk_fixed >= mk - 1e-12
     finally:
         dh.dh_layer_destroy(L)
