@@ -20,8 +20,9 @@ if ROOT not in sys.path:
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 # HBM bytes per launch of the dominant GEMM from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (scaled by a copy kernel of
-# known size); the summary with the commands is profiles/gemm_gateup_c2_hbm_traffic.txt.  Re-measure when the GEMM changes.
-HBM_TRAFFIC_BYTES = {"c2_llama8b_tp8": (176.2 + 28.6) * 2 ** 20}
+# known size: `bench.py --traffic-probe`); the summary with the commands is profiles/gemm_gateup_c2_hbm_traffic.txt.
+# Re-measure when the GEMM changes.
+HBM_TRAFFIC_BYTES = {"c2_llama8b_tp8": (176.3 + 28.3) * 2 ** 20}
 
 
 def log(*a):
@@ -76,6 +77,7 @@ def main():
     ap.add_argument("--comm-blocks", type=int, default=0, help="thread blocks per collective stand-in (0 = cover payload)")
     ap.add_argument("--profile-reps", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-probe", action="store_true", help="only launch a calibration copy and the dominant GEMM (for rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the SI step is a per-GPU schedule); use --gpus 1")
@@ -83,6 +85,29 @@ def main():
     import torch
     from paper_2411_15871_amd import dhelix as dh
     from paper_2411_15871_amd import harness as H
+
+    if args.traffic_probe:
+        # For `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs: a plain copy of known size (the stand-in kernel with
+        # one partial: reads 256 MiB, writes 256 MiB) calibrates the counters, then the dominant GEMM is launched alone.
+        c = H.CONFIGS[args.workload]
+        T, Hd = c["batch"] * c["seq"], c["hidden"]
+        T = T if c["arch"] != "moe" else 2 * T // c["n_local"]
+        F2 = c["ffn"] if c["arch"] == "gpt" else 2 * c["ffn"]
+        src = torch.empty(128 << 20, dtype=torch.bfloat16, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        a_mat = torch.empty(T, Hd, dtype=torch.bfloat16, device="cuda").normal_()
+        b_mat = torch.empty(Hd, F2, dtype=torch.bfloat16, device="cuda").normal_(0, 0.02)
+        c_mat = torch.empty(T, F2, dtype=torch.bfloat16, device="cuda")
+        wsb = dh.dh_gemm_workspace_bytes(dh.DH_BF16, 0, 0, T, F2, Hd)
+        gws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dh.dh_comm_standin(dh.DH_COMM_ALLREDUCE, [src], dst, src.numel(), dh.DH_BF16)
+        for _ in range(3):
+            dh.dh_gemm(dh.DH_BF16, 0, 0, T, F2, Hd, a_mat, b_mat, c_mat, False, gws, wsb)
+        torch.cuda.synchronize()
+        print("traffic probe: 3 x copy of %d KiB, 3 x GEMM %dx%dx%d" % (src.numel() * 2 // 1024, T, F2, Hd))
+        return
 
     cfg = dict(H.CONFIGS[args.workload])
     cfg["comm_blocks"] = args.comm_blocks
