@@ -68,6 +68,73 @@ def cpu_baseline(cfg, flops):
                       "%.1f s each" % (reps, dt)}
 
 
+def stack_bench(args, torch, dh, H):
+    """L stacked layers (Llama shapes only): a steady-state phase = forward sweep of one micro-batch co-run with the
+    backward sweep of the previous one; reports its rate and the activation arena against two unshared sets."""
+    from paper_2411_15871_amd import inputs as gen
+    c = H.CONFIGS[args.workload]
+    if c["arch"] != "llama":
+        sys.exit("bench.py --layers: only the Llama workloads can be stacked")
+    L, bf = args.layers, c["bf16"]
+    T, Hd = c["batch"] * c["seq"], c["hidden"]
+    n_qkv = (c["nq"] + 2 * c["nkv"]) * c["d"]
+    stack = dh.dh_stack_create(L, arch=dh.DH_ARCH_LLAMA, dtype=dh.DH_BF16 if bf else dh.DH_F32, batch=c["batch"], seq=c["seq"],
+                               hidden=Hd, n_q_heads=c["nq"], n_kv_heads=c["nkv"], head_dim=c["d"], ffn=c["ffn"], eps=1e-5,
+                               rope_base=10000.0, n_ranks=c["n_ranks"], comm_blocks=args.comm_blocks, n_experts=0, n_local_experts=0)
+    keep = []
+    for l in range(L):
+        w_np = gen.llama_weights(Hd, n_qkv, c["nq"] * c["d"], c["ffn"], bf, seed=gen.SEED_WEIGHTS + 100 * l)
+        w = {k: H.to_dev(v, bf) for k, v in w_np.items()}
+        g = {"d" + k: torch.zeros(v.shape, dtype=torch.float32, device="cuda") for k, v in w_np.items()}
+        dh.dh_layer_bind_weights(dh.dh_stack_layer(stack, l), **w)
+        dh.dh_layer_bind_wgrads(dh.dh_stack_layer(stack, l), **g)
+        keep.append((w, g))
+    n_peers = c["n_ranks"] - 1
+    peers = [H.to_dev(gen.peer_partials(300 + 10 * i, n_peers, T, Hd, bf), bf) if n_peers else None for i in range(4)]
+    xs = [H.to_dev(gen.strand_input(m, T, Hd, bf), bf) for m in range(2)]
+    douts = [H.to_dev(gen.strand_upstream_grad(m, T, Hd, bf), bf) for m in range(2)]
+    outs = [torch.empty_like(xs[0]) for _ in range(2)]
+    dxs = [torch.empty_like(xs[0]) for _ in range(2)]
+    arena_bytes, ws_bytes = dh.dh_stack_arena_bytes(stack), dh.dh_stack_workspace_bytes(stack)
+    arena = torch.empty(arena_bytes, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    sa, sb, sc = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    layer0 = dh.dh_stack_layer(stack, 0)
+    gf, gb = dh.dh_layer_op_graph(layer0, 0), dh.dh_layer_op_graph(layer0, 1)
+    plan = dh.make_plan(list(range(gf.n_ops)), list(range(gb.n_ops)), [(0, gf.n_ops, 0, gb.n_ops)])
+    fwd = lambda m: (xs[m], outs[m], peers[0], peers[1])
+    bwd = lambda m: (douts[m], dxs[m], peers[2], peers[3])
+    phase = lambda a, b, p: dh.dh_stack_phase(stack, a, b, p, arena, arena_bytes, ws, ws_bytes, sa, sb, sc)
+    phase(fwd(0), None, None)
+    state = {"m": 1}
+
+    def steady():
+        m = state["m"]
+        phase(fwd(m & 1), bwd((m - 1) & 1), plan)
+        state["m"] = m + 1
+    t_phase = time_steps(steady, args.steps, args.warmup, torch)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    phase(None, bwd((state["m"] - 1) & 1), None)   # cool-down
+    torch.cuda.synchronize()
+    # sequential reference: the same two sweeps one after the other
+    def seq():
+        phase(fwd(0), None, None)
+        phase(None, bwd(0), None)
+    t_seq = time_steps(seq, max(3, args.steps // 3), 2, torch)
+    flops = L * H.model_flops(c)
+    value = flops / t_phase / 1e12
+    out = {"metric": "SI phase over %d stacked layers, fwd sweep || bwd sweep, TFLOP/s per MI355X" % L, "value": value, "unit": "TFLOP/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": t_phase * 1e3, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if bf else "f32", "data": "synthetic",
+           "config": {"workload": args.workload, "layers": L, "tokens_per_strand": T},
+           "pct_bf16_peak": 100.0 * value / BF16_MFMA_PEAK_TFLOPS, "speedup_vs_sequential": t_seq / t_phase,
+           "ms_sequential": t_seq * 1e3, "arena_bytes": arena_bytes, "unshared_bytes": dh.dh_stack_unshared_bytes(stack),
+           "single_strand_bytes": dh.dh_stack_unshared_bytes(stack) // 2}
+    dh.dh_stack_destroy(stack)
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -77,6 +144,7 @@ def main():
     ap.add_argument("--comm-blocks", type=int, default=0, help="thread blocks per collective stand-in (0 = cover payload)")
     ap.add_argument("--profile-reps", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", type=int, default=0, help="stack this many layers: alpha sweeps forward while beta sweeps backward")
     ap.add_argument("--traffic-probe", action="store_true", help="only launch a calibration copy and the dominant GEMM (for rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -108,6 +176,9 @@ def main():
         torch.cuda.synchronize()
         print("traffic probe: 3 x copy of %d KiB, 3 x GEMM %dx%dx%d" % (src.numel() * 2 // 1024, T, F2, Hd))
         return
+
+    if args.layers > 0:
+        return stack_bench(args, torch, dh, H)
 
     cfg = dict(H.CONFIGS[args.workload])
     cfg["comm_blocks"] = args.comm_blocks

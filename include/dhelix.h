@@ -291,6 +291,42 @@ int dh_si_step(dh_layer* layer, const dh_fwd_args* alpha, const dh_bwd_args* bet
                const dh_plan* plan, void* ws, size_t ws_bytes, void* stream_alpha,
                void* stream_beta, void* stream_comm);
 
+/* One SI step across two layers of identical shape: forward of strand alpha through layer_alpha while
+ * strand beta runs backward through layer_beta (each layer has its own weights and gradient buffers).
+ * dh_si_step is the case layer_alpha == layer_beta. */
+int dh_si_step_layers(dh_layer* layer_alpha, dh_layer* layer_beta, const dh_fwd_args* alpha,
+                      const dh_bwd_args* beta, const dh_plan* plan, void* ws, size_t ws_bytes,
+                      void* stream_alpha, void* stream_beta, void* stream_comm);
+
+/* ------------------------------------------------------------------------------------------
+ * A stack of L layers of one shape under SI on one GPU: the single-stage case of the folded
+ * pipeline of Sec. 4.1.  In a phase, strand alpha (a new micro-batch) sweeps forward through layers
+ * 0..L-1 while strand beta (the micro-batch of the previous phase) sweeps backward through L-1..0;
+ * step k is one SI step of alpha's layer k with beta's layer L-1-k.  Activations live in a caller-owned
+ * arena shared by both strands in the two-triangle arrangement of Sec. 3.3: L+1 saved-activation slots
+ * and L layer-input buffers (dh_stack_arena_bytes) instead of two full sets (dh_stack_unshared_bytes).
+ * DH_ARCH_LLAMA only.  Host-side objects; every operator runs through the layer calls above.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct dh_stack dh_stack;
+/* x: device [T,H] input of layer 0, must stay valid until this micro-batch's backward phase has run;
+ * out: device [T,H] output of layer L-1; peers as in dh_fwd_args, the same buffers for every layer. */
+typedef struct { const void* x; void* out; const void* peers_ar1; const void* peers_ar2; } dh_stack_fwd;
+/* dout: device [T,H] gradient of the last layer's output; dx: device [T,H] gradient of layer 0's input. */
+typedef struct { const void* dout; void* dx; const void* peers_ar3; const void* peers_ar4; } dh_stack_bwd;
+int dh_stack_create(const dh_layer_config* cfg, int n_layers, dh_stack** out);
+void dh_stack_destroy(dh_stack* stack);
+/* Layer i of the stack (owned by the stack), to bind its weights and gradient buffers. */
+dh_layer* dh_stack_layer(dh_stack* stack, int i);
+size_t dh_stack_arena_bytes(const dh_stack* stack);
+size_t dh_stack_unshared_bytes(const dh_stack* stack);
+size_t dh_stack_workspace_bytes(const dh_stack* stack);
+/* One phase.  alpha != NULL, beta == NULL: warm-up (forward sweep only); both: L SI steps with `plan`;
+ * alpha == NULL: cool-down (backward sweep of the last micro-batch).  beta always refers to the
+ * micro-batch that was alpha in the previous phase.  Enqueues on the given streams and returns. */
+int dh_stack_phase(dh_stack* stack, const dh_stack_fwd* alpha, const dh_stack_bwd* beta,
+                   const dh_plan* plan, void* arena, size_t arena_bytes, void* ws, size_t ws_bytes,
+                   void* stream_alpha, void* stream_beta, void* stream_comm);
+
 /* The same step recorded once into a HIP graph (stream capture on stream_alpha, which forks into
  * stream_beta; nothing runs) and replayed with one launch per step, which removes the per-operator
  * launch intervals (Sec. 6.4 names them as the remaining loss).  The two streams must be distinct and

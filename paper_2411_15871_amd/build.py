@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdhelix.so")
 SOURCES = ["api.cpp", "plan.cpp", "rowops.hip", "standin.hip", "gemm_f32.hip", "gemm_bf16.hip", "attn_f32.hip",
-           "attn_bf16.hip", "moe.hip", "layer.hip"]
+           "attn_bf16.hip", "moe.hip", "layer.hip", "stack.cpp"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
          "-Wno-unknown-warning-option", "-Wno-inline-asm"]

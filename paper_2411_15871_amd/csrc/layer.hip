@@ -749,8 +749,8 @@ static int check_si_args(dh_layer* L, const dh_fwd_args* alpha, const dh_bwd_arg
 // Enqueues one SI step.  Stream beta (and the communication stream, through the events around each stand-in)
 // forks from stream alpha at the start and is joined back into it at the end, so the whole step is one
 // fork/join region of stream alpha -- which is also what stream capture requires.
-static int enqueue_si(dh_layer* L, const dh_fwd_args* alpha, const dh_bwd_args* beta, const dh_plan* plan, void* ws,
-                      hipStream_t sa, hipStream_t sb, hipStream_t sc) {
+static int enqueue_si(dh_layer* L, dh_layer* LB, const dh_fwd_args* alpha, const dh_bwd_args* beta, const dh_plan* plan, void* ws,
+                      hipStream_t sa, hipStream_t sb, hipStream_t sc) {  // L: alpha's layer (also the event pool), LB: beta's
   int rc;
   char* ws_f = (char*)ws;
   char* ws_b = (char*)ws + L->fwd_bytes;
@@ -773,8 +773,8 @@ static int enqueue_si(dh_layer* L, const dh_fwd_args* alpha, const dh_bwd_args* 
       }
       if (bj < p.b_end) {
         const int op = plan->bwd_order[bj++];
-        if (L->gb.is_comm[op]) rc = on_comm_stream(L, sb, sc, [&](hipStream_t s) { return run_bwd_op(L, op, *beta, ws_b, s); });
-        else rc = run_bwd_op(L, op, *beta, ws_b, sb);
+        if (L->gb.is_comm[op]) rc = on_comm_stream(L, sb, sc, [&](hipStream_t s) { return run_bwd_op(LB, op, *beta, ws_b, s); });
+        else rc = run_bwd_op(LB, op, *beta, ws_b, sb);
         if (rc) return rc;
       }
     }
@@ -796,7 +796,30 @@ extern "C" int dh_si_step(dh_layer* L, const dh_fwd_args* alpha, const dh_bwd_ar
   if (rc) return rc;
   if (L->T == 0) return DH_OK;
   if ((rc = ensure_events(L))) return rc;
-  return enqueue_si(L, alpha, beta, plan, ws, (hipStream_t)stream_alpha, (hipStream_t)stream_beta, (hipStream_t)stream_comm);
+  return enqueue_si(L, L, alpha, beta, plan, ws, (hipStream_t)stream_alpha, (hipStream_t)stream_beta, (hipStream_t)stream_comm);
+}
+
+static bool same_shape(const dh_layer_config& a, const dh_layer_config& b) {
+  return a.arch == b.arch && a.dtype == b.dtype && a.batch == b.batch && a.seq == b.seq && a.hidden == b.hidden &&
+         a.n_q_heads == b.n_q_heads && a.n_kv_heads == b.n_kv_heads && a.head_dim == b.head_dim && a.ffn == b.ffn &&
+         a.n_ranks == b.n_ranks && a.n_experts == b.n_experts && a.n_local_experts == b.n_local_experts;
+}
+
+extern "C" int dh_si_step_layers(dh_layer* layer_alpha, dh_layer* layer_beta, const dh_fwd_args* alpha, const dh_bwd_args* beta,
+                                 const dh_plan* plan, void* ws, size_t ws_bytes, void* stream_alpha, void* stream_beta,
+                                 void* stream_comm) {
+  if (!layer_alpha || !layer_beta) DH_FAIL(DH_ERR_INVALID_ARG, "si_step_layers: null layer");
+  if (!same_shape(layer_alpha->c, layer_beta->c)) DH_FAIL(DH_ERR_SHAPE, "si_step_layers: the two layers differ in shape");
+  int rc = check_fwd_args(layer_alpha, alpha);
+  if (rc) return rc;
+  if ((rc = check_bwd_args(layer_beta, beta))) return rc;
+  if (!plan) DH_FAIL(DH_ERR_INVALID_ARG, "si_step_layers: plan is null");
+  if ((rc = dh_plan_validate(&layer_alpha->gf, &layer_beta->gb, plan))) return rc;
+  if ((rc = check_ws(layer_alpha, DH_WS_SI, ws, ws_bytes))) return rc;
+  if (layer_alpha->T == 0) return DH_OK;
+  if ((rc = ensure_events(layer_alpha))) return rc;
+  return enqueue_si(layer_alpha, layer_beta, alpha, beta, plan, ws, (hipStream_t)stream_alpha, (hipStream_t)stream_beta,
+                    (hipStream_t)stream_comm);
 }
 
 // ------------------------------------------------------------------------------------ captured SI step
@@ -820,7 +843,7 @@ extern "C" int dh_si_graph_create(dh_layer* L, const dh_fwd_args* alpha, const d
   // consumes the result), so a stand-in is recorded as a node of its strand's chain; a separate communication
   // stream would add nothing but an order among the two strands' collectives.
   DH_HIP(hipStreamBeginCapture(sa, hipStreamCaptureModeThreadLocal));
-  rc = enqueue_si(L, alpha, beta, plan, ws, sa, sb, nullptr);
+  rc = enqueue_si(L, L, alpha, beta, plan, ws, sa, sb, nullptr);
   hipGraph_t graph = nullptr;
   hipError_t e = hipStreamEndCapture(sa, &graph);  // always end the capture, also after a failed enqueue
   if (rc != DH_OK) {

@@ -89,6 +89,14 @@ class dh_moe_tables(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in MOE_TABLES]
 
 
+class dh_stack_fwd(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("x", "out", "peers_ar1", "peers_ar2")]
+
+
+class dh_stack_bwd(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("dout", "dx", "peers_ar3", "peers_ar4")]
+
+
 class dh_plan(C.Structure):
     _fields_ = [("n_fwd", C.c_int), ("n_bwd", C.c_int), ("n_pairs", C.c_int), ("fwd_order", C.c_int * DH_MAX_OPS),
                 ("bwd_order", C.c_int * DH_MAX_OPS), ("pairs", dh_seg_pair * (2 * DH_MAX_OPS))]
@@ -119,6 +127,14 @@ SIGNATURES = {
     "dh_plan_round_robin": (_I, [C.POINTER(dh_op_graph), C.POINTER(dh_op_graph), C.POINTER(dh_plan)]),
     "dh_plan_sequential": (_I, [_P, C.POINTER(dh_plan)]),
     "dh_si_step": (_I, [_P, C.POINTER(dh_fwd_args), C.POINTER(dh_bwd_args), C.POINTER(dh_plan), _P, _Z, _P, _P, _P]),
+    "dh_si_step_layers": (_I, [_P, _P, C.POINTER(dh_fwd_args), C.POINTER(dh_bwd_args), C.POINTER(dh_plan), _P, _Z, _P, _P, _P]),
+    "dh_stack_create": (_I, [C.POINTER(dh_layer_config), _I, C.POINTER(_P)]),
+    "dh_stack_destroy": (None, [_P]),
+    "dh_stack_layer": (_P, [_P, _I]),
+    "dh_stack_arena_bytes": (_Z, [_P]),
+    "dh_stack_unshared_bytes": (_Z, [_P]),
+    "dh_stack_workspace_bytes": (_Z, [_P]),
+    "dh_stack_phase": (_I, [_P, C.POINTER(dh_stack_fwd), C.POINTER(dh_stack_bwd), C.POINTER(dh_plan), _P, _Z, _P, _Z, _P, _P, _P]),
     "dh_si_graph_create": (_I, [_P, C.POINTER(dh_fwd_args), C.POINTER(dh_bwd_args), C.POINTER(dh_plan), _P, _Z, _P, _P,
                                 C.POINTER(_P)]),
     "dh_si_graph_launch": (_I, [_P, _P]),
@@ -348,6 +364,48 @@ def dh_profile_pairs(layer, alpha, beta, ws, ws_bytes, stream_alpha, stream_beta
 def dh_si_step(layer, alpha, beta, plan, ws, ws_bytes, stream_alpha, stream_beta, stream_comm=None):
     _check(lib.dh_si_step(layer, C.byref(alpha), C.byref(beta), C.byref(plan), _ptr(ws), ws_bytes,
                           _stream(stream_alpha), _stream(stream_beta), _stream(stream_comm)))
+
+
+def dh_si_step_layers(layer_alpha, layer_beta, alpha, beta, plan, ws, ws_bytes, stream_alpha, stream_beta, stream_comm=None):
+    _check(lib.dh_si_step_layers(layer_alpha, layer_beta, C.byref(alpha), C.byref(beta), C.byref(plan), _ptr(ws), ws_bytes,
+                                 _stream(stream_alpha), _stream(stream_beta), _stream(stream_comm)))
+
+
+def dh_stack_create(n_layers, **cfg):
+    c = dh_layer_config(**cfg)
+    h = _P()
+    _check(lib.dh_stack_create(C.byref(c), n_layers, C.byref(h)))
+    return h
+
+
+def dh_stack_destroy(stack):
+    lib.dh_stack_destroy(stack)
+
+
+def dh_stack_layer(stack, i):
+    return _P(lib.dh_stack_layer(stack, i))
+
+
+def dh_stack_arena_bytes(stack):
+    return lib.dh_stack_arena_bytes(stack)
+
+
+def dh_stack_unshared_bytes(stack):
+    return lib.dh_stack_unshared_bytes(stack)
+
+
+def dh_stack_workspace_bytes(stack):
+    return lib.dh_stack_workspace_bytes(stack)
+
+
+def dh_stack_phase(stack, alpha, beta, plan, arena, arena_bytes, ws, ws_bytes, stream_alpha=None, stream_beta=None,
+                   stream_comm=None):
+    """alpha: (x, out, peers_ar1, peers_ar2) or None; beta: (dout, dx, peers_ar3, peers_ar4) or None."""
+    a = dh_stack_fwd(*[_ptr(t) for t in alpha]) if alpha is not None else None
+    b = dh_stack_bwd(*[_ptr(t) for t in beta]) if beta is not None else None
+    _check(lib.dh_stack_phase(stack, C.byref(a) if a is not None else None, C.byref(b) if b is not None else None,
+                              C.byref(plan) if plan is not None else None, _ptr(arena), arena_bytes, _ptr(ws), ws_bytes,
+                              _stream(stream_alpha), _stream(stream_beta), _stream(stream_comm)))
 
 
 def dh_si_graph_create(layer, alpha, beta, plan, ws, ws_bytes, stream_alpha, stream_beta):
