@@ -197,6 +197,63 @@ __device__ __forceinline__ bf16x8 pack_rows(const f32x16& t, int c) {
 }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Score tiles of a 64-token LDS tile: acc[mt] = sum over k of T[rows 32 mt .. 32 mt + 31][k] * b[k] (direct fragments
+// of the tile behind P against the D-long register fragments b).  A matrix instruction that accumulates into the
+// result of the one just before it has to wait for that result, so the products of the independent tiles are
+// issued round robin: score_tiles interleaves its two tiles, score_tiles2 the four tiles of two operand pairs
+// (the backward kernels' S and dP).  The LDS fragments of step k+1 are requested before the products of step k
+// are issued, and the matrix and LDS instructions are pinned in that order (vector-ALU work of the caller may
+// still move across), so no product waits for an LDS read issued just before it.
+#define SCHED_PIN_MFMA_DS() __builtin_amdgcn_sched_barrier(0x1 | 0x2 | 0x4 | 0x400)  // ALU, VALU, SALU, TRANS may cross
+template <int D>
+__device__ __forceinline__ void score_tiles(f32x16 (&acc)[2], const TilePtrs<D>& P, const bf16x8 (&b)[D / 16]) {
+  using TL = ATile<D>;
+  constexpr int KS = D / 16;
+  const f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  bf16x8 fr[2][4];  // two k-steps (two fragments each) per chunk
+  auto fetch = [&](int c) {
+#pragma unroll
+    for (int i = 0; i < 4; i++) fr[c & 1][i] = lds_frag(P.dir[2 * c + (i >> 1)], (i & 1) * 32 * TL::LD * 2);
+  };
+  fetch(0);
+#pragma unroll
+  for (int c = 0; c < KS / 2; c++) {
+    if (c + 1 < KS / 2) fetch(c + 1);
+    SCHED_PIN_MFMA_DS();
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      const int ks = 2 * c + (i >> 1), mt = i & 1;
+      acc[mt] = MFMA(fr[c & 1][i], b[ks], ks == 0 ? z : acc[mt]);
+    }
+    SCHED_PIN_MFMA_DS();
+  }
+}
+template <int D>
+__device__ __forceinline__ void score_tiles2(f32x16 (&acc0)[2], const TilePtrs<D>& P0, const bf16x8 (&b0)[D / 16],
+                                             f32x16 (&acc1)[2], const TilePtrs<D>& P1, const bf16x8 (&b1)[D / 16]) {
+  using TL = ATile<D>;
+  constexpr int KS = D / 16;
+  const f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  bf16x8 fr[2][4];  // one k-step of both operand pairs per chunk
+  auto fetch = [&](int ks) {
+    fr[ks & 1][0] = lds_frag(P0.dir[ks], 0);
+    fr[ks & 1][1] = lds_frag(P0.dir[ks], 32 * TL::LD * 2);
+    fr[ks & 1][2] = lds_frag(P1.dir[ks], 0);
+    fr[ks & 1][3] = lds_frag(P1.dir[ks], 32 * TL::LD * 2);
+  };
+  fetch(0);
+#pragma unroll
+  for (int ks = 0; ks < KS; ks++) {
+    if (ks + 1 < KS) fetch(ks + 1);
+    SCHED_PIN_MFMA_DS();
+    acc0[0] = MFMA(fr[ks & 1][0], b0[ks], ks == 0 ? z : acc0[0]);
+    acc0[1] = MFMA(fr[ks & 1][1], b0[ks], ks == 0 ? z : acc0[1]);
+    acc1[0] = MFMA(fr[ks & 1][2], b1[ks], ks == 0 ? z : acc1[0]);
+    acc1[1] = MFMA(fr[ks & 1][3], b1[ks], ks == 0 ? z : acc1[1]);
+    SCHED_PIN_MFMA_DS();
+  }
+}
+
 // acc[dt] += T[64 x D]^T (transposed fragments of the LDS tile behind P) * src, src = a 64 x 32 score tile held as
 // two 32x32 register tiles.  The 64 "k" rows go in four groups of 16 (g = 2*mt + c); the transposed fragments
 // of group g+1 are fetched before the products of group g are issued, so no product waits for its own LDS
@@ -333,13 +390,7 @@ __global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(int seq, i
     Kp.set(sm + slot * TL::BYTES, fa);
     Vp.set(sm + (AF_RING + slot) * TL::BYTES, fa);
     f32x16 st[2];
-#pragma unroll
-    for (int mt = 0; mt < 2; mt++) {
-#pragma unroll
-      for (int r = 0; r < 16; r++) st[mt][r] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < D / 16; ks++) st[mt] = MFMA(lds_frag(Kp.dir[ks], mt * 32 * TL::LD * 2), qf[ks], st[mt]);
-    }
+    score_tiles<D>(st, Kp, qf);
     if (kb + AB_KT - 1 > iw) {  // the tile crosses the diagonal for this wave: mask keys above the row
 #pragma unroll
       for (int mt = 0; mt < 2; mt++)
@@ -554,17 +605,7 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(int seq, i
     Kp.set(sm + slot * TL::BYTES, fa);
     Vp.set(sm + (AB_RING + slot) * TL::BYTES, fa);
     f32x16 st[2], dp[2];
-#pragma unroll
-    for (int mt = 0; mt < 2; mt++) {
-#pragma unroll
-      for (int r = 0; r < 16; r++) { st[mt][r] = 0.f; dp[mt][r] = 0.f; }
-#pragma unroll
-      for (int ks = 0; ks < D / 16; ks++) st[mt] = MFMA(lds_frag(Kp.dir[ks], mt * 32 * TL::LD * 2), qf[ks], st[mt]);
-    }
-#pragma unroll
-    for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-      for (int ks = 0; ks < D / 16; ks++) dp[mt] = MFMA(lds_frag(Vp.dir[ks], mt * 32 * TL::LD * 2), dof[ks], dp[mt]);
+    score_tiles2<D>(st, Kp, qf, dp, Vp, dof);
     // P^T from S^T while the dP^T products are still in the matrix pipeline
 #pragma unroll
     for (int mt = 0; mt < 2; mt++)
@@ -718,17 +759,7 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, 
     const float* ls = lse_s + slot * AB_KT;
     const float* ds = del_s + slot * AB_KT;
     f32x16 st[2], dp[2];
-#pragma unroll
-    for (int mt = 0; mt < 2; mt++) {
-#pragma unroll
-      for (int r = 0; r < 16; r++) { st[mt][r] = 0.f; dp[mt][r] = 0.f; }
-#pragma unroll
-      for (int ks = 0; ks < D / 16; ks++) st[mt] = MFMA(lds_frag(Qp.dir[ks], mt * 32 * TL::LD * 2), kf[ks], st[mt]);
-    }
-#pragma unroll
-    for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-      for (int ks = 0; ks < D / 16; ks++) dp[mt] = MFMA(lds_frag(Op.dir[ks], mt * 32 * TL::LD * 2), vf[ks], dp[mt]);
+    score_tiles2<D>(st, Qp, kf, dp, Op, vf);
     // P from S (rows 8*q4 + 4*kg + e of each 32-row half) while dP is in the matrix pipeline
 #pragma unroll
     for (int mt = 0; mt < 2; mt++)

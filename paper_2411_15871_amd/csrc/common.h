@@ -54,6 +54,16 @@ template <> struct Vec8<float> {
     q[0] = make_float4(v[0], v[1], v[2], v[3]);
     q[1] = make_float4(v[4], v[5], v[6], v[7]);
   }
+  __device__ __forceinline__ void load_stream(const float* p) {
+    const f32x4 a = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+    const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p) + 1);
+    v[0] = a[0]; v[1] = a[1]; v[2] = a[2]; v[3] = a[3]; v[4] = b[0]; v[5] = b[1]; v[6] = b[2]; v[7] = b[3];
+  }
+  __device__ __forceinline__ void store_stream(float* p) const {
+    const f32x4 a = {v[0], v[1], v[2], v[3]}, b = {v[4], v[5], v[6], v[7]};
+    __builtin_nontemporal_store(a, reinterpret_cast<f32x4*>(p));
+    __builtin_nontemporal_store(b, reinterpret_cast<f32x4*>(p) + 1);
+  }
 };
 template <> struct Vec8<bf16_t> {
   float v[8];
@@ -67,6 +77,19 @@ template <> struct Vec8<bf16_t> {
 #pragma unroll
     for (int i = 0; i < 8; i++) t[i] = (bf16_t)v[i];
     *reinterpret_cast<bf16x8*>(p) = t;
+  }
+  // Streaming forms for data that is touched once (collective payloads): non-temporal accesses, so that the
+  // lines do not displace the operand panels a co-running GEMM keeps in L2.
+  __device__ __forceinline__ void load_stream(const bf16_t* p) {
+    bf16x8 t = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(p));
+#pragma unroll
+    for (int i = 0; i < 8; i++) v[i] = (float)t[i];
+  }
+  __device__ __forceinline__ void store_stream(bf16_t* p) const {
+    bf16x8 t;
+#pragma unroll
+    for (int i = 0; i < 8; i++) t[i] = (bf16_t)v[i];
+    __builtin_nontemporal_store(t, reinterpret_cast<bf16x8*>(p));
   }
 };
 

@@ -15,14 +15,14 @@ __global__ __launch_bounds__(256) void allreduce_kernel(PartPtrs parts, int n_ra
   size_t stride = (size_t)gridDim.x * blockDim.x;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += stride) {
     Vec8<T> acc;
-    acc.load((const T*)parts.p[0] + i * 8);
+    acc.load_stream((const T*)parts.p[0] + i * 8);
     for (int r = 1; r < n_ranks; r++) {
       Vec8<T> v;
-      v.load((const T*)parts.p[r] + i * 8);
+      v.load_stream((const T*)parts.p[r] + i * 8);
 #pragma unroll
       for (int k = 0; k < 8; k++) acc.v[k] += v.v[k];
     }
-    acc.store(out + i * 8);
+    acc.store_stream(out + i * 8);
   }
 }
 
