@@ -83,15 +83,16 @@ def layernorm_bwd(dy, x, gamma, mu, rstd):
 
 
 # --------------------------------------------------------------------------- RoPE
-def rope(t, seq, base, inverse=False):
+def rope(t, seq, base, inverse=False, pos0=0):
     """Rotate head vectors t[T, nh, d] (T = batch*seq, sequence-major) by position*theta.
 
     Pair (i, i+d/2) at position p turns by angle p*base**(-2i/d); inverse=True turns by the
     negative angle, which is the backward of the forward rotation (a rotation's transpose).
+    pos0: position of each sequence's first row (a context-parallel rank holds a later chunk).
     """
     T, nh, d = t.shape
     half = d // 2
-    pos = (np.arange(T) % seq).astype(np.float64)
+    pos = (pos0 + np.arange(T) % seq).astype(np.float64)
     theta = base ** (-2.0 * np.arange(half, dtype=np.float64) / d)
     ang = pos[:, None] * theta[None, :]
     c = np.cos(ang)[:, None, :]
@@ -502,3 +503,158 @@ def moe_layer_bwd(cfg, W, saved, dout, n_local):
     dx = dx2 + dxn
     grads = dict(dWqkv=dWqkv, dWo=dWo, dWgu=dWgu, dWd=dWd, dg1=dg1, dg2=dg2, dlogits=dlogits)
     return dx, grads
+
+
+# --------------------------------------------------------------------------- context parallelism (Sec. 2.1 "Intra-layer
+# parallelism", Sec. 2.2: key/value chunks of the other ranks arrive by Send/Recv, ring-attention style)
+def attention_ctx_fwd(q, k, v, batch, s_l, q_off):
+    """Attention of a context-parallel rank: its s_l queries per sequence sit at positions q_off..q_off+s_l-1 and
+    read the keys/values of positions 0..q_off+s_l-1 (the earlier ranks' chunks followed by its own), causally.
+    q[batch*s_l,nq,d], k,v[batch*S,nkv,d] with S = q_off+s_l -> o[batch*s_l,nq,d], lse[nq,batch*s_l]."""
+    Tq, nq, d = q.shape
+    nkv = k.shape[1]
+    g = nq // nkv
+    S_all = q_off + s_l
+    scale = 1.0 / np.sqrt(d)
+    o = np.zeros_like(q)
+    lse = np.zeros((nq, Tq))
+    future = np.arange(S_all)[None, :] > (q_off + np.arange(s_l))[:, None]
+    for b in range(batch):
+        ql = slice(b * s_l, (b + 1) * s_l)
+        kl = slice(b * S_all, (b + 1) * S_all)
+        for h in range(nq):
+            S = (q[ql, h, :] @ k[kl, h // g, :].T) * scale
+            S[future] = -np.inf
+            m = np.max(S, axis=1, keepdims=True)
+            E = np.exp(S - m)
+            Z = np.sum(E, axis=1, keepdims=True)
+            o[ql, h, :] = (E / Z) @ v[kl, h // g, :]
+            lse[h, ql] = (m + np.log(Z))[:, 0]
+    return o, lse
+
+
+def attention_ctx_bwd(do, q, k, v, batch, s_l, q_off):
+    """Chain rule of attention_ctx_fwd: dq for the rank's own queries, dk/dv for every key row it read
+    (rows of earlier chunks are what the rank sends back to their owners)."""
+    Tq, nq, d = q.shape
+    nkv = k.shape[1]
+    g = nq // nkv
+    S_all = q_off + s_l
+    scale = 1.0 / np.sqrt(d)
+    dq = np.zeros_like(q)
+    dk = np.zeros_like(k)
+    dv = np.zeros_like(v)
+    future = np.arange(S_all)[None, :] > (q_off + np.arange(s_l))[:, None]
+    for b in range(batch):
+        ql = slice(b * s_l, (b + 1) * s_l)
+        kl = slice(b * S_all, (b + 1) * S_all)
+        for h in range(nq):
+            hk = h // g
+            S = (q[ql, h, :] @ k[kl, hk, :].T) * scale
+            S[future] = -np.inf
+            E = np.exp(S - np.max(S, axis=1, keepdims=True))
+            P = E / np.sum(E, axis=1, keepdims=True)
+            dO = do[ql, h, :]
+            dv[kl, hk, :] += P.T @ dO
+            dP = dO @ v[kl, hk, :].T
+            dS = P * (dP - np.sum(dP * P, axis=1, keepdims=True))
+            dq[ql, h, :] = (dS @ k[kl, hk, :]) * scale
+            dk[kl, hk, :] += (dS.T @ q[ql, h, :]) * scale
+    return dq, dk, dv
+
+
+def cp_gather_kv(k, v, peer_kv, batch, s_l, cp_rank):
+    """Key/value rows a rank attends to, per sequence: chunks 0..cp_rank-1 from the peers, then its own.
+    k,v[batch*s_l,nkv,d]; peer_kv[CP-1, batch*s_l, 2*nkv*d] holds the other ranks' chunks ([k heads | v heads], keys
+    already rotated), ordered by source rank with this rank left out.  Chunks of later ranks arrive too (the ring
+    passes every chunk through every rank) but no causal query reads them."""
+    nkv, d = k.shape[1], k.shape[2]
+    S_all = (cp_rank + 1) * s_l
+    K = np.zeros((batch * S_all, nkv, d))
+    V = np.zeros((batch * S_all, nkv, d))
+    for b in range(batch):
+        for c in range(cp_rank):
+            rows = slice(b * S_all + c * s_l, b * S_all + (c + 1) * s_l)
+            chunk = peer_kv[c][b * s_l:(b + 1) * s_l].astype(np.float64)
+            K[rows] = chunk[:, : nkv * d].reshape(s_l, nkv, d)
+            V[rows] = chunk[:, nkv * d:].reshape(s_l, nkv, d)
+        own = slice(b * S_all + cp_rank * s_l, (b + 1) * S_all)
+        K[own] = k[b * s_l:(b + 1) * s_l]
+        V[own] = v[b * s_l:(b + 1) * s_l]
+    return K, V
+
+
+def llama_cp_fwd(cfg, W, x, cp_rank, peers=None):
+    """llama_fwd for context-parallel rank cp_rank: cfg.seq is the rank's chunk length, its rows sit at positions
+    cp_rank*seq.. of each sequence.  peers: 'ar1','ar2' as llama_fwd, 'kv' -> [CP-1, T, 2*nkv*d] (see cp_gather_kv)."""
+    peers = peers or {}
+    T, nq, nkv, d, F = cfg.T, cfg.nq, cfg.nkv, cfg.d, cfg.F
+    q_off = cp_rank * cfg.seq
+    h1, r1 = rmsnorm_fwd(x, W["g1"], cfg.eps)
+    qkv = h1 @ W["Wqkv"]
+    q = rope(qkv[:, : nq * d].reshape(T, nq, d), cfg.seq, cfg.rope_base, pos0=q_off)
+    k = rope(qkv[:, nq * d: (nq + nkv) * d].reshape(T, nkv, d), cfg.seq, cfg.rope_base, pos0=q_off)
+    v = qkv[:, (nq + nkv) * d:].reshape(T, nkv, d)
+    K, V = cp_gather_kv(k, v, peers.get("kv"), cfg.batch, cfg.seq, cp_rank)
+    o, lse = attention_ctx_fwd(q, K, V, cfg.batch, cfg.seq, q_off)
+    o2 = o.reshape(T, nq * d)
+    y = standin_sum(o2 @ W["Wo"], peers.get("ar1"))
+    x2 = x + y
+    h2, r2 = rmsnorm_fwd(x2, W["g2"], cfg.eps)
+    gu = h2 @ W["Wgu"]
+    g, u = gu[:, :F], gu[:, F:]
+    a = swiglu_fwd(g, u)
+    z = standin_sum(a @ W["Wd"], peers.get("ar2"))
+    out = x2 + z
+    saved = dict(x=x, r1=r1, h1=h1, q=q, k=k, v=v, K=K, V=V, o=o2, lse=lse, x2=x2, r2=r2, h2=h2, g=g, u=u, a=a)
+    return out, saved
+
+
+def llama_cp_bwd(cfg, W, saved, dout, cp_rank, peers=None):
+    """Backward of llama_cp_fwd.  peers: 'ar3','ar4' as llama_bwd; 'dkv' -> [CP-1, T, 2*nkv*d], the other ranks'
+    gradient contributions to this rank's own keys/values (same order as 'kv'); only later ranks read this rank's
+    keys, so the chunks of ranks > cp_rank are added (index order, after the rank's own contribution).
+    Returns (dx, grads, inter); inter['dkv_peers'][c] = [T, 2*nkv*d] is the gradient this rank sends to rank c < cp_rank."""
+    peers = peers or {}
+    T, nq, nkv, d, F = cfg.T, cfg.nq, cfg.nkv, cfg.d, cfg.F
+    s_l, q_off = cfg.seq, cp_rank * cfg.seq
+    S_all = q_off + s_l
+    s = saved
+    da = dout @ W["Wd"].T
+    dWd = s["a"].T @ dout
+    dg, du = swiglu_bwd(da, s["g"], s["u"])
+    dgu = np.concatenate([dg, du], axis=1)
+    dWgu = s["h2"].T @ dgu
+    dh2 = standin_sum(dgu @ W["Wgu"].T, peers.get("ar3"))
+    dx2n, dg2 = rmsnorm_bwd(dh2, s["x2"], W["g2"], s["r2"])
+    dx2 = dout + dx2n
+    do = dx2 @ W["Wo"].T
+    dWo = s["o"].T @ dx2
+    dq, dK, dV = attention_ctx_bwd(do.reshape(T, nq, d), s["q"], s["K"], s["V"], cfg.batch, s_l, q_off)
+    dk = np.zeros((T, nkv, d))
+    dv = np.zeros((T, nkv, d))
+    dkv_peers = np.zeros((cp_rank, T, 2 * nkv * d))
+    for b in range(cfg.batch):
+        own = slice(b * S_all + q_off, (b + 1) * S_all)
+        dk[b * s_l:(b + 1) * s_l] = dK[own]
+        dv[b * s_l:(b + 1) * s_l] = dV[own]
+        for c in range(cp_rank):
+            rows = slice(b * S_all + c * s_l, b * S_all + (c + 1) * s_l)
+            dkv_peers[c, b * s_l:(b + 1) * s_l, : nkv * d] = dK[rows].reshape(s_l, nkv * d)
+            dkv_peers[c, b * s_l:(b + 1) * s_l, nkv * d:] = dV[rows].reshape(s_l, nkv * d)
+    dkv_own = np.concatenate([dk.reshape(T, -1), dv.reshape(T, -1)], axis=1)
+    if peers.get("dkv") is not None:
+        for c in range(cp_rank, len(peers["dkv"])):  # entries cp_rank.. are the ranks after this one
+            dkv_own = dkv_own + peers["dkv"][c].astype(np.float64)
+    dk = dkv_own[:, : nkv * d].reshape(T, nkv, d)
+    dv = dkv_own[:, nkv * d:]
+    dq = rope(dq, s_l, cfg.rope_base, inverse=True, pos0=q_off)
+    dk = rope(dk, s_l, cfg.rope_base, inverse=True, pos0=q_off)
+    dqkv = np.concatenate([dq.reshape(T, -1), dk.reshape(T, -1), dv], axis=1)
+    dWqkv = s["h1"].T @ dqkv
+    dh1 = standin_sum(dqkv @ W["Wqkv"].T, peers.get("ar4"))
+    dxn, dg1 = rmsnorm_bwd(dh1, s["x"], W["g1"], s["r1"])
+    dx = dx2 + dxn
+    grads = dict(dWqkv=dWqkv, dWo=dWo, dWgu=dWgu, dWd=dWd, dg1=dg1, dg2=dg2)
+    inter = dict(da=da, dgu=dgu, dh2=dh2, dx2=dx2, do=do, dqkv=dqkv, dh1=dh1, dkv_peers=dkv_peers, dkv_own=dkv_own)
+    return dx, grads, inter
