@@ -395,6 +395,10 @@ size_t dh_rmsnorm_bwd_ws_bytes(int T, int H);
  * p * base^(-2i/d); inverse != 0 turns back (the backward of the rotation). */
 int dh_rope(int dtype, int T, int seq, int n_heads, int head_dim, int row_stride, float base,
             int inverse, void* t, void* stream);
+/* The same with position p = pos0 + row % seq: the rows of a context-parallel rank (Sec. 2.1, "Intra-layer
+ * parallelism") are a later chunk of each sequence. */
+int dh_rope_at(int dtype, int T, int seq, int pos0, int n_heads, int head_dim, int row_stride, float base,
+               int inverse, void* t, void* stream);
 
 /* SwiGLU: gu[T,2F] = [gate | up]; a[T,F] = gate*sigmoid(gate)*up; backward writes dgu[T,2F]. */
 int dh_swiglu_fwd(int dtype, int T, int F, const void* gu, void* a, void* stream);
@@ -418,6 +422,23 @@ int dh_attn_bwd(int dtype, int batch, int seq, int nq, int nkv, int d, const voi
                 const void* dout, const float* lse, void* dqkv, float* delta, void* ws, size_t ws_bytes,
                 void* stream);
 size_t dh_attn_bwd_workspace_bytes(int dtype, int batch, int seq, int nq, int nkv, int d);
+
+/* Attention of a context-parallel rank (Sec. 2.1: the token sequence is partitioned over the CP ranks and each
+ * collects the others' key/value tensors; Sec. 2.2: by Send/Recv, ring-attention style).  The rank's seq queries
+ * per sequence sit at positions q_off .. q_off+seq-1 and read, causally, the keys/values of positions
+ * 0 .. q_off+seq-1 from kv[batch*(q_off+seq), 2*nkv*d] = [k heads | v heads] per row (keys rotated), sequence-major:
+ * q_off rows received from the earlier ranks, then the rank's own.  qkv, o, lse, dout, delta are as in dh_attn_fwd /
+ * dh_attn_bwd with T = batch*seq; only the q columns of qkv are read and only the q columns of dqkv written; dk,dv of
+ * every key row go to dkv (layout of kv): the rows of earlier chunks are what the rank sends back to their owners.
+ * q_off = 0 reduces to dh_attn_fwd/bwd with keys and values held apart.  bf16: q_off must be a multiple of 128;
+ * workspaces from the _ctx_ queries below.  Device pointers; nothing is allocated. */
+int dh_attn_ctx_fwd(int dtype, int batch, int seq, int q_off, int nq, int nkv, int d, const void* qkv,
+                    const void* kv, void* o, float* lse, void* ws, size_t ws_bytes, void* stream);
+size_t dh_attn_ctx_fwd_workspace_bytes(int dtype, int batch, int seq, int q_off, int nq, int nkv, int d);
+int dh_attn_ctx_bwd(int dtype, int batch, int seq, int q_off, int nq, int nkv, int d, const void* qkv,
+                    const void* kv, const void* o, const void* dout, const float* lse, void* dqkv, void* dkv,
+                    float* delta, void* ws, size_t ws_bytes, void* stream);
+size_t dh_attn_ctx_bwd_workspace_bytes(int dtype, int batch, int seq, int q_off, int nq, int nkv, int d);
 
 /* ------------------------------------------------------------------------------------------
  * Mixture-of-experts operators (Sec. 6.1, top-2 gating; operator bases Router, Permute, AlltoAll and

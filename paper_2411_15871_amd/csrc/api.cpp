@@ -61,8 +61,12 @@ static int check_attn(const char* who, int batch, int seq, int nq, int nkv, int 
 }
 
 extern "C" size_t dh_attn_fwd_workspace_bytes(int dtype, int batch, int seq, int nq, int nkv, int d) {
-  if (dtype != DH_BF16 || batch <= 0 || seq <= 0 || nq <= 0 || nkv <= 0 || d <= 0) return 0;
-  return dh_attn_fwd_bf16_ws_bytes(batch, seq, nq, nkv, d);
+  return dh_attn_ctx_fwd_workspace_bytes(dtype, batch, seq, 0, nq, nkv, d);
+}
+
+extern "C" size_t dh_attn_ctx_fwd_workspace_bytes(int dtype, int batch, int seq, int q_off, int nq, int nkv, int d) {
+  if (dtype != DH_BF16 || batch <= 0 || seq <= 0 || q_off < 0 || nq <= 0 || nkv <= 0 || d <= 0) return 0;
+  return dh_attn_fwd_bf16_ws_bytes(batch, seq, q_off, nq, nkv, d);
 }
 
 extern "C" int dh_attn_fwd(int dtype, int batch, int seq, int nq, int nkv, int d, const void* qkv, void* o, float* lse,
@@ -70,14 +74,36 @@ extern "C" int dh_attn_fwd(int dtype, int batch, int seq, int nq, int nkv, int d
   int rc = check_attn("attn_fwd", batch, seq, nq, nkv, d);
   if (rc) return rc;
   if (batch * seq > 0 && (!qkv || !o || !lse)) DH_FAIL(DH_ERR_INVALID_ARG, "attn_fwd: null pointer");
-  if (dtype == DH_F32) return dh_launch_attn_fwd_f32(batch, seq, nq, nkv, d, (const float*)qkv, (float*)o, lse, (hipStream_t)stream);
-  if (dtype == DH_BF16) return dh_launch_attn_fwd_bf16(batch, seq, nq, nkv, d, (const bf16_t*)qkv, (bf16_t*)o, lse, ws, ws_bytes, (hipStream_t)stream);
+  if (dtype == DH_F32)
+    return dh_launch_attn_fwd_f32(batch, seq, nq, nkv, d, (const float*)qkv, nullptr, 0, 0, (float*)o, lse, (hipStream_t)stream);
+  if (dtype == DH_BF16)
+    return dh_launch_attn_fwd_bf16(batch, seq, nq, nkv, d, (const bf16_t*)qkv, nullptr, 0, 0, (bf16_t*)o, lse, ws, ws_bytes,
+                                   (hipStream_t)stream);
   DH_FAIL(DH_ERR_INVALID_ARG, "attn_fwd: unknown dtype %d", dtype);
 }
 
+extern "C" int dh_attn_ctx_fwd(int dtype, int batch, int seq, int q_off, int nq, int nkv, int d, const void* qkv, const void* kv,
+                               void* o, float* lse, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_attn("attn_ctx_fwd", batch, seq, nq, nkv, d);
+  if (rc) return rc;
+  if (q_off < 0) DH_FAIL(DH_ERR_SHAPE, "attn_ctx_fwd: negative query offset");
+  if (batch * seq > 0 && (!qkv || !kv || !o || !lse)) DH_FAIL(DH_ERR_INVALID_ARG, "attn_ctx_fwd: null pointer");
+  if (dtype == DH_F32)
+    return dh_launch_attn_fwd_f32(batch, seq, nq, nkv, d, (const float*)qkv, (const float*)kv, 2 * nkv * d, q_off, (float*)o, lse,
+                                  (hipStream_t)stream);
+  if (dtype == DH_BF16)
+    return dh_launch_attn_fwd_bf16(batch, seq, nq, nkv, d, (const bf16_t*)qkv, (const bf16_t*)kv, 2 * nkv * d, q_off, (bf16_t*)o, lse,
+                                   ws, ws_bytes, (hipStream_t)stream);
+  DH_FAIL(DH_ERR_INVALID_ARG, "attn_ctx_fwd: unknown dtype %d", dtype);
+}
+
 extern "C" size_t dh_attn_bwd_workspace_bytes(int dtype, int batch, int seq, int nq, int nkv, int d) {
-  if (dtype != DH_BF16 || batch <= 0 || seq <= 0 || nq <= 0 || nkv <= 0 || d <= 0) return 0;
-  return dh_attn_bwd_bf16_ws_bytes(batch, seq, nq, nkv, d);
+  return dh_attn_ctx_bwd_workspace_bytes(dtype, batch, seq, 0, nq, nkv, d);
+}
+
+extern "C" size_t dh_attn_ctx_bwd_workspace_bytes(int dtype, int batch, int seq, int q_off, int nq, int nkv, int d) {
+  if (dtype != DH_BF16 || batch <= 0 || seq <= 0 || q_off < 0 || nq <= 0 || nkv <= 0 || d <= 0) return 0;
+  return dh_attn_bwd_bf16_ws_bytes(batch, seq, q_off, nq, nkv, d);
 }
 
 extern "C" int dh_attn_bwd(int dtype, int batch, int seq, int nq, int nkv, int d, const void* qkv, const void* o,
@@ -87,10 +113,28 @@ extern "C" int dh_attn_bwd(int dtype, int batch, int seq, int nq, int nkv, int d
   if (rc) return rc;
   if (batch * seq > 0 && (!qkv || !o || !dout || !lse || !dqkv || !delta)) DH_FAIL(DH_ERR_INVALID_ARG, "attn_bwd: null pointer");
   if (dtype == DH_F32)
-    return dh_launch_attn_bwd_f32(batch, seq, nq, nkv, d, (const float*)qkv, (const float*)o, (const float*)dout, lse,
-                                  (float*)dqkv, delta, (hipStream_t)stream);
+    return dh_launch_attn_bwd_f32(batch, seq, nq, nkv, d, (const float*)qkv, nullptr, 0, 0, (const float*)o, (const float*)dout, lse,
+                                  (float*)dqkv, nullptr, 0, delta, (hipStream_t)stream);
   if (dtype == DH_BF16)
-    return dh_launch_attn_bwd_bf16(batch, seq, nq, nkv, d, (const bf16_t*)qkv, (const bf16_t*)o, (const bf16_t*)dout, lse,
-                                   (bf16_t*)dqkv, delta, ws, ws_bytes, (hipStream_t)stream);
+    return dh_launch_attn_bwd_bf16(batch, seq, nq, nkv, d, (const bf16_t*)qkv, nullptr, 0, 0, (const bf16_t*)o, (const bf16_t*)dout,
+                                   lse, (bf16_t*)dqkv, nullptr, 0, delta, ws, ws_bytes, (hipStream_t)stream);
   DH_FAIL(DH_ERR_INVALID_ARG, "attn_bwd: unknown dtype %d", dtype);
+}
+
+extern "C" int dh_attn_ctx_bwd(int dtype, int batch, int seq, int q_off, int nq, int nkv, int d, const void* qkv, const void* kv,
+                               const void* o, const void* dout, const float* lse, void* dqkv, void* dkv, float* delta, void* ws,
+                               size_t ws_bytes, void* stream) {
+  int rc = check_attn("attn_ctx_bwd", batch, seq, nq, nkv, d);
+  if (rc) return rc;
+  if (q_off < 0) DH_FAIL(DH_ERR_SHAPE, "attn_ctx_bwd: negative query offset");
+  if (batch * seq > 0 && (!qkv || !kv || !o || !dout || !lse || !dqkv || !dkv || !delta))
+    DH_FAIL(DH_ERR_INVALID_ARG, "attn_ctx_bwd: null pointer");
+  if (dtype == DH_F32)
+    return dh_launch_attn_bwd_f32(batch, seq, nq, nkv, d, (const float*)qkv, (const float*)kv, 2 * nkv * d, q_off, (const float*)o,
+                                  (const float*)dout, lse, (float*)dqkv, (float*)dkv, 2 * nkv * d, delta, (hipStream_t)stream);
+  if (dtype == DH_BF16)
+    return dh_launch_attn_bwd_bf16(batch, seq, nq, nkv, d, (const bf16_t*)qkv, (const bf16_t*)kv, 2 * nkv * d, q_off, (const bf16_t*)o,
+                                   (const bf16_t*)dout, lse, (bf16_t*)dqkv, (bf16_t*)dkv, 2 * nkv * d, delta, ws, ws_bytes,
+                                   (hipStream_t)stream);
+  DH_FAIL(DH_ERR_INVALID_ARG, "attn_ctx_bwd: unknown dtype %d", dtype);
 }

@@ -2,6 +2,9 @@
 // Layout: qkv[T, (nq+2nkv)*D] = [q heads | k heads | v heads] (q, k already rotated), o[T, nq*D],
 // lse[nq, T] (natural log), delta[nq, T] = rowsum(dO * O).  Tokens are sequence-major; a block
 // never crosses a sequence boundary.  D = head_dim is 64 or 128.
+// Keys and values are read through AttnGeom: from the packed qkv rows for plain causal attention, or from a
+// gathered buffer that also holds the rows of earlier context-parallel ranks (the queries are then the last
+// seq - q_off positions of each sequence); dK/dV are written the same way.
 //
 // All three kernels compute score tiles "transposed" where that keeps per-query statistics
 // lane-local: v_mfma_f32_32x32x16_bf16 leaves column j of its result in lane j%32, so
@@ -32,32 +35,44 @@
 // Work split of the backward kernels.  Along the block's own dimension there are ceil(seq/128) blocks;
 // block i has tiles_of(i) tiles to walk and is cut into ceil(tiles/AB_CH) chunks.  A launch index is
 // mapped to (block, chunk) heaviest block first; `pair` numbers the (block, chunk) pairs in natural order.
+//
+// Positions.  seq = keys per sequence (positions 0..seq-1); the queries of a sequence are its positions
+// q_off..seq-1 (q_off = 0: every position; otherwise a multiple of 128, so that query blocks and key blocks
+// share one grid of 128-position blocks, of which blocks q_off/128.. hold queries).  Query-side arrays (q in qkv,
+// o, dout, lse, delta, dq) are indexed by the local token b*(seq-q_off) + position - q_off; keys, values and
+// their gradients by b*seq + position in kv / dkv, rows of ldkv / lddkv elements laid out [k heads | v heads].
+struct AttnGeom {
+  int seq, q_off, nq, nkv;
+  const bf16_t* kv; int ldkv;
+  bf16_t* dkv; int lddkv;
+};
 struct ChunkMap { int blk, chunk, pair, chunks; };
 __host__ __device__ static inline int dq_tiles(int i, int seq) { int e = (i + 1) * 128; return ((e < seq ? e : seq) + AB_KT - 1) / AB_KT; }
-__host__ __device__ static inline int dkv_tiles(int i, int seq) { return (seq - i * 128 + AB_KT - 1) / AB_KT; }
+__host__ __device__ static inline int dkv_first(int i, int q_off) { return i * 128 > q_off ? i * 128 : q_off; }  // first query position a key block meets
+__host__ __device__ static inline int dkv_tiles(int i, int seq, int q_off) { return (seq - dkv_first(i, q_off) + AB_KT - 1) / AB_KT; }
 __host__ __device__ static inline int chunks_of(int tiles) { return (tiles + AB_CH - 1) / AB_CH; }
-static int total_pairs_dq(int seq) {
+static int total_pairs_dq(int seq, int q_off) {
   int n = 0;
-  for (int i = 0; i < (seq + 127) / 128; i++) n += chunks_of(dq_tiles(i, seq));
+  for (int i = q_off / 128; i < (seq + 127) / 128; i++) n += chunks_of(dq_tiles(i, seq));
   return n;
 }
-static int total_pairs_dkv(int seq) {
+static int total_pairs_dkv(int seq, int q_off) {
   int n = 0;
-  for (int i = 0; i < (seq + 127) / 128; i++) n += chunks_of(dkv_tiles(i, seq));
+  for (int i = 0; i < (seq + 127) / 128; i++) n += chunks_of(dkv_tiles(i, seq, q_off));
   return n;
 }
 template <bool DKV>
-__device__ __forceinline__ ChunkMap map_chunk(int id, int seq, int total) {
+__device__ __forceinline__ ChunkMap map_chunk(int id, int seq, int q_off, int total) {
   const int nblk = (seq + 127) / 128;
   ChunkMap m;
   int rem = id, after = 0;  // `after` = pairs of the blocks visited before this one
   if (DKV) {  // heaviest = block 0; natural pair order = visiting order
     int i = 0;
-    for (;; i++) { int ch = chunks_of(dkv_tiles(i, seq)); if (rem < ch || i == nblk - 1) { m.chunks = ch; break; } rem -= ch; after += ch; }
+    for (;; i++) { int ch = chunks_of(dkv_tiles(i, seq, q_off)); if (rem < ch || i == nblk - 1) { m.chunks = ch; break; } rem -= ch; after += ch; }
     m.blk = i; m.chunk = rem; m.pair = after + rem;
-  } else {    // heaviest = last block
+  } else {    // heaviest = last block; the first block with queries is q_off/128
     int i = nblk - 1;
-    for (;; i--) { int ch = chunks_of(dq_tiles(i, seq)); if (rem < ch || i == 0) { m.chunks = ch; break; } rem -= ch; after += ch; }
+    for (;; i--) { int ch = chunks_of(dq_tiles(i, seq)); if (rem < ch || i == q_off / 128) { m.chunks = ch; break; } rem -= ch; after += ch; }
     m.blk = i; m.chunk = rem; m.pair = total - after - m.chunks + rem;
   }
   return m;
@@ -305,9 +320,9 @@ __device__ __forceinline__ void pin_scalar(float v) { asm volatile("" ::"v"(v));
 // maximum and sum, and a combine kernel merges the chunks in chunk order.
 __host__ __device__ static inline int fwd_tiles(int i, int seq) { int e = (i + 1) * 128; return ((e < seq ? e : seq) + AB_KT - 1) / AB_KT; }
 __host__ __device__ static inline int fwd_chunks(int i, int seq, int ch) { return ch > 0 ? (fwd_tiles(i, seq) + ch - 1) / ch : 1; }
-static int fwd_units(int seq, int ch) {
+static int fwd_units(int seq, int q_off, int ch) {
   int n = 0;
-  for (int i = 0; i < (seq + 127) / 128; i++) n += fwd_chunks(i, seq, ch);
+  for (int i = q_off / 128; i < (seq + 127) / 128; i++) n += fwd_chunks(i, seq, ch);
   return n;
 }
 
@@ -316,7 +331,7 @@ static int fwd_units(int seq, int ch) {
 // one block's waves then overlaps the softmax arithmetic of the other's.
 #define AF_RING 2
 template <int D>
-__global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(int seq, int nq, int nkv, const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(const AttnGeom g, const bf16_t* __restrict__ qkv,
                                                                    bf16_t* __restrict__ o, float* __restrict__ lse, int T,
                                                                    float scale_log2, int ch, int units,
                                                                    float* __restrict__ part_o, float* __restrict__ part_ml) {
@@ -325,18 +340,19 @@ __global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(int seq, i
   const lds_char* sm = (const lds_char*)smem;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l32 = lane & 31, kg = lane >> 5;
+  const int seq = g.seq, nq = g.nq, nkv = g.nkv, qb0 = g.q_off / 128, ldkv = g.ldkv;
   const int h = blockIdx.y, b = blockIdx.z, hk = h / (nq / nkv);
   const int ld = (nq + 2 * nkv) * D;
   int blk, chunk = 0, nchunks = 1, pair;
   if (ch == 0) {
-    blk = gridDim.x - 1 - blockIdx.x;
-    pair = blk;
+    pair = gridDim.x - 1 - blockIdx.x;
+    blk = qb0 + pair;
   } else {  // heaviest block first; `pair` numbers the (block, chunk) units in natural order
     int rem = blockIdx.x, after = 0;
     blk = (seq + 127) / 128 - 1;
     for (;; blk--) {
       nchunks = fwd_chunks(blk, seq, ch);
-      if (rem < nchunks || blk == 0) break;
+      if (rem < nchunks || blk == qb0) break;
       rem -= nchunks;
       after += nchunks;
     }
@@ -344,13 +360,14 @@ __global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(int seq, i
     pair = units - after - nchunks + rem;
   }
   const int i0 = blk * 128, iw = i0 + wave * 32, iq = iw + l32;  // positions in the sequence
-  const size_t tok0 = (size_t)b * seq;
-  const char* kbase = reinterpret_cast<const char*>(qkv + tok0 * ld + (size_t)(nq + hk) * D);
-  const char* vbase = reinterpret_cast<const char*>(qkv + tok0 * ld + (size_t)(nq + nkv + hk) * D);
-  const size_t tstride = (size_t)AB_KT * ld * sizeof(bf16_t);
+  const size_t ktok0 = (size_t)b * seq;
+  const long long qtok0 = (long long)b * (seq - g.q_off) - g.q_off;  // local token of position p = qtok0 + p
+  const char* kbase = reinterpret_cast<const char*>(g.kv + ktok0 * ldkv + (size_t)hk * D);
+  const char* vbase = reinterpret_cast<const char*>(g.kv + ktok0 * ldkv + (size_t)(nkv + hk) * D);
+  const size_t tstride = (size_t)AB_KT * ldkv * sizeof(bf16_t);
 
   bf16x8 qf[D / 16];
-  load_row_frags<D>(qf, qkv + (tok0 + min(iq, seq - 1)) * ld + (size_t)h * D, iq < seq, kg);
+  load_row_frags<D>(qf, qkv + (size_t)(qtok0 + min(iq, seq - 1)) * ld + (size_t)h * D, iq < seq, kg);
   f32x16 ot[D / 32];
 #pragma unroll
   for (int dt = 0; dt < D / 32; dt++)
@@ -361,7 +378,7 @@ __global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(int seq, i
   FragAddr<D> fa;
   fa.init(lane);
   uint32_t voff[TL::IPW];
-  tile_voff<D>(voff, ld, wave, lane, AB_KT);
+  tile_voff<D>(voff, ldkv, wave, lane, AB_KT);
   const uint32_t ldsK = lds_address(smem), ldsV = ldsK + AF_RING * TL::BYTES;
   const int tiles_all = (min(seq, i0 + 128) + AB_KT - 1) / AB_KT;  // keys needed by this block: [0, 64*tiles_all)
   const int t_begin = chunk * ch, ntiles = ch == 0 ? tiles_all : min(tiles_all, t_begin + ch);  // this unit: [t_begin, ntiles)
@@ -372,7 +389,7 @@ __global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(int seq, i
       tile_dma<D>(vbase + t * tstride, voff, ldsV + slot * TL::BYTES, wave);
     } else {
       uint32_t vc[TL::IPW];
-      tile_voff<D>(vc, ld, wave, lane, valid);
+      tile_voff<D>(vc, ldkv, wave, lane, valid);
       tile_dma<D>(kbase + t * tstride, vc, ldsK + slot * TL::BYTES, wave);
       tile_dma<D>(vbase + t * tstride, vc, ldsV + slot * TL::BYTES, wave);
     }
@@ -452,7 +469,7 @@ __global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(int seq, i
   }
   if (iq < seq) {
     const float inv = 1.0f / l;
-    bf16_t* orow = o + (tok0 + iq) * (size_t)nq * D + (size_t)h * D;
+    bf16_t* orow = o + (size_t)(qtok0 + iq) * nq * D + (size_t)h * D;
 #pragma unroll
     for (int dt = 0; dt < D / 32; dt++)
 #pragma unroll
@@ -462,7 +479,7 @@ __global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(int seq, i
         for (int i = 0; i < 4; i++) v[i] = (bf16_t)(ot[dt][4 * q4 + i] * inv);
         *reinterpret_cast<bf16x4*>(orow + dt * 32 + 8 * q4 + 4 * kg) = v;
       }
-    if (kg == 0) lse[(size_t)h * T + tok0 + iq] = (m + log2f(l)) * 0.6931471805599453f;
+    if (kg == 0) lse[(size_t)h * T + qtok0 + iq] = (m + log2f(l)) * 0.6931471805599453f;
   }
 }
 
@@ -470,16 +487,16 @@ __global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(int seq, i
 // L = sum_c 2^(m_c-M) l_c, lse = (M + log2 L) ln 2; chunks are added in chunk order.
 // grid (8 * blocks, nq, batch): a 256-thread block merges 16 rows, a thread D/16 columns of one row.
 template <int D>
-__global__ __launch_bounds__(256) void attn_fwd_combine_kernel(int seq, int nq, int ch, int units, const float* __restrict__ part_o,
+__global__ __launch_bounds__(256) void attn_fwd_combine_kernel(int seq, int q_off, int nq, int ch, int units, const float* __restrict__ part_o,
                                                                const float* __restrict__ part_ml, bf16_t* __restrict__ o,
                                                                float* __restrict__ lse, int T) {
-  const int blk = blockIdx.x >> 3, h = blockIdx.y, b = blockIdx.z;
+  const int blk = q_off / 128 + (blockIdx.x >> 3), h = blockIdx.y, b = blockIdx.z;
   const int nchunks = fwd_chunks(blk, seq, ch);
   if (nchunks == 1) return;
   const int r = (blockIdx.x & 7) * 16 + (threadIdx.x >> 4), pos = blk * 128 + r;
   if (pos >= seq) return;
   int pair0 = 0;
-  for (int i = 0; i < blk; i++) pair0 += fwd_chunks(i, seq, ch);
+  for (int i = q_off / 128; i < blk; i++) pair0 += fwd_chunks(i, seq, ch);
   const size_t unit0 = ((size_t)b * nq + h) * units + pair0;
   constexpr int CPT = D / 16;  // columns per thread
   const int c0 = (threadIdx.x & 15) * CPT;
@@ -500,7 +517,7 @@ __global__ __launch_bounds__(256) void attn_fwd_combine_kernel(int seq, int nq, 
     }
   }
   const float inv = 1.0f / L;
-  const size_t tok = (size_t)b * seq + pos;
+  const size_t tok = (size_t)b * (seq - q_off) + (pos - q_off);
   bf16_t* orow = o + tok * (size_t)nq * D + (size_t)h * D + c0;
 #pragma unroll
   for (int i = 0; i < CPT; i += 4) {
@@ -540,7 +557,7 @@ __global__ __launch_bounds__(256) void attn_bwd_prep_kernel(int nq, const bf16_t
 // Same tiling as the forward kernel.  dQ^T = sum over key tiles of K^T dS^T, dS^T = P^T (dP^T - delta),
 // P^T = exp2(S^T*scale_log2 - lse2), dP^T = V dO^T.
 template <int D>
-__global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(int seq, int nq, int nkv, const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(const AttnGeom g, const bf16_t* __restrict__ qkv,
                                                                       const bf16_t* __restrict__ dout,
                                                                       const float* __restrict__ lse2,
                                                                       const float* __restrict__ delta,
@@ -551,21 +568,23 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(int seq, i
   const lds_char* sm = (const lds_char*)smem;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l32 = lane & 31, kg = lane >> 5;
+  const int seq = g.seq, nq = g.nq, nkv = g.nkv, ldkv = g.ldkv;
   const int h = blockIdx.y, b = blockIdx.z, hk = h / (nq / nkv);
   const int ld = (nq + 2 * nkv) * D;
-  const ChunkMap cm = map_chunk<false>(blockIdx.x, seq, pairs);
+  const ChunkMap cm = map_chunk<false>(blockIdx.x, seq, g.q_off, pairs);
   const int i0 = cm.blk * 128, iw = i0 + wave * 32, iq = iw + l32;
-  const size_t tok0 = (size_t)b * seq;
-  const char* kbase = reinterpret_cast<const char*>(qkv + tok0 * ld + (size_t)(nq + hk) * D);
-  const char* vbase = reinterpret_cast<const char*>(qkv + tok0 * ld + (size_t)(nq + nkv + hk) * D);
-  const size_t tstride = (size_t)AB_KT * ld * sizeof(bf16_t);
+  const size_t ktok0 = (size_t)b * seq;
+  const long long qtok0 = (long long)b * (seq - g.q_off) - g.q_off;  // local token of position p = qtok0 + p
+  const char* kbase = reinterpret_cast<const char*>(g.kv + ktok0 * ldkv + (size_t)hk * D);
+  const char* vbase = reinterpret_cast<const char*>(g.kv + ktok0 * ldkv + (size_t)(nkv + hk) * D);
+  const size_t tstride = (size_t)AB_KT * ldkv * sizeof(bf16_t);
 
   bf16x8 qf[D / 16], dof[D / 16];
-  const int iqc = min(iq, seq - 1);
-  load_row_frags<D>(qf, qkv + (tok0 + iqc) * ld + (size_t)h * D, iq < seq, kg);
-  load_row_frags<D>(dof, dout + (tok0 + iqc) * (size_t)nq * D + (size_t)h * D, iq < seq, kg);
-  const float l2 = lse2[(size_t)h * T + tok0 + iqc];
-  const float dl = delta[(size_t)h * T + tok0 + iqc];
+  const size_t qrow = (size_t)(qtok0 + min(iq, seq - 1));
+  load_row_frags<D>(qf, qkv + qrow * ld + (size_t)h * D, iq < seq, kg);
+  load_row_frags<D>(dof, dout + qrow * (size_t)nq * D + (size_t)h * D, iq < seq, kg);
+  const float l2 = lse2[(size_t)h * T + qrow];
+  const float dl = delta[(size_t)h * T + qrow];
   f32x16 dqt[D / 32];
 #pragma unroll
   for (int dt = 0; dt < D / 32; dt++) acc_zero<D>(dqt[dt]);
@@ -573,7 +592,7 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(int seq, i
   FragAddr<D> fa;
   fa.init(lane);
   uint32_t voff[TL::IPW];
-  tile_voff<D>(voff, ld, wave, lane, AB_KT);
+  tile_voff<D>(voff, ldkv, wave, lane, AB_KT);
   const uint32_t ldsK = lds_address(smem), ldsV = ldsK + AB_RING * TL::BYTES;
   const int t0 = cm.chunk * AB_CH, ntiles = min(dq_tiles(cm.blk, seq), t0 + AB_CH);  // this block walks key tiles [t0, ntiles)
   auto issue = [&](int t, int slot) {
@@ -583,7 +602,7 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(int seq, i
       tile_dma<D>(vbase + t * tstride, voff, ldsV + slot * TL::BYTES, wave);
     } else {
       uint32_t vc[TL::IPW];
-      tile_voff<D>(vc, ld, wave, lane, valid);
+      tile_voff<D>(vc, ldkv, wave, lane, valid);
       tile_dma<D>(kbase + t * tstride, vc, ldsK + slot * TL::BYTES, wave);
       tile_dma<D>(vbase + t * tstride, vc, ldsV + slot * TL::BYTES, wave);
     }
@@ -637,7 +656,7 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(int seq, i
         *reinterpret_cast<f32x4*>(row + dt * 32 + 8 * q4 + 4 * kg) = v;
       }
   } else if (iq < seq) {
-    bf16_t* row = dqkv + (tok0 + iq) * ld + (size_t)h * D;
+    bf16_t* row = dqkv + (size_t)(qtok0 + iq) * ld + (size_t)h * D;
 #pragma unroll
     for (int dt = 0; dt < D / 32; dt++)
 #pragma unroll
@@ -651,13 +670,13 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(int seq, i
 }
 
 // dq[token][head] = scale * sum over the chunks of the token's query block (ascending) of the partials.
-// grid (8*ceil(seq/128), nq, batch), 256 threads: a block owns 16 rows of a query block, thread = (row, 4 columns).
+// grid (8*query blocks, nq, batch), 256 threads: a block owns 16 rows of a query block, thread = (row, 4 columns).
 template <int D>
 __global__ __launch_bounds__(256) void attn_bwd_dq_reduce_kernel(const float* __restrict__ part, bf16_t* __restrict__ dqkv, int seq,
-                                                                 int nq, int nkv, int pairs, float scale) {
-  const int i = blockIdx.x >> 3, r0 = (blockIdx.x & 7) * 16, h = blockIdx.y, b = blockIdx.z, ld = (nq + 2 * nkv) * D;
+                                                                 int q_off, int nq, int nkv, int pairs, float scale) {
+  const int i = q_off / 128 + (blockIdx.x >> 3), r0 = (blockIdx.x & 7) * 16, h = blockIdx.y, b = blockIdx.z, ld = (nq + 2 * nkv) * D;
   int base = 0;
-  for (int k = 0; k < i; k++) base += chunks_of(dq_tiles(k, seq));
+  for (int k = q_off / 128; k < i; k++) base += chunks_of(dq_tiles(k, seq));
   const int ch = chunks_of(dq_tiles(i, seq));
   const float* p0 = part + (((size_t)b * nq + h) * pairs + base) * 128 * D;
   for (int e = threadIdx.x; e < 16 * D / 4; e += 256) {
@@ -666,7 +685,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_reduce_kernel(const float* __
     f32x4 s = {0.f, 0.f, 0.f, 0.f};
     for (int c = 0; c < ch; c++) s += *reinterpret_cast<const f32x4*>(p0 + ((size_t)c * 128 + row) * D + c4);
     bf16x4 o = {(bf16_t)(s[0] * scale), (bf16_t)(s[1] * scale), (bf16_t)(s[2] * scale), (bf16_t)(s[3] * scale)};
-    *reinterpret_cast<bf16x4*>(dqkv + ((size_t)b * seq + i * 128 + row) * ld + (size_t)h * D + c4) = o;
+    *reinterpret_cast<bf16x4*>(dqkv + ((size_t)b * (seq - q_off) + (i * 128 + row - q_off)) * ld + (size_t)h * D + c4) = o;
   }
 }
 
@@ -678,33 +697,36 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_reduce_kernel(const float* __
 // attn_bwd_group_reduce_kernel adds the group's heads and the key block's chunks in index order; with
 // nq == nkv and no block longer than one chunk it writes dK, dV directly.
 template <int D>
-__global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, int nq, int nkv, const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(const AttnGeom g, const bf16_t* __restrict__ qkv,
                                                                        const bf16_t* __restrict__ dout,
                                                                        const float* __restrict__ lse2,
                                                                        const float* __restrict__ delta,
-                                                                       bf16_t* __restrict__ dqkv, float* __restrict__ part,
+                                                                       float* __restrict__ part,
                                                                        int pairs, int T, float scale, float scale_log2) {
   using TL = ATile<D>;
   extern __shared__ __attribute__((aligned(1024))) char smem[];  // Q ring, dO ring, lse2 ring, delta ring
   const lds_char* sm = (const lds_char*)smem;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l32 = lane & 31, kg = lane >> 5;
+  const int seq = g.seq, nq = g.nq, nkv = g.nkv;
   const int hq = blockIdx.y, b = blockIdx.z, grp = nq / nkv, hk = hq / grp;
   const int ld = (nq + 2 * nkv) * D, ldo = nq * D;
-  const ChunkMap cm = map_chunk<true>(blockIdx.x, seq, pairs);
+  const ChunkMap cm = map_chunk<true>(blockIdx.x, seq, g.q_off, pairs);
   const int j0 = cm.blk * 128, jw = j0 + wave * 32, jk = jw + l32;  // key positions in the sequence (block 0 is the heaviest)
-  const size_t tok0 = (size_t)b * seq;
-  const char* qbase = reinterpret_cast<const char*>(qkv + tok0 * ld + (size_t)hq * D);
-  const char* obase = reinterpret_cast<const char*>(dout + tok0 * ldo + (size_t)hq * D);
-  const float* lrow = lse2 + (size_t)hq * T + tok0;
-  const float* drow = delta + (size_t)hq * T + tok0;
+  const int q0 = dkv_first(cm.blk, g.q_off);                        // first query position this key block meets
+  const size_t ktok0 = (size_t)b * seq;
+  const size_t qtok = (size_t)b * (seq - g.q_off) + (q0 - g.q_off);  // local token of position q0
+  const char* qbase = reinterpret_cast<const char*>(qkv + qtok * ld + (size_t)hq * D);
+  const char* obase = reinterpret_cast<const char*>(dout + qtok * ldo + (size_t)hq * D);
+  const float* lrow = lse2 + (size_t)hq * T + qtok;
+  const float* drow = delta + (size_t)hq * T + qtok;
   float* lse_s = reinterpret_cast<float*>(smem + 2 * AB_RING * TL::BYTES);
   float* del_s = lse_s + AB_RING * AB_KT;
 
   bf16x8 kf[D / 16], vf[D / 16];
   const int jkc = min(jk, seq - 1);
-  load_row_frags<D>(kf, qkv + (tok0 + jkc) * ld + (size_t)(nq + hk) * D, jk < seq, kg);
-  load_row_frags<D>(vf, qkv + (tok0 + jkc) * ld + (size_t)(nq + nkv + hk) * D, jk < seq, kg);
+  load_row_frags<D>(kf, g.kv + (ktok0 + jkc) * g.ldkv + (size_t)hk * D, jk < seq, kg);
+  load_row_frags<D>(vf, g.kv + (ktok0 + jkc) * g.ldkv + (size_t)(nkv + hk) * D, jk < seq, kg);
   f32x16 dkt[D / 32], dvt[D / 32];
 #pragma unroll
   for (int dt = 0; dt < D / 32; dt++) { acc_zero<D>(dkt[dt]); acc_zero<D>(dvt[dt]); }
@@ -715,12 +737,12 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, 
   tile_voff<D>(vq, ld, wave, lane, AB_KT);
   tile_voff<D>(vo, ldo, wave, lane, AB_KT);
   const uint32_t ldsQ = lds_address(smem), ldsO = ldsQ + AB_RING * TL::BYTES;
-  const int t0 = cm.chunk * AB_CH, ntiles = min(dkv_tiles(cm.blk, seq), t0 + AB_CH);  // query tiles j0 + 64*[t0, ntiles)
+  const int t0 = cm.chunk * AB_CH, ntiles = min(dkv_tiles(cm.blk, seq, g.q_off), t0 + AB_CH);  // query tiles q0 + 64*[t0, ntiles)
   const size_t qstride = (size_t)AB_KT * ld * sizeof(bf16_t), ostride = (size_t)AB_KT * ldo * sizeof(bf16_t);
   auto issue = [&](int t, int slot) {
-    const int row0 = j0 + t * AB_KT, valid = seq - row0;
-    const char* qp = qbase + (size_t)j0 * ld * sizeof(bf16_t) + t * qstride;
-    const char* op = obase + (size_t)j0 * ldo * sizeof(bf16_t) + t * ostride;
+    const int valid = seq - (q0 + t * AB_KT);
+    const char* qp = qbase + t * qstride;
+    const char* op = obase + t * ostride;
     if (valid >= AB_KT) {
       tile_dma<D>(qp, vq, ldsQ + slot * TL::BYTES, wave);
       tile_dma<D>(op, vo, ldsO + slot * TL::BYTES, wave);
@@ -739,8 +761,8 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, 
   pin_frags(kf);
   pin_frags(vf);
   auto issue_stat = [&](int t, int slot) {
-    const int row0 = j0 + t * AB_KT;
-    dma4_base(srow + row0, (uint32_t)((min(row0 + lane, seq - 1) - row0) * sizeof(float)),
+    const int row0 = q0 + t * AB_KT;
+    dma4_base(srow + t * AB_KT, (uint32_t)((min(row0 + lane, seq - 1) - row0) * sizeof(float)),
               ldsS + slot * AB_KT * sizeof(float));
   };
   issue(t0, 0);
@@ -751,7 +773,7 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, 
     if (t + 1 < ntiles) dma_wait<2 * TL::IPW + 1>(); else dma_wait<0>();
     __syncthreads();
     if (t + 2 < ntiles) { const int ns = slot == 0 ? AB_RING - 1 : slot - 1; issue(t + 2, ns); issue_stat(t + 2, ns); }
-    const int qb = j0 + t * AB_KT;
+    const int qb = q0 + t * AB_KT;
     if (qb + AB_KT - 1 < jw) continue;  // every query of the tile precedes every key of this wave
     TilePtrs<D> Qp, Op;
     Qp.set(sm + slot * TL::BYTES, fa);
@@ -806,8 +828,8 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, 
         *reinterpret_cast<f32x4*>(prow + D + dt * 32 + 8 * q4 + 4 * kg) = c;
       }
   } else if (jk < seq) {
-    bf16_t* krow = dqkv + (tok0 + jk) * ld + (size_t)(nq + hk) * D;
-    bf16_t* vrow = dqkv + (tok0 + jk) * ld + (size_t)(nq + nkv + hk) * D;
+    bf16_t* krow = g.dkv + (ktok0 + jk) * g.lddkv + (size_t)hk * D;
+    bf16_t* vrow = g.dkv + (ktok0 + jk) * g.lddkv + (size_t)(nkv + hk) * D;
 #pragma unroll
     for (int dt = 0; dt < D / 32; dt++)
 #pragma unroll
@@ -829,22 +851,22 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(int seq, 
 // grid (8*ceil(seq/128), nkv, batch), 256 threads: a block owns 16 rows of a key block, thread = (key row, 4
 // columns of [dK | dV]).
 template <int D>
-__global__ __launch_bounds__(256) void attn_bwd_group_reduce_kernel(const float* __restrict__ part, bf16_t* __restrict__ dqkv,
-                                                                    int seq, int nq, int nkv, int pairs) {
-  const int i = blockIdx.x >> 3, r0 = (blockIdx.x & 7) * 16, hk = blockIdx.y, b = blockIdx.z, grp = nq / nkv, ld = (nq + 2 * nkv) * D;
+__global__ __launch_bounds__(256) void attn_bwd_group_reduce_kernel(const float* __restrict__ part, const AttnGeom g, int pairs) {
+  const int seq = g.seq, nq = g.nq, nkv = g.nkv;
+  const int i = blockIdx.x >> 3, r0 = (blockIdx.x & 7) * 16, hk = blockIdx.y, b = blockIdx.z, grp = nq / nkv;
   int base = 0;
-  for (int k = 0; k < i; k++) base += chunks_of(dkv_tiles(k, seq));
-  const int ch = chunks_of(dkv_tiles(i, seq));
+  for (int k = 0; k < i; k++) base += chunks_of(dkv_tiles(k, seq, g.q_off));
+  const int ch = chunks_of(dkv_tiles(i, seq, g.q_off));
   for (int e = threadIdx.x; e < 16 * 2 * D / 4; e += 256) {
     const int row = r0 + e / (2 * D / 4), c4 = (e % (2 * D / 4)) * 4;
     if (i * 128 + row >= seq) continue;
     f32x4 s = {0.f, 0.f, 0.f, 0.f};
-    for (int g = 0; g < grp; g++) {
-      const float* p0 = part + (((size_t)b * nq + hk * grp + g) * pairs + base) * 128 * (2 * D);
+    for (int gh = 0; gh < grp; gh++) {
+      const float* p0 = part + (((size_t)b * nq + hk * grp + gh) * pairs + base) * 128 * (2 * D);
       for (int c = 0; c < ch; c++) s += *reinterpret_cast<const f32x4*>(p0 + ((size_t)c * 128 + row) * (2 * D) + c4);
     }
     bf16x4 o = {(bf16_t)s[0], (bf16_t)s[1], (bf16_t)s[2], (bf16_t)s[3]};
-    bf16_t* dst = dqkv + ((size_t)b * seq + i * 128 + row) * ld + (c4 < D ? (size_t)(nq + hk) * D + c4 : (size_t)(nq + nkv + hk) * D + (c4 - D));
+    bf16_t* dst = g.dkv + ((size_t)b * seq + i * 128 + row) * g.lddkv + (c4 < D ? (size_t)hk * D + c4 : (size_t)(nkv + hk) * D + (c4 - D));
     *reinterpret_cast<bf16x4*>(dst) = o;
   }
 }
@@ -869,49 +891,64 @@ static int attn_num_cus() {
 
 // Tiles per chunk of the forward kernel: the largest of 64, 32, 16, 8 that still gives about three work
 // units per resident block slot (two per compute unit); 0 = blocks are not split.
-static int fwd_chunk_tiles(int batch, int seq, int nq) {
+static int fwd_chunk_tiles(int batch, int seq, int q_off, int nq) {
   const long long target = 6ll * attn_num_cus();
   const int max_tiles = fwd_tiles((seq + 127) / 128 - 1, seq);
   for (int ch = 64; ch >= 8; ch /= 2) {
     if (ch >= max_tiles) continue;
-    if ((long long)fwd_units(seq, ch) * nq * batch >= target || ch == 8) return ch;
+    if ((long long)fwd_units(seq, q_off, ch) * nq * batch >= target || ch == 8) return ch;
   }
   return 0;
 }
 
-size_t dh_attn_fwd_bf16_ws_bytes(int batch, int seq, int nq, int nkv, int d) {
-  (void)nkv;
-  if (batch * seq == 0) return 0;
-  const int ch = fwd_chunk_tiles(batch, seq, nq);
-  if (ch == 0) return 0;
-  return (size_t)batch * nq * fwd_units(seq, ch) * 128 * ((size_t)d + 2) * sizeof(float);
+// The launchers take the queries' sequence length seq_q and q_off; kv == nullptr selects plain attention (keys and
+// values in the packed qkv rows, gradients into the packed dqkv rows).
+static int check_geom(int d, int q_off, const void* kv, int ldkv, int nkv) {
+  if (d != 64 && d != 128) DH_FAIL(DH_ERR_SHAPE, "attention (bf16): head_dim %d must be 64 or 128", d);
+  if (q_off < 0 || q_off % 128) DH_FAIL(DH_ERR_SHAPE, "attention (bf16): the query offset %d must be a non-negative multiple of 128", q_off);
+  if (!kv && q_off) DH_FAIL(DH_ERR_INVALID_ARG, "attention (bf16): a query offset needs a key/value buffer");
+  if (kv && (ldkv < 2 * nkv * d || ldkv % 8 || ((uintptr_t)kv & 15)))
+    DH_FAIL(DH_ERR_SHAPE, "attention (bf16): key/value rows must hold 2*nkv*d elements, be a multiple of 8 long and 16-byte aligned");
+  return DH_OK;
 }
 
-int dh_launch_attn_fwd_bf16(int batch, int seq, int nq, int nkv, int d, const bf16_t* qkv, bf16_t* o, float* lse, void* ws,
-                            size_t ws_bytes, hipStream_t stream) {
-  if (d != 64 && d != 128) DH_FAIL(DH_ERR_SHAPE, "attention (bf16): head_dim %d must be 64 or 128", d);
-  if (batch * seq == 0) return DH_OK;
-  const int nblk = (seq + 127) / 128;
-  int ch = fwd_chunk_tiles(batch, seq, nq);
-  if (ch > 0 && (!ws || ws_bytes < dh_attn_fwd_bf16_ws_bytes(batch, seq, nq, nkv, d))) ch = 0;  // no room for partial results
-  const int units = ch > 0 ? fwd_units(seq, ch) : nblk;
+size_t dh_attn_fwd_bf16_ws_bytes(int batch, int seq_q, int q_off, int nq, int nkv, int d) {
+  (void)nkv;
+  if (batch * seq_q == 0) return 0;
+  const int seq = q_off + seq_q, ch = fwd_chunk_tiles(batch, seq, q_off, nq);
+  if (ch == 0) return 0;
+  return (size_t)batch * nq * fwd_units(seq, q_off, ch) * 128 * ((size_t)d + 2) * sizeof(float);
+}
+
+int dh_launch_attn_fwd_bf16(int batch, int seq_q, int nq, int nkv, int d, const bf16_t* qkv, const bf16_t* kv, int ldkv, int q_off,
+                            bf16_t* o, float* lse, void* ws, size_t ws_bytes, hipStream_t stream) {
+  int rc;
+  if ((rc = check_geom(d, q_off, kv, ldkv, nkv))) return rc;
+  if (batch * seq_q == 0) return DH_OK;
+  const int seq = q_off + seq_q, T = batch * seq_q;
+  AttnGeom g;
+  g.seq = seq; g.q_off = q_off; g.nq = nq; g.nkv = nkv; g.dkv = nullptr; g.lddkv = 0;
+  if (kv) { g.kv = kv; g.ldkv = ldkv; } else { g.kv = qkv + (size_t)nq * d; g.ldkv = (nq + 2 * nkv) * d; }
+  const int nblk = (seq + 127) / 128 - q_off / 128;  // blocks that hold queries
+  int ch = fwd_chunk_tiles(batch, seq, q_off, nq);
+  if (ch > 0 && (!ws || ws_bytes < dh_attn_fwd_bf16_ws_bytes(batch, seq_q, q_off, nq, nkv, d))) ch = 0;  // no room for partial results
+  const int units = ch > 0 ? fwd_units(seq, q_off, ch) : nblk;
   float* part_o = (float*)ws;
   float* part_ml = ch > 0 ? part_o + (size_t)batch * nq * units * 128 * d : nullptr;
   dim3 grid(units, nq, batch), cgrid(nblk * 8, nq, batch);
   const float sl2 = (float)(1.4426950408889634 / sqrt((double)d));
   const size_t lds = 2 * AF_RING * (size_t)AB_KT * d * 2;
   static bool ready[2] = {false, false};
-  int rc;
   if (d == 128) {
     if (!ready[0]) { if ((rc = set_lds(attn_fwd_bf16_kernel<128>, lds))) return rc; ready[0] = true; }
-    attn_fwd_bf16_kernel<128><<<grid, AB_THREADS, lds, stream>>>(seq, nq, nkv, qkv, o, lse, batch * seq, sl2, ch, units, part_o, part_ml);
+    attn_fwd_bf16_kernel<128><<<grid, AB_THREADS, lds, stream>>>(g, qkv, o, lse, T, sl2, ch, units, part_o, part_ml);
     DH_LAUNCH_CHECK();
-    if (ch > 0) attn_fwd_combine_kernel<128><<<cgrid, 256, 0, stream>>>(seq, nq, ch, units, part_o, part_ml, o, lse, batch * seq);
+    if (ch > 0) attn_fwd_combine_kernel<128><<<cgrid, 256, 0, stream>>>(seq, q_off, nq, ch, units, part_o, part_ml, o, lse, T);
   } else {
     if (!ready[1]) { if ((rc = set_lds(attn_fwd_bf16_kernel<64>, lds))) return rc; ready[1] = true; }
-    attn_fwd_bf16_kernel<64><<<grid, AB_THREADS, lds, stream>>>(seq, nq, nkv, qkv, o, lse, batch * seq, sl2, ch, units, part_o, part_ml);
+    attn_fwd_bf16_kernel<64><<<grid, AB_THREADS, lds, stream>>>(g, qkv, o, lse, T, sl2, ch, units, part_o, part_ml);
     DH_LAUNCH_CHECK();
-    if (ch > 0) attn_fwd_combine_kernel<64><<<cgrid, 256, 0, stream>>>(seq, nq, ch, units, part_o, part_ml, o, lse, batch * seq);
+    if (ch > 0) attn_fwd_combine_kernel<64><<<cgrid, 256, 0, stream>>>(seq, q_off, nq, ch, units, part_o, part_ml, o, lse, T);
   }
   DH_LAUNCH_CHECK();
   return DH_OK;
@@ -919,13 +956,13 @@ int dh_launch_attn_fwd_bf16(int batch, int seq, int nq, int nkv, int d, const bf
 
 // workspace: lse2[nq*T] floats; dK/dV partials [batch][nq][pairs][128][2d] floats when heads are grouped
 // or some block needs more than one chunk; dQ partials [batch][nq][pairs][128][d] floats in the latter case
-static void bwd_ws_layout(int batch, int seq, int nq, int nkv, int d, size_t& o_lse2, size_t& o_dkv, size_t& o_dq, size_t& total,
-                          int& pairs, bool& chunked) {
-  const size_t T = (size_t)batch * seq;
-  pairs = total_pairs_dq(seq);  // equals total_pairs_dkv(seq): the two tile counts mirror each other up to the ragged tail
-  const int pk = total_pairs_dkv(seq);
-  if (pk > pairs) pairs = pk;
-  chunked = pairs > (seq + 127) / 128;
+static void bwd_ws_layout(int batch, int seq_q, int q_off, int nq, int nkv, int d, size_t& o_lse2, size_t& o_dkv, size_t& o_dq,
+                          size_t& total, int& pairs, bool& chunked) {
+  const size_t T = (size_t)batch * seq_q;
+  const int seq = q_off + seq_q, nblk = (seq + 127) / 128;
+  const int pq = total_pairs_dq(seq, q_off), pk = total_pairs_dkv(seq, q_off);
+  pairs = pq > pk ? pq : pk;
+  chunked = pq > nblk - q_off / 128 || pk > nblk;
   size_t cur = 0;
   o_lse2 = cur; cur += dh_align_up(nq * T * sizeof(float), 256);
   o_dkv = cur; if (nq > nkv || chunked) cur += dh_align_up((size_t)batch * nq * pairs * 128 * 2 * d * sizeof(float), 256);
@@ -933,31 +970,37 @@ static void bwd_ws_layout(int batch, int seq, int nq, int nkv, int d, size_t& o_
   total = cur;
 }
 
-size_t dh_attn_bwd_bf16_ws_bytes(int batch, int seq, int nq, int nkv, int d) {
+size_t dh_attn_bwd_bf16_ws_bytes(int batch, int seq_q, int q_off, int nq, int nkv, int d) {
   size_t a, b, c, total; int pairs; bool chunked;
-  bwd_ws_layout(batch, seq, nq, nkv, d, a, b, c, total, pairs, chunked);
+  bwd_ws_layout(batch, seq_q, q_off, nq, nkv, d, a, b, c, total, pairs, chunked);
   return total;
 }
 
-int dh_launch_attn_bwd_bf16(int batch, int seq, int nq, int nkv, int d, const bf16_t* qkv, const bf16_t* o,
-                            const bf16_t* dout, const float* lse, bf16_t* dqkv, float* delta, void* ws, size_t ws_bytes,
-                            hipStream_t stream) {
-  if (d != 64 && d != 128) DH_FAIL(DH_ERR_SHAPE, "attention (bf16): head_dim %d must be 64 or 128", d);
-  const int T = batch * seq;
+int dh_launch_attn_bwd_bf16(int batch, int seq_q, int nq, int nkv, int d, const bf16_t* qkv, const bf16_t* kv, int ldkv, int q_off,
+                            const bf16_t* o, const bf16_t* dout, const float* lse, bf16_t* dqkv, bf16_t* dkv, int lddkv,
+                            float* delta, void* ws, size_t ws_bytes, hipStream_t stream) {
+  int rc;
+  if ((rc = check_geom(d, q_off, kv, ldkv, nkv))) return rc;
+  if (kv && (!dkv || lddkv < 2 * nkv * d || lddkv % 8 || ((uintptr_t)dkv & 15)))
+    DH_FAIL(DH_ERR_SHAPE, "attention (bf16): the key/value gradient buffer must match the key/value buffer's layout rules");
+  const int T = batch * seq_q, seq = q_off + seq_q;
   if (T == 0) return DH_OK;
+  AttnGeom g;
+  g.seq = seq; g.q_off = q_off; g.nq = nq; g.nkv = nkv;
+  if (kv) { g.kv = kv; g.ldkv = ldkv; g.dkv = dkv; g.lddkv = lddkv; }
+  else { g.kv = qkv + (size_t)nq * d; g.dkv = dqkv + (size_t)nq * d; g.ldkv = g.lddkv = (nq + 2 * nkv) * d; }
   size_t o_lse2, o_dkv, o_dq, need; int pairs_max; bool chunked;
-  bwd_ws_layout(batch, seq, nq, nkv, d, o_lse2, o_dkv, o_dq, need, pairs_max, chunked);
+  bwd_ws_layout(batch, seq_q, q_off, nq, nkv, d, o_lse2, o_dkv, o_dq, need, pairs_max, chunked);
   if (!ws || ws_bytes < need) DH_FAIL(DH_ERR_WORKSPACE_TOO_SMALL, "attn_bwd: workspace %zu < %zu bytes", ws_bytes, need);
   float* lse2 = (float*)((char*)ws + o_lse2);
   float* part_kv = (nq > nkv || chunked) ? (float*)((char*)ws + o_dkv) : nullptr;
   float* part_q = chunked ? (float*)((char*)ws + o_dq) : nullptr;
   const float sc = (float)(1.0 / sqrt((double)d)), sl2 = (float)(1.4426950408889634 / sqrt((double)d));
-  const int nblk = (seq + 127) / 128, pq = total_pairs_dq(seq), pk = total_pairs_dkv(seq);
-  dim3 gwq(pq, nq, batch), gwk(pk, nq, batch), gq(nblk * 8, nq, batch), gk(nblk * 8, nkv, batch);
+  const int nblk = (seq + 127) / 128, nblk_q = nblk - q_off / 128, pq = total_pairs_dq(seq, q_off), pk = total_pairs_dkv(seq, q_off);
+  dim3 gwq(pq, nq, batch), gwk(pk, nq, batch), gq(nblk_q * 8, nq, batch), gk(nblk * 8, nkv, batch);
   const unsigned nprep = (unsigned)(((size_t)T * nq + 3) / 4);
   const size_t lds_dq = 2 * AB_RING * (size_t)AB_KT * d * 2, lds_dkv = lds_dq + 2 * AB_RING * AB_KT * sizeof(float);
   static bool ready[2] = {false, false};
-  int rc;
 #define DH_ATTN_BWD(DD, IDX)                                                                                                   \
   do {                                                                                                                         \
     if (!ready[IDX]) {                                                                                                         \
@@ -966,12 +1009,12 @@ int dh_launch_attn_bwd_bf16(int batch, int seq, int nq, int nkv, int d, const bf
     }                                                                                                                          \
     attn_bwd_prep_kernel<DD><<<nprep, 256, 0, stream>>>(nq, o, dout, lse, delta, lse2, T);                                       \
     DH_LAUNCH_CHECK();                                                                                                         \
-    attn_bwd_dq_bf16_kernel<DD><<<gwq, AB_THREADS, lds_dq, stream>>>(seq, nq, nkv, qkv, dout, lse2, delta, dqkv, part_q, pq, T, sc, sl2); \
+    attn_bwd_dq_bf16_kernel<DD><<<gwq, AB_THREADS, lds_dq, stream>>>(g, qkv, dout, lse2, delta, dqkv, part_q, pq, T, sc, sl2);   \
     DH_LAUNCH_CHECK();                                                                                                         \
-    if (part_q) { attn_bwd_dq_reduce_kernel<DD><<<gq, 256, 0, stream>>>(part_q, dqkv, seq, nq, nkv, pq, sc); DH_LAUNCH_CHECK(); } \
-    attn_bwd_dkv_bf16_kernel<DD><<<gwk, AB_THREADS, lds_dkv, stream>>>(seq, nq, nkv, qkv, dout, lse2, delta, dqkv, part_kv, pk, T, sc, sl2); \
+    if (part_q) { attn_bwd_dq_reduce_kernel<DD><<<gq, 256, 0, stream>>>(part_q, dqkv, seq, q_off, nq, nkv, pq, sc); DH_LAUNCH_CHECK(); } \
+    attn_bwd_dkv_bf16_kernel<DD><<<gwk, AB_THREADS, lds_dkv, stream>>>(g, qkv, dout, lse2, delta, part_kv, pk, T, sc, sl2);      \
     DH_LAUNCH_CHECK();                                                                                                         \
-    if (part_kv) { attn_bwd_group_reduce_kernel<DD><<<gk, 256, 0, stream>>>(part_kv, dqkv, seq, nq, nkv, pk); DH_LAUNCH_CHECK(); } \
+    if (part_kv) { attn_bwd_group_reduce_kernel<DD><<<gk, 256, 0, stream>>>(part_kv, g, pk); DH_LAUNCH_CHECK(); }                \
   } while (0)
   if (d == 128) DH_ATTN_BWD(128, 0); else DH_ATTN_BWD(64, 1);
 #undef DH_ATTN_BWD

@@ -124,14 +124,17 @@ int dh_launch_gemm_grouped_f32(int mode, int n_groups, const int32_t* group_rows
 int dh_launch_gemm_grouped_bf16(int mode, int n_groups, const int32_t* group_rows, int max_rows, int dim_a, int dim_b,
                                 const bf16_t* A, const bf16_t* B, void* C, hipStream_t stream);
 size_t dh_gemm_bf16_ws_bytes(bool ta, bool tb, int M, int N, int K);
-int dh_launch_attn_fwd_f32(int batch, int seq, int nq, int nkv, int d, const float* qkv, float* o, float* lse,
-                           hipStream_t stream);
-int dh_launch_attn_bwd_f32(int batch, int seq, int nq, int nkv, int d, const float* qkv, const float* o,
-                           const float* dout, const float* lse, float* dqkv, float* delta, hipStream_t stream);
-int dh_launch_attn_fwd_bf16(int batch, int seq, int nq, int nkv, int d, const bf16_t* qkv, bf16_t* o, float* lse, void* ws,
-                            size_t ws_bytes, hipStream_t stream);
-size_t dh_attn_fwd_bf16_ws_bytes(int batch, int seq, int nq, int nkv, int d);
-int dh_launch_attn_bwd_bf16(int batch, int seq, int nq, int nkv, int d, const bf16_t* qkv, const bf16_t* o,
-                            const bf16_t* dout, const float* lse, bf16_t* dqkv, float* delta, void* ws, size_t ws_bytes,
-                            hipStream_t stream);
-size_t dh_attn_bwd_bf16_ws_bytes(int batch, int seq, int nq, int nkv, int d);
+// Attention launchers: seq = queries per sequence; kv == nullptr selects plain causal attention over the packed
+// qkv rows, otherwise keys/values come from kv[batch*(q_off+seq), ldkv] and their gradients go to dkv likewise.
+int dh_launch_attn_fwd_f32(int batch, int seq, int nq, int nkv, int d, const float* qkv, const float* kv, int ldkv,
+                           int q_off, float* o, float* lse, hipStream_t stream);
+int dh_launch_attn_bwd_f32(int batch, int seq, int nq, int nkv, int d, const float* qkv, const float* kv, int ldkv,
+                           int q_off, const float* o, const float* dout, const float* lse, float* dqkv, float* dkv, int lddkv,
+                           float* delta, hipStream_t stream);
+int dh_launch_attn_fwd_bf16(int batch, int seq, int nq, int nkv, int d, const bf16_t* qkv, const bf16_t* kv, int ldkv, int q_off,
+                            bf16_t* o, float* lse, void* ws, size_t ws_bytes, hipStream_t stream);
+size_t dh_attn_fwd_bf16_ws_bytes(int batch, int seq, int q_off, int nq, int nkv, int d);
+int dh_launch_attn_bwd_bf16(int batch, int seq, int nq, int nkv, int d, const bf16_t* qkv, const bf16_t* kv, int ldkv, int q_off,
+                            const bf16_t* o, const bf16_t* dout, const float* lse, bf16_t* dqkv, bf16_t* dkv, int lddkv,
+                            float* delta, void* ws, size_t ws_bytes, hipStream_t stream);
+size_t dh_attn_bwd_bf16_ws_bytes(int batch, int seq, int q_off, int nq, int nkv, int d);

@@ -205,7 +205,7 @@ extern "C" int dh_layer_create(const dh_layer_config* cfg, dh_layer** out) {
   L->f_red = take(cur, moe ? 0 : Ts * H * es);
   L->f_xp = take(cur, moe ? Tf * H * es : 0);
   L->f_yg = take(cur, moe ? Tf * H * es : 0);
-  L->f_attn_bytes = bf ? dh_attn_fwd_bf16_ws_bytes(c.batch, c.seq, c.n_q_heads, c.n_kv_heads, c.head_dim) : 0;
+  L->f_attn_bytes = bf ? dh_attn_fwd_bf16_ws_bytes(c.batch, c.seq, 0, c.n_q_heads, c.n_kv_heads, c.head_dim) : 0;
   L->f_attn = take(cur, L->f_attn_bytes);
   size_t fg = std::max(gw(0, 0, T, L->n_qkv, H), gw(0, 0, T, H, L->n_o));
   if (!moe) fg = std::max(fg, std::max(gw(0, 0, T, Fin, H), gw(0, 0, T, H, F)));
@@ -223,7 +223,7 @@ extern "C" int dh_layer_create(const dh_layer_config* cfg, dh_layer** out) {
   L->b_do = take(cur, T * L->n_o * es);
   L->b_dqkv = take(cur, T * L->n_qkv * es);
   L->b_delta = take(cur, (size_t)c.n_q_heads * T * 4);
-  L->b_attn_bytes = bf ? dh_attn_bwd_bf16_ws_bytes(c.batch, c.seq, c.n_q_heads, c.n_kv_heads, c.head_dim) : 0;
+  L->b_attn_bytes = bf ? dh_attn_bwd_bf16_ws_bytes(c.batch, c.seq, 0, c.n_q_heads, c.n_kv_heads, c.head_dim) : 0;
   L->b_attn = take(cur, L->b_attn_bytes);
   L->b_norm_bytes = gpt ? dh_layernorm_bwd_ws_bytes(L->Ts, c.hidden) : dh_rmsnorm_bwd_ws_bytes(L->Ts, c.hidden);
   L->b_norm = take(cur, L->b_norm_bytes);

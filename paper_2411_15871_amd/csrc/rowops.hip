@@ -166,7 +166,7 @@ __global__ void colsum_accumulate_kernel(const float* __restrict__ partial, floa
 // pairs (i, i + d/2).  Angles are formed in double so that position*theta keeps full fp32 accuracy
 // at long sequences.
 template <typename T>
-__global__ void rope_kernel(T* __restrict__ t, int rows, int seq, int n_heads, int d, int row_stride, double log2_base,
+__global__ void rope_kernel(T* __restrict__ t, int rows, int seq, int pos0, int n_heads, int d, int row_stride, double log2_base,
                             int inverse) {
   int half = d / 2;
   int chunks = half / 8;
@@ -176,7 +176,7 @@ __global__ void rope_kernel(T* __restrict__ t, int rows, int seq, int n_heads, i
   int c = (int)(idx % chunks);
   int head = (int)((idx / chunks) % n_heads);
   size_t row = idx / ((size_t)chunks * n_heads);
-  int pos = (int)(row % seq);
+  int pos = pos0 + (int)(row % seq);
   T* pa = t + row * row_stride + (size_t)head * d + c * 8;
   T* pb = pa + half;
   Vec8<T> a, b, oa, ob;
@@ -327,7 +327,12 @@ extern "C" int dh_rmsnorm_bwd(int dtype, int T, int H, const void* dy, const voi
 
 extern "C" int dh_rope(int dtype, int T, int seq, int n_heads, int head_dim, int row_stride, float base, int inverse,
                        void* t, void* stream) {
-  if (T < 0 || seq <= 0 || n_heads <= 0 || head_dim <= 0 || head_dim % 16 || row_stride % 8 || row_stride < n_heads * head_dim)
+  return dh_rope_at(dtype, T, seq, 0, n_heads, head_dim, row_stride, base, inverse, t, stream);
+}
+
+extern "C" int dh_rope_at(int dtype, int T, int seq, int pos0, int n_heads, int head_dim, int row_stride, float base, int inverse,
+                          void* t, void* stream) {
+  if (T < 0 || seq <= 0 || pos0 < 0 || n_heads <= 0 || head_dim <= 0 || head_dim % 16 || row_stride % 8 || row_stride < n_heads * head_dim)
     DH_FAIL(DH_ERR_SHAPE, "rope: T=%d seq=%d heads=%d d=%d stride=%d (d must be a multiple of 16)", T, seq, n_heads,
             head_dim, row_stride);
   if (T == 0) return DH_OK;
@@ -336,9 +341,9 @@ extern "C" int dh_rope(int dtype, int T, int seq, int n_heads, int head_dim, int
   dim3 g((unsigned)((total + 255) / 256)), b(256);
   double l2b = log2((double)base);
   if (dtype == DH_BF16)
-    rope_kernel<bf16_t><<<g, b, 0, (hipStream_t)stream>>>((bf16_t*)t, T, seq, n_heads, head_dim, row_stride, l2b, inverse);
+    rope_kernel<bf16_t><<<g, b, 0, (hipStream_t)stream>>>((bf16_t*)t, T, seq, pos0, n_heads, head_dim, row_stride, l2b, inverse);
   else
-    rope_kernel<float><<<g, b, 0, (hipStream_t)stream>>>((float*)t, T, seq, n_heads, head_dim, row_stride, l2b, inverse);
+    rope_kernel<float><<<g, b, 0, (hipStream_t)stream>>>((float*)t, T, seq, pos0, n_heads, head_dim, row_stride, l2b, inverse);
   DH_LAUNCH_CHECK();
   return DH_OK;
 }

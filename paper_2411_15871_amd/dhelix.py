@@ -148,6 +148,7 @@ SIGNATURES = {
     "dh_rmsnorm_bwd": (_I, [_I, _I, _I, _P, _P, _P, _P, _P, _P, _P, _P, _Z, _P]),
     "dh_rmsnorm_bwd_ws_bytes": (_Z, [_I, _I]),
     "dh_rope": (_I, [_I, _I, _I, _I, _I, _I, _F, _I, _P, _P]),
+    "dh_rope_at": (_I, [_I, _I, _I, _I, _I, _I, _I, _F, _I, _P, _P]),
     "dh_swiglu_fwd": (_I, [_I, _I, _I, _P, _P, _P]),
     "dh_swiglu_bwd": (_I, [_I, _I, _I, _P, _P, _P, _P]),
     "dh_add": (_I, [_I, _Z, _P, _P, _P, _P]),
@@ -155,6 +156,10 @@ SIGNATURES = {
     "dh_attn_fwd_workspace_bytes": (_Z, [_I, _I, _I, _I, _I, _I]),
     "dh_attn_bwd": (_I, [_I, _I, _I, _I, _I, _I, _P, _P, _P, _P, _P, _P, _P, _Z, _P]),
     "dh_attn_bwd_workspace_bytes": (_Z, [_I, _I, _I, _I, _I, _I]),
+    "dh_attn_ctx_fwd": (_I, [_I, _I, _I, _I, _I, _I, _I, _P, _P, _P, _P, _P, _Z, _P]),
+    "dh_attn_ctx_fwd_workspace_bytes": (_Z, [_I, _I, _I, _I, _I, _I, _I]),
+    "dh_attn_ctx_bwd": (_I, [_I, _I, _I, _I, _I, _I, _I, _P, _P, _P, _P, _P, _P, _P, _P, _P, _Z, _P]),
+    "dh_attn_ctx_bwd_workspace_bytes": (_Z, [_I, _I, _I, _I, _I, _I, _I]),
     "dh_moe_route": (_I, [_I, _I, _P, _P, _P, _P]),
     "dh_moe_route_bwd": (_I, [_I, _I, _P, _P, _P, _P, _P]),
     "dh_moe_plan": (_I, [_I, _I, _I, _P, C.POINTER(dh_moe_tables), _P]),
@@ -475,6 +480,28 @@ def dh_swiglu_bwd(dtype, T, F, gu, da, dgu, stream=None):
 
 def dh_add(dtype, n, a, b, out, stream=None):
     _check(lib.dh_add(dtype, n, _ptr(a), _ptr(b), _ptr(out), _stream(stream)))
+
+
+def dh_rope_at(dtype, T, seq, pos0, n_heads, head_dim, row_stride, base, inverse, t, stream=None):
+    _check(lib.dh_rope_at(dtype, T, seq, pos0, n_heads, head_dim, row_stride, base, int(inverse), _ptr(t), _stream(stream)))
+
+
+def dh_attn_ctx_fwd(dtype, batch, seq, q_off, nq, nkv, d, qkv, kv, o, lse, ws=None, ws_bytes=0, stream=None):
+    _check(lib.dh_attn_ctx_fwd(dtype, batch, seq, q_off, nq, nkv, d, _ptr(qkv), _ptr(kv), _ptr(o), _ptr(lse), _ptr(ws), ws_bytes,
+                               _stream(stream)))
+
+
+def dh_attn_ctx_fwd_workspace_bytes(dtype, batch, seq, q_off, nq, nkv, d):
+    return lib.dh_attn_ctx_fwd_workspace_bytes(dtype, batch, seq, q_off, nq, nkv, d)
+
+
+def dh_attn_ctx_bwd(dtype, batch, seq, q_off, nq, nkv, d, qkv, kv, o, dout, lse, dqkv, dkv, delta, ws=None, ws_bytes=0, stream=None):
+    _check(lib.dh_attn_ctx_bwd(dtype, batch, seq, q_off, nq, nkv, d, _ptr(qkv), _ptr(kv), _ptr(o), _ptr(dout), _ptr(lse), _ptr(dqkv),
+                               _ptr(dkv), _ptr(delta), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def dh_attn_ctx_bwd_workspace_bytes(dtype, batch, seq, q_off, nq, nkv, d):
+    return lib.dh_attn_ctx_bwd_workspace_bytes(dtype, batch, seq, q_off, nq, nkv, d)
 
 
 def dh_attn_fwd(dtype, batch, seq, nq, nkv, d, qkv, o, lse, ws=None, ws_bytes=0, stream=None):
