@@ -47,8 +47,10 @@ typedef enum { DH_F32 = 0, DH_BF16 = 1 } dh_dtype;
  * DH_ARCH_GPT:   LayerNorm, biases, GeLU, tensor + sequence parallel (all-gather / reduce-scatter; GPT
  *                models of Table 3).
  * DH_ARCH_MOE:   Llama-style attention (not sharded) + top-2 mixture-of-experts SwiGLU FFN under expert
- *                parallelism (all-to-all dispatch / combine; MoE models of Table 3). */
-typedef enum { DH_ARCH_LLAMA = 0, DH_ARCH_GPT = 1, DH_ARCH_MOE = 2 } dh_arch;
+ *                parallelism (all-to-all dispatch / combine; MoE models of Table 3).
+ * DH_ARCH_LLAMA_CP: DH_ARCH_LLAMA on one rank of a context-parallel group (Sec. 2.1): the rank holds one chunk of
+ *                each sequence and collects the earlier chunks' keys/values by Send/Recv (Sec. 2.2). */
+typedef enum { DH_ARCH_LLAMA = 0, DH_ARCH_GPT = 1, DH_ARCH_MOE = 2, DH_ARCH_LLAMA_CP = 3 } dh_arch;
 
 /* Message of the last error raised on this thread ("" if none).  Host memory owned by the library. */
 const char* dh_last_error(void);
@@ -63,6 +65,12 @@ const char* dh_last_error(void);
  * DH_ARCH_MOE: no tensor parallelism; the FFN is routed: top-2 of n_experts logical experts, of which
  * this GPU holds n_local_experts (logical expert e runs on local expert e % n_local_experts, the
  * other factor of e standing for the source rank of an expert-parallel group).
+ * DH_ARCH_LLAMA_CP: seq is the length of this rank's chunk; its rows sit at positions cp_rank*seq .. of each
+ * sequence (contiguous chunks in rank order).  After RoPE the rank's keys/values and those of the cp_rank earlier
+ * ranks are gathered into one buffer (the chunks of later ranks pass through the rank too, as on a ring, but no causal
+ * query reads them); attention runs over that buffer; in the backward pass the key/value gradients of the earlier
+ * chunks are sent back and the rank adds what the later ranks send for its own chunk.  bf16: cp_rank*seq must be
+ * a multiple of 128.
  * ------------------------------------------------------------------------------------------ */
 typedef struct {
   int arch;        /* dh_arch */
@@ -81,6 +89,10 @@ typedef struct {
                       to cover the payload */
   int n_experts;       /* DH_ARCH_MOE: logical experts E (2..256); else 0 */
   int n_local_experts; /* DH_ARCH_MOE: experts held by this GPU, divides E; else 0 */
+  int cp_ranks;        /* DH_ARCH_LLAMA_CP: ranks of the context-parallel group (1..16); else 0 */
+  int cp_rank;         /* DH_ARCH_LLAMA_CP: this rank's index, 0 .. cp_ranks-1 */
+  int cross_blocks;    /* DH_ARCH_LLAMA_CP: thread blocks of a Send/Recv stand-in (the cross-node link's rate);
+                          0 = one block */
 } dh_layer_config;
 
 /* Device pointers to the shard's weights (read only).  g1,g2: [H]; Wqkv: [H,(nq+2nkv)d] with columns
@@ -126,7 +138,9 @@ size_t dh_layer_workspace_bytes(const dh_layer* layer, int kind);
  * (ignored when n_ranks == 1): DH_ARCH_LLAMA [R-1,T,H] partials of the all-reduces; DH_ARCH_GPT
  * [R-1,Ts,H] partials of the reduce-scatters for this rank's rows.
  * peers_ag1/peers_ag2: DH_ARCH_GPT only, [R-1,Ts,H] the other ranks' shards entering the all-gathers.
- * logits: DH_ARCH_MOE only, float32 [T,n_experts] router logits (an input of the layer). */
+ * logits: DH_ARCH_MOE only, float32 [T,n_experts] router logits (an input of the layer).
+ * peers_kv: DH_ARCH_LLAMA_CP only, [cp_ranks-1, T, 2*nkv*d]: the other ranks' key/value chunks ([k heads | v heads]
+ * per row, keys rotated), ordered by source rank with this rank left out (ignored when cp_ranks == 1). */
 typedef struct {
   const void* x;
   void* out;
@@ -136,6 +150,7 @@ typedef struct {
   const void* peers_ag1;
   const void* peers_ag2;
   const float* logits;
+  const void* peers_kv;
 } dh_fwd_args;
 
 /* One strand's backward call.  dout: device [T,H] upstream gradient; dx: device [T,H] result;
@@ -151,6 +166,10 @@ typedef struct {
   const void* peers_ag3; /* DH_ARCH_GPT: [R-1,Ts,H] peers' gradient shards of the backward all-gathers */
   const void* peers_ag4;
   float* dlogits;        /* DH_ARCH_MOE: float32 [T,n_experts] gradient of the router logits (written) */
+  const void* peers_dkv; /* DH_ARCH_LLAMA_CP: [cp_ranks-1, T, 2*nkv*d] the other ranks' gradient contributions to this
+                            rank's keys/values (order of peers_kv); those of the later ranks are added */
+  void* dkv_peers;       /* DH_ARCH_LLAMA_CP: [cp_rank, T, 2*nkv*d] (written) the key/value gradients this rank sends
+                            back to each earlier rank */
 } dh_bwd_args;
 
 /* Forward / backward of one strand, operators in their default order, all on `stream`
@@ -196,11 +215,23 @@ typedef enum {
   DH_MB_NORM1, DH_MB_NOPS
 } dh_moe_bwd_op;
 
+/* DH_ARCH_LLAMA_CP: the Llama operators plus the key/value exchange and the gradient send-back. */
+typedef enum {
+  DH_CF_NORM1 = 0, DH_CF_QKV, DH_CF_ROPE, DH_CF_CP_KV, DH_CF_ATTN, DH_CF_PROJ, DH_CF_AR1, DH_CF_NORM2, DH_CF_FC1,
+  DH_CF_ACT, DH_CF_FC2, DH_CF_AR2, DH_CF_BDA2, DH_CF_NOPS
+} dh_cp_fwd_op;
+typedef enum {
+  DH_CB_FC2_DGRAD = 0, DH_CB_FC2_WGRAD, DH_CB_ACT, DH_CB_FC1_DGRAD, DH_CB_FC1_WGRAD, DH_CB_AR3, DH_CB_NORM2,
+  DH_CB_PROJ_DGRAD, DH_CB_PROJ_WGRAD, DH_CB_ATTN, DH_CB_CP_DKV, DH_CB_ROPE, DH_CB_QKV_DGRAD, DH_CB_QKV_WGRAD,
+  DH_CB_AR4, DH_CB_NORM1, DH_CB_NOPS
+} dh_cp_bwd_op;
+
 #define DH_MAX_OPS 32
 #define DH_MAX_DEPS 96
 typedef struct {
   int n_ops;
-  int is_comm[DH_MAX_OPS];   /* 1 = collective stand-in (issued on the communication stream) */
+  int is_comm[DH_MAX_OPS];   /* 1 = collective stand-in (issued on the communication stream); 2 = cross-node
+                                Send/Recv stand-in (issued on the layer's cross-node stream if one is set) */
   int n_deps;
   int dep_src[DH_MAX_DEPS];
   int dep_dst[DH_MAX_DEPS];
@@ -291,6 +322,11 @@ int dh_si_step(dh_layer* layer, const dh_fwd_args* alpha, const dh_bwd_args* bet
                const dh_plan* plan, void* ws, size_t ws_bytes, void* stream_alpha,
                void* stream_beta, void* stream_comm);
 
+/* Stream for the cross-node Send/Recv stand-ins of later SI steps of this layer (Sec. 5: computation, local-node
+ * and cross-node communication each get a stream); NULL (the default) issues them where the collective stand-ins
+ * go.  The stream must outlive those steps; each step joins it back into stream_alpha.  Host only. */
+int dh_layer_set_cross_stream(dh_layer* layer, void* stream_cross);
+
 /* One SI step across two layers of identical shape: forward of strand alpha through layer_alpha while
  * strand beta runs backward through layer_beta (each layer has its own weights and gradient buffers).
  * dh_si_step is the case layer_alpha == layer_beta. */
@@ -356,6 +392,25 @@ void dh_si_graph_destroy(dh_si_graph* graph);
 typedef enum { DH_COMM_ALLREDUCE = 0, DH_COMM_ALLGATHER = 1, DH_COMM_REDUCESCATTER = 2 } dh_comm_kind;
 int dh_comm_standin(int kind, int n_ranks, const void* const* parts, void* out, size_t elems,
                     int dtype, int n_blocks, void* stream);
+
+/* Context parallelism (Sec. 2.1, Sec. 2.2: CP ranks pass key/value chunks around by Send/Recv; Sec. 5: such
+ * cross-node transfers get a stream of their own).  One-GPU stand-in of the exchange: n_moves (<= 16) copies, each
+ * of `rows` rows of `width` elements (multiple of 8) for each of `batch` sequences.  A side of a move is a row-major
+ * buffer with a row pitch of ld elements holding seq_rows rows per sequence, of which the move touches rows
+ * row0 .. row0+rows-1.  Device pointers, 16-byte aligned; n_blocks as for dh_comm_standin (one or two blocks move
+ * data at about the rate of a network link, which is what the transfer is a stand-in for). */
+typedef struct {
+  const void* src;
+  void* dst;
+  int src_ld, src_seq_rows, src_row0;
+  int dst_ld, dst_seq_rows, dst_row0;
+} dh_cp_move;
+int dh_cp_exchange(int dtype, int n_moves, const dh_cp_move* moves, int batch, int rows, int width, int n_blocks,
+                   void* stream);
+/* The key/value gradient a CP rank keeps: own->dst rows = own->src rows + peers[0] + peers[1] + ... (added in that
+ * order in float32, rounded once); peers[k]: device [batch*rows, width] contiguous. */
+int dh_cp_grad_reduce(int dtype, const dh_cp_move* own, int n_peers, const void* const* peers, int batch, int rows,
+                      int width, int n_blocks, void* stream);
 
 /* Creates a stream whose kernels may only use n_cus compute units (spread over the chip), the
  * analogue of limiting a collective's thread/channel count (Sec. 5).  Default priority. */

@@ -20,7 +20,10 @@ struct dh_layer {
   bool have_w, have_g;
   // saved-slot offsets (bytes)
   size_t s_mu1, s_rstd1, s_h1, s_qkv, s_o, s_lse, s_x2, s_mu2, s_rstd2, s_h2, s_gu, s_a;
-  size_t s_idx, s_prob, s_tab[9], s_xg, s_yp, saved_bytes;
+  size_t s_idx, s_prob, s_tab[9], s_xg, s_yp, s_kv, saved_bytes;
+  int q_off, kv_w;  // context parallelism: first position of this rank's chunk; elements of a key/value row
+  size_t f_kvrecv, b_dkv;
+  hipStream_t cross_stream;
   // forward workspace offsets
   size_t f_hs, f_part, f_red, f_xp, f_yg, f_attn, f_attn_bytes, f_gemm, f_gemm_bytes, fwd_bytes;
   // backward workspace offsets
@@ -42,6 +45,11 @@ static const char* kGptFwd[DH_GF_NOPS] = {"F_NORM1", "F_AG1", "F_QKV", "F_ATTN",
 static const char* kGptBwd[DH_GB_NOPS] = {"B_AG3", "B_FC2_DGRAD", "B_FC2_WGRAD", "B_ACT", "B_FC1_DGRAD", "B_FC1_WGRAD",
                                           "B_RS3", "B_NORM2", "B_AG4", "B_PROJ_DGRAD", "B_PROJ_WGRAD", "B_ATTN",
                                           "B_QKV_DGRAD", "B_QKV_WGRAD", "B_RS4", "B_NORM1"};
+static const char* kCpFwd[DH_CF_NOPS] = {"F_NORM1", "F_QKV", "F_ROPE", "F_CP_KV", "F_ATTN", "F_PROJ", "F_AR1",
+                                         "F_NORM2", "F_FC1", "F_ACT", "F_FC2", "F_AR2", "F_BDA2"};
+static const char* kCpBwd[DH_CB_NOPS] = {"B_FC2_DGRAD", "B_FC2_WGRAD", "B_ACT", "B_FC1_DGRAD", "B_FC1_WGRAD", "B_AR3",
+                                         "B_NORM2", "B_PROJ_DGRAD", "B_PROJ_WGRAD", "B_ATTN", "B_CP_DKV", "B_ROPE",
+                                         "B_QKV_DGRAD", "B_QKV_WGRAD", "B_AR4", "B_NORM1"};
 static const char* kMoeFwd[DH_MF_NOPS] = {"F_NORM1", "F_QKV", "F_ROPE", "F_ATTN", "F_PROJ", "F_NORM2", "F_ROUTE",
                                           "F_PERMUTE", "F_A2A_DISPATCH", "F_FC1", "F_ACT", "F_FC2", "F_A2A_COMBINE",
                                           "F_UNPERMUTE"};
@@ -58,6 +66,7 @@ extern "C" const char* dh_op_name(int arch, int direction, int op) {
     case DH_ARCH_LLAMA: names = direction ? kLlamaBwd : kLlamaFwd; n = direction ? DH_B_NOPS : DH_F_NOPS; break;
     case DH_ARCH_GPT: names = direction ? kGptBwd : kGptFwd; n = direction ? DH_GB_NOPS : DH_GF_NOPS; break;
     case DH_ARCH_MOE: names = direction ? kMoeBwd : kMoeFwd; n = direction ? DH_MB_NOPS : DH_MF_NOPS; break;
+    case DH_ARCH_LLAMA_CP: names = direction ? kCpBwd : kCpFwd; n = direction ? DH_CB_NOPS : DH_CF_NOPS; break;
     default: return nullptr;
   }
   return op >= 0 && op < n ? names[op] : nullptr;
@@ -97,6 +106,19 @@ static void build_graphs(dh_layer* L) {
     add_dep(b, DH_B_ROPE, DH_B_QKV_WGRAD);    // needs dqkv
     // FC2_WGRAD needs only the upstream gradient and the saved activation: no predecessor.
     b.is_comm[DH_B_AR3] = b.is_comm[DH_B_AR4] = 1;
+  } else if (L->c.arch == DH_ARCH_LLAMA_CP) {
+    f.n_ops = DH_CF_NOPS;
+    for (int i = 0; i + 1 < DH_CF_NOPS; i++) add_dep(f, i, i + 1);
+    f.is_comm[DH_CF_AR1] = f.is_comm[DH_CF_AR2] = 1;
+    f.is_comm[DH_CF_CP_KV] = 2;
+    b.n_ops = DH_CB_NOPS;
+    CHAIN(b, DH_CB_FC2_DGRAD, DH_CB_ACT, DH_CB_FC1_DGRAD, DH_CB_AR3, DH_CB_NORM2, DH_CB_PROJ_DGRAD, DH_CB_ATTN, DH_CB_CP_DKV,
+          DH_CB_ROPE, DH_CB_QKV_DGRAD, DH_CB_AR4, DH_CB_NORM1);
+    add_dep(b, DH_CB_ACT, DH_CB_FC1_WGRAD);
+    add_dep(b, DH_CB_NORM2, DH_CB_PROJ_WGRAD);
+    add_dep(b, DH_CB_ROPE, DH_CB_QKV_WGRAD);
+    b.is_comm[DH_CB_AR3] = b.is_comm[DH_CB_AR4] = 1;
+    b.is_comm[DH_CB_CP_DKV] = 2;
   } else if (L->c.arch == DH_ARCH_GPT) {
     f.n_ops = DH_GF_NOPS;
     for (int i = 0; i + 1 < DH_GF_NOPS; i++) add_dep(f, i, i + 1);
@@ -142,7 +164,7 @@ static size_t take(size_t& cur, size_t bytes) {
 extern "C" int dh_layer_create(const dh_layer_config* cfg, dh_layer** out) {
   if (!cfg || !out) DH_FAIL(DH_ERR_INVALID_ARG, "layer_create: null pointer");
   const dh_layer_config& c = *cfg;
-  if (c.arch != DH_ARCH_LLAMA && c.arch != DH_ARCH_GPT && c.arch != DH_ARCH_MOE)
+  if (c.arch != DH_ARCH_LLAMA && c.arch != DH_ARCH_GPT && c.arch != DH_ARCH_MOE && c.arch != DH_ARCH_LLAMA_CP)
     DH_FAIL(DH_ERR_UNSUPPORTED, "layer_create: arch %d not supported", c.arch);
   if (c.dtype != DH_F32 && c.dtype != DH_BF16) DH_FAIL(DH_ERR_INVALID_ARG, "layer_create: dtype %d", c.dtype);
   if (c.batch < 0 || c.seq < 0 || c.hidden <= 0 || c.n_q_heads <= 0 || c.n_kv_heads <= 0 || c.head_dim <= 0 || c.ffn <= 0)
@@ -162,8 +184,20 @@ extern "C" int dh_layer_create(const dh_layer_config* cfg, dh_layer** out) {
       DH_FAIL(DH_ERR_SHAPE, "layer_create: n_experts %d (2..256) must be a multiple of n_local_experts %d (1..64)", c.n_experts, c.n_local_experts);
     if (c.n_ranks != 1) DH_FAIL(DH_ERR_INVALID_ARG, "layer_create: the MoE layer has no tensor-parallel peers (n_ranks must be 1)");
   }
+  const bool cp = c.arch == DH_ARCH_LLAMA_CP;
+  if (cp) {
+    if (c.cp_ranks < 1 || c.cp_ranks > 16 || c.cp_rank < 0 || c.cp_rank >= c.cp_ranks)
+      DH_FAIL(DH_ERR_INVALID_ARG, "layer_create: cp_rank %d / cp_ranks %d (1..16)", c.cp_rank, c.cp_ranks);
+    if ((long long)c.cp_rank * c.seq > (1 << 24)) DH_FAIL(DH_ERR_SHAPE, "layer_create: context too long");
+    if (c.dtype == DH_BF16 && (c.cp_rank * c.seq) % 128)
+      DH_FAIL(DH_ERR_SHAPE, "layer_create: bf16 context parallelism needs cp_rank*seq = %d to be a multiple of 128", c.cp_rank * c.seq);
+    if (c.cross_blocks < 0 || c.cross_blocks > 65536) DH_FAIL(DH_ERR_INVALID_ARG, "layer_create: cross_blocks %d outside 0..65536", c.cross_blocks);
+  }
   dh_layer* L = new dh_layer();
   L->c = c;
+  L->cross_stream = nullptr;
+  L->q_off = cp ? c.cp_rank * c.seq : 0;
+  L->kv_w = 2 * c.n_kv_heads * c.head_dim;
   L->T = c.batch * c.seq;
   L->Ts = c.arch == DH_ARCH_GPT ? L->T / c.n_ranks : L->T;
   L->Tf = c.arch == DH_ARCH_MOE ? 2 * L->T : L->T;
@@ -194,6 +228,8 @@ extern "C" int dh_layer_create(const dh_layer_config* cfg, dh_layer** out) {
   for (int i = 0; i < 9; i++) L->s_tab[i] = take(cur, moe ? tab_ints[i] * 4 : 0);
   L->s_xg = take(cur, moe ? Tf * H * es : 0);
   L->s_yp = take(cur, moe ? Tf * H * es : 0);
+  const size_t kv_rows = (size_t)c.batch * (L->q_off + c.seq);  // key/value rows a context-parallel rank attends to
+  L->s_kv = take(cur, cp ? kv_rows * L->kv_w * es : 0);
   L->saved_bytes = cur;
   const bool bf = c.dtype == DH_BF16;
   auto gw = [&](bool ta, bool tb, size_t M, size_t N, size_t K) {
@@ -205,7 +241,8 @@ extern "C" int dh_layer_create(const dh_layer_config* cfg, dh_layer** out) {
   L->f_red = take(cur, moe ? 0 : Ts * H * es);
   L->f_xp = take(cur, moe ? Tf * H * es : 0);
   L->f_yg = take(cur, moe ? Tf * H * es : 0);
-  L->f_attn_bytes = bf ? dh_attn_fwd_bf16_ws_bytes(c.batch, c.seq, 0, c.n_q_heads, c.n_kv_heads, c.head_dim) : 0;
+  L->f_kvrecv = take(cur, cp ? (size_t)(c.cp_ranks - 1 - c.cp_rank) * T * L->kv_w * es : 0);  // later ranks' chunks pass through
+  L->f_attn_bytes = bf ? dh_attn_fwd_bf16_ws_bytes(c.batch, c.seq, L->q_off, c.n_q_heads, c.n_kv_heads, c.head_dim) : 0;
   L->f_attn = take(cur, L->f_attn_bytes);
   size_t fg = std::max(gw(0, 0, T, L->n_qkv, H), gw(0, 0, T, H, L->n_o));
   if (!moe) fg = std::max(fg, std::max(gw(0, 0, T, Fin, H), gw(0, 0, T, H, F)));
@@ -223,7 +260,8 @@ extern "C" int dh_layer_create(const dh_layer_config* cfg, dh_layer** out) {
   L->b_do = take(cur, T * L->n_o * es);
   L->b_dqkv = take(cur, T * L->n_qkv * es);
   L->b_delta = take(cur, (size_t)c.n_q_heads * T * 4);
-  L->b_attn_bytes = bf ? dh_attn_bwd_bf16_ws_bytes(c.batch, c.seq, 0, c.n_q_heads, c.n_kv_heads, c.head_dim) : 0;
+  L->b_dkv = take(cur, cp ? kv_rows * L->kv_w * es : 0);
+  L->b_attn_bytes = bf ? dh_attn_bwd_bf16_ws_bytes(c.batch, c.seq, L->q_off, c.n_q_heads, c.n_kv_heads, c.head_dim) : 0;
   L->b_attn = take(cur, L->b_attn_bytes);
   L->b_norm_bytes = gpt ? dh_layernorm_bwd_ws_bytes(L->Ts, c.hidden) : dh_rmsnorm_bwd_ws_bytes(L->Ts, c.hidden);
   L->b_norm = take(cur, L->b_norm_bytes);
@@ -283,6 +321,12 @@ extern "C" int dh_layer_bind_wgrads(dh_layer* L, const dh_wgrads* g) {
 }
 
 extern "C" size_t dh_layer_saved_bytes(const dh_layer* L) { return L ? L->saved_bytes : 0; }
+
+extern "C" int dh_layer_set_cross_stream(dh_layer* L, void* stream_cross) {
+  if (!L) DH_FAIL(DH_ERR_INVALID_ARG, "layer_set_cross_stream: null layer");
+  L->cross_stream = (hipStream_t)stream_cross;
+  return DH_OK;
+}
 
 extern "C" size_t dh_layer_workspace_bytes(const dh_layer* L, int kind) {
   if (!L) return 0;
@@ -415,6 +459,78 @@ static int llama_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hip
                             L->g.dg1, ws + L->b_norm, L->b_norm_bytes, s);
   }
   DH_FAIL(DH_ERR_INVALID_ARG, "unknown backward operator %d", op);
+}
+
+// Llama-style layer on one rank of a context-parallel group (Sec. 2.1, 2.2): the Llama operators with rotary
+// positions and attention shifted to the rank's chunk, plus the key/value exchange and the gradient send-back.
+static int cp_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hipStream_t s) {
+  static const int same[DH_CF_NOPS] = {DH_F_NORM1, DH_F_QKV, -1, -1, -1, DH_F_PROJ, DH_F_AR1, DH_F_NORM2, DH_F_FC1,
+                                       DH_F_ACT,   DH_F_FC2, DH_F_AR2, DH_F_BDA2};
+  const dh_layer_config& c = L->c;
+  char* sv = (char*)a.saved;
+  const int r = c.cp_rank, S = L->q_off + c.seq, W = L->kv_w, blocks = c.cross_blocks > 0 ? c.cross_blocks : 1;
+  switch (op) {
+    case DH_CF_ROPE:
+      return dh_rope_at(c.dtype, L->T, c.seq, L->q_off, c.n_q_heads + c.n_kv_heads, c.head_dim, L->n_qkv, c.rope_base, 0, sv + L->s_qkv, s);
+    case DH_CF_CP_KV: {  // chunk k of the exchange comes from rank k: earlier ranks and this one land in the attention buffer
+      dh_cp_move mv[16];
+      for (int k = 0; k < c.cp_ranks; k++) {
+        dh_cp_move& m = mv[k];
+        if (k == r) {
+          m.src = sv + L->s_qkv + (size_t)c.n_q_heads * c.head_dim * L->es;
+          m.src_ld = L->n_qkv;
+        } else {
+          m.src = (const char*)a.peers_kv + (size_t)(k < r ? k : k - 1) * L->T * W * L->es;
+          m.src_ld = W;
+        }
+        m.src_seq_rows = c.seq; m.src_row0 = 0;
+        if (k <= r) { m.dst = sv + L->s_kv; m.dst_ld = W; m.dst_seq_rows = S; m.dst_row0 = k * c.seq; }
+        else { m.dst = ws + L->f_kvrecv + (size_t)(k - r - 1) * L->T * W * L->es; m.dst_ld = W; m.dst_seq_rows = c.seq; m.dst_row0 = 0; }
+      }
+      return dh_cp_exchange(c.dtype, c.cp_ranks, mv, c.batch, c.seq, W, blocks, s);
+    }
+    case DH_CF_ATTN:
+      return dh_attn_ctx_fwd(c.dtype, c.batch, c.seq, L->q_off, c.n_q_heads, c.n_kv_heads, c.head_dim, sv + L->s_qkv, sv + L->s_kv,
+                             sv + L->s_o, (float*)(sv + L->s_lse), ws + L->f_attn, L->f_attn_bytes, s);
+  }
+  if (op < 0 || op >= DH_CF_NOPS) DH_FAIL(DH_ERR_INVALID_ARG, "unknown forward operator %d", op);
+  return llama_fwd_op(L, same[op], a, ws, s);
+}
+
+static int cp_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipStream_t s) {
+  static const int same[DH_CB_NOPS] = {DH_B_FC2_DGRAD, DH_B_FC2_WGRAD, DH_B_ACT, DH_B_FC1_DGRAD, DH_B_FC1_WGRAD, DH_B_AR3,
+                                       DH_B_NORM2, DH_B_PROJ_DGRAD, DH_B_PROJ_WGRAD, -1, -1, -1, DH_B_QKV_DGRAD,
+                                       DH_B_QKV_WGRAD, DH_B_AR4, DH_B_NORM1};
+  const dh_layer_config& c = L->c;
+  const char* sv = (const char*)b.saved;
+  const int r = c.cp_rank, S = L->q_off + c.seq, W = L->kv_w, blocks = c.cross_blocks > 0 ? c.cross_blocks : 1;
+  switch (op) {
+    case DH_CB_ATTN:
+      return dh_attn_ctx_bwd(c.dtype, c.batch, c.seq, L->q_off, c.n_q_heads, c.n_kv_heads, c.head_dim, sv + L->s_qkv, sv + L->s_kv,
+                             sv + L->s_o, ws + L->b_do, (const float*)(sv + L->s_lse), ws + L->b_dqkv, ws + L->b_dkv,
+                             (float*)(ws + L->b_delta), ws + L->b_attn, L->b_attn_bytes, s);
+    case DH_CB_CP_DKV: {  // send the earlier chunks' gradients back; own chunk: own contribution + the later ranks'
+      dh_cp_move mv[16];
+      for (int k = 0; k < r; k++) {
+        dh_cp_move& m = mv[k];
+        m.src = ws + L->b_dkv; m.src_ld = W; m.src_seq_rows = S; m.src_row0 = k * c.seq;
+        m.dst = (char*)b.dkv_peers + (size_t)k * L->T * W * L->es; m.dst_ld = W; m.dst_seq_rows = c.seq; m.dst_row0 = 0;
+      }
+      int rc = dh_cp_exchange(c.dtype, r, mv, c.batch, c.seq, W, blocks, s);
+      if (rc) return rc;
+      dh_cp_move own;
+      own.src = ws + L->b_dkv; own.src_ld = W; own.src_seq_rows = S; own.src_row0 = L->q_off;
+      own.dst = ws + L->b_dqkv + (size_t)c.n_q_heads * c.head_dim * L->es; own.dst_ld = L->n_qkv; own.dst_seq_rows = c.seq; own.dst_row0 = 0;
+      const void* later[16];
+      const int n_later = c.cp_ranks - 1 - r;
+      for (int k = 0; k < n_later; k++) later[k] = (const char*)b.peers_dkv + (size_t)(r + k) * L->T * W * L->es;
+      return dh_cp_grad_reduce(c.dtype, &own, n_later, later, c.batch, c.seq, W, blocks, s);
+    }
+    case DH_CB_ROPE:
+      return dh_rope_at(c.dtype, L->T, c.seq, L->q_off, c.n_q_heads + c.n_kv_heads, c.head_dim, L->n_qkv, c.rope_base, 1, ws + L->b_dqkv, s);
+  }
+  if (op < 0 || op >= DH_CB_NOPS) DH_FAIL(DH_ERR_INVALID_ARG, "unknown backward operator %d", op);
+  return llama_bwd_op(L, same[op], b, ws, s);
 }
 
 // GPT-style layer under tensor + sequence parallelism (Sec. 2.1).  The norms, residuals and the
@@ -611,6 +727,7 @@ static int run_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hipSt
   switch (L->c.arch) {
     case DH_ARCH_GPT: return gpt_fwd_op(L, op, a, ws, s);
     case DH_ARCH_MOE: return moe_fwd_op(L, op, a, ws, s);
+    case DH_ARCH_LLAMA_CP: return cp_fwd_op(L, op, a, ws, s);
     default: return llama_fwd_op(L, op, a, ws, s);
   }
 }
@@ -618,6 +735,7 @@ static int run_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipSt
   switch (L->c.arch) {
     case DH_ARCH_GPT: return gpt_bwd_op(L, op, b, ws, s);
     case DH_ARCH_MOE: return moe_bwd_op(L, op, b, ws, s);
+    case DH_ARCH_LLAMA_CP: return cp_bwd_op(L, op, b, ws, s);
     default: return llama_bwd_op(L, op, b, ws, s);
   }
 }
@@ -631,6 +749,8 @@ static int check_fwd_args(const dh_layer* L, const dh_fwd_args* a) {
   if (L->c.arch == DH_ARCH_GPT && L->c.n_ranks > 1 && (!a->peers_ag1 || !a->peers_ag2))
     DH_FAIL(DH_ERR_INVALID_ARG, "forward: all-gather peer shards are null but n_ranks > 1");
   if (L->c.arch == DH_ARCH_MOE && !a->logits) DH_FAIL(DH_ERR_INVALID_ARG, "forward: router logits are null");
+  if (L->c.arch == DH_ARCH_LLAMA_CP && L->c.cp_ranks > 1 && !a->peers_kv)
+    DH_FAIL(DH_ERR_INVALID_ARG, "forward: the peers' key/value chunks are null but cp_ranks > 1");
   return DH_OK;
 }
 static int check_bwd_args(const dh_layer* L, const dh_bwd_args* b) {
@@ -642,6 +762,8 @@ static int check_bwd_args(const dh_layer* L, const dh_bwd_args* b) {
   if (L->c.arch == DH_ARCH_GPT && L->c.n_ranks > 1 && (!b->peers_ag3 || !b->peers_ag4))
     DH_FAIL(DH_ERR_INVALID_ARG, "backward: all-gather peer shards are null but n_ranks > 1");
   if (L->c.arch == DH_ARCH_MOE && !b->dlogits) DH_FAIL(DH_ERR_INVALID_ARG, "backward: dlogits is null");
+  if (L->c.arch == DH_ARCH_LLAMA_CP && ((L->c.cp_rank + 1 < L->c.cp_ranks && !b->peers_dkv) || (L->c.cp_rank > 0 && !b->dkv_peers)))
+    DH_FAIL(DH_ERR_INVALID_ARG, "backward: a key/value gradient exchange buffer is null");
   return DH_OK;
 }
 static int check_ws(const dh_layer* L, int kind, const void* ws, size_t ws_bytes) {
@@ -736,6 +858,11 @@ static int on_comm_stream(dh_layer* L, hipStream_t strand, hipStream_t comm, Fn 
   return DH_OK;
 }
 
+// Stream of a communication operator: cross-node transfers (kind 2) use the layer's cross-node stream if one is set.
+static hipStream_t comm_stream_of(const dh_layer* L, int kind, hipStream_t comm) {
+  return kind == 2 && L->cross_stream ? L->cross_stream : comm;
+}
+
 static int check_si_args(dh_layer* L, const dh_fwd_args* alpha, const dh_bwd_args* beta, const dh_plan* plan, const void* ws,
                          size_t ws_bytes) {
   int rc = check_fwd_args(L, alpha);
@@ -767,13 +894,13 @@ static int enqueue_si(dh_layer* L, dh_layer* LB, const dh_fwd_args* alpha, const
     while (fi < p.f_end || bj < p.b_end) {
       if (fi < p.f_end) {
         const int op = plan->fwd_order[fi++];
-        if (L->gf.is_comm[op]) rc = on_comm_stream(L, sa, sc, [&](hipStream_t s) { return run_fwd_op(L, op, *alpha, ws_f, s); });
+        if (L->gf.is_comm[op]) rc = on_comm_stream(L, sa, comm_stream_of(L, L->gf.is_comm[op], sc), [&](hipStream_t s) { return run_fwd_op(L, op, *alpha, ws_f, s); });
         else rc = run_fwd_op(L, op, *alpha, ws_f, sa);
         if (rc) return rc;
       }
       if (bj < p.b_end) {
         const int op = plan->bwd_order[bj++];
-        if (L->gb.is_comm[op]) rc = on_comm_stream(L, sb, sc, [&](hipStream_t s) { return run_bwd_op(LB, op, *beta, ws_b, s); });
+        if (L->gb.is_comm[op]) rc = on_comm_stream(L, sb, comm_stream_of(L, L->gb.is_comm[op], sc), [&](hipStream_t s) { return run_bwd_op(LB, op, *beta, ws_b, s); });
         else rc = run_bwd_op(LB, op, *beta, ws_b, sb);
         if (rc) return rc;
       }
@@ -842,10 +969,18 @@ extern "C" int dh_si_graph_create(dh_layer* L, const dh_fwd_args* alpha, const d
   // A graph holds dependencies, not streams.  A strand never runs past its own collective (its next operator
   // consumes the result), so a stand-in is recorded as a node of its strand's chain; a separate communication
   // stream would add nothing but an order among the two strands' collectives.
-  DH_HIP(hipStreamBeginCapture(sa, hipStreamCaptureModeThreadLocal));
+  hipStream_t cross = L->cross_stream;  // the same holds for cross-node transfers: recorded in their strand's chain
+  L->cross_stream = nullptr;
+  hipError_t e = hipStreamBeginCapture(sa, hipStreamCaptureModeThreadLocal);
+  if (e != hipSuccess) {
+    L->cross_stream = cross;
+    (void)hipGetLastError();
+    return dh_set_error(DH_ERR_HIP, "si_graph_create: hipStreamBeginCapture failed: %s", hipGetErrorString(e));
+  }
   rc = enqueue_si(L, L, alpha, beta, plan, ws, sa, sb, nullptr);
+  L->cross_stream = cross;
   hipGraph_t graph = nullptr;
-  hipError_t e = hipStreamEndCapture(sa, &graph);  // always end the capture, also after a failed enqueue
+  e = hipStreamEndCapture(sa, &graph);  // always end the capture, also after a failed enqueue
   if (rc != DH_OK) {
     if (graph) (void)hipGraphDestroy(graph);
     (void)hipGetLastError();
@@ -915,8 +1050,9 @@ extern "C" int dh_profile_pairs(dh_layer* L, const dh_fwd_args* alpha, const dh_
   DH_HIP(hipEventCreate(&e3));
   DH_HIP(hipEventCreateWithFlags(&gate, hipEventDisableTiming));
   auto stream_of = [&](int dir, int op) {
-    bool comm = dir == 0 ? L->gf.is_comm[op] : L->gb.is_comm[op];
-    if (comm && sc) return sc;
+    const int comm = dir == 0 ? L->gf.is_comm[op] : L->gb.is_comm[op];
+    hipStream_t cs = comm ? comm_stream_of(L, comm, sc) : nullptr;
+    if (cs) return cs;
     return dir == 0 ? sa : sb;
   };
   auto cleanup = [&]() {

@@ -19,7 +19,7 @@ lib = C.CDLL(_LIB_PATH)
 DH_OK, DH_ERR_INVALID_ARG, DH_ERR_SHAPE, DH_ERR_WORKSPACE_TOO_SMALL = 0, -1, -2, -3
 DH_ERR_PLAN_INVALID, DH_ERR_HIP, DH_ERR_UNSUPPORTED = -4, -5, -6
 DH_F32, DH_BF16 = 0, 1
-DH_ARCH_LLAMA, DH_ARCH_GPT, DH_ARCH_MOE = 0, 1, 2
+DH_ARCH_LLAMA, DH_ARCH_GPT, DH_ARCH_MOE, DH_ARCH_LLAMA_CP = 0, 1, 2, 3
 DH_WS_FWD, DH_WS_BWD, DH_WS_SI = 0, 1, 2
 DH_COMM_ALLREDUCE, DH_COMM_ALLGATHER, DH_COMM_REDUCESCATTER = 0, 1, 2
 DH_MAX_OPS, DH_MAX_DEPS = 32, 96
@@ -45,7 +45,8 @@ class dh_layer_config(C.Structure):
     _fields_ = [("arch", C.c_int), ("dtype", C.c_int), ("batch", C.c_int), ("seq", C.c_int), ("hidden", C.c_int),
                 ("n_q_heads", C.c_int), ("n_kv_heads", C.c_int), ("head_dim", C.c_int), ("ffn", C.c_int),
                 ("eps", C.c_float), ("rope_base", C.c_float), ("n_ranks", C.c_int), ("comm_blocks", C.c_int),
-                ("n_experts", C.c_int), ("n_local_experts", C.c_int)]
+                ("n_experts", C.c_int), ("n_local_experts", C.c_int), ("cp_ranks", C.c_int), ("cp_rank", C.c_int),
+                ("cross_blocks", C.c_int)]
 
 
 class dh_weights(C.Structure):
@@ -58,12 +59,13 @@ class dh_wgrads(C.Structure):
 
 
 class dh_fwd_args(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("x", "out", "saved", "peers_ar1", "peers_ar2", "peers_ag1", "peers_ag2", "logits")]
+    _fields_ = [(n, C.c_void_p) for n in ("x", "out", "saved", "peers_ar1", "peers_ar2", "peers_ag1", "peers_ag2", "logits",
+                                          "peers_kv")]
 
 
 class dh_bwd_args(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("dout", "dx", "x", "saved", "peers_ar3", "peers_ar4", "peers_ag3", "peers_ag4",
-                                          "dlogits")]
+                                          "dlogits", "peers_dkv", "dkv_peers")]
 
 
 class dh_op_graph(C.Structure):
@@ -87,6 +89,11 @@ MOE_TABLES = ("rank", "dest", "src_tok", "send_of_recv", "recv_of_send", "counts
 
 class dh_moe_tables(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in MOE_TABLES]
+
+
+class dh_cp_move(C.Structure):
+    _fields_ = [("src", C.c_void_p), ("dst", C.c_void_p), ("src_ld", C.c_int), ("src_seq_rows", C.c_int), ("src_row0", C.c_int),
+                ("dst_ld", C.c_int), ("dst_seq_rows", C.c_int), ("dst_row0", C.c_int)]
 
 
 class dh_stack_fwd(C.Structure):
@@ -140,6 +147,9 @@ SIGNATURES = {
     "dh_si_graph_launch": (_I, [_P, _P]),
     "dh_si_graph_destroy": (None, [_P]),
     "dh_comm_standin": (_I, [_I, _I, C.POINTER(_P), _P, _Z, _I, _I, _P]),
+    "dh_cp_exchange": (_I, [_I, _I, C.POINTER(dh_cp_move), _I, _I, _I, _I, _P]),
+    "dh_cp_grad_reduce": (_I, [_I, C.POINTER(dh_cp_move), _I, C.POINTER(_P), _I, _I, _I, _I, _P]),
+    "dh_layer_set_cross_stream": (_I, [_P, _P]),
     "dh_stream_create_masked": (_I, [_I, C.POINTER(_P)]),
     "dh_stream_destroy": (_I, [_P]),
     "dh_gemm": (_I, [_I, _I, _I, _I, _I, _I, _P, _P, _P, _I, _P, _Z, _P]),
@@ -237,14 +247,15 @@ def dh_layer_workspace_bytes(layer, kind):
     return lib.dh_layer_workspace_bytes(layer, kind)
 
 
-def fwd_args(x, out, saved, peers_ar1=None, peers_ar2=None, peers_ag1=None, peers_ag2=None, logits=None):
+def fwd_args(x, out, saved, peers_ar1=None, peers_ar2=None, peers_ag1=None, peers_ag2=None, logits=None, peers_kv=None):
     return dh_fwd_args(_ptr(x), _ptr(out), _ptr(saved), _ptr(peers_ar1), _ptr(peers_ar2), _ptr(peers_ag1), _ptr(peers_ag2),
-                       _ptr(logits))
+                       _ptr(logits), _ptr(peers_kv))
 
 
-def bwd_args(dout, dx, x, saved, peers_ar3=None, peers_ar4=None, peers_ag3=None, peers_ag4=None, dlogits=None):
+def bwd_args(dout, dx, x, saved, peers_ar3=None, peers_ar4=None, peers_ag3=None, peers_ag4=None, dlogits=None, peers_dkv=None,
+             dkv_peers=None):
     return dh_bwd_args(_ptr(dout), _ptr(dx), _ptr(x), _ptr(saved), _ptr(peers_ar3), _ptr(peers_ar4), _ptr(peers_ag3),
-                       _ptr(peers_ag4), _ptr(dlogits))
+                       _ptr(peers_ag4), _ptr(dlogits), _ptr(peers_dkv), _ptr(dkv_peers))
 
 
 def dh_layer_fwd(layer, args, ws, ws_bytes, stream=None):
@@ -431,6 +442,24 @@ def dh_si_graph_destroy(graph):
 def dh_comm_standin(kind, parts, out, elems, dtype, n_blocks=0, stream=None):
     arr = (_P * len(parts))(*[_ptr(p) for p in parts])
     _check(lib.dh_comm_standin(kind, len(parts), arr, _ptr(out), elems, dtype, n_blocks, _stream(stream)))
+
+
+def cp_move(src, dst, src_ld, src_seq_rows, src_row0, dst_ld, dst_seq_rows, dst_row0):
+    return dh_cp_move(_ptr(src), _ptr(dst), src_ld, src_seq_rows, src_row0, dst_ld, dst_seq_rows, dst_row0)
+
+
+def dh_cp_exchange(dtype, moves, batch, rows, width, n_blocks=0, stream=None):
+    arr = (dh_cp_move * max(len(moves), 1))(*moves)
+    _check(lib.dh_cp_exchange(dtype, len(moves), arr, batch, rows, width, n_blocks, _stream(stream)))
+
+
+def dh_cp_grad_reduce(dtype, own, peers, batch, rows, width, n_blocks=0, stream=None):
+    arr = (_P * max(len(peers), 1))(*[_ptr(p) for p in peers])
+    _check(lib.dh_cp_grad_reduce(dtype, C.byref(own), len(peers), arr, batch, rows, width, n_blocks, _stream(stream)))
+
+
+def dh_layer_set_cross_stream(layer, stream):
+    _check(lib.dh_layer_set_cross_stream(layer, _stream(stream)))
 
 
 def dh_stream_create_masked(n_cus):

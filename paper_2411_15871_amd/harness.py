@@ -16,8 +16,11 @@ CONFIGS = {
     "c4_llama70b_tp8": dict(arch="llama", batch=1, seq=8192, hidden=8192, nq=8, nkv=1, d=128, ffn=3584, n_ranks=8, bf16=True),
     "c5_phimoe_ep8": dict(arch="moe", batch=1, seq=4096, hidden=4096, nq=32, nkv=8, d=128, ffn=6400, n_ranks=1, bf16=True,
                           n_experts=16, n_local=2),
+    # Llama-8B TP8 shard at a 16K context cut over 4 context-parallel ranks; this GPU holds the third chunk
+    "c6_llama8b_tp8_cp4": dict(arch="llama_cp", batch=1, seq=4096, hidden=4096, nq=4, nkv=1, d=128, ffn=1792, n_ranks=8, bf16=True,
+                               cp_ranks=4, cp_rank=2),
 }
-ARCH = {"llama": dh.DH_ARCH_LLAMA, "gpt": dh.DH_ARCH_GPT, "moe": dh.DH_ARCH_MOE}
+ARCH = {"llama": dh.DH_ARCH_LLAMA, "gpt": dh.DH_ARCH_GPT, "moe": dh.DH_ARCH_MOE, "llama_cp": dh.DH_ARCH_LLAMA_CP}
 
 
 def model_flops(cfg):
@@ -33,6 +36,8 @@ def model_flops(cfg):
     else:
         ffn = 2.0 * T * H * 3 * F
     attn = 0.5 * 4.0 * cfg["batch"] * cfg["seq"] ** 2 * d * nq
+    if arch == "llama_cp":  # the rank's queries also read cp_rank full chunks of earlier keys
+        attn += 4.0 * cfg["batch"] * cfg["seq"] ** 2 * cfg["cp_rank"] * d * nq
     return 3.0 * (attn_gemm + ffn + attn)
 
 
@@ -62,9 +67,16 @@ class Strand:
             for i, (k, base, std) in enumerate([("ag1", gen.SEED_PEER_FWD, 1.0), ("ag2", gen.SEED_PEER_FWD, 1.0),
                                                 ("ag3", gen.SEED_PEER_BWD, 1e-2), ("ag4", gen.SEED_PEER_BWD, 1e-2)]):
                 self.peers_np[k] = gen.peer_partials(base + 50 + 10 * i + 1000 * seed, n_peers, rows, H, bf, std)
+        if arch == "llama_cp":
+            W, ncp = 2 * c["nkv"] * c["d"], c["cp_ranks"] - 1
+            self.peers_np["kv"] = gen.peer_partials(gen.SEED_PEER_FWD + 70 + 1000 * seed, ncp, rows, W, bf, 1.0)
+            self.peers_np["dkv"] = gen.peer_partials(gen.SEED_PEER_BWD + 70 + 1000 * seed, ncp, rows, W, bf, 1e-2)
         self.x = to_dev(self.x_np, bf)
         self.dout = to_dev(self.dout_np, bf)
-        self.peers = {k: (to_dev(v, bf) if n_peers else None) for k, v in self.peers_np.items()}
+        self.peers = {k: (to_dev(v, bf) if len(v) else None) for k, v in self.peers_np.items()}
+        self.dkv_peers = None
+        if arch == "llama_cp" and c["cp_rank"] > 0:
+            self.dkv_peers = torch.zeros(c["cp_rank"], rows, 2 * c["nkv"] * c["d"], dtype=self.x.dtype, device="cuda")
         self.out = torch.empty_like(self.x)
         self.dx = torch.empty_like(self.x)
         self.saved = torch.empty(dh.dh_layer_saved_bytes(run.layer), dtype=torch.uint8, device="cuda")
@@ -74,9 +86,10 @@ class Strand:
             self.logits = torch.from_numpy(self.logits_np).cuda()
             self.dlogits = torch.zeros_like(self.logits)
         p = self.peers
-        self.fwd_args = dh.fwd_args(self.x, self.out, self.saved, p["ar1"], p["ar2"], p.get("ag1"), p.get("ag2"), self.logits)
+        self.fwd_args = dh.fwd_args(self.x, self.out, self.saved, p["ar1"], p["ar2"], p.get("ag1"), p.get("ag2"), self.logits,
+                                    p.get("kv"))
         self.bwd_args = dh.bwd_args(self.dout, self.dx, self.x, self.saved, p["ar3"], p["ar4"], p.get("ag3"), p.get("ag4"),
-                                    self.dlogits)
+                                    self.dlogits, p.get("dkv"), self.dkv_peers)
 
 
 class LayerRun:
@@ -93,7 +106,9 @@ class LayerRun:
                                         seq=c["seq"], hidden=c["hidden"], n_q_heads=c["nq"], n_kv_heads=c["nkv"],
                                         head_dim=c["d"], ffn=c["ffn"], eps=c["eps"], rope_base=c["rope_base"],
                                         n_ranks=c["n_ranks"], comm_blocks=c.get("comm_blocks", 0),
-                                        n_experts=c.get("n_experts", 0), n_local_experts=c.get("n_local", 0))
+                                        n_experts=c.get("n_experts", 0), n_local_experts=c.get("n_local", 0),
+                                        cp_ranks=c.get("cp_ranks", 0), cp_rank=c.get("cp_rank", 0),
+                                        cross_blocks=c.get("cross_blocks", 0))
         n_qkv = (c["nq"] + 2 * c["nkv"]) * c["d"]
         if c["arch"] == "gpt":
             self.w_np = gen.gpt_weights(c["hidden"], n_qkv, c["nq"] * c["d"], c["ffn"], bf)

@@ -104,3 +104,46 @@ def test_rope_at(dh, bf16, batch, seq, pos0, nh, d):
     torch.cuda.synchronize()
     ref = R.rope(t.astype(np.float64).reshape(T, nh, d), seq, 10000.0, pos0=pos0).reshape(T, nh * d)
     assert rel(host(td), ref) <= (4e-3 if bf16 else 2e-6)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("n_blocks", [0, 1, 3])
+def test_cp_exchange_and_grad_reduce(dh, bf16, n_blocks):
+    """The Send/Recv stand-ins: chunk copies between buffers of different pitch (bit-exact) and the ordered sum that
+    forms the key/value gradient a rank keeps."""
+    dtp = dh.DH_BF16 if bf16 else dh.DH_F32
+    batch, rows, W, cp, r = 2, 45, 48, 4, 2
+    S, ld_own = (r + 1) * rows, 80
+    own = gen.normal(1, (batch * rows, ld_own), 1.0, 0.0, bf16)          # packed rows, key/value columns start at 24
+    peers = gen.normal(2, (cp - 1, batch * rows, W), 1.0, 0.0, bf16)
+    ownd, peersd = dev(own, bf16), dev(peers, bf16)
+    kv = torch.zeros(batch * S, W, dtype=ownd.dtype, device="cuda")
+    recv = torch.zeros(cp - 1 - r, batch * rows, W, dtype=ownd.dtype, device="cuda")
+    es = ownd.element_size()
+    moves = []
+    for k in range(cp):
+        src = ownd.data_ptr() + 24 * es if k == r else peersd.data_ptr() + (k if k < r else k - 1) * batch * rows * W * es
+        if k <= r:
+            moves.append(dh.cp_move(src, kv, ld_own if k == r else W, rows, 0, W, S, k * rows))
+        else:
+            moves.append(dh.cp_move(src, recv.data_ptr() + (k - r - 1) * batch * rows * W * es, W, rows, 0, W, rows, 0))
+    dh.dh_cp_exchange(dtp, moves, batch, rows, W, n_blocks)
+    torch.cuda.synchronize()
+    k64 = own[:, 24:24 + W // 2].reshape(batch * rows, 1, W // 2); v64 = own[:, 24 + W // 2:24 + W].reshape(batch * rows, 1, W // 2)
+    K, V = R.cp_gather_kv(k64.astype(np.float64), v64.astype(np.float64), peers, batch, rows, r)
+    assert np.array_equal(host(kv), np.concatenate([K.reshape(batch * S, -1), V.reshape(batch * S, -1)], axis=1))
+    assert np.array_equal(host(recv), peers[r:].astype(np.float64))
+    # gradient kept by the rank: its own rows of a [batch*S, W] buffer plus the later ranks' contributions, into packed rows
+    dkv = gen.normal(3, (batch * S, W), 1.0, 0.0, bf16)
+    later = gen.normal(4, (cp - 1 - r, batch * rows, W), 1.0, 0.0, bf16)
+    dkvd, laterd = dev(dkv, bf16), dev(later, bf16)
+    dq = torch.full((batch * rows, ld_own), 3.0, dtype=ownd.dtype, device="cuda")
+    mv = dh.cp_move(dkvd, dq.data_ptr() + 24 * es, W, S, r * rows, ld_own, rows, 0)
+    dh.dh_cp_grad_reduce(dtp, mv, [laterd.data_ptr() + i * batch * rows * W * es for i in range(cp - 1 - r)], batch, rows, W, n_blocks)
+    torch.cuda.synchronize()
+    ref = np.concatenate([dkv[b * S + r * rows:(b + 1) * S] for b in range(batch)]).astype(np.float64) + later.astype(np.float64).sum(axis=0)
+    got = host(dq)
+    assert np.linalg.norm(got[:, 24:24 + W] - ref) <= (1e-2 if bf16 else 1e-6) * np.linalg.norm(ref)
+    assert np.all(got[:, :24] == 3.0) and np.all(got[:, 24 + W:] == 3.0)
+    with pytest.raises(dh.DhelixError):
+        dh.dh_cp_exchange(dtp, [dh.cp_move(ownd, kv, ld_own, rows, 0, W, S, S - rows + 1)], batch, rows, W)  # runs past its sequence

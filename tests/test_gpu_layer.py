@@ -26,8 +26,19 @@ CASES = {
                           n_experts=16, n_local=2), 2e-2),
     "moe_bf16_all_local": (dict(arch="moe", batch=1, seq=130, hidden=128, nq=2, nkv=2, d=64, ffn=64, n_ranks=1, bf16=True,
                                 n_experts=4, n_local=4), 2e-2),
+    "cp_fp32_small": (dict(arch="llama_cp", batch=2, seq=37, hidden=136, nq=4, nkv=2, d=32, ffn=200, n_ranks=2, bf16=False,
+                           cp_ranks=3, cp_rank=1), 1e-5),
+    "cp_fp32_first_rank": (dict(arch="llama_cp", batch=1, seq=50, hidden=64, nq=2, nkv=1, d=32, ffn=72, n_ranks=1, bf16=False,
+                                cp_ranks=2, cp_rank=0), 1e-5),
+    "cp_fp32_alone": (dict(arch="llama_cp", batch=1, seq=21, hidden=64, nq=2, nkv=2, d=16, ffn=40, n_ranks=1, bf16=False,
+                           cp_ranks=1, cp_rank=0), 1e-5),
+    "cp_bf16_mid": (dict(arch="llama_cp", batch=1, seq=384, hidden=520, nq=4, nkv=1, d=128, ffn=1000, n_ranks=4, bf16=True,
+                         cp_ranks=4, cp_rank=2), 2e-2),
+    "cp_bf16_last_d64": (dict(arch="llama_cp", batch=2, seq=128, hidden=256, nq=4, nkv=2, d=64, ffn=344, n_ranks=1, bf16=True,
+                              cp_ranks=2, cp_rank=1), 2e-2),
     "c3_gpt_tp8_sp": (H.CONFIGS["c3_gpt_tp8_sp"], 2e-2),
     "c5_phimoe_ep8": (H.CONFIGS["c5_phimoe_ep8"], 2e-2),
+    "c6_llama8b_tp8_cp4": (H.CONFIGS["c6_llama8b_tp8_cp4"], 2e-2),
 }
 GPT_NAMES = dict(Wgu="W1", Wd="W2", bfc1="bf1", bfc2="bf2")  # harness / C-struct name -> oracle name
 
@@ -57,6 +68,12 @@ def oracle_run(run, s):
         out, saved = R.moe_layer_fwd(cfg, W, x, s.logits_np.astype(np.float64), c["n_local"])
         dx, grads = R.moe_layer_bwd(cfg, W, saved, dout, c["n_local"])
         return out, dx, grads
+    if c["arch"] == "llama_cp":
+        out, saved = R.llama_cp_fwd(cfg, W, x, c["cp_rank"], s.peers_np)
+        dx, grads, inter = R.llama_cp_bwd(cfg, W, saved, dout, c["cp_rank"], s.peers_np)
+        if c["cp_rank"] > 0:  # what the rank sends back to the earlier ranks is a result too
+            grads["dkv_peers"] = inter["dkv_peers"]
+        return out, dx, grads
     out, saved = R.llama_fwd(cfg, W, x, s.peers_np)
     dx, grads, _ = R.llama_bwd(cfg, W, saved, dout, s.peers_np)
     return out, dx, grads
@@ -64,11 +81,13 @@ def oracle_run(run, s):
 
 def check_grads(run, s, grads, tol):
     got = run.grads_np()
-    assert sorted(got) == sorted(k for k in grads if k != "dlogits")
+    assert sorted(got) == sorted(k for k in grads if k not in ("dlogits", "dkv_peers"))
     for k, v in got.items():
         assert rel(v, grads[k]) <= tol, k
     if "dlogits" in grads:
         assert rel(H.to_np(s.dlogits), grads["dlogits"]) <= tol, "dlogits"
+    if "dkv_peers" in grads:
+        assert rel(H.to_np(s.dkv_peers), grads["dkv_peers"]) <= tol, "dkv_peers"
     return got
 
 
@@ -98,7 +117,7 @@ def test_layer_fwd_bwd_matches_oracle(name):
 
 def snapshot(run, alpha, beta):
     torch.cuda.synchronize()
-    extra = [beta.dlogits.clone()] if beta.dlogits is not None else []
+    extra = [t.clone() for t in (beta.dlogits, beta.dkv_peers) if t is not None]
     return [alpha.out.clone(), alpha.saved.clone(), beta.dx.clone()] + extra + [g.clone() for g in run.g.values()]
 
 
@@ -129,12 +148,12 @@ def random_legal_plan(dh, run, rng):
 
 
 @pytest.mark.parametrize("name", ["c1_tiny_fp32", "bf16_mid_ragged", "gpt_fp32_small", "gpt_bf16_mid", "moe_fp32_small",
-                                  "moe_bf16_mid"])
+                                  "moe_bf16_mid", "cp_fp32_small", "cp_bf16_mid"])
 def test_si_step_bitwise_equals_sequential_and_matches_oracle(name):
     from paper_2411_15871_amd import dhelix as dh
     cfg, tol = CASES[name]
     run = H.LayerRun(cfg)
-    comm = torch.cuda.Stream()
+    comm, cross = torch.cuda.Stream(), torch.cuda.Stream()
     try:
         alpha, beta = run.strand(0), run.strand(1)
         sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
@@ -163,11 +182,17 @@ def test_si_step_bitwise_equals_sequential_and_matches_oracle(name):
             "random_b": random_legal_plan(dh, run, rng),
         }
         for pname, plan in plans.items():
-            for streams in ((sa, sb, comm), (sa, sb, None)):
-                print("plan", pname, "comm" if streams[2] else "nocomm", flush=True)
+            variants = [(sa, sb, comm, None), (sa, sb, None, None)]
+            if cfg.get("arch") == "llama_cp":  # Send/Recv stand-ins on a cross-node stream of their own
+                variants += [(sa, sb, comm, cross), (sa, sb, None, cross)]
+            for *streams, xs in variants:
+                print("plan", pname, "comm" if streams[2] else "nocomm", "cross" if xs else "", flush=True)
                 alpha.out.zero_(); alpha.saved.zero_(); beta.dx.zero_()
+                if beta.dkv_peers is not None:
+                    beta.dkv_peers.zero_()
                 run.zero_grads()
                 torch.cuda.synchronize()
+                dh.dh_layer_set_cross_stream(run.layer, xs)
                 run.si_step(alpha, beta, plan, *streams)
                 got = snapshot(run, alpha, beta)
                 for a, b in zip(got, ref):
@@ -196,7 +221,7 @@ def test_empty_micro_batch_is_a_no_op():
         run.close()
 
 
-@pytest.mark.parametrize("name", ["c1_tiny_fp32", "gpt_bf16_mid", "moe_bf16_mid"])
+@pytest.mark.parametrize("name", ["c1_tiny_fp32", "gpt_bf16_mid", "moe_bf16_mid", "cp_bf16_mid"])
 def test_captured_si_step_replays_bitwise(name):
     """The SI step recorded into a HIP graph gives, on every replay, bitwise what the eager step gives; replays are
     separated by eager work and synchronisations of the program's own."""

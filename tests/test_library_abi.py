@@ -30,6 +30,8 @@ def test_op_names_and_error_strings():
     assert dh.FWD_OPS[:4] == ["F_NORM1", "F_QKV", "F_ROPE", "F_ATTN"] and len(dh.FWD_OPS) == 12 and len(dh.BWD_OPS) == 15
     assert len(dh.op_names(dh.DH_ARCH_GPT, 0)) == 13 and len(dh.op_names(dh.DH_ARCH_GPT, 1)) == 16
     assert len(dh.op_names(dh.DH_ARCH_MOE, 0)) == 14 and len(dh.op_names(dh.DH_ARCH_MOE, 1)) == 18
+    assert len(dh.op_names(dh.DH_ARCH_LLAMA_CP, 0)) == 13 and len(dh.op_names(dh.DH_ARCH_LLAMA_CP, 1)) == 16
+    assert dh.op_names(dh.DH_ARCH_LLAMA_CP, 0)[3] == "F_CP_KV" and dh.op_names(dh.DH_ARCH_LLAMA_CP, 1)[10] == "B_CP_DKV"
     assert dh.dh_op_name(0, 0, 99) is None and dh.dh_op_name(0, 2, 0) is None and dh.dh_op_name(7, 0, 0) is None
     with pytest.raises(dh.DhelixError) as e:
         dh.dh_layer_create(arch=0, dtype=1, batch=1, seq=8, hidden=100, n_q_heads=2, n_kv_heads=1, head_dim=64, ffn=64,
