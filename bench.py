@@ -142,6 +142,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c2_llama8b_tp8")
     ap.add_argument("--comm-blocks", type=int, default=0, help="thread blocks per collective stand-in (0 = cover payload)")
+    ap.add_argument("--cross-blocks", type=int, default=0, help="thread blocks per cross-node Send/Recv stand-in (0 = 8, about one 400 Gb/s port)")
     ap.add_argument("--profile-reps", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", type=int, default=0, help="stack this many layers: alpha sweeps forward while beta sweeps backward")
@@ -182,6 +183,7 @@ def main():
 
     cfg = dict(H.CONFIGS[args.workload])
     cfg["comm_blocks"] = args.comm_blocks
+    cfg["cross_blocks"] = args.cross_blocks
     flops = H.model_flops(cfg)
     run = H.LayerRun(cfg)
     alpha, beta = run.strand(0), run.strand(1)
@@ -190,6 +192,10 @@ def main():
     run.bwd(beta)
     torch.cuda.synchronize()
     sa, sb, sc = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    sx = None
+    if cfg["arch"] == "llama_cp":  # Sec. 5: cross-node transfers get a stream of their own
+        sx = torch.cuda.Stream()
+        dh.dh_layer_set_cross_stream(run.layer, sx)
 
     # offline part of the method: pairwise profiling and plan search (Sec. 3.2, 4.2)
     t0 = time.perf_counter()
@@ -238,6 +244,13 @@ def main():
     t_rr = time_steps(lambda: run.si_step(alpha, beta, rr_plan, sa, sb, sc), probe, 2, torch)
     t_fixed = time_steps(lambda: run.si_step(alpha, beta, fixed_plan, sa, sb, sc), probe, 2, torch)
     log("ablations: round-robin %.1f us, weight gradients fixed %.1f us" % (t_rr * 1e6, t_fixed * 1e6))
+    t_shared = None
+    if sx is not None:  # ablation of Sec. 6.4 ("Communication and Communication Overlap"): both kinds of transfer on one stream
+        dh.dh_layer_set_cross_stream(run.layer, None)
+        t_shared = time_steps(lambda: run.si_step(alpha, beta, best_plan, sa, sb, sc), probe, 2, torch)
+        dh.dh_layer_set_cross_stream(run.layer, sx)
+        t_cross = sum(t_f[i] for i in range(nf) if gf.is_comm[i] == 2) + sum(t_b[j] for j in range(nb) if gb.is_comm[j] == 2)
+        log("cross-node stand-ins solo %.1f us; SI step with them on the collectives' stream %.1f us" % (t_cross * 1e6, t_shared * 1e6))
     # the same step replayed from a HIP graph (one launch per step instead of one per operator)
     graph = dh.dh_si_graph_create(run.layer, alpha.fwd_args, beta.bwd_args, best_plan, run.ws, run.ws_bytes, sa, sb)
     t_graph = time_steps(lambda: dh.dh_si_graph_launch(graph, sa), args.steps, args.warmup, torch)
@@ -277,12 +290,13 @@ def main():
         "ms_per_step": t_si * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg["bf16"] else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "arch": cfg["arch"], "tokens_per_strand": run.T, "comm_blocks": args.comm_blocks,
-                   "plan_pairs": len(pairs), "plan": best_name},
+                   "cp": [cfg["cp_rank"], cfg["cp_ranks"]] if cfg["arch"] == "llama_cp" else None, "plan_pairs": len(pairs), "plan": best_name},
         "pct_bf16_peak": 100.0 * value / BF16_MFMA_PEAK_TFLOPS,
         "tokens_per_s": run.T / t_si,
         "speedup_vs_sequential": t_seq / t_si,
         "ms_sequential": t_seq * 1e3, "ms_free_running": t_free * 1e3, "ms_graph_replay": t_graph * 1e3,
         "ms_round_robin": t_rr * 1e3, "ms_wgrad_fixed": t_fixed * 1e3,
+        "ms_one_comm_stream": t_shared * 1e3 if t_shared is not None else None,
         "comm_hidden_frac": (t_seq - t_si) / t_comm if t_comm > 0 else None,
         "roofline": {"bound": "mfma", "achieved": gemm_tflops, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": gemm_tflops / BF16_MFMA_PEAK_TFLOPS, "traffic": HBM_TRAFFIC_BYTES.get(args.workload),

@@ -91,8 +91,8 @@ typedef struct {
   int n_local_experts; /* DH_ARCH_MOE: experts held by this GPU, divides E; else 0 */
   int cp_ranks;        /* DH_ARCH_LLAMA_CP: ranks of the context-parallel group (1..16); else 0 */
   int cp_rank;         /* DH_ARCH_LLAMA_CP: this rank's index, 0 .. cp_ranks-1 */
-  int cross_blocks;    /* DH_ARCH_LLAMA_CP: thread blocks of a Send/Recv stand-in (the cross-node link's rate);
-                          0 = one block */
+  int cross_blocks;    /* DH_ARCH_LLAMA_CP: thread blocks of a Send/Recv stand-in, which set its rate (a block
+                          moves 5-7 GB/s on MI355X); 0 = 8 blocks, about one 400 Gb/s network port */
 } dh_layer_config;
 
 /* Device pointers to the shard's weights (read only).  g1,g2: [H]; Wqkv: [H,(nq+2nkv)d] with columns
@@ -397,7 +397,7 @@ int dh_comm_standin(int kind, int n_ranks, const void* const* parts, void* out, 
  * cross-node transfers get a stream of their own).  One-GPU stand-in of the exchange: n_moves (<= 16) copies, each
  * of `rows` rows of `width` elements (multiple of 8) for each of `batch` sequences.  A side of a move is a row-major
  * buffer with a row pitch of ld elements holding seq_rows rows per sequence, of which the move touches rows
- * row0 .. row0+rows-1.  Device pointers, 16-byte aligned; n_blocks as for dh_comm_standin (one or two blocks move
+ * row0 .. row0+rows-1.  Device pointers, 16-byte aligned; n_blocks as for dh_comm_standin (a handful of blocks move
  * data at about the rate of a network link, which is what the transfer is a stand-in for). */
 typedef struct {
   const void* src;

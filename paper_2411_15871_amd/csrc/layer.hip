@@ -468,7 +468,7 @@ static int cp_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hipStr
                                        DH_F_ACT,   DH_F_FC2, DH_F_AR2, DH_F_BDA2};
   const dh_layer_config& c = L->c;
   char* sv = (char*)a.saved;
-  const int r = c.cp_rank, S = L->q_off + c.seq, W = L->kv_w, blocks = c.cross_blocks > 0 ? c.cross_blocks : 1;
+  const int r = c.cp_rank, S = L->q_off + c.seq, W = L->kv_w, blocks = c.cross_blocks > 0 ? c.cross_blocks : 8;
   switch (op) {
     case DH_CF_ROPE:
       return dh_rope_at(c.dtype, L->T, c.seq, L->q_off, c.n_q_heads + c.n_kv_heads, c.head_dim, L->n_qkv, c.rope_base, 0, sv + L->s_qkv, s);
@@ -503,7 +503,7 @@ static int cp_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipStr
                                        DH_B_QKV_WGRAD, DH_B_AR4, DH_B_NORM1};
   const dh_layer_config& c = L->c;
   const char* sv = (const char*)b.saved;
-  const int r = c.cp_rank, S = L->q_off + c.seq, W = L->kv_w, blocks = c.cross_blocks > 0 ? c.cross_blocks : 1;
+  const int r = c.cp_rank, S = L->q_off + c.seq, W = L->kv_w, blocks = c.cross_blocks > 0 ? c.cross_blocks : 8;
   switch (op) {
     case DH_CB_ATTN:
       return dh_attn_ctx_bwd(c.dtype, c.batch, c.seq, L->q_off, c.n_q_heads, c.n_kv_heads, c.head_dim, sv + L->s_qkv, sv + L->s_kv,
