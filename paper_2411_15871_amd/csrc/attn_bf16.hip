@@ -23,17 +23,22 @@
 // Blocks are launched heaviest first (the causal work per block grows with its position).
 // No atomics: dQ is produced per query block, dK/dV per (key block, query head), then the heads of
 // a group are added in index order.
+#include <map>
+#include <mutex>
+#include <queue>
+#include <tuple>
+#include <vector>
 #include "common.h"
 #include "dma.h"
 
 #define AB_THREADS 256
 #define AB_KT 64   // tokens per LDS tile
 #define AB_RING 3  // tile slots
-#define AB_CH 16   // backward: a block walks at most this many 64-token tiles (longer causal rows are split
+#define AB_CH 16   // backward: a block walks at most g.ch 64-token tiles, this many by default (longer causal rows are split
                    // into chunks whose float32 partial results a second kernel adds in chunk order)
 
 // Work split of the backward kernels.  Along the block's own dimension there are ceil(seq/128) blocks;
-// block i has tiles_of(i) tiles to walk and is cut into ceil(tiles/AB_CH) chunks.  A launch index is
+// block i has tiles_of(i) tiles to walk and is cut into ceil(tiles/ch) chunks (ch is chosen per launch).  A launch index is
 // mapped to (block, chunk) heaviest block first; `pair` numbers the (block, chunk) pairs in natural order.
 //
 // Positions.  seq = keys per sequence (positions 0..seq-1); the queries of a sequence are its positions
@@ -45,34 +50,37 @@ struct AttnGeom {
   int seq, q_off, nq, nkv;
   const bf16_t* kv; int ldkv;
   bf16_t* dkv; int lddkv;
+  int ch;      // backward kernels: 64-token tiles per chunk
+  int nq_all;  // nq * batch: a launch index is (pair index) * nq_all + (batch * nq + head), so that the heaviest
+               // chunks of every head start first
 };
 struct ChunkMap { int blk, chunk, pair, chunks; };
 __host__ __device__ static inline int dq_tiles(int i, int seq) { int e = (i + 1) * 128; return ((e < seq ? e : seq) + AB_KT - 1) / AB_KT; }
 __host__ __device__ static inline int dkv_first(int i, int q_off) { return i * 128 > q_off ? i * 128 : q_off; }  // first query position a key block meets
 __host__ __device__ static inline int dkv_tiles(int i, int seq, int q_off) { return (seq - dkv_first(i, q_off) + AB_KT - 1) / AB_KT; }
-__host__ __device__ static inline int chunks_of(int tiles) { return (tiles + AB_CH - 1) / AB_CH; }
-static int total_pairs_dq(int seq, int q_off) {
+__host__ __device__ static inline int chunks_of(int tiles, int c) { return (tiles + c - 1) / c; }
+static int total_pairs_dq(int seq, int q_off, int c) {
   int n = 0;
-  for (int i = q_off / 128; i < (seq + 127) / 128; i++) n += chunks_of(dq_tiles(i, seq));
+  for (int i = q_off / 128; i < (seq + 127) / 128; i++) n += chunks_of(dq_tiles(i, seq), c);
   return n;
 }
-static int total_pairs_dkv(int seq, int q_off) {
+static int total_pairs_dkv(int seq, int q_off, int c) {
   int n = 0;
-  for (int i = 0; i < (seq + 127) / 128; i++) n += chunks_of(dkv_tiles(i, seq, q_off));
+  for (int i = 0; i < (seq + 127) / 128; i++) n += chunks_of(dkv_tiles(i, seq, q_off), c);
   return n;
 }
 template <bool DKV>
-__device__ __forceinline__ ChunkMap map_chunk(int id, int seq, int q_off, int total) {
+__device__ __forceinline__ ChunkMap map_chunk(int id, int seq, int q_off, int total, int c) {
   const int nblk = (seq + 127) / 128;
   ChunkMap m;
   int rem = id, after = 0;  // `after` = pairs of the blocks visited before this one
   if (DKV) {  // heaviest = block 0; natural pair order = visiting order
     int i = 0;
-    for (;; i++) { int ch = chunks_of(dkv_tiles(i, seq, q_off)); if (rem < ch || i == nblk - 1) { m.chunks = ch; break; } rem -= ch; after += ch; }
+    for (;; i++) { int ch = chunks_of(dkv_tiles(i, seq, q_off), c); if (rem < ch || i == nblk - 1) { m.chunks = ch; break; } rem -= ch; after += ch; }
     m.blk = i; m.chunk = rem; m.pair = after + rem;
   } else {    // heaviest = last block; the first block with queries is q_off/128
     int i = nblk - 1;
-    for (;; i--) { int ch = chunks_of(dq_tiles(i, seq)); if (rem < ch || i == q_off / 128) { m.chunks = ch; break; } rem -= ch; after += ch; }
+    for (;; i--) { int ch = chunks_of(dq_tiles(i, seq), c); if (rem < ch || i == q_off / 128) { m.chunks = ch; break; } rem -= ch; after += ch; }
     m.blk = i; m.chunk = rem; m.pair = total - after - m.chunks + rem;
   }
   return m;
@@ -326,7 +334,7 @@ static int fwd_units(int seq, int q_off, int ch) {
   return n;
 }
 
-// grid (units, nq, batch); wave w owns query rows i0 + 32w .. +31.  The K and V tiles go through two LDS
+// grid (units * nq * batch); wave w owns query rows i0 + 32w .. +31.  The K and V tiles go through two LDS
 // slots each (64 KiB per block at D = 128), so that two blocks fit a compute unit: the matrix work of
 // one block's waves then overlaps the softmax arithmetic of the other's.
 #define AF_RING 2
@@ -341,14 +349,15 @@ __global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(const Attn
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l32 = lane & 31, kg = lane >> 5;
   const int seq = g.seq, nq = g.nq, nkv = g.nkv, qb0 = g.q_off / 128, ldkv = g.ldkv;
-  const int h = blockIdx.y, b = blockIdx.z, hk = h / (nq / nkv);
+  const int hb = blockIdx.x % g.nq_all, launch = blockIdx.x / g.nq_all;
+  const int h = hb % nq, b = hb / nq, hk = h / (nq / nkv);
   const int ld = (nq + 2 * nkv) * D;
   int blk, chunk = 0, nchunks = 1, pair;
   if (ch == 0) {
-    pair = gridDim.x - 1 - blockIdx.x;
+    pair = units - 1 - launch;
     blk = qb0 + pair;
   } else {  // heaviest block first; `pair` numbers the (block, chunk) units in natural order
-    int rem = blockIdx.x, after = 0;
+    int rem = launch, after = 0;
     blk = (seq + 127) / 128 - 1;
     for (;; blk--) {
       nchunks = fwd_chunks(blk, seq, ch);
@@ -569,9 +578,10 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(const Attn
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l32 = lane & 31, kg = lane >> 5;
   const int seq = g.seq, nq = g.nq, nkv = g.nkv, ldkv = g.ldkv;
-  const int h = blockIdx.y, b = blockIdx.z, hk = h / (nq / nkv);
+  const int hb = blockIdx.x % g.nq_all;
+  const int h = hb % nq, b = hb / nq, hk = h / (nq / nkv);
   const int ld = (nq + 2 * nkv) * D;
-  const ChunkMap cm = map_chunk<false>(blockIdx.x, seq, g.q_off, pairs);
+  const ChunkMap cm = map_chunk<false>(blockIdx.x / g.nq_all, seq, g.q_off, pairs, g.ch);
   const int i0 = cm.blk * 128, iw = i0 + wave * 32, iq = iw + l32;
   const size_t ktok0 = (size_t)b * seq;
   const long long qtok0 = (long long)b * (seq - g.q_off) - g.q_off;  // local token of position p = qtok0 + p
@@ -594,7 +604,7 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(const Attn
   uint32_t voff[TL::IPW];
   tile_voff<D>(voff, ldkv, wave, lane, AB_KT);
   const uint32_t ldsK = lds_address(smem), ldsV = ldsK + AB_RING * TL::BYTES;
-  const int t0 = cm.chunk * AB_CH, ntiles = min(dq_tiles(cm.blk, seq), t0 + AB_CH);  // this block walks key tiles [t0, ntiles)
+  const int t0 = cm.chunk * g.ch, ntiles = min(dq_tiles(cm.blk, seq), t0 + g.ch);  // this block walks key tiles [t0, ntiles)
   auto issue = [&](int t, int slot) {
     const int valid = seq - t * AB_KT;
     if (valid >= AB_KT) {
@@ -673,11 +683,11 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(const Attn
 // grid (8*query blocks, nq, batch), 256 threads: a block owns 16 rows of a query block, thread = (row, 4 columns).
 template <int D>
 __global__ __launch_bounds__(256) void attn_bwd_dq_reduce_kernel(const float* __restrict__ part, bf16_t* __restrict__ dqkv, int seq,
-                                                                 int q_off, int nq, int nkv, int pairs, float scale) {
+                                                                 int q_off, int nq, int nkv, int pairs, int cl, float scale) {
   const int i = q_off / 128 + (blockIdx.x >> 3), r0 = (blockIdx.x & 7) * 16, h = blockIdx.y, b = blockIdx.z, ld = (nq + 2 * nkv) * D;
   int base = 0;
-  for (int k = q_off / 128; k < i; k++) base += chunks_of(dq_tiles(k, seq));
-  const int ch = chunks_of(dq_tiles(i, seq));
+  for (int k = q_off / 128; k < i; k++) base += chunks_of(dq_tiles(k, seq), cl);
+  const int ch = chunks_of(dq_tiles(i, seq), cl);
   const float* p0 = part + (((size_t)b * nq + h) * pairs + base) * 128 * D;
   for (int e = threadIdx.x; e < 16 * D / 4; e += 256) {
     const int row = r0 + e / (D / 4), c4 = (e % (D / 4)) * 4;
@@ -690,7 +700,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_reduce_kernel(const float* __
 }
 
 // ================================================================================ backward: dK, dV
-// grid (ceil(seq/128), nq, batch): one block per (key block, query head); wave w owns keys
+// grid (pairs * nq * batch): one block per (key block, chunk, query head); wave w owns keys
 // j0 + 32w .. +31 and keeps their K, V fragments and the dK^T, dV^T accumulators in registers while
 // 64-query tiles of that head's Q and dO stream through LDS.  With grouped heads (nq > nkv) the
 // block writes float32 partials part[batch][query head][pair][128 keys][dK | dV] and
@@ -709,9 +719,10 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(const Att
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l32 = lane & 31, kg = lane >> 5;
   const int seq = g.seq, nq = g.nq, nkv = g.nkv;
-  const int hq = blockIdx.y, b = blockIdx.z, grp = nq / nkv, hk = hq / grp;
+  const int hb = blockIdx.x % g.nq_all;
+  const int hq = hb % nq, b = hb / nq, grp = nq / nkv, hk = hq / grp;
   const int ld = (nq + 2 * nkv) * D, ldo = nq * D;
-  const ChunkMap cm = map_chunk<true>(blockIdx.x, seq, g.q_off, pairs);
+  const ChunkMap cm = map_chunk<true>(blockIdx.x / g.nq_all, seq, g.q_off, pairs, g.ch);
   const int j0 = cm.blk * 128, jw = j0 + wave * 32, jk = jw + l32;  // key positions in the sequence (block 0 is the heaviest)
   const int q0 = dkv_first(cm.blk, g.q_off);                        // first query position this key block meets
   const size_t ktok0 = (size_t)b * seq;
@@ -737,7 +748,7 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(const Att
   tile_voff<D>(vq, ld, wave, lane, AB_KT);
   tile_voff<D>(vo, ldo, wave, lane, AB_KT);
   const uint32_t ldsQ = lds_address(smem), ldsO = ldsQ + AB_RING * TL::BYTES;
-  const int t0 = cm.chunk * AB_CH, ntiles = min(dkv_tiles(cm.blk, seq, g.q_off), t0 + AB_CH);  // query tiles q0 + 64*[t0, ntiles)
+  const int t0 = cm.chunk * g.ch, ntiles = min(dkv_tiles(cm.blk, seq, g.q_off), t0 + g.ch);  // query tiles q0 + 64*[t0, ntiles)
   const size_t qstride = (size_t)AB_KT * ld * sizeof(bf16_t), ostride = (size_t)AB_KT * ldo * sizeof(bf16_t);
   auto issue = [&](int t, int slot) {
     const int valid = seq - (q0 + t * AB_KT);
@@ -855,8 +866,8 @@ __global__ __launch_bounds__(256) void attn_bwd_group_reduce_kernel(const float*
   const int seq = g.seq, nq = g.nq, nkv = g.nkv;
   const int i = blockIdx.x >> 3, r0 = (blockIdx.x & 7) * 16, hk = blockIdx.y, b = blockIdx.z, grp = nq / nkv;
   int base = 0;
-  for (int k = 0; k < i; k++) base += chunks_of(dkv_tiles(k, seq, g.q_off));
-  const int ch = chunks_of(dkv_tiles(i, seq, g.q_off));
+  for (int k = 0; k < i; k++) base += chunks_of(dkv_tiles(k, seq, g.q_off), g.ch);
+  const int ch = chunks_of(dkv_tiles(i, seq, g.q_off), g.ch);
   for (int e = threadIdx.x; e < 16 * 2 * D / 4; e += 256) {
     const int row = r0 + e / (2 * D / 4), c4 = (e % (2 * D / 4)) * 4;
     if (i * 128 + row >= seq) continue;
@@ -889,16 +900,91 @@ static int attn_num_cus() {
   return n_cus;
 }
 
-// Tiles per chunk of the forward kernel: the largest of 64, 32, 16, 8 that still gives about three work
-// units per resident block slot (two per compute unit); 0 = blocks are not split.
-static int fwd_chunk_tiles(int batch, int seq, int q_off, int nq) {
-  const long long target = 6ll * attn_num_cus();
-  const int max_tiles = fwd_tiles((seq + 127) / 128 - 1, seq);
-  for (int ch = 64; ch >= 8; ch /= 2) {
-    if (ch >= max_tiles) continue;
-    if ((long long)fwd_units(seq, q_off, ch) * nq * batch >= target || ch == 8) return ch;
+// Chunk length of a launch.  The blocks of a launch are (block of 128 positions, chunk) units times nq*batch heads,
+// started heaviest first; the hardware hands the next block to the first free compute unit.  That list schedule is
+// simulated for each candidate length: a unit costs its tiles plus a fixed overhead, every chunk of a split launch
+// costs the traffic of its float32 partial result (written, then read by the merging kernel), and a split launch
+// pays for the merging kernels.  The constants are measured on MI355X (microseconds): a compute unit finishes a
+// forward tile in 1.45 whether one or two blocks share it, a dQ plus a dK/dV tile in 4.4; HBM moves 4 MB per
+// microsecond under this load.  The backward kernels share one length (and one partial-result layout).
+enum { PICK_FWD = 0, PICK_BWD = 1 };
+struct PickKey {
+  int kind, seq, q_off, nq_all, d, grouped, cus;
+  bool operator<(const PickKey& o) const {
+    return std::tie(kind, seq, q_off, nq_all, d, grouped, cus) < std::tie(o.kind, o.seq, o.q_off, o.nq_all, o.d, o.grouped, o.cus);
   }
-  return 0;
+};
+static double simulate_launch(int kind, int seq, int q_off, int nq_all, int ch, int slots, double t_tile, double t_ovh) {
+  const int nblk = (seq + 127) / 128, qb0 = q_off / 128;
+  std::priority_queue<double, std::vector<double>, std::greater<double>> free_at;
+  for (int i = 0; i < slots; i++) free_at.push(0.0);
+  double makespan = 0.0;
+  auto run = [&](int tiles) {
+    for (int t0 = 0; t0 < tiles; t0 += ch) {
+      const double cost = (tiles - t0 < ch ? tiles - t0 : ch) * t_tile + t_ovh;
+      for (int h = 0; h < nq_all; h++) {
+        const double end = free_at.top() + cost;
+        free_at.pop();
+        free_at.push(end);
+        if (end > makespan) makespan = end;
+      }
+    }
+  };
+  if (kind == PICK_BWD) for (int i = 0; i < nblk; i++) run(dkv_tiles(i, seq, q_off));  // dQ walks the mirror image
+  else for (int i = nblk - 1; i >= qb0; i--) run(dq_tiles(i, seq));                    // forward: the tiles dQ walks
+  return makespan;
+}
+static int pick_chunk(int kind, int seq, int q_off, int nq_all, int d, bool grouped) {
+  static std::mutex mu;
+  static std::map<PickKey, int> cache;
+  const PickKey key{kind, seq, q_off, nq_all, d, grouped ? 1 : 0, attn_num_cus()};
+#ifdef DH_ATTN_SWEEP  // tuning builds only: chunk lengths from the environment
+  if (const char* e = getenv(kind == PICK_FWD ? "DH_ATTN_CH_FWD" : "DH_ATTN_CH_BWD")) return atoi(e) > 0 ? atoi(e) : (1 << 20);
+#endif
+  std::lock_guard<std::mutex> lock(mu);
+  auto it = cache.find(key);
+  if (it != cache.end()) return it->second;
+  const int nblk = (seq + 127) / 128, qb0 = q_off / 128;
+  const int max_tiles = kind == PICK_BWD ? dkv_tiles(0, seq, q_off) : dq_tiles(nblk - 1, seq);
+  const double t_tile = (kind == PICK_FWD ? 1.45 : 4.4) * d / 128.0, t_ovh = kind == PICK_FWD ? 3.0 : 6.0;
+  const double us_per_byte = 2.0 / 4.0e6, t_merge = kind == PICK_FWD ? 12.0 : 25.0;
+  static const int cand_fwd[] = {4, 8, 16, 32, 64, 1 << 20}, cand_bwd[] = {4, 6, 8, 12, 16, 24, 32, 48, 64, 1 << 20};
+  const int* cand = kind == PICK_FWD ? cand_fwd : cand_bwd;
+  const int n_cand = kind == PICK_FWD ? 6 : 10;
+  int best = cand[n_cand - 1];
+  double best_t = 1e300;
+  for (int k = 0; k < n_cand; k++) {
+    const int ch = cand[k];
+    if (ch < (1 << 20) && ch >= max_tiles) continue;  // same as not splitting
+    int units_q = 0, units_k = 0;
+    for (int i = qb0; i < nblk; i++) units_q += chunks_of(dq_tiles(i, seq), ch);
+    for (int i = 0; i < nblk; i++) units_k += chunks_of(dkv_tiles(i, seq, q_off), ch);
+    const bool split = units_q > nblk - qb0 || (kind == PICK_BWD && units_k > nblk);
+    double t = simulate_launch(kind, seq, q_off, nq_all, ch, attn_num_cus(), t_tile, t_ovh);
+    double bytes = 0.0;
+    if (kind == PICK_FWD) { if (split) bytes = (double)units_q * (d + 2); }
+    else {
+      if (split) bytes = (double)units_q * d;
+      if (split || grouped) bytes += (double)units_k * 2 * d;
+    }
+    t += bytes * nq_all * 128 * sizeof(float) * us_per_byte + (split ? t_merge : 0.0);
+#ifdef DH_ATTN_SWEEP
+    fprintf(stderr, "pick kind %d seq %d heads %d: ch %d -> %.1f us (split %d)\n", kind, seq, nq_all, ch, t, (int)split);
+#endif
+    if (t < best_t) { best_t = t; best = ch; }
+  }
+  cache[key] = best;
+  return best;
+}
+
+// Tiles per chunk of the forward kernel; 0 = blocks are not split.
+static int fwd_chunk_tiles(int batch, int seq, int q_off, int nq, int d) {
+  const int ch = pick_chunk(PICK_FWD, seq, q_off, nq * batch, d, false);
+  return ch >= (1 << 20) ? 0 : ch;
+}
+// Tiles per chunk of the two backward kernels.
+static int bwd_chunk_tiles(int batch, int seq, int q_off, int nq, int nkv, int d) {
+  return pick_chunk(PICK_BWD, seq, q_off, nq * batch, d, nq > nkv);
 }
 
 // The launchers take the queries' sequence length seq_q and q_off; kv == nullptr selects plain attention (keys and
@@ -915,7 +1001,7 @@ static int check_geom(int d, int q_off, const void* kv, int ldkv, int nkv) {
 size_t dh_attn_fwd_bf16_ws_bytes(int batch, int seq_q, int q_off, int nq, int nkv, int d) {
   (void)nkv;
   if (batch * seq_q == 0) return 0;
-  const int seq = q_off + seq_q, ch = fwd_chunk_tiles(batch, seq, q_off, nq);
+  const int seq = q_off + seq_q, ch = fwd_chunk_tiles(batch, seq, q_off, nq, d);
   if (ch == 0) return 0;
   return (size_t)batch * nq * fwd_units(seq, q_off, ch) * 128 * ((size_t)d + 2) * sizeof(float);
 }
@@ -927,15 +1013,15 @@ int dh_launch_attn_fwd_bf16(int batch, int seq_q, int nq, int nkv, int d, const 
   if (batch * seq_q == 0) return DH_OK;
   const int seq = q_off + seq_q, T = batch * seq_q;
   AttnGeom g;
-  g.seq = seq; g.q_off = q_off; g.nq = nq; g.nkv = nkv; g.dkv = nullptr; g.lddkv = 0;
+  g.seq = seq; g.q_off = q_off; g.nq = nq; g.nkv = nkv; g.dkv = nullptr; g.lddkv = 0; g.ch = 0; g.nq_all = nq * batch;
   if (kv) { g.kv = kv; g.ldkv = ldkv; } else { g.kv = qkv + (size_t)nq * d; g.ldkv = (nq + 2 * nkv) * d; }
   const int nblk = (seq + 127) / 128 - q_off / 128;  // blocks that hold queries
-  int ch = fwd_chunk_tiles(batch, seq, q_off, nq);
+  int ch = fwd_chunk_tiles(batch, seq, q_off, nq, d);
   if (ch > 0 && (!ws || ws_bytes < dh_attn_fwd_bf16_ws_bytes(batch, seq_q, q_off, nq, nkv, d))) ch = 0;  // no room for partial results
   const int units = ch > 0 ? fwd_units(seq, q_off, ch) : nblk;
   float* part_o = (float*)ws;
   float* part_ml = ch > 0 ? part_o + (size_t)batch * nq * units * 128 * d : nullptr;
-  dim3 grid(units, nq, batch), cgrid(nblk * 8, nq, batch);
+  dim3 grid((unsigned)units * nq * batch), cgrid(nblk * 8, nq, batch);
   const float sl2 = (float)(1.4426950408889634 / sqrt((double)d));
   const size_t lds = 2 * AF_RING * (size_t)AB_KT * d * 2;
   static bool ready[2] = {false, false};
@@ -957,10 +1043,11 @@ int dh_launch_attn_fwd_bf16(int batch, int seq_q, int nq, int nkv, int d, const 
 // workspace: lse2[nq*T] floats; dK/dV partials [batch][nq][pairs][128][2d] floats when heads are grouped
 // or some block needs more than one chunk; dQ partials [batch][nq][pairs][128][d] floats in the latter case
 static void bwd_ws_layout(int batch, int seq_q, int q_off, int nq, int nkv, int d, size_t& o_lse2, size_t& o_dkv, size_t& o_dq,
-                          size_t& total, int& pairs, bool& chunked) {
+                          size_t& total, int& pairs, bool& chunked, int& cl) {
   const size_t T = (size_t)batch * seq_q;
   const int seq = q_off + seq_q, nblk = (seq + 127) / 128;
-  const int pq = total_pairs_dq(seq, q_off), pk = total_pairs_dkv(seq, q_off);
+  cl = bwd_chunk_tiles(batch, seq, q_off, nq, nkv, d);
+  const int pq = total_pairs_dq(seq, q_off, cl), pk = total_pairs_dkv(seq, q_off, cl);
   pairs = pq > pk ? pq : pk;
   chunked = pq > nblk - q_off / 128 || pk > nblk;
   size_t cur = 0;
@@ -971,8 +1058,8 @@ static void bwd_ws_layout(int batch, int seq_q, int q_off, int nq, int nkv, int 
 }
 
 size_t dh_attn_bwd_bf16_ws_bytes(int batch, int seq_q, int q_off, int nq, int nkv, int d) {
-  size_t a, b, c, total; int pairs; bool chunked;
-  bwd_ws_layout(batch, seq_q, q_off, nq, nkv, d, a, b, c, total, pairs, chunked);
+  size_t a, b, c, total; int pairs, cl; bool chunked;
+  bwd_ws_layout(batch, seq_q, q_off, nq, nkv, d, a, b, c, total, pairs, chunked, cl);
   return total;
 }
 
@@ -989,15 +1076,16 @@ int dh_launch_attn_bwd_bf16(int batch, int seq_q, int nq, int nkv, int d, const 
   g.seq = seq; g.q_off = q_off; g.nq = nq; g.nkv = nkv;
   if (kv) { g.kv = kv; g.ldkv = ldkv; g.dkv = dkv; g.lddkv = lddkv; }
   else { g.kv = qkv + (size_t)nq * d; g.dkv = dqkv + (size_t)nq * d; g.ldkv = g.lddkv = (nq + 2 * nkv) * d; }
-  size_t o_lse2, o_dkv, o_dq, need; int pairs_max; bool chunked;
-  bwd_ws_layout(batch, seq_q, q_off, nq, nkv, d, o_lse2, o_dkv, o_dq, need, pairs_max, chunked);
+  size_t o_lse2, o_dkv, o_dq, need; int pairs_max, cl; bool chunked;
+  bwd_ws_layout(batch, seq_q, q_off, nq, nkv, d, o_lse2, o_dkv, o_dq, need, pairs_max, chunked, cl);
+  g.ch = cl; g.nq_all = nq * batch;
   if (!ws || ws_bytes < need) DH_FAIL(DH_ERR_WORKSPACE_TOO_SMALL, "attn_bwd: workspace %zu < %zu bytes", ws_bytes, need);
   float* lse2 = (float*)((char*)ws + o_lse2);
   float* part_kv = (nq > nkv || chunked) ? (float*)((char*)ws + o_dkv) : nullptr;
   float* part_q = chunked ? (float*)((char*)ws + o_dq) : nullptr;
   const float sc = (float)(1.0 / sqrt((double)d)), sl2 = (float)(1.4426950408889634 / sqrt((double)d));
-  const int nblk = (seq + 127) / 128, nblk_q = nblk - q_off / 128, pq = total_pairs_dq(seq, q_off), pk = total_pairs_dkv(seq, q_off);
-  dim3 gwq(pq, nq, batch), gwk(pk, nq, batch), gq(nblk_q * 8, nq, batch), gk(nblk * 8, nkv, batch);
+  const int nblk = (seq + 127) / 128, nblk_q = nblk - q_off / 128, pq = total_pairs_dq(seq, q_off, cl), pk = total_pairs_dkv(seq, q_off, cl);
+  dim3 gwq((unsigned)pq * nq * batch), gwk((unsigned)pk * nq * batch), gq(nblk_q * 8, nq, batch), gk(nblk * 8, nkv, batch);
   const unsigned nprep = (unsigned)(((size_t)T * nq + 3) / 4);
   const size_t lds_dq = 2 * AB_RING * (size_t)AB_KT * d * 2, lds_dkv = lds_dq + 2 * AB_RING * AB_KT * sizeof(float);
   static bool ready[2] = {false, false};
@@ -1011,7 +1099,7 @@ int dh_launch_attn_bwd_bf16(int batch, int seq_q, int nq, int nkv, int d, const 
     DH_LAUNCH_CHECK();                                                                                                         \
     attn_bwd_dq_bf16_kernel<DD><<<gwq, AB_THREADS, lds_dq, stream>>>(g, qkv, dout, lse2, delta, dqkv, part_q, pq, T, sc, sl2);   \
     DH_LAUNCH_CHECK();                                                                                                         \
-    if (part_q) { attn_bwd_dq_reduce_kernel<DD><<<gq, 256, 0, stream>>>(part_q, dqkv, seq, q_off, nq, nkv, pq, sc); DH_LAUNCH_CHECK(); } \
+    if (part_q) { attn_bwd_dq_reduce_kernel<DD><<<gq, 256, 0, stream>>>(part_q, dqkv, seq, q_off, nq, nkv, pq, cl, sc); DH_LAUNCH_CHECK(); } \
     attn_bwd_dkv_bf16_kernel<DD><<<gwk, AB_THREADS, lds_dkv, stream>>>(g, qkv, dout, lse2, delta, part_kv, pk, T, sc, sl2);      \
     DH_LAUNCH_CHECK();                                                                                                         \
     if (part_kv) { attn_bwd_group_reduce_kernel<DD><<<gk, 256, 0, stream>>>(part_kv, g, pk); DH_LAUNCH_CHECK(); }                \

@@ -248,7 +248,7 @@ def test_attention_fwd_bwd(dh, bf16, batch, seq, nq, nkv, d):
     assert np.max(np.abs(host(lse) - lse_ref)) <= (2e-2 if bf16 else 1e-5)
     assert rel(host(o_ns), o_ref.reshape(T, nq * d)) <= tol
     assert np.max(np.abs(host(lse_ns) - lse_ref)) <= (2e-2 if bf16 else 1e-5)
-    assert (fwsb > 0) == (bf16 and seq > 512)
+    assert bf16 or fwsb == 0  # only the matrix-core kernel splits rows (when that shortens the launch)
     dqkv = torch.zeros(T, nqkv, dtype=tdtype(bf16), device="cuda")
     delta = torch.empty(nq, T, dtype=torch.float32, device="cuda")
     wsb = dh.dh_attn_bwd_workspace_bytes(dt(dh, bf16), batch, seq, nq, nkv, d)
