@@ -362,7 +362,7 @@ __global__ void splitk_reduce_kernel(const float* __restrict__ part, int splits,
 
 // ------------------------------------------------------------------------------------ host side
 struct GemmPlan {
-  int cfg;  // 0: 256x256 (8 waves), 1: 128x128 (4 waves)
+  int cfg;  // 0: 256x256 (8 waves), 1: 128x128 (4 waves), 2: 256x128 (4 waves)
   int bm, bn, splits, kt_per_split;
 };
 
@@ -379,15 +379,21 @@ static int num_cus() {
   return g_num_cus;
 }
 
-// Tile and split-K choice.  256x256 tiles when they give most compute units a block, else 128x128;
+// Tile and split-K choice.  256x256 tiles when they give most compute units a block; else 256x128 when that gives
+// most units exactly one block (one 4-wave block per unit measured faster than two 128x128 blocks sharing a unit, for
+// row-major A: 4096x1792x4096 with B transposed 84 -> 72 us); else 128x128;
 // if a single wave of blocks still leaves units idle and K is long, split K (bounded by the
 // workspace) so that about one block per unit exists.
-static GemmPlan choose_plan(int M, int N, int K, size_t ws_bytes) {
+static GemmPlan choose_plan(bool ta, int M, int N, int K, size_t ws_bytes) {
   const int cus = num_cus();
   auto tiles = [&](int bm, int bn) { return (long long)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
   GemmPlan p;
   if (tiles(256, 256) * 2 >= cus) { p.cfg = 0; p.bm = 256; p.bn = 256; }
+  else if (!ta && tiles(256, 128) <= cus && tiles(256, 128) * 4 >= (long long)cus * 3) { p.cfg = 2; p.bm = 256; p.bn = 128; }
   else { p.cfg = 1; p.bm = 128; p.bn = 128; }
+#ifdef DH_GEMM_SWEEP  // tuning builds only
+  if (const char* e = getenv("DH_GEMM_CFG")) { p.cfg = atoi(e); p.bm = p.bn = p.cfg ? 128 : 256; }
+#endif
   const int nkt = (K + GB_BK - 1) / GB_BK;
   const long long t = tiles(p.bm, p.bn);
   int splits = 1;
@@ -398,14 +404,17 @@ static GemmPlan choose_plan(int M, int N, int K, size_t ws_bytes) {
     if (per == 0 || ws_bytes / per < (size_t)splits) splits = per ? (int)(ws_bytes / per) : 1;
     if (splits < 2) splits = 1;
   }
+#ifdef DH_GEMM_SWEEP
+  if (const char* e = getenv("DH_GEMM_SPLITS")) splits = atoi(e);
+#endif
   p.kt_per_split = nkt == 0 ? 1 : (nkt + splits - 1) / splits;
   p.splits = nkt == 0 ? 1 : (nkt + p.kt_per_split - 1) / p.kt_per_split;
   return p;
 }
 
 size_t dh_gemm_bf16_ws_bytes(bool ta, bool tb, int M, int N, int K) {
-  (void)ta; (void)tb;
-  GemmPlan p = choose_plan(M, N, K, (size_t)-1);
+  (void)tb;
+  GemmPlan p = choose_plan(ta, M, N, K, (size_t)-1);
   return p.splits > 1 ? (size_t)p.splits * M * N * sizeof(float) : 0;
 }
 
@@ -430,6 +439,7 @@ static int launch_cfg(GemmArgs g, int splits, hipStream_t stream, int n_groups =
 template <bool TA, bool TB>
 static int launch_layout(const GemmArgs& g, const GemmPlan& p, hipStream_t stream, int n_groups = 1) {
   if (p.cfg == 0) return launch_cfg<256, 256, 2, 4, TA, TB>(g, p.splits, stream, n_groups);
+  if (p.cfg == 2) return launch_cfg<256, 128, 2, 2, TA, TB>(g, p.splits, stream, n_groups);
   return launch_cfg<128, 128, 2, 2, TA, TB>(g, p.splits, stream, n_groups);
 }
 
@@ -442,7 +452,7 @@ int dh_launch_gemm_bf16(bool ta, bool tb, int M, int N, int K, const bf16_t* A, 
   if (bias && out_f32_accumulate) DH_FAIL(DH_ERR_INVALID_ARG, "gemm (bf16): a bias goes with a bf16 result only");
   if (M == 0 || N == 0) return DH_OK;
   if ((long long)M * N >= (1ll << 40) || (long long)M * K >= (1ll << 40)) DH_FAIL(DH_ERR_SHAPE, "gemm: matrix too large");
-  GemmPlan p = choose_plan(M, N, K, ws ? ws_bytes : 0);
+  GemmPlan p = choose_plan(ta, M, N, K, ws ? ws_bytes : 0);
   GemmArgs g;
   g.M = M; g.N = N; g.K = K; g.A = A; g.B = B;
   g.kt_per_split = p.kt_per_split;
@@ -477,8 +487,8 @@ int dh_launch_gemm_grouped_bf16(int mode, int n_groups, const int32_t* group_row
   g.tiles_m = g.tiles_n = g.tiles_per_xcd = 0;
   const int avg = std::max(1, max_rows / n_groups);
   GemmPlan p;
-  if (mode == 2) { g.M = dim_a; g.N = dim_b; g.K = max_rows; p = choose_plan(dim_a, dim_b, avg, 0); }
-  else { g.M = max_rows; g.N = dim_b; g.K = dim_a; p = choose_plan(avg, dim_b, dim_a, 0); }
+  if (mode == 2) { g.M = dim_a; g.N = dim_b; g.K = max_rows; p = choose_plan(true, dim_a, dim_b, avg, 0); }
+  else { g.M = max_rows; g.N = dim_b; g.K = dim_a; p = choose_plan(false, avg, dim_b, dim_a, 0); }
   p.splits = 1;
   g.kt_per_split = (g.K + GB_BK - 1) / GB_BK;
   g.epi = mode == 2 ? EPI_ACC_F32 : EPI_STORE_BF16;

@@ -182,7 +182,8 @@ def test_gemm_f32(dh, ta, tb, M, N, K):
 
 
 BF16_SHAPES = [(8, 8, 8), (128, 128, 64), (256, 256, 128), (300, 264, 200), (1000, 768, 520), (2048, 1024, 512),
-               (77, 4096, 1024), (512, 512, 4096), (0, 64, 64)]
+               (77, 4096, 1024), (512, 512, 4096), (0, 64, 64),
+               (4096, 1792, 136), (3900, 1704, 200)]  # the last two take the 256x128 tile when A is row-major
 
 
 @pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0)])
