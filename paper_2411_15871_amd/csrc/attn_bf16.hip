@@ -680,20 +680,20 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(const Attn
 }
 
 // dq[token][head] = scale * sum over the chunks of the token's query block (ascending) of the partials.
-// grid (8*query blocks, nq, batch), 256 threads: a block owns 16 rows of a query block, thread = (row, 4 columns).
+// grid (16*query blocks, nq, batch), 256 threads: a block owns 8 rows of a query block, thread = (row, 4 columns).
 template <int D>
 __global__ __launch_bounds__(256) void attn_bwd_dq_reduce_kernel(const float* __restrict__ part, bf16_t* __restrict__ dqkv, int seq,
                                                                  int q_off, int nq, int nkv, int pairs, int cl, float scale) {
-  const int i = q_off / 128 + (blockIdx.x >> 3), r0 = (blockIdx.x & 7) * 16, h = blockIdx.y, b = blockIdx.z, ld = (nq + 2 * nkv) * D;
+  const int i = q_off / 128 + (blockIdx.x >> 4), r0 = (blockIdx.x & 15) * 8, h = blockIdx.y, b = blockIdx.z, ld = (nq + 2 * nkv) * D;
   int base = 0;
   for (int k = q_off / 128; k < i; k++) base += chunks_of(dq_tiles(k, seq), cl);
   const int ch = chunks_of(dq_tiles(i, seq), cl);
   const float* p0 = part + (((size_t)b * nq + h) * pairs + base) * 128 * D;
-  for (int e = threadIdx.x; e < 16 * D / 4; e += 256) {
+  for (int e = threadIdx.x; e < 8 * D / 4; e += 256) {
     const int row = r0 + e / (D / 4), c4 = (e % (D / 4)) * 4;
     if (i * 128 + row >= seq) continue;
     f32x4 s = {0.f, 0.f, 0.f, 0.f};
-    for (int c = 0; c < ch; c++) s += *reinterpret_cast<const f32x4*>(p0 + ((size_t)c * 128 + row) * D + c4);
+    for (int c = 0; c < ch; c++) s += __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p0 + ((size_t)c * 128 + row) * D + c4));
     bf16x4 o = {(bf16_t)(s[0] * scale), (bf16_t)(s[1] * scale), (bf16_t)(s[2] * scale), (bf16_t)(s[3] * scale)};
     *reinterpret_cast<bf16x4*>(dqkv + ((size_t)b * (seq - q_off) + (i * 128 + row - q_off)) * ld + (size_t)h * D + c4) = o;
   }
@@ -859,22 +859,22 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(const Att
 
 // dk,dv[token][kv head] = sum over the group's query heads (ascending) and, inside a head, over the
 // chunks of the token's key block (ascending) of the float32 partials.
-// grid (8*ceil(seq/128), nkv, batch), 256 threads: a block owns 16 rows of a key block, thread = (key row, 4
+// grid (32*ceil(seq/128), nkv, batch), 256 threads: a block owns 4 rows of a key block, thread = (key row, 4
 // columns of [dK | dV]).
 template <int D>
 __global__ __launch_bounds__(256) void attn_bwd_group_reduce_kernel(const float* __restrict__ part, const AttnGeom g, int pairs) {
   const int seq = g.seq, nq = g.nq, nkv = g.nkv;
-  const int i = blockIdx.x >> 3, r0 = (blockIdx.x & 7) * 16, hk = blockIdx.y, b = blockIdx.z, grp = nq / nkv;
+  const int i = blockIdx.x >> 5, r0 = (blockIdx.x & 31) * 4, hk = blockIdx.y, b = blockIdx.z, grp = nq / nkv;
   int base = 0;
   for (int k = 0; k < i; k++) base += chunks_of(dkv_tiles(k, seq, g.q_off), g.ch);
   const int ch = chunks_of(dkv_tiles(i, seq, g.q_off), g.ch);
-  for (int e = threadIdx.x; e < 16 * 2 * D / 4; e += 256) {
+  for (int e = threadIdx.x; e < 4 * 2 * D / 4; e += 256) {
     const int row = r0 + e / (2 * D / 4), c4 = (e % (2 * D / 4)) * 4;
     if (i * 128 + row >= seq) continue;
     f32x4 s = {0.f, 0.f, 0.f, 0.f};
     for (int gh = 0; gh < grp; gh++) {
       const float* p0 = part + (((size_t)b * nq + hk * grp + gh) * pairs + base) * 128 * (2 * D);
-      for (int c = 0; c < ch; c++) s += *reinterpret_cast<const f32x4*>(p0 + ((size_t)c * 128 + row) * (2 * D) + c4);
+      for (int c = 0; c < ch; c++) s += __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p0 + ((size_t)c * 128 + row) * (2 * D) + c4));
     }
     bf16x4 o = {(bf16_t)s[0], (bf16_t)s[1], (bf16_t)s[2], (bf16_t)s[3]};
     bf16_t* dst = g.dkv + ((size_t)b * seq + i * 128 + row) * g.lddkv + (c4 < D ? (size_t)hk * D + c4 : (size_t)(nkv + hk) * D + (c4 - D));
@@ -1085,7 +1085,7 @@ int dh_launch_attn_bwd_bf16(int batch, int seq_q, int nq, int nkv, int d, const 
   float* part_q = chunked ? (float*)((char*)ws + o_dq) : nullptr;
   const float sc = (float)(1.0 / sqrt((double)d)), sl2 = (float)(1.4426950408889634 / sqrt((double)d));
   const int nblk = (seq + 127) / 128, nblk_q = nblk - q_off / 128, pq = total_pairs_dq(seq, q_off, cl), pk = total_pairs_dkv(seq, q_off, cl);
-  dim3 gwq((unsigned)pq * nq * batch), gwk((unsigned)pk * nq * batch), gq(nblk_q * 8, nq, batch), gk(nblk * 8, nkv, batch);
+  dim3 gwq((unsigned)pq * nq * batch), gwk((unsigned)pk * nq * batch), gq(nblk_q * 16, nq, batch), gk(nblk * 32, nkv, batch);
   const unsigned nprep = (unsigned)(((size_t)T * nq + 3) / 4);
   const size_t lds_dq = 2 * AB_RING * (size_t)AB_KT * d * 2, lds_dkv = lds_dq + 2 * AB_RING * AB_KT * sizeof(float);
   static bool ready[2] = {false, false};
