@@ -230,12 +230,27 @@ def main():
     timed = [(time_steps(lambda p=p: run.si_step(alpha, beta, p, sa, sb, sc), probe_steps, 2, torch), name, p) for name, p in cands]
     for t, name, _ in timed:
         log("  candidate %-48s %.1f us" % (name, t * 1e6))
-    _, best_name, best_plan = min(timed, key=lambda x: x[0])
+    t_best, best_name, best_plan = min(timed, key=lambda x: x[0])
+    # Weight-gradient operators may run beside the backward strand (on the forward strand's stream, which is the
+    # shorter one): try a few subsets on the chosen plan.
+    side_ok = sorted((op for op in range(nb) if gb.side_ok[op]), key=lambda o: -t_b[o])
+    in_strand_plan, side_ops = best_plan, []
+    for label, ops in (("all", side_ok), ("two largest", side_ok[:2]), ("largest", side_ok[:1]), ("all but the largest", side_ok[1:])):
+        if not ops:
+            continue
+        q = dh.with_side(in_strand_plan, ops)
+        t = time_steps(lambda q=q: run.si_step(alpha, beta, q, sa, sb, sc), probe_steps, 2, torch)
+        log("  weight gradients beside the strand (%s: %s): %.1f us" % (label, [bnames[o] for o in ops], t * 1e6))
+        if t < t_best:
+            t_best, best_plan, side_ops = t, q, ops
+    if side_ops:
+        best_name += ", beside the strand: " + "+".join(bnames[o] for o in side_ops)
     fo, bo, pairs = dh.plan_to_py(best_plan)
     log("chosen plan:", best_name, [([fnames[o] for o in fo[a:b]], [bnames[o] for o in bo[c:d]]) for a, b, c, d in pairs])
     t_seq = time_steps(lambda: run.si_step(alpha, beta, seq_plan, sa, sb, sc), args.steps, args.warmup, torch)
     t_free = time_steps(lambda: run.si_step(alpha, beta, free_plan, sa, sb, sc), args.steps, args.warmup, torch)
     t_si = time_steps(lambda: run.si_step(alpha, beta, best_plan, sa, sb, sc), args.steps, args.warmup, torch)
+    t_in_strand = time_steps(lambda: run.si_step(alpha, beta, in_strand_plan, sa, sb, sc), probe_steps, 2, torch) if side_ops else t_si
     # ablations of Sec. 6.1 / 6.4 through the same executor: round-robin interleaving ("Wavelet+"), and the searched plan
     # with the weight-gradient operators left in their default places
     rr_plan = dh.dh_plan_round_robin(gf, gb)
@@ -295,7 +310,7 @@ def main():
         "tokens_per_s": run.T / t_si,
         "speedup_vs_sequential": t_seq / t_si,
         "ms_sequential": t_seq * 1e3, "ms_free_running": t_free * 1e3, "ms_graph_replay": t_graph * 1e3,
-        "ms_round_robin": t_rr * 1e3, "ms_wgrad_fixed": t_fixed * 1e3,
+        "ms_round_robin": t_rr * 1e3, "ms_wgrad_fixed": t_fixed * 1e3, "ms_wgrad_in_strand": t_in_strand * 1e3,
         "ms_one_comm_stream": t_shared * 1e3 if t_shared is not None else None,
         "comm_hidden_frac": (t_seq - t_si) / t_comm if t_comm > 0 else None,
         "roofline": {"bound": "mfma", "achieved": gemm_tflops, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",

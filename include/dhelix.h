@@ -235,6 +235,8 @@ typedef struct {
   int n_deps;
   int dep_src[DH_MAX_DEPS];
   int dep_dst[DH_MAX_DEPS];
+  int side_ok[DH_MAX_OPS];   /* backward graph: 1 = the operator has no dependents and touches no buffer a later operator
+                                of its strand writes, so a plan may run it beside the strand (dh_plan.bwd_side) */
 } dh_op_graph;
 
 /* Fills the forward (direction 0) or backward (direction 1) operator graph of the layer. */
@@ -278,6 +280,10 @@ int dh_profile_pairs(dh_layer* layer, const dh_fwd_args* alpha, const dh_bwd_arg
  * Plans (Sec. 4.2).  A plan = one operator sequence per strand plus segment pairs: pair k
  * co-runs forward operators fwd_order[f_begin:f_end] with backward operators
  * bwd_order[b_begin:b_end]; a cross-strand barrier follows every pair.
+ * bwd_side[op] != 0 lets backward operator `op` run beside its strand: it is issued on the other strand's stream
+ * once the backward operators before it in bwd_order are done, so the backward strand goes on without waiting for it
+ * (Sec. 4.2: a weight-gradient operator has no dependents inside the layer and may overlap its own strand).  It still
+ * ends before its segment pair's barrier.  Only operators whose graph entry has side_ok set may be marked.
  * ------------------------------------------------------------------------------------------ */
 typedef struct { int f_begin, f_end, b_begin, b_end; } dh_seg_pair;
 typedef struct {
@@ -285,6 +291,7 @@ typedef struct {
   int fwd_order[DH_MAX_OPS];
   int bwd_order[DH_MAX_OPS];
   dh_seg_pair pairs[2 * DH_MAX_OPS];
+  int bwd_side[DH_MAX_OPS]; /* indexed by operator id */
 } dh_plan;
 
 /* Eq. 2 for given segments: p_f[i] = P(i, none), p_b[j] = P(none, j), p_fb[i*n_b + j] = P(i,j).

@@ -106,6 +106,7 @@ static void build_graphs(dh_layer* L) {
     add_dep(b, DH_B_ROPE, DH_B_QKV_WGRAD);    // needs dqkv
     // FC2_WGRAD needs only the upstream gradient and the saved activation: no predecessor.
     b.is_comm[DH_B_AR3] = b.is_comm[DH_B_AR4] = 1;
+    b.side_ok[DH_B_FC2_WGRAD] = b.side_ok[DH_B_FC1_WGRAD] = b.side_ok[DH_B_PROJ_WGRAD] = b.side_ok[DH_B_QKV_WGRAD] = 1;
   } else if (L->c.arch == DH_ARCH_LLAMA_CP) {
     f.n_ops = DH_CF_NOPS;
     for (int i = 0; i + 1 < DH_CF_NOPS; i++) add_dep(f, i, i + 1);
@@ -119,6 +120,7 @@ static void build_graphs(dh_layer* L) {
     add_dep(b, DH_CB_ROPE, DH_CB_QKV_WGRAD);
     b.is_comm[DH_CB_AR3] = b.is_comm[DH_CB_AR4] = 1;
     b.is_comm[DH_CB_CP_DKV] = 2;
+    b.side_ok[DH_CB_FC2_WGRAD] = b.side_ok[DH_CB_FC1_WGRAD] = b.side_ok[DH_CB_PROJ_WGRAD] = b.side_ok[DH_CB_QKV_WGRAD] = 1;
   } else if (L->c.arch == DH_ARCH_GPT) {
     f.n_ops = DH_GF_NOPS;
     for (int i = 0; i + 1 < DH_GF_NOPS; i++) add_dep(f, i, i + 1);
@@ -146,6 +148,7 @@ static void build_graphs(dh_layer* L) {
     add_dep(b, DH_MB_NORM2, DH_MB_PROJ_WGRAD);         // needs dx2
     add_dep(b, DH_MB_ROPE, DH_MB_QKV_WGRAD);           // needs dqkv
     b.is_comm[DH_MB_A2A_DISPATCH] = b.is_comm[DH_MB_A2A_COMBINE] = 1;
+    b.side_ok[DH_MB_FC2_WGRAD] = b.side_ok[DH_MB_FC1_WGRAD] = b.side_ok[DH_MB_PROJ_WGRAD] = b.side_ok[DH_MB_QKV_WGRAD] = 1;
   }
 }
 
@@ -246,6 +249,10 @@ extern "C" int dh_layer_create(const dh_layer_config* cfg, dh_layer** out) {
   L->f_attn = take(cur, L->f_attn_bytes);
   size_t fg = std::max(gw(0, 0, T, L->n_qkv, H), gw(0, 0, T, H, L->n_o));
   if (!moe) fg = std::max(fg, std::max(gw(0, 0, T, Fin, H), gw(0, 0, T, H, F)));
+  if (!gpt) {  // weight-gradient GEMMs that run beside their strand borrow this workspace
+    fg = std::max(fg, std::max(gw(1, 0, L->n_o, H, T), gw(1, 0, H, L->n_qkv, T)));
+    if (!moe) fg = std::max(fg, std::max(gw(1, 0, F, H, T), gw(1, 0, H, Fin, T)));
+  }
   L->f_gemm_bytes = fg;
   L->f_gemm = take(cur, fg);
   L->fwd_bytes = cur;
@@ -418,12 +425,14 @@ static int llama_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hip
   DH_FAIL(DH_ERR_INVALID_ARG, "unknown forward operator %d", op);
 }
 
-static int llama_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipStream_t s) {
+// side_ws: a weight-gradient operator that runs beside its strand (on the other strand's stream) takes its GEMM
+// workspace from there instead of the backward region, which the strand's own GEMMs are using meanwhile.
+static int llama_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipStream_t s, char* side_ws = nullptr) {
   const dh_layer_config& c = L->c;
   const int T = L->T, H = c.hidden, F = c.ffn, dt = c.dtype;
   const char* sv = (const char*)b.saved;
-  void* gws = ws + L->b_gemm;
-  const size_t gwb = L->b_gemm_bytes, n = (size_t)T * H;
+  void* gws = side_ws ? side_ws : ws + L->b_gemm;
+  const size_t gwb = side_ws ? L->f_gemm_bytes : L->b_gemm_bytes, n = (size_t)T * H;
   switch (op) {
     case DH_B_FC2_DGRAD:
       return gemm(L, false, true, T, F, H, b.dout, L->w.Wd, ws + L->b_da, false, gws, gwb, s);
@@ -497,7 +506,7 @@ static int cp_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hipStr
   return llama_fwd_op(L, same[op], a, ws, s);
 }
 
-static int cp_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipStream_t s) {
+static int cp_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipStream_t s, char* side_ws = nullptr) {
   static const int same[DH_CB_NOPS] = {DH_B_FC2_DGRAD, DH_B_FC2_WGRAD, DH_B_ACT, DH_B_FC1_DGRAD, DH_B_FC1_WGRAD, DH_B_AR3,
                                        DH_B_NORM2, DH_B_PROJ_DGRAD, DH_B_PROJ_WGRAD, -1, -1, -1, DH_B_QKV_DGRAD,
                                        DH_B_QKV_WGRAD, DH_B_AR4, DH_B_NORM1};
@@ -530,7 +539,7 @@ static int cp_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipStr
       return dh_rope_at(c.dtype, L->T, c.seq, L->q_off, c.n_q_heads + c.n_kv_heads, c.head_dim, L->n_qkv, c.rope_base, 1, ws + L->b_dqkv, s);
   }
   if (op < 0 || op >= DH_CB_NOPS) DH_FAIL(DH_ERR_INVALID_ARG, "unknown backward operator %d", op);
-  return llama_bwd_op(L, same[op], b, ws, s);
+  return llama_bwd_op(L, same[op], b, ws, s, side_ws);
 }
 
 // GPT-style layer under tensor + sequence parallelism (Sec. 2.1).  The norms, residuals and the
@@ -671,12 +680,12 @@ static int moe_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hipSt
   DH_FAIL(DH_ERR_INVALID_ARG, "unknown forward operator %d", op);
 }
 
-static int moe_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipStream_t s) {
+static int moe_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipStream_t s, char* side_ws = nullptr) {
   const dh_layer_config& c = L->c;
   const int T = L->T, Tf = L->Tf, H = c.hidden, F = c.ffn, dt = c.dtype, E = c.n_experts, nl = c.n_local_experts;
   const char* sv = (const char*)b.saved;
-  void* gws = ws + L->b_gemm;
-  const size_t gwb = L->b_gemm_bytes;
+  void* gws = side_ws ? side_ws : ws + L->b_gemm;
+  const size_t gwb = side_ws ? L->f_gemm_bytes : L->b_gemm_bytes;
   const dh_moe_tables tb = moe_tables_of(L, sv);
   const int32_t* idx = (const int32_t*)(sv + L->s_idx);
   const float* prob = (const float*)(sv + L->s_prob);
@@ -731,12 +740,12 @@ static int run_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hipSt
     default: return llama_fwd_op(L, op, a, ws, s);
   }
 }
-static int run_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipStream_t s) {
+static int run_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipStream_t s, char* side_ws = nullptr) {
   switch (L->c.arch) {
     case DH_ARCH_GPT: return gpt_bwd_op(L, op, b, ws, s);
-    case DH_ARCH_MOE: return moe_bwd_op(L, op, b, ws, s);
-    case DH_ARCH_LLAMA_CP: return cp_bwd_op(L, op, b, ws, s);
-    default: return llama_bwd_op(L, op, b, ws, s);
+    case DH_ARCH_MOE: return moe_bwd_op(L, op, b, ws, s, side_ws);
+    case DH_ARCH_LLAMA_CP: return cp_bwd_op(L, op, b, ws, s, side_ws);
+    default: return llama_bwd_op(L, op, b, ws, s, side_ws);
   }
 }
 
@@ -900,6 +909,13 @@ static int enqueue_si(dh_layer* L, dh_layer* LB, const dh_fwd_args* alpha, const
       }
       if (bj < p.b_end) {
         const int op = plan->bwd_order[bj++];
+        if (two && plan->bwd_side[op]) {  // beside the strand: after what the strand has issued so far, on the other stream
+          hipEvent_t e = next_event(L);
+          DH_HIP(hipEventRecord(e, sb));
+          DH_HIP(hipStreamWaitEvent(sa, e, 0));
+          if ((rc = run_bwd_op(LB, op, *beta, ws_b, sa, ws_f + L->f_gemm))) return rc;
+          continue;
+        }
         if (L->gb.is_comm[op]) rc = on_comm_stream(L, sb, comm_stream_of(L, L->gb.is_comm[op], sc), [&](hipStream_t s) { return run_bwd_op(LB, op, *beta, ws_b, s); });
         else rc = run_bwd_op(LB, op, *beta, ws_b, sb);
         if (rc) return rc;

@@ -188,6 +188,9 @@ extern "C" int dh_plan_validate(const dh_op_graph* fwd, const dh_op_graph* bwd, 
     fi = p.f_end; bj = p.b_end;
   }
   if (fi != plan->n_fwd || bj != plan->n_bwd) DH_FAIL(DH_ERR_PLAN_INVALID, "plan: segment pairs cover %d/%d of %d/%d operators", fi, bj, plan->n_fwd, plan->n_bwd);
+  for (int op = 0; op < DH_MAX_OPS; op++)
+    if (plan->bwd_side[op] && (op >= bwd->n_ops || !bwd->side_ok[op]))
+      DH_FAIL(DH_ERR_PLAN_INVALID, "plan: backward operator %d may not run beside its strand", op);
   return DH_OK;
 }
 

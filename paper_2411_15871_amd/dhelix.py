@@ -70,7 +70,7 @@ class dh_bwd_args(C.Structure):
 
 class dh_op_graph(C.Structure):
     _fields_ = [("n_ops", C.c_int), ("is_comm", C.c_int * DH_MAX_OPS), ("n_deps", C.c_int),
-                ("dep_src", C.c_int * DH_MAX_DEPS), ("dep_dst", C.c_int * DH_MAX_DEPS)]
+                ("dep_src", C.c_int * DH_MAX_DEPS), ("dep_dst", C.c_int * DH_MAX_DEPS), ("side_ok", C.c_int * DH_MAX_OPS)]
 
 
 class dh_overlap_table(C.Structure):
@@ -106,7 +106,8 @@ class dh_stack_bwd(C.Structure):
 
 class dh_plan(C.Structure):
     _fields_ = [("n_fwd", C.c_int), ("n_bwd", C.c_int), ("n_pairs", C.c_int), ("fwd_order", C.c_int * DH_MAX_OPS),
-                ("bwd_order", C.c_int * DH_MAX_OPS), ("pairs", dh_seg_pair * (2 * DH_MAX_OPS))]
+                ("bwd_order", C.c_int * DH_MAX_OPS), ("pairs", dh_seg_pair * (2 * DH_MAX_OPS)),
+                ("bwd_side", C.c_int * DH_MAX_OPS)]
 
 
 # Every symbol include/dhelix.h declares, with its C signature.
@@ -295,7 +296,7 @@ def make_table(t_fwd, t_bwd, rate_fwd, rate_bwd):
     return t
 
 
-def make_graph(n_ops, deps, comm=()):
+def make_graph(n_ops, deps, comm=(), side_ok=()):
     g = dh_op_graph()
     g.n_ops = n_ops
     g.n_deps = len(deps)
@@ -303,11 +304,23 @@ def make_graph(n_ops, deps, comm=()):
         g.dep_src[e], g.dep_dst[e] = s, d
     for c in comm:
         g.is_comm[c] = 1
+    for c in side_ok:
+        g.side_ok[c] = 1
     return g
 
 
-def make_plan(fwd_order, bwd_order, pairs):
+def with_side(plan, side_ops):
+    """A copy of the plan whose backward operators `side_ops` run beside their strand."""
+    q = dh_plan.from_buffer_copy(plan)
+    for op in range(DH_MAX_OPS):
+        q.bwd_side[op] = 1 if op in side_ops else 0
+    return q
+
+
+def make_plan(fwd_order, bwd_order, pairs, side=()):
     p = dh_plan()
+    for op in side:
+        p.bwd_side[op] = 1
     p.n_fwd, p.n_bwd, p.n_pairs = len(fwd_order), len(bwd_order), len(pairs)
     for i, v in enumerate(fwd_order):
         p.fwd_order[i] = v

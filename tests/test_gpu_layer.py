@@ -142,7 +142,8 @@ def random_legal_plan(dh, run, rng):
             continue
         pairs.append((fi, f2, bj, b2))
         fi, bj = f2, b2
-    plan = dh.make_plan(fo, bo, pairs)
+    side = [op for op in range(gb.n_ops) if gb.side_ok[op] and rng.random() < 0.5]  # weight gradients beside the strand
+    plan = dh.make_plan(fo, bo, pairs, side)
     dh.dh_plan_validate(gf, gb, plan)
     return plan
 
@@ -178,6 +179,8 @@ def test_si_step_bitwise_equals_sequential_and_matches_oracle(name):
             "one_pair": dh.make_plan(list(range(nf)), list(range(nb)), [(0, nf, 0, nb)]),
             "op_by_op": dh.make_plan(list(range(nf)), list(range(nb)),
                                      [(min(i, nf), min(i + 1, nf), min(i, nb), min(i + 1, nb)) for i in range(max(nf, nb))]),
+            "all_beside": dh.make_plan(list(range(nf)), list(range(nb)), [(0, nf, 0, nb)],
+                                       [op for op in range(nb) if gb.side_ok[op]]),
             "random_a": random_legal_plan(dh, run, rng),
             "random_b": random_legal_plan(dh, run, rng),
         }

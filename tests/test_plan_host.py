@@ -119,3 +119,19 @@ def test_layer_graphs_and_sequential_plan():
         assert dh.plan_to_py(fixed)[1] == list(range(nb)) and mk_fixed >= mk - 1e-12
     finally:
         dh.dh_layer_destroy(L)
+
+
+def test_side_operators_are_validated():
+    """Only operators the backward graph marks side_ok may be set to run beside their strand."""
+    from paper_2411_15871_amd import dhelix as dh
+    gf = dh.make_graph(2, [(0, 1)])
+    gb = dh.make_graph(3, [(0, 1)], side_ok=(2,))
+    ok = dh.make_plan([0, 1], [0, 1, 2], [(0, 2, 0, 3)], side=(2,))
+    dh.dh_plan_validate(gf, gb, ok)
+    for bad_op in (1, 5):
+        bad = dh.make_plan([0, 1], [0, 1, 2], [(0, 2, 0, 3)], side=(bad_op,))
+        with pytest.raises(dh.DhelixError) as e:
+            dh.dh_plan_validate(gf, gb, bad)
+        assert e.value.code == dh.DH_ERR_PLAN_INVALID
+    q = dh.with_side(ok, ())
+    assert list(q.bwd_side) == [0] * dh.DH_MAX_OPS and list(ok.bwd_side)[2] == 1
