@@ -57,7 +57,9 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_fwd_kernel(const T* __res
 // gradient sum_t dy*xh is accumulated per thread over the block's rows and written as one partial
 // row per block; two small kernels then add the partial rows in a fixed order (first groups of
 // COLSUM_GROUP consecutive rows, then the groups), so the result does not depend on scheduling.
-#define NORM_BWD_RPB 8
+// Rows a backward-norm block walks (its partial gain gradient is one row of the column-sum input): 8, fewer for
+// short inputs so that a couple of hundred blocks exist.
+__host__ __device__ static inline int norm_bwd_rpb(int rows) { return rows >= 4096 ? 8 : rows >= 1024 ? 4 : rows >= 512 ? 2 : 1; }
 #define COLSUM_GROUP 32
 template <typename T, int NCH>
 __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
@@ -75,8 +77,9 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_bwd_kernel(const T* __res
 #pragma unroll
     for (int i = 0; i < 8; i++) dg[c][i] = 0.f;
   }
-  const size_t row0 = (size_t)blockIdx.x * NORM_BWD_RPB;
-  const int nrows = min(NORM_BWD_RPB, rows - (int)row0);
+  const int rpb = norm_bwd_rpb(rows);
+  const size_t row0 = (size_t)blockIdx.x * rpb;
+  const int nrows = min(rpb, rows - (int)row0);
   Vec8<T> ndy[NCH], nx[NCH], nres[NCH];
   auto fetch = [&](size_t row) {
 #pragma unroll
@@ -157,17 +160,25 @@ __global__ void colsum_accumulate_kernel(const float* __restrict__ partial, floa
   int col = blockIdx.x * blockDim.x + threadIdx.x;
   if (col >= H) return;
   float s = 0.f;
-  for (int b = 0; b < nblk; b++) s += partial[(size_t)b * ld + col];
+  for (int b0 = 0; b0 < nblk; b0 += 16) {  // 16 independent loads in flight, added in ascending order
+    float v[16];
+#pragma unroll
+    for (int i = 0; i < 16; i++) v[i] = b0 + i < nblk ? partial[(size_t)(b0 + i) * ld + col] : 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; i++) s += v[i];
+  }
   dst[col] += s;
 }
 
 // ------------------------------------------------------------------------------------ RoPE
 // In place on heads stored side by side in a row of `row_stride` elements.  A thread rotates 8
 // pairs (i, i + d/2).  Angles are formed in double so that position*theta keeps full fp32 accuracy
-// at long sequences.
+// at long sequences: theta of the thread's first pair by one double exp2, the next seven by multiplying with
+// ratio = base^(-2/d); the angle is reduced to [-pi, pi] in double, and only sine and cosine of the reduced
+// angle are taken in float (absolute error ~1e-7).
 template <typename T>
 __global__ void rope_kernel(T* __restrict__ t, int rows, int seq, int pos0, int n_heads, int d, int row_stride, double log2_base,
-                            int inverse) {
+                            double ratio, int inverse) {
   int half = d / 2;
   int chunks = half / 8;
   size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -182,12 +193,15 @@ __global__ void rope_kernel(T* __restrict__ t, int rows, int seq, int pos0, int 
   Vec8<T> a, b, oa, ob;
   a.load(pa);
   b.load(pb);
+  double theta = exp2(-2.0 * (double)(c * 8) / (double)d * log2_base);
 #pragma unroll
   for (int i = 0; i < 8; i++) {
-    double theta = exp2(-2.0 * (double)(c * 8 + i) / (double)d * log2_base);
-    double sn, cs;
-    sincos((double)pos * theta, &sn, &cs);
-    float s = inverse ? -(float)sn : (float)sn, co = (float)cs;
+    double ang = (double)pos * theta;
+    ang -= 6.283185307179586476925 * rint(ang * 0.15915494309189533577);
+    theta *= ratio;
+    float sn, co;
+    sincosf((float)ang, &sn, &co);
+    float s = inverse ? -sn : sn;
     oa.v[i] = a.v[i] * co - b.v[i] * s;
     ob.v[i] = a.v[i] * s + b.v[i] * co;
   }
@@ -283,7 +297,7 @@ template <typename T>
 static int rmsnorm_bwd_t(int rows, int H, const void* dy, const void* x, const void* gamma, const float* rstd,
                          const void* dres, void* dx, float* dgamma, float* partial, hipStream_t s) {
   int nch = nch_for(H);
-  int nblk = (rows + NORM_BWD_RPB - 1) / NORM_BWD_RPB;
+  int nblk = (rows + norm_bwd_rpb(rows) - 1) / norm_bwd_rpb(rows);
   dim3 g(nblk), b(ROW_THREADS);
 #define GO(N)                                                                                                       \
   rmsnorm_bwd_kernel<T, N><<<g, b, 0, s>>>((const T*)dy, (const T*)x, (const T*)gamma, rstd, (const T*)dres, (T*)dx, \
@@ -301,13 +315,13 @@ static int rmsnorm_bwd_t(int rows, int H, const void* dy, const void* x, const v
   float* grouped = partial + (size_t)nblk * H;
   colsum_group_kernel<<<dim3((H + 255) / 256, ngrp), 256, 0, s>>>(partial, grouped, nblk, H);
   DH_LAUNCH_CHECK();
-  colsum_accumulate_kernel<<<(H + 255) / 256, 256, 0, s>>>(grouped, dgamma, ngrp, H, H);
+  colsum_accumulate_kernel<<<(H + 63) / 64, 64, 0, s>>>(grouped, dgamma, ngrp, H, H);
   DH_LAUNCH_CHECK();
   return DH_OK;
 }
 
 extern "C" size_t dh_rmsnorm_bwd_ws_bytes(int T, int H) {
-  size_t nblk = (size_t)(T + NORM_BWD_RPB - 1) / NORM_BWD_RPB;
+  size_t nblk = (size_t)(T + norm_bwd_rpb(T) - 1) / norm_bwd_rpb(T);
   size_t ngrp = (nblk + COLSUM_GROUP - 1) / COLSUM_GROUP;
   return (nblk + ngrp) * H * sizeof(float);
 }
@@ -339,11 +353,11 @@ extern "C" int dh_rope_at(int dtype, int T, int seq, int pos0, int n_heads, int 
   if (!t) DH_FAIL(DH_ERR_INVALID_ARG, "rope: null pointer");
   size_t total = (size_t)T * n_heads * (head_dim / 16);
   dim3 g((unsigned)((total + 255) / 256)), b(256);
-  double l2b = log2((double)base);
+  const double l2b = log2((double)base), ratio = exp2(-2.0 / (double)head_dim * l2b);
   if (dtype == DH_BF16)
-    rope_kernel<bf16_t><<<g, b, 0, (hipStream_t)stream>>>((bf16_t*)t, T, seq, pos0, n_heads, head_dim, row_stride, l2b, inverse);
+    rope_kernel<bf16_t><<<g, b, 0, (hipStream_t)stream>>>((bf16_t*)t, T, seq, pos0, n_heads, head_dim, row_stride, l2b, ratio, inverse);
   else
-    rope_kernel<float><<<g, b, 0, (hipStream_t)stream>>>((float*)t, T, seq, pos0, n_heads, head_dim, row_stride, l2b, inverse);
+    rope_kernel<float><<<g, b, 0, (hipStream_t)stream>>>((float*)t, T, seq, pos0, n_heads, head_dim, row_stride, l2b, ratio, inverse);
   DH_LAUNCH_CHECK();
   return DH_OK;
 }
@@ -474,8 +488,9 @@ __global__ __launch_bounds__(ROW_THREADS) void layernorm_bwd_kernel(const T* __r
 #pragma unroll
     for (int i = 0; i < 8; i++) dg[c][i] = db[c][i] = 0.f;
   }
-  const size_t row0 = (size_t)blockIdx.x * NORM_BWD_RPB;
-  const int nrows = min(NORM_BWD_RPB, rows - (int)row0);
+  const int rpb = norm_bwd_rpb(rows);
+  const size_t row0 = (size_t)blockIdx.x * rpb;
+  const int nrows = min(rpb, rows - (int)row0);
   for (int rr = 0; rr < nrows; rr++) {
     const size_t row = row0 + rr;
     const float r = rstd[row], m = mu[row];
@@ -633,7 +648,7 @@ extern "C" int dh_layernorm_bwd(int dtype, int T, int H, const void* dy, const v
   if (!ws || ws_bytes < dh_layernorm_bwd_ws_bytes(T, H))
     DH_FAIL(DH_ERR_WORKSPACE_TOO_SMALL, "layernorm_bwd: workspace %zu < %zu bytes", ws_bytes, dh_layernorm_bwd_ws_bytes(T, H));
   const int nch = nch_for(H);
-  const int nblk = (T + NORM_BWD_RPB - 1) / NORM_BWD_RPB;
+  const int nblk = (T + norm_bwd_rpb(T) - 1) / norm_bwd_rpb(T);
   float* partial = (float*)ws;
   hipStream_t s = (hipStream_t)stream;
 #define GO(TT, N)                                                                                                          \
@@ -654,9 +669,9 @@ extern "C" int dh_layernorm_bwd(int dtype, int T, int H, const void* dy, const v
   float* grouped = partial + (size_t)nblk * 2 * H;
   colsum_group_kernel<<<dim3((2 * H + 255) / 256, ngrp), 256, 0, s>>>(partial, grouped, nblk, 2 * H);
   DH_LAUNCH_CHECK();
-  colsum_accumulate_kernel<<<(H + 255) / 256, 256, 0, s>>>(grouped, dgamma, ngrp, H, 2 * H);
+  colsum_accumulate_kernel<<<(H + 63) / 64, 64, 0, s>>>(grouped, dgamma, ngrp, H, 2 * H);
   DH_LAUNCH_CHECK();
-  colsum_accumulate_kernel<<<(H + 255) / 256, 256, 0, s>>>(grouped + H, dbeta, ngrp, H, 2 * H);
+  colsum_accumulate_kernel<<<(H + 63) / 64, 64, 0, s>>>(grouped + H, dbeta, ngrp, H, 2 * H);
   DH_LAUNCH_CHECK();
   return DH_OK;
 }
@@ -720,7 +735,7 @@ extern "C" int dh_colsum(int dtype, int T, int N, const void* x, float* out, voi
   DH_LAUNCH_CHECK();
   colsum_group_kernel<<<dim3((N + 255) / 256, ngrp), 256, 0, s>>>(partial, grouped, nblk, N);
   DH_LAUNCH_CHECK();
-  colsum_accumulate_kernel<<<(N + 255) / 256, 256, 0, s>>>(grouped, out, ngrp, N, N);
+  colsum_accumulate_kernel<<<(N + 63) / 64, 64, 0, s>>>(grouped, out, ngrp, N, N);
   DH_LAUNCH_CHECK();
   return DH_OK;
 }
