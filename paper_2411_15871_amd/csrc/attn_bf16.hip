@@ -905,9 +905,9 @@ static int attn_num_cus() {
 // simulated for each candidate length: a unit costs its tiles plus a fixed overhead, every chunk of a split launch
 // costs the traffic of its float32 partial result (written, then read by the merging kernel), and a split launch
 // pays for the merging kernels.  The constants are measured on MI355X (microseconds): a compute unit finishes a
-// forward tile in 1.45 whether one or two blocks share it, a dQ plus a dK/dV tile in 4.4; HBM moves 4 MB per
-// microsecond under this load.  The backward kernels share one length (and one partial-result layout).
-enum { PICK_FWD = 0, PICK_BWD = 1 };
+// forward tile in 1.45 whether one or two blocks share it, a dQ tile in 1.8, a dK/dV tile in 2.5; HBM moves 4 MB per
+// microsecond under this load.
+enum { PICK_FWD = 0, PICK_DQ = 1, PICK_DKV = 2 };
 struct PickKey {
   int kind, seq, q_off, nq_all, d, grouped, cus;
   bool operator<(const PickKey& o) const {
@@ -930,8 +930,8 @@ static double simulate_launch(int kind, int seq, int q_off, int nq_all, int ch, 
       }
     }
   };
-  if (kind == PICK_BWD) for (int i = 0; i < nblk; i++) run(dkv_tiles(i, seq, q_off));  // dQ walks the mirror image
-  else for (int i = nblk - 1; i >= qb0; i--) run(dq_tiles(i, seq));                    // forward: the tiles dQ walks
+  if (kind == PICK_DKV) for (int i = 0; i < nblk; i++) run(dkv_tiles(i, seq, q_off));
+  else for (int i = nblk - 1; i >= qb0; i--) run(dq_tiles(i, seq));  // forward: the tiles dQ walks
   return makespan;
 }
 static int pick_chunk(int kind, int seq, int q_off, int nq_all, int d, bool grouped) {
@@ -939,35 +939,33 @@ static int pick_chunk(int kind, int seq, int q_off, int nq_all, int d, bool grou
   static std::map<PickKey, int> cache;
   const PickKey key{kind, seq, q_off, nq_all, d, grouped ? 1 : 0, attn_num_cus()};
 #ifdef DH_ATTN_SWEEP  // tuning builds only: chunk lengths from the environment
-  if (const char* e = getenv(kind == PICK_FWD ? "DH_ATTN_CH_FWD" : "DH_ATTN_CH_BWD")) return atoi(e) > 0 ? atoi(e) : (1 << 20);
+  if (const char* e = getenv(kind == PICK_FWD ? "DH_ATTN_CH_FWD" : kind == PICK_DQ ? "DH_ATTN_CH_DQ" : "DH_ATTN_CH_DKV")) return atoi(e) > 0 ? atoi(e) : (1 << 20);
 #endif
   std::lock_guard<std::mutex> lock(mu);
   auto it = cache.find(key);
   if (it != cache.end()) return it->second;
   const int nblk = (seq + 127) / 128, qb0 = q_off / 128;
-  const int max_tiles = kind == PICK_BWD ? dkv_tiles(0, seq, q_off) : dq_tiles(nblk - 1, seq);
-  const double t_tile = (kind == PICK_FWD ? 1.45 : 4.4) * d / 128.0, t_ovh = kind == PICK_FWD ? 3.0 : 6.0;
-  const double us_per_byte = 2.0 / 4.0e6, t_merge = kind == PICK_FWD ? 12.0 : 25.0;
-  static const int cand_fwd[] = {4, 8, 16, 32, 64, 1 << 20}, cand_bwd[] = {4, 6, 8, 12, 16, 24, 32, 48, 64, 1 << 20};
+  const int max_tiles = kind == PICK_DKV ? dkv_tiles(0, seq, q_off) : dq_tiles(nblk - 1, seq);
+  const double t_tile = (kind == PICK_FWD ? 1.45 : kind == PICK_DQ ? 1.8 : 2.5) * d / 128.0, t_ovh = 3.0;
+  const double us_per_byte = 2.0 / 4.0e6, t_merge = 12.0;
+  static const int cand_fwd[] = {4, 8, 16, 32, 64, 1 << 20}, cand_bwd[] = {4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 1 << 20};
   const int* cand = kind == PICK_FWD ? cand_fwd : cand_bwd;
-  const int n_cand = kind == PICK_FWD ? 6 : 10;
+  const int n_cand = kind == PICK_FWD ? 6 : 12;
   int best = cand[n_cand - 1];
   double best_t = 1e300;
   for (int k = 0; k < n_cand; k++) {
     const int ch = cand[k];
     if (ch < (1 << 20) && ch >= max_tiles) continue;  // same as not splitting
-    int units_q = 0, units_k = 0;
-    for (int i = qb0; i < nblk; i++) units_q += chunks_of(dq_tiles(i, seq), ch);
-    for (int i = 0; i < nblk; i++) units_k += chunks_of(dkv_tiles(i, seq, q_off), ch);
-    const bool split = units_q > nblk - qb0 || (kind == PICK_BWD && units_k > nblk);
+    int units = 0;
+    if (kind == PICK_DKV) for (int i = 0; i < nblk; i++) units += chunks_of(dkv_tiles(i, seq, q_off), ch);
+    else for (int i = qb0; i < nblk; i++) units += chunks_of(dq_tiles(i, seq), ch);
+    const bool split = units > (kind == PICK_DKV ? nblk : nblk - qb0);
     double t = simulate_launch(kind, seq, q_off, nq_all, ch, attn_num_cus(), t_tile, t_ovh);
     double bytes = 0.0;
-    if (kind == PICK_FWD) { if (split) bytes = (double)units_q * (d + 2); }
-    else {
-      if (split) bytes = (double)units_q * d;
-      if (split || grouped) bytes += (double)units_k * 2 * d;
-    }
-    t += bytes * nq_all * 128 * sizeof(float) * us_per_byte + (split ? t_merge : 0.0);
+    if (kind == PICK_FWD) { if (split) bytes = (double)units * (d + 2); }
+    else if (kind == PICK_DQ) { if (split) bytes = (double)units * d; }
+    else if (split || grouped) bytes = (double)units * 2 * d;
+    t += bytes * nq_all * 128 * sizeof(float) * us_per_byte + (split && !(kind == PICK_DKV && grouped) ? t_merge : 0.0);
 #ifdef DH_ATTN_SWEEP
     fprintf(stderr, "pick kind %d seq %d heads %d: ch %d -> %.1f us (split %d)\n", kind, seq, nq_all, ch, t, (int)split);
 #endif
@@ -982,9 +980,10 @@ static int fwd_chunk_tiles(int batch, int seq, int q_off, int nq, int d) {
   const int ch = pick_chunk(PICK_FWD, seq, q_off, nq * batch, d, false);
   return ch >= (1 << 20) ? 0 : ch;
 }
-// Tiles per chunk of the two backward kernels.
-static int bwd_chunk_tiles(int batch, int seq, int q_off, int nq, int nkv, int d) {
-  return pick_chunk(PICK_BWD, seq, q_off, nq * batch, d, nq > nkv);
+// Tiles per chunk of the dQ and of the dK/dV kernel.
+static void bwd_chunk_tiles(int batch, int seq, int q_off, int nq, int nkv, int d, int& ch_q, int& ch_k) {
+  ch_q = pick_chunk(PICK_DQ, seq, q_off, nq * batch, d, false);
+  ch_k = pick_chunk(PICK_DKV, seq, q_off, nq * batch, d, nq > nkv);
 }
 
 // The launchers take the queries' sequence length seq_q and q_off; kv == nullptr selects plain attention (keys and
@@ -1042,25 +1041,30 @@ int dh_launch_attn_fwd_bf16(int batch, int seq_q, int nq, int nkv, int d, const 
 
 // workspace: lse2[nq*T] floats; dK/dV partials [batch][nq][pairs][128][2d] floats when heads are grouped
 // or some block needs more than one chunk; dQ partials [batch][nq][pairs][128][d] floats in the latter case
-static void bwd_ws_layout(int batch, int seq_q, int q_off, int nq, int nkv, int d, size_t& o_lse2, size_t& o_dkv, size_t& o_dq,
-                          size_t& total, int& pairs, bool& chunked, int& cl) {
+struct BwdLayout {
+  size_t o_lse2, o_dkv, o_dq, total;
+  int ch_q, ch_k, pq, pk;   // chunk lengths and (block, chunk) pair counts of the dQ and the dK/dV launch
+  bool part_q, part_kv;     // whether the launch writes float32 partial results
+};
+static BwdLayout bwd_ws_layout(int batch, int seq_q, int q_off, int nq, int nkv, int d) {
+  BwdLayout L;
   const size_t T = (size_t)batch * seq_q;
   const int seq = q_off + seq_q, nblk = (seq + 127) / 128;
-  cl = bwd_chunk_tiles(batch, seq, q_off, nq, nkv, d);
-  const int pq = total_pairs_dq(seq, q_off, cl), pk = total_pairs_dkv(seq, q_off, cl);
-  pairs = pq > pk ? pq : pk;
-  chunked = pq > nblk - q_off / 128 || pk > nblk;
+  bwd_chunk_tiles(batch, seq, q_off, nq, nkv, d, L.ch_q, L.ch_k);
+  L.pq = total_pairs_dq(seq, q_off, L.ch_q);
+  L.pk = total_pairs_dkv(seq, q_off, L.ch_k);
+  L.part_q = L.pq > nblk - q_off / 128;
+  L.part_kv = nq > nkv || L.pk > nblk;
   size_t cur = 0;
-  o_lse2 = cur; cur += dh_align_up(nq * T * sizeof(float), 256);
-  o_dkv = cur; if (nq > nkv || chunked) cur += dh_align_up((size_t)batch * nq * pairs * 128 * 2 * d * sizeof(float), 256);
-  o_dq = cur; if (chunked) cur += dh_align_up((size_t)batch * nq * pairs * 128 * d * sizeof(float), 256);
-  total = cur;
+  L.o_lse2 = cur; cur += dh_align_up(nq * T * sizeof(float), 256);
+  L.o_dkv = cur; if (L.part_kv) cur += dh_align_up((size_t)batch * nq * L.pk * 128 * 2 * d * sizeof(float), 256);
+  L.o_dq = cur; if (L.part_q) cur += dh_align_up((size_t)batch * nq * L.pq * 128 * d * sizeof(float), 256);
+  L.total = cur;
+  return L;
 }
 
 size_t dh_attn_bwd_bf16_ws_bytes(int batch, int seq_q, int q_off, int nq, int nkv, int d) {
-  size_t a, b, c, total; int pairs, cl; bool chunked;
-  bwd_ws_layout(batch, seq_q, q_off, nq, nkv, d, a, b, c, total, pairs, chunked, cl);
-  return total;
+  return bwd_ws_layout(batch, seq_q, q_off, nq, nkv, d).total;
 }
 
 int dh_launch_attn_bwd_bf16(int batch, int seq_q, int nq, int nkv, int d, const bf16_t* qkv, const bf16_t* kv, int ldkv, int q_off,
@@ -1076,15 +1080,17 @@ int dh_launch_attn_bwd_bf16(int batch, int seq_q, int nq, int nkv, int d, const 
   g.seq = seq; g.q_off = q_off; g.nq = nq; g.nkv = nkv;
   if (kv) { g.kv = kv; g.ldkv = ldkv; g.dkv = dkv; g.lddkv = lddkv; }
   else { g.kv = qkv + (size_t)nq * d; g.dkv = dqkv + (size_t)nq * d; g.ldkv = g.lddkv = (nq + 2 * nkv) * d; }
-  size_t o_lse2, o_dkv, o_dq, need; int pairs_max, cl; bool chunked;
-  bwd_ws_layout(batch, seq_q, q_off, nq, nkv, d, o_lse2, o_dkv, o_dq, need, pairs_max, chunked, cl);
-  g.ch = cl; g.nq_all = nq * batch;
-  if (!ws || ws_bytes < need) DH_FAIL(DH_ERR_WORKSPACE_TOO_SMALL, "attn_bwd: workspace %zu < %zu bytes", ws_bytes, need);
-  float* lse2 = (float*)((char*)ws + o_lse2);
-  float* part_kv = (nq > nkv || chunked) ? (float*)((char*)ws + o_dkv) : nullptr;
-  float* part_q = chunked ? (float*)((char*)ws + o_dq) : nullptr;
+  const BwdLayout lay = bwd_ws_layout(batch, seq_q, q_off, nq, nkv, d);
+  g.nq_all = nq * batch;
+  AttnGeom gq_geom = g, gk_geom = g;
+  gq_geom.ch = lay.ch_q;
+  gk_geom.ch = lay.ch_k;
+  if (!ws || ws_bytes < lay.total) DH_FAIL(DH_ERR_WORKSPACE_TOO_SMALL, "attn_bwd: workspace %zu < %zu bytes", ws_bytes, lay.total);
+  float* lse2 = (float*)((char*)ws + lay.o_lse2);
+  float* part_kv = lay.part_kv ? (float*)((char*)ws + lay.o_dkv) : nullptr;
+  float* part_q = lay.part_q ? (float*)((char*)ws + lay.o_dq) : nullptr;
   const float sc = (float)(1.0 / sqrt((double)d)), sl2 = (float)(1.4426950408889634 / sqrt((double)d));
-  const int nblk = (seq + 127) / 128, nblk_q = nblk - q_off / 128, pq = total_pairs_dq(seq, q_off, cl), pk = total_pairs_dkv(seq, q_off, cl);
+  const int nblk = (seq + 127) / 128, nblk_q = nblk - q_off / 128, pq = lay.pq, pk = lay.pk;
   dim3 gwq((unsigned)pq * nq * batch), gwk((unsigned)pk * nq * batch), gq(nblk_q * 16, nq, batch), gk(nblk * 32, nkv, batch);
   const unsigned nprep = (unsigned)(((size_t)T * nq + 3) / 4);
   const size_t lds_dq = 2 * AB_RING * (size_t)AB_KT * d * 2, lds_dkv = lds_dq + 2 * AB_RING * AB_KT * sizeof(float);
@@ -1097,12 +1103,12 @@ int dh_launch_attn_bwd_bf16(int batch, int seq_q, int nq, int nkv, int d, const 
     }                                                                                                                          \
     attn_bwd_prep_kernel<DD><<<nprep, 256, 0, stream>>>(nq, o, dout, lse, delta, lse2, T);                                       \
     DH_LAUNCH_CHECK();                                                                                                         \
-    attn_bwd_dq_bf16_kernel<DD><<<gwq, AB_THREADS, lds_dq, stream>>>(g, qkv, dout, lse2, delta, dqkv, part_q, pq, T, sc, sl2);   \
+    attn_bwd_dq_bf16_kernel<DD><<<gwq, AB_THREADS, lds_dq, stream>>>(gq_geom, qkv, dout, lse2, delta, dqkv, part_q, pq, T, sc, sl2);   \
     DH_LAUNCH_CHECK();                                                                                                         \
-    if (part_q) { attn_bwd_dq_reduce_kernel<DD><<<gq, 256, 0, stream>>>(part_q, dqkv, seq, q_off, nq, nkv, pq, cl, sc); DH_LAUNCH_CHECK(); } \
-    attn_bwd_dkv_bf16_kernel<DD><<<gwk, AB_THREADS, lds_dkv, stream>>>(g, qkv, dout, lse2, delta, part_kv, pk, T, sc, sl2);      \
+    if (part_q) { attn_bwd_dq_reduce_kernel<DD><<<gq, 256, 0, stream>>>(part_q, dqkv, seq, q_off, nq, nkv, pq, lay.ch_q, sc); DH_LAUNCH_CHECK(); } \
+    attn_bwd_dkv_bf16_kernel<DD><<<gwk, AB_THREADS, lds_dkv, stream>>>(gk_geom, qkv, dout, lse2, delta, part_kv, pk, T, sc, sl2);      \
     DH_LAUNCH_CHECK();                                                                                                         \
-    if (part_kv) { attn_bwd_group_reduce_kernel<DD><<<gk, 256, 0, stream>>>(part_kv, g, pk); DH_LAUNCH_CHECK(); }                \
+    if (part_kv) { attn_bwd_group_reduce_kernel<DD><<<gk, 256, 0, stream>>>(part_kv, gk_geom, pk); DH_LAUNCH_CHECK(); }                \
   } while (0)
   if (d == 128) DH_ATTN_BWD(128, 0); else DH_ATTN_BWD(64, 1);
 #undef DH_ATTN_BWD
