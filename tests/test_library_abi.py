@@ -45,3 +45,32 @@ def test_op_names_and_error_strings():
         dh.dh_layer_create(arch=7, dtype=1, batch=1, seq=8, hidden=64, n_q_heads=2, n_kv_heads=1, head_dim=64, ffn=64,
                            eps=1e-5, rope_base=1e4, n_ranks=1)
     assert e.value.code == dh.DH_ERR_UNSUPPORTED
+
+
+def test_context_parallel_layer_configuration_is_checked():
+    """Host-only checks of the context-parallel layer description: rank range, the bf16 kernels' 128-position grid, and
+    the sizes that grow with the rank's position (it attends to cp_rank+1 chunks of keys)."""
+    base = dict(arch=dh.DH_ARCH_LLAMA_CP, dtype=dh.DH_BF16, batch=1, seq=256, hidden=64, n_q_heads=2, n_kv_heads=1, head_dim=64,
+                ffn=64, eps=1e-5, rope_base=1e4, n_ranks=1, cp_ranks=4)
+    for bad in (dict(cp_rank=4), dict(cp_rank=-1), dict(cp_ranks=0, cp_rank=0), dict(cp_ranks=17, cp_rank=0),
+                dict(cp_rank=1, cross_blocks=-1)):
+        with pytest.raises(dh.DhelixError) as e:
+            dh.dh_layer_create(**{**base, **bad})
+        assert e.value.code == dh.DH_ERR_INVALID_ARG
+    with pytest.raises(dh.DhelixError) as e:  # 3 * 200 is not a multiple of 128
+        dh.dh_layer_create(**{**base, "seq": 200, "cp_rank": 3})
+    assert e.value.code == dh.DH_ERR_SHAPE
+    dh.dh_layer_destroy(dh.dh_layer_create(**{**base, "seq": 200, "cp_rank": 3, "dtype": dh.DH_F32}))  # fp32 has no such grid
+    sizes = []
+    for r in range(4):
+        layer = dh.dh_layer_create(**{**base, "cp_rank": r})
+        sizes.append((dh.dh_layer_saved_bytes(layer), dh.dh_layer_workspace_bytes(layer, dh.DH_WS_BWD)))
+        gf, gb = dh.dh_layer_op_graph(layer, 0), dh.dh_layer_op_graph(layer, 1)
+        assert gf.n_ops == 13 and gb.n_ops == 16
+        assert [gf.is_comm[i] for i in range(13)].count(2) == 1 and [gb.is_comm[i] for i in range(16)].count(2) == 1
+        assert sum(gb.side_ok[i] for i in range(16)) == 4
+        dh.dh_layer_destroy(layer)
+    assert all(a[0] < b[0] and a[1] < b[1] for a, b in zip(sizes, sizes[1:]))  # one more chunk of keys and key gradients per rank
+    plain = dh.dh_layer_create(**{**base, "arch": dh.DH_ARCH_LLAMA, "cp_ranks": 0})
+    assert dh.dh_layer_saved_bytes(plain) < sizes[0][0]
+    dh.dh_layer_destroy(plain)
