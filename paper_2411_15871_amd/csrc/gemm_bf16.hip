@@ -55,7 +55,24 @@ struct GemmArgs {
   const bf16_t* bias;          // optional [N], added before the bf16 store
   const int32_t* group_rows;   // grouped GEMM: device array of row counts (blockIdx.z = group), else nullptr
   int group_mode;              // 0/1: groups split M (A and C rows), B per group; 2: groups split K, C per group
+  // Modes 0/1 are issued as two launches: part 1 with the large tile, part 2 with the 128x128 tile.  When the groups'
+  // large tiles would leave the last round of tiles over the compute units nearly empty (the row counts are data), part 1
+  // keeps only each group's whole large-tile rows and part 2 takes the remainders; otherwise part 1 does everything.
+  int group_part, n_groups, part1_bm, part1_bn, cus;
 };
+
+// Whether the remainders go to part 2: decided from the device-side row counts, the same way by both launches.
+__device__ __forceinline__ bool grouped_split_remainders(const GemmArgs& g) {
+  int full = 0, bulk = 0;
+  const int tn = (g.N + g.part1_bn - 1) / g.part1_bn;
+  for (int i = 0; i < g.n_groups; i++) {
+    const int r = g.group_rows[i];
+    full += (r + g.part1_bm - 1) / g.part1_bm * tn;
+    bulk += r / g.part1_bm * tn;
+  }
+  const int tail = full % g.cus;  // tiles of the last, partly filled round
+  return tail != 0 && tail * 4 < g.cus && bulk <= full / g.cus * g.cus;
+}
 
 // One 16-byte chunk per lane, global -> LDS.  lds_wave_base must be wave-uniform.  Written as inline
 // assembly so that the compiler does not order later LDS reads behind the transfer with a full
@@ -148,7 +165,17 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmArgs g) {
     // grid is sized for the largest possible group; surplus blocks leave at the tile check below.
     int row0 = 0;
     for (int i = 0; i < (int)blockIdx.z; i++) row0 += g.group_rows[i];
-    const int rows = g.group_rows[blockIdx.z];
+    int rows = g.group_rows[blockIdx.z];
+    if (g.group_part != 0) {
+      const bool split = grouped_split_remainders(g);
+      if (g.group_part == 1) {
+        if (split) rows -= rows % g.part1_bm;
+      } else {
+        if (!split) return;
+        row0 += rows - rows % g.part1_bm;
+        rows %= g.part1_bm;
+      }
+    }
     if (rows == 0) return;
     if (g.group_mode == 2) {
       g.A += (size_t)row0 * g.M;
@@ -458,6 +485,7 @@ int dh_launch_gemm_bf16(bool ta, bool tb, int M, int N, int K, const bf16_t* A, 
   g.kt_per_split = p.kt_per_split;
   g.tiles_m = g.tiles_n = g.tiles_per_xcd = 0;
   g.bias = bias; g.group_rows = nullptr; g.group_mode = 0;
+  g.group_part = 0; g.n_groups = 1; g.part1_bm = g.part1_bn = 256; g.cus = 0;
   const int final_epi = out_f32_accumulate ? EPI_ACC_F32 : EPI_STORE_BF16;
   if (p.splits > 1) { g.C = ws; g.epi = EPI_PARTIAL_F32; } else { g.C = C; g.epi = final_epi; }
   int rc;
@@ -485,6 +513,7 @@ int dh_launch_gemm_grouped_bf16(int mode, int n_groups, const int32_t* group_row
   g.A = A; g.B = B; g.C = C;
   g.bias = nullptr; g.group_rows = group_rows; g.group_mode = mode;
   g.tiles_m = g.tiles_n = g.tiles_per_xcd = 0;
+  g.group_part = 0; g.n_groups = n_groups; g.part1_bm = g.part1_bn = 256; g.cus = num_cus();
   const int avg = std::max(1, max_rows / n_groups);
   GemmPlan p;
   if (mode == 2) { g.M = dim_a; g.N = dim_b; g.K = max_rows; p = choose_plan(true, dim_a, dim_b, avg, 0); }
@@ -492,7 +521,14 @@ int dh_launch_gemm_grouped_bf16(int mode, int n_groups, const int32_t* group_row
   p.splits = 1;
   g.kt_per_split = (g.K + GB_BK - 1) / GB_BK;
   g.epi = mode == 2 ? EPI_ACC_F32 : EPI_STORE_BF16;
-  if (mode == 0) return launch_layout<false, false>(g, p, stream, n_groups);
-  if (mode == 1) return launch_layout<false, true>(g, p, stream, n_groups);
-  return launch_layout<true, false>(g, p, stream, n_groups);
+  if (mode == 2) return launch_layout<true, false>(g, p, stream, n_groups);
+  if (p.cfg != 0 || n_groups > 64)  // small tiles already, or too many groups for the in-kernel row scan: one launch
+    return mode == 0 ? launch_layout<false, false>(g, p, stream, n_groups) : launch_layout<false, true>(g, p, stream, n_groups);
+  g.group_part = 1;
+  int rc = mode == 0 ? launch_layout<false, false>(g, p, stream, n_groups) : launch_layout<false, true>(g, p, stream, n_groups);
+  if (rc != DH_OK) return rc;
+  g.group_part = 2;
+  g.M = std::min(max_rows, g.part1_bm - 1);  // a remainder is shorter than a large tile
+  p.cfg = 1; p.bm = p.bn = 128;
+  return mode == 0 ? launch_layout<false, false>(g, p, stream, n_groups) : launch_layout<false, true>(g, p, stream, n_groups);
 }

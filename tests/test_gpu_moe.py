@@ -168,6 +168,34 @@ def test_gemm_grouped(dh, bf16, rows, K, N):
         r0 = r1
 
 
+@pytest.mark.parametrize("rows", [[2100, 2000], [2304, 1792], [2660, 1000], [4100, 0]])
+def test_gemm_grouped_large_tiles_and_remainders(dh, rows):
+    """Shapes that take the 256x256 tile: with 2100 + 2000 rows the large tiles would need a nearly empty second round,
+    so the groups' remainder rows go to the second (small-tile) launch; the other row counts keep everything in the first."""
+    K = N = 4096
+    G, Tt = len(rows), sum(rows)
+    A = gen.normal(31, (Tt, K), 1.0, 0.0, True); W = gen.normal(32, (G, K, N), 0.02, 0.0, True)
+    Ad, Wd = dev(A, True), dev(W, True)
+    Cd = torch.zeros(Tt, N, dtype=Ad.dtype, device="cuda"); dAd = torch.zeros(Tt, K, dtype=Ad.dtype, device="cuda")
+    rd = torch.tensor(rows, dtype=torch.int32, device="cuda")
+    dh.dh_gemm_grouped(dh.DH_BF16, 0, G, rd, Tt, K, N, Ad, Wd, Cd)
+    dh.dh_gemm_grouped(dh.DH_BF16, 1, G, rd, Tt, N, K, Ad, Wd, dAd)   # A stands in for an upstream gradient [Tt, N]
+    torch.cuda.synchronize()
+    r0 = 0
+    A64, W64 = A.astype(np.float64), W.astype(np.float64)
+    for g in range(G):
+        r1 = r0 + rows[g]
+        if r1 > r0:
+            assert rel(host(Cd)[r0:r1], A64[r0:r1] @ W64[g]) <= TOL[True]
+            assert rel(host(dAd)[r0:r1], A64[r0:r1] @ W64[g].T) <= TOL[True]
+            # the seam between the two launches: last whole large-tile row and first remainder row
+            seam = r0 + rows[g] // 256 * 256
+            for r in (seam - 1, seam, r1 - 1):
+                if r0 <= r < r1:
+                    assert rel(host(Cd)[r], A64[r] @ W64[g]) <= TOL[True]
+        r0 = r1
+
+
 @pytest.mark.parametrize("bf16,T,H,F,E,n_local", [(False, 300, 64, 96, 8, 2), (True, 1000, 256, 384, 16, 2),
                                                   (True, 257, 128, 64, 4, 4)])
 def test_moe_block_fwd_bwd(dh, bf16, T, H, F, E, n_local):
