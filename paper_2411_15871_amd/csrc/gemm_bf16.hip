@@ -42,7 +42,7 @@ typedef __attribute__((ext_vector_type(8))) short s16x8;
 
 __device__ __attribute__((aligned(16))) const uint32_t dh_zero_chunk[4] = {0, 0, 0, 0};
 
-enum { EPI_STORE_BF16 = 0, EPI_ACC_F32 = 1, EPI_PARTIAL_F32 = 2 };
+enum { EPI_STORE_BF16 = 0, EPI_ACC_F32 = 1, EPI_PARTIAL_F32 = 2, EPI_TAIL_F32 = 3 };
 
 struct GemmArgs {
   int M, N, K;
@@ -59,7 +59,25 @@ struct GemmArgs {
   // large tiles would leave the last round of tiles over the compute units nearly empty (the row counts are data), part 1
   // keeps only each group's whole large-tile rows and part 2 takes the remainders; otherwise part 1 does everything.
   int group_part, n_groups, part1_bm, part1_bn, cus;
+  // Tail launch: when the tile count leaves the last round over the compute units less than half full, those tiles
+  // are issued apart with K split over blockIdx.y, so that the round is short; tile_first = launch index of this
+  // launch's first tile; EPI_TAIL_F32 writes tile-local float32 partials [split][tile][BM][BN].
+  int tile_first;
 };
+
+// Launch index -> tile coordinates.  XCD-aware: launch indices go round-robin over the 8 XCDs, each XCD owns a
+// contiguous range of the logical tile order, which walks the tiles in bands of 4 tile rows.
+__device__ __forceinline__ bool tile_of_launch(int idx, int tiles_m, int tiles_n, int tiles_per_xcd, int& tm, int& tn) {
+  if ((idx >> 3) >= tiles_per_xcd) return false;  // grouped launches: grid sized for the largest group
+  const int logical = (idx & 7) * tiles_per_xcd + (idx >> 3);
+  if (logical >= tiles_m * tiles_n) return false;
+  const int group = logical / (4 * tiles_n);
+  const int rows_in_group = min(4, tiles_m - group * 4);
+  const int in_group = logical - group * 4 * tiles_n;
+  tm = group * 4 + in_group % rows_in_group;
+  tn = in_group / rows_in_group;
+  return true;
+}
 
 // Whether the remainders go to part 2: decided from the device-side row counts, the same way by both launches.
 __device__ __forceinline__ bool grouped_split_remainders(const GemmArgs& g) {
@@ -201,18 +219,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmArgs g) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm0 = (wave / WN) * WTM, wn0 = (wave % WN) * WTN;
 
-  // XCD-aware tile mapping (see the header comment)
-  if ((int)(blockIdx.x >> 3) >= g.tiles_per_xcd) return;  // only in grouped launches (grid sized for the largest group)
-  const int logical = (blockIdx.x & 7) * g.tiles_per_xcd + (blockIdx.x >> 3);
-  if (logical >= g.tiles_m * g.tiles_n) return;
   int tm, tn;
-  {
-    const int group = logical / (4 * g.tiles_n);
-    const int rows_in_group = min(4, g.tiles_m - group * 4);
-    const int in_group = logical - group * 4 * g.tiles_n;
-    tm = group * 4 + in_group % rows_in_group;
-    tn = in_group / rows_in_group;
-  }
+  if (!tile_of_launch((int)blockIdx.x + g.tile_first, g.tiles_m, g.tiles_n, g.tiles_per_xcd, tm, tn)) return;
   const int m0 = tm * BM, n0 = tn * BN;
   const int nkt_total = (g.K + GB_BK - 1) / GB_BK;
   const int kt_begin = blockIdx.y * g.kt_per_split;
@@ -338,6 +346,19 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmArgs g) {
   float* Cf = reinterpret_cast<float*>(g.C);
   bf16_t* Cb = reinterpret_cast<bf16_t*>(g.C);
   if (g.epi == EPI_PARTIAL_F32) Cf += (size_t)blockIdx.y * g.M * g.N;
+  if (g.epi == EPI_TAIL_F32) {  // whole tile, tile-local layout (rows/columns beyond the matrix are never read back)
+    Cf += ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * (BM * BN);
+#pragma unroll
+    for (int i = 0; i < MT; i++)
+#pragma unroll
+      for (int j = 0; j < NT; j++)
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+          const f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+          *reinterpret_cast<f32x4*>(Cf + (size_t)(wm0 + i * 32 + l32) * BN + wn0 + j * 32 + 8 * q + 4 * kg) = v;
+        }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < MT; i++) {
     const int row = m0 + wm0 + i * 32 + l32;
@@ -387,10 +408,36 @@ __global__ void splitk_reduce_kernel(const float* __restrict__ part, int splits,
   }
 }
 
+// Adds the tail tiles' K splits in split order and applies the final epilogue.  grid (BM*BN/4/256, tail tiles).
+template <int BM, int BN>
+__global__ __launch_bounds__(256) void tail_reduce_kernel(const float* __restrict__ part, int splits, GemmArgs g, int final_epi) {
+  int tm, tn;
+  if (!tile_of_launch((int)blockIdx.y + g.tile_first, g.tiles_m, g.tiles_n, g.tiles_per_xcd, tm, tn)) return;
+  const int e = (blockIdx.x * 256 + threadIdx.x) * 4, r = e / BN, c = e % BN;
+  const int row = tm * BM + r, col = tn * BN + c;
+  if (row >= g.M || col >= g.N) return;
+  const size_t tile_elems = (size_t)BM * BN, n_tail = gridDim.y;
+  f32x4 s = *reinterpret_cast<const f32x4*>(part + blockIdx.y * tile_elems + e);
+  for (int z = 1; z < splits; z++) s += *reinterpret_cast<const f32x4*>(part + ((size_t)z * n_tail + blockIdx.y) * tile_elems + e);
+  const size_t o = (size_t)row * g.N + col;
+  if (final_epi == EPI_STORE_BF16) {
+    if (g.bias != nullptr) {
+      const bf16x4 bb = *reinterpret_cast<const bf16x4*>(g.bias + col);
+      s += f32x4{(float)bb[0], (float)bb[1], (float)bb[2], (float)bb[3]};
+    }
+    bf16x4 b = {(bf16_t)s[0], (bf16_t)s[1], (bf16_t)s[2], (bf16_t)s[3]};
+    *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16_t*>(g.C) + o) = b;
+  } else {
+    f32x4* p = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + o);
+    *p = *p + s;
+  }
+}
+
 // ------------------------------------------------------------------------------------ host side
 struct GemmPlan {
   int cfg;  // 0: 256x256 (8 waves), 1: 128x128 (4 waves), 2: 256x128 (4 waves)
   int bm, bn, splits, kt_per_split;
+  int tail_tiles, tail_splits, tail_kt;  // tail launch (0 tiles = none): its tiles, K splits and K tiles per split
 };
 
 static int g_num_cus = 0;
@@ -436,17 +483,45 @@ static GemmPlan choose_plan(bool ta, int M, int N, int K, size_t ws_bytes) {
 #endif
   p.kt_per_split = nkt == 0 ? 1 : (nkt + splits - 1) / splits;
   p.splits = nkt == 0 ? 1 : (nkt + p.kt_per_split - 1) / p.kt_per_split;
+  // Tail: more than one round of 256x256 tiles whose last round is at most half full -> split those tiles' K so that
+  // the last round takes 1/splits of a round (plus a small ordered reduction) instead of a whole one.
+  p.tail_tiles = p.tail_splits = p.tail_kt = 0;
+  const int tail = (int)(t % cus);
+  if (p.cfg == 0 && p.splits == 1 && t > cus && tail > 0 && tail * 2 <= cus && nkt >= 64) {
+    int ts = cus / tail;
+    if (ts > 8) ts = 8;
+    if (ts > nkt / 16) ts = nkt / 16;
+    const size_t per = (size_t)(tail + 7) * p.bm * p.bn * sizeof(float);  // the launch index range is padded to a multiple of 8
+    if (ws_bytes / per < (size_t)ts) ts = (int)(ws_bytes / per);
+    if (ts >= 2) {
+      p.tail_tiles = tail;
+      p.tail_kt = (nkt + ts - 1) / ts;
+      p.tail_splits = (nkt + p.tail_kt - 1) / p.tail_kt;
+    }
+  }
   return p;
+}
+
+// Launch indices of the tail launch: from the first index of the last round to the end of the (padded) index range.
+static void tail_range(int M, int N, const GemmPlan& p, int& first, int& count) {
+  const long long t = (long long)((M + p.bm - 1) / p.bm) * ((N + p.bn - 1) / p.bn);
+  first = (int)(t / num_cus()) * num_cus();
+  count = (int)((t + 7) / 8 * 8) - first;
 }
 
 size_t dh_gemm_bf16_ws_bytes(bool ta, bool tb, int M, int N, int K) {
   (void)tb;
   GemmPlan p = choose_plan(ta, M, N, K, (size_t)-1);
+  if (p.tail_tiles > 0) {
+    int first, count;
+    tail_range(M, N, p, first, count);
+    return (size_t)count * p.tail_splits * p.bm * p.bn * sizeof(float);
+  }
   return p.splits > 1 ? (size_t)p.splits * M * N * sizeof(float) : 0;
 }
 
 template <int BM, int BN, int WM, int WN, bool TA, bool TB>
-static int launch_cfg(GemmArgs g, int splits, hipStream_t stream, int n_groups = 1) {
+static int launch_cfg(GemmArgs g, int splits, hipStream_t stream, int n_groups = 1, int tile_first = 0, int n_tiles = -1) {
   constexpr size_t LDS_BYTES = GB_STAGES * (size_t)(BM + BN) * GB_BK * sizeof(bf16_t);
   static bool attr_set = false;
   if (!attr_set) {
@@ -457,18 +532,28 @@ static int launch_cfg(GemmArgs g, int splits, hipStream_t stream, int n_groups =
   g.tiles_m = (g.M + BM - 1) / BM;
   g.tiles_n = (g.N + BN - 1) / BN;
   g.tiles_per_xcd = (g.tiles_m * g.tiles_n + 7) / 8;
-  dim3 grid(g.tiles_per_xcd * 8, splits, n_groups);
+  g.tile_first = tile_first;
+  dim3 grid(n_tiles >= 0 ? n_tiles : g.tiles_per_xcd * 8, splits, n_groups);
   gemm_bf16_kernel<BM, BN, WM, WN, TA, TB><<<grid, 64 * WM * WN, LDS_BYTES, stream>>>(g);
   DH_LAUNCH_CHECK();
   return DH_OK;
 }
 
 template <bool TA, bool TB>
-static int launch_layout(const GemmArgs& g, const GemmPlan& p, hipStream_t stream, int n_groups = 1) {
-  if (p.cfg == 0) return launch_cfg<256, 256, 2, 4, TA, TB>(g, p.splits, stream, n_groups);
-  if (p.cfg == 2) return launch_cfg<256, 128, 2, 2, TA, TB>(g, p.splits, stream, n_groups);
-  return launch_cfg<128, 128, 2, 2, TA, TB>(g, p.splits, stream, n_groups);
+static int launch_layout(const GemmArgs& g, const GemmPlan& p, hipStream_t stream, int n_groups = 1, int tile_first = 0,
+                         int n_tiles = -1, int splits = 0) {
+  if (splits == 0) splits = p.splits;
+  if (p.cfg == 0) return launch_cfg<256, 256, 2, 4, TA, TB>(g, splits, stream, n_groups, tile_first, n_tiles);
+  if (p.cfg == 2) return launch_cfg<256, 128, 2, 2, TA, TB>(g, splits, stream, n_groups, tile_first, n_tiles);
+  return launch_cfg<128, 128, 2, 2, TA, TB>(g, splits, stream, n_groups, tile_first, n_tiles);
 }
+template <typename... Args>
+static int launch_any(bool ta, bool tb, Args... args) {
+  if (!ta && !tb) return launch_layout<false, false>(args...);
+  if (!ta && tb) return launch_layout<false, true>(args...);
+  return launch_layout<true, false>(args...);
+}
+
 
 int dh_launch_gemm_bf16(bool ta, bool tb, int M, int N, int K, const bf16_t* A, const bf16_t* B, void* C,
                         bool out_f32_accumulate, const bf16_t* bias, void* ws, size_t ws_bytes, hipStream_t stream) {
@@ -485,14 +570,27 @@ int dh_launch_gemm_bf16(bool ta, bool tb, int M, int N, int K, const bf16_t* A, 
   g.kt_per_split = p.kt_per_split;
   g.tiles_m = g.tiles_n = g.tiles_per_xcd = 0;
   g.bias = bias; g.group_rows = nullptr; g.group_mode = 0;
-  g.group_part = 0; g.n_groups = 1; g.part1_bm = g.part1_bn = 256; g.cus = 0;
+  g.group_part = 0; g.n_groups = 1; g.part1_bm = g.part1_bn = 256; g.cus = 0; g.tile_first = 0;
   const int final_epi = out_f32_accumulate ? EPI_ACC_F32 : EPI_STORE_BF16;
-  if (p.splits > 1) { g.C = ws; g.epi = EPI_PARTIAL_F32; } else { g.C = C; g.epi = final_epi; }
   int rc;
-  if (!ta && !tb) rc = launch_layout<false, false>(g, p, stream);
-  else if (!ta && tb) rc = launch_layout<false, true>(g, p, stream);
-  else rc = launch_layout<true, false>(g, p, stream);
-  if (rc != DH_OK) return rc;
+  if (p.tail_tiles > 0) {  // whole rounds with the final epilogue, then the last round's tiles with K split, then their sum
+    int first, count;
+    tail_range(M, N, p, first, count);
+    g.C = C; g.epi = final_epi;
+    if ((rc = launch_any(ta, tb, g, p, stream, 1, 0, first, 1))) return rc;
+    GemmArgs gt = g;
+    gt.C = ws; gt.epi = EPI_TAIL_F32; gt.kt_per_split = p.tail_kt;
+    if ((rc = launch_any(ta, tb, gt, p, stream, 1, first, count, p.tail_splits))) return rc;
+    gt.C = C;
+    gt.tiles_m = (M + p.bm - 1) / p.bm; gt.tiles_n = (N + p.bn - 1) / p.bn;
+    gt.tiles_per_xcd = (gt.tiles_m * gt.tiles_n + 7) / 8;
+    gt.tile_first = first;
+    tail_reduce_kernel<256, 256><<<dim3(256 * 256 / 4 / 256, count), 256, 0, stream>>>((const float*)ws, p.tail_splits, gt, final_epi);
+    DH_LAUNCH_CHECK();
+    return DH_OK;
+  }
+  if (p.splits > 1) { g.C = ws; g.epi = EPI_PARTIAL_F32; } else { g.C = C; g.epi = final_epi; }
+  if ((rc = launch_any(ta, tb, g, p, stream))) return rc;
   if (p.splits > 1) {
     const size_t mn = (size_t)M * N;  // multiple of 8 because N is
     splitk_reduce_kernel<<<(unsigned)((mn / 4 + 255) / 256), 256, 0, stream>>>((const float*)ws, p.splits, mn, C, final_epi, bias, N);
@@ -513,7 +611,7 @@ int dh_launch_gemm_grouped_bf16(int mode, int n_groups, const int32_t* group_row
   g.A = A; g.B = B; g.C = C;
   g.bias = nullptr; g.group_rows = group_rows; g.group_mode = mode;
   g.tiles_m = g.tiles_n = g.tiles_per_xcd = 0;
-  g.group_part = 0; g.n_groups = n_groups; g.part1_bm = g.part1_bn = 256; g.cus = num_cus();
+  g.group_part = 0; g.n_groups = n_groups; g.part1_bm = g.part1_bn = 256; g.cus = num_cus(); g.tile_first = 0;
   const int avg = std::max(1, max_rows / n_groups);
   GemmPlan p;
   if (mode == 2) { g.M = dim_a; g.N = dim_b; g.K = max_rows; p = choose_plan(true, dim_a, dim_b, avg, 0); }

@@ -120,7 +120,7 @@ def test_bias_residual_add_and_colsum(dh, bf16, T, N):
 
 
 @pytest.mark.parametrize("bf16", [False, True])
-@pytest.mark.parametrize("M,N,K", [(5, 8, 16), (300, 264, 520), (64, 128, 4096), (1030, 1544, 72)])
+@pytest.mark.parametrize("M,N,K", [(5, 8, 16), (300, 264, 520), (64, 128, 4096), (1030, 1544, 72), (4100, 4104, 2048)])
 def test_gemm_bias(dh, bf16, M, N, K):
     A = gen.normal(1, (M, K), 1.0, 0.0, bf16); B = gen.normal(2, (K, N), 0.05, 0.0, bf16); bias = gen.normal(3, (N,), 0.5, 0.0, bf16)
     Ad, Bd, biasd = dev(A, bf16), dev(B, bf16), dev(bias, bf16)

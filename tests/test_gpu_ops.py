@@ -183,7 +183,8 @@ def test_gemm_f32(dh, ta, tb, M, N, K):
 
 BF16_SHAPES = [(8, 8, 8), (128, 128, 64), (256, 256, 128), (300, 264, 200), (1000, 768, 520), (2048, 1024, 512),
                (77, 4096, 1024), (512, 512, 4096), (0, 64, 64),
-               (4096, 1792, 136), (3900, 1704, 200)]  # the last two take the 256x128 tile when A is row-major
+               (4096, 1792, 136), (3900, 1704, 200),  # these two take the 256x128 tile when A is row-major
+               (4104, 4104, 2056)]  # 17 x 17 large tiles: the 33 of the last round are issued apart with K split
 
 
 @pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0)])
