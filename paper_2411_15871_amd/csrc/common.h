@@ -40,10 +40,31 @@ template <typename T> __device__ __forceinline__ T from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }
 
+// 8 elements as they lie in memory (16 bytes of bf16, 32 of float): what a kernel holds for data fetched ahead of
+// its use, converted to float (Vec8) only when the row's turn comes.
+template <typename T> struct Raw8;
+template <> struct Raw8<float> {
+  f32x4 a, b;
+  __device__ __forceinline__ void load(const float* p) {
+    a = *reinterpret_cast<const f32x4*>(p);
+    b = *reinterpret_cast<const f32x4*>(p + 4);
+  }
+  __device__ __forceinline__ float get(int i) const { return i < 4 ? a[i] : b[i - 4]; }
+};
+template <> struct Raw8<bf16_t> {
+  bf16x8 t;
+  __device__ __forceinline__ void load(const bf16_t* p) { t = *reinterpret_cast<const bf16x8*>(p); }
+  __device__ __forceinline__ float get(int i) const { return (float)t[i]; }
+};
+
 // 8-element vector of the storage type, loaded/stored with the widest access.
 template <typename T> struct Vec8;
 template <> struct Vec8<float> {
   float v[8];
+  __device__ __forceinline__ void from(const Raw8<float>& r) {
+#pragma unroll
+    for (int i = 0; i < 8; i++) v[i] = r.get(i);
+  }
   __device__ __forceinline__ void load(const float* p) {
     const float4* q = reinterpret_cast<const float4*>(p);
     float4 a = q[0], b = q[1];
@@ -67,6 +88,10 @@ template <> struct Vec8<float> {
 };
 template <> struct Vec8<bf16_t> {
   float v[8];
+  __device__ __forceinline__ void from(const Raw8<bf16_t>& r) {
+#pragma unroll
+    for (int i = 0; i < 8; i++) v[i] = r.get(i);
+  }
   __device__ __forceinline__ void load(const bf16_t* p) {
     bf16x8 t = *reinterpret_cast<const bf16x8*>(p);
 #pragma unroll

@@ -80,7 +80,7 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_bwd_kernel(const T* __res
   const int rpb = norm_bwd_rpb(rows);
   const size_t row0 = (size_t)blockIdx.x * rpb;
   const int nrows = min(rpb, rows - (int)row0);
-  Vec8<T> ndy[NCH], nx[NCH], nres[NCH];
+  Raw8<T> ndy[NCH], nx[NCH], nres[NCH];  // the next row, as fetched
   auto fetch = [&](size_t row) {
 #pragma unroll
     for (int c = 0; c < NCH; c++) {
@@ -96,9 +96,10 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_bwd_kernel(const T* __res
   for (int rr = 0; rr < nrows; rr++) {
     const size_t row = row0 + rr;
     const float r = rstd[row];
-    Vec8<T> gh[NCH], xh[NCH], rs[NCH];
+    Vec8<T> gh[NCH], xh[NCH];
+    Raw8<T> rs[NCH];
 #pragma unroll
-    for (int c = 0; c < NCH; c++) { gh[c] = ndy[c]; xh[c] = nx[c]; rs[c] = nres[c]; }
+    for (int c = 0; c < NCH; c++) { gh[c].from(ndy[c]); xh[c].from(nx[c]); rs[c] = nres[c]; }
     if (rr + 1 < nrows) fetch(row + 1);
     float dot = 0.f;
 #pragma unroll
@@ -124,7 +125,7 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_bwd_kernel(const T* __res
         for (int i = 0; i < 8; i++) o.v[i] = r * (gh[c].v[i] - xh[c].v[i] * dot);
         if (dres != nullptr) {
 #pragma unroll
-          for (int i = 0; i < 8; i++) o.v[i] += rs[c].v[i];
+          for (int i = 0; i < 8; i++) o.v[i] += rs[c].get(i);
         }
         o.store(dx + row * H + col);
       }
