@@ -338,6 +338,7 @@ def main():
         "config": {"workload": args.workload, "arch": cfg["arch"], "tokens_per_strand": run.T, "comm_blocks": args.comm_blocks,
                    "cp": [cfg["cp_rank"], cfg["cp_ranks"]] if cfg["arch"] == "llama_cp" else None, "plan_pairs": len(pairs), "plan": best_name, "execution": execution, "standins_on": comm_placement},
         "pct_bf16_peak": 100.0 * value / BF16_MFMA_PEAK_TFLOPS,
+        "tflops_full_attention_convention": H.model_flops(cfg, full_attention=True) / t_si / 1e12,
         "tokens_per_s": run.T / t_si,
         "speedup_vs_sequential": t_seq / t_si,
         "ms_sequential": t_seq * 1e3, "ms_free_running": t_free * 1e3, "ms_eager": t_eager * 1e3, "ms_graph_replay": t_graph * 1e3,

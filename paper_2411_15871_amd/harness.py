@@ -23,7 +23,7 @@ CONFIGS = {
 ARCH = {"llama": dh.DH_ARCH_LLAMA, "gpt": dh.DH_ARCH_GPT, "moe": dh.DH_ARCH_MOE, "llama_cp": dh.DH_ARCH_LLAMA_CP}
 
 
-def model_flops(cfg):
+def model_flops(cfg, full_attention=False):
     """Model FLOPs of one forward+backward of the layer share: 2*M*N*K per GEMM, causal attention at
     half of the dense 4*s^2*d per head, backward = 2 x forward (no recompute credit)."""
     T, H, nq, nkv, d, F = cfg["batch"] * cfg["seq"], cfg["hidden"], cfg["nq"], cfg["nkv"], cfg["d"], cfg["ffn"]
@@ -36,6 +36,8 @@ def model_flops(cfg):
     else:
         ffn = 2.0 * T * H * 3 * F
     attn = 0.5 * 4.0 * cfg["batch"] * cfg["seq"] ** 2 * d * nq
+    if full_attention:  # the convention that counts the masked half of the score matrix too (Sec. 6.1 follows Megatron-LM's count)
+        attn *= 2.0
     if arch == "llama_cp":  # the rank's queries also read cp_rank full chunks of earlier keys
         attn += 4.0 * cfg["batch"] * cfg["seq"] ** 2 * cfg["cp_rank"] * d * nq
     return 3.0 * (attn_gemm + ffn + attn)
