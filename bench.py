@@ -229,14 +229,18 @@ def main():
     seq_plan = dh.dh_plan_sequential(run.layer)
     free_plan = dh.make_plan(list(seq_plan.fwd_order[:nf]), list(seq_plan.bwd_order[:nb]), [(0, nf, 0, nb)])
     # Last offline step: the cost model ranks plans, measurement picks among its best few.  Candidates: the searched
-    # plan at three barrier prices (dearer barriers -> fewer, longer segment pairs), each also with its operator orders
+    # plan at several barrier prices (dearer barriers -> fewer, longer segment pairs), each also with its operator orders
     # kept but all barriers dropped, and the default orders without barriers.
-    cands = [("default order, one pair", free_plan)]
-    for bc in (5e-6, 3e-5, 2e-4):
-        p_bc, _ = dh.dh_plan_search(gf, gb, table, bc, 256)
+    cands, seen = [("default order, one pair", free_plan)], {dh.plan_to_py(free_plan).__repr__()}
+    for bc in (0.0, 3e-7, 1e-6, 2.5e-6, 5e-6, 1.5e-5, 3e-5, 6e-5, 2e-4):
+        p_bc, _ = dh.dh_plan_search(gf, gb, table, bc, 512)
         fo_c, bo_c, pairs_c = dh.plan_to_py(p_bc)
-        cands.append(("searched, barrier %.0e, %d pairs" % (bc, len(pairs_c)), p_bc))
-        cands.append(("searched orders (barrier %.0e), one pair" % bc, dh.make_plan(fo_c, bo_c, [(0, nf, 0, nb)])))
+        for name, q in (("searched, barrier %.1e, %d pairs" % (bc, len(pairs_c)), p_bc),
+                        ("searched orders (barrier %.1e), one pair" % bc, dh.make_plan(fo_c, bo_c, [(0, nf, 0, nb)]))):
+            key = dh.plan_to_py(q).__repr__()
+            if key not in seen:  # different barrier prices often give the same plan
+                seen.add(key)
+                cands.append((name, q))
     # Where the collective stand-ins go is part of the schedule too: on one shared communication stream (their order
     # there is the host's issue order, so a strand's collective can wait behind the other strand's) or each in its own
     # strand's stream.
