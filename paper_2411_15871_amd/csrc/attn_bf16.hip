@@ -15,12 +15,15 @@
 // matching A operand (V^T, K^T, dO^T, Q^T: "k" is the token index, the slow dimension in memory)
 // comes from LDS through the transposing load ds_read_b64_tr_b16.
 //
-// 64-token tiles stream global -> LDS directly (see dma.h) through a ring of three slots: the
-// transfer of tile t+2 is issued right after the barrier that publishes tile t.  A tile is stored
+// 64-token tiles stream global -> LDS directly (see dma.h) through a ring of three slots (two in the
+// forward kernel, so that two of its blocks fit a compute unit): the transfer of tile t+2 (t+1) is issued
+// right after the barrier that publishes tile t.  A tile is stored
 // [token][D] unpadded; the 16-byte chunk c of row r sits at chunk position c ^ swz(r), which makes
 // the 16-byte fragment reads (16 consecutive rows, one chunk) and the transposing reads (4
 // consecutive rows x 64 bytes) both bank-conflict free for 256-byte rows (D = 128).
-// Blocks are launched heaviest first (the causal work per block grows with its position).
+// Blocks are launched heaviest first over all heads (the causal work per block grows with its position).
+// Long rows of tiles may be cut into chunks whose float32 partial results a small kernel merges in chunk
+// order; the chunk length is chosen per launch from a simulation of the launch (pick_chunk below).
 // No atomics: dQ is produced per query block, dK/dV per (key block, query head), then the heads of
 // a group are added in index order.
 #include <map>
