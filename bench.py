@@ -50,21 +50,52 @@ def cpu_baseline(cfg, flops):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count()
+    arch, bf = cfg["arch"], cfg["bf16"]
     T, H = cfg["batch"] * cfg["seq"], cfg["hidden"]
+    rows = T // cfg["n_ranks"] if arch == "gpt" else T
     n_qkv = (cfg["nq"] + 2 * cfg["nkv"]) * cfg["d"]
     ocfg = R.LayerCfg(batch=cfg["batch"], seq=cfg["seq"], H=H, nq=cfg["nq"], nkv=cfg["nkv"], d=cfg["d"], F=cfg["ffn"])
-    W = {k: v.astype(np.float64) for k, v in gen.llama_weights(H, n_qkv, cfg["nq"] * cfg["d"], cfg["ffn"], cfg["bf16"]).items()}
-    x = gen.strand_input(0, T, H, cfg["bf16"]).astype(np.float64)
-    dout = gen.strand_upstream_grad(0, T, H, cfg["bf16"]).astype(np.float64)
+    x = gen.strand_input(0, rows, H, bf).astype(np.float64)
+    dout = gen.strand_upstream_grad(0, rows, H, bf).astype(np.float64)
+    f64 = lambda w: {k: v.astype(np.float64) for k, v in w.items()}
+    if arch == "gpt":
+        names = dict(Wgu="W1", Wd="W2", bfc1="bf1", bfc2="bf2")
+        W = {names.get(k, k): v for k, v in f64(gen.gpt_weights(H, n_qkv, cfg["nq"] * cfg["d"], cfg["ffn"], bf)).items()}
+        peers = lambda n: {k: np.zeros((cfg["n_ranks"] - 1, rows, H)) for k in n}
+
+        def once():
+            _, saved = R.gpt_fwd(ocfg, W, x, peers(("ag1", "ag2", "rs1", "rs2")))
+            R.gpt_bwd(ocfg, W, saved, dout, peers(("ag3", "ag4", "rs3", "rs4")))
+    elif arch == "moe":
+        W = f64(gen.moe_weights(H, n_qkv, cfg["nq"] * cfg["d"], cfg["ffn"], cfg["n_local"], bf))
+        logits = gen.router_logits(T, cfg["n_experts"]).astype(np.float64)
+
+        def once():
+            _, saved = R.moe_layer_fwd(ocfg, W, x, logits, cfg["n_local"])
+            R.moe_layer_bwd(ocfg, W, saved, dout, cfg["n_local"])
+    elif arch == "llama_cp":
+        W = f64(gen.llama_weights(H, n_qkv, cfg["nq"] * cfg["d"], cfg["ffn"], bf))
+        Wkv = 2 * cfg["nkv"] * cfg["d"]
+        kv = gen.peer_partials(170, cfg["cp_ranks"] - 1, T, Wkv, bf, 1.0)
+        dkv = gen.peer_partials(270, cfg["cp_ranks"] - 1, T, Wkv, bf, 1e-2)
+
+        def once():
+            _, saved = R.llama_cp_fwd(ocfg, W, x, cfg["cp_rank"], {"kv": kv})
+            R.llama_cp_bwd(ocfg, W, saved, dout, cfg["cp_rank"], {"dkv": dkv})
+    else:
+        W = f64(gen.llama_weights(H, n_qkv, cfg["nq"] * cfg["d"], cfg["ffn"], bf))
+
+        def once():
+            _, saved = R.llama_fwd(ocfg, W, x)
+            R.llama_bwd(ocfg, W, saved, dout)
     t0 = time.perf_counter()
     reps = 0
     while reps < 1 or (time.perf_counter() - t0 < 10.0 and reps < 20):
-        _, saved = R.llama_fwd(ocfg, W, x)
-        R.llama_bwd(ocfg, W, saved, dout)
+        once()
         reps += 1
     dt = (time.perf_counter() - t0) / reps
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
-            "sample": "%d x one full layer forward+backward of one strand at the benchmark shapes (no peer partials), "
+            "sample": "%d x one full layer forward+backward of one strand at the benchmark shapes (peer partials absent or zero), "
                       "%.1f s each" % (reps, dt)}
 
 
@@ -355,7 +386,7 @@ def main():
                      "traffic_unit": "bytes/launch", "algorithmic_bytes": 2.0 * (T * Hd + Hd * F2 + T * F2),
                      "kernel": "gemm_bf16_kernel (first FFN projection %dx%dx%d)" % (T, F2, Hd)},
     }
-    if not args.no_cpu_baseline and cfg["arch"] == "llama":
+    if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, flops)
     run.close()
     print(json.dumps(out), flush=True)
