@@ -22,7 +22,7 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 # HBM bytes per launch of the dominant GEMM from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (scaled by a copy kernel of
 # known size: `bench.py --traffic-probe`); the summary with the commands is profiles/gemm_gateup_c2_hbm_traffic.txt.
 # Re-measure when the GEMM changes.
-HBM_TRAFFIC_BYTES = {"c2_llama8b_tp8": (176.3 + 28.5) * 2 ** 20}
+HBM_TRAFFIC_BYTES = {"c2_llama8b_tp8": (176.3 + 28.3) * 2 ** 20}
 
 
 def log(*a):
