@@ -272,6 +272,16 @@ def main():
             if key not in seen:  # different barrier prices often give the same plan
                 seen.add(key)
                 cands.append((name, q))
+    # Transfers that wait for nothing (the context-parallel key/value exchange) can start the step: the same candidates
+    # again with such operators moved to the front of the forward order.
+    free_comm = [op for op in range(nf) if gf.is_comm[op] and not any(gf.dep_dst[e] == op for e in range(gf.n_deps))]
+    if free_comm:
+        for name, q in list(cands):
+            fo_c, bo_c, pairs_c = dh.plan_to_py(q)
+            if len(pairs_c) != 1:
+                continue  # segment boundaries are positions in the order: only hoist in single-pair plans
+            hoisted = free_comm + [op for op in fo_c if op not in free_comm]
+            cands.append((name + ", exchange first", dh.make_plan(hoisted, bo_c, pairs_c)))
     # Where the collective stand-ins go is part of the schedule too: on one shared communication stream (their order
     # there is the host's issue order, so a strand's collective can wait behind the other strand's) or each in its own
     # strand's stream.

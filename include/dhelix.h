@@ -215,15 +215,17 @@ typedef enum {
   DH_MB_NORM1, DH_MB_NOPS
 } dh_moe_bwd_op;
 
-/* DH_ARCH_LLAMA_CP: the Llama operators plus the key/value exchange and the gradient send-back. */
+/* DH_ARCH_LLAMA_CP: the Llama operators plus the key/value exchange (F_CP_KV: no predecessor, only attention waits for
+ * it; the rank's own keys/values are put in place by F_ROPE), the reduction of the rank's own key/value gradient with
+ * what later ranks send (B_CP_DKV) and the send-back of the earlier chunks' gradients (B_CP_SEND: no successor). */
 typedef enum {
   DH_CF_NORM1 = 0, DH_CF_QKV, DH_CF_ROPE, DH_CF_CP_KV, DH_CF_ATTN, DH_CF_PROJ, DH_CF_AR1, DH_CF_NORM2, DH_CF_FC1,
   DH_CF_ACT, DH_CF_FC2, DH_CF_AR2, DH_CF_BDA2, DH_CF_NOPS
 } dh_cp_fwd_op;
 typedef enum {
   DH_CB_FC2_DGRAD = 0, DH_CB_FC2_WGRAD, DH_CB_ACT, DH_CB_FC1_DGRAD, DH_CB_FC1_WGRAD, DH_CB_AR3, DH_CB_NORM2,
-  DH_CB_PROJ_DGRAD, DH_CB_PROJ_WGRAD, DH_CB_ATTN, DH_CB_CP_DKV, DH_CB_ROPE, DH_CB_QKV_DGRAD, DH_CB_QKV_WGRAD,
-  DH_CB_AR4, DH_CB_NORM1, DH_CB_NOPS
+  DH_CB_PROJ_DGRAD, DH_CB_PROJ_WGRAD, DH_CB_ATTN, DH_CB_CP_DKV, DH_CB_CP_SEND, DH_CB_ROPE, DH_CB_QKV_DGRAD,
+  DH_CB_QKV_WGRAD, DH_CB_AR4, DH_CB_NORM1, DH_CB_NOPS
 } dh_cp_bwd_op;
 
 #define DH_MAX_OPS 32
@@ -323,6 +325,10 @@ int dh_plan_sequential(const dh_layer* layer, dh_plan* out);
 /* One SI step (Sec. 3.3, 5): forward of strand alpha and backward of strand beta, operators issued
  * per plan on stream_alpha / stream_beta, collective stand-ins on stream_comm (NULL = issue them on
  * the strand's own stream), barriers between segment pairs by events (no host synchronisation).
+ * A stand-in issued on another stream than its strand's starts after what the strand has issued so far; the strand
+ * waits for it only when an operator that depends on it (operator graph) comes up, or at the end of the segment
+ * pair, so operators of the same strand that do not need the result overlap the transfer (Sec. 4.2, the
+ * "self-overlapping" operators of the pairing figure).
  * On return all work is enqueued; all three streams are joined back into stream_alpha.
  * ws: at least dh_layer_workspace_bytes(layer, DH_WS_SI). */
 int dh_si_step(dh_layer* layer, const dh_fwd_args* alpha, const dh_bwd_args* beta,

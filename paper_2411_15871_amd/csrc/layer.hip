@@ -48,7 +48,7 @@ static const char* kGptBwd[DH_GB_NOPS] = {"B_AG3", "B_FC2_DGRAD", "B_FC2_WGRAD",
 static const char* kCpFwd[DH_CF_NOPS] = {"F_NORM1", "F_QKV", "F_ROPE", "F_CP_KV", "F_ATTN", "F_PROJ", "F_AR1",
                                          "F_NORM2", "F_FC1", "F_ACT", "F_FC2", "F_AR2", "F_BDA2"};
 static const char* kCpBwd[DH_CB_NOPS] = {"B_FC2_DGRAD", "B_FC2_WGRAD", "B_ACT", "B_FC1_DGRAD", "B_FC1_WGRAD", "B_AR3",
-                                         "B_NORM2", "B_PROJ_DGRAD", "B_PROJ_WGRAD", "B_ATTN", "B_CP_DKV", "B_ROPE",
+                                         "B_NORM2", "B_PROJ_DGRAD", "B_PROJ_WGRAD", "B_ATTN", "B_CP_DKV", "B_CP_SEND", "B_ROPE",
                                          "B_QKV_DGRAD", "B_QKV_WGRAD", "B_AR4", "B_NORM1"};
 static const char* kMoeFwd[DH_MF_NOPS] = {"F_NORM1", "F_QKV", "F_ROPE", "F_ATTN", "F_PROJ", "F_NORM2", "F_ROUTE",
                                           "F_PERMUTE", "F_A2A_DISPATCH", "F_FC1", "F_ACT", "F_FC2", "F_A2A_COMBINE",
@@ -108,13 +108,19 @@ static void build_graphs(dh_layer* L) {
     b.is_comm[DH_B_AR3] = b.is_comm[DH_B_AR4] = 1;
     b.side_ok[DH_B_FC2_WGRAD] = b.side_ok[DH_B_FC1_WGRAD] = b.side_ok[DH_B_PROJ_WGRAD] = b.side_ok[DH_B_QKV_WGRAD] = 1;
   } else if (L->c.arch == DH_ARCH_LLAMA_CP) {
+    // The other ranks' key/value chunks depend on nothing this rank computes: the exchange has no predecessor and only
+    // attention waits for it.  The gradient send-back has no successor.
     f.n_ops = DH_CF_NOPS;
-    for (int i = 0; i + 1 < DH_CF_NOPS; i++) add_dep(f, i, i + 1);
+    CHAIN(f, DH_CF_NORM1, DH_CF_QKV, DH_CF_ROPE, DH_CF_ATTN, DH_CF_PROJ, DH_CF_AR1, DH_CF_NORM2, DH_CF_FC1, DH_CF_ACT, DH_CF_FC2,
+          DH_CF_AR2, DH_CF_BDA2);
+    add_dep(f, DH_CF_CP_KV, DH_CF_ATTN);
     f.is_comm[DH_CF_AR1] = f.is_comm[DH_CF_AR2] = 1;
     f.is_comm[DH_CF_CP_KV] = 2;
     b.n_ops = DH_CB_NOPS;
     CHAIN(b, DH_CB_FC2_DGRAD, DH_CB_ACT, DH_CB_FC1_DGRAD, DH_CB_AR3, DH_CB_NORM2, DH_CB_PROJ_DGRAD, DH_CB_ATTN, DH_CB_CP_DKV,
           DH_CB_ROPE, DH_CB_QKV_DGRAD, DH_CB_AR4, DH_CB_NORM1);
+    add_dep(b, DH_CB_ATTN, DH_CB_CP_SEND);
+    b.is_comm[DH_CB_CP_SEND] = 2;
     add_dep(b, DH_CB_ACT, DH_CB_FC1_WGRAD);
     add_dep(b, DH_CB_NORM2, DH_CB_PROJ_WGRAD);
     add_dep(b, DH_CB_ROPE, DH_CB_QKV_WGRAD);
@@ -479,24 +485,27 @@ static int cp_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hipStr
   char* sv = (char*)a.saved;
   const int r = c.cp_rank, S = L->q_off + c.seq, W = L->kv_w, blocks = c.cross_blocks > 0 ? c.cross_blocks : 8;
   switch (op) {
-    case DH_CF_ROPE:
-      return dh_rope_at(c.dtype, L->T, c.seq, L->q_off, c.n_q_heads + c.n_kv_heads, c.head_dim, L->n_qkv, c.rope_base, 0, sv + L->s_qkv, s);
-    case DH_CF_CP_KV: {  // chunk k of the exchange comes from rank k: earlier ranks and this one land in the attention buffer
+    case DH_CF_ROPE: {  // rotate q and k, then put the rank's own keys/values in their place of the attention buffer
+      int rc = dh_rope_at(c.dtype, L->T, c.seq, L->q_off, c.n_q_heads + c.n_kv_heads, c.head_dim, L->n_qkv, c.rope_base, 0, sv + L->s_qkv, s);
+      if (rc) return rc;
+      dh_cp_move m;
+      m.src = sv + L->s_qkv + (size_t)c.n_q_heads * c.head_dim * L->es;
+      m.src_ld = L->n_qkv; m.src_seq_rows = c.seq; m.src_row0 = 0;
+      m.dst = sv + L->s_kv; m.dst_ld = W; m.dst_seq_rows = S; m.dst_row0 = r * c.seq;
+      return dh_cp_exchange(c.dtype, 1, &m, c.batch, c.seq, W, 0, s);  // a local copy, not a transfer: at full speed
+    }
+    case DH_CF_CP_KV: {  // the exchange: the chunks of earlier ranks land in the attention buffer, later ranks' pass through
       dh_cp_move mv[16];
+      int n = 0;
       for (int k = 0; k < c.cp_ranks; k++) {
-        dh_cp_move& m = mv[k];
-        if (k == r) {
-          m.src = sv + L->s_qkv + (size_t)c.n_q_heads * c.head_dim * L->es;
-          m.src_ld = L->n_qkv;
-        } else {
-          m.src = (const char*)a.peers_kv + (size_t)(k < r ? k : k - 1) * L->T * W * L->es;
-          m.src_ld = W;
-        }
-        m.src_seq_rows = c.seq; m.src_row0 = 0;
-        if (k <= r) { m.dst = sv + L->s_kv; m.dst_ld = W; m.dst_seq_rows = S; m.dst_row0 = k * c.seq; }
+        if (k == r) continue;
+        dh_cp_move& m = mv[n++];
+        m.src = (const char*)a.peers_kv + (size_t)(k < r ? k : k - 1) * L->T * W * L->es;
+        m.src_ld = W; m.src_seq_rows = c.seq; m.src_row0 = 0;
+        if (k < r) { m.dst = sv + L->s_kv; m.dst_ld = W; m.dst_seq_rows = S; m.dst_row0 = k * c.seq; }
         else { m.dst = ws + L->f_kvrecv + (size_t)(k - r - 1) * L->T * W * L->es; m.dst_ld = W; m.dst_seq_rows = c.seq; m.dst_row0 = 0; }
       }
-      return dh_cp_exchange(c.dtype, c.cp_ranks, mv, c.batch, c.seq, W, blocks, s);
+      return dh_cp_exchange(c.dtype, n, mv, c.batch, c.seq, W, blocks, s);
     }
     case DH_CF_ATTN:
       return dh_attn_ctx_fwd(c.dtype, c.batch, c.seq, L->q_off, c.n_q_heads, c.n_kv_heads, c.head_dim, sv + L->s_qkv, sv + L->s_kv,
@@ -508,7 +517,7 @@ static int cp_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hipStr
 
 static int cp_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipStream_t s, char* side_ws = nullptr) {
   static const int same[DH_CB_NOPS] = {DH_B_FC2_DGRAD, DH_B_FC2_WGRAD, DH_B_ACT, DH_B_FC1_DGRAD, DH_B_FC1_WGRAD, DH_B_AR3,
-                                       DH_B_NORM2, DH_B_PROJ_DGRAD, DH_B_PROJ_WGRAD, -1, -1, -1, DH_B_QKV_DGRAD,
+                                       DH_B_NORM2, DH_B_PROJ_DGRAD, DH_B_PROJ_WGRAD, -1, -1, -1, -1, DH_B_QKV_DGRAD,
                                        DH_B_QKV_WGRAD, DH_B_AR4, DH_B_NORM1};
   const dh_layer_config& c = L->c;
   const char* sv = (const char*)b.saved;
@@ -518,15 +527,16 @@ static int cp_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipStr
       return dh_attn_ctx_bwd(c.dtype, c.batch, c.seq, L->q_off, c.n_q_heads, c.n_kv_heads, c.head_dim, sv + L->s_qkv, sv + L->s_kv,
                              sv + L->s_o, ws + L->b_do, (const float*)(sv + L->s_lse), ws + L->b_dqkv, ws + L->b_dkv,
                              (float*)(ws + L->b_delta), ws + L->b_attn, L->b_attn_bytes, s);
-    case DH_CB_CP_DKV: {  // send the earlier chunks' gradients back; own chunk: own contribution + the later ranks'
+    case DH_CB_CP_SEND: {  // the earlier chunks' key/value gradients go back to their owners: nothing here waits for it
       dh_cp_move mv[16];
       for (int k = 0; k < r; k++) {
         dh_cp_move& m = mv[k];
         m.src = ws + L->b_dkv; m.src_ld = W; m.src_seq_rows = S; m.src_row0 = k * c.seq;
         m.dst = (char*)b.dkv_peers + (size_t)k * L->T * W * L->es; m.dst_ld = W; m.dst_seq_rows = c.seq; m.dst_row0 = 0;
       }
-      int rc = dh_cp_exchange(c.dtype, r, mv, c.batch, c.seq, W, blocks, s);
-      if (rc) return rc;
+      return dh_cp_exchange(c.dtype, r, mv, c.batch, c.seq, W, blocks, s);
+    }
+    case DH_CB_CP_DKV: {  // own chunk: own contribution + what the later ranks send for it
       dh_cp_move own;
       own.src = ws + L->b_dkv; own.src_ld = W; own.src_seq_rows = S; own.src_row0 = L->q_off;
       own.dst = ws + L->b_dqkv + (size_t)c.n_q_heads * c.head_dim * L->es; own.dst_ld = L->n_qkv; own.dst_seq_rows = c.seq; own.dst_row0 = 0;
@@ -852,10 +862,13 @@ static hipEvent_t next_event(dh_layer* L) {
   return e;
 }
 
-// Runs `launch` on the communication stream between the work already queued on `strand` and the
-// work queued on it afterwards.
+// Runs `launch` on the communication stream after the work already queued on `strand`.  *done receives the event that
+// marks its completion (nullptr if it ran in the strand's own stream): the strand does not wait for it here but when
+// an operator that needs the result comes up, so that operators of the same strand that do not need it (weight
+// gradients, mostly) overlap the transfer -- the "self-overlapping" operators of the paper's pairing figure.
 template <typename Fn>
-static int on_comm_stream(dh_layer* L, hipStream_t strand, hipStream_t comm, Fn launch) {
+static int on_comm_stream(dh_layer* L, hipStream_t strand, hipStream_t comm, hipEvent_t* done, Fn launch) {
+  *done = nullptr;
   if (comm == nullptr || comm == strand) return launch(strand);
   hipEvent_t before = next_event(L), after = next_event(L);
   DH_HIP(hipEventRecord(before, strand));
@@ -863,7 +876,32 @@ static int on_comm_stream(dh_layer* L, hipStream_t strand, hipStream_t comm, Fn 
   int rc = launch(comm);
   if (rc) return rc;
   DH_HIP(hipEventRecord(after, comm));
-  DH_HIP(hipStreamWaitEvent(strand, after, 0));
+  *done = after;
+  return DH_OK;
+}
+
+// Completion events of the communication operators a strand has issued on another stream and not waited for yet.
+struct PendingComm {
+  hipEvent_t ev[DH_MAX_OPS];
+};
+// Before operator `op` is issued: its strand waits for the pending transfers among op's direct predecessors (everything
+// issued to the strand's stream afterwards is then ordered behind them too).
+static int wait_for_inputs(const dh_op_graph& g, PendingComm& pd, int op, hipStream_t strand) {
+  for (int e = 0; e < g.n_deps; e++) {
+    const int src = g.dep_src[e];
+    if (g.dep_dst[e] == op && pd.ev[src]) {
+      DH_HIP(hipStreamWaitEvent(strand, pd.ev[src], 0));
+      pd.ev[src] = nullptr;
+    }
+  }
+  return DH_OK;
+}
+static int wait_for_all(const dh_op_graph& g, PendingComm& pd, hipStream_t strand) {
+  for (int op = 0; op < g.n_ops; op++)
+    if (pd.ev[op]) {
+      DH_HIP(hipStreamWaitEvent(strand, pd.ev[op], 0));
+      pd.ev[op] = nullptr;
+    }
   return DH_OK;
 }
 
@@ -891,6 +929,9 @@ static int enqueue_si(dh_layer* L, dh_layer* LB, const dh_fwd_args* alpha, const
   char* ws_f = (char*)ws;
   char* ws_b = (char*)ws + L->fwd_bytes;
   const bool two = sb != sa;
+  PendingComm pf, pb;
+  memset(&pf, 0, sizeof(pf));
+  memset(&pb, 0, sizeof(pb));
   if (two) {  // beta starts after whatever alpha's stream already holds
     hipEvent_t e = next_event(L);
     DH_HIP(hipEventRecord(e, sa));
@@ -903,12 +944,14 @@ static int enqueue_si(dh_layer* L, dh_layer* LB, const dh_fwd_args* alpha, const
     while (fi < p.f_end || bj < p.b_end) {
       if (fi < p.f_end) {
         const int op = plan->fwd_order[fi++];
-        if (L->gf.is_comm[op]) rc = on_comm_stream(L, sa, comm_stream_of(L, L->gf.is_comm[op], sc), [&](hipStream_t s) { return run_fwd_op(L, op, *alpha, ws_f, s); });
+        if ((rc = wait_for_inputs(L->gf, pf, op, sa))) return rc;
+        if (L->gf.is_comm[op]) rc = on_comm_stream(L, sa, comm_stream_of(L, L->gf.is_comm[op], sc), &pf.ev[op], [&](hipStream_t s) { return run_fwd_op(L, op, *alpha, ws_f, s); });
         else rc = run_fwd_op(L, op, *alpha, ws_f, sa);
         if (rc) return rc;
       }
       if (bj < p.b_end) {
         const int op = plan->bwd_order[bj++];
+        if ((rc = wait_for_inputs(L->gb, pb, op, sb))) return rc;
         if (two && plan->bwd_side[op]) {  // beside the strand: after what the strand has issued so far, on the other stream
           hipEvent_t e = next_event(L);
           DH_HIP(hipEventRecord(e, sb));
@@ -916,11 +959,13 @@ static int enqueue_si(dh_layer* L, dh_layer* LB, const dh_fwd_args* alpha, const
           if ((rc = run_bwd_op(LB, op, *beta, ws_b, sa, ws_f + L->f_gemm))) return rc;
           continue;
         }
-        if (L->gb.is_comm[op]) rc = on_comm_stream(L, sb, comm_stream_of(L, L->gb.is_comm[op], sc), [&](hipStream_t s) { return run_bwd_op(LB, op, *beta, ws_b, s); });
+        if (L->gb.is_comm[op]) rc = on_comm_stream(L, sb, comm_stream_of(L, L->gb.is_comm[op], sc), &pb.ev[op], [&](hipStream_t s) { return run_bwd_op(LB, op, *beta, ws_b, s); });
         else rc = run_bwd_op(LB, op, *beta, ws_b, sb);
         if (rc) return rc;
       }
     }
+    // a segment pair ends with all of its transfers done
+    if ((rc = wait_for_all(L->gf, pf, sa)) || (rc = wait_for_all(L->gb, pb, sb))) return rc;
     if (two) {  // cross-strand barrier on the device; after the last pair beta only joins alpha
       hipEvent_t ea = next_event(L), eb = next_event(L);
       const bool last = k + 1 == plan->n_pairs;
@@ -945,7 +990,8 @@ extern "C" int dh_si_step(dh_layer* L, const dh_fwd_args* alpha, const dh_bwd_ar
 static bool same_shape(const dh_layer_config& a, const dh_layer_config& b) {
   return a.arch == b.arch && a.dtype == b.dtype && a.batch == b.batch && a.seq == b.seq && a.hidden == b.hidden &&
          a.n_q_heads == b.n_q_heads && a.n_kv_heads == b.n_kv_heads && a.head_dim == b.head_dim && a.ffn == b.ffn &&
-         a.n_ranks == b.n_ranks && a.n_experts == b.n_experts && a.n_local_experts == b.n_local_experts;
+         a.n_ranks == b.n_ranks && a.n_experts == b.n_experts && a.n_local_experts == b.n_local_experts &&
+         a.cp_ranks == b.cp_ranks && a.cp_rank == b.cp_rank;
 }
 
 extern "C" int dh_si_step_layers(dh_layer* layer_alpha, dh_layer* layer_beta, const dh_fwd_args* alpha, const dh_bwd_args* beta,

@@ -30,8 +30,8 @@ def test_op_names_and_error_strings():
     assert dh.FWD_OPS[:4] == ["F_NORM1", "F_QKV", "F_ROPE", "F_ATTN"] and len(dh.FWD_OPS) == 12 and len(dh.BWD_OPS) == 15
     assert len(dh.op_names(dh.DH_ARCH_GPT, 0)) == 13 and len(dh.op_names(dh.DH_ARCH_GPT, 1)) == 16
     assert len(dh.op_names(dh.DH_ARCH_MOE, 0)) == 14 and len(dh.op_names(dh.DH_ARCH_MOE, 1)) == 18
-    assert len(dh.op_names(dh.DH_ARCH_LLAMA_CP, 0)) == 13 and len(dh.op_names(dh.DH_ARCH_LLAMA_CP, 1)) == 16
-    assert dh.op_names(dh.DH_ARCH_LLAMA_CP, 0)[3] == "F_CP_KV" and dh.op_names(dh.DH_ARCH_LLAMA_CP, 1)[10] == "B_CP_DKV"
+    assert len(dh.op_names(dh.DH_ARCH_LLAMA_CP, 0)) == 13 and len(dh.op_names(dh.DH_ARCH_LLAMA_CP, 1)) == 17
+    assert dh.op_names(dh.DH_ARCH_LLAMA_CP, 0)[3] == "F_CP_KV" and dh.op_names(dh.DH_ARCH_LLAMA_CP, 1)[10:12] == ["B_CP_DKV", "B_CP_SEND"]
     assert dh.dh_op_name(0, 0, 99) is None and dh.dh_op_name(0, 2, 0) is None and dh.dh_op_name(7, 0, 0) is None
     with pytest.raises(dh.DhelixError) as e:
         dh.dh_layer_create(arch=0, dtype=1, batch=1, seq=8, hidden=100, n_q_heads=2, n_kv_heads=1, head_dim=64, ffn=64,
@@ -66,9 +66,11 @@ def test_context_parallel_layer_configuration_is_checked():
         layer = dh.dh_layer_create(**{**base, "cp_rank": r})
         sizes.append((dh.dh_layer_saved_bytes(layer), dh.dh_layer_workspace_bytes(layer, dh.DH_WS_BWD)))
         gf, gb = dh.dh_layer_op_graph(layer, 0), dh.dh_layer_op_graph(layer, 1)
-        assert gf.n_ops == 13 and gb.n_ops == 16
-        assert [gf.is_comm[i] for i in range(13)].count(2) == 1 and [gb.is_comm[i] for i in range(16)].count(2) == 1
-        assert sum(gb.side_ok[i] for i in range(16)) == 4
+        assert gf.n_ops == 13 and gb.n_ops == 17
+        assert [gf.is_comm[i] for i in range(13)].count(2) == 1 and [gb.is_comm[i] for i in range(17)].count(2) == 2
+        assert sum(gb.side_ok[i] for i in range(17)) == 4
+        deps_f = [(gf.dep_src[e], gf.dep_dst[e]) for e in range(gf.n_deps)]
+        assert not any(d == dh.op_names(dh.DH_ARCH_LLAMA_CP, 0).index("F_CP_KV") for _, d in deps_f)  # the exchange waits for nothing
         dh.dh_layer_destroy(layer)
     assert all(a[0] < b[0] and a[1] < b[1] for a, b in zip(sizes, sizes[1:]))  # one more chunk of keys and key gradients per rank
     plain = dh.dh_layer_create(**{**base, "arch": dh.DH_ARCH_LLAMA, "cp_ranks": 0})
