@@ -39,6 +39,7 @@ CASES = {
     "c3_gpt_tp8_sp": (H.CONFIGS["c3_gpt_tp8_sp"], 2e-2),
     "c5_phimoe_ep8": (H.CONFIGS["c5_phimoe_ep8"], 2e-2),
     "c6_llama8b_tp8_cp4": (H.CONFIGS["c6_llama8b_tp8_cp4"], 2e-2),
+    "c4_llama70b_tp8": (H.CONFIGS["c4_llama70b_tp8"], 2e-2),
 }
 GPT_NAMES = dict(Wgu="W1", Wd="W2", bfc1="bf1", bfc2="bf2")  # harness / C-struct name -> oracle name
 
