@@ -99,6 +99,23 @@ def cpu_baseline(cfg, flops):
                       "%.1f s each" % (reps, dt)}
 
 
+def write_pair_table(path, args, table, fnames, bnames, t_f, t_b):
+    """The profiler's output as text: solo times, then for every forward/backward operator pair the rate each keeps
+    while the other runs (percent of its solo rate) and the overlap effectiveness factor of Eq. 1,
+    (t_i + t_j - P_ij) / min(t_i, t_j): 1 = the shorter operator is hidden completely, 0 = nothing gained."""
+    nf, nb = len(t_f), len(t_b)
+    with open(path, "w") as f:
+        f.write("operator-pair table, workload %s, %d repetitions per measurement\n" % (args.workload, args.profile_reps))
+        f.write("solo us, forward : " + "  ".join("%s %.1f" % (fnames[i], t_f[i] * 1e6) for i in range(nf)) + "\n")
+        f.write("solo us, backward: " + "  ".join("%s %.1f" % (bnames[j], t_b[j] * 1e6) for j in range(nb)) + "\n\n")
+        f.write("cell: rate kept while co-running forward%/backward%, then OEF (Eq. 1); rows: forward operator of strand alpha, "
+                "columns: backward operator of strand beta\n")
+        f.write("%-8s" % "" + "".join("%-14s" % n[2:] for n in bnames[:nb]) + "\n")
+        for i in range(nf):
+            cells = ["%3.0f/%-3.0f %4.2f" % (100 * table.rate_fwd[i][j], 100 * table.rate_bwd[i][j], table.oef[i][j]) for j in range(nb)]
+            f.write("%-8s" % fnames[i][2:] + "".join("%-14s" % c for c in cells) + "\n")
+
+
 def stack_bench(args, torch, dh, H):
     """L stacked layers (Llama shapes only): a steady-state phase = forward sweep of one micro-batch co-run with the
     backward sweep of the previous one; reports its rate and the activation arena against two unshared sets."""
@@ -189,6 +206,11 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", type=int, default=0, help="stack this many layers: alpha sweeps forward while beta sweeps backward")
     ap.add_argument("--traffic-probe", action="store_true", help="only launch a calibration copy and the dominant GEMM (for rocprofv3 --pmc)")
+    ap.add_argument("--sequential-probe", action="store_true",
+                    help="only run alpha's forward then beta's backward, one kernel at a time, --steps times (for rocprofv3: every kernel's solo "
+                         "duration and counters at the workload's shapes)")
+    ap.add_argument("--pair-table", default=None, metavar="PATH",
+                    help="also write the measured operator-pair table (solo times, co-run rates, Eq. 1 overlap factors) to this text file")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the SI step is a per-GPU schedule); use --gpus 1")
@@ -233,6 +255,19 @@ def main():
     run.fwd(alpha)
     run.bwd(beta)
     torch.cuda.synchronize()
+    if args.sequential_probe:
+        # a plain copy of known size first (the stand-in kernel with one partial: 256 MiB read, 256 MiB written): the
+        # scale of the HBM byte counters in the same run
+        src = torch.empty(128 << 20, dtype=torch.bfloat16, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dh.dh_comm_standin(dh.DH_COMM_ALLREDUCE, [src], dst, src.numel(), dh.DH_BF16)
+        for _ in range(args.steps):
+            run.fwd(alpha)
+            run.bwd(beta)
+        torch.cuda.synchronize()
+        print("sequential probe: %d x (forward of one strand, backward of the other), workload %s" % (args.steps, args.workload))
+        run.close()
+        return
     sa, sb, sc = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
     sx = None
     if cfg["arch"] == "llama_cp":  # Sec. 5: cross-node transfers get a stream of their own
@@ -255,6 +290,8 @@ def main():
     log("fwd solo us:", {fnames[i]: round(t_f[i] * 1e6, 1) for i in range(gf.n_ops)})
     log("bwd solo us:", {bnames[j]: round(t_b[j] * 1e6, 1) for j in range(gb.n_ops)})
     log("plan:", [([fnames[o] for o in fo[a:b]], [bnames[o] for o in bo[c:d]]) for a, b, c, d in pairs])
+    if args.pair_table:
+        write_pair_table(args.pair_table, args, table, fnames, bnames, t_f, t_b)
 
     nf, nb = gf.n_ops, gb.n_ops
     seq_plan = dh.dh_plan_sequential(run.layer)
