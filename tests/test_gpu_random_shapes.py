@@ -139,3 +139,94 @@ def test_norms_random(dh, T, H):
     dx_ref, dg_ref = R.rmsnorm_bwd(dy.astype(np.float64), host(x2), g.astype(np.float64), host(rstd)[:, None])
     assert rel(host(dx), dx_ref) <= 6e-3
     assert rel(host(dg), dg_ref) <= 1e-4
+
+
+def grouped_cases():
+    rng = np.random.default_rng(777)
+    out = []
+    for i in range(10):
+        G = int(rng.integers(1, 6))
+        hi = (400, 1500, 2600)[i % 3]
+        rows = [int(rng.integers(0, hi)) if rng.random() > 0.15 else 0 for _ in range(G)]
+        K = int(rng.integers(1, 130)) * 8; N = int(rng.integers(1, (130, 520)[i % 2])) * 8
+        out.append((tuple(rows), K, N))
+    return out
+
+
+@pytest.mark.parametrize("rows,K,N", grouped_cases())
+def test_gemm_grouped_random(dh, rows, K, N):
+    """Row counts are device data: groups of any size, empty ones included, in all three grouped forms."""
+    G, Tt = len(rows), sum(rows)
+    A = gen.normal(31, (max(Tt, 1), K), 1.0, 0.0, True); W = gen.normal(32, (G, K, N), 0.05, 0.0, True)
+    dC = gen.normal(33, (max(Tt, 1), N), 1.0, 0.0, True)
+    Ad, Wd, dCd = dev(A), dev(W), dev(dC)
+    Cd = torch.full((max(Tt, 1) + 1, N), 5.0, dtype=torch.bfloat16, device="cuda")   # one guard row behind the groups
+    dAd = torch.full((max(Tt, 1) + 1, K), 5.0, dtype=torch.bfloat16, device="cuda")
+    dW = torch.full((G, K, N), 0.5, dtype=torch.float32, device="cuda")
+    rd = torch.tensor(rows, dtype=torch.int32, device="cuda")
+    dh.dh_gemm_grouped(dh.DH_BF16, 0, G, rd, Tt, K, N, Ad, Wd, Cd)
+    dh.dh_gemm_grouped(dh.DH_BF16, 1, G, rd, Tt, N, K, dCd, Wd, dAd)
+    dh.dh_gemm_grouped(dh.DH_BF16, 2, G, rd, Tt, K, N, Ad, dCd, dW)
+    torch.cuda.synchronize()
+    A64, W64, dC64 = A.astype(np.float64), W.astype(np.float64), dC.astype(np.float64)
+    r0 = 0
+    for g in range(G):
+        r1 = r0 + rows[g]
+        if r1 > r0:
+            assert rel(host(Cd)[r0:r1], A64[r0:r1] @ W64[g]) <= 4e-3
+            assert rel(host(dAd)[r0:r1], dC64[r0:r1] @ W64[g].T) <= 4e-3
+        ref = A64[r0:r1].T @ dC64[r0:r1]
+        assert np.linalg.norm(host(dW)[g] - 0.5 - ref) <= 2e-5 * max(np.linalg.norm(ref), 1e-30) + 1e-12
+        r0 = r1
+    assert torch.all(Cd[Tt:] == 5.0) and torch.all(dAd[Tt:] == 5.0)
+
+
+def ctx_cases():
+    rng = np.random.default_rng(4096)
+    out = []
+    for i in range(8):
+        d = (128, 64)[i % 2]
+        nkv = int(rng.integers(1, 3)); nq = nkv * int(rng.integers(1, 5))
+        batch = int(rng.integers(1, 3))
+        seq = int(rng.integers(1, (500, 1500)[i % 4 == 1]))
+        q_off = 128 * int(rng.integers(0, (8, 20)[i % 4 == 2]))   # the matrix-core kernels take offsets in whole key blocks
+        out.append((batch, seq, q_off, nq, nkv, d))
+    return out
+
+
+@pytest.mark.parametrize("batch,seq,q_off,nq,nkv,d", ctx_cases())
+def test_ctx_attention_bf16_random(dh, batch, seq, q_off, nq, nkv, d):
+    T, S = batch * seq, q_off + seq
+    nqkv = (nq + 2 * nkv) * d
+    qkv = gen.normal(50, (T, nqkv), 1.0, 0.0, True)
+    kv = gen.normal(52, (batch * S, 2 * nkv * d), 1.0, 0.0, True)
+    do = gen.normal(51, (T, nq * d), 1.0, 0.0, True)
+    qd, kvd, dod = dev(qkv), dev(kv), dev(do)
+    o = torch.empty(T, nq * d, dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty(nq, T, dtype=torch.float32, device="cuda")
+    fwsb = dh.dh_attn_ctx_fwd_workspace_bytes(dh.DH_BF16, batch, seq, q_off, nq, nkv, d)
+    fws = torch.empty(max(fwsb, 16), dtype=torch.uint8, device="cuda")
+    dh.dh_attn_ctx_fwd(dh.DH_BF16, batch, seq, q_off, nq, nkv, d, qd, kvd, o, lse, fws, fwsb)
+    q64 = qkv[:, : nq * d].astype(np.float64).reshape(T, nq, d)
+    k64 = kv[:, : nkv * d].astype(np.float64).reshape(batch * S, nkv, d)
+    v64 = kv[:, nkv * d:].astype(np.float64).reshape(batch * S, nkv, d)
+    o_ref, lse_ref = R.attention_ctx_fwd(q64, k64, v64, batch, seq, q_off)
+    assert rel(host(o), o_ref.reshape(T, nq * d)) <= 1e-2
+    assert np.max(np.abs(host(lse) - lse_ref)) <= 2e-2
+    qcols = torch.full((T, nqkv), 7.0, dtype=torch.bfloat16, device="cuda")
+    dkv = torch.zeros(batch * S, 2 * nkv * d, dtype=torch.bfloat16, device="cuda")
+    delta = torch.empty(nq, T, dtype=torch.float32, device="cuda")
+    wsb = dh.dh_attn_ctx_bwd_workspace_bytes(dh.DH_BF16, batch, seq, q_off, nq, nkv, d)
+    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+    dh.dh_attn_ctx_bwd(dh.DH_BF16, batch, seq, q_off, nq, nkv, d, qd, kvd, o, dod, lse, qcols, dkv, delta, ws, wsb)
+    torch.cuda.synchronize()
+    dq, dk, dv = R.attention_ctx_bwd(do.astype(np.float64).reshape(T, nq, d), q64, k64, v64, batch, seq, q_off)
+    got_q, got_kv = host(qcols), host(dkv)
+    floor = np.linalg.norm(dv) if S == 1 else 0.0
+
+    def relf(a, b):
+        return np.linalg.norm(a - b) / max(np.linalg.norm(b), floor, 1e-30)
+    assert relf(got_q[:, : nq * d], dq.reshape(T, nq * d)) <= 2e-2
+    assert np.all(got_q[:, nq * d:] == 7.0)   # only the query columns of the gradient rows are written
+    assert relf(got_kv[:, : nkv * d], dk.reshape(batch * S, nkv * d)) <= 2e-2
+    assert relf(got_kv[:, nkv * d:], dv.reshape(batch * S, nkv * d)) <= 2e-2
