@@ -592,19 +592,30 @@ __global__ void bias_residual_add_kernel(const T* __restrict__ a, const T* __res
   x.store(out + idx * 8);
 }
 
-// partial[by][col] = sum of rows by*COLSUM_ROWS .. +COLSUM_ROWS-1 of x (ascending); a thread owns 8 columns.
-#define COLSUM_ROWS 32
+// partial[by][col] = sum of rows by*rpb .. +rpb-1 of x (ascending); a thread owns 8 columns and keeps 8 rows'
+// loads in flight.  Short inputs (the row shard of sequence parallelism) take fewer rows per block so that the
+// launch still covers the chip.
+static inline int colsum_rows_per_block(int T) { return T >= 2048 ? 32 : 8; }
 template <typename T>
-__global__ __launch_bounds__(256) void colsum_rows_kernel(const T* __restrict__ x, float* __restrict__ partial, int rows, int N) {
+__global__ __launch_bounds__(256) void colsum_rows_kernel(const T* __restrict__ x, float* __restrict__ partial, int rows, int N,
+                                                          int rpb) {
   const int col = (blockIdx.x * 256 + threadIdx.x) * 8;
   if (col >= N) return;
-  const int r0 = blockIdx.y * COLSUM_ROWS, r1 = min(rows, r0 + COLSUM_ROWS);
+  const int r0 = blockIdx.y * rpb, r1 = min(rows, r0 + rpb);
   float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  for (int r = r0; r < r1; r++) {
-    Vec8<T> v;
-    v.load(x + (size_t)r * N + col);
+  for (int r = r0; r < r1; r += 8) {
+    Raw8<T> raw[8];
 #pragma unroll
-    for (int i = 0; i < 8; i++) s[i] += v.v[i];
+    for (int u = 0; u < 8; u++)
+      if (r + u < r1) raw[u].load(x + (size_t)(r + u) * N + col);
+#pragma unroll
+    for (int u = 0; u < 8; u++)
+      if (r + u < r1) {
+        Vec8<T> v;
+        v.from(raw[u]);
+#pragma unroll
+        for (int i = 0; i < 8; i++) s[i] += v.v[i];
+      }
   }
   float4* p = reinterpret_cast<float4*>(partial + (size_t)blockIdx.y * N + col);
   p[0] = make_float4(s[0], s[1], s[2], s[3]);
@@ -717,7 +728,8 @@ extern "C" int dh_bias_residual_add(int dtype, int T, int H, const void* a, cons
 }
 
 extern "C" size_t dh_colsum_ws_bytes(int T, int N) {
-  const size_t nblk = (size_t)(T + COLSUM_ROWS - 1) / COLSUM_ROWS, ngrp = (nblk + COLSUM_GROUP - 1) / COLSUM_GROUP;
+  const size_t rpb = colsum_rows_per_block(T);
+  const size_t nblk = ((size_t)T + rpb - 1) / rpb, ngrp = (nblk + COLSUM_GROUP - 1) / COLSUM_GROUP;
   return (nblk + ngrp) * N * sizeof(float);
 }
 
@@ -726,13 +738,14 @@ extern "C" int dh_colsum(int dtype, int T, int N, const void* x, float* out, voi
   if (T == 0) return DH_OK;
   if (!x || !out) DH_FAIL(DH_ERR_INVALID_ARG, "colsum: null pointer");
   if (!ws || ws_bytes < dh_colsum_ws_bytes(T, N)) DH_FAIL(DH_ERR_WORKSPACE_TOO_SMALL, "colsum: workspace %zu < %zu bytes", ws_bytes, dh_colsum_ws_bytes(T, N));
-  const int nblk = (T + COLSUM_ROWS - 1) / COLSUM_ROWS, ngrp = (nblk + COLSUM_GROUP - 1) / COLSUM_GROUP;
+  const int rpb = colsum_rows_per_block(T);
+  const int nblk = (T + rpb - 1) / rpb, ngrp = (nblk + COLSUM_GROUP - 1) / COLSUM_GROUP;
   float* partial = (float*)ws;
   float* grouped = partial + (size_t)nblk * N;
   hipStream_t s = (hipStream_t)stream;
   dim3 g((N / 8 + 255) / 256, nblk);
-  if (dtype == DH_BF16) colsum_rows_kernel<bf16_t><<<g, 256, 0, s>>>((const bf16_t*)x, partial, T, N);
-  else colsum_rows_kernel<float><<<g, 256, 0, s>>>((const float*)x, partial, T, N);
+  if (dtype == DH_BF16) colsum_rows_kernel<bf16_t><<<g, 256, 0, s>>>((const bf16_t*)x, partial, T, N, rpb);
+  else colsum_rows_kernel<float><<<g, 256, 0, s>>>((const float*)x, partial, T, N, rpb);
   DH_LAUNCH_CHECK();
   colsum_group_kernel<<<dim3((N + 255) / 256, ngrp), 256, 0, s>>>(partial, grouped, nblk, N);
   DH_LAUNCH_CHECK();
