@@ -368,7 +368,6 @@ def main():
     # the same step replayed from a HIP graph (one launch per step instead of one per operator)
     graph = dh.dh_si_graph_create(run.layer, alpha.fwd_args, beta.bwd_args, best_plan, run.ws, run.ws_bytes, sa, sb)
     t_graph = time_steps(lambda: dh.dh_si_graph_launch(graph, sa), args.steps, args.warmup, torch)
-    dh.dh_si_graph_destroy(graph)
     t_comm = sum(t_f[i] for i in range(nf) if gf.is_comm[i]) + sum(t_b[j] for j in range(nb) if gb.is_comm[j])
     log("T_seq %.1f us, T_free-running %.1f us, T_SI(plan) %.1f us, T_SI(plan, graph replay) %.1f us, stand-ins solo %.1f us"
         % (t_seq * 1e6, t_free * 1e6, t_si * 1e6, t_graph * 1e6, t_comm * 1e6))
@@ -404,6 +403,20 @@ def main():
     if t_graph < t_si:
         t_si, execution = t_graph, "graph replay (dh_si_graph_launch)"
     value = flops / t_si / 1e12
+    # Spread of the step time: events between consecutive steps on strand alpha's stream (every step forks from it
+    # and joins it), same plan and execution as `value`.
+    step_fn = ((lambda: dh.dh_si_graph_launch(graph, sa)) if execution.startswith("graph")
+               else (lambda: run.si_step(alpha, beta, best_plan, sa, sb, sc)))
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    for _ in range(3):
+        step_fn()
+    marks[0].record(sa)
+    for i in range(args.steps):
+        step_fn()
+        marks[i + 1].record(sa)
+    torch.cuda.synchronize()
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    pct = lambda q: per_step[min(len(per_step) - 1, int(q * len(per_step)))]
     # Composition of the stand-in (communication) time in the manner of Table 7: the share SI hides, the visible share
     # that launch intervals cost (what the graph replay of the same plan saves over eager launches), the visible rest
     # (kernel slowdown under co-execution).  Hidden is capped at the whole: SI also overlaps work that is not communication.
@@ -415,7 +428,8 @@ def main():
     out = {
         "metric": "SI layer fwd+bwd TFLOP/s per MI355X (% bf16 peak); speedup vs sequential",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": t_si * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": t_si * 1e3, "ms_per_step_events": {"p10": pct(0.1), "median": pct(0.5), "p90": pct(0.9)},
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg["bf16"] else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "arch": cfg["arch"], "tokens_per_strand": run.T, "comm_blocks": args.comm_blocks,
                    "cp": [cfg["cp_rank"], cfg["cp_ranks"]] if cfg["arch"] == "llama_cp" else None, "plan_pairs": len(pairs), "plan": best_name, "execution": execution, "standins_on": comm_placement},
@@ -433,6 +447,7 @@ def main():
                      "traffic_unit": "bytes/launch", "algorithmic_bytes": 2.0 * (T * Hd + Hd * F2 + T * F2),
                      "kernel": "gemm_bf16_kernel (first FFN projection %dx%dx%d)" % (T, F2, Hd)},
     }
+    dh.dh_si_graph_destroy(graph)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, flops)
     run.close()
