@@ -372,6 +372,27 @@ def main():
     log("T_seq %.1f us, T_free-running %.1f us, T_SI(plan) %.1f us, T_SI(plan, graph replay) %.1f us, stand-ins solo %.1f us"
         % (t_seq * 1e6, t_free * 1e6, t_si * 1e6, t_graph * 1e6, t_comm * 1e6))
 
+    # The step is timed both ways it can be issued (operator by operator, or as one replay of its recorded graph: same
+    # kernels, bitwise the same results); the faster one is the step time, and config.execution says which.
+    t_eager = t_si
+    execution = "eager (one launch per operator)"
+    if t_graph < t_si:
+        t_si, execution = t_graph, "graph replay (dh_si_graph_launch)"
+    value = flops / t_si / 1e12
+    # Spread of the step time: events between consecutive steps on strand alpha's stream (every step forks from it
+    # and joins it), same plan and execution as `value`.
+    step_fn = ((lambda: dh.dh_si_graph_launch(graph, sa)) if execution.startswith("graph")
+               else (lambda: run.si_step(alpha, beta, best_plan, sa, sb, sc)))
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    for _ in range(3):
+        step_fn()
+    marks[0].record(sa)
+    for i in range(args.steps):
+        step_fn()
+        marks[i + 1].record(sa)
+    torch.cuda.synchronize()
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    pct = lambda q: per_step[min(len(per_step) - 1, int(q * len(per_step)))]
     # roofline of the dominant kernel: the first FFN GEMM (gate/up projection; largest share of the FLOPs), timed
     # alone with events on the stream it is launched on.  MoE: one local expert's balanced share of the rows.
     Hd = cfg["hidden"]
@@ -396,27 +417,6 @@ def main():
     gemm_tflops = 2.0 * T * F2 * Hd / gemm_s / 1e12
     log("dominant GEMM [%d x %d x %d]: %.1f us, %.1f TFLOP/s" % (T, F2, Hd, gemm_s * 1e6, gemm_tflops))
 
-    # The step is timed both ways it can be issued (operator by operator, or as one replay of its recorded graph: same
-    # kernels, bitwise the same results); the faster one is the step time, and config.execution says which.
-    t_eager = t_si
-    execution = "eager (one launch per operator)"
-    if t_graph < t_si:
-        t_si, execution = t_graph, "graph replay (dh_si_graph_launch)"
-    value = flops / t_si / 1e12
-    # Spread of the step time: events between consecutive steps on strand alpha's stream (every step forks from it
-    # and joins it), same plan and execution as `value`.
-    step_fn = ((lambda: dh.dh_si_graph_launch(graph, sa)) if execution.startswith("graph")
-               else (lambda: run.si_step(alpha, beta, best_plan, sa, sb, sc)))
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    for _ in range(3):
-        step_fn()
-    marks[0].record(sa)
-    for i in range(args.steps):
-        step_fn()
-        marks[i + 1].record(sa)
-    torch.cuda.synchronize()
-    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
-    pct = lambda q: per_step[min(len(per_step) - 1, int(q * len(per_step)))]
     # Composition of the stand-in (communication) time in the manner of Table 7: the share SI hides, the visible share
     # that launch intervals cost (what the graph replay of the same plan saves over eager launches), the visible rest
     # (kernel slowdown under co-execution).  Hidden is capped at the whole: SI also overlaps work that is not communication.
