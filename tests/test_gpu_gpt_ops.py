@@ -42,7 +42,7 @@ def f32(*shape, fill=0.0):
 
 
 @pytest.mark.parametrize("bf16", [False, True])
-@pytest.mark.parametrize("T,H", [(1, 8), (37, 256), (130, 4096), (19, 8192), (0, 64)])
+@pytest.mark.parametrize("T,H", [(1, 8), (37, 256), (130, 4096), (19, 8192), (0, 64), (5, 16384)])
 def test_layernorm_fwd_bwd(dh, bf16, T, H):
     x = gen.normal(1, (T, H), 1.0, 0.3, bf16); res = gen.normal(2, (T, H), 0.5, 0.0, bf16)
     rb = gen.normal(6, (H,), 0.1, 0.0, bf16)

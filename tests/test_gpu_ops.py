@@ -41,7 +41,7 @@ def tdtype(bf16):
 
 
 @pytest.mark.parametrize("bf16", [False, True])
-@pytest.mark.parametrize("T,H", [(1, 8), (37, 256), (130, 4096), (19, 8192), (0, 64)])
+@pytest.mark.parametrize("T,H", [(1, 8), (37, 256), (130, 4096), (19, 8192), (0, 64), (7, 16384)])  # 16384: the widest row
 def test_rmsnorm_fwd_bwd(dh, bf16, T, H):
     x = gen.normal(1, (T, H), 1.0, 0.0, bf16); res = gen.normal(2, (T, H), 0.5, 0.0, bf16)
     g = gen.normal(3, (H,), 0.02, 1.0, bf16); dy = gen.normal(4, (T, H), 1e-2, 0.0, bf16)
@@ -73,6 +73,10 @@ def test_rmsnorm_fwd_bwd(dh, bf16, T, H):
 
 
 def test_rmsnorm_errors(dh):
+    wide = torch.zeros(2, 16392, device="cuda"); r2 = torch.zeros(2, device="cuda")
+    with pytest.raises(dh.DhelixError) as e:   # one chunk past the widest supported row
+        dh.dh_rmsnorm_fwd(dh.DH_F32, 2, 16392, wide, None, wide, 1e-5, None, wide, r2)
+    assert e.value.code == dh.DH_ERR_SHAPE
     x = torch.zeros(4, 12, device="cuda")
     with pytest.raises(dh.DhelixError) as e:
         dh.dh_rmsnorm_fwd(dh.DH_F32, 4, 12, x, None, x, 1e-5, None, x, x)
