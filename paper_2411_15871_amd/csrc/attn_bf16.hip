@@ -892,15 +892,16 @@ static int set_lds(K kernel, size_t bytes) {
   return DH_OK;
 }
 
-static int attn_num_cus() {
-  static int n_cus = 0;
-  if (n_cus == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) n_cus = n;
-    else n_cus = 256;
+static int attn_num_cus() {  // of the current device
+  static int cached[DH_MAX_DEVICES] = {};
+  const int dev = dh_device_index();
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) cached[dev] = n;
+    else cached[dev] = 256;
     (void)hipGetLastError();
   }
-  return n_cus;
+  return cached[dev];
 }
 
 // Chunk length of a launch.  The blocks of a launch are (block of 128 positions, chunk) units times nq*batch heads,
@@ -1026,7 +1027,8 @@ int dh_launch_attn_fwd_bf16(int batch, int seq_q, int nq, int nkv, int d, const 
   dim3 grid((unsigned)units * nq * batch), cgrid(nblk * 8, nq, batch);
   const float sl2 = (float)(1.4426950408889634 / sqrt((double)d));
   const size_t lds = 2 * AF_RING * (size_t)AB_KT * d * 2;
-  static bool ready[2] = {false, false};
+  static bool ready_dev[DH_MAX_DEVICES][2] = {};
+  bool* ready = ready_dev[dh_device_index()];
   if (d == 128) {
     if (!ready[0]) { if ((rc = set_lds(attn_fwd_bf16_kernel<128>, lds))) return rc; ready[0] = true; }
     attn_fwd_bf16_kernel<128><<<grid, AB_THREADS, lds, stream>>>(g, qkv, o, lse, T, sl2, ch, units, part_o, part_ml);
@@ -1097,7 +1099,8 @@ int dh_launch_attn_bwd_bf16(int batch, int seq_q, int nq, int nkv, int d, const 
   dim3 gwq((unsigned)pq * nq * batch), gwk((unsigned)pk * nq * batch), gq(nblk_q * 16, nq, batch), gk(nblk * 32, nkv, batch);
   const unsigned nprep = (unsigned)(((size_t)T * nq + 3) / 4);
   const size_t lds_dq = 2 * AB_RING * (size_t)AB_KT * d * 2, lds_dkv = lds_dq + 2 * AB_RING * AB_KT * sizeof(float);
-  static bool ready[2] = {false, false};
+  static bool ready_dev[DH_MAX_DEVICES][2] = {};
+  bool* ready = ready_dev[dh_device_index()];
 #define DH_ATTN_BWD(DD, IDX)                                                                                                   \
   do {                                                                                                                         \
     if (!ready[IDX]) {                                                                                                         \

@@ -16,6 +16,14 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 // ---- error plumbing (host) -------------------------------------------------------------------
 int dh_set_error(int code, const char* fmt, ...);
 #define DH_FAIL(code, ...) return dh_set_error(code, __VA_ARGS__)
+// Host-side state cached per device (kernel attributes, compute-unit counts): index of the current device.
+constexpr int DH_MAX_DEVICES = 64;
+static inline int dh_device_index() {
+  int d = 0;
+  if (hipGetDevice(&d) != hipSuccess || d < 0 || d >= DH_MAX_DEVICES) d = 0;
+  return d;
+}
+
 #define DH_HIP(expr)                                                                     \
   do {                                                                                   \
     hipError_t _e = (expr);                                                              \

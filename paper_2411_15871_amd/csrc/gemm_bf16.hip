@@ -440,17 +440,16 @@ struct GemmPlan {
   int tail_tiles, tail_splits, tail_kt;  // tail launch (0 tiles = none): its tiles, K splits and K tiles per split
 };
 
-static int g_num_cus = 0;
-static int num_cus() {
-  if (g_num_cus == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-      g_num_cus = n;
-    else
-      g_num_cus = 256;
+static int num_cus() {  // of the current device
+  static int cached[DH_MAX_DEVICES] = {};
+  const int dev = dh_device_index();
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) cached[dev] = n;
+    else cached[dev] = 256;
     (void)hipGetLastError();
   }
-  return g_num_cus;
+  return cached[dev];
 }
 
 // Tile and split-K choice.  256x256 tiles when they give most compute units a block; else 256x128 when that gives
@@ -523,11 +522,12 @@ size_t dh_gemm_bf16_ws_bytes(bool ta, bool tb, int M, int N, int K) {
 template <int BM, int BN, int WM, int WN, bool TA, bool TB>
 static int launch_cfg(GemmArgs g, int splits, hipStream_t stream, int n_groups = 1, int tile_first = 0, int n_tiles = -1) {
   constexpr size_t LDS_BYTES = GB_STAGES * (size_t)(BM + BN) * GB_BK * sizeof(bf16_t);
-  static bool attr_set = false;
-  if (!attr_set) {
+  static bool attr_set[DH_MAX_DEVICES] = {};  // the attribute belongs to the kernel's code object on one device
+  const int dev = dh_device_index();
+  if (!attr_set[dev]) {
     DH_HIP(hipFuncSetAttribute((const void*)gemm_bf16_kernel<BM, BN, WM, WN, TA, TB>,
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES));
-    attr_set = true;
+    attr_set[dev] = true;
   }
   g.tiles_m = (g.M + BM - 1) / BM;
   g.tiles_n = (g.N + BN - 1) / BN;
