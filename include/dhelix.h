@@ -83,7 +83,7 @@ typedef struct {
   int head_dim;    /* d */
   int ffn;         /* local FFN width F (per expert for DH_ARCH_MOE) */
   float eps;       /* RMSNorm epsilon */
-  float rope_base; /* RoPE base; pair (i, i+d/2) turns by position * base^(-2i/d) */
+  float rope_base; /* RoPE base; pair i turns by position * base^(-2i/d) */
   int n_ranks;     /* R: partials summed by each collective stand-in (1 = no peers) */
   int comm_blocks; /* thread blocks a collective stand-in may use (its "channel" count); 0 = enough
                       to cover the payload */
@@ -93,6 +93,9 @@ typedef struct {
   int cp_rank;         /* DH_ARCH_LLAMA_CP: this rank's index, 0 .. cp_ranks-1 */
   int cross_blocks;    /* DH_ARCH_LLAMA_CP: thread blocks of a Send/Recv stand-in, which set its rate (a block
                           moves 5-7 GB/s on MI355X); 0 = 8 blocks, about one 400 Gb/s network port */
+  int rope_pairing;    /* dh_rope_pairing: which two elements of a head form RoPE pair i (the paper names no
+                          convention); 0 = DH_ROPE_HALVES */
+  int gelu_form;       /* DH_ARCH_GPT: dh_gelu_form of the MLP activation; 0 = DH_GELU_TANH */
 } dh_layer_config;
 
 /* Device pointers to the shard's weights (read only).  g1,g2: [H]; Wqkv: [H,(nq+2nkv)d] with columns
@@ -458,6 +461,14 @@ int dh_rmsnorm_bwd(int dtype, int T, int H, const void* dy, const void* x, const
                    size_t ws_bytes, void* stream);
 size_t dh_rmsnorm_bwd_ws_bytes(int T, int H);
 
+/* RoPE pair i of a head of d elements: DH_ROPE_HALVES = elements (i, i + d/2), DH_ROPE_ADJACENT = elements
+ * (2i, 2i + 1).  Attention does not care (both are the same rotation up to a fixed permutation of the head's
+ * elements); what matters is that weights trained with one convention meet the same one. */
+typedef enum { DH_ROPE_HALVES = 0, DH_ROPE_ADJACENT = 1 } dh_rope_pairing;
+/* GeLU of the GPT-style MLP (Table 2): DH_GELU_TANH = 0.5 f (1 + tanh(sqrt(2/pi)(f + 0.044715 f^3))),
+ * DH_GELU_ERF = f Phi(f) = 0.5 f (1 + erf(f / sqrt 2)). */
+typedef enum { DH_GELU_TANH = 0, DH_GELU_ERF = 1 } dh_gelu_form;
+
 /* Rotary embedding in place on n_heads heads stored side by side at the start of each row of
  * row_stride elements: pair (i, i+d/2) of a token at position p (= row % seq) turns by
  * p * base^(-2i/d); inverse != 0 turns back (the backward of the rotation). */
@@ -467,6 +478,9 @@ int dh_rope(int dtype, int T, int seq, int n_heads, int head_dim, int row_stride
  * parallelism") are a later chunk of each sequence. */
 int dh_rope_at(int dtype, int T, int seq, int pos0, int n_heads, int head_dim, int row_stride, float base,
                int inverse, void* t, void* stream);
+/* The same with the pairing convention given (dh_rope_pairing); dh_rope and dh_rope_at use DH_ROPE_HALVES. */
+int dh_rope_pairs(int dtype, int pairing, int T, int seq, int pos0, int n_heads, int head_dim, int row_stride,
+                  float base, int inverse, void* t, void* stream);
 
 /* SwiGLU: gu[T,2F] = [gate | up]; a[T,F] = gate*sigmoid(gate)*up; backward writes dgu[T,2F]. */
 int dh_swiglu_fwd(int dtype, int T, int F, const void* gu, void* a, void* stream);
@@ -592,6 +606,9 @@ size_t dh_layernorm_bwd_ws_bytes(int T, int H);
  * n elements, n % 8 == 0. */
 int dh_gelu_fwd(int dtype, size_t n, const void* f, void* a, void* stream);
 int dh_gelu_bwd(int dtype, size_t n, const void* f, const void* da, void* df, void* stream);
+/* The same with the form given (dh_gelu_form); backward of the erf form: df = da (Phi(f) + f phi(f)). */
+int dh_gelu_fwd_form(int dtype, int form, size_t n, const void* f, void* a, void* stream);
+int dh_gelu_bwd_form(int dtype, int form, size_t n, const void* f, const void* da, void* df, void* stream);
 
 /* out[t,:] = a[t,:] + b[t,:] + bias[:]: bias-dropout-add with p = 0 and the residual. */
 int dh_bias_residual_add(int dtype, int T, int H, const void* a, const void* b, const void* bias,

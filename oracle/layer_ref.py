@@ -37,6 +37,8 @@ class LayerCfg:
     F: int
     eps: float = 1e-5
     rope_base: float = 10000.0
+    rope_pairing: int = 0   # 0: pair (i, i + d/2), 1: pair (2i, 2i + 1)
+    gelu_form: int = 0      # 0: tanh form, 1: erf form
 
     @property
     def T(self):
@@ -83,11 +85,12 @@ def layernorm_bwd(dy, x, gamma, mu, rstd):
 
 
 # --------------------------------------------------------------------------- RoPE
-def rope(t, seq, base, inverse=False, pos0=0):
+def rope(t, seq, base, inverse=False, pos0=0, pairing=0):
     """Rotate head vectors t[T, nh, d] (T = batch*seq, sequence-major) by position*theta.
 
-    Pair (i, i+d/2) at position p turns by angle p*base**(-2i/d); inverse=True turns by the
+    Pair i at position p turns by angle p*base**(-2i/d); inverse=True turns by the
     negative angle, which is the backward of the forward rotation (a rotation's transpose).
+    pairing 0: pair i is elements (i, i+d/2); pairing 1: elements (2i, 2i+1).
     pos0: position of each sequence's first row (a context-parallel rank holds a later chunk).
     """
     T, nh, d = t.shape
@@ -99,6 +102,13 @@ def rope(t, seq, base, inverse=False, pos0=0):
     s = np.sin(ang)[:, None, :]
     if inverse:
         s = -s
+    if pairing == 1:
+        out = np.empty_like(t, dtype=np.float64)
+        a = t[..., 0::2]
+        b = t[..., 1::2]
+        out[..., 0::2] = a * c - b * s
+        out[..., 1::2] = a * s + b * c
+        return out
     a = t[..., :half]
     b = t[..., half:]
     return np.concatenate([a * c - b * s, a * s + b * c], axis=-1)
@@ -174,16 +184,26 @@ def swiglu_bwd(da, g, u):
     return da * u * s * (1.0 + g * (1.0 - s)), da * g * s
 
 
+try:  # the error function as a library primitive
+    from scipy.special import erf as _erf
+except ImportError:  # pragma: no cover
+    import math
+    _erf = np.vectorize(math.erf, otypes=[np.float64])
 _K0 = np.sqrt(2.0 / np.pi)
 _K1 = 0.044715
 
 
-def gelu_fwd(x):
-    """tanh-form GeLU: 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3)))."""
+def gelu_fwd(x, form=0):
+    """GeLU.  form 0, tanh form: 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3)));
+    form 1, erf form: x Phi(x) = 0.5 x (1 + erf(x / sqrt 2))."""
+    if form == 1:
+        return 0.5 * x * (1.0 + _erf(x / np.sqrt(2.0)))
     return 0.5 * x * (1.0 + np.tanh(_K0 * (x + _K1 * x ** 3)))
 
 
-def gelu_bwd(dy, x):
+def gelu_bwd(dy, x, form=0):
+    if form == 1:  # d/dx [x Phi(x)] = Phi(x) + x phi(x)
+        return dy * (0.5 * (1.0 + _erf(x / np.sqrt(2.0))) + x * np.exp(-0.5 * x * x) / np.sqrt(2.0 * np.pi))
     t = np.tanh(_K0 * (x + _K1 * x ** 3))
     return dy * (0.5 * (1.0 + t) + 0.5 * x * (1.0 - t * t) * _K0 * (1.0 + 3.0 * _K1 * x * x))
 
@@ -213,8 +233,8 @@ def llama_fwd(cfg, W, x, peers=None):
     q = qkv[:, : nq * d].reshape(T, nq, d)
     k = qkv[:, nq * d: (nq + nkv) * d].reshape(T, nkv, d)
     v = qkv[:, (nq + nkv) * d:].reshape(T, nkv, d)
-    q = rope(q, cfg.seq, cfg.rope_base)
-    k = rope(k, cfg.seq, cfg.rope_base)
+    q = rope(q, cfg.seq, cfg.rope_base, pairing=cfg.rope_pairing)
+    k = rope(k, cfg.seq, cfg.rope_base, pairing=cfg.rope_pairing)
     o, lse = attention_fwd(q, k, v, cfg.batch, cfg.seq)
     o2 = o.reshape(T, nq * d)
     y = standin_sum(o2 @ W["Wo"], peers.get("ar1"))
@@ -247,8 +267,8 @@ def llama_bwd(cfg, W, saved, dout, peers=None):
     do = dx2 @ W["Wo"].T
     dWo = s["o"].T @ dx2
     dq, dk, dv = attention_bwd(do.reshape(T, nq, d), s["q"], s["k"], s["v"], cfg.batch, cfg.seq)
-    dq = rope(dq, cfg.seq, cfg.rope_base, inverse=True)
-    dk = rope(dk, cfg.seq, cfg.rope_base, inverse=True)
+    dq = rope(dq, cfg.seq, cfg.rope_base, inverse=True, pairing=cfg.rope_pairing)
+    dk = rope(dk, cfg.seq, cfg.rope_base, inverse=True, pairing=cfg.rope_pairing)
     dqkv = np.concatenate([dq.reshape(T, -1), dk.reshape(T, -1), dv.reshape(T, -1)], axis=1)
     dWqkv = s["h1"].T @ dqkv
     dh1 = standin_sum(dqkv @ W["Wqkv"].T, peers.get("ar4"))
@@ -419,7 +439,7 @@ def gpt_fwd(cfg, W, x_s, peers=None):
     h2_s, mu2, r2 = layernorm_fwd(x2_s, W["g2"], W["b2"], cfg.eps)
     h2 = allgather_standin(h2_s, peers.get("ag2"))
     f = h2 @ W["W1"] + W["bf1"]
-    a = gelu_fwd(f)
+    a = gelu_fwd(f, cfg.gelu_form)
     z_s = reducescatter_standin(a @ W["W2"], peers.get("rs2"))
     out_s = x2_s + z_s + W["bf2"]
     saved = dict(x=x_s, mu1=mu1, r1=r1, h1=h1, q=q, k=k, v=v, o=o2, lse=lse, x2=x2_s, mu2=mu2, r2=r2, h2=h2, f=f, a=a)
@@ -439,7 +459,7 @@ def gpt_bwd(cfg, W, saved, dout_s, peers=None):
     dz = allgather_standin(dout_s, peers.get("ag3"))
     da = dz @ W["W2"].T
     dW2 = s["a"].T @ dz
-    df = gelu_bwd(da, s["f"])
+    df = gelu_bwd(da, s["f"], cfg.gelu_form)
     dbf1 = df.sum(axis=0)
     dW1 = s["h2"].T @ df
     dh2_s = reducescatter_standin(df @ W["W1"].T, peers.get("rs3"))
@@ -471,8 +491,8 @@ def moe_layer_fwd(cfg, W, x, logits, n_local):
     T, nq, nkv, d = cfg.T, cfg.nq, cfg.nkv, cfg.d
     h1, r1 = rmsnorm_fwd(x, W["g1"], cfg.eps)
     qkv = h1 @ W["Wqkv"]
-    q = rope(qkv[:, : nq * d].reshape(T, nq, d), cfg.seq, cfg.rope_base)
-    k = rope(qkv[:, nq * d: (nq + nkv) * d].reshape(T, nkv, d), cfg.seq, cfg.rope_base)
+    q = rope(qkv[:, : nq * d].reshape(T, nq, d), cfg.seq, cfg.rope_base, pairing=cfg.rope_pairing)
+    k = rope(qkv[:, nq * d: (nq + nkv) * d].reshape(T, nkv, d), cfg.seq, cfg.rope_base, pairing=cfg.rope_pairing)
     v = qkv[:, (nq + nkv) * d:].reshape(T, nkv, d)
     o, lse = attention_fwd(q, k, v, cfg.batch, cfg.seq)
     o2 = o.reshape(T, nq * d)
@@ -494,8 +514,8 @@ def moe_layer_bwd(cfg, W, saved, dout, n_local):
     do = dx2 @ W["Wo"].T
     dWo = s["o"].T @ dx2
     dq, dk, dv = attention_bwd(do.reshape(T, nq, d), s["q"], s["k"], s["v"], cfg.batch, cfg.seq)
-    dq = rope(dq, cfg.seq, cfg.rope_base, inverse=True)
-    dk = rope(dk, cfg.seq, cfg.rope_base, inverse=True)
+    dq = rope(dq, cfg.seq, cfg.rope_base, inverse=True, pairing=cfg.rope_pairing)
+    dk = rope(dk, cfg.seq, cfg.rope_base, inverse=True, pairing=cfg.rope_pairing)
     dqkv = np.concatenate([dq.reshape(T, -1), dk.reshape(T, -1), dv.reshape(T, -1)], axis=1)
     dWqkv = s["h1"].T @ dqkv
     dh1 = dqkv @ W["Wqkv"].T
@@ -592,8 +612,8 @@ def llama_cp_fwd(cfg, W, x, cp_rank, peers=None):
     q_off = cp_rank * cfg.seq
     h1, r1 = rmsnorm_fwd(x, W["g1"], cfg.eps)
     qkv = h1 @ W["Wqkv"]
-    q = rope(qkv[:, : nq * d].reshape(T, nq, d), cfg.seq, cfg.rope_base, pos0=q_off)
-    k = rope(qkv[:, nq * d: (nq + nkv) * d].reshape(T, nkv, d), cfg.seq, cfg.rope_base, pos0=q_off)
+    q = rope(qkv[:, : nq * d].reshape(T, nq, d), cfg.seq, cfg.rope_base, pos0=q_off, pairing=cfg.rope_pairing)
+    k = rope(qkv[:, nq * d: (nq + nkv) * d].reshape(T, nkv, d), cfg.seq, cfg.rope_base, pos0=q_off, pairing=cfg.rope_pairing)
     v = qkv[:, (nq + nkv) * d:].reshape(T, nkv, d)
     K, V = cp_gather_kv(k, v, peers.get("kv"), cfg.batch, cfg.seq, cp_rank)
     o, lse = attention_ctx_fwd(q, K, V, cfg.batch, cfg.seq, q_off)
@@ -648,8 +668,8 @@ def llama_cp_bwd(cfg, W, saved, dout, cp_rank, peers=None):
             dkv_own = dkv_own + peers["dkv"][c].astype(np.float64)
     dk = dkv_own[:, : nkv * d].reshape(T, nkv, d)
     dv = dkv_own[:, nkv * d:]
-    dq = rope(dq, s_l, cfg.rope_base, inverse=True, pos0=q_off)
-    dk = rope(dk, s_l, cfg.rope_base, inverse=True, pos0=q_off)
+    dq = rope(dq, s_l, cfg.rope_base, inverse=True, pos0=q_off, pairing=cfg.rope_pairing)
+    dk = rope(dk, s_l, cfg.rope_base, inverse=True, pos0=q_off, pairing=cfg.rope_pairing)
     dqkv = np.concatenate([dq.reshape(T, -1), dk.reshape(T, -1), dv], axis=1)
     dWqkv = s["h1"].T @ dqkv
     dh1 = standin_sum(dqkv @ W["Wqkv"].T, peers.get("ar4"))

@@ -184,6 +184,9 @@ extern "C" int dh_layer_create(const dh_layer_config* cfg, dh_layer** out) {
   if (c.dtype == DH_BF16 && c.head_dim != 64 && c.head_dim != 128) DH_FAIL(DH_ERR_SHAPE, "layer_create: bf16 needs head_dim 64 or 128");
   if (c.dtype == DH_F32 && c.head_dim > 256) DH_FAIL(DH_ERR_SHAPE, "layer_create: fp32 needs head_dim <= 256");
   if (c.n_ranks < 1 || c.n_ranks > 16) DH_FAIL(DH_ERR_INVALID_ARG, "layer_create: n_ranks %d outside 1..16", c.n_ranks);
+  if (c.rope_pairing != DH_ROPE_HALVES && c.rope_pairing != DH_ROPE_ADJACENT)
+    DH_FAIL(DH_ERR_INVALID_ARG, "layer_create: rope_pairing %d", c.rope_pairing);
+  if (c.gelu_form != DH_GELU_TANH && c.gelu_form != DH_GELU_ERF) DH_FAIL(DH_ERR_INVALID_ARG, "layer_create: gelu_form %d", c.gelu_form);
   if (c.comm_blocks < 0 || c.comm_blocks > 65536) DH_FAIL(DH_ERR_INVALID_ARG, "layer_create: comm_blocks %d outside 0..65536", c.comm_blocks);
   if ((long long)c.batch * c.seq > (1 << 24)) DH_FAIL(DH_ERR_SHAPE, "layer_create: too many tokens");
   if (c.arch == DH_ARCH_GPT && (c.batch * c.seq) % c.n_ranks)
@@ -393,7 +396,7 @@ static int op_attn_bwd(dh_layer* L, const char* sv, char* ws, hipStream_t s) {
 }
 static int op_rope(dh_layer* L, void* qkv, int inverse, hipStream_t s) {
   const dh_layer_config& c = L->c;
-  return dh_rope(c.dtype, L->T, c.seq, c.n_q_heads + c.n_kv_heads, c.head_dim, L->n_qkv, c.rope_base, inverse, qkv, s);
+  return dh_rope_pairs(c.dtype, c.rope_pairing, L->T, c.seq, 0, c.n_q_heads + c.n_kv_heads, c.head_dim, L->n_qkv, c.rope_base, inverse, qkv, s);
 }
 
 static int llama_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hipStream_t s) {
@@ -486,7 +489,7 @@ static int cp_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hipStr
   const int r = c.cp_rank, S = L->q_off + c.seq, W = L->kv_w, blocks = c.cross_blocks > 0 ? c.cross_blocks : 8;
   switch (op) {
     case DH_CF_ROPE: {  // rotate q and k, then put the rank's own keys/values in their place of the attention buffer
-      int rc = dh_rope_at(c.dtype, L->T, c.seq, L->q_off, c.n_q_heads + c.n_kv_heads, c.head_dim, L->n_qkv, c.rope_base, 0, sv + L->s_qkv, s);
+      int rc = dh_rope_pairs(c.dtype, c.rope_pairing, L->T, c.seq, L->q_off, c.n_q_heads + c.n_kv_heads, c.head_dim, L->n_qkv, c.rope_base, 0, sv + L->s_qkv, s);
       if (rc) return rc;
       dh_cp_move m;
       m.src = sv + L->s_qkv + (size_t)c.n_q_heads * c.head_dim * L->es;
@@ -546,7 +549,7 @@ static int cp_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipStr
       return dh_cp_grad_reduce(c.dtype, &own, n_later, later, c.batch, c.seq, W, blocks, s);
     }
     case DH_CB_ROPE:
-      return dh_rope_at(c.dtype, L->T, c.seq, L->q_off, c.n_q_heads + c.n_kv_heads, c.head_dim, L->n_qkv, c.rope_base, 1, ws + L->b_dqkv, s);
+      return dh_rope_pairs(c.dtype, c.rope_pairing, L->T, c.seq, L->q_off, c.n_q_heads + c.n_kv_heads, c.head_dim, L->n_qkv, c.rope_base, 1, ws + L->b_dqkv, s);
   }
   if (op < 0 || op >= DH_CB_NOPS) DH_FAIL(DH_ERR_INVALID_ARG, "unknown backward operator %d", op);
   return llama_bwd_op(L, same[op], b, ws, s, side_ws);
@@ -582,7 +585,7 @@ static int gpt_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hipSt
     case DH_GF_FC1:
       return gemm(L, false, false, T, F, H, sv + L->s_h2, L->w.Wgu, sv + L->s_gu, false, gws, L->f_gemm_bytes, s, L->w.bfc1);
     case DH_GF_ACT:
-      return dh_gelu_fwd(dt, (size_t)T * F, sv + L->s_gu, sv + L->s_a, s);
+      return dh_gelu_fwd_form(dt, c.gelu_form, (size_t)T * F, sv + L->s_gu, sv + L->s_a, s);
     case DH_GF_FC2:
       return gemm(L, false, false, T, H, F, sv + L->s_a, L->w.Wd, ws + L->f_part, false, gws, L->f_gemm_bytes, s);
     case DH_GF_RS2:
@@ -609,7 +612,7 @@ static int gpt_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipSt
       if ((rc = gemm(L, true, false, F, H, T, sv + L->s_a, ws + L->b_dz, L->g.dWd, true, gws, gwb, s))) return rc;
       return dh_colsum(dt, Ts, H, b.dout, L->g.dbfc2, ws + L->b_colsum, L->b_colsum_bytes, s);
     case DH_GB_ACT:
-      return dh_gelu_bwd(dt, (size_t)T * F, sv + L->s_gu, ws + L->b_da, ws + L->b_dgu, s);
+      return dh_gelu_bwd_form(dt, c.gelu_form, (size_t)T * F, sv + L->s_gu, ws + L->b_da, ws + L->b_dgu, s);
     case DH_GB_FC1_DGRAD:
       return gemm(L, false, true, T, H, F, ws + L->b_dgu, L->w.Wgu, ws + L->b_part, false, gws, gwb, s);
     case DH_GB_FC1_WGRAD:
@@ -991,7 +994,7 @@ static bool same_shape(const dh_layer_config& a, const dh_layer_config& b) {
   return a.arch == b.arch && a.dtype == b.dtype && a.batch == b.batch && a.seq == b.seq && a.hidden == b.hidden &&
          a.n_q_heads == b.n_q_heads && a.n_kv_heads == b.n_kv_heads && a.head_dim == b.head_dim && a.ffn == b.ffn &&
          a.n_ranks == b.n_ranks && a.n_experts == b.n_experts && a.n_local_experts == b.n_local_experts &&
-         a.cp_ranks == b.cp_ranks && a.cp_rank == b.cp_rank;
+         a.cp_ranks == b.cp_ranks && a.cp_rank == b.cp_rank && a.rope_pairing == b.rope_pairing && a.gelu_form == b.gelu_form;
 }
 
 extern "C" int dh_si_step_layers(dh_layer* layer_alpha, dh_layer* layer_beta, const dh_fwd_args* alpha, const dh_bwd_args* beta,

@@ -177,7 +177,8 @@ __global__ void colsum_accumulate_kernel(const float* __restrict__ partial, floa
 // at long sequences: theta of the thread's first pair by one double exp2, the next seven by multiplying with
 // ratio = base^(-2/d); the angle is reduced to [-pi, pi] in double, and only sine and cosine of the reduced
 // angle are taken in float (absolute error ~1e-7).
-template <typename T>
+// ADJACENT: pair i is elements (2i, 2i+1): the thread's 8 pairs are 16 consecutive elements.
+template <typename T, bool ADJACENT>
 __global__ void rope_kernel(T* __restrict__ t, int rows, int seq, int pos0, int n_heads, int d, int row_stride, double log2_base,
                             double ratio, int inverse) {
   int half = d / 2;
@@ -189,11 +190,19 @@ __global__ void rope_kernel(T* __restrict__ t, int rows, int seq, int pos0, int 
   int head = (int)((idx / chunks) % n_heads);
   size_t row = idx / ((size_t)chunks * n_heads);
   int pos = pos0 + (int)(row % seq);
-  T* pa = t + row * row_stride + (size_t)head * d + c * 8;
-  T* pb = pa + half;
+  T* pa = t + row * row_stride + (size_t)head * d + (ADJACENT ? c * 16 : c * 8);
+  T* pb = pa + (ADJACENT ? 8 : half);
   Vec8<T> a, b, oa, ob;
   a.load(pa);
   b.load(pb);
+  if (ADJACENT) {  // de-interleave: a = first elements of the 8 pairs, b = second elements
+    Vec8<T> lo = a, hi = b;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      a.v[i] = lo.v[2 * i]; b.v[i] = lo.v[2 * i + 1];
+      a.v[4 + i] = hi.v[2 * i]; b.v[4 + i] = hi.v[2 * i + 1];
+    }
+  }
   double theta = exp2(-2.0 * (double)(c * 8) / (double)d * log2_base);
 #pragma unroll
   for (int i = 0; i < 8; i++) {
@@ -205,6 +214,15 @@ __global__ void rope_kernel(T* __restrict__ t, int rows, int seq, int pos0, int 
     float s = inverse ? -sn : sn;
     oa.v[i] = a.v[i] * co - b.v[i] * s;
     ob.v[i] = a.v[i] * s + b.v[i] * co;
+  }
+  if (ADJACENT) {
+    Vec8<T> lo, hi;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      lo.v[2 * i] = oa.v[i]; lo.v[2 * i + 1] = ob.v[i];
+      hi.v[2 * i] = oa.v[4 + i]; hi.v[2 * i + 1] = ob.v[4 + i];
+    }
+    oa = lo; ob = hi;
   }
   oa.store(pa);
   ob.store(pb);
@@ -347,6 +365,12 @@ extern "C" int dh_rope(int dtype, int T, int seq, int n_heads, int head_dim, int
 
 extern "C" int dh_rope_at(int dtype, int T, int seq, int pos0, int n_heads, int head_dim, int row_stride, float base, int inverse,
                           void* t, void* stream) {
+  return dh_rope_pairs(dtype, DH_ROPE_HALVES, T, seq, pos0, n_heads, head_dim, row_stride, base, inverse, t, stream);
+}
+
+extern "C" int dh_rope_pairs(int dtype, int pairing, int T, int seq, int pos0, int n_heads, int head_dim, int row_stride, float base,
+                             int inverse, void* t, void* stream) {
+  if (pairing != DH_ROPE_HALVES && pairing != DH_ROPE_ADJACENT) DH_FAIL(DH_ERR_INVALID_ARG, "rope: unknown pairing %d", pairing);
   if (T < 0 || seq <= 0 || pos0 < 0 || n_heads <= 0 || head_dim <= 0 || head_dim % 16 || row_stride % 8 || row_stride < n_heads * head_dim)
     DH_FAIL(DH_ERR_SHAPE, "rope: T=%d seq=%d heads=%d d=%d stride=%d (d must be a multiple of 16)", T, seq, n_heads,
             head_dim, row_stride);
@@ -355,10 +379,10 @@ extern "C" int dh_rope_at(int dtype, int T, int seq, int pos0, int n_heads, int 
   size_t total = (size_t)T * n_heads * (head_dim / 16);
   dim3 g((unsigned)((total + 255) / 256)), b(256);
   const double l2b = log2((double)base), ratio = exp2(-2.0 / (double)head_dim * l2b);
-  if (dtype == DH_BF16)
-    rope_kernel<bf16_t><<<g, b, 0, (hipStream_t)stream>>>((bf16_t*)t, T, seq, pos0, n_heads, head_dim, row_stride, l2b, ratio, inverse);
-  else
-    rope_kernel<float><<<g, b, 0, (hipStream_t)stream>>>((float*)t, T, seq, pos0, n_heads, head_dim, row_stride, l2b, ratio, inverse);
+#define GO(TT, ADJ) rope_kernel<TT, ADJ><<<g, b, 0, (hipStream_t)stream>>>((TT*)t, T, seq, pos0, n_heads, head_dim, row_stride, l2b, ratio, inverse)
+  if (dtype == DH_BF16) { if (pairing == DH_ROPE_ADJACENT) GO(bf16_t, true); else GO(bf16_t, false); }
+  else { if (pairing == DH_ROPE_ADJACENT) GO(float, true); else GO(float, false); }
+#undef GO
   DH_LAUNCH_CHECK();
   return DH_OK;
 }
@@ -547,21 +571,23 @@ __global__ __launch_bounds__(ROW_THREADS) void layernorm_bwd_kernel(const T* __r
   }
 }
 
-// ------------------------------------------------------------------------------------ GeLU (tanh form)
+// ------------------------------------------------------------------------------------ GeLU (tanh form, erf form)
 __device__ __forceinline__ float gelu_tanh_inner(float x) { return 0.7978845608028654f * (x + 0.044715f * x * x * x); }
 
-template <typename T>
+template <typename T, bool ERF>
 __global__ void gelu_fwd_kernel(const T* __restrict__ f, T* __restrict__ a, size_t n8) {
   size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= n8) return;
   Vec8<T> x;
   x.load(f + idx * 8);
 #pragma unroll
-  for (int i = 0; i < 8; i++) x.v[i] = 0.5f * x.v[i] * (1.0f + tanhf(gelu_tanh_inner(x.v[i])));
+  for (int i = 0; i < 8; i++)
+    x.v[i] = ERF ? 0.5f * x.v[i] * (1.0f + erff(x.v[i] * 0.7071067811865476f))
+                 : 0.5f * x.v[i] * (1.0f + tanhf(gelu_tanh_inner(x.v[i])));
   x.store(a + idx * 8);
 }
 
-template <typename T>
+template <typename T, bool ERF>
 __global__ void gelu_bwd_kernel(const T* __restrict__ f, const T* __restrict__ da, T* __restrict__ df, size_t n8) {
   size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= n8) return;
@@ -570,8 +596,13 @@ __global__ void gelu_bwd_kernel(const T* __restrict__ f, const T* __restrict__ d
   d.load(da + idx * 8);
 #pragma unroll
   for (int i = 0; i < 8; i++) {
-    const float v = x.v[i], t = tanhf(gelu_tanh_inner(v));
-    d.v[i] *= 0.5f * (1.0f + t) + 0.5f * v * (1.0f - t * t) * 0.7978845608028654f * (1.0f + 3.0f * 0.044715f * v * v);
+    const float v = x.v[i];
+    if (ERF) {  // Phi(v) + v phi(v)
+      d.v[i] *= 0.5f * (1.0f + erff(v * 0.7071067811865476f)) + v * 0.3989422804014327f * expf(-0.5f * v * v);
+    } else {
+      const float t = tanhf(gelu_tanh_inner(v));
+      d.v[i] *= 0.5f * (1.0f + t) + 0.5f * v * (1.0f - t * t) * 0.7978845608028654f * (1.0f + 3.0f * 0.044715f * v * v);
+    }
   }
   d.store(df + idx * 8);
 }
@@ -689,25 +720,38 @@ extern "C" int dh_layernorm_bwd(int dtype, int T, int H, const void* dy, const v
 }
 
 extern "C" int dh_gelu_fwd(int dtype, size_t n, const void* f, void* a, void* stream) {
+  return dh_gelu_fwd_form(dtype, DH_GELU_TANH, n, f, a, stream);
+}
+extern "C" int dh_gelu_bwd(int dtype, size_t n, const void* f, const void* da, void* df, void* stream) {
+  return dh_gelu_bwd_form(dtype, DH_GELU_TANH, n, f, da, df, stream);
+}
+
+extern "C" int dh_gelu_fwd_form(int dtype, int form, size_t n, const void* f, void* a, void* stream) {
+  if (form != DH_GELU_TANH && form != DH_GELU_ERF) DH_FAIL(DH_ERR_INVALID_ARG, "gelu: unknown form %d", form);
   if (n % 8) DH_FAIL(DH_ERR_SHAPE, "gelu_fwd: element count %zu must be a multiple of 8", n);
   if (n == 0) return DH_OK;
   if (!f || !a) DH_FAIL(DH_ERR_INVALID_ARG, "gelu_fwd: null pointer");
   const size_t n8 = n / 8;
   dim3 g((unsigned)((n8 + 255) / 256)), b(256);
-  if (dtype == DH_BF16) gelu_fwd_kernel<bf16_t><<<g, b, 0, (hipStream_t)stream>>>((const bf16_t*)f, (bf16_t*)a, n8);
-  else gelu_fwd_kernel<float><<<g, b, 0, (hipStream_t)stream>>>((const float*)f, (float*)a, n8);
+#define GO(TT, E) gelu_fwd_kernel<TT, E><<<g, b, 0, (hipStream_t)stream>>>((const TT*)f, (TT*)a, n8)
+  if (dtype == DH_BF16) { if (form == DH_GELU_ERF) GO(bf16_t, true); else GO(bf16_t, false); }
+  else { if (form == DH_GELU_ERF) GO(float, true); else GO(float, false); }
+#undef GO
   DH_LAUNCH_CHECK();
   return DH_OK;
 }
 
-extern "C" int dh_gelu_bwd(int dtype, size_t n, const void* f, const void* da, void* df, void* stream) {
+extern "C" int dh_gelu_bwd_form(int dtype, int form, size_t n, const void* f, const void* da, void* df, void* stream) {
+  if (form != DH_GELU_TANH && form != DH_GELU_ERF) DH_FAIL(DH_ERR_INVALID_ARG, "gelu: unknown form %d", form);
   if (n % 8) DH_FAIL(DH_ERR_SHAPE, "gelu_bwd: element count %zu must be a multiple of 8", n);
   if (n == 0) return DH_OK;
   if (!f || !da || !df) DH_FAIL(DH_ERR_INVALID_ARG, "gelu_bwd: null pointer");
   const size_t n8 = n / 8;
   dim3 g((unsigned)((n8 + 255) / 256)), b(256);
-  if (dtype == DH_BF16) gelu_bwd_kernel<bf16_t><<<g, b, 0, (hipStream_t)stream>>>((const bf16_t*)f, (const bf16_t*)da, (bf16_t*)df, n8);
-  else gelu_bwd_kernel<float><<<g, b, 0, (hipStream_t)stream>>>((const float*)f, (const float*)da, (float*)df, n8);
+#define GO(TT, E) gelu_bwd_kernel<TT, E><<<g, b, 0, (hipStream_t)stream>>>((const TT*)f, (const TT*)da, (TT*)df, n8)
+  if (dtype == DH_BF16) { if (form == DH_GELU_ERF) GO(bf16_t, true); else GO(bf16_t, false); }
+  else { if (form == DH_GELU_ERF) GO(float, true); else GO(float, false); }
+#undef GO
   DH_LAUNCH_CHECK();
   return DH_OK;
 }

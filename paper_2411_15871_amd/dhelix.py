@@ -20,6 +20,8 @@ DH_OK, DH_ERR_INVALID_ARG, DH_ERR_SHAPE, DH_ERR_WORKSPACE_TOO_SMALL = 0, -1, -2,
 DH_ERR_PLAN_INVALID, DH_ERR_HIP, DH_ERR_UNSUPPORTED = -4, -5, -6
 DH_F32, DH_BF16 = 0, 1
 DH_ARCH_LLAMA, DH_ARCH_GPT, DH_ARCH_MOE, DH_ARCH_LLAMA_CP = 0, 1, 2, 3
+DH_ROPE_HALVES, DH_ROPE_ADJACENT = 0, 1
+DH_GELU_TANH, DH_GELU_ERF = 0, 1
 DH_WS_FWD, DH_WS_BWD, DH_WS_SI = 0, 1, 2
 DH_COMM_ALLREDUCE, DH_COMM_ALLGATHER, DH_COMM_REDUCESCATTER = 0, 1, 2
 DH_MAX_OPS, DH_MAX_DEPS = 32, 96
@@ -46,7 +48,7 @@ class dh_layer_config(C.Structure):
                 ("n_q_heads", C.c_int), ("n_kv_heads", C.c_int), ("head_dim", C.c_int), ("ffn", C.c_int),
                 ("eps", C.c_float), ("rope_base", C.c_float), ("n_ranks", C.c_int), ("comm_blocks", C.c_int),
                 ("n_experts", C.c_int), ("n_local_experts", C.c_int), ("cp_ranks", C.c_int), ("cp_rank", C.c_int),
-                ("cross_blocks", C.c_int)]
+                ("cross_blocks", C.c_int), ("rope_pairing", C.c_int), ("gelu_form", C.c_int)]
 
 
 class dh_weights(C.Structure):
@@ -160,6 +162,7 @@ SIGNATURES = {
     "dh_rmsnorm_bwd_ws_bytes": (_Z, [_I, _I]),
     "dh_rope": (_I, [_I, _I, _I, _I, _I, _I, _F, _I, _P, _P]),
     "dh_rope_at": (_I, [_I, _I, _I, _I, _I, _I, _I, _F, _I, _P, _P]),
+    "dh_rope_pairs": (_I, [_I, _I, _I, _I, _I, _I, _I, _I, _F, _I, _P, _P]),
     "dh_swiglu_fwd": (_I, [_I, _I, _I, _P, _P, _P]),
     "dh_swiglu_bwd": (_I, [_I, _I, _I, _P, _P, _P, _P]),
     "dh_add": (_I, [_I, _Z, _P, _P, _P, _P]),
@@ -184,6 +187,8 @@ SIGNATURES = {
     "dh_layernorm_bwd_ws_bytes": (_Z, [_I, _I]),
     "dh_gelu_fwd": (_I, [_I, _Z, _P, _P, _P]),
     "dh_gelu_bwd": (_I, [_I, _Z, _P, _P, _P, _P]),
+    "dh_gelu_fwd_form": (_I, [_I, _I, _Z, _P, _P, _P]),
+    "dh_gelu_bwd_form": (_I, [_I, _I, _Z, _P, _P, _P, _P]),
     "dh_bias_residual_add": (_I, [_I, _I, _I, _P, _P, _P, _P, _P]),
     "dh_colsum": (_I, [_I, _I, _I, _P, _P, _P, _Z, _P]),
     "dh_colsum_ws_bytes": (_Z, [_I, _I]),
@@ -615,6 +620,19 @@ def dh_layernorm_bwd_ws_bytes(T, H):
 def dh_layernorm_bwd(dtype, T, H, dy, x, gamma, mu, rstd, dres, dx, dgamma, dbeta, ws, ws_bytes, stream=None):
     _check(lib.dh_layernorm_bwd(dtype, T, H, _ptr(dy), _ptr(x), _ptr(gamma), _ptr(mu), _ptr(rstd), _ptr(dres), _ptr(dx),
                                 _ptr(dgamma), _ptr(dbeta), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def dh_rope_pairs(dtype, pairing, T, seq, pos0, n_heads, head_dim, row_stride, base, inverse, t, stream=None):
+    _check(lib.dh_rope_pairs(dtype, pairing, T, seq, pos0, n_heads, head_dim, row_stride, base, int(inverse), _ptr(t),
+                             _stream(stream)))
+
+
+def dh_gelu_fwd_form(dtype, form, n, f, a, stream=None):
+    _check(lib.dh_gelu_fwd_form(dtype, form, n, _ptr(f), _ptr(a), _stream(stream)))
+
+
+def dh_gelu_bwd_form(dtype, form, n, f, da, df, stream=None):
+    _check(lib.dh_gelu_bwd_form(dtype, form, n, _ptr(f), _ptr(da), _ptr(df), _stream(stream)))
 
 
 def dh_gelu_fwd(dtype, n, f, a, stream=None):

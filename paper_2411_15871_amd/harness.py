@@ -110,7 +110,8 @@ class LayerRun:
                                         n_ranks=c["n_ranks"], comm_blocks=c.get("comm_blocks", 0),
                                         n_experts=c.get("n_experts", 0), n_local_experts=c.get("n_local", 0),
                                         cp_ranks=c.get("cp_ranks", 0), cp_rank=c.get("cp_rank", 0),
-                                        cross_blocks=c.get("cross_blocks", 0))
+                                        cross_blocks=c.get("cross_blocks", 0), rope_pairing=c.get("rope_pairing", 0),
+                                        gelu_form=c.get("gelu_form", 0))
         n_qkv = (c["nq"] + 2 * c["nkv"]) * c["d"]
         if c["arch"] == "gpt":
             self.w_np = gen.gpt_weights(c["hidden"], n_qkv, c["nq"] * c["d"], c["ffn"], bf)

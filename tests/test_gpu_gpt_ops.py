@@ -97,6 +97,23 @@ def test_gelu(dh, bf16, n):
 
 
 @pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("n", [8, 1000 * 8, 4096 * 520])
+def test_gelu_erf_form(dh, bf16, n):
+    f = gen.normal(1, (n,), 2.0, 0.0, bf16); da = gen.normal(2, (n,), 1e-2, 0.0, bf16)
+    fd, dad = dev(f, bf16), dev(da, bf16)
+    a = torch.empty_like(fd); df = torch.empty_like(fd)
+    dh.dh_gelu_fwd_form(dt(dh, bf16), dh.DH_GELU_ERF, n, fd, a)
+    dh.dh_gelu_bwd_form(dt(dh, bf16), dh.DH_GELU_ERF, n, fd, dad, df)
+    torch.cuda.synchronize()
+    assert rel(host(a), R.gelu_fwd(f.astype(np.float64), 1)) <= TOL[bf16]
+    assert rel(host(df), R.gelu_bwd(da.astype(np.float64), f.astype(np.float64), 1)) <= TOL[bf16]
+    if not bf16 and n > 8:   # and it is not the tanh form
+        assert rel(host(a), R.gelu_fwd(f.astype(np.float64), 0)) > 1e-5
+    with pytest.raises(dh.DhelixError):
+        dh.dh_gelu_fwd_form(dt(dh, bf16), 7, n, fd, a)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
 @pytest.mark.parametrize("T,N", [(1, 8), (33, 264), (4096, 3072), (1000, 8192), (0, 64)])
 def test_bias_residual_add_and_colsum(dh, bf16, T, N):
     a = gen.normal(1, (T, N), 1.0, 0.0, bf16); b = gen.normal(2, (T, N), 1.0, 0.0, bf16); bias = gen.normal(3, (N,), 0.1, 0.0, bf16)

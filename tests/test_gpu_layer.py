@@ -16,6 +16,12 @@ CASES = {
     "fp32_ragged": (dict(batch=2, seq=75, hidden=136, nq=4, nkv=2, d=32, ffn=200, n_ranks=3, bf16=False), 1e-5),
     "bf16_mid_ragged": (dict(batch=2, seq=330, hidden=520, nq=4, nkv=1, d=128, ffn=1000, n_ranks=4, bf16=True), 2e-2),
     "bf16_d64_mha": (dict(batch=1, seq=257, hidden=256, nq=4, nkv=4, d=64, ffn=344, n_ranks=1, bf16=True), 2e-2),
+    "fp32_rope_adjacent": (dict(batch=2, seq=75, hidden=136, nq=4, nkv=2, d=32, ffn=200, n_ranks=3, bf16=False, rope_pairing=1), 1e-5),
+    "bf16_rope_adjacent": (dict(batch=2, seq=330, hidden=520, nq=4, nkv=1, d=128, ffn=1000, n_ranks=4, bf16=True, rope_pairing=1), 2e-2),
+    "cp_fp32_rope_adjacent": (dict(arch="llama_cp", batch=2, seq=37, hidden=136, nq=4, nkv=2, d=32, ffn=200, n_ranks=2, bf16=False,
+                                   cp_ranks=3, cp_rank=1, rope_pairing=1), 1e-5),
+    "gpt_fp32_gelu_erf": (dict(arch="gpt", batch=2, seq=40, hidden=136, nq=4, nkv=4, d=32, ffn=200, n_ranks=4, bf16=False, gelu_form=1), 1e-5),
+    "gpt_bf16_gelu_erf": (dict(arch="gpt", batch=2, seq=264, hidden=520, nq=4, nkv=4, d=128, ffn=1000, n_ranks=4, bf16=True, gelu_form=1), 2e-2),
     "c2_llama8b_tp8": (H.CONFIGS["c2_llama8b_tp8"], 2e-2),
     "gpt_fp32_small": (dict(arch="gpt", batch=2, seq=40, hidden=136, nq=4, nkv=4, d=32, ffn=200, n_ranks=4, bf16=False), 1e-5),
     "gpt_bf16_mid": (dict(arch="gpt", batch=2, seq=264, hidden=520, nq=4, nkv=4, d=128, ffn=1000, n_ranks=4, bf16=True), 2e-2),
@@ -51,7 +57,7 @@ def rel(a, b):
 def oracle_run(run, s):
     c = run.cfg
     cfg = R.LayerCfg(batch=c["batch"], seq=c["seq"], H=c["hidden"], nq=c["nq"], nkv=c["nkv"], d=c["d"], F=c["ffn"],
-                     eps=c["eps"], rope_base=c["rope_base"])
+                     eps=c["eps"], rope_base=c["rope_base"], rope_pairing=c.get("rope_pairing", 0), gelu_form=c.get("gelu_form", 0))
     W = {k: v.astype(np.float64) for k, v in run.w_np.items()}
     x, dout = s.x_np.astype(np.float64), s.dout_np.astype(np.float64)
     if c["arch"] == "gpt":

@@ -105,6 +105,26 @@ def test_rope(dh, bf16, batch, seq, nh, d, extra):
 
 
 @pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("batch,seq,pos0,nh,d,extra", [(1, 9, 0, 3, 16, 0), (2, 130, 4096, 5, 128, 64), (1, 700, 37, 2, 64, 8)])
+def test_rope_adjacent_pairs(dh, bf16, batch, seq, pos0, nh, d, extra):
+    """Pairing (2i, 2i+1), at a position offset, forward and back."""
+    T = batch * seq
+    stride = nh * d + extra
+    t = gen.normal(9, (T, stride), 1.0, 0.0, bf16)
+    td = dev(t, bf16)
+    dh.dh_rope_pairs(dt(dh, bf16), dh.DH_ROPE_ADJACENT, T, seq, pos0, nh, d, stride, 10000.0, False, td)
+    got = host(td)
+    ref = R.rope(t[:, : nh * d].astype(np.float64).reshape(T, nh, d), seq, 10000.0, pos0=pos0, pairing=1).reshape(T, nh * d)
+    assert rel(got[:, : nh * d], ref) <= (4e-3 if bf16 else 2e-6)
+    assert np.array_equal(got[:, nh * d:], t[:, nh * d:].astype(np.float64))
+    if not bf16:
+        dh.dh_rope_pairs(dt(dh, bf16), dh.DH_ROPE_ADJACENT, T, seq, pos0, nh, d, stride, 10000.0, True, td)
+        assert rel(host(td)[:, : nh * d], t[:, : nh * d]) <= 2e-6
+    with pytest.raises(dh.DhelixError):
+        dh.dh_rope_pairs(dt(dh, bf16), 2, T, seq, pos0, nh, d, stride, 10000.0, False, td)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
 @pytest.mark.parametrize("T,F", [(5, 8), (77, 688), (256, 1792)])
 def test_swiglu_and_add(dh, bf16, T, F):
     gu = gen.normal(11, (T, 2 * F), 2.0, 0.0, bf16); da = gen.normal(12, (T, F), 1.0, 0.0, bf16)

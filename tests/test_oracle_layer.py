@@ -93,6 +93,33 @@ def test_rope_pairing_and_angle_by_hand():
     assert np.allclose(out, exp, atol=1e-14)
 
 
+def test_rope_adjacent_pairing():
+    """Pairing (2i, 2i+1): by hand on one vector; the same rotation as the half-split pairing seen through the
+    permutation that brings element 2i to i and 2i+1 to i + d/2; norm, position 0, inverse and relative position."""
+    d, base = 4, 10000.0
+    q = np.zeros((3, 1, d)); q[2, 0] = [1.0, 2.0, 3.0, 4.0]
+    out = R.rope(q, 3, base, pairing=1)[2, 0]
+    th = [1.0, base ** (-2.0 / d)]
+    exp = [1 * math.cos(2 * th[0]) - 2 * math.sin(2 * th[0]), 1 * math.sin(2 * th[0]) + 2 * math.cos(2 * th[0]),
+           3 * math.cos(2 * th[1]) - 4 * math.sin(2 * th[1]), 3 * math.sin(2 * th[1]) + 4 * math.cos(2 * th[1])]
+    assert np.allclose(out, exp, atol=1e-14)
+    seq, d = 6, 16
+    x = rng.standard_normal((2 * seq, 3, d))
+    perm = np.concatenate([np.arange(0, d, 2), np.arange(1, d, 2)])   # halves layout <- adjacent layout
+    via_halves = np.empty_like(x)
+    via_halves[..., perm] = R.rope(x[..., perm], seq, 500.0, pos0=3)
+    got = R.rope(x, seq, 500.0, pos0=3, pairing=1)
+    assert np.allclose(got, via_halves, atol=1e-14)
+    assert not np.allclose(got, R.rope(x, seq, 500.0, pos0=3))        # and it is a different map on the same layout
+    assert np.allclose(np.linalg.norm(got, axis=-1), np.linalg.norm(x, axis=-1), atol=1e-13)
+    assert np.allclose(R.rope(x, seq, 500.0, pairing=1)[0], x[0])
+    assert np.allclose(R.rope(got, seq, 500.0, inverse=True, pos0=3, pairing=1), x, atol=1e-13)
+    a = rng.standard_normal(d); b2 = rng.standard_normal(d)
+    A = R.rope(np.tile(a, (seq, 1, 1)), seq, 500.0, pairing=1)[:, 0]
+    B = R.rope(np.tile(b2, (seq, 1, 1)), seq, 500.0, pairing=1)[:, 0]
+    assert abs(A[3] @ B[1] - A[5] @ B[3]) < 1e-12
+
+
 # ------------------------------------------------------------------ attention
 def brute_attention(q, k, v, batch, seq):
     T, nq, d = q.shape
@@ -169,6 +196,29 @@ def test_swiglu_and_gelu_scalar_forms():
     xs = np.linspace(-4, 4, 33)
     erf_form = np.array([0.5 * t * (1 + math.erf(t / math.sqrt(2))) for t in xs])
     assert np.max(np.abs(R.gelu_fwd(xs) - erf_form)) < 1e-3
+
+
+def test_gelu_erf_form():
+    """x Phi(x): Phi from the printed normal table (4 digits) and from Simpson integration of the density (no error
+    function involved), the odd-part identity gelu(x) - gelu(-x) = x, the derivative Phi(x) + x phi(x) by hand at one
+    point and by finite differences."""
+    def phi_cdf(t, n=20000):   # 0.5 + integral of the density from 0 to t, Simpson's rule
+        h = t / n
+        f = lambda u: math.exp(-0.5 * u * u) / math.sqrt(2 * math.pi)
+        acc = f(0.0) + f(t) + sum((4 if i % 2 else 2) * f(i * h) for i in range(1, n))
+        return 0.5 + acc * h / 3
+    assert R.gelu_fwd(np.zeros(1), 1)[0] == 0.0 and abs(R.gelu_bwd(np.ones(1), np.zeros(1), 1)[0] - 0.5) < 1e-15
+    assert abs(R.gelu_fwd(np.array([1.0]), 1)[0] - 0.8413) < 5e-5             # table: Phi(1.00) = 0.8413
+    assert abs(R.gelu_fwd(np.array([-1.96]), 1)[0] + 1.96 * 0.0250) < 1e-4    # table: Phi(-1.96) = 0.0250
+    for t in (0.3, 1.0, 2.5, -1.7):
+        assert abs(R.gelu_fwd(np.array([t]), 1)[0] - t * phi_cdf(t)) < 1e-12
+    x = rng.standard_normal((3, 4)); w = rng.standard_normal((3, 4))
+    assert np.allclose(R.gelu_fwd(x, 1) - R.gelu_fwd(-x, 1), x, atol=1e-15)
+    d1 = phi_cdf(1.0) + 1.0 * math.exp(-0.5) / math.sqrt(2 * math.pi)
+    assert abs(R.gelu_bwd(np.ones(1), np.ones(1), 1)[0] - d1) < 1e-12
+    fg = lambda: float(np.sum(R.gelu_fwd(x, 1) * w))
+    assert relerr(R.gelu_bwd(w, x, 1), fd_grad(fg, x)) < 1e-8
+    assert np.max(np.abs(R.gelu_fwd(x, 1) - R.gelu_fwd(x, 0))) > 1e-5      # the two forms do differ
 
 
 def test_standin_sum_is_exact_ordered_sum():
