@@ -219,6 +219,56 @@ def test_si_step_bitwise_equals_sequential_and_matches_oracle(name):
         run.close()
 
 
+@pytest.mark.parametrize("name", ["c2_llama8b_tp8", "c3_gpt_tp8_sp", "c5_phimoe_ep8", "c6_llama8b_tp8_cp4"])
+def test_si_step_bitwise_equals_sequential_at_full_size(name):
+    """The invariant holds at any size: at the benchmark shapes, in the configurations bench.py times (stand-ins in the
+    strand streams or on a communication stream, a searched plan, eager and graph replay), the interleaved step
+    leaves bitwise what alpha's forward followed by beta's backward leaves."""
+    from paper_2411_15871_amd import dhelix as dh
+    cfg, _ = CASES[name]
+    run = H.LayerRun(cfg)
+    comm = torch.cuda.Stream()
+    try:
+        alpha, beta = run.strand(0), run.strand(1)
+        sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+        run.fwd(beta)
+        torch.cuda.synchronize()
+        alpha.out.zero_(); alpha.saved.zero_(); beta.dx.zero_()
+        run.zero_grads()
+        run.fwd(alpha)
+        run.bwd(beta)
+        ref = snapshot(run, alpha, beta)
+        gf, gb = dh.dh_layer_op_graph(run.layer, 0), dh.dh_layer_op_graph(run.layer, 1)
+        table = dh.dh_profile_pairs(run.layer, alpha.fwd_args, beta.bwd_args, run.ws, run.ws_bytes, sa, sb, comm, 1)
+        searched, _ = dh.dh_plan_search(gf, gb, table, 5e-6, 64)
+        plans = {"searched": searched, "random": random_legal_plan(dh, run, random.Random(11))}
+
+        def reset():
+            alpha.out.zero_(); alpha.saved.zero_(); beta.dx.zero_()
+            if beta.dkv_peers is not None:
+                beta.dkv_peers.zero_()
+            run.zero_grads()
+            torch.cuda.synchronize()
+        for pname, plan in plans.items():
+            for c in (None, comm):
+                print("plan", pname, "comm" if c else "nocomm", flush=True)
+                reset()
+                run.si_step(alpha, beta, plan, sa, sb, c)
+                for a, b in zip(snapshot(run, alpha, beta), ref):
+                    assert torch.equal(a, b), pname
+            graph = dh.dh_si_graph_create(run.layer, alpha.fwd_args, beta.bwd_args, plan, run.ws, run.ws_bytes, sa, sb)
+            try:
+                for _ in range(2):
+                    reset()
+                    dh.dh_si_graph_launch(graph, sa)
+                    for a, b in zip(snapshot(run, alpha, beta), ref):
+                        assert torch.equal(a, b), pname + " (graph)"
+            finally:
+                dh.dh_si_graph_destroy(graph)
+    finally:
+        run.close()
+
+
 def test_empty_micro_batch_is_a_no_op():
     run = H.LayerRun(dict(batch=0, seq=16, hidden=64, nq=2, nkv=1, d=32, ffn=64, n_ranks=2, bf16=False))
     try:
