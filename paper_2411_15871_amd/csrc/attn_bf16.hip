@@ -540,26 +540,26 @@ __global__ __launch_bounds__(256) void attn_fwd_combine_kernel(int seq, int q_of
 }
 
 // ================================================================================ backward prologue
-// delta[h,t] = sum_c dO[t,h,c]*O[t,h,c]; lse2[h,t] = lse[h,t]*log2(e).  One wave per (token, head).
+// delta[h,t] = sum_c dO[t,h,c]*O[t,h,c]; lse2[h,t] = lse[h,t]*log2(e).  D/8 lanes per (token, head), 16 bytes of
+// each operand per lane.
 template <int D>
 __global__ __launch_bounds__(256) void attn_bwd_prep_kernel(int nq, const bf16_t* __restrict__ o, const bf16_t* __restrict__ dout,
                                                             const float* __restrict__ lse, float* __restrict__ delta,
                                                             float* __restrict__ lse2, int T) {
-  const int lane = threadIdx.x & 63;
-  const size_t pair = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // (token, head) index
+  constexpr int LPP = D / 8;  // lanes per (token, head); divides the wave, so a group leaves or stays as a whole
+  const size_t pair = ((size_t)blockIdx.x * 256 + threadIdx.x) / LPP;
+  const int sub = threadIdx.x % LPP;
   if (pair >= (size_t)T * nq) return;
   const size_t tok = pair / nq;
   const int h = (int)(pair % nq);
-  const size_t base = tok * (size_t)nq * D + (size_t)h * D;
+  const size_t base = pair * D + sub * 8;  // rows are [token][head][D]
+  const bf16x8 a = *reinterpret_cast<const bf16x8*>(o + base), c = *reinterpret_cast<const bf16x8*>(dout + base);
   float s = 0.f;
-  if (D == 128) {
-    bf16x2 a = *reinterpret_cast<const bf16x2*>(o + base + lane * 2), c = *reinterpret_cast<const bf16x2*>(dout + base + lane * 2);
-    s = (float)a[0] * (float)c[0] + (float)a[1] * (float)c[1];
-  } else {
-    s = (float)o[base + lane] * (float)dout[base + lane];
-  }
-  s = wave_sum(s);
-  if (lane == 0) {
+#pragma unroll
+  for (int i = 0; i < 8; i++) s += (float)a[i] * (float)c[i];
+#pragma unroll
+  for (int off = LPP / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+  if (sub == 0) {
     delta[(size_t)h * T + tok] = s;
     lse2[(size_t)h * T + tok] = lse[(size_t)h * T + tok] * LOG2E;
   }
@@ -685,9 +685,10 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(const Attn
 // dq[token][head] = scale * sum over the chunks of the token's query block (ascending) of the partials.
 // grid (16*query blocks, nq, batch), 256 threads: a block owns 8 rows of a query block, thread = (row, 4 columns).
 template <int D>
-__global__ __launch_bounds__(256) void attn_bwd_dq_reduce_kernel(const float* __restrict__ part, bf16_t* __restrict__ dqkv, int seq,
-                                                                 int q_off, int nq, int nkv, int pairs, int cl, float scale) {
-  const int i = q_off / 128 + (blockIdx.x >> 4), r0 = (blockIdx.x & 15) * 8, h = blockIdx.y, b = blockIdx.z, ld = (nq + 2 * nkv) * D;
+__device__ __forceinline__ void attn_bwd_dq_reduce_block(int bx, int by, int bz, const float* __restrict__ part,
+                                                         bf16_t* __restrict__ dqkv, int seq, int q_off, int nq, int nkv, int pairs,
+                                                         int cl, float scale) {
+  const int i = q_off / 128 + (bx >> 4), r0 = (bx & 15) * 8, h = by, b = bz, ld = (nq + 2 * nkv) * D;
   int base = 0;
   for (int k = q_off / 128; k < i; k++) base += chunks_of(dq_tiles(k, seq), cl);
   const int ch = chunks_of(dq_tiles(i, seq), cl);
@@ -865,9 +866,10 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(const Att
 // grid (32*ceil(seq/128), nkv, batch), 256 threads: a block owns 4 rows of a key block, thread = (key row, 4
 // columns of [dK | dV]).
 template <int D>
-__global__ __launch_bounds__(256) void attn_bwd_group_reduce_kernel(const float* __restrict__ part, const AttnGeom g, int pairs) {
+__device__ __forceinline__ void attn_bwd_group_reduce_block(int bx, int by, int bz, const float* __restrict__ part, const AttnGeom& g,
+                                                            int pairs) {
   const int seq = g.seq, nq = g.nq, nkv = g.nkv;
-  const int i = blockIdx.x >> 5, r0 = (blockIdx.x & 31) * 4, hk = blockIdx.y, b = blockIdx.z, grp = nq / nkv;
+  const int i = bx >> 5, r0 = (bx & 31) * 4, hk = by, b = bz, grp = nq / nkv;
   int base = 0;
   for (int k = 0; k < i; k++) base += chunks_of(dkv_tiles(k, seq, g.q_off), g.ch);
   const int ch = chunks_of(dkv_tiles(i, seq, g.q_off), g.ch);
@@ -882,6 +884,24 @@ __global__ __launch_bounds__(256) void attn_bwd_group_reduce_kernel(const float*
     bf16x4 o = {(bf16_t)s[0], (bf16_t)s[1], (bf16_t)s[2], (bf16_t)s[3]};
     bf16_t* dst = g.dkv + ((size_t)b * seq + i * 128 + row) * g.lddkv + (c4 < D ? (size_t)hk * D + c4 : (size_t)(nkv + hk) * D + (c4 - D));
     *reinterpret_cast<bf16x4*>(dst) = o;
+  }
+}
+
+// Both merges in one launch (they are independent, short and bandwidth-bound): the first nb_q blocks are the
+// (x, y, z) = (16 * query blocks, nq, batch) grid of the dQ merge, the rest the (32 * key blocks, nkv, batch) grid of
+// the dK/dV merge; either part may be empty.
+template <int D>
+__global__ __launch_bounds__(256) void attn_bwd_reduce_kernel(const float* __restrict__ part_q, bf16_t* __restrict__ dqkv, int pairs_q,
+                                                              int ch_q, float scale, unsigned nb_q, unsigned gqx, unsigned gqy,
+                                                              const float* __restrict__ part_kv, const AttnGeom g, int pairs_k,
+                                                              unsigned gkx, unsigned gky) {
+  unsigned id = blockIdx.x;
+  if (id < nb_q) {
+    attn_bwd_dq_reduce_block<D>((int)(id % gqx), (int)(id / gqx % gqy), (int)(id / (gqx * gqy)), part_q, dqkv, g.seq, g.q_off, g.nq,
+                                g.nkv, pairs_q, ch_q, scale);
+  } else {
+    id -= nb_q;
+    attn_bwd_group_reduce_block<D>((int)(id % gkx), (int)(id / gkx % gky), (int)(id / (gkx * gky)), part_kv, g, pairs_k);
   }
 }
 
@@ -1097,7 +1117,9 @@ int dh_launch_attn_bwd_bf16(int batch, int seq_q, int nq, int nkv, int d, const 
   const float sc = (float)(1.0 / sqrt((double)d)), sl2 = (float)(1.4426950408889634 / sqrt((double)d));
   const int nblk = (seq + 127) / 128, nblk_q = nblk - q_off / 128, pq = lay.pq, pk = lay.pk;
   dim3 gwq((unsigned)pq * nq * batch), gwk((unsigned)pk * nq * batch), gq(nblk_q * 16, nq, batch), gk(nblk * 32, nkv, batch);
-  const unsigned nprep = (unsigned)(((size_t)T * nq + 3) / 4);
+  const unsigned nb_q = part_q ? gq.x * gq.y * gq.z : 0, nb_k = part_kv ? gk.x * gk.y * gk.z : 0;
+  const size_t prep_pairs = 256 / (d / 8);  // (token, head) pairs per block of the prologue
+  const unsigned nprep = (unsigned)(((size_t)T * nq + prep_pairs - 1) / prep_pairs);
   const size_t lds_dq = 2 * AB_RING * (size_t)AB_KT * d * 2, lds_dkv = lds_dq + 2 * AB_RING * AB_KT * sizeof(float);
   static bool ready_dev[DH_MAX_DEVICES][2] = {};
   bool* ready = ready_dev[dh_device_index()];
@@ -1111,10 +1133,13 @@ int dh_launch_attn_bwd_bf16(int batch, int seq_q, int nq, int nkv, int d, const 
     DH_LAUNCH_CHECK();                                                                                                         \
     attn_bwd_dq_bf16_kernel<DD><<<gwq, AB_THREADS, lds_dq, stream>>>(gq_geom, qkv, dout, lse2, delta, dqkv, part_q, pq, T, sc, sl2);   \
     DH_LAUNCH_CHECK();                                                                                                         \
-    if (part_q) { attn_bwd_dq_reduce_kernel<DD><<<gq, 256, 0, stream>>>(part_q, dqkv, seq, q_off, nq, nkv, pq, lay.ch_q, sc); DH_LAUNCH_CHECK(); } \
     attn_bwd_dkv_bf16_kernel<DD><<<gwk, AB_THREADS, lds_dkv, stream>>>(gk_geom, qkv, dout, lse2, delta, part_kv, pk, T, sc, sl2);      \
     DH_LAUNCH_CHECK();                                                                                                         \
-    if (part_kv) { attn_bwd_group_reduce_kernel<DD><<<gk, 256, 0, stream>>>(part_kv, gk_geom, pk); DH_LAUNCH_CHECK(); }                \
+    if (nb_q + nb_k > 0) {                                                                                                     \
+      attn_bwd_reduce_kernel<DD><<<nb_q + nb_k, 256, 0, stream>>>(part_q, dqkv, pq, lay.ch_q, sc, nb_q, gq.x, gq.y, part_kv, gk_geom, pk, \
+                                                                 gk.x, gk.y);                                                  \
+      DH_LAUNCH_CHECK();                                                                                                       \
+    }                                                                                                                          \
   } while (0)
   if (d == 128) DH_ATTN_BWD(128, 0); else DH_ATTN_BWD(64, 1);
 #undef DH_ATTN_BWD
