@@ -539,40 +539,19 @@ __global__ __launch_bounds__(256) void attn_fwd_combine_kernel(int seq, int q_of
   if (c0 == 0) lse[(size_t)h * T + tok] = (M + log2f(L)) * 0.6931471805599453f;
 }
 
-// ================================================================================ backward prologue
-// delta[h,t] = sum_c dO[t,h,c]*O[t,h,c]; lse2[h,t] = lse[h,t]*log2(e).  D/8 lanes per (token, head), 16 bytes of
-// each operand per lane.
-template <int D>
-__global__ __launch_bounds__(256) void attn_bwd_prep_kernel(int nq, const bf16_t* __restrict__ o, const bf16_t* __restrict__ dout,
-                                                            const float* __restrict__ lse, float* __restrict__ delta,
-                                                            float* __restrict__ lse2, int T) {
-  constexpr int LPP = D / 8;  // lanes per (token, head); divides the wave, so a group leaves or stays as a whole
-  const size_t pair = ((size_t)blockIdx.x * 256 + threadIdx.x) / LPP;
-  const int sub = threadIdx.x % LPP;
-  if (pair >= (size_t)T * nq) return;
-  const size_t tok = pair / nq;
-  const int h = (int)(pair % nq);
-  const size_t base = pair * D + sub * 8;  // rows are [token][head][D]
-  const bf16x8 a = *reinterpret_cast<const bf16x8*>(o + base), c = *reinterpret_cast<const bf16x8*>(dout + base);
-  float s = 0.f;
-#pragma unroll
-  for (int i = 0; i < 8; i++) s += (float)a[i] * (float)c[i];
-#pragma unroll
-  for (int off = LPP / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-  if (sub == 0) {
-    delta[(size_t)h * T + tok] = s;
-    lse2[(size_t)h * T + tok] = lse[(size_t)h * T + tok] * LOG2E;
-  }
-}
-
 // ================================================================================ backward: dQ
 // Same tiling as the forward kernel.  dQ^T = sum over key tiles of K^T dS^T, dS^T = P^T (dP^T - delta),
 // P^T = exp2(S^T*scale_log2 - lse2), dP^T = V dO^T.
+// The kernel also forms the backward pass's per-row statistics, delta[h,t] = sum_c dO[t,h,c] O[t,h,c] and
+// lse2[h,t] = lse[h,t] log2(e): every block for its own rows (a row's two lanes each hold half of dO), and the block
+// of a query block's first chunk stores them for the dK/dV kernel, which runs after this one.
 template <int D>
 __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(const AttnGeom g, const bf16_t* __restrict__ qkv,
+                                                                      const bf16_t* __restrict__ o,
                                                                       const bf16_t* __restrict__ dout,
-                                                                      const float* __restrict__ lse2,
-                                                                      const float* __restrict__ delta,
+                                                                      const float* __restrict__ lse,
+                                                                      float* __restrict__ lse2,
+                                                                      float* __restrict__ delta,
                                                                       bf16_t* __restrict__ dqkv, float* __restrict__ part,
                                                                       int pairs, int T, float scale, float scale_log2) {
   using TL = ATile<D>;
@@ -596,8 +575,21 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(const Attn
   const size_t qrow = (size_t)(qtok0 + min(iq, seq - 1));
   load_row_frags<D>(qf, qkv + qrow * ld + (size_t)h * D, iq < seq, kg);
   load_row_frags<D>(dof, dout + qrow * (size_t)nq * D + (size_t)h * D, iq < seq, kg);
-  const float l2 = lse2[(size_t)h * T + qrow];
-  const float dl = delta[(size_t)h * T + qrow];
+  const float l2 = lse[(size_t)h * T + qrow] * LOG2E;
+  float dl = 0.f;
+  {
+    bf16x8 of[D / 16];
+    load_row_frags<D>(of, o + qrow * (size_t)nq * D + (size_t)h * D, iq < seq, kg);
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ks++)
+#pragma unroll
+      for (int e = 0; e < 8; e++) dl = fmaf((float)dof[ks][e], (float)of[ks][e], dl);
+    dl += __shfl_xor(dl, 32, 64);  // the row's other half
+    if (cm.chunk == 0 && kg == 0 && iq < seq) {
+      delta[(size_t)h * T + qrow] = dl;
+      lse2[(size_t)h * T + qrow] = l2;
+    }
+  }
   f32x16 dqt[D / 32];
 #pragma unroll
   for (int dt = 0; dt < D / 32; dt++) acc_zero<D>(dqt[dt]);
@@ -1118,8 +1110,6 @@ int dh_launch_attn_bwd_bf16(int batch, int seq_q, int nq, int nkv, int d, const 
   const int nblk = (seq + 127) / 128, nblk_q = nblk - q_off / 128, pq = lay.pq, pk = lay.pk;
   dim3 gwq((unsigned)pq * nq * batch), gwk((unsigned)pk * nq * batch), gq(nblk_q * 16, nq, batch), gk(nblk * 32, nkv, batch);
   const unsigned nb_q = part_q ? gq.x * gq.y * gq.z : 0, nb_k = part_kv ? gk.x * gk.y * gk.z : 0;
-  const size_t prep_pairs = 256 / (d / 8);  // (token, head) pairs per block of the prologue
-  const unsigned nprep = (unsigned)(((size_t)T * nq + prep_pairs - 1) / prep_pairs);
   const size_t lds_dq = 2 * AB_RING * (size_t)AB_KT * d * 2, lds_dkv = lds_dq + 2 * AB_RING * AB_KT * sizeof(float);
   static bool ready_dev[DH_MAX_DEVICES][2] = {};
   bool* ready = ready_dev[dh_device_index()];
@@ -1129,9 +1119,7 @@ int dh_launch_attn_bwd_bf16(int batch, int seq_q, int nq, int nkv, int d, const 
       if ((rc = set_lds(attn_bwd_dq_bf16_kernel<DD>, lds_dq)) || (rc = set_lds(attn_bwd_dkv_bf16_kernel<DD>, lds_dkv))) return rc; \
       ready[IDX] = true;                                                                                                       \
     }                                                                                                                          \
-    attn_bwd_prep_kernel<DD><<<nprep, 256, 0, stream>>>(nq, o, dout, lse, delta, lse2, T);                                       \
-    DH_LAUNCH_CHECK();                                                                                                         \
-    attn_bwd_dq_bf16_kernel<DD><<<gwq, AB_THREADS, lds_dq, stream>>>(gq_geom, qkv, dout, lse2, delta, dqkv, part_q, pq, T, sc, sl2);   \
+    attn_bwd_dq_bf16_kernel<DD><<<gwq, AB_THREADS, lds_dq, stream>>>(gq_geom, qkv, o, dout, lse, lse2, delta, dqkv, part_q, pq, T, sc, sl2); \
     DH_LAUNCH_CHECK();                                                                                                         \
     attn_bwd_dkv_bf16_kernel<DD><<<gwk, AB_THREADS, lds_dkv, stream>>>(gk_geom, qkv, dout, lse2, delta, part_kv, pk, T, sc, sl2);      \
     DH_LAUNCH_CHECK();                                                                                                         \
