@@ -700,7 +700,7 @@ __device__ __forceinline__ void attn_bwd_dq_reduce_block(int bx, int by, int bz,
 // j0 + 32w .. +31 and keeps their K, V fragments and the dK^T, dV^T accumulators in registers while
 // 64-query tiles of that head's Q and dO stream through LDS.  With grouped heads (nq > nkv) the
 // block writes float32 partials part[batch][query head][pair][128 keys][dK | dV] and
-// attn_bwd_group_reduce_kernel adds the group's heads and the key block's chunks in index order; with
+// attn_bwd_reduce_kernel (its dK/dV part) adds the group's heads and the key block's chunks in index order; with
 // nq == nkv and no block longer than one chunk it writes dK, dV directly.
 template <int D>
 __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(const AttnGeom g, const bf16_t* __restrict__ qkv,
