@@ -55,12 +55,11 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_fwd_kernel(const T* __res
 // Block b handles rows [b*RPB, (b+1)*RPB).  dx = rstd*(gh - xh*mean(gh*xh)) (+ dres), gh = gamma*dy,
 // xh = x*rstd.  The next row is already in flight while the current one is reduced.  The gain
 // gradient sum_t dy*xh is accumulated per thread over the block's rows and written as one partial
-// row per block; two small kernels then add the partial rows in a fixed order (first groups of
-// COLSUM_GROUP consecutive rows, then the groups), so the result does not depend on scheduling.
+// row per block; colsum_finish_kernel then adds the partial rows in an order fixed by the shapes, so the result
+// does not depend on scheduling.
 // Rows a backward-norm block walks (its partial gain gradient is one row of the column-sum input): 8, fewer for
 // short inputs so that a couple of hundred blocks exist.
 __host__ __device__ static inline int norm_bwd_rpb(int rows) { return rows >= 4096 ? 8 : rows >= 1024 ? 4 : rows >= 512 ? 2 : 1; }
-#define COLSUM_GROUP 32
 template <typename T, int NCH>
 __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                                                                   const T* __restrict__ gamma,
@@ -142,33 +141,34 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_bwd_kernel(const T* __res
   }
 }
 
-// out[grp][col] = sum of partial rows grp*COLSUM_GROUP .. +COLSUM_GROUP-1 (ascending), one thread per column.
-__global__ void colsum_group_kernel(const float* __restrict__ partial, float* __restrict__ out, int nrows, int H) {
-  int col = blockIdx.x * blockDim.x + threadIdx.x;
-  if (col >= H) return;
-  int r0 = blockIdx.y * COLSUM_GROUP, r1 = min(nrows, r0 + COLSUM_GROUP);
-  float v[COLSUM_GROUP];
-#pragma unroll
-  for (int i = 0; i < COLSUM_GROUP; i++) v[i] = r0 + i < r1 ? partial[(size_t)(r0 + i) * H + col] : 0.f;
+// dst[col] += sum over the nrows partial rows of partial[row][col], in an order fixed by the shapes alone: a block owns
+// 32 columns, its 8 slices of threads each add a contiguous eighth of the rows in ascending order (16 loads in
+// flight), and slice 0 adds the eight sums in slice order.  Columns [0, H0) go to dst0, columns [H0, ld) to dst1.
+#define COLSUM_SLICES 8
+__global__ __launch_bounds__(256) void colsum_finish_kernel(const float* __restrict__ partial, int nrows, int ld,
+                                                            float* __restrict__ dst0, int H0, float* __restrict__ dst1) {
+  __shared__ float part[COLSUM_SLICES][32];
+  const int c = threadIdx.x & 31, slice = threadIdx.x >> 5, col = blockIdx.x * 32 + c;
+  const int per = (nrows + COLSUM_SLICES - 1) / COLSUM_SLICES, r0 = slice * per, r1 = min(nrows, r0 + per);
   float s = 0.f;
+  if (col < ld) {
+    for (int b0 = r0; b0 < r1; b0 += 16) {
+      float v[16];
 #pragma unroll
-  for (int i = 0; i < COLSUM_GROUP; i++) s += v[i];
-  out[(size_t)blockIdx.y * H + col] = s;
-}
-
-// dst[col] += sum_b partial[b*ld + col], b ascending.
-__global__ void colsum_accumulate_kernel(const float* __restrict__ partial, float* __restrict__ dst, int nblk, int H, int ld) {
-  int col = blockIdx.x * blockDim.x + threadIdx.x;
-  if (col >= H) return;
-  float s = 0.f;
-  for (int b0 = 0; b0 < nblk; b0 += 16) {  // 16 independent loads in flight, added in ascending order
-    float v[16];
+      for (int i = 0; i < 16; i++) v[i] = b0 + i < r1 ? partial[(size_t)(b0 + i) * ld + col] : 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; i++) v[i] = b0 + i < nblk ? partial[(size_t)(b0 + i) * ld + col] : 0.f;
-#pragma unroll
-    for (int i = 0; i < 16; i++) s += v[i];
+      for (int i = 0; i < 16; i++) s += v[i];
+    }
   }
-  dst[col] += s;
+  part[slice][c] = s;
+  __syncthreads();
+  if (slice == 0 && col < ld) {
+    float t = part[0][c];
+#pragma unroll
+    for (int k = 1; k < COLSUM_SLICES; k++) t += part[k][c];
+    if (col < H0) dst0[col] += t;
+    else dst1[col - H0] += t;
+  }
 }
 
 // ------------------------------------------------------------------------------------ RoPE
@@ -330,19 +330,14 @@ static int rmsnorm_bwd_t(int rows, int H, const void* dy, const void* x, const v
   }
 #undef GO
   DH_LAUNCH_CHECK();
-  const int ngrp = (nblk + COLSUM_GROUP - 1) / COLSUM_GROUP;
-  float* grouped = partial + (size_t)nblk * H;
-  colsum_group_kernel<<<dim3((H + 255) / 256, ngrp), 256, 0, s>>>(partial, grouped, nblk, H);
-  DH_LAUNCH_CHECK();
-  colsum_accumulate_kernel<<<(H + 63) / 64, 64, 0, s>>>(grouped, dgamma, ngrp, H, H);
+  colsum_finish_kernel<<<(H + 31) / 32, 256, 0, s>>>(partial, nblk, H, dgamma, H, nullptr);
   DH_LAUNCH_CHECK();
   return DH_OK;
 }
 
 extern "C" size_t dh_rmsnorm_bwd_ws_bytes(int T, int H) {
   size_t nblk = (size_t)(T + norm_bwd_rpb(T) - 1) / norm_bwd_rpb(T);
-  size_t ngrp = (nblk + COLSUM_GROUP - 1) / COLSUM_GROUP;
-  return (nblk + ngrp) * H * sizeof(float);
+  return nblk * H * sizeof(float);
 }
 
 extern "C" int dh_rmsnorm_bwd(int dtype, int T, int H, const void* dy, const void* x, const void* gamma,
@@ -708,13 +703,7 @@ extern "C" int dh_layernorm_bwd(int dtype, int T, int H, const void* dy, const v
 #undef GO2
 #undef GO
   DH_LAUNCH_CHECK();
-  const int ngrp = (nblk + COLSUM_GROUP - 1) / COLSUM_GROUP;
-  float* grouped = partial + (size_t)nblk * 2 * H;
-  colsum_group_kernel<<<dim3((2 * H + 255) / 256, ngrp), 256, 0, s>>>(partial, grouped, nblk, 2 * H);
-  DH_LAUNCH_CHECK();
-  colsum_accumulate_kernel<<<(H + 63) / 64, 64, 0, s>>>(grouped, dgamma, ngrp, H, 2 * H);
-  DH_LAUNCH_CHECK();
-  colsum_accumulate_kernel<<<(H + 63) / 64, 64, 0, s>>>(grouped + H, dbeta, ngrp, H, 2 * H);
+  colsum_finish_kernel<<<(2 * H + 31) / 32, 256, 0, s>>>(partial, nblk, 2 * H, dgamma, H, dbeta);
   DH_LAUNCH_CHECK();
   return DH_OK;
 }
@@ -773,8 +762,8 @@ extern "C" int dh_bias_residual_add(int dtype, int T, int H, const void* a, cons
 
 extern "C" size_t dh_colsum_ws_bytes(int T, int N) {
   const size_t rpb = colsum_rows_per_block(T);
-  const size_t nblk = ((size_t)T + rpb - 1) / rpb, ngrp = (nblk + COLSUM_GROUP - 1) / COLSUM_GROUP;
-  return (nblk + ngrp) * N * sizeof(float);
+  const size_t nblk = ((size_t)T + rpb - 1) / rpb;
+  return nblk * N * sizeof(float);
 }
 
 extern "C" int dh_colsum(int dtype, int T, int N, const void* x, float* out, void* ws, size_t ws_bytes, void* stream) {
@@ -783,17 +772,14 @@ extern "C" int dh_colsum(int dtype, int T, int N, const void* x, float* out, voi
   if (!x || !out) DH_FAIL(DH_ERR_INVALID_ARG, "colsum: null pointer");
   if (!ws || ws_bytes < dh_colsum_ws_bytes(T, N)) DH_FAIL(DH_ERR_WORKSPACE_TOO_SMALL, "colsum: workspace %zu < %zu bytes", ws_bytes, dh_colsum_ws_bytes(T, N));
   const int rpb = colsum_rows_per_block(T);
-  const int nblk = (T + rpb - 1) / rpb, ngrp = (nblk + COLSUM_GROUP - 1) / COLSUM_GROUP;
+  const int nblk = (T + rpb - 1) / rpb;
   float* partial = (float*)ws;
-  float* grouped = partial + (size_t)nblk * N;
   hipStream_t s = (hipStream_t)stream;
   dim3 g((N / 8 + 255) / 256, nblk);
   if (dtype == DH_BF16) colsum_rows_kernel<bf16_t><<<g, 256, 0, s>>>((const bf16_t*)x, partial, T, N, rpb);
   else colsum_rows_kernel<float><<<g, 256, 0, s>>>((const float*)x, partial, T, N, rpb);
   DH_LAUNCH_CHECK();
-  colsum_group_kernel<<<dim3((N + 255) / 256, ngrp), 256, 0, s>>>(partial, grouped, nblk, N);
-  DH_LAUNCH_CHECK();
-  colsum_accumulate_kernel<<<(N + 63) / 64, 64, 0, s>>>(grouped, out, ngrp, N, N);
+  colsum_finish_kernel<<<(N + 31) / 32, 256, 0, s>>>(partial, nblk, N, out, N, nullptr);
   DH_LAUNCH_CHECK();
   return DH_OK;
 }
