@@ -511,17 +511,32 @@ __global__ __launch_bounds__(ROW_THREADS) void layernorm_bwd_kernel(const T* __r
   const int rpb = norm_bwd_rpb(rows);
   const size_t row0 = (size_t)blockIdx.x * rpb;
   const int nrows = min(rpb, rows - (int)row0);
+  Raw8<T> ndy[NCH], nx[NCH], nres[NCH];  // the next row, as fetched
+  auto fetch = [&](size_t row) {
+#pragma unroll
+    for (int c = 0; c < NCH; c++) {
+      int col = (threadIdx.x + ROW_THREADS * c) * 8;
+      if (col < H) {
+        ndy[c].load(dy + row * H + col);
+        nx[c].load(x + row * H + col);
+        if (dres != nullptr) nres[c].load(dres + row * H + col);
+      }
+    }
+  };
+  fetch(row0);
   for (int rr = 0; rr < nrows; rr++) {
     const size_t row = row0 + rr;
     const float r = rstd[row], m = mu[row];
     Vec8<T> gh[NCH], xh[NCH];
+    Raw8<T> rs[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; c++) { gh[c].from(ndy[c]); xh[c].from(nx[c]); rs[c] = nres[c]; }
+    if (rr + 1 < nrows) fetch(row + 1);
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int c = 0; c < NCH; c++) {
       int col = (threadIdx.x + ROW_THREADS * c) * 8;
       if (col < H) {
-        gh[c].load(dy + row * H + col);
-        xh[c].load(x + row * H + col);
 #pragma unroll
         for (int i = 0; i < 8; i++) {
           xh[c].v[i] = (xh[c].v[i] - m) * r;
@@ -543,10 +558,8 @@ __global__ __launch_bounds__(ROW_THREADS) void layernorm_bwd_kernel(const T* __r
 #pragma unroll
         for (int i = 0; i < 8; i++) o.v[i] = r * (gh[c].v[i] - s1 - xh[c].v[i] * s2);
         if (dres != nullptr) {
-          Vec8<T> rs;
-          rs.load(dres + row * H + col);
 #pragma unroll
-          for (int i = 0; i < 8; i++) o.v[i] += rs.v[i];
+          for (int i = 0; i < 8; i++) o.v[i] += rs[c].get(i);
         }
         o.store(dx + row * H + col);
       }
