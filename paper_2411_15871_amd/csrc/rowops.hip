@@ -580,7 +580,10 @@ __global__ __launch_bounds__(ROW_THREADS) void layernorm_bwd_kernel(const T* __r
 }
 
 // ------------------------------------------------------------------------------------ GeLU (tanh form, erf form)
+// 0.5 (1 + tanh u) = sigmoid(2u), so the tanh form is x * sigmoid(2u), u = sqrt(2/pi) (x + 0.044715 x^3): one
+// exponential per element; its derivative is s + x s (1 - s) 2 u', s = sigmoid(2u).
 __device__ __forceinline__ float gelu_tanh_inner(float x) { return 0.7978845608028654f * (x + 0.044715f * x * x * x); }
+__device__ __forceinline__ float gelu_sigmoid2u(float x) { return 1.0f / (1.0f + expf(-2.0f * gelu_tanh_inner(x))); }
 
 template <typename T, bool ERF>
 __global__ void gelu_fwd_kernel(const T* __restrict__ f, T* __restrict__ a, size_t n8) {
@@ -591,7 +594,7 @@ __global__ void gelu_fwd_kernel(const T* __restrict__ f, T* __restrict__ a, size
 #pragma unroll
   for (int i = 0; i < 8; i++)
     x.v[i] = ERF ? 0.5f * x.v[i] * (1.0f + erff(x.v[i] * 0.7071067811865476f))
-                 : 0.5f * x.v[i] * (1.0f + tanhf(gelu_tanh_inner(x.v[i])));
+                 : x.v[i] * gelu_sigmoid2u(x.v[i]);
   x.store(a + idx * 8);
 }
 
@@ -608,8 +611,8 @@ __global__ void gelu_bwd_kernel(const T* __restrict__ f, const T* __restrict__ d
     if (ERF) {  // Phi(v) + v phi(v)
       d.v[i] *= 0.5f * (1.0f + erff(v * 0.7071067811865476f)) + v * 0.3989422804014327f * expf(-0.5f * v * v);
     } else {
-      const float t = tanhf(gelu_tanh_inner(v));
-      d.v[i] *= 0.5f * (1.0f + t) + 0.5f * v * (1.0f - t * t) * 0.7978845608028654f * (1.0f + 3.0f * 0.044715f * v * v);
+      const float sg = gelu_sigmoid2u(v);
+      d.v[i] *= sg + v * sg * (1.0f - sg) * 2.0f * 0.7978845608028654f * (1.0f + 3.0f * 0.044715f * v * v);
     }
   }
   d.store(df + idx * 8);
