@@ -548,7 +548,7 @@ typedef struct {
   int32_t* counts;       /* [E]    rows per logical expert                                       */
   int32_t* offsets;      /* [E+1]  first send row of each logical expert                         */
   int32_t* recv_start;   /* [E]    first receive row of each logical expert                      */
-  int32_t* group_rows;   /* [n_local] rows per local expert (copy to the host for dh_gemm_grouped) */
+  int32_t* group_rows;   /* [n_local] rows per local expert (dh_gemm_grouped reads it on the device)     */
 } dh_moe_tables;
 /* Fills every table from idx[T,2].  E % n_local must be 0. */
 int dh_moe_plan(int T, int E, int n_local, const int32_t* idx, const dh_moe_tables* tables,
