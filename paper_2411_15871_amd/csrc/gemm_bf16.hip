@@ -359,6 +359,37 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmArgs g) {
         }
     return;
   }
+  if (g.epi == EPI_STORE_BF16 && m0 + BM <= g.M && n0 + BN <= g.N) {
+    // Whole tile, bf16 result: the wave turns its part of C around in LDS (the ring is free now) so that a lane
+    // stores 16 bytes and a store instruction covers 8 rows of 128 contiguous bytes, instead of 8 bytes per lane
+    // scattered over 32 rows.  Wave-private region [WTM rows][64 columns], 16-byte chunks XOR-swizzled by row.
+    static_assert(WTN == 64, "a row of the wave's part is 128 bytes");
+    __syncthreads();
+    bf16_t* reg = smem + wave * (WTM * WTN);
+#pragma unroll
+    for (int i = 0; i < MT; i++)
+#pragma unroll
+      for (int j = 0; j < NT; j++)
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+          const int row = i * 32 + l32, c0 = j * 32 + 8 * q + 4 * kg;
+          f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+          if (g.bias != nullptr) {
+            const bf16x4 bb = *reinterpret_cast<const bf16x4*>(g.bias + n0 + wn0 + c0);
+            v += f32x4{(float)bb[0], (float)bb[1], (float)bb[2], (float)bb[3]};
+          }
+          const bf16x4 o = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+          *reinterpret_cast<bf16x4*>(reg + row * WTN + ((((c0 >> 3) ^ (row & 7)) << 3) | (c0 & 4))) = o;
+        }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int it = 0; it < WTM / 8; it++) {
+      const int row = it * 8 + (lane >> 3), ch = lane & 7;
+      const bf16x8 o = *reinterpret_cast<const bf16x8*>(reg + row * WTN + ((ch ^ (row & 7)) << 3));
+      *reinterpret_cast<bf16x8*>(Cb + (size_t)(m0 + wm0 + row) * g.N + n0 + wn0 + ch * 8) = o;
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < MT; i++) {
     const int row = m0 + wm0 + i * 32 + l32;
