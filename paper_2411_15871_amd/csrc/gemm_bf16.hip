@@ -390,6 +390,35 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmArgs g) {
     }
     return;
   }
+  if (g.epi != EPI_STORE_BF16 && m0 + BM <= g.M && n0 + BN <= g.N) {
+    // Whole tile, float32 result (accumulate or partial): the same turn through LDS, one 32-column tile column j at a
+    // time (wave-private region [WTM rows][32 floats], 16-byte chunks XOR-swizzled by row), so that a lane reads /
+    // adds / writes 16 bytes of a 128-byte row segment.
+    __syncthreads();
+    float* reg = reinterpret_cast<float*>(smem_raw) + wave * (WTM * 32);
+#pragma unroll
+    for (int j = 0; j < NT; j++) {
+      if (j > 0) __builtin_amdgcn_wave_barrier();  // the region's previous contents have been read
+#pragma unroll
+      for (int i = 0; i < MT; i++)
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+          const int row = i * 32 + l32, ch = 2 * q + kg;
+          const f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+          *reinterpret_cast<f32x4*>(reg + row * 32 + ((ch ^ (row & 7)) << 2)) = v;
+        }
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int it = 0; it < WTM / 8; it++) {
+        const int row = it * 8 + (lane >> 3), ch = lane & 7;
+        const f32x4 v = *reinterpret_cast<const f32x4*>(reg + row * 32 + ((ch ^ (row & 7)) << 2));
+        f32x4* p = reinterpret_cast<f32x4*>(Cf + (size_t)(m0 + wm0 + row) * g.N + n0 + wn0 + j * 32 + ch * 4);
+        if (g.epi == EPI_ACC_F32) *p = *p + v;
+        else *p = v;
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < MT; i++) {
     const int row = m0 + wm0 + i * 32 + l32;
