@@ -341,6 +341,54 @@ static int fwd_units(int seq, int q_off, int ch) {
 // slots each (64 KiB per block at D = 128), so that two blocks fit a compute unit: the matrix work of
 // one block's waves then overlaps the softmax arithmetic of the other's.
 #define AF_RING 2
+
+// A wave's 32 rows x D columns in the transposed accumulator layout (lane l32 = row, kg = lane / 32; quad (dt, q4) of
+// a lane is columns dt*32 + 8*q4 + 4*kg .. +3) leave through a wave-private LDS region so that a lane stores 16 bytes
+// of a contiguous row segment instead of 16 (float32) or 8 (bf16) bytes scattered over 32 rows.  16-byte chunks are
+// XOR-swizzled by row; quad(dt, q4) returns the four values, row_ptr(r) the destination of row r or nullptr.
+// The region must not be in use by any wave (block barrier before the first call).
+template <int D, typename Quad, typename RowPtr>
+__device__ __forceinline__ void wave_rows_out_f32(float* reg, int lane, Quad quad, RowPtr row_ptr) {
+  constexpr int NCH = D / 4;  // 16-byte chunks per row
+  const int l32 = lane & 31, kg = lane >> 5;
+#pragma unroll
+  for (int dt = 0; dt < D / 32; dt++)
+#pragma unroll
+    for (int q4 = 0; q4 < 4; q4++) {
+      const int ch = (dt * 32 + 8 * q4 + 4 * kg) >> 2;
+      *reinterpret_cast<f32x4*>(reg + l32 * D + ((ch ^ (l32 & (NCH - 1))) << 2)) = quad(dt, q4);
+    }
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll
+  for (int it = 0; it < 32 * NCH / 64; it++) {
+    const int row = it * (64 / NCH) + lane / NCH, ch = lane % NCH;
+    const f32x4 v = *reinterpret_cast<const f32x4*>(reg + row * D + ((ch ^ (row & (NCH - 1))) << 2));
+    float* dst = row_ptr(row);
+    if (dst != nullptr) *reinterpret_cast<f32x4*>(dst + ch * 4) = v;
+  }
+}
+template <int D, typename Quad, typename RowPtr>
+__device__ __forceinline__ void wave_rows_out_bf16(bf16_t* reg, int lane, Quad quad, RowPtr row_ptr) {
+  constexpr int NCH = D / 8;  // 16-byte chunks per row
+  const int l32 = lane & 31, kg = lane >> 5;
+#pragma unroll
+  for (int dt = 0; dt < D / 32; dt++)
+#pragma unroll
+    for (int q4 = 0; q4 < 4; q4++) {
+      const int c0 = dt * 32 + 8 * q4 + 4 * kg;
+      const f32x4 v = quad(dt, q4);
+      const bf16x4 o = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+      *reinterpret_cast<bf16x4*>(reg + l32 * D + ((((c0 >> 3) ^ (l32 & (NCH - 1))) << 3) | (c0 & 4))) = o;
+    }
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll
+  for (int it = 0; it < 32 * NCH / 64; it++) {
+    const int row = it * (64 / NCH) + lane / NCH, ch = lane % NCH;
+    const bf16x8 v = *reinterpret_cast<const bf16x8*>(reg + row * D + ((ch ^ (row & (NCH - 1))) << 3));
+    bf16_t* dst = row_ptr(row);
+    if (dst != nullptr) *reinterpret_cast<bf16x8*>(dst + ch * 8) = v;
+  }
+}
 template <int D>
 __global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(const AttnGeom g, const bf16_t* __restrict__ qkv,
                                                                    bf16_t* __restrict__ o, float* __restrict__ lse, int T,
@@ -461,38 +509,27 @@ __global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(const Attn
         for (int dt = 0; dt < D / 32; dt++) ot[dt] = MFMA(lds_frag_tr(Vp.t0[dt], Vp.t1[dt], ro), pf, ot[dt]);
       }
   }
+  __syncthreads();  // every wave is done with the K/V rings: their LDS serves the output turn
   if (nchunks > 1) {  // partial result of this chunk
-    if (iq < seq) {
-      const size_t unit = ((size_t)b * nq + h) * units + pair;
-      float* prow = part_o + (unit * 128 + (iq - i0)) * D;
-#pragma unroll
-      for (int dt = 0; dt < D / 32; dt++)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; q4++) {
-          f32x4 v = {ot[dt][4 * q4], ot[dt][4 * q4 + 1], ot[dt][4 * q4 + 2], ot[dt][4 * q4 + 3]};
-          *reinterpret_cast<f32x4*>(prow + dt * 32 + 8 * q4 + 4 * kg) = v;
-        }
-      if (kg == 0) {
-        part_ml[(unit * 128 + (iq - i0)) * 2] = m;
-        part_ml[(unit * 128 + (iq - i0)) * 2 + 1] = l;
-      }
+    const size_t unit = ((size_t)b * nq + h) * units + pair;
+    wave_rows_out_f32<D>(
+        reinterpret_cast<float*>(smem) + wave * (32 * D), lane,
+        [&](int dt, int q4) { return f32x4{ot[dt][4 * q4], ot[dt][4 * q4 + 1], ot[dt][4 * q4 + 2], ot[dt][4 * q4 + 3]}; },
+        [&](int r) { return iw + r < seq ? part_o + (unit * 128 + (iw + r - i0)) * D : nullptr; });
+    if (iq < seq && kg == 0) {
+      part_ml[(unit * 128 + (iq - i0)) * 2] = m;
+      part_ml[(unit * 128 + (iq - i0)) * 2 + 1] = l;
     }
     return;
   }
-  if (iq < seq) {
-    const float inv = 1.0f / l;
-    bf16_t* orow = o + (size_t)(qtok0 + iq) * nq * D + (size_t)h * D;
-#pragma unroll
-    for (int dt = 0; dt < D / 32; dt++)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; q4++) {
-        bf16x4 v;
-#pragma unroll
-        for (int i = 0; i < 4; i++) v[i] = (bf16_t)(ot[dt][4 * q4 + i] * inv);
-        *reinterpret_cast<bf16x4*>(orow + dt * 32 + 8 * q4 + 4 * kg) = v;
-      }
-    if (kg == 0) lse[(size_t)h * T + qtok0 + iq] = (m + log2f(l)) * 0.6931471805599453f;
-  }
+  const float inv = 1.0f / l;
+  wave_rows_out_bf16<D>(
+      reinterpret_cast<bf16_t*>(smem) + wave * (32 * D), lane,
+      [&](int dt, int q4) {
+        return f32x4{ot[dt][4 * q4] * inv, ot[dt][4 * q4 + 1] * inv, ot[dt][4 * q4 + 2] * inv, ot[dt][4 * q4 + 3] * inv};
+      },
+      [&](int r) { return iw + r < seq ? o + (size_t)(qtok0 + iw + r) * nq * D + (size_t)h * D : nullptr; });
+  if (iq < seq && kg == 0) lse[(size_t)h * T + qtok0 + iq] = (m + log2f(l)) * 0.6931471805599453f;
 }
 
 // Merges the chunks of the query blocks that were split: with M = max_c m_c, o = sum_c 2^(m_c-M) o_c / L,
