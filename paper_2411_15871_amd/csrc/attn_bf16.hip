@@ -688,26 +688,20 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(const Attn
     acc_tile_tr<D>(dqt, Kp, st, [&](int g) { if (g + 1 < 4) ds_quarter(g + 1); });
   }
   acc_settle<D>(dqt);
+  __syncthreads();  // every wave is done with the K/V rings: their LDS serves the output turn
   if (part != nullptr) {  // float32 partial of this chunk: part[batch][head][pair][128 rows][D], unscaled
-    float* row = part + ((((size_t)b * nq + h) * pairs + cm.pair) * 128 + wave * 32 + l32) * D;
-#pragma unroll
-    for (int dt = 0; dt < D / 32; dt++)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; q4++) {
-        f32x4 v = {dqt[dt][4 * q4], dqt[dt][4 * q4 + 1], dqt[dt][4 * q4 + 2], dqt[dt][4 * q4 + 3]};
-        *reinterpret_cast<f32x4*>(row + dt * 32 + 8 * q4 + 4 * kg) = v;
-      }
-  } else if (iq < seq) {
-    bf16_t* row = dqkv + (size_t)(qtok0 + iq) * ld + (size_t)h * D;
-#pragma unroll
-    for (int dt = 0; dt < D / 32; dt++)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; q4++) {
-        bf16x4 v;
-#pragma unroll
-        for (int i = 0; i < 4; i++) v[i] = (bf16_t)(dqt[dt][4 * q4 + i] * scale);
-        *reinterpret_cast<bf16x4*>(row + dt * 32 + 8 * q4 + 4 * kg) = v;
-      }
+    float* rows = part + ((((size_t)b * nq + h) * pairs + cm.pair) * 128 + wave * 32) * D;
+    wave_rows_out_f32<D>(
+        reinterpret_cast<float*>(smem) + wave * (32 * D), lane,
+        [&](int dt, int q4) { return f32x4{dqt[dt][4 * q4], dqt[dt][4 * q4 + 1], dqt[dt][4 * q4 + 2], dqt[dt][4 * q4 + 3]}; },
+        [&](int r) { return rows + (size_t)r * D; });
+  } else {
+    wave_rows_out_bf16<D>(
+        reinterpret_cast<bf16_t*>(smem) + wave * (32 * D), lane,
+        [&](int dt, int q4) {
+          return f32x4{dqt[dt][4 * q4] * scale, dqt[dt][4 * q4 + 1] * scale, dqt[dt][4 * q4 + 2] * scale, dqt[dt][4 * q4 + 3] * scale};
+        },
+        [&](int r) { return iw + r < seq ? dqkv + (size_t)(qtok0 + iw + r) * ld + (size_t)h * D : nullptr; });
   }
 }
 
@@ -859,34 +853,24 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(const Att
   }
   acc_settle<D>(dkt);
   acc_settle<D>(dvt);
+  __syncthreads();  // every wave is done with the Q/dO rings: their LDS serves the output turn (dK, then dV)
+  auto dk_quad = [&](int dt, int q4) {
+    return f32x4{dkt[dt][4 * q4] * scale, dkt[dt][4 * q4 + 1] * scale, dkt[dt][4 * q4 + 2] * scale, dkt[dt][4 * q4 + 3] * scale};
+  };
+  auto dv_quad = [&](int dt, int q4) { return f32x4{dvt[dt][4 * q4], dvt[dt][4 * q4 + 1], dvt[dt][4 * q4 + 2], dvt[dt][4 * q4 + 3]}; };
   if (part != nullptr) {
-    float* prow = part + ((((size_t)b * nq + hq) * pairs + cm.pair) * 128 + wave * 32 + l32) * (2 * D);
-#pragma unroll
-    for (int dt = 0; dt < D / 32; dt++)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; q4++) {
-        f32x4 a, c;
-#pragma unroll
-        for (int i = 0; i < 4; i++) { a[i] = dkt[dt][4 * q4 + i] * scale; c[i] = dvt[dt][4 * q4 + i]; }
-        *reinterpret_cast<f32x4*>(prow + dt * 32 + 8 * q4 + 4 * kg) = a;
-        *reinterpret_cast<f32x4*>(prow + D + dt * 32 + 8 * q4 + 4 * kg) = c;
-      }
-  } else if (jk < seq) {
-    bf16_t* krow = g.dkv + (ktok0 + jk) * g.lddkv + (size_t)hk * D;
-    bf16_t* vrow = g.dkv + (ktok0 + jk) * g.lddkv + (size_t)(nkv + hk) * D;
-#pragma unroll
-    for (int dt = 0; dt < D / 32; dt++)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; q4++) {
-        bf16x4 a, c;
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-          a[i] = (bf16_t)(dkt[dt][4 * q4 + i] * scale);
-          c[i] = (bf16_t)dvt[dt][4 * q4 + i];
-        }
-        *reinterpret_cast<bf16x4*>(krow + dt * 32 + 8 * q4 + 4 * kg) = a;
-        *reinterpret_cast<bf16x4*>(vrow + dt * 32 + 8 * q4 + 4 * kg) = c;
-      }
+    float* rows = part + ((((size_t)b * nq + hq) * pairs + cm.pair) * 128 + wave * 32) * (2 * D);
+    float* reg = reinterpret_cast<float*>(smem) + wave * (32 * D);
+    wave_rows_out_f32<D>(reg, lane, dk_quad, [&](int r) { return rows + (size_t)r * (2 * D); });
+    __builtin_amdgcn_wave_barrier();
+    wave_rows_out_f32<D>(reg, lane, dv_quad, [&](int r) { return rows + (size_t)r * (2 * D) + D; });
+  } else {
+    bf16_t* reg = reinterpret_cast<bf16_t*>(smem) + wave * (32 * D);
+    wave_rows_out_bf16<D>(reg, lane, dk_quad,
+                          [&](int r) { return jw + r < seq ? g.dkv + (ktok0 + jw + r) * g.lddkv + (size_t)hk * D : nullptr; });
+    __builtin_amdgcn_wave_barrier();
+    wave_rows_out_bf16<D>(reg, lane, dv_quad,
+                          [&](int r) { return jw + r < seq ? g.dkv + (ktok0 + jw + r) * g.lddkv + (size_t)(nkv + hk) * D : nullptr; });
   }
 }
 
