@@ -276,7 +276,11 @@ double dh_segment_cost(const dh_overlap_table* t, const int* seg_f, int n_f, con
 /* Measures the table on the current device: every operator alone and every forward/backward pair
  * co-started on two streams (collective stand-ins on comm_stream).  The strands' buffers must
  * already hold a completed forward (alpha, beta) and backward (beta) so every operator has valid
- * inputs; gradient buffers are added to.  Blocks until done.  reps: timed repetitions (>=1). */
+ * inputs.  The operators run over and over in place: the gradient buffers are added to, and alpha's
+ * saved slot, alpha's out and beta's dx are overwritten (RoPE turns alpha's saved qkv again on every
+ * repetition), so run the strands' forward and backward again before their results are used.  Solo
+ * times have a floor of 0.1 us (an operator that launches nothing), rates lie in [0.02, 1].
+ * Blocks until done.  reps: timed repetitions (>=1). */
 int dh_profile_pairs(dh_layer* layer, const dh_fwd_args* alpha, const dh_bwd_args* beta, void* ws,
                      size_t ws_bytes, void* stream_alpha, void* stream_beta, void* comm_stream,
                      int reps, dh_overlap_table* out);
@@ -402,10 +406,17 @@ void dh_si_graph_destroy(dh_si_graph* graph);
  *                          (Receive side only: the own partial's other slices, which a real
  *                          reduce-scatter sends away, are not touched.)
  *   DH_COMM_ALLGATHER      out = [parts[0] | parts[1] | ...]; out: n_ranks*elems.
+ *   DH_COMM_A2A_DISPATCH,  an expert-parallel all-to-all with equal splits (fixed expert capacity, Sec. 6.1), receive
+ *   DH_COMM_A2A_COMBINE    side: parts[r] = the elems elements rank r sends to this rank, out = [parts[0] | parts[1] | ...].
+ *                          Dispatch and combine move the same payload in opposite directions.  (The layer's dropless
+ *                          routing has data-dependent splits and uses dh_moe_gather_rows with its index maps instead.)
+ * dtype must be DH_F32 or DH_BF16; out and every parts[r] must be 16-byte aligned (DH_ERR_INVALID_ARG otherwise).
  * n_blocks: 256-thread blocks the kernel may use (the analogue of a collective library's
  * channel/thread limit, Sec. 5); 0 = enough to cover the payload (at most 2048).  Enqueued on `stream`.
  * ------------------------------------------------------------------------------------------ */
-typedef enum { DH_COMM_ALLREDUCE = 0, DH_COMM_ALLGATHER = 1, DH_COMM_REDUCESCATTER = 2 } dh_comm_kind;
+typedef enum {
+  DH_COMM_ALLREDUCE = 0, DH_COMM_ALLGATHER = 1, DH_COMM_REDUCESCATTER = 2, DH_COMM_A2A_DISPATCH = 3, DH_COMM_A2A_COMBINE = 4
+} dh_comm_kind;
 int dh_comm_standin(int kind, int n_ranks, const void* const* parts, void* out, size_t elems,
                     int dtype, int n_blocks, void* stream);
 

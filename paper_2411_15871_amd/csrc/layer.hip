@@ -1108,21 +1108,25 @@ extern "C" int dh_profile_pairs(dh_layer* L, const dh_fwd_args* alpha, const dh_
   out->n_fwd = NF;
   out->n_bwd = NB;
   if (L->T == 0) return DH_OK;
-  hipEvent_t e0, e1, e2, e3, gate;
-  DH_HIP(hipEventCreate(&e0));
-  DH_HIP(hipEventCreate(&e1));
-  DH_HIP(hipEventCreate(&e2));
-  DH_HIP(hipEventCreate(&e3));
-  DH_HIP(hipEventCreateWithFlags(&gate, hipEventDisableTiming));
+  hipEvent_t e0 = nullptr, e1 = nullptr, e3 = nullptr, gate = nullptr;
+  auto cleanup = [&]() {
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (e3) (void)hipEventDestroy(e3);
+    if (gate) (void)hipEventDestroy(gate);
+  };
+  {
+    hipError_t he = hipEventCreate(&e0);
+    if (he == hipSuccess) he = hipEventCreate(&e1);
+    if (he == hipSuccess) he = hipEventCreate(&e3);
+    if (he == hipSuccess) he = hipEventCreateWithFlags(&gate, hipEventDisableTiming);
+    if (he != hipSuccess) { cleanup(); return dh_set_error(DH_ERR_HIP, "profile: event creation failed: %s", hipGetErrorString(he)); }
+  }
   auto stream_of = [&](int dir, int op) {
     const int comm = dir == 0 ? L->gf.is_comm[op] : L->gb.is_comm[op];
     hipStream_t cs = comm ? comm_stream_of(L, comm, sc) : nullptr;
     if (cs) return cs;
     return dir == 0 ? sa : sb;
-  };
-  auto cleanup = [&]() {
-    (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); (void)hipEventDestroy(e2); (void)hipEventDestroy(e3);
-    (void)hipEventDestroy(gate);
   };
   // solo times
   for (int dir = 0; dir < 2; dir++) {
@@ -1139,7 +1143,9 @@ extern "C" int dh_profile_pairs(dh_layer* L, const dh_fwd_args* alpha, const dh_
       if (he != hipSuccess) { cleanup(); return dh_set_error(DH_ERR_HIP, "profile: %s", hipGetErrorString(he)); }
       float ms = 0.f;
       (void)hipEventElapsedTime(&ms, e0, e1);
-      (dir == 0 ? out->t_fwd : out->t_bwd)[op] = (double)ms * 1e-3 / reps;
+      // an operator that launches nothing (a Send/Recv stand-in with no peer) measures ~0: floor it, so that the
+      // repeat counts, rates and Eq. 1 below stay finite
+      (dir == 0 ? out->t_fwd : out->t_bwd)[op] = std::max((double)ms * 1e-3 / reps, 1e-7);
     }
   }
   // pairs: both operators repeated so that the two streams stay busy for about the same window
@@ -1147,7 +1153,8 @@ extern "C" int dh_profile_pairs(dh_layer* L, const dh_fwd_args* alpha, const dh_
     for (int j = 0; j < NB; j++) {
       const double ta = out->t_fwd[i], tb = out->t_bwd[j];
       const double window = std::max(ta, tb) * reps;
-      const int ra = std::max(1, (int)std::lround(window / ta)), rb = std::max(1, (int)std::lround(window / tb));
+      const int ra = (int)std::min(64.0 * reps, std::max(1.0, std::round(window / ta)));
+      const int rb = (int)std::min(64.0 * reps, std::max(1.0, std::round(window / tb)));
       hipStream_t s1 = stream_of(0, i), s2 = stream_of(1, j);
       TimedOp A{0, i}, B{1, j};
       double end_a, end_b;

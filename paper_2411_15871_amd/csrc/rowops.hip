@@ -2,6 +2,7 @@
 // bias-dropout-add operator fused in, dropout p = 0), RoPE, SwiGLU, residual add.
 // All are HBM-bound: every tensor is read or written exactly once with 16-byte (bf16) or
 // 2x16-byte (fp32) accesses per thread; reductions are wave/block reductions in registers.
+#include <mutex>
 #include "common.h"
 
 #define ROW_THREADS 256

@@ -42,15 +42,21 @@ __global__ __launch_bounds__(256) void allgather_kernel(PartPtrs parts, int n_ra
 
 extern "C" int dh_comm_standin(int kind, int n_ranks, const void* const* parts, void* out, size_t elems, int dtype,
                                int n_blocks, void* stream) {
-  if (kind != DH_COMM_ALLREDUCE && kind != DH_COMM_ALLGATHER && kind != DH_COMM_REDUCESCATTER)
+  if (kind != DH_COMM_ALLREDUCE && kind != DH_COMM_ALLGATHER && kind != DH_COMM_REDUCESCATTER && kind != DH_COMM_A2A_DISPATCH &&
+      kind != DH_COMM_A2A_COMBINE)
     DH_FAIL(DH_ERR_UNSUPPORTED, "comm_standin: kind %d not supported", kind);
+  if (dtype != DH_F32 && dtype != DH_BF16) DH_FAIL(DH_ERR_INVALID_ARG, "comm_standin: dtype %d", dtype);
+  // an equal-split all-to-all seen from the receiving rank moves what an all-gather moves: one block from every rank
+  if (kind == DH_COMM_A2A_DISPATCH || kind == DH_COMM_A2A_COMBINE) kind = DH_COMM_ALLGATHER;
   if (n_ranks < 1 || n_ranks > DH_MAX_RANKS) DH_FAIL(DH_ERR_INVALID_ARG, "comm_standin: n_ranks %d outside 1..%d", n_ranks, DH_MAX_RANKS);
   if (elems % 8) DH_FAIL(DH_ERR_SHAPE, "comm_standin: element count %zu must be a multiple of 8", elems);
   if (!parts || !out) DH_FAIL(DH_ERR_INVALID_ARG, "comm_standin: null pointer");
+  if ((uintptr_t)out & 15) DH_FAIL(DH_ERR_INVALID_ARG, "comm_standin: out must be 16-byte aligned");
   if (n_blocks < 0 || n_blocks > 65536) DH_FAIL(DH_ERR_INVALID_ARG, "comm_standin: n_blocks %d outside 0..65536", n_blocks);
   PartPtrs pp;
   for (int r = 0; r < n_ranks; r++) {
     if (!parts[r]) DH_FAIL(DH_ERR_INVALID_ARG, "comm_standin: partial %d is null", r);
+    if ((uintptr_t)parts[r] & 15) DH_FAIL(DH_ERR_INVALID_ARG, "comm_standin: partial %d must be 16-byte aligned", r);
     pp.p[r] = parts[r];
   }
   if (elems == 0) return DH_OK;

@@ -24,6 +24,7 @@ DH_ROPE_HALVES, DH_ROPE_ADJACENT = 0, 1
 DH_GELU_TANH, DH_GELU_ERF = 0, 1
 DH_WS_FWD, DH_WS_BWD, DH_WS_SI = 0, 1, 2
 DH_COMM_ALLREDUCE, DH_COMM_ALLGATHER, DH_COMM_REDUCESCATTER = 0, 1, 2
+DH_COMM_A2A_DISPATCH, DH_COMM_A2A_COMBINE = 3, 4
 DH_MAX_OPS, DH_MAX_DEPS = 32, 96
 
 

@@ -54,6 +54,51 @@ def rel(a, b):
     return np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30)
 
 
+# A whole-tensor norm hides a wrong row or a dropped chunk, so every [rows, features] result is also checked row by row,
+# and every weight gradient in blocks of 32 columns: the error norm of a row (block) against that row's (block's) own
+# oracle norm, with a floor at the tensor's root-mean-square row (block) norm so that near-zero rows are measured
+# against the tensor's scale.  bf16 rounding of a stored element is 2^-9 relative, of an intermediate activation a few
+# times that: 3e-2 per row in bf16 mode, 2e-5 in fp32 mode.
+ROW_TOL = {1e-5: 2e-5, 2e-2: 3e-2}
+
+
+def row_err(got, ref):
+    got, ref = np.atleast_2d(got), np.atleast_2d(ref)
+    got, ref = got.reshape(-1, got.shape[-1]), ref.reshape(-1, ref.shape[-1])
+    d, n = np.linalg.norm(got - ref, axis=1), np.linalg.norm(ref, axis=1)
+    floor = max(float(np.sqrt(np.mean(n * n))), 1e-30)
+    return float((d / np.maximum(n, floor)).max())
+
+
+def colblock_err(got, ref, width=32):
+    got, ref = np.atleast_2d(got), np.atleast_2d(ref)
+    got, ref = got.reshape(-1, got.shape[-1]), ref.reshape(-1, ref.shape[-1])
+    edges = list(range(0, got.shape[1], width))
+    d = np.array([np.linalg.norm(got[:, c:c + width] - ref[:, c:c + width]) for c in edges])
+    n = np.array([np.linalg.norm(ref[:, c:c + width]) for c in edges])
+    floor = max(float(np.sqrt(np.mean(n * n))), 1e-30)
+    return float((d / np.maximum(n, floor)).max())
+
+
+class Worst:
+    """Collects (name, whole-tensor error, per-row or per-block error) of a case and prints the largest."""
+
+    def __init__(self, case, tol):
+        self.case, self.tol, self.rows = case, tol, []
+
+    def check(self, name, got, ref, blocks=False):
+        g = rel(got, ref)
+        r = colblock_err(got, ref) if blocks else row_err(got, ref)
+        self.rows.append((name, g, r))
+        assert g <= self.tol, (name, g)
+        assert r <= ROW_TOL[self.tol], (name, "per block" if blocks else "per row", r)
+
+    def report(self):
+        wg, wr = max(self.rows, key=lambda t: t[1]), max(self.rows, key=lambda t: t[2])
+        print("worst errors of %s: whole tensor %.3e (%s), per row/block %.3e (%s)" % (self.case, wg[1], wg[0], wr[2], wr[0]),
+              flush=True)
+
+
 def oracle_run(run, s):
     c = run.cfg
     cfg = R.LayerCfg(batch=c["batch"], seq=c["seq"], H=c["hidden"], nq=c["nq"], nkv=c["nkv"], d=c["d"], F=c["ffn"],
@@ -86,15 +131,19 @@ def oracle_run(run, s):
     return out, dx, grads
 
 
-def check_grads(run, s, grads, tol):
+def check_grads(run, s, grads, tol, worst=None):
+    worst = worst or Worst("-", tol)
     got = run.grads_np()
     assert sorted(got) == sorted(k for k in grads if k not in ("dlogits", "dkv_peers"))
     for k, v in got.items():
-        assert rel(v, grads[k]) <= tol, k
+        if v.ndim >= 2:
+            worst.check(k, v, grads[k], blocks=True)  # weight gradients: per 32-column block
+        else:
+            assert rel(v, grads[k]) <= tol, k         # gain / bias gradients: one row
     if "dlogits" in grads:
-        assert rel(H.to_np(s.dlogits), grads["dlogits"]) <= tol, "dlogits"
+        worst.check("dlogits", H.to_np(s.dlogits), grads["dlogits"])
     if "dkv_peers" in grads:
-        assert rel(H.to_np(s.dkv_peers), grads["dkv_peers"]) <= tol, "dkv_peers"
+        worst.check("dkv_peers", H.to_np(s.dkv_peers), grads["dkv_peers"])
     return got
 
 
@@ -109,9 +158,13 @@ def test_layer_fwd_bwd_matches_oracle(name):
         run.bwd(s)
         torch.cuda.synchronize()
         out, dx, grads = oracle_run(run, s)
-        assert rel(H.to_np(s.out), out) <= tol, "out"
-        assert rel(H.to_np(s.dx), dx) <= tol, "dx"
-        got = check_grads(run, s, grads, tol)
+        worst = Worst(name, tol)
+        try:
+            worst.check("out", H.to_np(s.out), out)
+            worst.check("dx", H.to_np(s.dx), dx)
+            got = check_grads(run, s, grads, tol, worst)
+        finally:
+            worst.report()
         # gradient buffers accumulate: a second backward doubles them
         run.bwd(s)
         torch.cuda.synchronize()
@@ -176,8 +229,13 @@ def test_si_step_bitwise_equals_sequential_and_matches_oracle(name):
         ref = snapshot(run, alpha, beta)
         out_o, _, _ = oracle_run(run, alpha)
         _, dx_o, grads_o = oracle_run(run, beta)
-        assert rel(H.to_np(alpha.out), out_o) <= tol and rel(H.to_np(beta.dx), dx_o) <= tol
-        check_grads(run, beta, grads_o, tol)
+        worst = Worst(name, tol)
+        try:
+            worst.check("out", H.to_np(alpha.out), out_o)
+            worst.check("dx", H.to_np(beta.dx), dx_o)
+            check_grads(run, beta, grads_o, tol, worst)
+        finally:
+            worst.report()
         gf, gb = dh.dh_layer_op_graph(run.layer, 0), dh.dh_layer_op_graph(run.layer, 1)
         nf, nb = gf.n_ops, gb.n_ops
         rng = random.Random(5)

@@ -32,6 +32,19 @@ def rel(a, b):
     return np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30)
 
 
+def row_err(got, ref, width=None):
+    """Largest error norm of a row against the row's own oracle norm, floored at the tensor's root-mean-square row
+    norm (a whole-tensor norm hides one wrong row); width cuts the rows into pieces (one head of a token)."""
+    if width is not None:
+        got, ref = got.reshape(-1, width), ref.reshape(-1, width)
+    d, n = np.linalg.norm(got - ref, axis=1), np.linalg.norm(ref, axis=1)
+    floor = max(float(np.sqrt(np.mean(n * n))), 1e-30)
+    return float((d / np.maximum(n, floor)).max())
+
+
+ROW_TOL = {False: 2e-5, True: 3e-2}  # per row: fp32 storage, bf16 storage
+
+
 def dt(dh, bf16):
     return dh.DH_BF16 if bf16 else dh.DH_F32
 
@@ -66,6 +79,9 @@ def test_rmsnorm_fwd_bwd(dh, bf16, T, H):
     dx_ref, dg_ref = R.rmsnorm_bwd(dy.astype(np.float64), host(x2), g.astype(np.float64), host(rstd)[:, None])
     assert rel(host(dx), dx_ref + dres) <= TOL[bf16]
     assert rel(host(dg) - 0.25, dg_ref) <= TOL[bf16]
+    rows = {"x2": row_err(host(x2), x2_ref), "h": row_err(host(h), h_ref), "dx": row_err(host(dx), dx_ref + dres)}
+    print("rmsnorm T=%d H=%d bf16=%d worst per-row errors %r" % (T, H, bf16, rows), flush=True)
+    assert max(rows.values()) <= ROW_TOL[bf16], rows
     # no residual: x_out untouched path
     h2 = torch.empty_like(xd)
     dh.dh_rmsnorm_fwd(dt(dh, bf16), T, H, xd, None, gd, 1e-5, None, h2, rstd)
@@ -160,12 +176,32 @@ def test_comm_standin_allreduce(dh, bf16, n, R_):
         assert rel(host(out), ref) <= 1e-6
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("kind", ["DH_COMM_A2A_DISPATCH", "DH_COMM_A2A_COMBINE"])
+def test_comm_standin_a2a_equal_split(dh, bf16, kind):
+    n, R_ = 5000 * 8, 8
+    parts = [gen.normal(60 + r, (n,), 1.0, 0.0, bf16) for r in range(R_)]
+    pd = [dev(p, bf16) for p in parts]
+    out = torch.empty(n * R_, dtype=tdtype(bf16), device="cuda")
+    dh.dh_comm_standin(getattr(dh, kind), pd, out, n, dt(dh, bf16), n_blocks=5)
+    assert np.array_equal(host(out), np.concatenate(parts).astype(np.float64))  # a copy: exact
+
+
 def test_comm_standin_errors_and_masked_stream(dh):
     a = torch.zeros(64, device="cuda")
     with pytest.raises(dh.DhelixError):
         dh.dh_comm_standin(dh.DH_COMM_ALLREDUCE, [a], a, 12, dh.DH_F32)
     with pytest.raises(dh.DhelixError):
         dh.dh_comm_standin(5, [a], a, 64, dh.DH_F32)
+    with pytest.raises(dh.DhelixError) as e:  # a dtype outside {DH_F32, DH_BF16} is refused, not run as float32
+        dh.dh_comm_standin(dh.DH_COMM_ALLREDUCE, [a], a, 64, 2)
+    assert e.value.code == dh.DH_ERR_INVALID_ARG
+    with pytest.raises(dh.DhelixError) as e:  # the kernels use 16-byte accesses
+        dh.dh_comm_standin(dh.DH_COMM_ALLREDUCE, [a[1:33]], a, 32, dh.DH_F32)
+    assert e.value.code == dh.DH_ERR_INVALID_ARG
+    with pytest.raises(dh.DhelixError) as e:
+        dh.dh_comm_standin(dh.DH_COMM_ALLREDUCE, [a], a[1:33], 32, dh.DH_F32)
+    assert e.value.code == dh.DH_ERR_INVALID_ARG
     with pytest.raises(dh.DhelixError):
         dh.dh_stream_create_masked(0)
     try:
@@ -292,3 +328,11 @@ def test_attention_fwd_bwd(dh, bf16, batch, seq, nq, nkv, d):
     assert relf(got[:, : nq * d], dq.reshape(T, -1)) <= tol
     assert relf(got[:, nq * d: (nq + nkv) * d], dk.reshape(T, -1)) <= tol
     assert relf(got[:, (nq + nkv) * d:], dv.reshape(T, -1)) <= tol
+    # row by row: one head of one token at a time
+    rows = {"o": row_err(host(o), o_ref.reshape(T, nq * d), d), "o_unsplit": row_err(host(o_ns), o_ref.reshape(T, nq * d), d),
+            "dv": row_err(got[:, (nq + nkv) * d:], dv.reshape(T, -1), d)}
+    if seq > 1:
+        rows["dq"] = row_err(got[:, : nq * d], dq.reshape(T, -1), d)
+        rows["dk"] = row_err(got[:, nq * d: (nq + nkv) * d], dk.reshape(T, -1), d)
+    print("attention %r bf16=%d worst per-row errors %r" % ((batch, seq, nq, nkv, d), bf16, rows), flush=True)
+    assert max(rows.values()) <= ROW_TOL[bf16], rows
