@@ -472,6 +472,16 @@ int dh_rmsnorm_bwd(int dtype, int T, int H, const void* dy, const void* x, const
                    size_t ws_bytes, void* stream);
 size_t dh_rmsnorm_bwd_ws_bytes(int T, int H);
 
+/* dh_rmsnorm_bwd for callers that cannot allocate or carry a workspace: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments and results (bitwise) without ws: the partial rows of the gain
+ * gradient go to a static device array of dh_rmsnorm_bwd_noalloc_max_bytes() (8 MiB) that every GPU the library runs on
+ * holds until the process ends.  The call allocates and frees nothing; dh_rmsnorm_bwd_ws_bytes(T,H) above that limit
+ * returns DH_ERR_WORKSPACE_TOO_SMALL.  All calls on one GPU share the array: calls that overlap on one GPU (two
+ * streams, two threads) race; calls on one stream are safe. */
+int dh_rmsnorm_bwd_noalloc(int dtype, int T, int H, const void* dy, const void* x, const void* gamma,
+                           const float* rstd, const void* dres, void* dx, float* dgamma, void* stream);
+size_t dh_rmsnorm_bwd_noalloc_max_bytes(void);
+
 /* RoPE pair i of a head of d elements: DH_ROPE_HALVES = elements (i, i + d/2), DH_ROPE_ADJACENT = elements
  * (2i, 2i + 1).  Attention does not care (both are the same rotation up to a fixed permutation of the head's
  * elements); what matters is that weights trained with one convention meet the same one. */

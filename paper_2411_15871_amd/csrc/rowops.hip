@@ -354,6 +354,48 @@ extern "C" int dh_rmsnorm_bwd(int dtype, int T, int H, const void* dy, const voi
              : rmsnorm_bwd_t<float>(T, H, dy, x, gamma, rstd, dres, dx, dgamma, (float*)ws, (hipStream_t)stream);
 }
 
+// RMSNorm backward for callers that may not allocate (code under stream capture, serving loops): the per-block partial
+// rows of the gain gradient live in a library-owned static device array instead of a caller workspace.  Every GPU holds
+// its own copy of the array at its own address; the address is looked up once per device, with that device current.
+#define DH_NORM_SCRATCH_BYTES (8u << 20)
+static __device__ __align__(256) float dh_norm_scratch[DH_NORM_SCRATCH_BYTES / sizeof(float)];
+static int norm_scratch_ptr(float** out) {
+  static float* ptr[DH_MAX_DEVICES] = {};
+  static std::mutex mu;
+  int dev = 0;
+  DH_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= DH_MAX_DEVICES) DH_FAIL(DH_ERR_UNSUPPORTED, "rmsnorm_bwd_noalloc: device index %d above %d", dev, DH_MAX_DEVICES - 1);
+  std::lock_guard<std::mutex> lock(mu);
+  if (ptr[dev] == nullptr) {
+    void* p = nullptr;
+    DH_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(dh_norm_scratch)));
+    if (p == nullptr) DH_FAIL(DH_ERR_HIP, "rmsnorm_bwd_noalloc: the scratch array has no device address");
+    ptr[dev] = (float*)p;
+  }
+  *out = ptr[dev];
+  return DH_OK;
+}
+
+extern "C" size_t dh_rmsnorm_bwd_noalloc_max_bytes(void) { return DH_NORM_SCRATCH_BYTES; }
+
+extern "C" int dh_rmsnorm_bwd_noalloc(int dtype, int T, int H, const void* dy, const void* x, const void* gamma,
+                                      const float* rstd, const void* dres, void* dx, float* dgamma, void* stream) {
+  if (T < 0 || H <= 0 || H % 8) DH_FAIL(DH_ERR_SHAPE, "rmsnorm_bwd_noalloc: T=%d H=%d (H must be a positive multiple of 8)", T, H);
+  if (dtype != DH_F32 && dtype != DH_BF16) DH_FAIL(DH_ERR_INVALID_ARG, "rmsnorm_bwd_noalloc: dtype %d", dtype);
+  if (T == 0) return DH_OK;
+  if (!dy || !x || !gamma || !rstd || !dx || !dgamma) DH_FAIL(DH_ERR_INVALID_ARG, "rmsnorm_bwd_noalloc: null pointer");
+  const size_t need = dh_rmsnorm_bwd_ws_bytes(T, H);
+  if (need > DH_NORM_SCRATCH_BYTES)
+    DH_FAIL(DH_ERR_WORKSPACE_TOO_SMALL, "rmsnorm_bwd_noalloc: T=%d H=%d needs %zu bytes of scratch, the static array holds %u", T, H,
+            need, DH_NORM_SCRATCH_BYTES);
+  float* scratch = nullptr;
+  int rc = norm_scratch_ptr(&scratch);
+  if (rc) return rc;
+  // every partial row the finishing kernel reads is written by this call's first kernel: nothing to clear
+  return dtype == DH_BF16 ? rmsnorm_bwd_t<bf16_t>(T, H, dy, x, gamma, rstd, dres, dx, dgamma, scratch, (hipStream_t)stream)
+                          : rmsnorm_bwd_t<float>(T, H, dy, x, gamma, rstd, dres, dx, dgamma, scratch, (hipStream_t)stream);
+}
+
 extern "C" int dh_rope(int dtype, int T, int seq, int n_heads, int head_dim, int row_stride, float base, int inverse,
                        void* t, void* stream) {
   return dh_rope_at(dtype, T, seq, 0, n_heads, head_dim, row_stride, base, inverse, t, stream);

@@ -161,6 +161,8 @@ SIGNATURES = {
     "dh_rmsnorm_fwd": (_I, [_I, _I, _I, _P, _P, _P, _F, _P, _P, _P, _P]),
     "dh_rmsnorm_bwd": (_I, [_I, _I, _I, _P, _P, _P, _P, _P, _P, _P, _P, _Z, _P]),
     "dh_rmsnorm_bwd_ws_bytes": (_Z, [_I, _I]),
+    "dh_rmsnorm_bwd_noalloc": (_I, [_I, _I, _I, _P, _P, _P, _P, _P, _P, _P, _P]),
+    "dh_rmsnorm_bwd_noalloc_max_bytes": (_Z, []),
     "dh_rope": (_I, [_I, _I, _I, _I, _I, _I, _F, _I, _P, _P]),
     "dh_rope_at": (_I, [_I, _I, _I, _I, _I, _I, _I, _F, _I, _P, _P]),
     "dh_rope_pairs": (_I, [_I, _I, _I, _I, _I, _I, _I, _I, _F, _I, _P, _P]),
@@ -512,6 +514,15 @@ def dh_rmsnorm_bwd_ws_bytes(T, H):
 def dh_rmsnorm_bwd(dtype, T, H, dy, x, gamma, rstd, dres, dx, dgamma, ws, ws_bytes, stream=None):
     _check(lib.dh_rmsnorm_bwd(dtype, T, H, _ptr(dy), _ptr(x), _ptr(gamma), _ptr(rstd), _ptr(dres), _ptr(dx),
                               _ptr(dgamma), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def dh_rmsnorm_bwd_noalloc(dtype, T, H, dy, x, gamma, rstd, dres, dx, dgamma, stream=None):
+    _check(lib.dh_rmsnorm_bwd_noalloc(dtype, T, H, _ptr(dy), _ptr(x), _ptr(gamma), _ptr(rstd), _ptr(dres), _ptr(dx),
+                                      _ptr(dgamma), _stream(stream)))
+
+
+def dh_rmsnorm_bwd_noalloc_max_bytes():
+    return lib.dh_rmsnorm_bwd_noalloc_max_bytes()
 
 
 def dh_rope(dtype, T, seq, n_heads, head_dim, row_stride, base, inverse, t, stream=None):
