@@ -242,6 +242,11 @@ typedef struct {
   int dep_dst[DH_MAX_DEPS];
   int side_ok[DH_MAX_OPS];   /* backward graph: 1 = the operator has no dependents and touches no buffer a later operator
                                 of its strand writes, so a plan may run it beside the strand (dh_plan.bwd_side) */
+  int like_other[DH_MAX_OPS]; /* 1 + id of the operator of the OTHER direction's graph that runs the same kernel on the
+                                same amount of data (a backward all-reduce and a forward one; a weight-gradient GEMM and
+                                the forward GEMM of its shape), 0 = none.  The pair profiler co-runs forward with backward
+                                operators only; the lane model (dh_plan_cost) looks up two operators of one direction
+                                through this. */
 } dh_op_graph;
 
 /* Fills the forward (direction 0) or backward (direction 1) operator graph of the layer. */
@@ -316,6 +321,48 @@ int dh_pair_dp(const double* p_f, int n_f, const double* p_b, int n_b, const dou
 int dh_plan_search(const dh_op_graph* fwd, const dh_op_graph* bwd, const dh_overlap_table* table,
                    double barrier_cost, int max_orders, dh_plan* out, double* makespan);
 
+/* Number of topological orders of an operator graph, counted up to `cap` (the count stops there): Sec. 4.2 step (1)
+ * enumerates them all.  dh_plan_search tries every order when there are at most max_orders (default 20000; the Llama
+ * backward graph has 5760); otherwise the first half of the depth-first enumeration plus as many orders drawn by a
+ * seeded generator, so that operators without successors are tried everywhere.  Host only; negative dh_status on bad
+ * arguments. */
+long long dh_plan_count_orders(const dh_op_graph* g, long long cap);
+
+/* Where dh_si_step places the stand-ins, as the lane model needs to know it. */
+typedef struct {
+  int comm_alpha; /* strand alpha's collectives: 0 = in alpha's stream (stream_comm == NULL), 1 = on the communication stream */
+  int comm_beta;  /* strand beta's: 0 = in beta's stream, 1 = on the communication stream shared with alpha's,
+                     2 = on beta's own communication stream (dh_layer_set_beta_comm_stream) */
+  int cross;      /* cross-node transfers (is_comm == 2): 0 = where their strand's collectives go, 1 = on the cross-node stream */
+} dh_lanes;
+
+/* Predicted time of a plan under the lane model: the segment pairs are replayed the way dh_si_step issues them -- the
+ * two strands, the communication stream(s) and the cross-node stream are lanes that run their operators in issue
+ * order; a stand-in on a lane of its own starts behind what its strand has issued and holds up only the operators
+ * that consume its result; bwd_side operators run in alpha's lane -- and integrated as a fluid: every active operator
+ * advances at the product of its profiled pairwise rates against the other active operators (operators of one
+ * direction through like_other, rate 1 where that is 0).  barrier_cost is added per segment pair.  This is P of Eq. 2
+ * for three and more participants (a stand-in beside two compute kernels), which the two-queue dh_segment_cost cannot
+ * express.  Host only; returns seconds, or a negative dh_status cast to double. */
+double dh_plan_cost(const dh_op_graph* fwd, const dh_op_graph* bwd, const dh_overlap_table* table, const dh_plan* plan,
+                    const dh_lanes* lanes, double barrier_cost);
+
+typedef struct {
+  long long orders_fwd_total, orders_bwd_total; /* topological orders of the graphs (counted up to max_orders + 1) */
+  int orders_fwd_tried, orders_bwd_tried;
+  int truncated;                                /* 1 = not every order was tried */
+  int refined;                                  /* order pairs that went through barrier placement */
+} dh_search_info;
+
+/* Plan search under the lane model (Sec. 4.2 with P = dh_plan_cost of a segment pair).  Step 1 ranks every pair of
+ * operator orders (all orders, see dh_plan_count_orders) as one free-running segment pair.  Step 2 takes the 24 best
+ * and 8 spread over the rest, tries the side_ok operators beside their strand (every subset of up to 4), and places
+ * barriers by Eq. 2 over operator prefixes.  Writes the best plan (orders, segment pairs, bwd_side) and its predicted
+ * time; info may be NULL.  Host only, multi-threaded. */
+int dh_plan_search_lanes(const dh_op_graph* fwd, const dh_op_graph* bwd, const dh_overlap_table* table,
+                         const dh_lanes* lanes, double barrier_cost, int max_orders, dh_plan* out, double* makespan,
+                         dh_search_info* info);
+
 /* Checks that a plan's orders are permutations respecting the graphs and that its pairs tile both
  * sequences.  Returns DH_OK or DH_ERR_PLAN_INVALID. */
 int dh_plan_validate(const dh_op_graph* fwd, const dh_op_graph* bwd, const dh_plan* plan);
@@ -341,6 +388,17 @@ int dh_plan_sequential(const dh_layer* layer, dh_plan* out);
 int dh_si_step(dh_layer* layer, const dh_fwd_args* alpha, const dh_bwd_args* beta,
                const dh_plan* plan, void* ws, size_t ws_bytes, void* stream_alpha,
                void* stream_beta, void* stream_comm);
+
+/* A communication stream of strand beta's own for later SI steps of this layer (NULL, the default: beta's collectives
+ * go where alpha's go).  With one shared stream the two strands' collectives run one after the other in issue order;
+ * when a collective costs what a link makes it cost, that order is the step's critical path.  Host only. */
+int dh_layer_set_beta_comm_stream(dh_layer* layer, void* stream_comm_beta);
+
+/* Thread blocks of the layer's collective stand-ins from now on (the layer configuration's comm_blocks): 0 = cover the
+ * payload, n > 0 = n blocks (a link-like rate), -1 = the stand-ins launch nothing (their events and stream
+ * dependencies stay): the step then computes nothing meaningful and serves only to time the schedule without its
+ * communication, T_SI,no-comm of the hidden-communication measure.  Host only. */
+int dh_layer_set_comm_blocks(dh_layer* layer, int comm_blocks);
 
 /* Stream for the cross-node Send/Recv stand-ins of later SI steps of this layer (Sec. 5: computation, local-node
  * and cross-node communication each get a stream); NULL (the default) issues them where the collective stand-ins

@@ -24,6 +24,7 @@ struct dh_layer {
   int q_off, kv_w;  // context parallelism: first position of this rank's chunk; elements of a key/value row
   size_t f_kvrecv, b_dkv;
   hipStream_t cross_stream;
+  hipStream_t beta_comm_stream;  // beta's collectives in SI steps (nullptr: where alpha's go)
   // forward workspace offsets
   size_t f_hs, f_part, f_red, f_xp, f_yg, f_attn, f_attn_bytes, f_gemm, f_gemm_bytes, fwd_bytes;
   // backward workspace offsets
@@ -158,6 +159,40 @@ static void build_graphs(dh_layer* L) {
   }
 }
 
+// like_other: pairs (forward op, backward op) that run the same kernel on the same amount of data.
+static void link_like(dh_op_graph& f, dh_op_graph& b, int fop, int bop) {
+  if (f.like_other[fop] == 0) f.like_other[fop] = bop + 1;
+  if (b.like_other[bop] == 0) b.like_other[bop] = fop + 1;
+}
+static void build_likes(dh_layer* L) {
+  dh_op_graph& f = L->gf;
+  dh_op_graph& b = L->gb;
+  switch (L->c.arch) {
+    case DH_ARCH_LLAMA:
+      link_like(f, b, DH_F_AR1, DH_B_AR3); link_like(f, b, DH_F_AR2, DH_B_AR4);
+      link_like(f, b, DH_F_FC1, DH_B_FC1_WGRAD); link_like(f, b, DH_F_FC2, DH_B_FC2_WGRAD);
+      link_like(f, b, DH_F_PROJ, DH_B_PROJ_WGRAD); link_like(f, b, DH_F_QKV, DH_B_QKV_WGRAD);
+      break;
+    case DH_ARCH_LLAMA_CP:
+      link_like(f, b, DH_CF_AR1, DH_CB_AR3); link_like(f, b, DH_CF_AR2, DH_CB_AR4);
+      link_like(f, b, DH_CF_FC1, DH_CB_FC1_WGRAD); link_like(f, b, DH_CF_FC2, DH_CB_FC2_WGRAD);
+      link_like(f, b, DH_CF_PROJ, DH_CB_PROJ_WGRAD); link_like(f, b, DH_CF_QKV, DH_CB_QKV_WGRAD);
+      link_like(f, b, DH_CF_CP_KV, DH_CB_CP_SEND); link_like(f, b, DH_CF_CP_KV, DH_CB_CP_DKV);
+      break;
+    case DH_ARCH_GPT:
+      link_like(f, b, DH_GF_AG1, DH_GB_AG3); link_like(f, b, DH_GF_AG2, DH_GB_AG4);
+      link_like(f, b, DH_GF_RS1, DH_GB_RS3); link_like(f, b, DH_GF_RS2, DH_GB_RS4);
+      link_like(f, b, DH_GF_FC1, DH_GB_FC1_WGRAD); link_like(f, b, DH_GF_FC2, DH_GB_FC2_WGRAD);
+      link_like(f, b, DH_GF_PROJ, DH_GB_PROJ_WGRAD); link_like(f, b, DH_GF_QKV, DH_GB_QKV_WGRAD);
+      break;
+    default:
+      link_like(f, b, DH_MF_A2A_DISPATCH, DH_MB_A2A_DISPATCH); link_like(f, b, DH_MF_A2A_COMBINE, DH_MB_A2A_COMBINE);
+      link_like(f, b, DH_MF_FC1, DH_MB_FC1_WGRAD); link_like(f, b, DH_MF_FC2, DH_MB_FC2_WGRAD);
+      link_like(f, b, DH_MF_PROJ, DH_MB_PROJ_WGRAD); link_like(f, b, DH_MF_QKV, DH_MB_QKV_WGRAD);
+      break;
+  }
+}
+
 extern "C" int dh_layer_op_graph(const dh_layer* layer, int direction, dh_op_graph* out) {
   if (!layer || !out || (direction != 0 && direction != 1)) DH_FAIL(DH_ERR_INVALID_ARG, "layer_op_graph: bad arguments");
   *out = direction == 0 ? layer->gf : layer->gb;
@@ -208,6 +243,7 @@ extern "C" int dh_layer_create(const dh_layer_config* cfg, dh_layer** out) {
   dh_layer* L = new dh_layer();
   L->c = c;
   L->cross_stream = nullptr;
+  L->beta_comm_stream = nullptr;
   L->q_off = cp ? c.cp_rank * c.seq : 0;
   L->kv_w = 2 * c.n_kv_heads * c.head_dim;
   L->T = c.batch * c.seq;
@@ -302,6 +338,7 @@ extern "C" int dh_layer_create(const dh_layer_config* cfg, dh_layer** out) {
   L->b_gemm = take(cur, gb);
   L->bwd_bytes = cur;
   build_graphs(L);
+  build_likes(L);
   for (int i = 0; i < DH_EVENT_POOL; i++) L->ev[i] = nullptr;
   L->have_events = false;
   L->ev_next = 0;
@@ -341,6 +378,19 @@ extern "C" size_t dh_layer_saved_bytes(const dh_layer* L) { return L ? L->saved_
 extern "C" int dh_layer_set_cross_stream(dh_layer* L, void* stream_cross) {
   if (!L) DH_FAIL(DH_ERR_INVALID_ARG, "layer_set_cross_stream: null layer");
   L->cross_stream = (hipStream_t)stream_cross;
+  return DH_OK;
+}
+
+extern "C" int dh_layer_set_beta_comm_stream(dh_layer* L, void* stream_comm_beta) {
+  if (!L) DH_FAIL(DH_ERR_INVALID_ARG, "layer_set_beta_comm_stream: null layer");
+  L->beta_comm_stream = (hipStream_t)stream_comm_beta;
+  return DH_OK;
+}
+
+extern "C" int dh_layer_set_comm_blocks(dh_layer* L, int comm_blocks) {
+  if (!L) DH_FAIL(DH_ERR_INVALID_ARG, "layer_set_comm_blocks: null layer");
+  if (comm_blocks < -1 || comm_blocks > 65536) DH_FAIL(DH_ERR_INVALID_ARG, "layer_set_comm_blocks: %d outside -1..65536", comm_blocks);
+  L->c.comm_blocks = comm_blocks;
   return DH_OK;
 }
 
@@ -746,6 +796,7 @@ static int moe_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipSt
 }
 
 static int run_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hipStream_t s) {
+  if (L->c.comm_blocks < 0 && L->gf.is_comm[op] != 0) return DH_OK;  // timing without communication: the stand-in launches nothing
   switch (L->c.arch) {
     case DH_ARCH_GPT: return gpt_fwd_op(L, op, a, ws, s);
     case DH_ARCH_MOE: return moe_fwd_op(L, op, a, ws, s);
@@ -754,6 +805,7 @@ static int run_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hipSt
   }
 }
 static int run_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hipStream_t s, char* side_ws = nullptr) {
+  if (L->c.comm_blocks < 0 && L->gb.is_comm[op] != 0) return DH_OK;
   switch (L->c.arch) {
     case DH_ARCH_GPT: return gpt_bwd_op(L, op, b, ws, s);
     case DH_ARCH_MOE: return moe_bwd_op(L, op, b, ws, s, side_ws);
@@ -932,6 +984,7 @@ static int enqueue_si(dh_layer* L, dh_layer* LB, const dh_fwd_args* alpha, const
   char* ws_f = (char*)ws;
   char* ws_b = (char*)ws + L->fwd_bytes;
   const bool two = sb != sa;
+  const hipStream_t scb = sc != nullptr && L->beta_comm_stream != nullptr ? L->beta_comm_stream : sc;  // beta's collectives
   PendingComm pf, pb;
   memset(&pf, 0, sizeof(pf));
   memset(&pb, 0, sizeof(pb));
@@ -962,7 +1015,7 @@ static int enqueue_si(dh_layer* L, dh_layer* LB, const dh_fwd_args* alpha, const
           if ((rc = run_bwd_op(LB, op, *beta, ws_b, sa, ws_f + L->f_gemm))) return rc;
           continue;
         }
-        if (L->gb.is_comm[op]) rc = on_comm_stream(L, sb, comm_stream_of(L, L->gb.is_comm[op], sc), &pb.ev[op], [&](hipStream_t s) { return run_bwd_op(LB, op, *beta, ws_b, s); });
+        if (L->gb.is_comm[op]) rc = on_comm_stream(L, sb, comm_stream_of(L, L->gb.is_comm[op], scb), &pb.ev[op], [&](hipStream_t s) { return run_bwd_op(LB, op, *beta, ws_b, s); });
         else rc = run_bwd_op(LB, op, *beta, ws_b, sb);
         if (rc) return rc;
       }
@@ -1124,7 +1177,8 @@ extern "C" int dh_profile_pairs(dh_layer* L, const dh_fwd_args* alpha, const dh_
   }
   auto stream_of = [&](int dir, int op) {
     const int comm = dir == 0 ? L->gf.is_comm[op] : L->gb.is_comm[op];
-    hipStream_t cs = comm ? comm_stream_of(L, comm, sc) : nullptr;
+    const hipStream_t base = dir == 1 && sc != nullptr && L->beta_comm_stream != nullptr ? L->beta_comm_stream : sc;
+    hipStream_t cs = comm ? comm_stream_of(L, comm, base) : nullptr;
     if (cs) return cs;
     return dir == 0 ? sa : sb;
   };

@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <cstring>
 #include <limits>
+#include <thread>
 #include <vector>
 #include "common.h"
 
@@ -194,6 +195,8 @@ extern "C" int dh_plan_validate(const dh_op_graph* fwd, const dh_op_graph* bwd, 
   return DH_OK;
 }
 
+static void search_orders(const dh_op_graph& g, int cap, std::vector<std::vector<int>>& out, long long* total);
+
 extern "C" int dh_plan_search(const dh_op_graph* fwd, const dh_op_graph* bwd, const dh_overlap_table* table,
                               double barrier_cost, int max_orders, dh_plan* out, double* makespan) {
   if (check_graph(fwd) != DH_OK || check_graph(bwd) != DH_OK || !table || !out || !makespan || barrier_cost < 0)
@@ -202,10 +205,11 @@ extern "C" int dh_plan_search(const dh_op_graph* fwd, const dh_op_graph* bwd, co
   for (int i = 0; i < fwd->n_ops; i++)
     for (int j = 0; j < bwd->n_ops; j++)
       if (!(table->rate_fwd[i][j] > 0.0) || !(table->rate_bwd[i][j] > 0.0)) DH_FAIL(DH_ERR_INVALID_ARG, "plan_search: non-positive rate at (%d,%d)", i, j);
-  if (max_orders <= 0) max_orders = 512;
+  if (max_orders <= 0) max_orders = 20000;  // every order of the layers' graphs (5760 for the Llama backward graph); dh_plan_count_orders tells
   std::vector<std::vector<int>> of, ob;
-  enum_orders(*fwd, max_orders, of);
-  enum_orders(*bwd, max_orders, ob);
+  long long tot_f = 0, tot_b = 0;
+  search_orders(*fwd, max_orders, of, &tot_f);
+  search_orders(*bwd, max_orders, ob, &tot_b);
   if (of.empty() || ob.empty()) DH_FAIL(DH_ERR_PLAN_INVALID, "plan_search: an operator graph has a cycle");
   double best = std::numeric_limits<double>::infinity();
   size_t bi = 0, bj = 0;
@@ -223,6 +227,365 @@ extern "C" int dh_plan_search(const dh_op_graph* fwd, const dh_op_graph* bwd, co
   out->n_pairs = (int)pairs.size();
   for (size_t k = 0; k < pairs.size(); k++) out->pairs[k] = pairs[k];
   *makespan = best;
+  return DH_OK;
+}
+
+// ------------------------------------------------------------------------------------ lane model
+// Cost of a segment pair as dh_si_step runs it.  The two-queue model above knows two participants; the executor has
+// up to five streams ("lanes"): the two strands, a communication stream (shared, or one per strand) and the cross-node
+// stream.  A stand-in issued on another lane than its strand's starts when everything its strand has issued so far
+// is done, and the strand waits for it only before an operator that consumes its result (operator graph) -- so weight
+// gradients overlap their own strand's collective (Sec. 4.2: the movable, "self-overlapping" operators), and an
+// operator flagged bwd_side runs on alpha's lane once beta's operators before it are done.  The model replays exactly
+// that issue logic as a dependency graph over lanes (a lane runs its operators in issue order) and integrates it as a
+// fluid: an active operator advances at the product of the pairwise rates of the table against every other active
+// operator.  Pairs of one direction are not in the table (the profiler co-runs forward with backward operators); they
+// are looked up through the operator of the other direction that runs the same kernel on the same data size
+// (dh_op_graph.like_other), and count as undisturbed (rate 1) when there is none.
+namespace {
+enum { LANE_A = 0, LANE_B = 1, LANE_COMM = 2, LANE_COMM_B = 3, LANE_CROSS = 4, N_LANES = 5 };
+struct Node {
+  int dir, op, lane;
+  double work;
+  int ndep;
+  int dep[4 + DH_MAX_OPS];  // nodes that must have finished (besides the lane's previous node)
+};
+struct LaneSim {
+  const dh_op_graph& gf;
+  const dh_op_graph& gb;
+  const dh_overlap_table& t;
+  dh_lanes lanes;
+  std::vector<Node> nodes;
+  std::vector<int> lane_nodes[N_LANES];
+  LaneSim(const dh_op_graph& f, const dh_op_graph& b, const dh_overlap_table& tab, const dh_lanes& l) : gf(f), gb(b), t(tab), lanes(l) {}
+
+  int comm_lane(int dir, int kind) const {
+    if (kind == 2 && lanes.cross) return LANE_CROSS;
+    if (dir == 0) return lanes.comm_alpha ? LANE_COMM : LANE_A;
+    return lanes.comm_beta == 0 ? LANE_B : lanes.comm_beta == 1 ? LANE_COMM : LANE_COMM_B;
+  }
+  // rate of x while y is active
+  double pair_rate(const Node& x, const Node& y) const {
+    int xd = x.dir, xo = x.op, yd = y.dir, yo = y.op;
+    if (xd == yd) {  // same direction: stand in the like operator of the other direction for one of them
+      const dh_op_graph& g = xd == 0 ? gf : gb;
+      if (g.like_other[yo] > 0) { yd = 1 - yd; yo = g.like_other[yo] - 1; }
+      else if (g.like_other[xo] > 0) { xd = 1 - xd; xo = g.like_other[xo] - 1; }
+      else return 1.0;
+    }
+    return xd == 0 ? t.rate_fwd[xo][yo] : t.rate_bwd[yo][xo];
+  }
+  // Builds the nodes of one segment pair the way dh_si_step issues it (alternating forward and backward operators).
+  void build(const int* fo, int nf, const int* bo, int nb, const int* side) {
+    nodes.clear();
+    for (auto& v : lane_nodes) v.clear();
+    int pend_f[DH_MAX_OPS], pend_b[DH_MAX_OPS];  // node of a stand-in its strand has not waited for yet, or -1
+    for (int i = 0; i < DH_MAX_OPS; i++) pend_f[i] = pend_b[i] = -1;
+    std::vector<int> carry[N_LANES];  // extra dependencies of the next node issued on a lane (stream waits)
+    auto last_of = [&](int lane) { return lane_nodes[lane].empty() ? -1 : lane_nodes[lane].back(); };
+    auto add = [&](int dir, int op, int lane, int extra_dep) {
+      Node n;
+      n.dir = dir; n.op = op; n.lane = lane; n.ndep = 0;
+      n.work = dir == 0 ? t.t_fwd[op] : t.t_bwd[op];
+      for (int d : carry[lane]) n.dep[n.ndep++] = d;
+      carry[lane].clear();
+      if (extra_dep >= 0) n.dep[n.ndep++] = extra_dep;
+      nodes.push_back(n);
+      lane_nodes[lane].push_back((int)nodes.size() - 1);
+      return (int)nodes.size() - 1;
+    };
+    auto wait_inputs = [&](const dh_op_graph& g, int* pend, int op, int lane) {
+      for (int e = 0; e < g.n_deps; e++)
+        if (g.dep_dst[e] == op && pend[g.dep_src[e]] >= 0) { carry[lane].push_back(pend[g.dep_src[e]]); pend[g.dep_src[e]] = -1; }
+    };
+    int fi = 0, bj = 0;
+    while (fi < nf || bj < nb) {
+      if (fi < nf) {
+        const int op = fo[fi++];
+        wait_inputs(gf, pend_f, op, LANE_A);
+        const int lane = gf.is_comm[op] ? comm_lane(0, gf.is_comm[op]) : LANE_A;
+        if (lane != LANE_A) pend_f[op] = add(0, op, lane, last_of(LANE_A));
+        else add(0, op, LANE_A, -1);
+      }
+      if (bj < nb) {
+        const int op = bo[bj++];
+        wait_inputs(gb, pend_b, op, LANE_B);
+        if (side && side[op]) {
+          // beta's lane has taken up its waits (they order the event the side operator starts behind)
+          std::vector<int> deps = carry[LANE_B];
+          const int n = add(1, op, LANE_A, last_of(LANE_B));
+          for (int d : deps) nodes[n].dep[nodes[n].ndep++] = d;
+          continue;
+        }
+        const int lane = gb.is_comm[op] ? comm_lane(1, gb.is_comm[op]) : LANE_B;
+        if (lane != LANE_B) pend_b[op] = add(1, op, lane, last_of(LANE_B));
+        else add(1, op, LANE_B, -1);
+      }
+    }
+  }
+  // Fluid integration; returns the time at which the last node finishes.
+  double run() {
+    const int n = (int)nodes.size();
+    std::vector<double> left(n);
+    std::vector<char> done(n, 0);
+    for (int i = 0; i < n; i++) left[i] = nodes[i].work;
+    size_t head[N_LANES] = {0, 0, 0, 0, 0};
+    double now = 0.0;
+    int remaining = n;
+    while (remaining > 0) {
+      int act[N_LANES], na = 0;
+      for (int l = 0; l < N_LANES; l++) {
+        while (head[l] < lane_nodes[l].size() && done[lane_nodes[l][head[l]]]) head[l]++;
+        if (head[l] >= lane_nodes[l].size()) continue;
+        const int v = lane_nodes[l][head[l]];
+        bool ready = true;
+        for (int d = 0; d < nodes[v].ndep && ready; d++) ready = done[nodes[v].dep[d]];
+        if (ready) act[na++] = v;
+      }
+      if (na == 0) return -1.0;  // cannot happen for a validated plan
+      double rate[N_LANES], dt = std::numeric_limits<double>::infinity();
+      for (int a = 0; a < na; a++) {
+        double r = 1.0;
+        for (int b = 0; b < na; b++)
+          if (b != a) r *= pair_rate(nodes[act[a]], nodes[act[b]]);
+        rate[a] = r;
+        dt = std::min(dt, left[act[a]] / r);
+      }
+      now += dt;
+      for (int a = 0; a < na; a++) {
+        left[act[a]] -= rate[a] * dt;
+        if (left[act[a]] <= 1e-15 * (nodes[act[a]].work + 1e-300) || left[act[a]] / rate[a] <= dt * 1e-12) { done[act[a]] = 1; remaining--; }
+      }
+    }
+    return now;
+  }
+  double segment(const int* fo, int nf, const int* bo, int nb, const int* side) {
+    build(fo, nf, bo, nb, side);
+    return run();
+  }
+};
+
+int check_lanes(const dh_lanes* l) {
+  if (!l || l->comm_alpha < 0 || l->comm_alpha > 1 || l->comm_beta < 0 || l->comm_beta > 2 || l->cross < 0 || l->cross > 1) return DH_ERR_INVALID_ARG;
+  return DH_OK;
+}
+int check_table_for(const dh_op_graph* fwd, const dh_op_graph* bwd, const dh_overlap_table* table) {
+  if (!table || table->n_fwd < fwd->n_ops || table->n_bwd < bwd->n_ops) return DH_ERR_INVALID_ARG;
+  for (int i = 0; i < fwd->n_ops; i++)
+    for (int j = 0; j < bwd->n_ops; j++)
+      if (!(table->rate_fwd[i][j] > 0.0) || !(table->rate_bwd[i][j] > 0.0)) return DH_ERR_INVALID_ARG;
+  for (int i = 0; i < fwd->n_ops; i++) if (fwd->like_other[i] < 0 || fwd->like_other[i] > bwd->n_ops) return DH_ERR_INVALID_ARG;
+  for (int j = 0; j < bwd->n_ops; j++) if (bwd->like_other[j] < 0 || bwd->like_other[j] > fwd->n_ops) return DH_ERR_INVALID_ARG;
+  return DH_OK;
+}
+
+// Barrier placement with the lane model as P: the same recurrence as place_barriers.
+double place_barriers_lanes(LaneSim& sim, const std::vector<int>& sf, const std::vector<int>& sb, const int* side, double barrier,
+                            std::vector<dh_seg_pair>* pairs) {
+  const int nf = (int)sf.size(), nb = (int)sb.size(), W = nb + 1;
+  std::vector<double> T((size_t)(nf + 1) * W, std::numeric_limits<double>::infinity());
+  std::vector<int> from((size_t)(nf + 1) * W, -1);
+  T[0] = 0.0;
+  for (int i = 0; i <= nf; i++)
+    for (int j = 0; j <= nb; j++) {
+      if (i == 0 && j == 0) continue;
+      double best = std::numeric_limits<double>::infinity();
+      int bf = -1;
+      for (int ip = 0; ip <= i; ip++)
+        for (int jp = 0; jp <= j; jp++) {
+          if (ip == i && jp == j) continue;
+          if (T[ip * W + jp] + barrier >= best) continue;  // a segment pair never costs less than nothing
+          const double c = T[ip * W + jp] + sim.segment(sf.data() + ip, i - ip, sb.data() + jp, j - jp, side) + barrier;
+          if (c < best) { best = c; bf = ip * W + jp; }
+        }
+      T[i * W + j] = best;
+      from[i * W + j] = bf;
+    }
+  if (pairs) {
+    pairs->clear();
+    int i = nf, j = nb;
+    while (i > 0 || j > 0) {
+      int f = from[i * W + j], ip = f / W, jp = f % W;
+      pairs->push_back({ip, i, jp, j});
+      i = ip; j = jp;
+    }
+    std::reverse(pairs->begin(), pairs->end());
+  }
+  return T[(size_t)nf * W + nb];
+}
+}  // namespace
+
+extern "C" double dh_plan_cost(const dh_op_graph* fwd, const dh_op_graph* bwd, const dh_overlap_table* table, const dh_plan* plan,
+                               const dh_lanes* lanes, double barrier_cost) {
+  int rc = DH_OK;
+  if (check_graph(fwd) != DH_OK || check_graph(bwd) != DH_OK || check_lanes(lanes) != DH_OK || !plan || barrier_cost < 0) rc = DH_ERR_INVALID_ARG;
+  if (rc == DH_OK) rc = check_table_for(fwd, bwd, table);
+  if (rc != DH_OK) { dh_set_error(rc, "plan_cost: bad graph, table, lanes or plan"); return (double)rc; }
+  if ((rc = dh_plan_validate(fwd, bwd, plan)) != DH_OK) return (double)rc;
+  LaneSim sim(*fwd, *bwd, *table, *lanes);
+  double total = 0.0;
+  for (int k = 0; k < plan->n_pairs; k++) {
+    const dh_seg_pair& p = plan->pairs[k];
+    total += sim.segment(plan->fwd_order + p.f_begin, p.f_end - p.f_begin, plan->bwd_order + p.b_begin, p.b_end - p.b_begin, plan->bwd_side);
+    total += barrier_cost;
+  }
+  return total;
+}
+
+extern "C" long long dh_plan_count_orders(const dh_op_graph* g, long long cap) {
+  if (check_graph(g) != DH_OK || cap <= 0) { dh_set_error(DH_ERR_INVALID_ARG, "plan_count_orders: bad arguments"); return DH_ERR_INVALID_ARG; }
+  const int n = g->n_ops;
+  std::vector<int> indeg(n, 0);
+  std::vector<char> used(n, 0);
+  for (int e = 0; e < g->n_deps; e++) indeg[g->dep_dst[e]]++;
+  long long count = 0;
+  struct Rec {
+    const dh_op_graph& g; long long cap; long long& count; std::vector<int>& indeg; std::vector<char>& used; int depth;
+    void go() {
+      if (count >= cap) return;
+      if (depth == g.n_ops) { count++; return; }
+      for (int v = 0; v < g.n_ops && count < cap; v++) {
+        if (used[v] || indeg[v] != 0) continue;
+        used[v] = 1; depth++;
+        for (int e = 0; e < g.n_deps; e++) if (g.dep_src[e] == v) indeg[g.dep_dst[e]]--;
+        go();
+        for (int e = 0; e < g.n_deps; e++) if (g.dep_src[e] == v) indeg[g.dep_dst[e]]++;
+        depth--; used[v] = 0;
+      }
+    }
+  } rec{*g, cap, count, indeg, used, 0};
+  rec.go();
+  return count;
+}
+
+// Orders of a graph for the search: all of them when there are at most `cap`; otherwise the first cap/2 of the
+// depth-first enumeration plus cap/2 orders drawn by a seeded generator (uniform choice among the ready operators at
+// every step), so that operators without successors are tried in every place and not only at the tail.
+static void search_orders(const dh_op_graph& g, int cap, std::vector<std::vector<int>>& out, long long* total) {
+  const long long count = dh_plan_count_orders(&g, (long long)cap + 1);
+  *total = count;
+  if (count <= cap) { enum_orders(g, cap, out); return; }
+  enum_orders(g, (cap + 1) / 2, out);
+  uint64_t state = 0x9E3779B97F4A7C15ull;
+  auto next = [&]() { state = state * 6364136223846793005ull + 1442695040888963407ull; return (uint32_t)(state >> 33); };
+  const int n = g.n_ops;
+  for (int k = 0; k < cap - (cap + 1) / 2; k++) {
+    std::vector<int> indeg(n, 0), order;
+    std::vector<char> used(n, 0);
+    for (int e = 0; e < g.n_deps; e++) indeg[g.dep_dst[e]]++;
+    for (int step = 0; step < n; step++) {
+      int ready[DH_MAX_OPS], nr = 0;
+      for (int v = 0; v < n; v++) if (!used[v] && indeg[v] == 0) ready[nr++] = v;
+      const int v = ready[next() % nr];
+      used[v] = 1; order.push_back(v);
+      for (int e = 0; e < g.n_deps; e++) if (g.dep_src[e] == v) indeg[g.dep_dst[e]]--;
+    }
+    out.push_back(order);
+  }
+}
+
+extern "C" int dh_plan_search_lanes(const dh_op_graph* fwd, const dh_op_graph* bwd, const dh_overlap_table* table, const dh_lanes* lanes,
+                                    double barrier_cost, int max_orders, dh_plan* out, double* makespan, dh_search_info* info) {
+  if (check_graph(fwd) != DH_OK || check_graph(bwd) != DH_OK || check_lanes(lanes) != DH_OK || !out || !makespan || barrier_cost < 0)
+    DH_FAIL(DH_ERR_INVALID_ARG, "plan_search_lanes: bad arguments");
+  if (check_table_for(fwd, bwd, table) != DH_OK) DH_FAIL(DH_ERR_INVALID_ARG, "plan_search_lanes: table does not fit the graphs or holds a non-positive rate");
+  if (max_orders <= 0) max_orders = 20000;
+  std::vector<std::vector<int>> of, ob;
+  long long tot_f = 0, tot_b = 0;
+  search_orders(*fwd, std::max(1, std::min(max_orders, 64)), of, &tot_f);  // the forward graphs are (nearly) chains
+  search_orders(*bwd, max_orders, ob, &tot_b);
+  if (of.empty() || ob.empty()) DH_FAIL(DH_ERR_PLAN_INVALID, "plan_search_lanes: an operator graph has a cycle");
+  // Step 1: every pair of orders as one free-running segment pair, with no operator beside its strand.
+  struct Cand { double m; int a, b; };
+  std::vector<Cand> cands(of.size() * ob.size());
+  const int zero_side[DH_MAX_OPS] = {0};
+  {
+    const unsigned nt = std::max(1u, std::min(16u, std::thread::hardware_concurrency()));
+    std::vector<std::thread> pool;
+    for (unsigned w = 0; w < nt; w++)
+      pool.emplace_back([&, w]() {
+        LaneSim sim(*fwd, *bwd, *table, *lanes);
+        for (size_t k = w; k < cands.size(); k += nt) {
+          const int a = (int)(k / ob.size()), b = (int)(k % ob.size());
+          cands[k] = {sim.segment(of[a].data(), fwd->n_ops, ob[b].data(), bwd->n_ops, zero_side) + barrier_cost, a, b};
+        }
+      });
+    for (auto& th : pool) th.join();
+  }
+  std::stable_sort(cands.begin(), cands.end(), [](const Cand& x, const Cand& y) { return x.m < y.m; });
+  // Step 2: barrier placement (Eq. 2 over prefixes) on the best orders and on a spread of the rest; for each, the
+  // side_ok operators beside the strand or not (all subsets up to 4 such operators, else none / each alone / all).
+  std::vector<size_t> refine;
+  const size_t n_top = std::min<size_t>(cands.size(), 24), n_spread = std::min<size_t>(cands.size() - n_top, 8);
+  for (size_t k = 0; k < n_top; k++) refine.push_back(k);
+  for (size_t k = 0; k < n_spread; k++) refine.push_back(n_top + (cands.size() - n_top) * k / n_spread);
+  std::vector<int> side_ops;
+  for (int op = 0; op < bwd->n_ops; op++) if (bwd->side_ok[op]) side_ops.push_back(op);
+  std::vector<std::vector<int>> subsets;
+  if (side_ops.size() <= 4) {
+    for (unsigned m = 0; m < (1u << side_ops.size()); m++) {
+      std::vector<int> sset;
+      for (size_t i = 0; i < side_ops.size(); i++) if (m >> i & 1) sset.push_back(side_ops[i]);
+      subsets.push_back(sset);
+    }
+  } else {
+    subsets.push_back({});
+    for (int op : side_ops) subsets.push_back({op});
+    subsets.push_back(side_ops);
+  }
+  struct Best { double m = std::numeric_limits<double>::infinity(); int a = 0, b = 0, subset = 0; bool dp = false; };
+  std::vector<Best> bests(refine.size());
+  {
+    const unsigned nt = std::max(1u, std::min(16u, std::thread::hardware_concurrency()));
+    std::vector<std::thread> pool;
+    for (unsigned w = 0; w < nt; w++)
+      pool.emplace_back([&, w]() {
+        LaneSim sim(*fwd, *bwd, *table, *lanes);
+        for (size_t r = w; r < refine.size(); r += nt) {
+          const Cand& c = cands[refine[r]];
+          Best& bb = bests[r];
+          bb.a = c.a; bb.b = c.b;
+          // first the subsets on the free-running pair, then barrier placement under the best subset
+          for (size_t si = 0; si < subsets.size(); si++) {
+            int side[DH_MAX_OPS] = {0};
+            for (int op : subsets[si]) side[op] = 1;
+            const double m = sim.segment(of[c.a].data(), fwd->n_ops, ob[c.b].data(), bwd->n_ops, side) + barrier_cost;
+            if (m < bb.m) { bb.m = m; bb.subset = (int)si; bb.dp = false; }
+          }
+          int side[DH_MAX_OPS] = {0};
+          for (int op : subsets[bb.subset]) side[op] = 1;
+          const double m = place_barriers_lanes(sim, of[c.a], ob[c.b], side, barrier_cost, nullptr);
+          if (m < bb.m) { bb.m = m; bb.dp = true; }
+        }
+      });
+    for (auto& th : pool) th.join();
+  }
+  size_t win = 0;
+  for (size_t r = 1; r < bests.size(); r++) if (bests[r].m < bests[win].m) win = r;
+  const Best& bw = bests[win];
+  memset(out, 0, sizeof(*out));
+  out->n_fwd = fwd->n_ops;
+  out->n_bwd = bwd->n_ops;
+  for (int i = 0; i < fwd->n_ops; i++) out->fwd_order[i] = of[bw.a][i];
+  for (int j = 0; j < bwd->n_ops; j++) out->bwd_order[j] = ob[bw.b][j];
+  for (int op : subsets[bw.subset]) out->bwd_side[op] = 1;
+  if (bw.dp) {
+    LaneSim sim(*fwd, *bwd, *table, *lanes);
+    std::vector<dh_seg_pair> pairs;
+    place_barriers_lanes(sim, of[bw.a], ob[bw.b], out->bwd_side, barrier_cost, &pairs);
+    out->n_pairs = (int)pairs.size();
+    for (size_t k = 0; k < pairs.size(); k++) out->pairs[k] = pairs[k];
+  } else {
+    out->n_pairs = 1;
+    out->pairs[0] = {0, fwd->n_ops, 0, bwd->n_ops};
+  }
+  *makespan = bw.m;
+  if (info) {
+    info->orders_fwd_total = tot_f; info->orders_bwd_total = tot_b;
+    info->orders_fwd_tried = (int)of.size(); info->orders_bwd_tried = (int)ob.size();
+    info->truncated = (tot_f > (long long)of.size() || tot_b > (long long)ob.size()) ? 1 : 0;
+    info->refined = (int)refine.size();
+  }
   return DH_OK;
 }
 

@@ -73,7 +73,17 @@ class dh_bwd_args(C.Structure):
 
 class dh_op_graph(C.Structure):
     _fields_ = [("n_ops", C.c_int), ("is_comm", C.c_int * DH_MAX_OPS), ("n_deps", C.c_int),
-                ("dep_src", C.c_int * DH_MAX_DEPS), ("dep_dst", C.c_int * DH_MAX_DEPS), ("side_ok", C.c_int * DH_MAX_OPS)]
+                ("dep_src", C.c_int * DH_MAX_DEPS), ("dep_dst", C.c_int * DH_MAX_DEPS), ("side_ok", C.c_int * DH_MAX_OPS),
+                ("like_other", C.c_int * DH_MAX_OPS)]
+
+
+class dh_lanes(C.Structure):
+    _fields_ = [("comm_alpha", C.c_int), ("comm_beta", C.c_int), ("cross", C.c_int)]
+
+
+class dh_search_info(C.Structure):
+    _fields_ = [("orders_fwd_total", C.c_longlong), ("orders_bwd_total", C.c_longlong), ("orders_fwd_tried", C.c_int),
+                ("orders_bwd_tried", C.c_int), ("truncated", C.c_int), ("refined", C.c_int)]
 
 
 class dh_overlap_table(C.Structure):
@@ -135,6 +145,13 @@ SIGNATURES = {
     "dh_plan_search": (_I, [C.POINTER(dh_op_graph), C.POINTER(dh_op_graph), C.POINTER(dh_overlap_table), _D, _I,
                             C.POINTER(dh_plan), C.POINTER(_D)]),
     "dh_plan_validate": (_I, [C.POINTER(dh_op_graph), C.POINTER(dh_op_graph), C.POINTER(dh_plan)]),
+    "dh_plan_count_orders": (C.c_longlong, [C.POINTER(dh_op_graph), C.c_longlong]),
+    "dh_plan_cost": (_D, [C.POINTER(dh_op_graph), C.POINTER(dh_op_graph), C.POINTER(dh_overlap_table), C.POINTER(dh_plan),
+                          C.POINTER(dh_lanes), _D]),
+    "dh_plan_search_lanes": (_I, [C.POINTER(dh_op_graph), C.POINTER(dh_op_graph), C.POINTER(dh_overlap_table),
+                                  C.POINTER(dh_lanes), _D, _I, C.POINTER(dh_plan), C.POINTER(_D), C.POINTER(dh_search_info)]),
+    "dh_layer_set_beta_comm_stream": (_I, [_P, _P]),
+    "dh_layer_set_comm_blocks": (_I, [_P, _I]),
     "dh_plan_round_robin": (_I, [C.POINTER(dh_op_graph), C.POINTER(dh_op_graph), C.POINTER(dh_plan)]),
     "dh_plan_sequential": (_I, [_P, C.POINTER(dh_plan)]),
     "dh_si_step": (_I, [_P, C.POINTER(dh_fwd_args), C.POINTER(dh_bwd_args), C.POINTER(dh_plan), _P, _Z, _P, _P, _P]),
@@ -304,7 +321,8 @@ def make_table(t_fwd, t_bwd, rate_fwd, rate_bwd):
     return t
 
 
-def make_graph(n_ops, deps, comm=(), side_ok=()):
+def make_graph(n_ops, deps, comm=(), side_ok=(), like=None):
+    """like: {op: id of the like operator of the other direction's graph}."""
     g = dh_op_graph()
     g.n_ops = n_ops
     g.n_deps = len(deps)
@@ -314,6 +332,8 @@ def make_graph(n_ops, deps, comm=(), side_ok=()):
         g.is_comm[c] = 1
     for c in side_ok:
         g.side_ok[c] = 1
+    for op, other in (like or {}).items():
+        g.like_other[op] = other + 1
     return g
 
 
@@ -373,6 +393,40 @@ def dh_plan_search(fwd_graph, bwd_graph, table, barrier_cost=0.0, max_orders=0):
     _check(lib.dh_plan_search(C.byref(fwd_graph), C.byref(bwd_graph), C.byref(table), barrier_cost, max_orders,
                               C.byref(p), C.byref(m)))
     return p, m.value
+
+
+def dh_plan_count_orders(graph, cap=1 << 40):
+    r = lib.dh_plan_count_orders(C.byref(graph), cap)
+    if r < 0:
+        raise DhelixError(int(r), dh_last_error())
+    return r
+
+
+def lanes(comm_alpha=0, comm_beta=0, cross=0):
+    return dh_lanes(comm_alpha, comm_beta, cross)
+
+
+def dh_plan_cost(fwd_graph, bwd_graph, table, plan, lane_cfg, barrier_cost=0.0):
+    r = lib.dh_plan_cost(C.byref(fwd_graph), C.byref(bwd_graph), C.byref(table), C.byref(plan), C.byref(lane_cfg), barrier_cost)
+    if r < 0:
+        raise DhelixError(int(r), dh_last_error())
+    return r
+
+
+def dh_plan_search_lanes(fwd_graph, bwd_graph, table, lane_cfg, barrier_cost=0.0, max_orders=0):
+    """Returns (plan, predicted makespan, dh_search_info)."""
+    p, m, info = dh_plan(), C.c_double(), dh_search_info()
+    _check(lib.dh_plan_search_lanes(C.byref(fwd_graph), C.byref(bwd_graph), C.byref(table), C.byref(lane_cfg), barrier_cost,
+                                    max_orders, C.byref(p), C.byref(m), C.byref(info)))
+    return p, m.value, info
+
+
+def dh_layer_set_beta_comm_stream(layer, stream):
+    _check(lib.dh_layer_set_beta_comm_stream(layer, _stream(stream)))
+
+
+def dh_layer_set_comm_blocks(layer, comm_blocks):
+    _check(lib.dh_layer_set_comm_blocks(layer, comm_blocks))
 
 
 def dh_plan_validate(fwd_graph, bwd_graph, plan):

@@ -180,3 +180,110 @@ def test_search_uses_movable_operator():
     assert abs(m - 4.0) < 1e-12     # b0, b1 alone (2.0) + f0 || b2 (2.0), in either order
     tot = sum(t_f) + sum(t_b)
     assert m < tot
+
+
+# ------------------------------------------------------------------ lane model (more than two participants)
+def rand_tab(nf, nb, lo=0.3):
+    t_f = [random.uniform(0.5, 3) for _ in range(nf)]
+    t_b = [random.uniform(0.5, 3) for _ in range(nb)]
+    rf = [[random.uniform(lo, 1.0) for _ in range(nb)] for _ in range(nf)]
+    rb = [[random.uniform(lo, 1.0) for _ in range(nb)] for _ in range(nf)]
+    return t_f, t_b, rf, rb
+
+
+def test_lane_cost_reduces_to_the_two_queue_model():
+    """No stream of its own for any stand-in, nothing beside the strand: two lanes, i.e. segment_cost, whatever the
+    operator graphs and kinds say."""
+    for _ in range(50):
+        t_f, t_b, rf, rb = rand_tab(5, 6)
+        sf = random.sample(range(5), random.randrange(0, 6))
+        sb = random.sample(range(6), random.randrange(0, 7))
+        ref = P.segment_cost(sf, sb, t_f, t_b, rf, rb)
+        got = P.lane_cost(sf, sb, t_f, t_b, rf, rb, deps_f=[(0, 1)], deps_b=[(2, 3)], comm_f={1: 1}, comm_b={2: 1, 4: 2},
+                          lanes=(0, 0, 0))
+        assert abs(got - ref) <= 1e-12 * max(1.0, ref)
+
+
+def test_lane_cost_closed_forms():
+    one = [[1.0] * 4 for _ in range(3)]
+    t_f, t_b = [2.0, 5.0, 1.0], [1.0, 4.0, 3.0, 2.0]
+    # backward strand alone: compute 0, collective 1 (own lane), independent compute 2, consumer 3 of the collective.
+    # The collective starts after op 0; op 2 overlaps it; op 3 waits for both: 1 + max(4, 3) + 2
+    kw = dict(deps_b=[(0, 1), (1, 3)], comm_b={1: 1}, lanes=(0, 1, 0))
+    assert abs(P.lane_cost([], [0, 1, 2, 3], t_f, t_b, one, one, **kw) - (1 + 4 + 2)) < 1e-12
+    # the same with the collective in the strand's own stream: everything in a row
+    assert abs(P.lane_cost([], [0, 1, 2, 3], t_f, t_b, one, one, deps_b=kw["deps_b"], comm_b={1: 1}, lanes=(0, 0, 0)) - 10) < 1e-12
+    # the independent operator issued BEFORE the collective cannot overlap it (streams run in issue order)
+    assert abs(P.lane_cost([], [0, 2, 1, 3], t_f, t_b, one, one, **kw) - (1 + 3 + 4 + 2)) < 1e-12
+    # both strands' collectives on one shared communication stream run one after the other in issue order;
+    # on separate streams they overlap.  forward: compute 0 (2), collective 1 (5), consumer 2 (1);
+    # backward: compute 0 (1), collective 1 (4), consumer 3 (2)
+    f = dict(deps_f=[(0, 1), (1, 2)], comm_f={1: 1}, deps_b=[(0, 1), (1, 3)], comm_b={1: 1})
+    shared = P.lane_cost([0, 1, 2], [0, 1, 3], t_f, t_b, one, one, lanes=(1, 1, 0), **f)
+    # forward collective issued first: starts at 2, ends 7; backward's starts at 7 (its strand was ready at 1), ends 11, consumer 13
+    assert abs(shared - 13.0) < 1e-12
+    apart = P.lane_cost([0, 1, 2], [0, 1, 3], t_f, t_b, one, one, lanes=(1, 2, 0), **f)
+    assert abs(apart - max(2 + 5 + 1, 1 + 4 + 2)) < 1e-12
+    # an operator beside its strand runs in alpha's stream behind beta's issued work: beta 0 (1), side op 2 (3) on alpha
+    # after alpha's op 0 (2) and beta's op 0, beta goes on with op 3 (2) meanwhile
+    side = P.lane_cost([0], [0, 2, 3], t_f, t_b, one, one, side=(2,))
+    assert abs(side - max(2 + 3, 1 + 2)) < 1e-12
+    # slow-down of three participants multiplies: forward compute 0 against backward compute 0 and backward collective 1
+    rf = [[0.5, 0.5, 1, 1]] + [[1.0] * 4] * 2
+    tri = P.lane_cost([0], [1, 0], [4.0, 1, 1], [8.0, 8.0, 1, 1], rf, one, comm_b={1: 1}, lanes=(0, 2, 0))
+    # backward issues op 1 (collective, own lane, 8) then op 0 (compute, 8): both run from t = 0 undisturbed; forward op 0
+    # advances at 0.5 * 0.5: 2 of its 4 units are done at t = 8, the rest runs alone
+    assert abs(tri - 10.0) < 1e-12
+
+
+def brute_force_lanes(jobs_spec, dt=1e-3):
+    """Independent check by time stepping.  jobs_spec: list of (stream, work, after, rate_fn) with rate_fn(k, running)."""
+    left = [w for _, w, _, _ in jobs_spec]
+    done = [False] * len(jobs_spec)
+    t = 0.0
+    while not all(done):
+        running, seen = [], set()
+        for k, (stream, _, after, _) in enumerate(jobs_spec):
+            if done[k] or stream in seen:
+                continue
+            seen.add(stream)                       # the first unfinished job of a stream
+            if all(done[a] for a in after):
+                running.append(k)
+        for k in running:
+            left[k] -= jobs_spec[k][3](k, running) * dt
+        for k in running:
+            if left[k] <= 0:
+                done[k] = True
+        t += dt
+    return t
+
+
+def test_lane_cost_against_time_stepping():
+    """Three lanes, pairwise rates multiplied: the event-driven result against plain time stepping."""
+    for _ in range(6):
+        t_f, t_b, rf, rb = rand_tab(2, 3, lo=0.5)
+        # forward: ops 0, 1 in alpha's stream.  backward: op 0 compute, op 1 collective (own lane, like forward op 1),
+        # op 2 compute independent of the collective
+        like_b = {1: 1}
+        got = P.lane_cost([0, 1], [0, 1, 2], t_f, t_b, rf, rb, deps_b=[(0, 1)], comm_b={1: 1}, lanes=(0, 2, 0), like_b=like_b)
+
+        def rate(k, running):
+            ident = {0: ("f", 0), 1: ("f", 1), 2: ("b", 0), 3: ("b", 1), 4: ("b", 2)}
+            r = 1.0
+            for o in running:
+                if o == k:
+                    continue
+                (xd, xo), (yd, yo) = ident[k], ident[o]
+                if xd == yd:
+                    if yd == "b" and yo in like_b:
+                        yd, yo = "f", like_b[yo]
+                    elif xd == "b" and xo in like_b:
+                        xd, xo = "f", like_b[xo]
+                    else:
+                        continue
+                r *= rf[xo][yo] if xd == "f" else rb[yo][xo]
+            return r
+        spec = [("A", t_f[0], [], rate), ("A", t_f[1], [], rate), ("B", t_b[0], [], rate), ("CB", t_b[1], [2], rate),
+                ("B", t_b[2], [], rate)]
+        ref = brute_force_lanes(spec)
+        assert abs(got - ref) <= 6e-3

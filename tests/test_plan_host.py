@@ -135,3 +135,109 @@ def test_side_operators_are_validated():
         assert e.value.code == dh.DH_ERR_PLAN_INVALID
     q = dh.with_side(ok, ())
     assert list(q.bwd_side) == [0] * dh.DH_MAX_OPS and list(ok.bwd_side)[2] == 1
+
+
+# ------------------------------------------------------------------ lane model and its search
+def rand_case():
+    """Small operator graphs with collectives, a movable operator and like operators; a random table."""
+    nf, nb = 4, 6
+    deps_f = [(0, 1), (1, 2), (2, 3)]                 # chain; op 1 is a collective
+    deps_b = [(0, 1), (1, 2), (2, 3), (0, 4), (2, 5)]  # chain 0-1-2-3 with the collective at 1; 4 and 5 hang off (movable)
+    comm_f, comm_b = {1: 1}, {1: 1}
+    like_f, like_b = {1: 1, 2: 4}, {1: 1, 4: 2}
+    t_f, t_b, rf, rb = rand_table(nf, nb)
+    gf = dh.make_graph(nf, deps_f, comm=comm_f, like=like_f)
+    gb = dh.make_graph(nb, deps_b, comm=comm_b, side_ok=(4, 5), like=like_b)
+    okw = dict(deps_f=deps_f, deps_b=deps_b, comm_f=comm_f, comm_b=comm_b, like_f=like_f, like_b=like_b)
+    return nf, nb, deps_f, deps_b, t_f, t_b, rf, rb, gf, gb, okw
+
+
+def rand_order(n, deps):
+    left, order = set(range(n)), []
+    while left:
+        ready = sorted(v for v in left if all(s not in left for s, d in deps if d == v))
+        v = random.choice(ready)
+        order.append(v)
+        left.remove(v)
+    return order
+
+
+def test_plan_cost_matches_oracle_lane_model():
+    for _ in range(30):
+        nf, nb, deps_f, deps_b, t_f, t_b, rf, rb, gf, gb, okw = rand_case()
+        tab = dh.make_table(t_f, t_b, rf, rb)
+        fo, bo = rand_order(nf, deps_f), rand_order(nb, deps_b)
+        cut_f, cut_b = random.randrange(nf + 1), random.randrange(nb + 1)
+        pairs = [q for q in [(0, cut_f, 0, cut_b), (cut_f, nf, cut_b, nb)] if q[0] != q[1] or q[2] != q[3]]
+        side = tuple(op for op in (4, 5) if random.random() < 0.5)
+        plan = dh.make_plan(fo, bo, pairs, side)
+        for lanes in [(0, 0, 0), (1, 1, 0), (1, 2, 0), (0, 2, 0)]:
+            got = dh.dh_plan_cost(gf, gb, tab, plan, dh.lanes(*lanes), 0.01)
+            ref = P.plan_cost_lanes(pairs, fo, bo, t_f, t_b, rf, rb, 0.01, lanes=lanes, side=side, **okw)
+            assert abs(got - ref) <= 1e-11 * max(1.0, ref), (lanes, fo, bo, pairs, side)
+    with pytest.raises(dh.DhelixError):
+        dh.dh_plan_cost(gf, gb, tab, plan, dh.lanes(3, 0, 0), 0.0)
+
+
+def test_plan_search_lanes_matches_brute_force_and_moves_the_weight_gradient():
+    # brute force over all orders, side subsets and barrier placements with the oracle's lane model
+    for trial in range(2):
+        nf, nb, deps_f, deps_b, t_f, t_b, rf, rb, gf, gb, okw = rand_case()
+        tab = dh.make_table(t_f, t_b, rf, rb)
+        lanes = (1, 2, 0)
+        plan, mk, info = dh.dh_plan_search_lanes(gf, gb, tab, dh.lanes(*lanes), 0.02, 0)
+        assert info.truncated == 0 and info.orders_bwd_total == dh.dh_plan_count_orders(gb) == len(P.topo_orders(nb, deps_b))
+        dh.dh_plan_validate(gf, gb, plan)
+        fo, bo, pairs = dh.plan_to_py(plan)
+        side = tuple(op for op in range(nb) if plan.bwd_side[op])
+        again = P.plan_cost_lanes(pairs, fo, bo, t_f, t_b, rf, rb, 0.02, lanes=lanes, side=side, **okw)
+        assert abs(again - mk) <= 1e-11 * max(1.0, mk)          # the reported time is the plan's time
+        assert abs(dh.dh_plan_cost(gf, gb, tab, plan, dh.lanes(*lanes), 0.02) - mk) <= 1e-11 * max(1.0, mk)
+        best = min(P.search_cuts_lanes(of, ob, t_f, t_b, rf, rb, 0.02, lanes=lanes, side=sd, **okw)[0]
+                   for of in P.topo_orders(nf, deps_f) for ob in P.topo_orders(nb, deps_b)
+                   for sd in [(), (4,), (5,), (4, 5)])
+        assert mk >= best - 1e-11          # never better than the exhaustive optimum ...
+        assert mk <= best * 1.03 + 1e-12   # ... and, on graphs this small, within the refinement's reach of it
+    # a table on which the movable operator 4 (like the forward GEMM 2) pairs well only with the strand's own collective:
+    # every forward operator halves it, the collective leaves it alone -> the search must issue it right after the collective
+    nf, nb, deps_f, deps_b, _, _, _, _, gf, gb, okw = rand_case()
+    t_f, t_b = [1.0] * nf, [1.0, 4.0, 1.0, 1.0, 4.0, 0.1]
+    rf = [[1.0] * nb for _ in range(nf)]
+    rb = [[1.0] * nb for _ in range(nf)]
+    for i in range(nf):
+        rb[i][4] = 0.25                       # operator 4 crawls beside any forward operator ...
+    rb[1][4] = 1.0                            # ... except beside a collective (forward collective 1 is the like of backward 1)
+    rf[2][1] = 1.0
+    tab = dh.make_table(t_f, t_b, rf, rb)
+    plan, mk, _ = dh.dh_plan_search_lanes(gf, gb, tab, dh.lanes(0, 2, 0), 0.0, 0)
+    fo, bo, pairs = dh.plan_to_py(plan)
+    assert bo.index(4) > bo.index(1) and bo.index(4) < bo.index(2)  # after the collective is issued, before its consumer
+    default = dh.make_plan(list(range(nf)), list(range(nb)), [(0, nf, 0, nb)])
+    assert mk < dh.dh_plan_cost(gf, gb, tab, default, dh.lanes(0, 2, 0), 0.0) - 0.5
+
+
+def test_count_orders_and_full_enumeration():
+    L = dh.dh_layer_create(arch=0, dtype=0, batch=1, seq=16, hidden=64, n_q_heads=2, n_kv_heads=1, head_dim=16, ffn=32,
+                           eps=1e-5, rope_base=1e4, n_ranks=2)
+    try:
+        gf, gb = dh.dh_layer_op_graph(L, 0), dh.dh_layer_op_graph(L, 1)
+        assert dh.dh_plan_count_orders(gf) == 1 and dh.dh_plan_count_orders(gb) == 5760
+        assert dh.dh_plan_count_orders(gb, 100) == 100       # counting stops at the cap
+        # like operators: the backward all-reduces and weight gradients name their forward counterparts
+        assert gb.like_other[dh.BWD_OPS.index("B_AR3")] == dh.FWD_OPS.index("F_AR1") + 1
+        assert gb.like_other[dh.BWD_OPS.index("B_FC1_WGRAD")] == dh.FWD_OPS.index("F_FC1") + 1
+        assert gb.like_other[dh.BWD_OPS.index("B_ATTN")] == 0
+        # a table where the down-projection weight gradient pairs well only late (beside the last forward operators):
+        # the search must move it there -- with the enumeration cut to the first orders it could not
+        nf, nb = gf.n_ops, gb.n_ops
+        w = dh.BWD_OPS.index("B_FC2_WGRAD")
+        rf = [[0.5] * nb for _ in range(nf)]
+        rb = [[0.5] * nb for _ in range(nf)]
+        for i in (nf - 2, nf - 1):
+            rf[i][w] = rb[i][w] = 1.0
+        tab = dh.make_table([1.0] * nf, [1.0] * nb, rf, rb)
+        plan, mk = dh.dh_plan_search(gf, gb, tab, 0.3, 0)   # (barriers cost something: aligning by barriers alone loses)
+        bo = dh.plan_to_py(plan)[1]
+        assert bo.index(w) >= 8, bo
+    finally:
+        dh.dh_layer_destroy(L)
