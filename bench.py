@@ -5,8 +5,11 @@
 
 A step = one dh_si_step over one micro-batch per strand with all inputs resident in HBM.  Prints one
 JSON line: model TFLOP/s of the step (2MNK per GEMM, causal attention at half dense, backward =
-2x forward), SI speedup over sequential alpha-then-beta through the same executor, the fraction of
-collective stand-in time hidden, the roofline of the dominant kernel and the CPU oracle baseline.
+2x forward; the step time is the median of per-step event times), SI speedup over sequential
+alpha-then-beta through the same executor, the share of the collective stand-ins' time that is hidden
+(1 - (T_SI - T_SI without communication) / sum of the stand-ins' solo times), the same again with the
+stand-ins at a link-like rate (`link_rate`), predicted against measured step time, the roofline of
+every operator and of the one with the largest share of the solo time, and the CPU oracle baseline.
 """
 import argparse
 import json
@@ -17,12 +20,74 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
+# The step uses up to five streams at once (two strands, a communication stream per strand, the cross-node stream).  The
+# HIP runtime spreads a process's streams over GPU_MAX_HW_QUEUES hardware queues (4 unless told otherwise) and two streams
+# on one queue run one after the other; eight queues give every stream its own.  Read when the runtime starts.
+if int(os.environ.get("GPU_MAX_HW_QUEUES", "0") or 0) < 8:
+    os.environ["GPU_MAX_HW_QUEUES"] = "8"
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
-# HBM bytes per launch of the dominant GEMM from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (scaled by a copy kernel of
-# known size: `bench.py --traffic-probe`); the summary with the commands is profiles/gemm_gateup_c2_hbm_traffic.txt.
-# Re-measure when the GEMM changes.
-HBM_TRAFFIC_BYTES = {"c2_llama8b_tp8": (176.3 + 28.3) * 2 ** 20}
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E
+# kernels behind an operator name (for the roofline's description)
+OP_KERNELS = {"ATTN": "attention kernels and their merge launches", "FC1": "gemm_bf16_kernel", "FC2": "gemm_bf16_kernel",
+              "QKV": "gemm_bf16_kernel", "PROJ": "gemm_bf16_kernel"}
+
+
+def read_traffic(workload, op):
+    """HBM bytes per launch of an operator from profiles/roofline_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+    scaled by a copy kernel of known size; the file names its sources).  None if the file has no line for it."""
+    path = os.path.join(ROOT, "profiles", "roofline_traffic.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) >= 3 and f[0] == workload and f[1] == op:
+                return float(f[2])
+    except OSError:
+        pass
+    return None
+
+
+def op_work(cfg, name):
+    """Algorithmic work of one launch of an operator: ("mfma", flops) for the dense contractions (2MNK; causal attention at
+    half the dense count, backward twice the forward), ("hbm", bytes) for the memory-bound operators (every operand read
+    once, every result written once).  None for operators without a formula here."""
+    arch = cfg["arch"]
+    T, Hd, nq, nkv, d, F = cfg["batch"] * cfg["seq"], cfg["hidden"], cfg["nq"], cfg["nkv"], cfg["d"], cfg["ffn"]
+    es = 2 if cfg["bf16"] else 4
+    nqkv, no, R = (nq + 2 * nkv) * d, nq * d, cfg["n_ranks"]
+    Tf = 2 * T if arch == "moe" else T                 # rows entering the FFN GEMMs
+    Fin = F if arch == "gpt" else 2 * F
+    Ts = T // R if arch == "gpt" else T
+    attn = 0.5 * 4.0 * cfg["batch"] * cfg["seq"] ** 2 * d * nq
+    if arch == "llama_cp":
+        attn += 4.0 * cfg["batch"] * cfg["seq"] ** 2 * cfg["cp_rank"] * d * nq
+    direction, op = name.split("_", 1)
+    gemm = {"QKV": 2.0 * T * Hd * nqkv, "PROJ": 2.0 * T * Hd * no, "FC1": 2.0 * Tf * Hd * Fin, "FC2": 2.0 * Tf * Hd * F}
+    for k, v in gemm.items():
+        if op in (k, k + "_DGRAD", k + "_WGRAD"):
+            return "mfma", v
+    if op == "ATTN":
+        return "mfma", attn * (2.0 if direction == "B" else 1.0)
+    row = Ts * Hd * es
+    if op in ("AR1", "AR2", "AR3", "AR4"):
+        return "hbm", (R + 1.0) * T * Hd * es
+    if op in ("RS1", "RS2", "RS3", "RS4"):
+        return "hbm", (R + 1.0) * row
+    if op in ("AG1", "AG2", "AG3", "AG4"):
+        return "hbm", 2.0 * T * Hd * es
+    if op in ("A2A_DISPATCH", "A2A_COMBINE", "PERMUTE") and arch == "moe":
+        return "hbm", 2.0 * Tf * Hd * es
+    if op == "NORM1":
+        return "hbm", (2.0 if direction == "F" else 4.0) * row
+    if op == "NORM2":
+        return "hbm", 4.0 * row
+    if op == "ROPE":
+        return "hbm", 2.0 * T * (nq + nkv) * d * es
+    if op == "ACT":
+        return "hbm", Tf * es * ((Fin + F) if direction == "F" else (Fin + F + Fin))
+    if op == "BDA2":
+        return "hbm", 3.0 * row
+    return None
 
 
 def log(*a):
@@ -202,13 +267,18 @@ def main():
     ap.add_argument("--workload", default="c2_llama8b_tp8")
     ap.add_argument("--comm-blocks", type=int, default=0, help="thread blocks per collective stand-in (0 = cover payload)")
     ap.add_argument("--cross-blocks", type=int, default=0, help="thread blocks per cross-node Send/Recv stand-in (0 = 8, about one 400 Gb/s port)")
-    ap.add_argument("--profile-reps", type=int, default=3)
+    ap.add_argument("--profile-reps", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", type=int, default=0, help="stack this many layers: alpha sweeps forward while beta sweeps backward")
     ap.add_argument("--traffic-probe", action="store_true", help="only launch a calibration copy and the dominant GEMM (for rocprofv3 --pmc)")
     ap.add_argument("--sequential-probe", action="store_true",
                     help="only run alpha's forward then beta's backward, one kernel at a time, --steps times (for rocprofv3: every kernel's solo "
                          "duration and counters at the workload's shapes)")
+    ap.add_argument("--link-blocks", type=int, default=64,
+                    help="thread blocks per stand-in of the second, link-rate regime (0 = skip it)")
+    ap.add_argument("--barrier-cost", type=float, default=5e-6, help="seconds a cross-strand barrier is priced at in the plan search")
+    ap.add_argument("--plan-table", default=None, metavar="PATH",
+                    help="also write the predicted-vs-measured table of the plan candidates to this text file")
     ap.add_argument("--pair-table", default=None, metavar="PATH",
                     help="also write the measured operator-pair table (solo times, co-run rates, Eq. 1 overlap factors) to this text file")
     args = ap.parse_args()
@@ -268,186 +338,219 @@ def main():
         print("sequential probe: %d x (forward of one strand, backward of the other), workload %s" % (args.steps, args.workload))
         run.close()
         return
-    sa, sb, sc = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    sa, sb, sc, scb = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
     sx = None
     if cfg["arch"] == "llama_cp":  # Sec. 5: cross-node transfers get a stream of their own
         sx = torch.cuda.Stream()
         dh.dh_layer_set_cross_stream(run.layer, sx)
-
-    # offline part of the method: pairwise profiling and plan search (Sec. 3.2, 4.2)
-    t0 = time.perf_counter()
-    table = dh.dh_profile_pairs(run.layer, alpha.fwd_args, beta.bwd_args, run.ws, run.ws_bytes, sa, sb, sc, args.profile_reps)
-    t_prof = time.perf_counter() - t0
     gf, gb = dh.dh_layer_op_graph(run.layer, 0), dh.dh_layer_op_graph(run.layer, 1)
-    t0 = time.perf_counter()
-    plan, predicted = dh.dh_plan_search(gf, gb, table, 5e-6, 256)
-    t_search = time.perf_counter() - t0
-    fo, bo, pairs = dh.plan_to_py(plan)
-    t_f = [table.t_fwd[i] for i in range(gf.n_ops)]
-    t_b = [table.t_bwd[j] for j in range(gb.n_ops)]
-    log("profile %.2fs, search %.2fs, predicted makespan %.1f us, sum solo %.1f us" % (t_prof, t_search, predicted * 1e6, (sum(t_f) + sum(t_b)) * 1e6))
-    fnames, bnames = dh.op_names(H.ARCH[cfg["arch"]], 0), dh.op_names(H.ARCH[cfg["arch"]], 1)
-    log("fwd solo us:", {fnames[i]: round(t_f[i] * 1e6, 1) for i in range(gf.n_ops)})
-    log("bwd solo us:", {bnames[j]: round(t_b[j] * 1e6, 1) for j in range(gb.n_ops)})
-    log("plan:", [([fnames[o] for o in fo[a:b]], [bnames[o] for o in bo[c:d]]) for a, b, c, d in pairs])
-    if args.pair_table:
-        write_pair_table(args.pair_table, args, table, fnames, bnames, t_f, t_b)
-
     nf, nb = gf.n_ops, gb.n_ops
+    fnames, bnames = dh.op_names(H.ARCH[cfg["arch"]], 0), dh.op_names(H.ARCH[cfg["arch"]], 1)
     seq_plan = dh.dh_plan_sequential(run.layer)
     free_plan = dh.make_plan(list(seq_plan.fwd_order[:nf]), list(seq_plan.bwd_order[:nb]), [(0, nf, 0, nb)])
-    # Last offline step: the cost model ranks plans, measurement picks among its best few.  Candidates: the searched
-    # plan at several barrier prices (dearer barriers -> fewer, longer segment pairs), each also with its operator orders
-    # kept but all barriers dropped, and the default orders without barriers.
-    cands, seen = [("default order, one pair", free_plan)], {dh.plan_to_py(free_plan).__repr__()}
-    for bc in (0.0, 3e-7, 1e-6, 2.5e-6, 5e-6, 1.5e-5, 3e-5, 6e-5, 2e-4):
-        p_bc, _ = dh.dh_plan_search(gf, gb, table, bc, 512)
-        fo_c, bo_c, pairs_c = dh.plan_to_py(p_bc)
-        for name, q in (("searched, barrier %.1e, %d pairs" % (bc, len(pairs_c)), p_bc),
-                        ("searched orders (barrier %.1e), one pair" % bc, dh.make_plan(fo_c, bo_c, [(0, nf, 0, nb)]))):
-            key = dh.plan_to_py(q).__repr__()
-            if key not in seen:  # different barrier prices often give the same plan
-                seen.add(key)
-                cands.append((name, q))
-    # Transfers that wait for nothing (the context-parallel key/value exchange) can start the step: the same candidates
-    # again with such operators moved to the front of the forward order.
-    free_comm = [op for op in range(nf) if gf.is_comm[op] and not any(gf.dep_dst[e] == op for e in range(gf.n_deps))]
-    if free_comm:
-        for name, q in list(cands):
-            fo_c, bo_c, pairs_c = dh.plan_to_py(q)
-            if len(pairs_c) != 1:
-                continue  # segment boundaries are positions in the order: only hoist in single-pair plans
-            hoisted = free_comm + [op for op in fo_c if op not in free_comm]
-            cands.append((name + ", exchange first", dh.make_plan(hoisted, bo_c, pairs_c)))
-    # Where the collective stand-ins go is part of the schedule too: on one shared communication stream (their order
-    # there is the host's issue order, so a strand's collective can wait behind the other strand's) or each in its own
-    # strand's stream.
-    probe_steps = max(5, args.steps // 5)
-    sc_stream = sc
-    timed = [(time_steps(lambda p=p, c=c: run.si_step(alpha, beta, p, sa, sb, c), probe_steps, 2, torch), name, p, c)
-             for name, p in cands for c in (sc_stream, None)]
-    for t, name, _, c in timed:
-        log("  candidate %-48s stand-ins on %-20s %.1f us" % (name, "the comm stream" if c is not None else "strand streams", t * 1e6))
-    t_best, best_name, best_plan, sc = min(timed, key=lambda x: x[0])
-    comm_placement = "communication stream" if sc is not None else "strand streams"
-    # Weight-gradient operators may run beside the backward strand (on the forward strand's stream, which is the
-    # shorter one): try a few subsets on the chosen plan.
-    side_ok = sorted((op for op in range(nb) if gb.side_ok[op]), key=lambda o: -t_b[o])
-    in_strand_plan, side_ops = best_plan, []
-    for label, ops in (("all", side_ok), ("two largest", side_ok[:2]), ("largest", side_ok[:1]), ("all but the largest", side_ok[1:])):
-        if not ops:
-            continue
-        q = dh.with_side(in_strand_plan, ops)
-        t = time_steps(lambda q=q: run.si_step(alpha, beta, q, sa, sb, sc), probe_steps, 2, torch)
-        log("  weight gradients beside the strand (%s: %s): %.1f us" % (label, [bnames[o] for o in ops], t * 1e6))
-        if t < t_best:
-            t_best, best_plan, side_ops = t, q, ops
-    if side_ops:
-        best_name += ", beside the strand: " + "+".join(bnames[o] for o in side_ops)
-    fo, bo, pairs = dh.plan_to_py(best_plan)
-    log("chosen plan:", best_name, [([fnames[o] for o in fo[a:b]], [bnames[o] for o in bo[c:d]]) for a, b, c, d in pairs])
-    t_seq = time_steps(lambda: run.si_step(alpha, beta, seq_plan, sa, sb, sc), args.steps, args.warmup, torch)
-    t_free = time_steps(lambda: run.si_step(alpha, beta, free_plan, sa, sb, sc), args.steps, args.warmup, torch)
-    t_si = time_steps(lambda: run.si_step(alpha, beta, best_plan, sa, sb, sc), args.steps, args.warmup, torch)
-    t_in_strand = time_steps(lambda: run.si_step(alpha, beta, in_strand_plan, sa, sb, sc), probe_steps, 2, torch) if side_ops else t_si
-    # ablations of Sec. 6.1 / 6.4 through the same executor: round-robin interleaving ("Wavelet+"), and the searched plan
-    # with the weight-gradient operators left in their default places
+    # where the stand-ins go is part of the schedule (Sec. 5: one stream per kind of work): in their strand's stream, on
+    # one communication stream, or on a communication stream per strand
+    placements = {"strand streams": (dh.lanes(0, 0, 1 if sx else 0), None, None),
+                  "one communication stream": (dh.lanes(1, 1, 1 if sx else 0), sc, None),
+                  "a communication stream per strand": (dh.lanes(1, 2, 1 if sx else 0), sc, scb)}
+
+    def describe(plan):
+        fo, bo, pairs = dh.plan_to_py(plan)
+        side = [bnames[o] for o in range(nb) if plan.bwd_side[o]]
+        return [([fnames[o] for o in fo[a:b]], [bnames[o] for o in bo[c:d]]) for a, b, c, d in pairs], side
+
+    def event_times(fn, steps, warmup):
+        """Per-step durations from events recorded between consecutive steps on strand alpha's stream (every step forks
+        from that stream and joins it)."""
+        for _ in range(warmup):
+            fn()
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        marks[0].record(sa)
+        for i in range(steps):
+            fn()
+            marks[i + 1].record(sa)
+        torch.cuda.synchronize()
+        return sorted(marks[i].elapsed_time(marks[i + 1]) * 1e-3 for i in range(steps))
+
+    def median(v):
+        return v[len(v) // 2]
+
+    def regime(label, comm_blocks, steps, warmup, table_path=None):
+        """Offline part of the method (Sec. 3.2, 4.2) and the timed step, with the stand-ins at one cost."""
+        dh.dh_layer_set_comm_blocks(run.layer, comm_blocks)
+        dh.dh_layer_set_beta_comm_stream(run.layer, scb)   # the profile co-runs the two strands' collectives on two streams
+        t0 = time.perf_counter()
+        table = dh.dh_profile_pairs(run.layer, alpha.fwd_args, beta.bwd_args, run.ws, run.ws_bytes, sa, sb, sc, args.profile_reps)
+        t_prof = time.perf_counter() - t0
+        t_f = [table.t_fwd[i] for i in range(nf)]
+        t_b = [table.t_bwd[j] for j in range(nb)]
+        t_comm = sum(t_f[i] for i in range(nf) if gf.is_comm[i]) + sum(t_b[j] for j in range(nb) if gb.is_comm[j])
+        log("[%s] profile %.2fs; sum of solo times %.1f us, of which stand-ins %.1f us" % (label, t_prof, (sum(t_f) + sum(t_b)) * 1e6, t_comm * 1e6))
+        log("[%s] fwd solo us:" % label, {fnames[i]: round(t_f[i] * 1e6, 1) for i in range(nf)})
+        log("[%s] bwd solo us:" % label, {bnames[j]: round(t_b[j] * 1e6, 1) for j in range(nb)})
+        if args.pair_table:
+            write_pair_table(args.pair_table if label == "default" else args.pair_table + "." + label.replace(" ", "_"), args, table,
+                             fnames, bnames, t_f, t_b)
+        rows = []   # (name, placement, predicted, measured, plan)
+        probe = max(15, steps // 3)
+
+        def measure(plan, placement):
+            lanes, c, cb = placements[placement]
+            dh.dh_layer_set_beta_comm_stream(run.layer, cb)
+            return median(event_times(lambda: run.si_step(alpha, beta, plan, sa, sb, c), probe, 6))
+        t0 = time.perf_counter()
+        for placement, (lanes, c, cb) in placements.items():
+            plan, predicted, info = dh.dh_plan_search_lanes(gf, gb, table, lanes, args.barrier_cost, 0)
+            rows.append(["searched", placement, predicted, None, plan, info])
+            for name, q in (("default orders, one pair", free_plan), ("sequential", seq_plan)):
+                rows.append([name, placement, dh.dh_plan_cost(gf, gb, table, q, lanes, args.barrier_cost), None, q, None])
+        t_search = time.perf_counter() - t0
+        info = rows[0][5]
+        log("[%s] search %.2fs over %d x %d operator orders (%s), %d refined by barrier placement" %
+            (label, t_search, info.orders_fwd_tried, info.orders_bwd_tried, "truncated" if info.truncated else "all of them", info.refined))
+        for r in rows:
+            r[3] = measure(r[4], r[1])
+        # Every plan that runs comes from dh_plan_search_lanes, one per placement of the stand-ins; which of the three
+        # placements to use is a property of the machine (how its queues and caches take a third and fourth stream) that
+        # the pairwise table does not hold, so that one choice is made by measurement.  The other rows are measured too,
+        # so that the table shows what the model is worth.
+        searched = [r for r in rows if r[0] == "searched"]
+        best = min(searched, key=lambda r: r[3])
+        lines = ["predicted (lane model) vs measured step time, workload %s, stand-ins on %s blocks" % (args.workload, comm_blocks or "payload-sized"),
+                 "%-28s %-36s %12s %12s %8s" % ("plan", "stand-ins on", "predicted us", "measured us", "ratio")]
+        for name, placement, pred, meas, _, _ in rows:
+            lines.append("%-28s %-36s %12.1f %12.1f %8.3f%s" % (name, placement, pred * 1e6, meas * 1e6, pred / meas,
+                                                                   "   <- chosen" if (name, placement) == (best[0], best[1]) else ""))
+        for ln in lines:
+            log("[%s] " % label + ln)
+        if table_path:
+            with open(table_path, "a") as f:
+                f.write("\n".join(lines) + "\n\n")
+        plan, placement = best[4], best[1]
+        lanes, c, cb = placements[placement]
+        segs, side = describe(plan)
+        log("[%s] chosen plan (stand-ins on %s), beside the strand %s:" % (label, placement, side), segs)
+        dh.dh_layer_set_beta_comm_stream(run.layer, cb)
+        step = lambda q=plan: run.si_step(alpha, beta, q, sa, sb, c)
+        ts_si = event_times(step, steps, warmup)
+        ts_seq = event_times(lambda: run.si_step(alpha, beta, seq_plan, sa, sb, c), max(10, steps // 2), 3)
+        # the same two schedules with every stand-in launching nothing (events and dependencies stay): what the
+        # communication costs each of them
+        dh.dh_layer_set_comm_blocks(run.layer, -1)
+        ts_si_nc = event_times(step, max(10, steps // 2), 3)
+        ts_seq_nc = event_times(lambda: run.si_step(alpha, beta, seq_plan, sa, sb, c), max(10, steps // 2), 3)
+        dh.dh_layer_set_comm_blocks(run.layer, comm_blocks)
+        t_si, t_seq, t_si_nc, t_seq_nc = median(ts_si), median(ts_seq), median(ts_si_nc), median(ts_seq_nc)
+        visible = max(0.0, t_si - t_si_nc)
+        rec = {"comm_blocks": comm_blocks, "standins_on": placement, "plan_pairs": len(segs), "beside_strand": side,
+               "ms_si": t_si * 1e3, "ms_sequential": t_seq * 1e3, "ms_si_no_comm": t_si_nc * 1e3, "ms_sequential_no_comm": t_seq_nc * 1e3,
+               "ms_standins_solo": t_comm * 1e3, "speedup_vs_sequential": t_seq / t_si,
+               "comm_visible_ms": visible * 1e3, "comm_hidden_frac": (1.0 - visible / t_comm) if t_comm > 0 else None,
+               "comm_hidden_frac_sequential": (1.0 - max(0.0, t_seq - t_seq_nc) / t_comm) if t_comm > 0 else None,
+               "predicted_ms": best[2] * 1e3, "predicted_over_measured": best[2] / t_si,
+               "orders_searched": [info.orders_fwd_tried, info.orders_bwd_tried], "orders_truncated": bool(info.truncated)}
+        log("[%s] T_seq %.1f us, T_SI %.1f us (predicted %.1f), without communication: T_seq %.1f, T_SI %.1f; stand-ins solo %.1f us; hidden %.2f" %
+            (label, t_seq * 1e6, t_si * 1e6, best[2] * 1e6, t_seq_nc * 1e6, t_si_nc * 1e6, t_comm * 1e6, rec["comm_hidden_frac"] or 0.0))
+        return rec, plan, (c, cb), table, ts_si
+
+    if args.plan_table and os.path.exists(args.plan_table):
+        os.remove(args.plan_table)
+    rec, best_plan, (c_best, cb_best), table, ts_si = regime("default", args.comm_blocks, args.steps, args.warmup, args.plan_table)
+    t_si = median(ts_si)
+    pct = lambda q: ts_si[min(len(ts_si) - 1, int(q * len(ts_si)))]
+    dh.dh_layer_set_beta_comm_stream(run.layer, cb_best)
+    step_fn = lambda: run.si_step(alpha, beta, best_plan, sa, sb, c_best)
+    t_wall = time_steps(step_fn, args.steps, 3, torch)   # the same steps back to back against the host clock
+
+    # ablations of Sec. 6.1 / 6.4 through the same executor: round-robin interleaving ("Wavelet+"), the searched plan with
+    # the weight-gradient operators left in their default places, the default orders free-running, and the replay of
+    # the chosen plan from a HIP graph (one launch per step instead of one per operator)
+    probe = max(5, args.steps // 5)
     rr_plan = dh.dh_plan_round_robin(gf, gb)
-    fixed_plan, _ = dh.dh_plan_search(gf, gb, table, 5e-6, 1)
-    probe = max(5, args.steps // 3)
-    t_rr = time_steps(lambda: run.si_step(alpha, beta, rr_plan, sa, sb, sc), probe, 2, torch)
-    t_fixed = time_steps(lambda: run.si_step(alpha, beta, fixed_plan, sa, sb, sc), probe, 2, torch)
-    log("ablations: round-robin %.1f us, weight gradients fixed %.1f us" % (t_rr * 1e6, t_fixed * 1e6))
+    lanes_best = placements[rec["standins_on"]][0]
+    fixed_plan, _, _ = dh.dh_plan_search_lanes(gf, gb, table, lanes_best, args.barrier_cost, 1)
+    t_rr = median(event_times(lambda: run.si_step(alpha, beta, rr_plan, sa, sb, c_best), probe, 2))
+    t_fixed = median(event_times(lambda: run.si_step(alpha, beta, fixed_plan, sa, sb, c_best), probe, 2))
+    t_free = median(event_times(lambda: run.si_step(alpha, beta, free_plan, sa, sb, c_best), probe, 2))
+    graph = dh.dh_si_graph_create(run.layer, alpha.fwd_args, beta.bwd_args, best_plan, run.ws, run.ws_bytes, sa, sb)
+    t_graph = median(event_times(lambda: dh.dh_si_graph_launch(graph, sa), probe, 2))
+    dh.dh_si_graph_destroy(graph)
     t_shared = None
     if sx is not None:  # ablation of Sec. 6.4 ("Communication and Communication Overlap"): both kinds of transfer on one stream
         dh.dh_layer_set_cross_stream(run.layer, None)
-        t_shared = time_steps(lambda: run.si_step(alpha, beta, best_plan, sa, sb, sc_stream), probe, 2, torch)
+        t_shared = median(event_times(lambda: run.si_step(alpha, beta, best_plan, sa, sb, sc), probe, 2))
         dh.dh_layer_set_cross_stream(run.layer, sx)
-        t_cross = sum(t_f[i] for i in range(nf) if gf.is_comm[i] == 2) + sum(t_b[j] for j in range(nb) if gb.is_comm[j] == 2)
-        log("cross-node stand-ins solo %.1f us; SI step with them on the collectives' stream %.1f us" % (t_cross * 1e6, t_shared * 1e6))
-    # the same step replayed from a HIP graph (one launch per step instead of one per operator)
-    graph = dh.dh_si_graph_create(run.layer, alpha.fwd_args, beta.bwd_args, best_plan, run.ws, run.ws_bytes, sa, sb)
-    t_graph = time_steps(lambda: dh.dh_si_graph_launch(graph, sa), args.steps, args.warmup, torch)
-    t_comm = sum(t_f[i] for i in range(nf) if gf.is_comm[i]) + sum(t_b[j] for j in range(nb) if gb.is_comm[j])
-    log("T_seq %.1f us, T_free-running %.1f us, T_SI(plan) %.1f us, T_SI(plan, graph replay) %.1f us, stand-ins solo %.1f us"
-        % (t_seq * 1e6, t_free * 1e6, t_si * 1e6, t_graph * 1e6, t_comm * 1e6))
+    log("ablations: round-robin %.1f us, weight gradients fixed %.1f us, default orders free-running %.1f us, graph replay %.1f us" %
+        (t_rr * 1e6, t_fixed * 1e6, t_free * 1e6, t_graph * 1e6))
 
-    # The step is timed both ways it can be issued (operator by operator, or as one replay of its recorded graph: same
-    # kernels, bitwise the same results); the faster one is the step time, and config.execution says which.
-    t_eager = t_si
-    execution = "eager (one launch per operator)"
-    if t_graph < t_si:
-        t_si, execution = t_graph, "graph replay (dh_si_graph_launch)"
+    # the same workload with the stand-ins at a link-like rate (64 thread blocks: a 32 MiB all-reduce then takes what an
+    # 8-GPU xGMI ring takes): profile, search and timing anew
+    link = None
+    if args.link_blocks > 0 and rec["ms_standins_solo"] > 0:
+        link, _, _, _, _ = regime("link rate", args.link_blocks, max(10, args.steps // 2), 3, args.plan_table)
+        dh.dh_layer_set_comm_blocks(run.layer, args.comm_blocks)
+        dh.dh_layer_set_beta_comm_stream(run.layer, cb_best)
+
+    # Roofline of every operator: algorithmic flops or bytes over its solo launch time, timed with events on the stream it
+    # runs on (dh_profile_solo); the headline roofline is the operator with the largest share of the step's solo time.
+    dh.dh_layer_set_beta_comm_stream(run.layer, scb)
+    tf20, tb20 = dh.dh_profile_solo(run.layer, alpha.fwd_args, beta.bwd_args, run.ws, run.ws_bytes, sa, sb, sc, 20)
+    dh.dh_layer_set_beta_comm_stream(run.layer, cb_best)
+    ops = []
+    total_solo = sum(tf20[:nf]) + sum(tb20[:nb])
+    for names, ts in ((fnames, tf20), (bnames, tb20)):
+        for k, name in enumerate(names):
+            w = op_work(cfg, name)
+            if w is None:
+                continue
+            kind, amount = w
+            peak = BF16_MFMA_PEAK_TFLOPS if kind == "mfma" else HBM_PEAK_GBS
+            ach = amount / ts[k] / (1e12 if kind == "mfma" else 1e9)
+            ops.append({"op": name, "bound": kind, "solo_us": ts[k] * 1e6, "share_of_solo": ts[k] / total_solo,
+                        "work": amount, "work_unit": "flop" if kind == "mfma" else "bytes", "achieved": ach,
+                        "unit": "TFLOP/s" if kind == "mfma" else "GB/s", "peak": peak, "frac": ach / peak})
+    dom = max(ops, key=lambda o: o["solo_us"])
+    log("operator rooflines (solo):", ", ".join("%s %.1fus %.0f%%" % (o["op"], o["solo_us"], 100 * o["frac"]) for o in ops))
+    traffic = read_traffic(args.workload, dom["op"])
+    roofline = {"bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac"],
+                "traffic": traffic, "traffic_unit": "bytes/launch", "algorithmic_work": dom["work"], "work_unit": dom["work_unit"],
+                "kernel": "%s (the operator with the largest share, %.1f %%, of the step's summed solo time; %s)" %
+                          (dom["op"], 100 * dom["share_of_solo"], OP_KERNELS.get(dom["op"].split("_", 1)[1] if "_" in dom["op"] else dom["op"], "its kernels")),
+                "solo_us": dom["solo_us"]}
+
     value = flops / t_si / 1e12
-    # Spread of the step time: events between consecutive steps on strand alpha's stream (every step forks from it
-    # and joins it), same plan and execution as `value`.
-    step_fn = ((lambda: dh.dh_si_graph_launch(graph, sa)) if execution.startswith("graph")
-               else (lambda: run.si_step(alpha, beta, best_plan, sa, sb, sc)))
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    for _ in range(3):
-        step_fn()
-    marks[0].record(sa)
-    for i in range(args.steps):
-        step_fn()
-        marks[i + 1].record(sa)
-    torch.cuda.synchronize()
-    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
-    pct = lambda q: per_step[min(len(per_step) - 1, int(q * len(per_step)))]
-    # roofline of the dominant kernel: the first FFN GEMM (gate/up projection; largest share of the FLOPs), timed
-    # alone with events on the stream it is launched on.  MoE: one local expert's balanced share of the rows.
-    Hd = cfg["hidden"]
-    T = run.T if cfg["arch"] != "moe" else 2 * run.T // cfg["n_local"]
-    F2 = cfg["ffn"] if cfg["arch"] == "gpt" else 2 * cfg["ffn"]
-    a_mat = torch.empty(T, Hd, dtype=torch.bfloat16, device="cuda").normal_()
-    b_mat = torch.empty(Hd, F2, dtype=torch.bfloat16, device="cuda").normal_(0, 0.02)
-    c_mat = torch.empty(T, F2, dtype=torch.bfloat16, device="cuda")
-    wsb = dh.dh_gemm_workspace_bytes(dh.DH_BF16, 0, 0, T, F2, Hd)
-    gws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
-    torch.cuda.synchronize()
-    reps = 50
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    for _ in range(5):
-        dh.dh_gemm(dh.DH_BF16, 0, 0, T, F2, Hd, a_mat, b_mat, c_mat, False, gws, wsb, sa)
-    e0.record(sa)
-    for _ in range(reps):
-        dh.dh_gemm(dh.DH_BF16, 0, 0, T, F2, Hd, a_mat, b_mat, c_mat, False, gws, wsb, sa)
-    e1.record(sa)
-    torch.cuda.synchronize()
-    gemm_s = e0.elapsed_time(e1) * 1e-3 / reps
-    gemm_tflops = 2.0 * T * F2 * Hd / gemm_s / 1e12
-    log("dominant GEMM [%d x %d x %d]: %.1f us, %.1f TFLOP/s" % (T, F2, Hd, gemm_s * 1e6, gemm_tflops))
-
     # Composition of the stand-in (communication) time in the manner of Table 7: the share SI hides, the visible share
     # that launch intervals cost (what the graph replay of the same plan saves over eager launches), the visible rest
-    # (kernel slowdown under co-execution).  Hidden is capped at the whole: SI also overlaps work that is not communication.
+    # (kernel slowdown under co-execution).
     comp = None
-    if t_comm > 0:
-        hidden = min(1.0, max(0.0, (t_seq - t_eager) / t_comm))
-        launch = min(1.0 - hidden, max(0.0, (t_eager - t_graph) / t_comm))
+    if rec["comm_hidden_frac"] is not None:
+        hidden = min(1.0, max(0.0, rec["comm_hidden_frac"]))
+        launch = min(1.0 - hidden, max(0.0, (t_si - t_graph) / (rec["ms_standins_solo"] * 1e-3)))
         comp = {"hidden": hidden, "visible_launch_interval": launch, "visible_slowdown": 1.0 - hidden - launch}
+    segs, side = describe(best_plan)
     out = {
         "metric": "SI layer fwd+bwd TFLOP/s per MI355X (% bf16 peak); speedup vs sequential",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": t_si * 1e3, "ms_per_step_events": {"p10": pct(0.1), "median": pct(0.5), "p90": pct(0.9)},
+        "ms_per_step": t_si * 1e3, "ms_per_step_events": {"p10": pct(0.1) * 1e3, "median": t_si * 1e3, "p90": pct(0.9) * 1e3},
+        "ms_per_step_host_clock": t_wall * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg["bf16"] else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "arch": cfg["arch"], "tokens_per_strand": run.T, "comm_blocks": args.comm_blocks,
-                   "cp": [cfg["cp_rank"], cfg["cp_ranks"]] if cfg["arch"] == "llama_cp" else None, "plan_pairs": len(pairs), "plan": best_name, "execution": execution, "standins_on": comm_placement},
+                   "cp": [cfg["cp_rank"], cfg["cp_ranks"]] if cfg["arch"] == "llama_cp" else None, "plan_pairs": len(segs),
+                   "plan": "dh_plan_search_lanes (lane model, all operator orders), beside the strand: %s" % ("+".join(side) or "none"),
+                   "execution": "eager (one launch per operator)", "standins_on": rec["standins_on"]},
         "pct_bf16_peak": 100.0 * value / BF16_MFMA_PEAK_TFLOPS,
         "tflops_full_attention_convention": H.model_flops(cfg, full_attention=True) / t_si / 1e12,
         "tokens_per_s": run.T / t_si,
-        "speedup_vs_sequential": t_seq / t_si,
-        "ms_sequential": t_seq * 1e3, "ms_free_running": t_free * 1e3, "ms_eager": t_eager * 1e3, "ms_graph_replay": t_graph * 1e3,
-        "ms_round_robin": t_rr * 1e3, "ms_wgrad_fixed": t_fixed * 1e3, "ms_wgrad_in_strand": t_in_strand * 1e3,
+        "speedup_vs_sequential": rec["speedup_vs_sequential"],
+        "ms_sequential": rec["ms_sequential"], "ms_si_no_comm": rec["ms_si_no_comm"], "ms_sequential_no_comm": rec["ms_sequential_no_comm"],
+        "ms_free_running": t_free * 1e3, "ms_graph_replay": t_graph * 1e3, "ms_round_robin": t_rr * 1e3, "ms_wgrad_fixed": t_fixed * 1e3,
         "ms_one_comm_stream": t_shared * 1e3 if t_shared is not None else None,
-        "comm_hidden_frac": (t_seq - t_si) / t_comm if t_comm > 0 else None,
-        "comm_composition": comp,
-        "roofline": {"bound": "mfma", "achieved": gemm_tflops, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": gemm_tflops / BF16_MFMA_PEAK_TFLOPS, "traffic": HBM_TRAFFIC_BYTES.get(args.workload),
-                     "traffic_unit": "bytes/launch", "algorithmic_bytes": 2.0 * (T * Hd + Hd * F2 + T * F2),
-                     "kernel": "gemm_bf16_kernel (first FFN projection %dx%dx%d)" % (T, F2, Hd)},
+        "comm_hidden_frac": rec["comm_hidden_frac"], "comm_composition": comp,
+        "predicted_ms": rec["predicted_ms"], "predicted_over_measured": rec["predicted_over_measured"],
+        "link_rate": link,
+        "roofline": roofline, "roofline_ops": ops,
     }
-    dh.dh_si_graph_destroy(graph)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, flops)
     run.close()

@@ -214,7 +214,7 @@ def test_si_step_bitwise_equals_sequential_and_matches_oracle(name):
     from paper_2411_15871_amd import dhelix as dh
     cfg, tol = CASES[name]
     run = H.LayerRun(cfg)
-    comm, cross = torch.cuda.Stream(), torch.cuda.Stream()
+    comm, cross, comm_b = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
     try:
         alpha, beta = run.strand(0), run.strand(1)
         sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
@@ -253,18 +253,36 @@ def test_si_step_bitwise_equals_sequential_and_matches_oracle(name):
             variants = [(sa, sb, comm, None), (sa, sb, None, None)]
             if cfg.get("arch") == "llama_cp":  # Send/Recv stand-ins on a cross-node stream of their own
                 variants += [(sa, sb, comm, cross), (sa, sb, None, cross)]
-            for *streams, xs in variants:
-                print("plan", pname, "comm" if streams[2] else "nocomm", "cross" if xs else "", flush=True)
+            variants = [v + (None,) for v in variants] + [(sa, sb, comm, None, comm_b)]  # beta's collectives on a stream of their own
+            for *streams, xs, cb in variants:
+                print("plan", pname, "comm" if streams[2] else "nocomm", "cross" if xs else "", "beta-comm" if cb else "", flush=True)
                 alpha.out.zero_(); alpha.saved.zero_(); beta.dx.zero_()
                 if beta.dkv_peers is not None:
                     beta.dkv_peers.zero_()
                 run.zero_grads()
                 torch.cuda.synchronize()
                 dh.dh_layer_set_cross_stream(run.layer, xs)
+                dh.dh_layer_set_beta_comm_stream(run.layer, cb)
                 run.si_step(alpha, beta, plan, *streams)
                 got = snapshot(run, alpha, beta)
+                dh.dh_layer_set_beta_comm_stream(run.layer, None)
                 for a, b in zip(got, ref):
                     assert torch.equal(a, b), pname
+        # stand-ins that launch nothing (the timing-only mode) leave the schedule runnable, and the normal mode comes back
+        dh.dh_layer_set_comm_blocks(run.layer, -1)
+        run.si_step(alpha, beta, plans["random_a"], sa, sb, comm)
+        torch.cuda.synchronize()
+        dh.dh_layer_set_comm_blocks(run.layer, 3)   # a few blocks: the result does not depend on the block count
+        alpha.out.zero_(); alpha.saved.zero_(); beta.dx.zero_()
+        if beta.dkv_peers is not None:
+            beta.dkv_peers.zero_()
+        run.zero_grads()
+        run.si_step(alpha, beta, plans["random_a"], sa, sb, comm)
+        for a, b in zip(snapshot(run, alpha, beta), ref):
+            assert torch.equal(a, b), "after the no-op mode"
+        dh.dh_layer_set_comm_blocks(run.layer, 0)
+        with pytest.raises(dh.DhelixError):
+            dh.dh_layer_set_comm_blocks(run.layer, -2)
         # invalid plans are rejected before anything is enqueued
         bad = dh.make_plan(list(range(nf)), list(range(nb)), [(0, nf, 0, nb - 1)])
         with pytest.raises(dh.DhelixError) as e:
