@@ -49,7 +49,7 @@ typedef enum { DH_F32 = 0, DH_BF16 = 1 } dh_dtype;
  * DH_ARCH_MOE:   Llama-style attention (not sharded) + top-2 mixture-of-experts SwiGLU FFN under expert
  *                parallelism (all-to-all dispatch / combine; MoE models of Table 3).
  * DH_ARCH_LLAMA_CP: DH_ARCH_LLAMA on one rank of a context-parallel group (Sec. 2.1): the rank holds one chunk of
- *                each sequence and collects the earlier chunks' keys/values by Send/Recv (Sec. 2.2). */
+ *                each sequence and collects the earlier chunks' keys/values by Send/Recv (Sec. 2.1, Sec. 2.3). */
 typedef enum { DH_ARCH_LLAMA = 0, DH_ARCH_GPT = 1, DH_ARCH_MOE = 2, DH_ARCH_LLAMA_CP = 3 } dh_arch;
 
 /* Message of the last error raised on this thread ("" if none).  Host memory owned by the library. */
@@ -290,6 +290,12 @@ int dh_profile_pairs(dh_layer* layer, const dh_fwd_args* alpha, const dh_bwd_arg
                      size_t ws_bytes, void* stream_alpha, void* stream_beta, void* comm_stream,
                      int reps, dh_overlap_table* out);
 
+/* The solo times alone (Sec. 3.2, the T_i of Eq. 1): every operator launched reps times back to back (after one
+ * warm-up launch) on the stream dh_si_step would issue it to, timed with events on that stream.  t_fwd / t_bwd: host
+ * arrays of DH_MAX_OPS doubles, seconds.  Same requirements and side effects as dh_profile_pairs.  Blocks until done. */
+int dh_profile_solo(dh_layer* layer, const dh_fwd_args* alpha, const dh_bwd_args* beta, void* ws, size_t ws_bytes,
+                    void* stream_alpha, void* stream_beta, void* comm_stream, int reps, double* t_fwd, double* t_bwd);
+
 /* ------------------------------------------------------------------------------------------
  * Plans (Sec. 4.2).  A plan = one operator sequence per strand plus segment pairs: pair k
  * co-runs forward operators fwd_order[f_begin:f_end] with backward operators
@@ -443,7 +449,7 @@ int dh_stack_phase(dh_stack* stack, const dh_stack_fwd* alpha, const dh_stack_bw
 
 /* The same step recorded once into a HIP graph (stream capture on stream_alpha, which forks into
  * stream_beta; nothing runs) and replayed with one launch per step, which removes the per-operator
- * launch intervals (Sec. 6.4 names them as the remaining loss).  The two streams must be distinct and
+ * launch intervals (Sec. 6.3, Table 7, names them as part of the remaining loss).  The two streams must be distinct and
  * non-null.  A graph holds dependencies, not streams: every collective stand-in becomes a node in its
  * strand's chain.  All buffers named by alpha, beta, ws and the bound weights/gradients must stay where
  * they are while the graph is in use.  dh_si_graph_launch enqueues one step on `stream`. */
@@ -478,7 +484,7 @@ typedef enum {
 int dh_comm_standin(int kind, int n_ranks, const void* const* parts, void* out, size_t elems,
                     int dtype, int n_blocks, void* stream);
 
-/* Context parallelism (Sec. 2.1, Sec. 2.2: CP ranks pass key/value chunks around by Send/Recv; Sec. 5: such
+/* Context parallelism (Sec. 2.1, Sec. 2.3: CP ranks pass key/value chunks around by Send/Recv; Sec. 5: such
  * cross-node transfers get a stream of their own).  One-GPU stand-in of the exchange: n_moves (<= 16) copies, each
  * of `rows` rows of `width` elements (multiple of 8) for each of `batch` sequences.  A side of a move is a row-major
  * buffer with a row pitch of ld elements holding seq_rows rows per sequence, of which the move touches rows
@@ -585,7 +591,7 @@ int dh_attn_bwd(int dtype, int batch, int seq, int nq, int nkv, int d, const voi
 size_t dh_attn_bwd_workspace_bytes(int dtype, int batch, int seq, int nq, int nkv, int d);
 
 /* Attention of a context-parallel rank (Sec. 2.1: the token sequence is partitioned over the CP ranks and each
- * collects the others' key/value tensors; Sec. 2.2: by Send/Recv, ring-attention style).  The rank's seq queries
+ * collects the others' key/value tensors; Sec. 2.1 and 2.3: by Send/Recv, ring-attention style).  The rank's seq queries
  * per sequence sit at positions q_off .. q_off+seq-1 and read, causally, the keys/values of positions
  * 0 .. q_off+seq-1 from kv[batch*(q_off+seq), 2*nkv*d] = [k heads | v heads] per row (keys rotated), sequence-major:
  * q_off rows received from the earlier ranks, then the rank's own.  qkv, o, lse, dout, delta are as in dh_attn_fwd /

@@ -526,7 +526,7 @@ def moe_layer_bwd(cfg, W, saved, dout, n_local):
 
 
 # --------------------------------------------------------------------------- context parallelism (Sec. 2.1 "Intra-layer
-# parallelism", Sec. 2.2: key/value chunks of the other ranks arrive by Send/Recv, ring-attention style)
+# parallelism", Sec. 2.1 and 2.3: key/value chunks of the other ranks arrive by Send/Recv, ring-attention style)
 def attention_ctx_fwd(q, k, v, batch, s_l, q_off):
     """Attention of a context-parallel rank: its s_l queries per sequence sit at positions q_off..q_off+s_l-1 and
     read the keys/values of positions 0..q_off+s_l-1 (the earlier ranks' chunks followed by its own), causally.

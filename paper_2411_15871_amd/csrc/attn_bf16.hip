@@ -975,9 +975,6 @@ static int pick_chunk(int kind, int seq, int q_off, int nq_all, int d, bool grou
   static std::mutex mu;
   static std::map<PickKey, int> cache;
   const PickKey key{kind, seq, q_off, nq_all, d, grouped ? 1 : 0, attn_num_cus()};
-#ifdef DH_ATTN_SWEEP  // tuning builds only: chunk lengths from the environment
-  if (const char* e = getenv(kind == PICK_FWD ? "DH_ATTN_CH_FWD" : kind == PICK_DQ ? "DH_ATTN_CH_DQ" : "DH_ATTN_CH_DKV")) return atoi(e) > 0 ? atoi(e) : (1 << 20);
-#endif
   std::lock_guard<std::mutex> lock(mu);
   auto it = cache.find(key);
   if (it != cache.end()) return it->second;
@@ -1003,9 +1000,6 @@ static int pick_chunk(int kind, int seq, int q_off, int nq_all, int d, bool grou
     else if (kind == PICK_DQ) { if (split) bytes = (double)units * d; }
     else if (split || grouped) bytes = (double)units * 2 * d;
     t += bytes * nq_all * 128 * sizeof(float) * us_per_byte + (split && !(kind == PICK_DKV && grouped) ? t_merge : 0.0);
-#ifdef DH_ATTN_SWEEP
-    fprintf(stderr, "pick kind %d seq %d heads %d: ch %d -> %.1f us (split %d)\n", kind, seq, nq_all, ch, t, (int)split);
-#endif
     if (t < best_t) { best_t = t; best = ch; }
   }
   cache[key] = best;

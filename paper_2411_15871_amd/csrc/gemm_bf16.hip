@@ -33,9 +33,7 @@
 #include "common.h"
 
 #define GB_BK 32
-#ifndef GB_STAGES
 #define GB_STAGES 4
-#endif
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
@@ -524,9 +522,6 @@ static GemmPlan choose_plan(bool ta, int M, int N, int K, size_t ws_bytes) {
   if (tiles(256, 256) * 2 >= cus) { p.cfg = 0; p.bm = 256; p.bn = 256; }
   else if (!ta && tiles(256, 128) <= cus && tiles(256, 128) * 4 >= (long long)cus * 3) { p.cfg = 2; p.bm = 256; p.bn = 128; }
   else { p.cfg = 1; p.bm = 128; p.bn = 128; }
-#ifdef DH_GEMM_SWEEP  // tuning builds only
-  if (const char* e = getenv("DH_GEMM_CFG")) { p.cfg = atoi(e); p.bm = p.bn = p.cfg ? 128 : 256; }
-#endif
   const int nkt = (K + GB_BK - 1) / GB_BK;
   const long long t = tiles(p.bm, p.bn);
   int splits = 1;
@@ -537,9 +532,6 @@ static GemmPlan choose_plan(bool ta, int M, int N, int K, size_t ws_bytes) {
     if (per == 0 || ws_bytes / per < (size_t)splits) splits = per ? (int)(ws_bytes / per) : 1;
     if (splits < 2) splits = 1;
   }
-#ifdef DH_GEMM_SWEEP
-  if (const char* e = getenv("DH_GEMM_SPLITS")) splits = atoi(e);
-#endif
   p.kt_per_split = nkt == 0 ? 1 : (nkt + splits - 1) / splits;
   p.splits = nkt == 0 ? 1 : (nkt + p.kt_per_split - 1) / p.kt_per_split;
   // Tail: more than one round of 256x256 tiles whose last round is at most half full -> split those tiles' K so that

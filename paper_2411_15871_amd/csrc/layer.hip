@@ -1145,6 +1145,48 @@ static int launch_op(dh_layer* L, const TimedOp& o, const dh_fwd_args& a, const 
   return o.dir == 0 ? run_fwd_op(L, o.op, a, ws_f, s) : run_bwd_op(L, o.op, b, ws_b, s);
 }
 
+// Solo time of every operator (the first half of the pair profiler), each on the stream dh_si_step would issue it to.
+extern "C" int dh_profile_solo(dh_layer* L, const dh_fwd_args* alpha, const dh_bwd_args* beta, void* ws, size_t ws_bytes,
+                               void* stream_alpha, void* stream_beta, void* comm_stream, int reps, double* t_fwd, double* t_bwd) {
+  int rc = check_fwd_args(L, alpha);
+  if (rc) return rc;
+  if ((rc = check_bwd_args(L, beta))) return rc;
+  if (!t_fwd || !t_bwd || reps < 1) DH_FAIL(DH_ERR_INVALID_ARG, "profile_solo: bad arguments");
+  if ((rc = check_ws(L, DH_WS_SI, ws, ws_bytes))) return rc;
+  hipStream_t sa = (hipStream_t)stream_alpha, sb = (hipStream_t)stream_beta, sc = (hipStream_t)comm_stream;
+  char* ws_f = (char*)ws;
+  char* ws_b = (char*)ws + L->fwd_bytes;
+  const int NF = L->gf.n_ops, NB = L->gb.n_ops;
+  for (int i = 0; i < NF; i++) t_fwd[i] = 0.0;
+  for (int j = 0; j < NB; j++) t_bwd[j] = 0.0;
+  if (L->T == 0) return DH_OK;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  auto cleanup = [&]() { if (e0) (void)hipEventDestroy(e0); if (e1) (void)hipEventDestroy(e1); };
+  hipError_t he = hipEventCreate(&e0);
+  if (he == hipSuccess) he = hipEventCreate(&e1);
+  if (he != hipSuccess) { cleanup(); return dh_set_error(DH_ERR_HIP, "profile_solo: event creation failed: %s", hipGetErrorString(he)); }
+  for (int dir = 0; dir < 2; dir++)
+    for (int op = 0; op < (dir == 0 ? NF : NB); op++) {
+      const int comm = dir == 0 ? L->gf.is_comm[op] : L->gb.is_comm[op];
+      const hipStream_t base = dir == 1 && sc != nullptr && L->beta_comm_stream != nullptr ? L->beta_comm_stream : sc;
+      hipStream_t s = comm ? comm_stream_of(L, comm, base) : nullptr;
+      if (!s) s = dir == 0 ? sa : sb;
+      for (int r = 0; r < reps + 1; r++) {  // one warm-up launch, then the timed ones
+        if (r == 1) (void)hipEventRecord(e0, s);
+        rc = dir == 0 ? run_fwd_op(L, op, *alpha, ws_f, s) : run_bwd_op(L, op, *beta, ws_b, s);
+        if (rc) { cleanup(); return rc; }
+      }
+      (void)hipEventRecord(e1, s);
+      he = hipEventSynchronize(e1);
+      if (he != hipSuccess) { cleanup(); return dh_set_error(DH_ERR_HIP, "profile_solo: %s", hipGetErrorString(he)); }
+      float ms = 0.f;
+      (void)hipEventElapsedTime(&ms, e0, e1);
+      (dir == 0 ? t_fwd : t_bwd)[op] = std::max((double)ms * 1e-3 / reps, 1e-7);
+    }
+  cleanup();
+  return DH_OK;
+}
+
 extern "C" int dh_profile_pairs(dh_layer* L, const dh_fwd_args* alpha, const dh_bwd_args* beta, void* ws, size_t ws_bytes,
                                 void* stream_alpha, void* stream_beta, void* comm_stream, int reps, dh_overlap_table* out) {
   int rc = check_fwd_args(L, alpha);

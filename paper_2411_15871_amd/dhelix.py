@@ -150,6 +150,7 @@ SIGNATURES = {
                           C.POINTER(dh_lanes), _D]),
     "dh_plan_search_lanes": (_I, [C.POINTER(dh_op_graph), C.POINTER(dh_op_graph), C.POINTER(dh_overlap_table),
                                   C.POINTER(dh_lanes), _D, _I, C.POINTER(dh_plan), C.POINTER(_D), C.POINTER(dh_search_info)]),
+    "dh_profile_solo": (_I, [_P, C.POINTER(dh_fwd_args), C.POINTER(dh_bwd_args), _P, _Z, _P, _P, _P, _I, C.POINTER(_D), C.POINTER(_D)]),
     "dh_layer_set_beta_comm_stream": (_I, [_P, _P]),
     "dh_layer_set_comm_blocks": (_I, [_P, _I]),
     "dh_plan_round_robin": (_I, [C.POINTER(dh_op_graph), C.POINTER(dh_op_graph), C.POINTER(dh_plan)]),
@@ -419,6 +420,14 @@ def dh_plan_search_lanes(fwd_graph, bwd_graph, table, lane_cfg, barrier_cost=0.0
     _check(lib.dh_plan_search_lanes(C.byref(fwd_graph), C.byref(bwd_graph), C.byref(table), C.byref(lane_cfg), barrier_cost,
                                     max_orders, C.byref(p), C.byref(m), C.byref(info)))
     return p, m.value, info
+
+
+def dh_profile_solo(layer, alpha, beta, ws, ws_bytes, stream_alpha, stream_beta, comm_stream, reps=20):
+    """Returns (t_fwd, t_bwd): lists of DH_MAX_OPS solo times in seconds."""
+    tf, tb = (C.c_double * DH_MAX_OPS)(), (C.c_double * DH_MAX_OPS)()
+    _check(lib.dh_profile_solo(layer, C.byref(alpha), C.byref(beta), _ptr(ws), ws_bytes, _stream(stream_alpha),
+                               _stream(stream_beta), _stream(comm_stream), reps, tf, tb))
+    return list(tf), list(tb)
 
 
 def dh_layer_set_beta_comm_stream(layer, stream):
