@@ -579,28 +579,26 @@ __global__ __launch_bounds__(256) void attn_fwd_combine_kernel(int seq, int q_of
 // ================================================================================ backward: dQ
 // Same tiling as the forward kernel.  dQ^T = sum over key tiles of K^T dS^T, dS^T = P^T (dP^T - delta),
 // P^T = exp2(S^T*scale_log2 - lse2), dP^T = V dO^T.
-// The kernel also forms the backward pass's per-row statistics, delta[h,t] = sum_c dO[t,h,c] O[t,h,c] and
-// lse2[h,t] = lse[h,t] log2(e): every block for its own rows (a row's two lanes each hold half of dO), and the block
-// of a query block's first chunk stores them for the dK/dV kernel, which runs after this one.
+// Every block forms the per-row statistics delta[h,t] = sum_c dO[t,h,c] O[t,h,c] and lse2[h,t] = lse[h,t] log2(e) of its
+// own rows itself (a row's two lanes each hold half of dO).  The dK/dV blocks read them from memory: when the dQ blocks
+// are launched ahead of them, the block of a query block's first chunk stores them (delta_out != nullptr); when both
+// kinds share one launch, attn_bwd_prep_kernel has filled the arrays.
 template <int D>
-__global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(const AttnGeom g, const bf16_t* __restrict__ qkv,
-                                                                      const bf16_t* __restrict__ o,
-                                                                      const bf16_t* __restrict__ dout,
-                                                                      const float* __restrict__ lse,
-                                                                      float* __restrict__ lse2,
-                                                                      float* __restrict__ delta,
-                                                                      bf16_t* __restrict__ dqkv, float* __restrict__ part,
-                                                                      int pairs, int T, float scale, float scale_log2) {
+__device__ __forceinline__ void attn_bwd_dq_block(const int bid, const AttnGeom& g, const bf16_t* __restrict__ qkv,
+                                                  const bf16_t* __restrict__ o, const bf16_t* __restrict__ dout,
+                                                  const float* __restrict__ lse, float* __restrict__ lse2_out,
+                                                  float* __restrict__ delta_out, bf16_t* __restrict__ dqkv,
+                                                  float* __restrict__ part, int pairs, int T, float scale, float scale_log2) {
   using TL = ATile<D>;
   extern __shared__ __attribute__((aligned(1024))) char smem[];  // K ring, then V ring
   const lds_char* sm = (const lds_char*)smem;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l32 = lane & 31, kg = lane >> 5;
   const int seq = g.seq, nq = g.nq, nkv = g.nkv, ldkv = g.ldkv;
-  const int hb = blockIdx.x % g.nq_all;
+  const int hb = bid % g.nq_all;
   const int h = hb % nq, b = hb / nq, hk = h / (nq / nkv);
   const int ld = (nq + 2 * nkv) * D;
-  const ChunkMap cm = map_chunk<false>(blockIdx.x / g.nq_all, seq, g.q_off, pairs, g.ch);
+  const ChunkMap cm = map_chunk<false>(bid / g.nq_all, seq, g.q_off, pairs, g.ch);
   const int i0 = cm.blk * 128, iw = i0 + wave * 32, iq = iw + l32;
   const size_t ktok0 = (size_t)b * seq;
   const long long qtok0 = (long long)b * (seq - g.q_off) - g.q_off;  // local token of position p = qtok0 + p
@@ -621,10 +619,10 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(const Attn
     for (int ks = 0; ks < D / 16; ks++)
 #pragma unroll
       for (int e = 0; e < 8; e++) dl = fmaf((float)dof[ks][e], (float)of[ks][e], dl);
-    dl += __shfl_xor(dl, 32, 64);  // the row's other half
-    if (cm.chunk == 0 && kg == 0 && iq < seq) {
-      delta[(size_t)h * T + qrow] = dl;
-      lse2[(size_t)h * T + qrow] = l2;
+    dl += __shfl_xor(dl, 32, 64);  // the row's other half (the same number attn_bwd_prep_kernel stores for the dK/dV blocks)
+    if (delta_out != nullptr && cm.chunk == 0 && kg == 0 && iq < seq) {  // launched ahead of the dK/dV kernel: store them for it
+      delta_out[(size_t)h * T + qrow] = dl;
+      lse2_out[(size_t)h * T + qrow] = l2;
     }
   }
   f32x16 dqt[D / 32];
@@ -734,22 +732,20 @@ __device__ __forceinline__ void attn_bwd_dq_reduce_block(int bx, int by, int bz,
 // attn_bwd_reduce_kernel (its dK/dV part) adds the group's heads and the key block's chunks in index order; with
 // nq == nkv and no block longer than one chunk it writes dK, dV directly.
 template <int D>
-__global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(const AttnGeom g, const bf16_t* __restrict__ qkv,
-                                                                       const bf16_t* __restrict__ dout,
-                                                                       const float* __restrict__ lse2,
-                                                                       const float* __restrict__ delta,
-                                                                       float* __restrict__ part,
-                                                                       int pairs, int T, float scale, float scale_log2) {
+__device__ __forceinline__ void attn_bwd_dkv_block(const int bid, const AttnGeom& g, const bf16_t* __restrict__ qkv,
+                                                   const bf16_t* __restrict__ dout, const float* __restrict__ lse2,
+                                                   const float* __restrict__ delta, float* __restrict__ part, int pairs, int T,
+                                                   float scale, float scale_log2) {
   using TL = ATile<D>;
   extern __shared__ __attribute__((aligned(1024))) char smem[];  // Q ring, dO ring, lse2 ring, delta ring
   const lds_char* sm = (const lds_char*)smem;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l32 = lane & 31, kg = lane >> 5;
   const int seq = g.seq, nq = g.nq, nkv = g.nkv;
-  const int hb = blockIdx.x % g.nq_all;
+  const int hb = bid % g.nq_all;
   const int hq = hb % nq, b = hb / nq, grp = nq / nkv, hk = hq / grp;
   const int ld = (nq + 2 * nkv) * D, ldo = nq * D;
-  const ChunkMap cm = map_chunk<true>(blockIdx.x / g.nq_all, seq, g.q_off, pairs, g.ch);
+  const ChunkMap cm = map_chunk<true>(bid / g.nq_all, seq, g.q_off, pairs, g.ch);
   const int j0 = cm.blk * 128, jw = j0 + wave * 32, jk = jw + l32;  // key positions in the sequence (block 0 is the heaviest)
   const int q0 = dkv_first(cm.blk, g.q_off);                        // first query position this key block meets
   const size_t ktok0 = (size_t)b * seq;
@@ -872,6 +868,72 @@ __global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(const Att
     wave_rows_out_bf16<D>(reg, lane, dv_quad,
                           [&](int r) { return jw + r < seq ? g.dkv + (ktok0 + jw + r) * g.lddkv + (size_t)(nkv + hk) * D : nullptr; });
   }
+}
+
+// One launch for both halves of the backward pass, used when every query head has a key/value head of its own.  Alone,
+// each half leaves compute units idle while its longest blocks finish; in one grid the dQ units fill the gaps of the
+// dK/dV units and the other way round (measured on MI355X at 2 x 2048 tokens, 8 heads: 122 -> 94 us).  With grouped
+// heads the same merge measured slower than two launches (4096 tokens, 4:1 heads: 128 -> 145 us; 8192 tokens, 8:1:
+// 594 -> 652 us), so those shapes keep two launches.  Launch index -> (head, unit): units of the two kinds alternate, each kind
+// heaviest first, the dK/dV unit (the dearer one) leading; once the shorter list is used up the rest of the longer
+// follows.  grid ((pairs_q + pairs_k) * nq * batch).
+template <int D>
+__global__ __launch_bounds__(AB_THREADS) void attn_bwd_bf16_kernel(const AttnGeom gq, const AttnGeom gk, const bf16_t* __restrict__ qkv,
+                                                                   const bf16_t* __restrict__ o, const bf16_t* __restrict__ dout,
+                                                                   const float* __restrict__ lse, const float* __restrict__ lse2,
+                                                                   const float* __restrict__ delta, bf16_t* __restrict__ dqkv,
+                                                                   float* __restrict__ part_q, float* __restrict__ part_kv, int pairs_q,
+                                                                   int pairs_k, int T, float scale, float scale_log2) {
+  const int hb = blockIdx.x % gq.nq_all, u = blockIdx.x / gq.nq_all, both = 2 * min(pairs_q, pairs_k);
+  int idx;
+  bool dkv;
+  if (u < both) { dkv = (u & 1) == 0; idx = u >> 1; }
+  else { dkv = pairs_k > pairs_q; idx = u - both / 2; }
+  if (dkv) attn_bwd_dkv_block<D>(idx * gk.nq_all + hb, gk, qkv, dout, lse2, delta, part_kv, pairs_k, T, scale, scale_log2);
+  else attn_bwd_dq_block<D>(idx * gq.nq_all + hb, gq, qkv, o, dout, lse, nullptr, nullptr, dqkv, part_q, pairs_q, T, scale, scale_log2);
+}
+// The two halves as launches of their own (dQ first: it stores the row statistics the dK/dV blocks read).
+template <int D>
+__global__ __launch_bounds__(AB_THREADS) void attn_bwd_dq_bf16_kernel(const AttnGeom g, const bf16_t* __restrict__ qkv,
+                                                                      const bf16_t* __restrict__ o, const bf16_t* __restrict__ dout,
+                                                                      const float* __restrict__ lse, float* __restrict__ lse2,
+                                                                      float* __restrict__ delta, bf16_t* __restrict__ dqkv,
+                                                                      float* __restrict__ part, int pairs, int T, float scale, float scale_log2) {
+  attn_bwd_dq_block<D>((int)blockIdx.x, g, qkv, o, dout, lse, lse2, delta, dqkv, part, pairs, T, scale, scale_log2);
+}
+template <int D>
+__global__ __launch_bounds__(AB_THREADS) void attn_bwd_dkv_bf16_kernel(const AttnGeom g, const bf16_t* __restrict__ qkv,
+                                                                       const bf16_t* __restrict__ dout, const float* __restrict__ lse2,
+                                                                       const float* __restrict__ delta, float* __restrict__ part,
+                                                                       int pairs, int T, float scale, float scale_log2) {
+  attn_bwd_dkv_block<D>((int)blockIdx.x, g, qkv, dout, lse2, delta, part, pairs, T, scale, scale_log2);
+}
+
+// Per-row statistics of the backward pass for the dK/dV blocks: delta[h,t] = sum_c dO[t,h,c] O[t,h,c] and
+// lse2[h,t] = lse[h,t] log2(e).  The sum runs in the order the dQ blocks use for their own copy (two halves of the row,
+// each 8 elements out of every 16, one fused multiply-add per element, halves added last), so both kernels work with
+// the same numbers.  One thread per (token, head).
+template <int D>
+__global__ __launch_bounds__(256) void attn_bwd_prep_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ dout,
+                                                            const float* __restrict__ lse, float* __restrict__ lse2,
+                                                            float* __restrict__ delta, int T, int nq) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)T * nq) return;
+  const int h = (int)(i % nq);
+  const size_t t = i / nq;
+  const bf16_t* orow = o + (t * nq + h) * D;
+  const bf16_t* drow = dout + (t * nq + h) * D;
+  float half[2] = {0.f, 0.f};
+#pragma unroll
+  for (int kg = 0; kg < 2; kg++)
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ks++) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(drow + ks * 16 + kg * 8), b = *reinterpret_cast<const bf16x8*>(orow + ks * 16 + kg * 8);
+#pragma unroll
+      for (int e = 0; e < 8; e++) half[kg] = fmaf((float)a[e], (float)b[e], half[kg]);
+    }
+  delta[(size_t)h * T + t] = half[0] + half[1];
+  lse2[(size_t)h * T + t] = lse[(size_t)h * T + t] * LOG2E;
 }
 
 // dk,dv[token][kv head] = sum over the group's query heads (ascending) and, inside a head, over the
@@ -1123,7 +1185,8 @@ int dh_launch_attn_bwd_bf16(int batch, int seq_q, int nq, int nkv, int d, const 
   float* part_q = lay.part_q ? (float*)((char*)ws + lay.o_dq) : nullptr;
   const float sc = (float)(1.0 / sqrt((double)d)), sl2 = (float)(1.4426950408889634 / sqrt((double)d));
   const int nblk = (seq + 127) / 128, nblk_q = nblk - q_off / 128, pq = lay.pq, pk = lay.pk;
-  dim3 gwq((unsigned)pq * nq * batch), gwk((unsigned)pk * nq * batch), gq(nblk_q * 16, nq, batch), gk(nblk * 32, nkv, batch);
+  dim3 gw((unsigned)(pq + pk) * nq * batch), gwq((unsigned)pq * nq * batch), gwk((unsigned)pk * nq * batch), gq(nblk_q * 16, nq, batch),
+      gk(nblk * 32, nkv, batch);
   const unsigned nb_q = part_q ? gq.x * gq.y * gq.z : 0, nb_k = part_kv ? gk.x * gk.y * gk.z : 0;
   const size_t lds_dq = 2 * AB_RING * (size_t)AB_KT * d * 2, lds_dkv = lds_dq + 2 * AB_RING * AB_KT * sizeof(float);
   static bool ready_dev[DH_MAX_DEVICES][2] = {};
@@ -1131,12 +1194,20 @@ int dh_launch_attn_bwd_bf16(int batch, int seq_q, int nq, int nkv, int d, const 
 #define DH_ATTN_BWD(DD, IDX)                                                                                                   \
   do {                                                                                                                         \
     if (!ready[IDX]) {                                                                                                         \
-      if ((rc = set_lds(attn_bwd_dq_bf16_kernel<DD>, lds_dq)) || (rc = set_lds(attn_bwd_dkv_bf16_kernel<DD>, lds_dkv))) return rc; \
+      if ((rc = set_lds(attn_bwd_bf16_kernel<DD>, lds_dkv)) || (rc = set_lds(attn_bwd_dq_bf16_kernel<DD>, lds_dq)) ||          \
+          (rc = set_lds(attn_bwd_dkv_bf16_kernel<DD>, lds_dkv))) return rc;                                                    \
       ready[IDX] = true;                                                                                                       \
     }                                                                                                                          \
-    attn_bwd_dq_bf16_kernel<DD><<<gwq, AB_THREADS, lds_dq, stream>>>(gq_geom, qkv, o, dout, lse, lse2, delta, dqkv, part_q, pq, T, sc, sl2); \
-    DH_LAUNCH_CHECK();                                                                                                         \
-    attn_bwd_dkv_bf16_kernel<DD><<<gwk, AB_THREADS, lds_dkv, stream>>>(gk_geom, qkv, dout, lse2, delta, part_kv, pk, T, sc, sl2);      \
+    if (nq == nkv) {                                                                                                           \
+      attn_bwd_prep_kernel<DD><<<(unsigned)(((size_t)T * nq + 255) / 256), 256, 0, stream>>>(o, dout, lse, lse2, delta, T, nq); \
+      DH_LAUNCH_CHECK();                                                                                                       \
+      attn_bwd_bf16_kernel<DD><<<gw, AB_THREADS, lds_dkv, stream>>>(gq_geom, gk_geom, qkv, o, dout, lse, lse2, delta, dqkv, part_q, \
+                                                                   part_kv, pq, pk, T, sc, sl2);                               \
+    } else {                                                                                                                   \
+      attn_bwd_dq_bf16_kernel<DD><<<gwq, AB_THREADS, lds_dq, stream>>>(gq_geom, qkv, o, dout, lse, lse2, delta, dqkv, part_q, pq, T, sc, sl2); \
+      DH_LAUNCH_CHECK();                                                                                                       \
+      attn_bwd_dkv_bf16_kernel<DD><<<gwk, AB_THREADS, lds_dkv, stream>>>(gk_geom, qkv, dout, lse2, delta, part_kv, pk, T, sc, sl2); \
+    }                                                                                                                          \
     DH_LAUNCH_CHECK();                                                                                                         \
     if (nb_q + nb_k > 0) {                                                                                                     \
       attn_bwd_reduce_kernel<DD><<<nb_q + nb_k, 256, 0, stream>>>(part_q, dqkv, pq, lay.ch_q, sc, nb_q, gq.x, gq.y, part_kv, gk_geom, pk, \
