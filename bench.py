@@ -496,7 +496,7 @@ def main():
     dh.dh_layer_set_beta_comm_stream(run.layer, scb)
     tf20, tb20 = dh.dh_profile_solo(run.layer, alpha.fwd_args, beta.bwd_args, run.ws, run.ws_bytes, sa, sb, sc, 20)
     dh.dh_layer_set_beta_comm_stream(run.layer, cb_best)
-    ops = []
+    ops, fused = [], []
     total_solo = sum(tf20[:nf]) + sum(tb20[:nb])
     for names, ts in ((fnames, tf20), (bnames, tb20)):
         for k, name in enumerate(names):
@@ -504,6 +504,9 @@ def main():
             if w is None:
                 continue
             kind, amount = w
+            if ts[k] < 1e-6:   # launches nothing: SwiGLU merged into the neighbouring GEMM's epilogue
+                fused.append(name)
+                continue
             peak = BF16_MFMA_PEAK_TFLOPS if kind == "mfma" else HBM_PEAK_GBS
             ach = amount / ts[k] / (1e12 if kind == "mfma" else 1e9)
             ops.append({"op": name, "bound": kind, "solo_us": ts[k] * 1e6, "share_of_solo": ts[k] / total_solo,
@@ -549,7 +552,7 @@ def main():
         "comm_hidden_frac": rec["comm_hidden_frac"], "comm_composition": comp,
         "predicted_ms": rec["predicted_ms"], "predicted_over_measured": rec["predicted_over_measured"],
         "link_rate": link,
-        "roofline": roofline, "roofline_ops": ops,
+        "roofline": roofline, "roofline_ops": ops, "ops_without_launch": fused,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, flops)

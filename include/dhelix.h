@@ -665,6 +665,22 @@ int dh_moe_combine_bwd(int dtype, int T, int H, const void* dy, const void* yp, 
 int dh_gemm_grouped(int dtype, int mode, int n_groups, const int32_t* group_rows, int max_rows,
                     int dim_a, int dim_b, const void* A, const void* B, void* C, void* stream);
 
+/* The feed-forward block's SwiGLU (operator ACT of the layer, Sec. 4.2's operator list; Table 2 bases it on an
+ * element-wise kernel) run inside the epilogue of the GEMM next to it, bf16 only, so that the activation costs no
+ * launch and no second pass over the gate/up tensor.  Results are bit-identical to dh_gemm followed by
+ * dh_swiglu_fwd / dh_swiglu_bwd.  All pointers device, row-major, 16-byte aligned; nothing is allocated.
+ *   forward : gu[T,2F] = x[T,H] * w_gate_up[H,2F] (columns [gate | up]), a[T,F] = gate * sigmoid(gate) * up.
+ *             Fits (dh_gemm_swiglu_fwd_fits = 1) when T % 256 == 0, F % 128 == 0, H % 32 == 0 and the plain GEMM
+ *             would be a single launch of 256x256 tiles.
+ *   backward: dgu[T,2F] = (d gate | d up) from dA = dy[T,H] * w_down[F,H]^T (never stored) and gu[T,2F].
+ *             Fits when the plain GEMM would be a single launch of whole tiles without a K split.
+ * A shape that does not fit returns DH_ERR_UNSUPPORTED (the caller then uses the two separate operators, as the
+ * layer does); null pointers DH_ERR_INVALID_ARG. */
+int dh_gemm_swiglu_fwd_fits(int T, int F, int H);
+int dh_gemm_swiglu_fwd(int T, int F, int H, const void* x, const void* w_gate_up, void* gu, void* a, void* stream);
+int dh_gemm_swiglu_bwd_fits(int T, int F, int H);
+int dh_gemm_swiglu_bwd(int T, int F, int H, const void* dy, const void* w_down, const void* gu, void* dgu, void* stream);
+
 /* dh_gemm with a bias row: C = opA(A)*opB(B) + bias[N] (bias in the operand dtype; stored results only). */
 int dh_gemm_bias(int dtype, int trans_a, int trans_b, int M, int N, int K, const void* A, const void* B,
                  const void* bias, void* C, int out_f32_accumulate, void* ws, size_t ws_bytes,

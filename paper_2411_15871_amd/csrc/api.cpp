@@ -49,6 +49,21 @@ extern "C" int dh_gemm_grouped(int dtype, int mode, int n_groups, const int32_t*
   DH_FAIL(DH_ERR_INVALID_ARG, "gemm_grouped: unknown dtype %d", dtype);
 }
 
+extern "C" int dh_gemm_swiglu_fwd_fits(int T, int F, int H) { return dh_glu_fwd_fits(T, F, H) ? 1 : 0; }
+extern "C" int dh_gemm_swiglu_bwd_fits(int T, int F, int H) { return dh_glu_bwd_fits(T, F, H) ? 1 : 0; }
+
+extern "C" int dh_gemm_swiglu_fwd(int T, int F, int H, const void* x, const void* w_gate_up, void* gu, void* a, void* stream) {
+  if (!dh_glu_fwd_fits(T, F, H)) DH_FAIL(DH_ERR_UNSUPPORTED, "gemm_swiglu_fwd: T=%d F=%d H=%d does not fit the fused kernel", T, F, H);
+  if (!x || !w_gate_up || !gu || !a) DH_FAIL(DH_ERR_INVALID_ARG, "gemm_swiglu_fwd: null pointer");
+  return dh_launch_gemm_swiglu_fwd_bf16(T, F, H, (const bf16_t*)x, (const bf16_t*)w_gate_up, (bf16_t*)gu, (bf16_t*)a, (hipStream_t)stream);
+}
+
+extern "C" int dh_gemm_swiglu_bwd(int T, int F, int H, const void* dy, const void* w_down, const void* gu, void* dgu, void* stream) {
+  if (!dh_glu_bwd_fits(T, F, H)) DH_FAIL(DH_ERR_UNSUPPORTED, "gemm_swiglu_bwd: T=%d F=%d H=%d does not fit the fused kernel", T, F, H);
+  if (!dy || !w_down || !gu || !dgu) DH_FAIL(DH_ERR_INVALID_ARG, "gemm_swiglu_bwd: null pointer");
+  return dh_launch_gemm_swiglu_bwd_bf16(T, F, H, (const bf16_t*)dy, (const bf16_t*)w_down, (const bf16_t*)gu, (bf16_t*)dgu, (hipStream_t)stream);
+}
+
 extern "C" size_t dh_gemm_workspace_bytes(int dtype, int trans_a, int trans_b, int M, int N, int K) {
   if (dtype != DH_BF16 || M <= 0 || N <= 0 || K <= 0) return 0;
   return dh_gemm_bf16_ws_bytes(trans_a != 0, trans_b != 0, M, N, K);

@@ -389,6 +389,7 @@ __device__ __forceinline__ void wave_rows_out_bf16(bf16_t* reg, int lane, Quad q
     if (dst != nullptr) *reinterpret_cast<bf16x8*>(dst + ch * 8) = v;
   }
 }
+#define AF_TAU 8.0f  // log2 of the headroom a row's probabilities may take over its reference maximum
 template <int D>
 __global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(const AttnGeom g, const bf16_t* __restrict__ qkv,
                                                                    bf16_t* __restrict__ o, float* __restrict__ lse, int T,
@@ -479,26 +480,34 @@ __global__ __launch_bounds__(AB_THREADS, 2) void attn_fwd_bf16_kernel(const Attn
 #pragma unroll
     for (int r = 1; r < 16; r++) mx = fmaxf(mx, fmaxf(st[0][r], st[1][r]));
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float mn = fmaxf(m, mx * scale_log2);  // finite from the unit's first tile on: its first key is visible to every row
-    const float alpha = fast_exp2(m - mn);
+    // The reference maximum m of a row moves only when some row of the wave outgrows its reference by more than
+    // 2^AF_TAU (then every row takes its true maximum and the accumulators are rescaled); otherwise the tile's
+    // probabilities are formed against the old reference and may reach 2^AF_TAU, which float32 sums and the bf16 P
+    // fragments hold without loss of relative precision.  The result depends on m only through rounding: the
+    // normalisation by l at the end and lse = m + log2 l use the same reference.  After the first few tiles of a row the
+    // rescaling (one multiply per accumulator element per tile) almost never runs.
+    const float mnew = mx * scale_log2;  // finite from the unit's first tile on: its first key is visible to every row
     float rs = 0.f;
-#pragma unroll
-    for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-      for (int r = 0; r < 16; r++) {
-        const float p = fast_exp2(fmaf(st[mt][r], scale_log2, -mn));
-        st[mt][r] = p;
-        rs += p;
-      }
-    rs += __shfl_xor(rs, 32, 64);
-    l = l * alpha + rs;
-    m = mn;
-    if (__any(alpha != 1.0f)) {
+    if (__any(mnew > m + AF_TAU)) {
+      const float mn = fmaxf(m, mnew);
+      const float alpha = fast_exp2(m - mn);
+      l *= alpha;
+      m = mn;
 #pragma unroll
       for (int dt = 0; dt < D / 32; dt++)
 #pragma unroll
         for (int r = 0; r < 16; r++) ot[dt][r] *= alpha;
     }
+#pragma unroll
+    for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const float p = fast_exp2(fmaf(st[mt][r], scale_log2, -m));
+        st[mt][r] = p;
+        rs += p;
+      }
+    rs += __shfl_xor(rs, 32, 64);
+    l += rs;
 #pragma unroll
     for (int mt = 0; mt < 2; mt++)
 #pragma unroll

@@ -126,6 +126,18 @@ template <> struct Vec8<bf16_t> {
   }
 };
 
+// SwiGLU element arithmetic with every rounding spelled out (no contraction into fused multiply-adds), so that the
+// row-wise kernels and the GEMM epilogues that fuse them give the same bits.
+__device__ __forceinline__ float swiglu_fwd_elem(float g, float u) {
+  return __fmul_rn(__fdiv_rn(g, __fadd_rn(1.0f, expf(-g))), u);
+}
+__device__ __forceinline__ void swiglu_bwd_elem(float g, float u, float d, float& dg, float& du) {
+  const float s = __fdiv_rn(1.0f, __fadd_rn(1.0f, expf(-g)));
+  const float gs = __fmul_rn(g, s);  // g * sigmoid(g)
+  dg = __fmul_rn(__fmul_rn(__fmul_rn(d, u), s), __fadd_rn(1.0f, __fmul_rn(g, __fsub_rn(1.0f, s))));
+  du = __fmul_rn(d, gs);
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
@@ -157,6 +169,12 @@ int dh_launch_gemm_grouped_f32(int mode, int n_groups, const int32_t* group_rows
 int dh_launch_gemm_grouped_bf16(int mode, int n_groups, const int32_t* group_rows, int max_rows, int dim_a, int dim_b,
                                 const bf16_t* A, const bf16_t* B, void* C, hipStream_t stream);
 size_t dh_gemm_bf16_ws_bytes(bool ta, bool tb, int M, int N, int K);
+// SwiGLU fused into the epilogue of the gate/up projection (forward) and of the down projection's data gradient
+// (backward); *_fits says whether the shapes allow it (otherwise: the GEMM, then the row-wise kernel).
+bool dh_glu_fwd_fits(int T, int F, int H);
+int dh_launch_gemm_swiglu_fwd_bf16(int T, int F, int H, const bf16_t* x, const bf16_t* Wgu, bf16_t* gu, bf16_t* a, hipStream_t stream);
+bool dh_glu_bwd_fits(int T, int F, int H);
+int dh_launch_gemm_swiglu_bwd_bf16(int T, int F, int H, const bf16_t* dy, const bf16_t* Wd, const bf16_t* gu, bf16_t* dgu, hipStream_t stream);
 // Attention launchers: seq = queries per sequence; kv == nullptr selects plain causal attention over the packed
 // qkv rows, otherwise keys/values come from kv[batch*(q_off+seq), ldkv] and their gradients go to dkv likewise.
 int dh_launch_attn_fwd_f32(int batch, int seq, int nq, int nkv, int d, const float* qkv, const float* kv, int ldkv,

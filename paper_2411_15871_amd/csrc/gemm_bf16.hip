@@ -61,7 +61,16 @@ struct GemmArgs {
   // are issued apart with K split over blockIdx.y, so that the round is short; tile_first = launch index of this
   // launch's first tile; EPI_TAIL_F32 writes tile-local float32 partials [split][tile][BM][BN].
   int tile_first;
+  // SwiGLU fused into the epilogue (whole tiles only, bf16 result).  GLU_FWD: the GEMM is the gate/up projection with
+  // N = 2*glu_f columns [gate | up]; a tile takes 128 gate columns and the 128 up columns of the same outputs (its B
+  // panel is fetched from two places), stores both to C and gate*sigmoid(gate)*up to glu_out [M, glu_f].
+  // GLU_BWD: the GEMM yields dA [M, N = glu_f]; instead of storing it the epilogue reads gate/up from glu_in
+  // [M, 2*glu_f] and stores d(gate), d(up) to C [M, 2*glu_f].  Element arithmetic: swiglu_*_elem, as the row-wise kernels.
+  int glu_mode, glu_f;
+  const bf16_t* glu_in;
+  bf16_t* glu_out;
 };
+enum { GLU_NONE = 0, GLU_FWD = 1, GLU_BWD = 2 };
 
 // Launch index -> tile coordinates.  XCD-aware: launch indices go round-robin over the 8 XCDs, each XCD owns a
 // contiguous range of the logical tile order, which walks the tiles in bands of 4 tile rows.
@@ -108,9 +117,10 @@ __device__ __forceinline__ void dma16_base(const void* sbase, uint32_t voff, uin
 // Per-lane byte offsets of this wave's chunks relative to the tile origin (row r0, k = tile start).
 // Rows/columns beyond the matrix are clamped to the last valid one: they only feed rows/columns of C
 // that are never stored.  (K must not be clamped; ragged K tiles take issue_tile below.)
+// half_jump != 0 (K-major only, whole tiles): the tile's second half of columns lies half_jump columns further on.
 template <int ROWS, int NWAVES, bool KMAJOR>
 __device__ __forceinline__ void tile_offsets(uint32_t (&voff)[ROWS * GB_BK / 8 / 64 / NWAVES], int r0, int R, int K, int wave,
-                                             int lane) {
+                                             int lane, int half_jump = 0) {
   constexpr int IPW = ROWS * GB_BK / 8 / 64 / NWAVES;
 #pragma unroll
   for (int j = 0; j < IPW; j++) {
@@ -118,7 +128,8 @@ __device__ __forceinline__ void tile_offsets(uint32_t (&voff)[ROWS * GB_BK / 8 /
     if (KMAJOR) {
       constexpr int CPR = ROWS / 8;
       const int kr = p / CPR, c = (p % CPR) ^ ((kr & 3) << 2);
-      const int col = min(r0 + c * 8, R - 8) - r0;
+      int col = min(r0 + c * 8, R - 8) - r0;
+      if (half_jump != 0) col = c * 8 + (c * 8 >= ROWS / 2 ? half_jump : 0);
       voff[j] = (uint32_t)(((size_t)kr * R + col) * sizeof(bf16_t));
     } else {
       const int row = p >> 2, c = (p & 3) ^ ((row >> 2) & 3);
@@ -220,6 +231,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmArgs g) {
   int tm, tn;
   if (!tile_of_launch((int)blockIdx.x + g.tile_first, g.tiles_m, g.tiles_n, g.tiles_per_xcd, tm, tn)) return;
   const int m0 = tm * BM, n0 = tn * BN;
+  const bool glu_fwd = !TA && !TB && BN == 256 && g.glu_mode == GLU_FWD;
+  const int nb0 = glu_fwd ? tn * (BN / 2) : n0;  // first column of the tile's B panel (its first half, if fused)
   const int nkt_total = (g.K + GB_BK - 1) / GB_BK;
   const int kt_begin = blockIdx.y * g.kt_per_split;
   const int kt_end = min(nkt_total, kt_begin + g.kt_per_split);
@@ -235,10 +248,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmArgs g) {
   constexpr int IPA = BM * GB_BK / 8 / 64 / NW, IPB = BN * GB_BK / 8 / 64 / NW, IPS = IPA + IPB;
   uint32_t voa[IPA], vob[IPB];
   tile_offsets<BM, NW, TA>(voa, m0, g.M, g.K, wave, lane);
-  tile_offsets<BN, NW, !TB>(vob, n0, g.N, g.K, wave, lane);
+  tile_offsets<BN, NW, !TB>(vob, n0, g.N, g.K, wave, lane, glu_fwd ? g.glu_f - BN / 2 : 0);
   // tile origins at k = 0 and the byte stride of one K step
   const char* a0 = reinterpret_cast<const char*>(g.A + (TA ? (size_t)m0 : (size_t)m0 * g.K));
-  const char* b0 = reinterpret_cast<const char*>(g.B + (TB ? (size_t)n0 * g.K : (size_t)n0));
+  const char* b0 = reinterpret_cast<const char*>(g.B + (TB ? (size_t)n0 * g.K : (size_t)nb0));
   const size_t sa = (TA ? (size_t)GB_BK * g.M : (size_t)GB_BK) * sizeof(bf16_t);
   const size_t sb = (TB ? (size_t)GB_BK : (size_t)GB_BK * g.N) * sizeof(bf16_t);
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem;
@@ -380,6 +393,67 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmArgs g) {
           *reinterpret_cast<bf16x4*>(reg + row * WTN + ((((c0 >> 3) ^ (row & 7)) << 3) | (c0 & 4))) = o;
         }
     __builtin_amdgcn_wave_barrier();
+    if (glu_fwd) {
+      // the wave's 64 columns are gate columns (first two wave columns) or up columns (last two) of outputs nb0 + ...
+      const int cb = nb0 + (wn0 < BN / 2 ? wn0 : g.glu_f - BN / 2 + wn0);
+#pragma unroll
+      for (int it = 0; it < WTM / 8; it++) {
+        const int row = it * 8 + (lane >> 3), ch = lane & 7;
+        const bf16x8 o = *reinterpret_cast<const bf16x8*>(reg + row * WTN + ((ch ^ (row & 7)) << 3));
+        *reinterpret_cast<bf16x8*>(Cb + (size_t)(m0 + wm0 + row) * g.N + cb + ch * 8) = o;
+      }
+      // gate and up of one output sit in the regions of waves two wave columns apart: once every wave has written,
+      // each wave combines half of the rows of its pair (the values as stored, i.e. rounded to bf16)
+      __syncthreads();
+      const int pw = (wave % WN) & 1, hi = (wave % WN) >> 1;
+      const bf16_t* rg = smem + ((wave / WN) * WN + pw) * (WTM * WTN);
+      const bf16_t* ru = rg + 2 * (WTM * WTN);
+#pragma unroll
+      for (int it = 0; it < WTM / 16; it++) {
+        const int row = hi * (WTM / 2) + it * 8 + (lane >> 3), ch = lane & 7;
+        const bf16x8 gv = *reinterpret_cast<const bf16x8*>(rg + row * WTN + ((ch ^ (row & 7)) << 3));
+        const bf16x8 uv = *reinterpret_cast<const bf16x8*>(ru + row * WTN + ((ch ^ (row & 7)) << 3));
+        bf16x8 o;
+#pragma unroll
+        for (int e = 0; e < 8; e++) o[e] = (bf16_t)swiglu_fwd_elem((float)gv[e], (float)uv[e]);
+        *reinterpret_cast<bf16x8*>(g.glu_out + (size_t)(m0 + wm0 + row) * g.glu_f + nb0 + pw * WTN + ch * 8) = o;
+      }
+      return;
+    }
+    if (g.glu_mode == GLU_BWD) {
+      // gate/up of 8 row groups are fetched together (the accumulators' registers are free by now), so that the
+      // epilogue waits for memory twice, not once per row group
+      constexpr int NB = 8;
+      static_assert((WTM / 8) % NB == 0, "row groups come in batches");
+#pragma unroll
+      for (int it0 = 0; it0 < WTM / 8; it0 += NB) {
+        bf16x8 gv[NB], uv[NB];
+#pragma unroll
+        for (int u = 0; u < NB; u++) {
+          const int row = (it0 + u) * 8 + (lane >> 3), ch = lane & 7;
+          const size_t r2 = (size_t)(m0 + wm0 + row) * (2 * (size_t)g.glu_f) + n0 + wn0 + ch * 8;
+          gv[u] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(g.glu_in + r2));
+          uv[u] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(g.glu_in + r2 + g.glu_f));
+        }
+#pragma unroll
+        for (int u = 0; u < NB; u++) {
+          const int row = (it0 + u) * 8 + (lane >> 3), ch = lane & 7;
+          const size_t r2 = (size_t)(m0 + wm0 + row) * (2 * (size_t)g.glu_f) + n0 + wn0 + ch * 8;
+          const bf16x8 o = *reinterpret_cast<const bf16x8*>(reg + row * WTN + ((ch ^ (row & 7)) << 3));
+          bf16x8 dg, du;
+#pragma unroll
+          for (int e = 0; e < 8; e++) {
+            float a, b;
+            swiglu_bwd_elem((float)gv[u][e], (float)uv[u][e], (float)o[e], a, b);
+            dg[e] = (bf16_t)a;
+            du[e] = (bf16_t)b;
+          }
+          *reinterpret_cast<bf16x8*>(Cb + r2) = dg;
+          *reinterpret_cast<bf16x8*>(Cb + r2 + g.glu_f) = du;
+        }
+      }
+      return;
+    }
 #pragma unroll
     for (int it = 0; it < WTM / 8; it++) {
       const int row = it * 8 + (lane >> 3), ch = lane & 7;
@@ -623,6 +697,7 @@ int dh_launch_gemm_bf16(bool ta, bool tb, int M, int N, int K, const bf16_t* A, 
   g.tiles_m = g.tiles_n = g.tiles_per_xcd = 0;
   g.bias = bias; g.group_rows = nullptr; g.group_mode = 0;
   g.group_part = 0; g.n_groups = 1; g.part1_bm = g.part1_bn = 256; g.cus = 0; g.tile_first = 0;
+  g.glu_mode = GLU_NONE; g.glu_f = 0; g.glu_in = nullptr; g.glu_out = nullptr;
   const int final_epi = out_f32_accumulate ? EPI_ACC_F32 : EPI_STORE_BF16;
   int rc;
   if (p.tail_tiles > 0) {  // whole rounds with the final epilogue, then the last round's tiles with K split, then their sum
@@ -651,6 +726,48 @@ int dh_launch_gemm_bf16(bool ta, bool tb, int M, int N, int K, const bf16_t* A, 
   return DH_OK;
 }
 
+// Gate/up projection with SwiGLU in its epilogue: gu[T, 2F] = x[T, H] * Wgu[H, 2F] (columns [gate | up]) and
+// a[T, F] = gate * sigmoid(gate) * up computed from the stored (rounded) values -- the same bits as
+// dh_launch_gemm_bf16 followed by the row-wise kernel.  Fits when the plain GEMM would be one launch of whole 256x256
+// tiles and F is a multiple of 128 (a tile = 128 gate + the 128 matching up columns).
+bool dh_glu_fwd_fits(int T, int F, int H) {
+  if (T <= 0 || F <= 0 || H <= 0 || T % 256 || F % 128 || H % GB_BK) return false;
+  const GemmPlan p = choose_plan(false, T, 2 * F, H, (size_t)-1);
+  return p.cfg == 0 && p.splits == 1 && p.tail_tiles == 0;
+}
+int dh_launch_gemm_swiglu_fwd_bf16(int T, int F, int H, const bf16_t* x, const bf16_t* Wgu, bf16_t* gu, bf16_t* a, hipStream_t stream) {
+  if (!dh_glu_fwd_fits(T, F, H)) DH_FAIL(DH_ERR_SHAPE, "gemm+swiglu forward: T=%d F=%d H=%d does not fit the fused kernel", T, F, H);
+  GemmArgs g;
+  g.M = T; g.N = 2 * F; g.K = H; g.A = x; g.B = Wgu; g.C = gu; g.epi = EPI_STORE_BF16;
+  g.kt_per_split = H / GB_BK;
+  g.tiles_m = g.tiles_n = g.tiles_per_xcd = 0;
+  g.bias = nullptr; g.group_rows = nullptr; g.group_mode = 0;
+  g.group_part = 0; g.n_groups = 1; g.part1_bm = g.part1_bn = 256; g.cus = 0; g.tile_first = 0;
+  g.glu_mode = GLU_FWD; g.glu_f = F; g.glu_in = nullptr; g.glu_out = a;
+  return launch_cfg<256, 256, 2, 4, false, false>(g, 1, stream);
+}
+
+// Data gradient of the down projection with SwiGLU's backward in its epilogue: dA = dY[T, H] * Wd[F, H]^T is not
+// stored; dgu[T, 2F] = (d gate | d up) from dA (rounded to bf16 as the stored dA would be) and gu[T, 2F] -- the same
+// bits as the GEMM followed by the row-wise kernel.  Fits when the plain GEMM would be one launch of whole tiles.
+bool dh_glu_bwd_fits(int T, int F, int H) {
+  if (T <= 0 || F <= 0 || H <= 0 || F % 8 || H % 8) return false;
+  const GemmPlan p = choose_plan(false, T, F, H, (size_t)-1);
+  return p.splits == 1 && p.tail_tiles == 0 && T % p.bm == 0 && F % p.bn == 0;
+}
+int dh_launch_gemm_swiglu_bwd_bf16(int T, int F, int H, const bf16_t* dy, const bf16_t* Wd, const bf16_t* gu, bf16_t* dgu, hipStream_t stream) {
+  if (!dh_glu_bwd_fits(T, F, H)) DH_FAIL(DH_ERR_SHAPE, "gemm+swiglu backward: T=%d F=%d H=%d does not fit the fused kernel", T, F, H);
+  const GemmPlan p = choose_plan(false, T, F, H, (size_t)-1);
+  GemmArgs g;
+  g.M = T; g.N = F; g.K = H; g.A = dy; g.B = Wd; g.C = dgu; g.epi = EPI_STORE_BF16;
+  g.kt_per_split = p.kt_per_split;
+  g.tiles_m = g.tiles_n = g.tiles_per_xcd = 0;
+  g.bias = nullptr; g.group_rows = nullptr; g.group_mode = 0;
+  g.group_part = 0; g.n_groups = 1; g.part1_bm = g.part1_bn = 256; g.cus = 0; g.tile_first = 0;
+  g.glu_mode = GLU_BWD; g.glu_f = F; g.glu_in = gu; g.glu_out = nullptr;
+  return launch_layout<false, true>(g, p, stream);
+}
+
 // Grouped GEMM with device-side row counts (expert routing is data): group z owns group_rows[z] consecutive
 // rows, max_rows bounds any group (the grid is sized for it).  mode 0: C[rows,dim_b] = A[rows,dim_a] B_z[dim_a,dim_b];
 // mode 1: C[rows,dim_b] = A[rows,dim_a] B_z[dim_b,dim_a]^T; mode 2: C_z[dim_a,dim_b] += A[rows,dim_a]^T B[rows,dim_b]
@@ -664,6 +781,7 @@ int dh_launch_gemm_grouped_bf16(int mode, int n_groups, const int32_t* group_row
   g.bias = nullptr; g.group_rows = group_rows; g.group_mode = mode;
   g.tiles_m = g.tiles_n = g.tiles_per_xcd = 0;
   g.group_part = 0; g.n_groups = n_groups; g.part1_bm = g.part1_bn = 256; g.cus = num_cus(); g.tile_first = 0;
+  g.glu_mode = GLU_NONE; g.glu_f = 0; g.glu_in = nullptr; g.glu_out = nullptr;
   const int avg = std::max(1, max_rows / n_groups);
   GemmPlan p;
   if (mode == 2) { g.M = dim_a; g.N = dim_b; g.K = max_rows; p = choose_plan(true, dim_a, dim_b, avg, 0); }

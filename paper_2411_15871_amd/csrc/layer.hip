@@ -25,6 +25,9 @@ struct dh_layer {
   size_t f_kvrecv, b_dkv;
   hipStream_t cross_stream;
   hipStream_t beta_comm_stream;  // beta's collectives in SI steps (nullptr: where alpha's go)
+  // SwiGLU runs in the epilogue of the gate/up projection (forward) / of the down projection's data gradient (backward)
+  // where the shapes allow; the activation operator of that direction then launches nothing
+  bool fuse_act_fwd, fuse_act_bwd;
   // forward workspace offsets
   size_t f_hs, f_part, f_red, f_xp, f_yg, f_attn, f_attn_bytes, f_gemm, f_gemm_bytes, fwd_bytes;
   // backward workspace offsets
@@ -249,6 +252,9 @@ extern "C" int dh_layer_create(const dh_layer_config* cfg, dh_layer** out) {
   L->T = c.batch * c.seq;
   L->Ts = c.arch == DH_ARCH_GPT ? L->T / c.n_ranks : L->T;
   L->Tf = c.arch == DH_ARCH_MOE ? 2 * L->T : L->T;
+  const bool glu_layer = c.dtype == DH_BF16 && (c.arch == DH_ARCH_LLAMA || c.arch == DH_ARCH_LLAMA_CP);
+  L->fuse_act_fwd = glu_layer && dh_glu_fwd_fits(L->T, c.ffn, c.hidden);
+  L->fuse_act_bwd = glu_layer && dh_glu_bwd_fits(L->T, c.ffn, c.hidden);
   L->n_qkv = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
   L->n_o = c.n_q_heads * c.head_dim;
   L->es = dh_elem_size(c.dtype);
@@ -471,8 +477,12 @@ static int llama_fwd_op(dh_layer* L, int op, const dh_fwd_args& a, char* ws, hip
     case DH_F_NORM2:  // x2 = x + y (residual of the bias-dropout-add operator), h2 = norm(x2)
       return dh_rmsnorm_fwd(dt, T, H, a.x, ws + L->f_red, L->w.g2, c.eps, sv + L->s_x2, sv + L->s_h2, (float*)(sv + L->s_rstd2), s);
     case DH_F_FC1:
+      if (L->fuse_act_fwd)
+        return dh_launch_gemm_swiglu_fwd_bf16(T, F, H, (const bf16_t*)(sv + L->s_h2), (const bf16_t*)L->w.Wgu, (bf16_t*)(sv + L->s_gu),
+                                              (bf16_t*)(sv + L->s_a), s);
       return gemm(L, false, false, T, 2 * F, H, sv + L->s_h2, L->w.Wgu, sv + L->s_gu, false, gws, L->f_gemm_bytes, s);
     case DH_F_ACT:
+      if (L->fuse_act_fwd) return DH_OK;  // done by F_FC1's epilogue
       return dh_swiglu_fwd(dt, T, F, sv + L->s_gu, sv + L->s_a, s);
     case DH_F_FC2:
       return gemm(L, false, false, T, H, F, sv + L->s_a, L->w.Wd, ws + L->f_part, false, gws, L->f_gemm_bytes, s);
@@ -494,10 +504,14 @@ static int llama_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hip
   const size_t gwb = side_ws ? L->f_gemm_bytes : L->b_gemm_bytes, n = (size_t)T * H;
   switch (op) {
     case DH_B_FC2_DGRAD:
+      if (L->fuse_act_bwd)
+        return dh_launch_gemm_swiglu_bwd_bf16(T, F, H, (const bf16_t*)b.dout, (const bf16_t*)L->w.Wd, (const bf16_t*)(sv + L->s_gu),
+                                              (bf16_t*)(ws + L->b_dgu), s);
       return gemm(L, false, true, T, F, H, b.dout, L->w.Wd, ws + L->b_da, false, gws, gwb, s);
     case DH_B_FC2_WGRAD:
       return gemm(L, true, false, F, H, T, sv + L->s_a, b.dout, L->g.dWd, true, gws, gwb, s);
     case DH_B_ACT:
+      if (L->fuse_act_bwd) return DH_OK;  // done by B_FC2_DGRAD's epilogue
       return dh_swiglu_bwd(dt, T, F, sv + L->s_gu, ws + L->b_da, ws + L->b_dgu, s);
     case DH_B_FC1_DGRAD:
       return gemm(L, false, true, T, H, 2 * F, ws + L->b_dgu, L->w.Wgu, ws + L->b_part, false, gws, gwb, s);
@@ -1171,17 +1185,23 @@ extern "C" int dh_profile_solo(dh_layer* L, const dh_fwd_args* alpha, const dh_b
       const hipStream_t base = dir == 1 && sc != nullptr && L->beta_comm_stream != nullptr ? L->beta_comm_stream : sc;
       hipStream_t s = comm ? comm_stream_of(L, comm, base) : nullptr;
       if (!s) s = dir == 0 ? sa : sb;
-      for (int r = 0; r < reps + 1; r++) {  // one warm-up launch, then the timed ones
-        if (r == 1) (void)hipEventRecord(e0, s);
-        rc = dir == 0 ? run_fwd_op(L, op, *alpha, ws_f, s) : run_bwd_op(L, op, *beta, ws_b, s);
-        if (rc) { cleanup(); return rc; }
+      // one warm-up launch, then two timed groups of reps launches; the shorter group counts (a hiccup of the machine --
+      // a clock ramp, a first touch -- lengthens one group, not both)
+      double best = 1e30;
+      for (int grp = 0; grp < 2; grp++) {
+        for (int r = (grp == 0 ? 0 : 1); r < reps + 1; r++) {
+          if (r == 1) (void)hipEventRecord(e0, s);
+          rc = dir == 0 ? run_fwd_op(L, op, *alpha, ws_f, s) : run_bwd_op(L, op, *beta, ws_b, s);
+          if (rc) { cleanup(); return rc; }
+        }
+        (void)hipEventRecord(e1, s);
+        he = hipEventSynchronize(e1);
+        if (he != hipSuccess) { cleanup(); return dh_set_error(DH_ERR_HIP, "profile_solo: %s", hipGetErrorString(he)); }
+        float ms = 0.f;
+        (void)hipEventElapsedTime(&ms, e0, e1);
+        best = std::min(best, (double)ms * 1e-3 / reps);
       }
-      (void)hipEventRecord(e1, s);
-      he = hipEventSynchronize(e1);
-      if (he != hipSuccess) { cleanup(); return dh_set_error(DH_ERR_HIP, "profile_solo: %s", hipGetErrorString(he)); }
-      float ms = 0.f;
-      (void)hipEventElapsedTime(&ms, e0, e1);
-      (dir == 0 ? t_fwd : t_bwd)[op] = std::max((double)ms * 1e-3 / reps, 1e-7);
+      (dir == 0 ? t_fwd : t_bwd)[op] = std::max(best, 1e-7);
     }
   cleanup();
   return DH_OK;
@@ -1231,17 +1251,23 @@ extern "C" int dh_profile_pairs(dh_layer* L, const dh_fwd_args* alpha, const dh_
       hipStream_t s = stream_of(dir, op);
       TimedOp t{dir, op};
       if ((rc = launch_op(L, t, *alpha, *beta, ws_f, ws_b, s))) { cleanup(); return rc; }  // warm-up
-      (void)hipEventRecord(e0, s);
-      for (int r = 0; r < reps; r++)
-        if ((rc = launch_op(L, t, *alpha, *beta, ws_f, ws_b, s))) { cleanup(); return rc; }
-      (void)hipEventRecord(e1, s);
-      hipError_t he = hipEventSynchronize(e1);
-      if (he != hipSuccess) { cleanup(); return dh_set_error(DH_ERR_HIP, "profile: %s", hipGetErrorString(he)); }
-      float ms = 0.f;
-      (void)hipEventElapsedTime(&ms, e0, e1);
-      // an operator that launches nothing (a Send/Recv stand-in with no peer) measures ~0: floor it, so that the
-      // repeat counts, rates and Eq. 1 below stay finite
-      (dir == 0 ? out->t_fwd : out->t_bwd)[op] = std::max((double)ms * 1e-3 / reps, 1e-7);
+      // two timed groups of reps launches, the shorter one counts: a hiccup of the machine (a clock ramp, a first touch)
+      // lengthens one group, not both, and every pair measurement below is sized from these times
+      double best = 1e30;
+      for (int grp = 0; grp < 2; grp++) {
+        (void)hipEventRecord(e0, s);
+        for (int r = 0; r < reps; r++)
+          if ((rc = launch_op(L, t, *alpha, *beta, ws_f, ws_b, s))) { cleanup(); return rc; }
+        (void)hipEventRecord(e1, s);
+        hipError_t he = hipEventSynchronize(e1);
+        if (he != hipSuccess) { cleanup(); return dh_set_error(DH_ERR_HIP, "profile: %s", hipGetErrorString(he)); }
+        float ms = 0.f;
+        (void)hipEventElapsedTime(&ms, e0, e1);
+        best = std::min(best, (double)ms * 1e-3 / reps);
+      }
+      // an operator that launches nothing (a Send/Recv stand-in with no peer, an activation that runs in its
+      // neighbour's epilogue) measures ~0: floor it, so that the repeat counts, rates and Eq. 1 below stay finite
+      (dir == 0 ? out->t_fwd : out->t_bwd)[op] = std::max(best, 1e-7);
     }
   }
   // pairs: both operators repeated so that the two streams stay busy for about the same window

@@ -241,7 +241,7 @@ __global__ void swiglu_fwd_kernel(const T* __restrict__ gu, T* __restrict__ a, i
   g.load(gu + row * 2 * F + col);
   u.load(gu + row * 2 * F + F + col);
 #pragma unroll
-  for (int i = 0; i < 8; i++) o.v[i] = g.v[i] / (1.0f + expf(-g.v[i])) * u.v[i];
+  for (int i = 0; i < 8; i++) o.v[i] = swiglu_fwd_elem(g.v[i], u.v[i]);
   o.store(a + row * F + col);
 }
 
@@ -257,11 +257,7 @@ __global__ void swiglu_bwd_kernel(const T* __restrict__ gu, const T* __restrict_
   u.load(gu + row * 2 * F + F + col);
   d.load(da + row * F + col);
 #pragma unroll
-  for (int i = 0; i < 8; i++) {
-    float s = 1.0f / (1.0f + expf(-g.v[i]));
-    og.v[i] = d.v[i] * u.v[i] * s * (1.0f + g.v[i] * (1.0f - s));
-    ou.v[i] = d.v[i] * g.v[i] * s;
-  }
+  for (int i = 0; i < 8; i++) swiglu_bwd_elem(g.v[i], u.v[i], d.v[i], og.v[i], ou.v[i]);
   og.store(dgu + row * 2 * F + col);
   ou.store(dgu + row * 2 * F + F + col);
 }

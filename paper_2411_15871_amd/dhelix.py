@@ -186,6 +186,10 @@ SIGNATURES = {
     "dh_rope_pairs": (_I, [_I, _I, _I, _I, _I, _I, _I, _I, _F, _I, _P, _P]),
     "dh_swiglu_fwd": (_I, [_I, _I, _I, _P, _P, _P]),
     "dh_swiglu_bwd": (_I, [_I, _I, _I, _P, _P, _P, _P]),
+    "dh_gemm_swiglu_fwd_fits": (_I, [_I, _I, _I]),
+    "dh_gemm_swiglu_fwd": (_I, [_I, _I, _I, _P, _P, _P, _P, _P]),
+    "dh_gemm_swiglu_bwd_fits": (_I, [_I, _I, _I]),
+    "dh_gemm_swiglu_bwd": (_I, [_I, _I, _I, _P, _P, _P, _P, _P]),
     "dh_add": (_I, [_I, _Z, _P, _P, _P, _P]),
     "dh_attn_fwd": (_I, [_I, _I, _I, _I, _I, _I, _P, _P, _P, _P, _Z, _P]),
     "dh_attn_fwd_workspace_bytes": (_Z, [_I, _I, _I, _I, _I, _I]),
@@ -598,6 +602,22 @@ def dh_swiglu_fwd(dtype, T, F, gu, a, stream=None):
 
 def dh_swiglu_bwd(dtype, T, F, gu, da, dgu, stream=None):
     _check(lib.dh_swiglu_bwd(dtype, T, F, _ptr(gu), _ptr(da), _ptr(dgu), _stream(stream)))
+
+
+def dh_gemm_swiglu_fwd_fits(T, F, H):
+    return bool(lib.dh_gemm_swiglu_fwd_fits(T, F, H))
+
+
+def dh_gemm_swiglu_fwd(T, F, H, x, w_gate_up, gu, a, stream=None):
+    _check(lib.dh_gemm_swiglu_fwd(T, F, H, _ptr(x), _ptr(w_gate_up), _ptr(gu), _ptr(a), _stream(stream)))
+
+
+def dh_gemm_swiglu_bwd_fits(T, F, H):
+    return bool(lib.dh_gemm_swiglu_bwd_fits(T, F, H))
+
+
+def dh_gemm_swiglu_bwd(T, F, H, dy, w_down, gu, dgu, stream=None):
+    _check(lib.dh_gemm_swiglu_bwd(T, F, H, _ptr(dy), _ptr(w_down), _ptr(gu), _ptr(dgu), _stream(stream)))
 
 
 def dh_add(dtype, n, a, b, out, stream=None):

@@ -274,6 +274,59 @@ def test_gemm_bf16(dh, ta, tb, M, N, K):
     assert rel(host(Cn), ref) <= 2e-5
 
 
+# T, F, H.  The forward fusion needs at least 128 tiles of 256x256 (the first shape has too few: the error path), the
+# backward one runs with each of the three tile shapes; K of 2, 3 and 5 ring steps and a long one; the Llama-8B
+# shard's width (14 column tiles).
+GLU_SHAPES = [(512, 256, 64), (4096, 1024, 96), (2048, 2048, 160), (4096, 2048, 64), (4096, 1792, 1024)]
+
+
+@pytest.mark.parametrize("T,F,H", GLU_SHAPES)
+def test_gemm_swiglu_fused(dh, T, F, H):
+    """SwiGLU inside the GEMM epilogues (operator ACT of the layer merged into FC1 / FC2's data gradient): bit-identical to the
+    GEMM followed by the row-wise kernel, and both within tolerance of the fp64 definition."""
+    x = gen.normal(60, (T, H), 1.0, 0.0, True); w1 = gen.normal(61, (H, 2 * F), 0.05, 0.0, True)
+    wd = gen.normal(62, (F, H), 0.05, 0.0, True); dy = gen.normal(63, (T, H), 1.0, 0.0, True)
+    xd, w1d, wdd, dyd = dev(x, True), dev(w1, True), dev(wd, True), dev(dy, True)
+    mk = lambda *shape: torch.zeros(shape, dtype=torch.bfloat16, device="cuda")
+    wsb = max(dh.dh_gemm_workspace_bytes(dh.DH_BF16, 0, 0, T, 2 * F, H), dh.dh_gemm_workspace_bytes(dh.DH_BF16, 0, 1, T, F, H))
+    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+    # forward: separate operators, then fused
+    gu0, a0 = mk(T, 2 * F), mk(T, F)
+    dh.dh_gemm(dh.DH_BF16, 0, 0, T, 2 * F, H, xd, w1d, gu0, False, ws, wsb)
+    dh.dh_swiglu_fwd(dh.DH_BF16, T, F, gu0, a0)
+    ref_gu = x.astype(np.float64) @ w1.astype(np.float64)
+    g, u = ref_gu[:, :F], ref_gu[:, F:]
+    ref_a = g / (1 + np.exp(-g)) * u
+    assert rel(host(gu0), ref_gu) <= 4e-3 and rel(host(a0), ref_a) <= 2e-2
+    print("fwd fits:", dh.dh_gemm_swiglu_fwd_fits(T, F, H), " bwd fits:", dh.dh_gemm_swiglu_bwd_fits(T, F, H), flush=True)
+    if dh.dh_gemm_swiglu_fwd_fits(T, F, H):
+        gu1, a1 = mk(T, 2 * F), mk(T, F)
+        dh.dh_gemm_swiglu_fwd(T, F, H, xd, w1d, gu1, a1)
+        assert torch.equal(gu0, gu1) and torch.equal(a0, a1)
+    else:
+        with pytest.raises(dh.DhelixError) as e:
+            dh.dh_gemm_swiglu_fwd(T, F, H, xd, w1d, mk(T, 2 * F), mk(T, F))
+        assert e.value.code == dh.DH_ERR_UNSUPPORTED
+    # backward
+    da0, dgu0 = mk(T, F), mk(T, 2 * F)
+    dh.dh_gemm(dh.DH_BF16, 0, 1, T, F, H, dyd, wdd, da0, False, ws, wsb)
+    dh.dh_swiglu_bwd(dh.DH_BF16, T, F, gu0, da0, dgu0)
+    gq = host(gu0).astype(np.float64)   # the gradient at the stored gate/up values
+    g, u = gq[:, :F], gq[:, F:]
+    sg = 1 / (1 + np.exp(-g))
+    ref_da = dy.astype(np.float64) @ wd.astype(np.float64).T
+    ref_dgu = np.concatenate([ref_da * u * sg * (1 + g * (1 - sg)), ref_da * g * sg], axis=1)
+    assert rel(host(dgu0), ref_dgu) <= 2e-2
+    if dh.dh_gemm_swiglu_bwd_fits(T, F, H):
+        dgu1 = mk(T, 2 * F)
+        dh.dh_gemm_swiglu_bwd(T, F, H, dyd, wdd, gu0, dgu1)
+        assert torch.equal(dgu0, dgu1)
+    else:
+        with pytest.raises(dh.DhelixError) as e:
+            dh.dh_gemm_swiglu_bwd(T, F, H, dyd, wdd, gu0, mk(T, 2 * F))
+        assert e.value.code == dh.DH_ERR_UNSUPPORTED
+
+
 def test_gemm_bf16_shape_errors(dh):
     a = torch.zeros(64 * 64, dtype=torch.bfloat16, device="cuda")
     for args in [(0, 0, 16, 12, 16), (0, 0, 16, 16, 12), (1, 0, 12, 16, 16), (1, 1, 16, 16, 16)]:

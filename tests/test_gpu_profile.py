@@ -14,6 +14,8 @@ pytestmark = pytest.mark.gpu
 CASES = {
     "llama_bf16_mid": dict(arch="llama", batch=1, seq=1024, hidden=1024, nq=4, nkv=1, d=128, ffn=1408, n_ranks=4, bf16=True),
     "gpt_bf16_mid": dict(arch="gpt", batch=2, seq=512, hidden=1024, nq=4, nkv=4, d=128, ffn=2048, n_ranks=4, bf16=True),
+    # shapes at which SwiGLU runs inside the neighbouring GEMMs' epilogues: F_ACT and B_ACT launch nothing
+    "llama_bf16_fused_act": dict(arch="llama", batch=2, seq=2048, hidden=512, nq=4, nkv=1, d=128, ffn=1024, n_ranks=2, bf16=True),
     # rank 0 of a context-parallel group sends nothing back: B_CP_SEND launches no kernel and measures ~0
     "cp_first_rank": dict(arch="llama_cp", batch=1, seq=256, hidden=512, nq=4, nkv=1, d=128, ffn=512, n_ranks=2, bf16=True,
                           cp_ranks=2, cp_rank=0),
@@ -43,6 +45,12 @@ def test_profile_table_entries(name):
         names_b = dh.op_names(H.ARCH[run.cfg["arch"]], 1)
         if name == "cp_first_rank":
             assert t_b[names_b.index("B_CP_SEND")] <= 5e-6  # an operator that launches nothing sits at (about) the floor
+        if name == "llama_bf16_fused_act":
+            names_f = dh.op_names(H.ARCH[run.cfg["arch"]], 0)
+            c = run.cfg
+            assert dh.dh_gemm_swiglu_fwd_fits(c["batch"] * c["seq"], c["ffn"], c["hidden"])
+            assert dh.dh_gemm_swiglu_bwd_fits(c["batch"] * c["seq"], c["ffn"], c["hidden"])
+            assert t_f[names_f.index("F_ACT")] <= 5e-6 and t_b[names_b.index("B_ACT")] <= 5e-6
         for i in range(nf):
             for j in range(nb):
                 assert 0.02 <= rf[i][j] <= 1.0 and 0.02 <= rb[i][j] <= 1.0
@@ -72,6 +80,7 @@ def test_profile_table_entries(name):
                 e0.record(sa); run.bwd(beta, sa); e1.record(sa)
             torch.cuda.synchronize()
             best_b = min(best_b, e0.elapsed_time(e1) * 1e-3)
+        print("solo us, forward:", [round(v * 1e6, 1) for v in t_f], "backward:", [round(v * 1e6, 1) for v in t_b], flush=True)
         print("forward: sum of solo %.1f us, strand %.1f us; backward: %.1f us, %.1f us" %
               (sum(t_f) * 1e6, best_f * 1e6, sum(t_b) * 1e6, best_b * 1e6), flush=True)
         # launch gaps make the strand a little longer than the sum of back-to-back repetitions, clock ramps either way
