@@ -335,6 +335,59 @@ def test_gemm_bf16_shape_errors(dh):
         assert e.value.code in (dh.DH_ERR_SHAPE, dh.DH_ERR_UNSUPPORTED)
 
 
+@pytest.mark.parametrize("batch,seq,nq,nkv,d", [(1, 700, 4, 1, 128), (2, 300, 2, 2, 64), (1, 2100, 2, 1, 128)])
+def test_attention_scores_rising_along_the_keys(dh, batch, seq, nq, nkv, d):
+    """The matrix-core forward keeps a row's reference maximum until a tile outgrows it by 2^8 and only then rescales
+    its accumulators.  Scores that climb by ~90 (base 2) along the keys make that happen about ten times per row, with
+    probabilities above 1 in between; half of the heads keep ordinary scores.  Forward and backward against the fp64
+    definition, row by row."""
+    T = batch * seq
+    nqkv = (nq + 2 * nkv) * d
+    qkv = gen.normal(70, (T, nqkv), 1.0, 0.0, False)
+    u = gen.normal(71, (d,), 1.0, 0.0, False)
+    u /= np.linalg.norm(u)
+    pos = np.tile(np.arange(seq), batch)[:, None]
+    for h in range(0, nq, 2):      # every other query head looks along u with weight 8 sqrt(d)
+        qkv[:, h * d:(h + 1) * d] = 0.1 * qkv[:, h * d:(h + 1) * d] + 8.0 * np.sqrt(d) * u
+    for h in range(nkv):           # keys grow along u: score of key j ~ 8 * 8 j / seq = up to 64 (92 in base 2)
+        c0 = (nq + h) * d
+        qkv[:, c0:c0 + d] = qkv[:, c0:c0 + d] + (8.0 * pos / seq) * u
+    qkv = gen.round_bf16(qkv)
+    do = gen.normal(72, (T, nq * d), 1.0, 0.0, True)
+    qd, dod = dev(qkv, True), dev(do, True)
+    o = torch.empty(T, nq * d, dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty(nq, T, dtype=torch.float32, device="cuda")
+    fwsb = dh.dh_attn_fwd_workspace_bytes(dh.DH_BF16, batch, seq, nq, nkv, d)
+    fws = torch.empty(max(fwsb, 16), dtype=torch.uint8, device="cuda")
+    dh.dh_attn_fwd(dh.DH_BF16, batch, seq, nq, nkv, d, qd, o, lse, fws, fwsb)
+    o_ns = torch.empty_like(o); lse_ns = torch.empty_like(lse)
+    dh.dh_attn_fwd(dh.DH_BF16, batch, seq, nq, nkv, d, qd, o_ns, lse_ns)
+    q64 = qkv[:, : nq * d].astype(np.float64).reshape(T, nq, d)
+    k64 = qkv[:, nq * d: (nq + nkv) * d].astype(np.float64).reshape(T, nkv, d)
+    v64 = qkv[:, (nq + nkv) * d:].astype(np.float64).reshape(T, nkv, d)
+    o_ref, lse_ref = R.attention_fwd(q64, k64, v64, batch, seq)
+    assert lse_ref.max() > 40.0     # the scores did climb
+    assert rel(host(o), o_ref.reshape(T, nq * d)) <= 1e-2 and rel(host(o_ns), o_ref.reshape(T, nq * d)) <= 1e-2
+    # lse is tens here: bf16 operands put ~2^-9 relative error into a score, the statistic inherits it
+    assert np.max(np.abs(host(lse) - lse_ref) / np.maximum(1.0, np.abs(lse_ref))) <= 2e-2
+    assert np.max(np.abs(host(lse_ns) - lse_ref) / np.maximum(1.0, np.abs(lse_ref))) <= 2e-2
+    dqkv = torch.zeros(T, nqkv, dtype=torch.bfloat16, device="cuda")
+    delta = torch.empty(nq, T, dtype=torch.float32, device="cuda")
+    wsb = dh.dh_attn_bwd_workspace_bytes(dh.DH_BF16, batch, seq, nq, nkv, d)
+    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+    dh.dh_attn_bwd(dh.DH_BF16, batch, seq, nq, nkv, d, qd, o, dod, lse, dqkv, delta, ws, wsb)
+    dq, dk, dv = R.attention_bwd(do.astype(np.float64).reshape(T, nq, d), q64, k64, v64, batch, seq)
+    got = host(dqkv)
+    rows = {"o": row_err(host(o), o_ref.reshape(T, nq * d), d), "o_unsplit": row_err(host(o_ns), o_ref.reshape(T, nq * d), d),
+            "dv": row_err(got[:, (nq + nkv) * d:], dv.reshape(T, -1), d)}
+    print("rising scores %r worst per-row errors %r; dq %.2e dk %.2e" % ((batch, seq, nq, nkv, d), rows,
+          rel(got[:, : nq * d], dq.reshape(T, -1)), rel(got[:, nq * d: (nq + nkv) * d], dk.reshape(T, -1))), flush=True)
+    assert max(rows.values()) <= ROW_TOL[True], rows
+    assert rel(got[:, (nq + nkv) * d:], dv.reshape(T, -1)) <= 2e-2
+    assert rel(got[:, : nq * d], dq.reshape(T, -1)) <= 2e-2
+    assert rel(got[:, nq * d: (nq + nkv) * d], dk.reshape(T, -1)) <= 2e-2
+
+
 ATTN_CASES = [  # batch, seq, nq, nkv, d
     (1, 1, 2, 1, 64), (1, 128, 4, 4, 64), (2, 200, 4, 2, 64), (1, 333, 4, 1, 128), (2, 512, 2, 1, 128), (1, 1100, 8, 2, 128),
     (1, 2100, 2, 1, 64)]
