@@ -482,6 +482,17 @@ def main():
         dh.dh_layer_set_cross_stream(run.layer, sx)
     log("ablations: round-robin %.1f us, weight gradients fixed %.1f us, default orders free-running %.1f us, graph replay %.1f us" %
         (t_rr * 1e6, t_fixed * 1e6, t_free * 1e6, t_graph * 1e6))
+    # SwiGLU inside the GEMM epilogues against the separate activation operators: the same plan, same results (bitwise)
+    t_unfused = t_seq_unfused = None
+    if dh.dh_layer_set_fused_activation(run.layer, True):
+        dh.dh_layer_set_fused_activation(run.layer, False)
+        n_ab = max(15, args.steps // 2)
+        t_unfused = median(event_times(lambda: run.si_step(alpha, beta, best_plan, sa, sb, c_best), n_ab, 3))
+        t_seq_unfused = median(event_times(lambda: run.si_step(alpha, beta, seq_plan, sa, sb, c_best), n_ab, 3))
+        dh.dh_layer_set_fused_activation(run.layer, True)
+        t_again = median(event_times(lambda: run.si_step(alpha, beta, best_plan, sa, sb, c_best), n_ab, 3))
+        log("activation as separate operators: T_SI %.1f us, T_seq %.1f us (fused, timed again right after: T_SI %.1f us)" %
+            (t_unfused * 1e6, t_seq_unfused * 1e6, t_again * 1e6))
 
     # the same workload with the stand-ins at a link-like rate (64 thread blocks: a 32 MiB all-reduce then takes what an
     # 8-GPU xGMI ring takes): profile, search and timing anew
@@ -549,6 +560,8 @@ def main():
         "ms_sequential": rec["ms_sequential"], "ms_si_no_comm": rec["ms_si_no_comm"], "ms_sequential_no_comm": rec["ms_sequential_no_comm"],
         "ms_free_running": t_free * 1e3, "ms_graph_replay": t_graph * 1e3, "ms_round_robin": t_rr * 1e3, "ms_wgrad_fixed": t_fixed * 1e3,
         "ms_one_comm_stream": t_shared * 1e3 if t_shared is not None else None,
+        "ms_separate_activation": t_unfused * 1e3 if t_unfused is not None else None,
+        "ms_sequential_separate_activation": t_seq_unfused * 1e3 if t_seq_unfused is not None else None,
         "comm_hidden_frac": rec["comm_hidden_frac"], "comm_composition": comp,
         "predicted_ms": rec["predicted_ms"], "predicted_over_measured": rec["predicted_over_measured"],
         "link_rate": link,

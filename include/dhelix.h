@@ -395,6 +395,13 @@ int dh_si_step(dh_layer* layer, const dh_fwd_args* alpha, const dh_bwd_args* bet
                const dh_plan* plan, void* ws, size_t ws_bytes, void* stream_alpha,
                void* stream_beta, void* stream_comm);
 
+/* SwiGLU inside the epilogues of the neighbouring GEMMs (dh_gemm_swiglu_fwd / _bwd below) for later calls on this
+ * layer: enable != 0 (the state after dh_layer_create) uses them wherever the layer's shapes fit, 0 runs the separate
+ * operators.  Results are bit-identical either way; the switch exists to measure one against the other.  Returns a
+ * negative dh_status on error, else a bit mask of what is now fused: 1 = forward (F_ACT launches nothing),
+ * 2 = backward (B_ACT launches nothing).  Host only. */
+int dh_layer_set_fused_activation(dh_layer* layer, int enable);
+
 /* A communication stream of strand beta's own for later SI steps of this layer (NULL, the default: beta's collectives
  * go where alpha's go).  With one shared stream the two strands' collectives run one after the other in issue order;
  * when a collective costs what a link makes it cost, that order is the step's critical path.  Host only. */

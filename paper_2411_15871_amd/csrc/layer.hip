@@ -387,6 +387,16 @@ extern "C" int dh_layer_set_cross_stream(dh_layer* L, void* stream_cross) {
   return DH_OK;
 }
 
+extern "C" int dh_layer_set_fused_activation(dh_layer* L, int enable) {
+  if (!L) DH_FAIL(DH_ERR_INVALID_ARG, "layer_set_fused_activation: null layer");
+  const dh_layer_config& c = L->c;
+  const bool glu_layer = c.dtype == DH_BF16 && (c.arch == DH_ARCH_LLAMA || c.arch == DH_ARCH_LLAMA_CP);
+  if (enable < 0 || enable > 3) DH_FAIL(DH_ERR_INVALID_ARG, "layer_set_fused_activation: mask %d outside 0..3", enable);
+  L->fuse_act_fwd = (enable & 1) && glu_layer && dh_glu_fwd_fits(L->T, c.ffn, c.hidden);
+  L->fuse_act_bwd = (enable & 2) && glu_layer && dh_glu_bwd_fits(L->T, c.ffn, c.hidden);
+  return (L->fuse_act_fwd ? 1 : 0) | (L->fuse_act_bwd ? 2 : 0);
+}
+
 extern "C" int dh_layer_set_beta_comm_stream(dh_layer* L, void* stream_comm_beta) {
   if (!L) DH_FAIL(DH_ERR_INVALID_ARG, "layer_set_beta_comm_stream: null layer");
   L->beta_comm_stream = (hipStream_t)stream_comm_beta;

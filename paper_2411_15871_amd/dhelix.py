@@ -186,6 +186,7 @@ SIGNATURES = {
     "dh_rope_pairs": (_I, [_I, _I, _I, _I, _I, _I, _I, _I, _F, _I, _P, _P]),
     "dh_swiglu_fwd": (_I, [_I, _I, _I, _P, _P, _P]),
     "dh_swiglu_bwd": (_I, [_I, _I, _I, _P, _P, _P, _P]),
+    "dh_layer_set_fused_activation": (_I, [_P, _I]),
     "dh_gemm_swiglu_fwd_fits": (_I, [_I, _I, _I]),
     "dh_gemm_swiglu_fwd": (_I, [_I, _I, _I, _P, _P, _P, _P, _P]),
     "dh_gemm_swiglu_bwd_fits": (_I, [_I, _I, _I]),
@@ -602,6 +603,14 @@ def dh_swiglu_fwd(dtype, T, F, gu, a, stream=None):
 
 def dh_swiglu_bwd(dtype, T, F, gu, da, dgu, stream=None):
     _check(lib.dh_swiglu_bwd(dtype, T, F, _ptr(gu), _ptr(da), _ptr(dgu), _stream(stream)))
+
+
+def dh_layer_set_fused_activation(layer, enable):
+    """Returns the bit mask of what is fused afterwards (1 forward, 2 backward)."""
+    rc = lib.dh_layer_set_fused_activation(layer, 3 if enable is True else int(enable))
+    if rc < 0:
+        _check(rc)
+    return rc
 
 
 def dh_gemm_swiglu_fwd_fits(T, F, H):

@@ -314,6 +314,24 @@ def test_si_step_bitwise_equals_sequential_at_full_size(name):
         run.fwd(alpha)
         run.bwd(beta)
         ref = snapshot(run, alpha, beta)
+        # SwiGLU inside the GEMM epilogues (on by default where the shapes fit) against the separate operators: the same bits
+        fused = dh.dh_layer_set_fused_activation(run.layer, True)
+        print("fused activation mask", fused, flush=True)
+        if name in ("c2_llama8b_tp8", "c6_llama8b_tp8_cp4"):
+            assert fused == 3
+        if fused:
+            assert dh.dh_layer_set_fused_activation(run.layer, False) == 0
+            run.fwd(beta)
+            torch.cuda.synchronize()
+            alpha.out.zero_(); alpha.saved.zero_(); beta.dx.zero_()
+            if beta.dkv_peers is not None:
+                beta.dkv_peers.zero_()
+            run.zero_grads()
+            run.fwd(alpha)
+            run.bwd(beta)
+            for a, b in zip(snapshot(run, alpha, beta), ref):
+                assert torch.equal(a, b), "separate activation operators"
+            assert dh.dh_layer_set_fused_activation(run.layer, True) == fused
         gf, gb = dh.dh_layer_op_graph(run.layer, 0), dh.dh_layer_op_graph(run.layer, 1)
         table = dh.dh_profile_pairs(run.layer, alpha.fwd_args, beta.bwd_args, run.ws, run.ws_bytes, sa, sb, comm, 1)
         searched, _ = dh.dh_plan_search(gf, gb, table, 5e-6, 64)
