@@ -270,7 +270,6 @@ def main():
     ap.add_argument("--profile-reps", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", type=int, default=0, help="stack this many layers: alpha sweeps forward while beta sweeps backward")
-    ap.add_argument("--traffic-probe", action="store_true", help="only launch a calibration copy and the dominant GEMM (for rocprofv3 --pmc)")
     ap.add_argument("--sequential-probe", action="store_true",
                     help="only run alpha's forward then beta's backward, one kernel at a time, --steps times (for rocprofv3: every kernel's solo "
                          "duration and counters at the workload's shapes)")
@@ -288,29 +287,6 @@ def main():
     import torch
     from paper_2411_15871_amd import dhelix as dh
     from paper_2411_15871_amd import harness as H
-
-    if args.traffic_probe:
-        # For `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs: a plain copy of known size (the stand-in kernel with
-        # one partial: reads 256 MiB, writes 256 MiB) calibrates the counters, then the dominant GEMM is launched alone.
-        c = H.CONFIGS[args.workload]
-        T, Hd = c["batch"] * c["seq"], c["hidden"]
-        T = T if c["arch"] != "moe" else 2 * T // c["n_local"]
-        F2 = c["ffn"] if c["arch"] == "gpt" else 2 * c["ffn"]
-        src = torch.empty(128 << 20, dtype=torch.bfloat16, device="cuda").normal_()
-        dst = torch.empty_like(src)
-        a_mat = torch.empty(T, Hd, dtype=torch.bfloat16, device="cuda").normal_()
-        b_mat = torch.empty(Hd, F2, dtype=torch.bfloat16, device="cuda").normal_(0, 0.02)
-        c_mat = torch.empty(T, F2, dtype=torch.bfloat16, device="cuda")
-        wsb = dh.dh_gemm_workspace_bytes(dh.DH_BF16, 0, 0, T, F2, Hd)
-        gws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
-        torch.cuda.synchronize()
-        for _ in range(3):
-            dh.dh_comm_standin(dh.DH_COMM_ALLREDUCE, [src], dst, src.numel(), dh.DH_BF16)
-        for _ in range(3):
-            dh.dh_gemm(dh.DH_BF16, 0, 0, T, F2, Hd, a_mat, b_mat, c_mat, False, gws, wsb)
-        torch.cuda.synchronize()
-        print("traffic probe: 3 x copy of %d KiB, 3 x GEMM %dx%dx%d" % (src.numel() * 2 // 1024, T, F2, Hd))
-        return
 
     if args.layers > 0:
         return stack_bench(args, torch, dh, H)

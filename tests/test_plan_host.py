@@ -241,3 +241,48 @@ def test_count_orders_and_full_enumeration():
         assert bo.index(w) >= 8, bo
     finally:
         dh.dh_layer_destroy(L)
+
+
+ARCH_CFGS = {
+    "llama": dict(arch=0, n_ranks=2),
+    "gpt": dict(arch=1, n_ranks=2, n_kv_heads=2),
+    "moe": dict(arch=2, n_ranks=1, n_experts=4, n_local_experts=2),
+    "llama_cp": dict(arch=3, n_ranks=2, cp_ranks=2, cp_rank=1),
+}
+
+
+@pytest.mark.parametrize("name", list(ARCH_CFGS))
+def test_lane_search_on_every_architecture_graph(name):
+    """dh_plan_search_lanes on the layer's own operator graphs with random tables (some operators at the profiler's floor
+    time, some pairs undisturbed), under every placement of the stand-ins and a small order cap: the plan is valid, its
+    bwd_side marks only side_ok operators, dh_plan_cost reproduces the makespan the search reports, and no plan is worse
+    than the sequential or the default free-running one costed the same way."""
+    cfg = dict(dtype=0, batch=1, seq=64, hidden=64, n_q_heads=2, n_kv_heads=1, head_dim=32, ffn=64, eps=1e-5, rope_base=1e4)
+    cfg.update(ARCH_CFGS[name])
+    L = dh.dh_layer_create(**cfg)
+    rng = random.Random(5)
+    try:
+        gf, gb = dh.dh_layer_op_graph(L, 0), dh.dh_layer_op_graph(L, 1)
+        nf, nb = gf.n_ops, gb.n_ops
+        assert dh.dh_plan_count_orders(gb, 10 ** 6) >= 1
+        seq = dh.dh_plan_sequential(L)
+        free = dh.make_plan(list(seq.fwd_order[:nf]), list(seq.bwd_order[:nb]), [(0, nf, 0, nb)])
+        for trial in range(3):
+            t_f = [1e-7 if rng.random() < 0.1 else rng.uniform(1e-6, 2e-4) for _ in range(nf)]
+            t_b = [1e-7 if rng.random() < 0.1 else rng.uniform(1e-6, 2e-4) for _ in range(nb)]
+            rf = [[1.0 if rng.random() < 0.2 else rng.uniform(0.02, 1.0) for _ in range(nb)] for _ in range(nf)]
+            rb = [[1.0 if rng.random() < 0.2 else rng.uniform(0.02, 1.0) for _ in range(nb)] for _ in range(nf)]
+            tab = dh.make_table(t_f, t_b, rf, rb)
+            bc = 5e-6 if trial & 1 else 0.0
+            for lanes in [(0, 0, 0), (1, 1, 0), (1, 2, 0), (1, 1, 1), (1, 2, 1)]:
+                ln = dh.lanes(*lanes)
+                plan, mk, info = dh.dh_plan_search_lanes(gf, gb, tab, ln, bc, 40)
+                dh.dh_plan_validate(gf, gb, plan)
+                assert all(gb.side_ok[o] for o in range(nb) if plan.bwd_side[o])
+                assert info.orders_bwd_tried <= 40 and info.orders_fwd_tried <= 40
+                again = dh.dh_plan_cost(gf, gb, tab, plan, ln, bc)
+                assert abs(again - mk) <= 1e-9 * mk
+                assert mk <= dh.dh_plan_cost(gf, gb, tab, seq, ln, bc) * (1 + 1e-9)
+                assert mk <= dh.dh_plan_cost(gf, gb, tab, free, ln, bc) * (1 + 1e-9)
+    finally:
+        dh.dh_layer_destroy(L)
