@@ -402,6 +402,14 @@ int dh_si_step(dh_layer* layer, const dh_fwd_args* alpha, const dh_bwd_args* bet
  * 2 = backward (B_ACT launches nothing).  Host only. */
 int dh_layer_set_fused_activation(dh_layer* layer, int enable);
 
+/* Backward all-reduces carried by a weight-gradient GEMM of their own strand (dh_gemm_allreduce below) for later
+ * calls on this layer, Llama architectures in bf16: bit 1 = B_AR3 with B_FC1_WGRAD, bit 2 = B_AR4 with B_QKV_WGRAD
+ * (Sec. 4.2: the weight gradients are the operators free to move; here they move into the collective's launch).  While
+ * the stand-ins run on a block budget (comm_blocks > 0) and the GEMM fits, the collective operator launches both and
+ * the weight-gradient operator launches nothing; otherwise the operators run apart as before.  Default 0.  Results
+ * are bit-identical either way.  Returns a negative dh_status on error, else the mask now in force.  Host only. */
+int dh_layer_set_fused_collective(dh_layer* layer, int mask);
+
 /* A communication stream of strand beta's own for later SI steps of this layer (NULL, the default: beta's collectives
  * go where alpha's go).  With one shared stream the two strands' collectives run one after the other in issue order;
  * when a collective costs what a link makes it cost, that order is the step's critical path.  Host only. */
@@ -671,6 +679,21 @@ int dh_moe_combine_bwd(int dtype, int T, int H, const void* dy, const void* yp, 
  * dim_a, dim_b multiples of 8 for DH_BF16; at most 64 groups. */
 int dh_gemm_grouped(int dtype, int mode, int n_groups, const int32_t* group_rows, int max_rows,
                     int dim_a, int dim_b, const void* A, const void* B, void* C, void* stream);
+
+/* A bf16 GEMM and an all-reduce stand-in in ONE launch (the direction the closing paragraph of the cross-node analysis
+ * of Sec. 6.3 / Table 7 names: computation and communication inside one kernel, so that their shares of the machine
+ * are fixed in the kernel and not by the dispatcher).  The launch's first blocks -- as many threads as n_blocks
+ * 256-thread blocks of dh_comm_standin -- stream the payload and hold their compute units until it is through; the
+ * GEMM's tiles take the other units.  C (+)= opA(A) opB(B) exactly as dh_gemm (bf16, no bias), ar_out = the sum of the
+ * n_ranks bf16 partial buffers of ar_elems elements exactly as dh_comm_standin(DH_COMM_ALLREDUCE): both results are
+ * bit-identical to the two separate calls.  The two halves are independent: the payload is NOT the GEMM's result.
+ * Fits (dh_gemm_allreduce_fits = 1) when the GEMM is a single launch without workspace (no K split, no tail launch);
+ * otherwise DH_ERR_UNSUPPORTED.  All pointers device, 16-byte aligned; parts is a host array of n_ranks device
+ * pointers; nothing is allocated. */
+int dh_gemm_allreduce_fits(int trans_a, int trans_b, int M, int N, int K);
+int dh_gemm_allreduce(int trans_a, int trans_b, int M, int N, int K, const void* A, const void* B, void* C,
+                      int out_f32_accumulate, int n_ranks, const void* const* parts, void* ar_out, size_t ar_elems,
+                      int n_blocks, void* stream);
 
 /* The feed-forward block's SwiGLU (operator ACT of the layer, Sec. 4.2's operator list; Table 2 bases it on an
  * element-wise kernel) run inside the epilogue of the GEMM next to it, bf16 only, so that the activation costs no

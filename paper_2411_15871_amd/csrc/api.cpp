@@ -1,5 +1,6 @@
 // Error reporting and the generic single-operator entry points of libdhelix.
 #include <cstdarg>
+#include <cstdint>
 #include <cstdio>
 #include "common.h"
 
@@ -47,6 +48,26 @@ extern "C" int dh_gemm_grouped(int dtype, int mode, int n_groups, const int32_t*
     return dh_launch_gemm_grouped_bf16(mode, n_groups, group_rows, max_rows, dim_a, dim_b, (const bf16_t*)A, (const bf16_t*)B, C,
                                        (hipStream_t)stream);
   DH_FAIL(DH_ERR_INVALID_ARG, "gemm_grouped: unknown dtype %d", dtype);
+}
+
+extern "C" int dh_gemm_allreduce_fits(int trans_a, int trans_b, int M, int N, int K) {
+  return dh_gemm_ar_fits(trans_a != 0, trans_b != 0, M, N, K) ? 1 : 0;
+}
+
+extern "C" int dh_gemm_allreduce(int trans_a, int trans_b, int M, int N, int K, const void* A, const void* B, void* C,
+                                 int out_f32_accumulate, int n_ranks, const void* const* parts, void* ar_out, size_t ar_elems,
+                                 int n_blocks, void* stream) {
+  if (!dh_gemm_ar_fits(trans_a != 0, trans_b != 0, M, N, K))
+    DH_FAIL(DH_ERR_UNSUPPORTED, "gemm_allreduce: M=%d N=%d K=%d ta=%d tb=%d does not run as a single launch", M, N, K, trans_a, trans_b);
+  if (!A || !B || !C || !parts || !ar_out) DH_FAIL(DH_ERR_INVALID_ARG, "gemm_allreduce: null pointer");
+  if (n_ranks < 1 || n_ranks > DH_MAX_RANKS) DH_FAIL(DH_ERR_INVALID_ARG, "gemm_allreduce: n_ranks %d outside 1..%d", n_ranks, DH_MAX_RANKS);
+  if (n_blocks < 1 || n_blocks > 65536) DH_FAIL(DH_ERR_INVALID_ARG, "gemm_allreduce: n_blocks %d outside 1..65536", n_blocks);
+  if (ar_elems == 0 || ar_elems % 8) DH_FAIL(DH_ERR_SHAPE, "gemm_allreduce: element count %zu must be a positive multiple of 8", ar_elems);
+  if ((uintptr_t)ar_out & 15) DH_FAIL(DH_ERR_INVALID_ARG, "gemm_allreduce: ar_out must be 16-byte aligned");
+  for (int r = 0; r < n_ranks; r++)
+    if (!parts[r] || ((uintptr_t)parts[r] & 15)) DH_FAIL(DH_ERR_INVALID_ARG, "gemm_allreduce: partial %d is null or not 16-byte aligned", r);
+  return dh_launch_gemm_bf16_ar(trans_a != 0, trans_b != 0, M, N, K, (const bf16_t*)A, (const bf16_t*)B, C, out_f32_accumulate != 0,
+                                n_ranks, parts, (bf16_t*)ar_out, ar_elems, n_blocks, (hipStream_t)stream);
 }
 
 extern "C" int dh_gemm_swiglu_fwd_fits(int T, int F, int H) { return dh_glu_fwd_fits(T, F, H) ? 1 : 0; }

@@ -138,6 +138,29 @@ __device__ __forceinline__ void swiglu_bwd_elem(float g, float u, float d, float
   du = __fmul_rn(d, gs);
 }
 
+// All-reduce stand-in: out = sum over the n_ranks partial buffers, added in rank order in float32.  A thread handles the
+// 8-element vectors first, first + stride, ... below n8; shared by the stand-in kernel and the GEMM launches that carry
+// a stand-in along (the same bits either way).
+#define DH_MAX_RANKS 16
+struct PartPtrs {
+  const void* p[DH_MAX_RANKS];
+};
+template <typename T>
+__device__ __forceinline__ void allreduce_span(const PartPtrs& parts, int n_ranks, T* __restrict__ out, size_t n8, size_t first,
+                                               size_t stride) {
+  for (size_t i = first; i < n8; i += stride) {
+    Vec8<T> acc;
+    acc.load_stream((const T*)parts.p[0] + i * 8);
+    for (int r = 1; r < n_ranks; r++) {
+      Vec8<T> v;
+      v.load_stream((const T*)parts.p[r] + i * 8);
+#pragma unroll
+      for (int k = 0; k < 8; k++) acc.v[k] += v.v[k];
+    }
+    acc.store_stream(out + i * 8);
+  }
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
@@ -169,6 +192,12 @@ int dh_launch_gemm_grouped_f32(int mode, int n_groups, const int32_t* group_rows
 int dh_launch_gemm_grouped_bf16(int mode, int n_groups, const int32_t* group_rows, int max_rows, int dim_a, int dim_b,
                                 const bf16_t* A, const bf16_t* B, void* C, hipStream_t stream);
 size_t dh_gemm_bf16_ws_bytes(bool ta, bool tb, int M, int N, int K);
+// A bf16 GEMM launch that carries an all-reduce stand-in along: the first ar_blocks*256/(block size) thread blocks of the
+// launch stream the payload (elems bf16 elements, n_ranks partials), the others compute the GEMM's tiles.  *_fits: the
+// GEMM is a single launch without workspace.
+bool dh_gemm_ar_fits(bool ta, bool tb, int M, int N, int K);
+int dh_launch_gemm_bf16_ar(bool ta, bool tb, int M, int N, int K, const bf16_t* A, const bf16_t* B, void* C, bool out_f32_accumulate,
+                           int n_ranks, const void* const* parts, bf16_t* ar_out, size_t ar_elems, int ar_blocks, hipStream_t stream);
 // SwiGLU fused into the epilogue of the gate/up projection (forward) and of the down projection's data gradient
 // (backward); *_fits says whether the shapes allow it (otherwise: the GEMM, then the row-wise kernel).
 bool dh_glu_fwd_fits(int T, int F, int H);

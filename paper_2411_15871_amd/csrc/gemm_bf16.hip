@@ -69,6 +69,19 @@ struct GemmArgs {
   int glu_mode, glu_f;
   const bf16_t* glu_in;
   bf16_t* glu_out;
+  // An all-reduce stand-in carried along (Sec. 6.3, Table 7's closing remark: computation and communication in one kernel,
+  // their shares of the machine fixed inside it instead of left to the dispatcher): the first ar_blocks thread blocks of
+  // the launch stream the payload -- they hold their compute units for as long as the transfer lasts --, the tiles
+  // follow.  0 = none.
+  int ar_blocks;
+};
+// The stand-in's operands travel as a kernel argument of their own: GemmArgs is edited by the grouped path and lives in
+// registers, the partial pointers are indexed at run time and stay in the argument segment.
+struct GemmAr {
+  int ranks;
+  size_t n8;
+  bf16_t* out;
+  PartPtrs parts;
 };
 enum { GLU_NONE = 0, GLU_FWD = 1, GLU_BWD = 2 };
 
@@ -184,8 +197,14 @@ __device__ __forceinline__ bf16x8 frag_km(const bf16_t* tile, int k0, int c16, i
 }
 
 template <int BM, int BN, int WM, int WN, bool TA, bool TB>
-__global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmArgs g) {
+__global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmArgs g, const GemmAr ar) {
   constexpr int NW = WM * WN;
+  if (g.ar_blocks > 0 && blockIdx.x < (unsigned)g.ar_blocks) {  // this block is a share of the stand-in, not a tile
+    if (blockIdx.y == 0 && blockIdx.z == 0)
+      allreduce_span<bf16_t>(ar.parts, ar.ranks, ar.out, ar.n8, (size_t)blockIdx.x * blockDim.x + threadIdx.x,
+                             (size_t)g.ar_blocks * blockDim.x);
+    return;
+  }
   if (g.group_rows != nullptr) {
     // Grouped: the groups' rows lie behind one another; this block's group is blockIdx.z.  The row
     // counts are data (expert routing), so the extents are fixed up here from device memory and the
@@ -229,7 +248,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmArgs g) {
   const int wm0 = (wave / WN) * WTM, wn0 = (wave % WN) * WTN;
 
   int tm, tn;
-  if (!tile_of_launch((int)blockIdx.x + g.tile_first, g.tiles_m, g.tiles_n, g.tiles_per_xcd, tm, tn)) return;
+  if (!tile_of_launch((int)blockIdx.x - g.ar_blocks + g.tile_first, g.tiles_m, g.tiles_n, g.tiles_per_xcd, tm, tn)) return;
   const int m0 = tm * BM, n0 = tn * BN;
   const bool glu_fwd = !TA && !TB && BN == 256 && g.glu_mode == GLU_FWD;
   const int nb0 = glu_fwd ? tn * (BN / 2) : n0;  // first column of the tile's B panel (its first half, if fused)
@@ -646,7 +665,8 @@ size_t dh_gemm_bf16_ws_bytes(bool ta, bool tb, int M, int N, int K) {
 }
 
 template <int BM, int BN, int WM, int WN, bool TA, bool TB>
-static int launch_cfg(GemmArgs g, int splits, hipStream_t stream, int n_groups = 1, int tile_first = 0, int n_tiles = -1) {
+static int launch_cfg(GemmArgs g, int splits, hipStream_t stream, int n_groups = 1, int tile_first = 0, int n_tiles = -1,
+                      const GemmAr* ar = nullptr) {
   constexpr size_t LDS_BYTES = GB_STAGES * (size_t)(BM + BN) * GB_BK * sizeof(bf16_t);
   static bool attr_set[DH_MAX_DEVICES] = {};  // the attribute belongs to the kernel's code object on one device
   const int dev = dh_device_index();
@@ -659,19 +679,22 @@ static int launch_cfg(GemmArgs g, int splits, hipStream_t stream, int n_groups =
   g.tiles_n = (g.N + BN - 1) / BN;
   g.tiles_per_xcd = (g.tiles_m * g.tiles_n + 7) / 8;
   g.tile_first = tile_first;
-  dim3 grid(n_tiles >= 0 ? n_tiles : g.tiles_per_xcd * 8, splits, n_groups);
-  gemm_bf16_kernel<BM, BN, WM, WN, TA, TB><<<grid, 64 * WM * WN, LDS_BYTES, stream>>>(g);
+  dim3 grid((n_tiles >= 0 ? n_tiles : g.tiles_per_xcd * 8) + g.ar_blocks, splits, n_groups);
+  GemmAr none;
+  none.ranks = 0; none.n8 = 0; none.out = nullptr;
+  for (int r = 0; r < DH_MAX_RANKS; r++) none.parts.p[r] = nullptr;
+  gemm_bf16_kernel<BM, BN, WM, WN, TA, TB><<<grid, 64 * WM * WN, LDS_BYTES, stream>>>(g, ar ? *ar : none);
   DH_LAUNCH_CHECK();
   return DH_OK;
 }
 
 template <bool TA, bool TB>
 static int launch_layout(const GemmArgs& g, const GemmPlan& p, hipStream_t stream, int n_groups = 1, int tile_first = 0,
-                         int n_tiles = -1, int splits = 0) {
+                         int n_tiles = -1, int splits = 0, const GemmAr* ar = nullptr) {
   if (splits == 0) splits = p.splits;
-  if (p.cfg == 0) return launch_cfg<256, 256, 2, 4, TA, TB>(g, splits, stream, n_groups, tile_first, n_tiles);
-  if (p.cfg == 2) return launch_cfg<256, 128, 2, 2, TA, TB>(g, splits, stream, n_groups, tile_first, n_tiles);
-  return launch_cfg<128, 128, 2, 2, TA, TB>(g, splits, stream, n_groups, tile_first, n_tiles);
+  if (p.cfg == 0) return launch_cfg<256, 256, 2, 4, TA, TB>(g, splits, stream, n_groups, tile_first, n_tiles, ar);
+  if (p.cfg == 2) return launch_cfg<256, 128, 2, 2, TA, TB>(g, splits, stream, n_groups, tile_first, n_tiles, ar);
+  return launch_cfg<128, 128, 2, 2, TA, TB>(g, splits, stream, n_groups, tile_first, n_tiles, ar);
 }
 template <typename... Args>
 static int launch_any(bool ta, bool tb, Args... args) {
@@ -697,7 +720,7 @@ int dh_launch_gemm_bf16(bool ta, bool tb, int M, int N, int K, const bf16_t* A, 
   g.tiles_m = g.tiles_n = g.tiles_per_xcd = 0;
   g.bias = bias; g.group_rows = nullptr; g.group_mode = 0;
   g.group_part = 0; g.n_groups = 1; g.part1_bm = g.part1_bn = 256; g.cus = 0; g.tile_first = 0;
-  g.glu_mode = GLU_NONE; g.glu_f = 0; g.glu_in = nullptr; g.glu_out = nullptr;
+  g.glu_mode = GLU_NONE; g.glu_f = 0; g.glu_in = nullptr; g.glu_out = nullptr; g.ar_blocks = 0;
   const int final_epi = out_f32_accumulate ? EPI_ACC_F32 : EPI_STORE_BF16;
   int rc;
   if (p.tail_tiles > 0) {  // whole rounds with the final epilogue, then the last round's tiles with K split, then their sum
@@ -726,6 +749,38 @@ int dh_launch_gemm_bf16(bool ta, bool tb, int M, int N, int K, const bf16_t* A, 
   return DH_OK;
 }
 
+// GEMM with an all-reduce stand-in in the same launch.  ar_blocks counts 256-thread blocks, as dh_comm_standin's
+// n_blocks does; the launch's blocks are 256 or 512 threads, so the same number of threads streams the payload.
+bool dh_gemm_ar_fits(bool ta, bool tb, int M, int N, int K) {
+  if (M <= 0 || N <= 0 || K <= 0 || (ta && tb) || N % 8 || (ta ? M : K) % 8 || (tb ? K : N) % 8) return false;
+  const GemmPlan p = choose_plan(ta, M, N, K, (size_t)-1);
+  return p.splits == 1 && p.tail_tiles == 0;
+}
+int dh_launch_gemm_bf16_ar(bool ta, bool tb, int M, int N, int K, const bf16_t* A, const bf16_t* B, void* C, bool out_f32_accumulate,
+                           int n_ranks, const void* const* parts, bf16_t* ar_out, size_t ar_elems, int ar_blocks, hipStream_t stream) {
+  if (!dh_gemm_ar_fits(ta, tb, M, N, K)) DH_FAIL(DH_ERR_UNSUPPORTED, "gemm+allreduce: M=%d N=%d K=%d does not run as a single launch", M, N, K);
+  if (n_ranks < 1 || n_ranks > DH_MAX_RANKS || ar_blocks < 1 || ar_blocks > 65536 || ar_elems % 8 || ar_elems == 0)
+    DH_FAIL(DH_ERR_INVALID_ARG, "gemm+allreduce: n_ranks %d, n_blocks %d, elements %zu", n_ranks, ar_blocks, ar_elems);
+  const GemmPlan p = choose_plan(ta, M, N, K, (size_t)-1);
+  GemmArgs g;
+  g.M = M; g.N = N; g.K = K; g.A = A; g.B = B; g.C = C;
+  g.epi = out_f32_accumulate ? EPI_ACC_F32 : EPI_STORE_BF16;
+  g.kt_per_split = p.kt_per_split;
+  g.tiles_m = g.tiles_n = g.tiles_per_xcd = 0;
+  g.bias = nullptr; g.group_rows = nullptr; g.group_mode = 0;
+  g.group_part = 0; g.n_groups = 1; g.part1_bm = g.part1_bn = 256; g.cus = 0; g.tile_first = 0;
+  g.glu_mode = GLU_NONE; g.glu_f = 0; g.glu_in = nullptr; g.glu_out = nullptr;
+  const int threads = p.cfg == 0 ? 512 : 256;
+  const size_t n8 = ar_elems / 8, want = (n8 + threads - 1) / threads;
+  size_t nb = ((size_t)ar_blocks * 256 + threads - 1) / threads;
+  if (nb > want) nb = want;
+  g.ar_blocks = (int)nb;
+  GemmAr ar;
+  ar.ranks = n_ranks; ar.n8 = n8; ar.out = ar_out;
+  for (int r = 0; r < DH_MAX_RANKS; r++) ar.parts.p[r] = r < n_ranks ? parts[r] : nullptr;
+  return launch_any(ta, tb, g, p, stream, 1, 0, -1, 0, (const GemmAr*)&ar);
+}
+
 // Gate/up projection with SwiGLU in its epilogue: gu[T, 2F] = x[T, H] * Wgu[H, 2F] (columns [gate | up]) and
 // a[T, F] = gate * sigmoid(gate) * up computed from the stored (rounded) values -- the same bits as
 // dh_launch_gemm_bf16 followed by the row-wise kernel.  Fits when the plain GEMM would be one launch of whole 256x256
@@ -743,7 +798,7 @@ int dh_launch_gemm_swiglu_fwd_bf16(int T, int F, int H, const bf16_t* x, const b
   g.tiles_m = g.tiles_n = g.tiles_per_xcd = 0;
   g.bias = nullptr; g.group_rows = nullptr; g.group_mode = 0;
   g.group_part = 0; g.n_groups = 1; g.part1_bm = g.part1_bn = 256; g.cus = 0; g.tile_first = 0;
-  g.glu_mode = GLU_FWD; g.glu_f = F; g.glu_in = nullptr; g.glu_out = a;
+  g.glu_mode = GLU_FWD; g.glu_f = F; g.glu_in = nullptr; g.glu_out = a; g.ar_blocks = 0;
   return launch_cfg<256, 256, 2, 4, false, false>(g, 1, stream);
 }
 
@@ -764,7 +819,7 @@ int dh_launch_gemm_swiglu_bwd_bf16(int T, int F, int H, const bf16_t* dy, const 
   g.tiles_m = g.tiles_n = g.tiles_per_xcd = 0;
   g.bias = nullptr; g.group_rows = nullptr; g.group_mode = 0;
   g.group_part = 0; g.n_groups = 1; g.part1_bm = g.part1_bn = 256; g.cus = 0; g.tile_first = 0;
-  g.glu_mode = GLU_BWD; g.glu_f = F; g.glu_in = gu; g.glu_out = nullptr;
+  g.glu_mode = GLU_BWD; g.glu_f = F; g.glu_in = gu; g.glu_out = nullptr; g.ar_blocks = 0;
   return launch_layout<false, true>(g, p, stream);
 }
 
@@ -781,7 +836,7 @@ int dh_launch_gemm_grouped_bf16(int mode, int n_groups, const int32_t* group_row
   g.bias = nullptr; g.group_rows = group_rows; g.group_mode = mode;
   g.tiles_m = g.tiles_n = g.tiles_per_xcd = 0;
   g.group_part = 0; g.n_groups = n_groups; g.part1_bm = g.part1_bn = 256; g.cus = num_cus(); g.tile_first = 0;
-  g.glu_mode = GLU_NONE; g.glu_f = 0; g.glu_in = nullptr; g.glu_out = nullptr;
+  g.glu_mode = GLU_NONE; g.glu_f = 0; g.glu_in = nullptr; g.glu_out = nullptr; g.ar_blocks = 0;
   const int avg = std::max(1, max_rows / n_groups);
   GemmPlan p;
   if (mode == 2) { g.M = dim_a; g.N = dim_b; g.K = max_rows; p = choose_plan(true, dim_a, dim_b, avg, 0); }

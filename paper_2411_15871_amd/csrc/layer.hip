@@ -28,6 +28,9 @@ struct dh_layer {
   // SwiGLU runs in the epilogue of the gate/up projection (forward) / of the down projection's data gradient (backward)
   // where the shapes allow; the activation operator of that direction then launches nothing
   bool fuse_act_fwd, fuse_act_bwd;
+  // backward all-reduces carried by a weight-gradient GEMM's launch: bit 1 = B_AR3 with B_FC1_WGRAD, bit 2 = B_AR4 with
+  // B_QKV_WGRAD; in force only while the stand-ins run on a block budget (comm_blocks > 0)
+  int fuse_comm;
   // forward workspace offsets
   size_t f_hs, f_part, f_red, f_xp, f_yg, f_attn, f_attn_bytes, f_gemm, f_gemm_bytes, fwd_bytes;
   // backward workspace offsets
@@ -253,6 +256,7 @@ extern "C" int dh_layer_create(const dh_layer_config* cfg, dh_layer** out) {
   L->Ts = c.arch == DH_ARCH_GPT ? L->T / c.n_ranks : L->T;
   L->Tf = c.arch == DH_ARCH_MOE ? 2 * L->T : L->T;
   const bool glu_layer = c.dtype == DH_BF16 && (c.arch == DH_ARCH_LLAMA || c.arch == DH_ARCH_LLAMA_CP);
+  L->fuse_comm = 0;
   L->fuse_act_fwd = glu_layer && dh_glu_fwd_fits(L->T, c.ffn, c.hidden);
   L->fuse_act_bwd = glu_layer && dh_glu_bwd_fits(L->T, c.ffn, c.hidden);
   L->n_qkv = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
@@ -387,6 +391,18 @@ extern "C" int dh_layer_set_cross_stream(dh_layer* L, void* stream_cross) {
   return DH_OK;
 }
 
+extern "C" int dh_layer_set_fused_collective(dh_layer* L, int mask) {
+  if (!L) DH_FAIL(DH_ERR_INVALID_ARG, "layer_set_fused_collective: null layer");
+  if (mask < 0 || mask > 3) DH_FAIL(DH_ERR_INVALID_ARG, "layer_set_fused_collective: mask %d outside 0..3", mask);
+  const dh_layer_config& c = L->c;
+  const bool ok = c.dtype == DH_BF16 && (c.arch == DH_ARCH_LLAMA || c.arch == DH_ARCH_LLAMA_CP) && L->T > 0;
+  int m = 0;
+  if (ok && (mask & 1) && dh_gemm_ar_fits(true, false, c.hidden, 2 * c.ffn, L->T)) m |= 1;
+  if (ok && (mask & 2) && dh_gemm_ar_fits(true, false, c.hidden, L->n_qkv, L->T)) m |= 2;
+  L->fuse_comm = m;
+  return m;
+}
+
 extern "C" int dh_layer_set_fused_activation(dh_layer* L, int enable) {
   if (!L) DH_FAIL(DH_ERR_INVALID_ARG, "layer_set_fused_activation: null layer");
   const dh_layer_config& c = L->c;
@@ -432,6 +448,19 @@ static int collective(const dh_layer* L, int kind, const void* own, const void* 
   parts[0] = own;
   for (int r = 1; r < L->c.n_ranks; r++) parts[r] = (const char*)peers + (size_t)(r - 1) * elems * L->es;
   return dh_comm_standin(kind, L->c.n_ranks, parts, out, elems, L->c.dtype, L->c.comm_blocks, (void*)s);
+}
+
+// Whether backward all-reduce `which` (1: AR3, 2: AR4) is carried by its weight-gradient GEMM right now.
+static bool fused_collective(const dh_layer* L, int which) { return (L->fuse_comm & which) != 0 && L->c.comm_blocks > 0; }
+
+// The all-reduce stand-in over {own, peers...} and an unrelated bf16 GEMM in one launch.
+static int collective_with_gemm(const dh_layer* L, const void* own, const void* peers, size_t elems, void* out, bool ta, bool tb, int M,
+                                int N, int K, const void* A, const void* B, void* C, bool acc, hipStream_t s) {
+  const void* parts[16];
+  parts[0] = own;
+  for (int r = 1; r < L->c.n_ranks; r++) parts[r] = (const char*)peers + (size_t)(r - 1) * elems * L->es;
+  return dh_launch_gemm_bf16_ar(ta, tb, M, N, K, (const bf16_t*)A, (const bf16_t*)B, C, acc, L->c.n_ranks, parts, (bf16_t*)out, elems,
+                                L->c.comm_blocks, s);
 }
 
 static dh_moe_tables moe_tables_of(const dh_layer* L, const void* saved) {
@@ -526,8 +555,12 @@ static int llama_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hip
     case DH_B_FC1_DGRAD:
       return gemm(L, false, true, T, H, 2 * F, ws + L->b_dgu, L->w.Wgu, ws + L->b_part, false, gws, gwb, s);
     case DH_B_FC1_WGRAD:
+      if (fused_collective(L, 1)) return DH_OK;  // rides in B_AR3's launch
       return gemm(L, true, false, H, 2 * F, T, sv + L->s_h2, ws + L->b_dgu, L->g.dWgu, true, gws, gwb, s);
     case DH_B_AR3:
+      if (fused_collective(L, 1))
+        return collective_with_gemm(L, ws + L->b_part, b.peers_ar3, n, ws + L->b_red, true, false, H, 2 * F, T, sv + L->s_h2,
+                                    ws + L->b_dgu, L->g.dWgu, true, s);
       return collective(L, DH_COMM_ALLREDUCE, ws + L->b_part, b.peers_ar3, n, ws + L->b_red, s);
     case DH_B_NORM2:  // dx2 = dout + norm2_bwd(dh2)
       return dh_rmsnorm_bwd(dt, T, H, ws + L->b_red, sv + L->s_x2, L->w.g2, (const float*)(sv + L->s_rstd2), b.dout,
@@ -543,8 +576,12 @@ static int llama_bwd_op(dh_layer* L, int op, const dh_bwd_args& b, char* ws, hip
     case DH_B_QKV_DGRAD:
       return gemm(L, false, true, T, H, L->n_qkv, ws + L->b_dqkv, L->w.Wqkv, ws + L->b_part, false, gws, gwb, s);
     case DH_B_QKV_WGRAD:
+      if (fused_collective(L, 2)) return DH_OK;  // rides in B_AR4's launch
       return gemm(L, true, false, H, L->n_qkv, T, sv + L->s_h1, ws + L->b_dqkv, L->g.dWqkv, true, gws, gwb, s);
     case DH_B_AR4:
+      if (fused_collective(L, 2))
+        return collective_with_gemm(L, ws + L->b_part, b.peers_ar4, n, ws + L->b_red, true, false, H, L->n_qkv, T, sv + L->s_h1,
+                                    ws + L->b_dqkv, L->g.dWqkv, true, s);
       return collective(L, DH_COMM_ALLREDUCE, ws + L->b_part, b.peers_ar4, n, ws + L->b_red, s);
     case DH_B_NORM1:  // dx = dx2 + norm1_bwd(dh1)
       return dh_rmsnorm_bwd(dt, T, H, ws + L->b_red, b.x, L->w.g1, (const float*)(sv + L->s_rstd1), ws + L->b_dx2, b.dx,

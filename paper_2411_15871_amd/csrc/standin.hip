@@ -5,25 +5,9 @@
 // so the grid is small and grid-strided: each thread streams 16-byte vectors.
 #include "common.h"
 
-#define DH_MAX_RANKS 16
-struct PartPtrs {
-  const void* p[DH_MAX_RANKS];
-};
-
 template <typename T>
 __global__ __launch_bounds__(256) void allreduce_kernel(PartPtrs parts, int n_ranks, T* __restrict__ out, size_t n8) {
-  size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += stride) {
-    Vec8<T> acc;
-    acc.load_stream((const T*)parts.p[0] + i * 8);
-    for (int r = 1; r < n_ranks; r++) {
-      Vec8<T> v;
-      v.load_stream((const T*)parts.p[r] + i * 8);
-#pragma unroll
-      for (int k = 0; k < 8; k++) acc.v[k] += v.v[k];
-    }
-    acc.store_stream(out + i * 8);
-  }
+  allreduce_span<T>(parts, n_ranks, out, n8, (size_t)blockIdx.x * blockDim.x + threadIdx.x, (size_t)gridDim.x * blockDim.x);
 }
 
 // out = [parts[0] | parts[1] | ... ], each part n8 vectors of 8 elements.

@@ -187,6 +187,9 @@ SIGNATURES = {
     "dh_swiglu_fwd": (_I, [_I, _I, _I, _P, _P, _P]),
     "dh_swiglu_bwd": (_I, [_I, _I, _I, _P, _P, _P, _P]),
     "dh_layer_set_fused_activation": (_I, [_P, _I]),
+    "dh_layer_set_fused_collective": (_I, [_P, _I]),
+    "dh_gemm_allreduce_fits": (_I, [_I, _I, _I, _I, _I]),
+    "dh_gemm_allreduce": (_I, [_I, _I, _I, _I, _I, _P, _P, _P, _I, _I, C.POINTER(_P), _P, _Z, _I, _P]),
     "dh_gemm_swiglu_fwd_fits": (_I, [_I, _I, _I]),
     "dh_gemm_swiglu_fwd": (_I, [_I, _I, _I, _P, _P, _P, _P, _P]),
     "dh_gemm_swiglu_bwd_fits": (_I, [_I, _I, _I]),
@@ -611,6 +614,24 @@ def dh_layer_set_fused_activation(layer, enable):
     if rc < 0:
         _check(rc)
     return rc
+
+
+def dh_layer_set_fused_collective(layer, mask):
+    """Returns the mask in force afterwards (1: B_AR3 carries B_FC1_WGRAD, 2: B_AR4 carries B_QKV_WGRAD)."""
+    rc = lib.dh_layer_set_fused_collective(layer, int(mask))
+    if rc < 0:
+        _check(rc)
+    return rc
+
+
+def dh_gemm_allreduce_fits(trans_a, trans_b, M, N, K):
+    return bool(lib.dh_gemm_allreduce_fits(trans_a, trans_b, M, N, K))
+
+
+def dh_gemm_allreduce(trans_a, trans_b, M, N, K, A, B, Cmat, out_f32_accumulate, parts, ar_out, ar_elems, n_blocks, stream=None):
+    arr = (_P * len(parts))(*[_ptr(q) for q in parts])
+    _check(lib.dh_gemm_allreduce(trans_a, trans_b, M, N, K, _ptr(A), _ptr(B), _ptr(Cmat), 1 if out_f32_accumulate else 0,
+                                 len(parts), arr, _ptr(ar_out), ar_elems, n_blocks, _stream(stream)))
 
 
 def dh_gemm_swiglu_fwd_fits(T, F, H):

@@ -350,6 +350,27 @@ def test_si_step_bitwise_equals_sequential_at_full_size(name):
                 run.si_step(alpha, beta, plan, sa, sb, c)
                 for a, b in zip(snapshot(run, alpha, beta), ref):
                     assert torch.equal(a, b), pname
+        if name in ("c2_llama8b_tp8", "c6_llama8b_tp8_cp4"):
+            # the backward all-reduces carried by their strand's weight-gradient GEMMs (one launch each; stand-ins on a block
+            # budget): sequentially and interleaved, the same bits
+            dh.dh_layer_set_comm_blocks(run.layer, 64)
+            assert dh.dh_layer_set_fused_collective(run.layer, 3) == 3
+            try:
+                reset()
+                run.fwd(alpha)
+                run.bwd(beta)
+                for a, b in zip(snapshot(run, alpha, beta), ref):
+                    assert torch.equal(a, b), "fused collectives, sequential"
+                for pname, plan in plans.items():
+                    for c in (None, comm):
+                        print("fused collectives: plan", pname, "comm" if c else "nocomm", flush=True)
+                        reset()
+                        run.si_step(alpha, beta, plan, sa, sb, c)
+                        for a, b in zip(snapshot(run, alpha, beta), ref):
+                            assert torch.equal(a, b), pname + " (fused collectives)"
+            finally:
+                dh.dh_layer_set_fused_collective(run.layer, 0)
+                dh.dh_layer_set_comm_blocks(run.layer, cfg.get("comm_blocks", 0))
             graph = dh.dh_si_graph_create(run.layer, alpha.fwd_args, beta.bwd_args, plan, run.ws, run.ws_bytes, sa, sb)
             try:
                 for _ in range(2):

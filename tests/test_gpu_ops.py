@@ -327,6 +327,49 @@ def test_gemm_swiglu_fused(dh, T, F, H):
         assert e.value.code == dh.DH_ERR_UNSUPPORTED
 
 
+# trans_a, trans_b, M, N, K, accumulate: the weight-gradient form with each tile shape, the plain form, a ragged one
+GEMM_AR_CASES = [(1, 0, 4096, 3584, 1024, True), (1, 0, 4096, 768, 1024, True), (0, 0, 4096, 1792, 512, False),
+                 (0, 1, 2048, 4096, 256, False), (1, 0, 1000, 520, 264, True)]
+
+
+@pytest.mark.parametrize("ta,tb,M,N,K,acc", GEMM_AR_CASES)
+@pytest.mark.parametrize("n_ranks,n_blocks,elems", [(8, 64, 1 << 20), (1, 1, 8), (3, 7, 40 * 1024 + 8), (4, 65536, 1 << 16)])
+def test_gemm_allreduce_one_launch(dh, ta, tb, M, N, K, acc, n_ranks, n_blocks, elems):
+    """A GEMM that carries an all-reduce stand-in in its launch (Sec. 6.3, closing remark of the Table 7 analysis): both
+    results bit-identical to dh_gemm and dh_comm_standin run apart."""
+    if not dh.dh_gemm_allreduce_fits(ta, tb, M, N, K):
+        pytest.skip("this GEMM is not a single launch")
+    A = gen.normal(80, (K, M) if ta else (M, K), 1.0, 0.0, True); B = gen.normal(81, (N, K) if tb else (K, N), 0.05, 0.0, True)
+    Ad, Bd = dev(A, True), dev(B, True)
+    parts = [dev(gen.normal(90 + r, (elems,), 1.0, 0.0, True), True) for r in range(n_ranks)]
+    cdt = torch.float32 if acc else torch.bfloat16
+    C0 = torch.full((M, N), 0.25, dtype=cdt, device="cuda"); C1 = C0.clone()
+    out0 = torch.zeros(elems, dtype=torch.bfloat16, device="cuda"); out1 = torch.zeros_like(out0)
+    dh.dh_gemm(dh.DH_BF16, ta, tb, M, N, K, Ad, Bd, C0, acc, None, 0)
+    dh.dh_comm_standin(dh.DH_COMM_ALLREDUCE, parts, out0, elems, dh.DH_BF16, n_blocks)
+    dh.dh_gemm_allreduce(ta, tb, M, N, K, Ad, Bd, C1, acc, parts, out1, elems, n_blocks)
+    torch.cuda.synchronize()
+    assert torch.equal(C0, C1) and torch.equal(out0, out1)
+    ref = gemm_ref(A, B, ta, tb)
+    assert rel(host(C1) - (0.25 if acc else 0.0), ref) <= (2e-5 if acc else 4e-3)
+    ref_sum = np.zeros(elems, np.float32)
+    for q in parts:
+        ref_sum = ref_sum + host(q).astype(np.float32)    # rank order, float32, one rounding at the end
+    assert np.array_equal(host(out1).astype(np.float32), gen.round_bf16(ref_sum))
+
+
+def test_gemm_allreduce_rejects(dh):
+    a = torch.zeros(64 * 64, dtype=torch.bfloat16, device="cuda")
+    big = dh.dh_gemm_allreduce_fits(0, 0, 4104, 4104, 2056)   # needs a tail launch
+    assert not big
+    with pytest.raises(dh.DhelixError) as e:
+        dh.dh_gemm_allreduce(0, 0, 4104, 4104, 2056, a, a, a, False, [a], a, 64, 4)
+    assert e.value.code == dh.DH_ERR_UNSUPPORTED
+    for kw in (dict(elems=12), dict(n_blocks=0), dict(parts=[])):
+        with pytest.raises(dh.DhelixError):
+            dh.dh_gemm_allreduce(0, 0, 64, 64, 64, a, a, a, False, kw.get("parts", [a]), a, kw.get("elems", 64), kw.get("n_blocks", 4))
+
+
 def test_gemm_bf16_shape_errors(dh):
     a = torch.zeros(64 * 64, dtype=torch.bfloat16, device="cuda")
     for args in [(0, 0, 16, 12, 16), (0, 0, 16, 16, 12), (1, 0, 12, 16, 16), (1, 1, 16, 16, 16)]:
