@@ -427,6 +427,26 @@ def main():
                "orders_searched": [info.orders_fwd_tried, info.orders_bwd_tried], "orders_truncated": bool(info.truncated)}
         log("[%s] T_seq %.1f us, T_SI %.1f us (predicted %.1f), without communication: T_seq %.1f, T_SI %.1f; stand-ins solo %.1f us; hidden %.2f" %
             (label, t_seq * 1e6, t_si * 1e6, best[2] * 1e6, t_seq_nc * 1e6, t_si_nc * 1e6, t_comm * 1e6, rec["comm_hidden_frac"] or 0.0))
+        if comm_blocks > 0 and dh.dh_layer_set_fused_collective(run.layer, 3):
+            # The backward all-reduces carried by their strand's weight-gradient GEMMs, one launch each (Sec. 6.3's closing
+            # remark on Table 7: computation and communication in one kernel): profile, search and timing anew under the
+            # placement chosen above; the pair's makespan against the two kernels co-running on two streams (pair table).
+            dh.dh_layer_set_beta_comm_stream(run.layer, scb)
+            table_f = dh.dh_profile_pairs(run.layer, alpha.fwd_args, beta.bwd_args, run.ws, run.ws_bytes, sa, sb, sc, args.profile_reps)
+            plan_f, pred_f, _ = dh.dh_plan_search_lanes(gf, gb, table_f, lanes, args.barrier_cost, 0)
+            dh.dh_layer_set_beta_comm_stream(run.layer, cb)
+            t_si_f = median(event_times(lambda: run.si_step(alpha, beta, plan_f, sa, sb, c), steps, warmup))
+            pairs_f = {}
+            for ar_f, ar_b, wg in (("F_AR1", "B_AR3", "B_FC1_WGRAD"), ("F_AR2", "B_AR4", "B_QKV_WGRAD")):
+                if ar_f in fnames and ar_b in bnames and wg in bnames and table_f.t_bwd[bnames.index(wg)] < 1e-6:
+                    i, j = fnames.index(ar_f), bnames.index(wg)
+                    pairs_f[ar_b + "+" + wg] = {"one_launch_us": table_f.t_bwd[bnames.index(ar_b)] * 1e6,
+                                                "two_kernels_corun_us": table.p_pair[i][j] * 1e6,
+                                                "allreduce_solo_us": t_b[bnames.index(ar_b)] * 1e6, "gemm_solo_us": t_b[j] * 1e6}
+            dh.dh_layer_set_fused_collective(run.layer, 0)
+            rec["fused_collective"] = {"ms_si": t_si_f * 1e3, "predicted_ms": pred_f * 1e3, "pairs": pairs_f,
+                                       "comm_hidden_frac": (1.0 - max(0.0, t_si_f - t_si_nc) / t_comm) if t_comm > 0 else None}
+            log("[%s] all-reduces carried by weight-gradient GEMMs: T_SI %.1f us (predicted %.1f); %s" % (label, t_si_f * 1e6, pred_f * 1e6, pairs_f))
         return rec, plan, (c, cb), table, ts_si
 
     if args.plan_table and os.path.exists(args.plan_table):
