@@ -525,7 +525,7 @@ def main():
     roofline = {"bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac"],
                 "traffic": traffic, "traffic_unit": "bytes/launch", "algorithmic_work": dom["work"], "work_unit": dom["work_unit"],
                 "kernel": "%s (the operator with the largest share, %.1f %%, of the step's summed solo time; %s)" %
-                          (dom["op"], 100 * dom["share_of_solo"], OP_KERNELS.get(dom["op"].split("_", 1)[1] if "_" in dom["op"] else dom["op"], "its kernels")),
+                          (dom["op"], 100 * dom["share_of_solo"], OP_KERNELS.get(dom["op"].split("_")[1] if "_" in dom["op"] else dom["op"], "its kernels")),
                 "solo_us": dom["solo_us"]}
 
     value = flops / t_si / 1e12
