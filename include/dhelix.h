@@ -284,14 +284,16 @@ double dh_segment_cost(const dh_overlap_table* t, const int* seg_f, int n_f, con
  * inputs.  The operators run over and over in place: the gradient buffers are added to, and alpha's
  * saved slot, alpha's out and beta's dx are overwritten (RoPE turns alpha's saved qkv again on every
  * repetition), so run the strands' forward and backward again before their results are used.  Solo
- * times have a floor of 0.1 us (an operator that launches nothing), rates lie in [0.02, 1].
+ * times are the shorter of two timed groups of reps launches (a hiccup of the machine lengthens one group, not both)
+ * and have a floor of 0.1 us (an operator that launches nothing), rates lie in [0.02, 1].
  * Blocks until done.  reps: timed repetitions (>=1). */
 int dh_profile_pairs(dh_layer* layer, const dh_fwd_args* alpha, const dh_bwd_args* beta, void* ws,
                      size_t ws_bytes, void* stream_alpha, void* stream_beta, void* comm_stream,
                      int reps, dh_overlap_table* out);
 
 /* The solo times alone (Sec. 3.2, the T_i of Eq. 1): every operator launched reps times back to back (after one
- * warm-up launch) on the stream dh_si_step would issue it to, timed with events on that stream.  t_fwd / t_bwd: host
+ * warm-up launch; two such groups, the shorter counts) on the stream dh_si_step would issue it to, timed with events on
+ * that stream.  t_fwd / t_bwd: host
  * arrays of DH_MAX_OPS doubles, seconds.  Same requirements and side effects as dh_profile_pairs.  Blocks until done. */
 int dh_profile_solo(dh_layer* layer, const dh_fwd_args* alpha, const dh_bwd_args* beta, void* ws, size_t ws_bytes,
                     void* stream_alpha, void* stream_beta, void* comm_stream, int reps, double* t_fwd, double* t_bwd);
